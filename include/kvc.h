@@ -1,0 +1,200 @@
+/*
+ * kvc.h - C ABI of libkvc: head-variable paged KV cache for MI355X (gfx950).
+ *
+ * The library implements the data-parallel hot path of KV-Compress
+ * (arXiv 2410.00161): a paged decode attention in which every
+ * (sequence, layer, KV head) owns its own block table and context length over
+ * one unified [N, b, d] cache, the per-KV eviction metric accumulated in the
+ * same pass, a block-level reduction of that metric, a lowest-metric block
+ * selection across layers and heads, and a MoveCache compaction that returns
+ * whole blocks to an on-device allocator.
+ *
+ * Conventions common to every call
+ *   - Plain C ABI.  Every function returns a kvc_status (KVC_OK = 0).
+ *   - Every pointer named below is DEVICE memory on the current HIP device and
+ *     is owned by the caller, unless its comment says "host".  The library
+ *     allocates nothing; its temporaries live in the caller's workspace `ws`
+ *     of at least kvc_workspace_bytes(cfg) bytes, 256-byte aligned.  Two calls
+ *     that share a workspace must be ordered on one stream.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     All work is enqueued on it.
+ *   - Argument errors are found on the host before anything is launched.
+ *     Capacity and numeric errors are found on the device before any state is
+ *     written: on ANY error the cache state is left exactly as it was.
+ *   - Calls documented as "synchronises" wait for the stream before returning
+ *     because they return a count or an error found on the device.  Passing
+ *     KVC_ASYNC in `flags` skips that wait: the call returns KVC_OK at once,
+ *     later launches that depend on a failed step become no-ops, and the code
+ *     is read later with kvc_poll_status().
+ *   - Head instance g = (s * num_layers + l) * num_kv_heads + h; G = S*Lyr*Hk.
+ *     Query head hq of a layer belongs to KV head hq / group_size.
+ *   - A head instance holds the blocks block_table[g][0 .. held), held = the
+ *     length of the non-negative prefix of its row; its ctx_len[g] KVs occupy
+ *     logical slots 0 .. ctx_len-1, slot j at (block_table[g][j / b], j % b).
+ */
+#ifndef KVC_H_
+#define KVC_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  KVC_OK = 0,
+  KVC_ERR_ARG = 1,        /* null / misaligned pointer, bad enum, bad range     */
+  KVC_ERR_OOM = 2,        /* fewer free blocks than requested                    */
+  KVC_ERR_TABLE_FULL = 3, /* a head would exceed max_blocks_per_head             */
+  KVC_ERR_BUDGET = 4,     /* reserved                                            */
+  KVC_ERR_NUMERIC = 5,    /* NaN, infinite or negative block key                 */
+  KVC_ERR_HIP = 6,        /* a HIP runtime call failed                           */
+  KVC_ERR_UNSUPPORTED = 7 /* shape outside what the kernels cover                */
+} kvc_status;
+
+enum { KVC_F32 = 0, KVC_BF16 = 1 };  /* kv_dtype                                  */
+enum { KVC_L2 = 0, KVC_L1 = 1 };     /* metric_mode: sum of p^2 (default) or of p */
+enum { KVC_ASYNC = 1 };              /* flags                                     */
+
+/* Immutable description of the cache (paper: Method, "Block Layout and Parallel
+ * Allocation": block tables B x l x H x Lmax/b, one cache N x b x d).           */
+typedef struct kvc_config {
+  int32_t num_seqs;            /* S (paper B)                                   */
+  int32_t num_layers;          /* Lyr (paper l)                                 */
+  int32_t num_kv_heads;        /* Hk (paper H)                                  */
+  int32_t group_size;          /* r = query heads per KV head                   */
+  int32_t head_dim;            /* d                                             */
+  int32_t block_size;          /* b                                             */
+  int32_t num_blocks;          /* N                                             */
+  int32_t max_blocks_per_head; /* Lmax / b                                      */
+  int32_t kv_dtype;            /* KVC_F32 | KVC_BF16; q has the same type       */
+  int32_t metric_mode;         /* KVC_L2 | KVC_L1                               */
+} kvc_config;
+
+/* Mutable state, all device memory ("Evicting from a Paged KV Cache": K_u, V_u
+ * of shape N x b x d, metrics M of shape N x b in the same layout, the logical
+ * index of every slot; "Block Layout and Parallel Allocation": tables, context
+ * lengths and the flat length-N allocation tensor).                            */
+typedef struct kvc_state {
+  void*    k_cache;     /* [N, b, d] kv_dtype, 16-byte aligned                  */
+  void*    v_cache;     /* [N, b, d] kv_dtype, 16-byte aligned                  */
+  float*   metric;      /* [N, b] f32                                           */
+  int32_t* pos;         /* [N, b] logical index, may be NULL                    */
+  int32_t* block_table; /* [S, Lyr, Hk, max_blocks_per_head], -1 = none         */
+  int32_t* ctx_len;     /* [S, Lyr, Hk]                                         */
+  uint8_t* free_map;    /* [N], 1 = free                                        */
+} kvc_state;
+
+/* Bytes of workspace any call with this config may need.  Host only, no HIP
+ * call.  Returns 0 when cfg is invalid.                                        */
+size_t kvc_workspace_bytes(const kvc_config* cfg);
+
+/* Checks cfg (and st when non-NULL) the way every entry point does.  Host
+ * only.  KVC_OK, KVC_ERR_ARG or KVC_ERR_UNSUPPORTED.                           */
+int kvc_validate(const kvc_config* cfg, const kvc_state* st);
+
+/* Host string for a status code; never NULL.                                   */
+const char* kvc_status_string(int status);
+
+/* Zeroes the workspace header.  Call once after allocating `ws`, and again to
+ * clear an error left by an asynchronous call.                                 */
+int kvc_workspace_reset(const kvc_config* cfg, void* ws, void* stream);
+
+/* Reads the error word the device-side guards write (host out-param `status`).
+ * Synchronises the stream.                                                     */
+int kvc_poll_status(const kvc_config* cfg, void* ws, void* stream, int* status);
+
+/* On-device block allocator ("Block Layout and Parallel Allocation": a flat
+ * tensor of length N tracks allocation; counting and allocation run in
+ * parallel over all sequences, layers and heads).
+ * n_new [G] i32: blocks wanted per head instance, appended to its row after the
+ * blocks it holds.  Requesters are served in ascending g and the k-th requested
+ * block overall is the k-th lowest-numbered free block.  ctx_len is not
+ * changed.  Errors: KVC_ERR_OOM, KVC_ERR_TABLE_FULL, KVC_ERR_ARG (negative
+ * request).  Synchronises unless KVC_ASYNC.                                    */
+int kvc_block_alloc(const kvc_config* cfg, const kvc_state* st, const int32_t* n_new,
+                    void* ws, void* stream, int flags);
+
+/* Drops the last n_drop[g] blocks of every head instance (a preemption drops
+ * them all): their ids go back to free_map, their table cells become -1 and
+ * ctx_len[g] is clamped to the slots that remain.  blocks_freed: host int64
+ * out-param, may be NULL (then nothing is read back).  KVC_ERR_ARG when a count
+ * is negative or exceeds the blocks held.  Synchronises unless KVC_ASYNC.      */
+int kvc_block_free(const kvc_config* cfg, const kvc_state* st, const int32_t* n_drop,
+                   int64_t* blocks_freed, void* ws, void* stream, int flags);
+
+/* Appends one new token's key and value to every head instance of layers
+ * [layer_begin, layer_end).  k_new, v_new [S, Lyr, Hk, d] kv_dtype.  A head
+ * whose blocks are all full first takes one block (same order rule as
+ * kvc_block_alloc).  The new slot's metric starts at 0 ("Continual
+ * Compression": later queries add into it) and its logical index is
+ * new_pos[s] (device [S] i32) or, when new_pos is NULL, the head's old length.
+ * Errors as kvc_block_alloc.  Synchronises unless KVC_ASYNC.                   */
+int kvc_append(const kvc_config* cfg, const kvc_state* st, const void* k_new,
+               const void* v_new, const int32_t* new_pos, int layer_begin, int layer_end,
+               void* ws, void* stream, int flags);
+
+/* One decode step of paged attention with per-head tables (Preliminaries:
+ * A = softmax(q K^T / sqrt d), out = A V; Method: "Block Layout and Parallel
+ * Allocation") over layers [layer_begin, layer_end).
+ * q [S, Lyr, Hq, d] kv_dtype, out [S, Lyr, Hq, d] f32; rows of other layers are
+ * neither read nor written.  Head instance g attends to its own ctx_len[g]
+ * KVs; a head with no KV gets zeros.  When accumulate_metric != 0 every
+ * attended slot's metric grows by the sum over the r query heads of its group
+ * ("Query Group Compression") of p^2 ("Squared Attention Metric"; p with
+ * KVC_L1), p being the normalised probability ("Continual Compression").
+ * Asynchronous; no device-side error exists for this call.                     */
+int kvc_paged_decode(const kvc_config* cfg, const kvc_state* st, const void* q, float* out,
+                     int layer_begin, int layer_end, int accumulate_metric,
+                     void* ws, void* stream);
+
+/* Block-level reduction of the metric ("Evicting from a Paged KV Cache": blocks
+ * are ordered by the SUM of their KVs' metrics).  block_key [G, max_blocks] f32:
+ * block_key[g][u] = M[n][0] + M[n][1] + ... over the filled slots of logical
+ * block u (n = block_table[g][u]), added left to right in f32; a partial last
+ * block contributes only its real slots.  Cells with u >= ceil(ctx_len/b) are
+ * set to 0.  Asynchronous.                                                     */
+int kvc_metric_reduce(const kvc_config* cfg, const kvc_state* st, float* block_key,
+                      void* ws, void* stream);
+
+/* Lowest-metric block selection across layers and heads (same section: each
+ * sequence s evicts its budget E_s of blocks, the cheapest first).
+ * A segment is a run of consecutive sequences: seg_offsets [nseg + 1] i32
+ * (device) in sequence units, seg_offsets[0] = 0, last = S; NULL = one segment
+ * per sequence (then nseg must equal S).  budget [nseg] i32 (device).
+ * Candidates of head g are its logical blocks u < ceil(ctx_len/b) -
+ * protect_tail_blocks (1 keeps every head's last block, matching the domain
+ * 1 <= e < ceil(C_h/b); 0 lets a head lose everything).  Per segment the
+ * min(budget, candidates) candidates smallest in (key, s, l, h, u) are chosen.
+ * Outputs: evict_flag [G, max_blocks] u8 (fully rewritten), evict_count [G]
+ * i32, selected [nseg] i32 = blocks actually chosen.
+ * KVC_ERR_NUMERIC when a candidate key is NaN, infinite or negative (outputs
+ * are then all zero).  Synchronises unless KVC_ASYNC.                          */
+int kvc_evict_select(const kvc_config* cfg, const kvc_state* st, const float* block_key,
+                     const int32_t* seg_offsets, const int32_t* budget, int nseg,
+                     int protect_tail_blocks, uint8_t* evict_flag, int32_t* evict_count,
+                     int32_t* selected, void* ws, void* stream, int flags);
+
+/* MoveCache (Algorithm 1) for every head at once, then the free step.  Per head
+ * with flagged blocks: n_ev = KVs in flagged blocks, T = ctx_len - n_ev; kept
+ * KVs in slots >= T move, highest first, into the evicted slots below T, lowest
+ * first (key, value, metric and pos together); ctx_len becomes T and the table
+ * cells from ceil(T/b) on are freed.  evict_flag / evict_count as produced by
+ * kvc_evict_select.  blocks_freed: device int64, set to the number of blocks
+ * returned to free_map; may be NULL.  KVC_ERR_ARG (nothing modified) when a flag
+ * is set at or beyond ceil(ctx_len/b) or a count disagrees with its flags.
+ * Synchronises unless KVC_ASYNC.                                               */
+int kvc_compact(const kvc_config* cfg, const kvc_state* st, const uint8_t* evict_flag,
+                const int32_t* evict_count, int64_t* blocks_freed, void* ws, void* stream,
+                int flags);
+
+/* Tuning knob of kvc_paged_decode: tokens handled by one workgroup before a
+ * head is split across workgroups.  0 restores the default.  Process-wide,
+ * host only.  KVC_ERR_ARG unless 0 or a multiple of 64 in [64, 8192].          */
+int kvc_set_decode_chunk(int tokens);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KVC_H_ */

@@ -1,0 +1,206 @@
+"""ctypes binding of libkvc.so: argument marshalling only.
+
+Every function here has the name and the argument order of the C entry point
+it calls (include/kvc.h).  Tensors are torch tensors used as device memory;
+the stream is torch's current stream unless one is given.  Nothing is computed
+in Python and there is no fallback: a missing library raises at first use.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import torch
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libkvc.so")
+
+KVC_OK, KVC_ERR_ARG, KVC_ERR_OOM, KVC_ERR_TABLE_FULL = 0, 1, 2, 3
+KVC_ERR_BUDGET, KVC_ERR_NUMERIC, KVC_ERR_HIP, KVC_ERR_UNSUPPORTED = 4, 5, 6, 7
+KVC_F32, KVC_BF16 = 0, 1
+KVC_L2, KVC_L1 = 0, 1
+KVC_ASYNC = 1
+
+EXPORTS = [
+    "kvc_workspace_bytes", "kvc_validate", "kvc_status_string", "kvc_workspace_reset",
+    "kvc_poll_status", "kvc_block_alloc", "kvc_block_free", "kvc_append", "kvc_paged_decode",
+    "kvc_metric_reduce", "kvc_evict_select", "kvc_compact", "kvc_set_decode_chunk",
+]
+
+
+class kvc_config(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in (
+        "num_seqs", "num_layers", "num_kv_heads", "group_size", "head_dim", "block_size",
+        "num_blocks", "max_blocks_per_head", "kv_dtype", "metric_mode")]
+
+
+class kvc_state(C.Structure):
+    _fields_ = [("k_cache", C.c_void_p), ("v_cache", C.c_void_p), ("metric", C.c_void_p),
+                ("pos", C.c_void_p), ("block_table", C.c_void_p), ("ctx_len", C.c_void_p),
+                ("free_map", C.c_void_p)]
+
+
+class KvcError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        super().__init__(f"{where}: {status_string(code)} ({code})")
+        self.code = code
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """Loads libkvc.so (built by paper_2410_00161_amd.build).  No fallback."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: run `python -m paper_2410_00161_amd.build`")
+        L = C.CDLL(LIB_PATH)
+        P, I = C.c_void_p, C.c_int
+        cfgp, stp = C.POINTER(kvc_config), C.POINTER(kvc_state)
+        L.kvc_workspace_bytes.restype = C.c_size_t
+        L.kvc_workspace_bytes.argtypes = [cfgp]
+        L.kvc_validate.argtypes = [cfgp, stp]
+        L.kvc_status_string.restype = C.c_char_p
+        L.kvc_status_string.argtypes = [I]
+        L.kvc_workspace_reset.argtypes = [cfgp, P, P]
+        L.kvc_poll_status.argtypes = [cfgp, P, P, C.POINTER(C.c_int)]
+        L.kvc_block_alloc.argtypes = [cfgp, stp, P, P, P, I]
+        L.kvc_block_free.argtypes = [cfgp, stp, P, C.POINTER(C.c_int64), P, P, I]
+        L.kvc_append.argtypes = [cfgp, stp, P, P, P, I, I, P, P, I]
+        L.kvc_paged_decode.argtypes = [cfgp, stp, P, P, I, I, I, P, P]
+        L.kvc_metric_reduce.argtypes = [cfgp, stp, P, P, P]
+        L.kvc_evict_select.argtypes = [cfgp, stp, P, P, P, I, I, P, P, P, P, P, I]
+        L.kvc_compact.argtypes = [cfgp, stp, P, P, P, P, P, I]
+        L.kvc_set_decode_chunk.argtypes = [I]
+        for n in EXPORTS:
+            if n not in ("kvc_workspace_bytes", "kvc_status_string"):
+                getattr(L, n).restype = I
+        _lib = L
+    return _lib
+
+
+def status_string(code: int) -> str:
+    return lib().kvc_status_string(int(code)).decode()
+
+
+def _ptr(t, dtype=None):
+    if t is None:
+        return None
+    if not isinstance(t, torch.Tensor):
+        raise TypeError("expected a torch tensor")
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError(f"expected {dtype}, got {t.dtype}")
+    if not t.is_contiguous():
+        raise ValueError("tensor must be contiguous")
+    return C.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    if stream is None:
+        return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+    if isinstance(stream, torch.cuda.Stream):
+        return C.c_void_p(stream.cuda_stream)
+    return C.c_void_p(int(stream))
+
+
+def _check(rc: int, where: str):
+    if rc != KVC_OK:
+        raise KvcError(rc, where)
+
+
+def make_config(num_seqs, num_layers, num_kv_heads, group_size, head_dim, block_size,
+                num_blocks, max_blocks_per_head, kv_dtype, metric_mode=KVC_L2) -> kvc_config:
+    if isinstance(kv_dtype, str):
+        kv_dtype = {"bf16": KVC_BF16, "f32": KVC_F32}[kv_dtype]
+    return kvc_config(num_seqs, num_layers, num_kv_heads, group_size, head_dim, block_size,
+                      num_blocks, max_blocks_per_head, kv_dtype, metric_mode)
+
+
+def make_state(k_cache, v_cache, metric, pos, block_table, ctx_len, free_map) -> kvc_state:
+    """Wraps device tensors; the caller keeps them alive."""
+    st = kvc_state(_ptr(k_cache), _ptr(v_cache), _ptr(metric, torch.float32),
+                   _ptr(pos, torch.int32) if pos is not None else None,
+                   _ptr(block_table, torch.int32), _ptr(ctx_len, torch.int32),
+                   _ptr(free_map, torch.uint8))
+    return st
+
+
+def kvc_workspace_bytes(cfg) -> int:
+    return int(lib().kvc_workspace_bytes(C.byref(cfg)))
+
+
+def kvc_validate(cfg, st=None) -> int:
+    return int(lib().kvc_validate(C.byref(cfg), C.byref(st) if st is not None else None))
+
+
+def new_workspace(cfg, device) -> torch.Tensor:
+    n = kvc_workspace_bytes(cfg)
+    if n == 0:
+        raise KvcError(KVC_ERR_ARG, "kvc_workspace_bytes")
+    ws = torch.empty(n + 256, dtype=torch.uint8, device=device)
+    off = (-ws.data_ptr()) % 256
+    ws = ws[off:off + n]
+    with torch.cuda.device(device):
+        kvc_workspace_reset(cfg, ws)
+    return ws
+
+
+def kvc_workspace_reset(cfg, ws, stream=None):
+    _check(lib().kvc_workspace_reset(C.byref(cfg), _ptr(ws), _stream(stream)), "kvc_workspace_reset")
+
+
+def kvc_poll_status(cfg, ws, stream=None) -> int:
+    out = C.c_int(0)
+    _check(lib().kvc_poll_status(C.byref(cfg), _ptr(ws), _stream(stream), C.byref(out)), "kvc_poll_status")
+    return out.value
+
+
+def kvc_block_alloc(cfg, st, n_new, ws, stream=None, flags=0):
+    _check(lib().kvc_block_alloc(C.byref(cfg), C.byref(st), _ptr(n_new, torch.int32), _ptr(ws),
+                                 _stream(stream), flags), "kvc_block_alloc")
+
+
+def kvc_block_free(cfg, st, n_drop, ws, stream=None, flags=0) -> int:
+    freed = C.c_int64(0)
+    _check(lib().kvc_block_free(C.byref(cfg), C.byref(st), _ptr(n_drop, torch.int32), C.byref(freed),
+                                _ptr(ws), _stream(stream), flags), "kvc_block_free")
+    return freed.value
+
+
+def kvc_append(cfg, st, k_new, v_new, new_pos, layer_begin, layer_end, ws, stream=None, flags=0):
+    _check(lib().kvc_append(C.byref(cfg), C.byref(st), _ptr(k_new), _ptr(v_new),
+                            _ptr(new_pos, torch.int32) if new_pos is not None else None,
+                            layer_begin, layer_end, _ptr(ws), _stream(stream), flags), "kvc_append")
+
+
+def kvc_paged_decode(cfg, st, q, out, layer_begin, layer_end, accumulate_metric, ws, stream=None):
+    _check(lib().kvc_paged_decode(C.byref(cfg), C.byref(st), _ptr(q), _ptr(out, torch.float32),
+                                  layer_begin, layer_end, int(accumulate_metric), _ptr(ws),
+                                  _stream(stream)), "kvc_paged_decode")
+
+
+def kvc_metric_reduce(cfg, st, block_key, ws, stream=None):
+    _check(lib().kvc_metric_reduce(C.byref(cfg), C.byref(st), _ptr(block_key, torch.float32), _ptr(ws),
+                                   _stream(stream)), "kvc_metric_reduce")
+
+
+def kvc_evict_select(cfg, st, block_key, seg_offsets, budget, nseg, protect_tail_blocks, evict_flag,
+                     evict_count, selected, ws, stream=None, flags=0):
+    _check(lib().kvc_evict_select(C.byref(cfg), C.byref(st), _ptr(block_key, torch.float32),
+                                  _ptr(seg_offsets, torch.int32) if seg_offsets is not None else None,
+                                  _ptr(budget, torch.int32), nseg, protect_tail_blocks,
+                                  _ptr(evict_flag, torch.uint8), _ptr(evict_count, torch.int32),
+                                  _ptr(selected, torch.int32), _ptr(ws), _stream(stream), flags),
+           "kvc_evict_select")
+
+
+def kvc_compact(cfg, st, evict_flag, evict_count, blocks_freed, ws, stream=None, flags=0):
+    _check(lib().kvc_compact(C.byref(cfg), C.byref(st), _ptr(evict_flag, torch.uint8),
+                             _ptr(evict_count, torch.int32),
+                             _ptr(blocks_freed, torch.int64) if blocks_freed is not None else None,
+                             _ptr(ws), _stream(stream), flags), "kvc_compact")
+
+
+def kvc_set_decode_chunk(tokens: int):
+    _check(lib().kvc_set_decode_chunk(int(tokens)), "kvc_set_decode_chunk")

@@ -1,0 +1,85 @@
+// Host-side entry points that launch little or nothing: validation, workspace
+// sizing, status words.  Also the one kernel the device-wide scan shares.
+#include "kvc_common.h"
+
+namespace kvc {
+
+int validate(const kvc_config* c, const kvc_state* st) {
+  if (!c) return KVC_ERR_ARG;
+  if (c->num_seqs <= 0 || c->num_layers <= 0 || c->num_kv_heads <= 0 || c->group_size <= 0 ||
+      c->head_dim <= 0 || c->block_size <= 0 || c->num_blocks <= 0 || c->max_blocks_per_head <= 0)
+    return KVC_ERR_ARG;
+  if (c->kv_dtype != KVC_F32 && c->kv_dtype != KVC_BF16) return KVC_ERR_ARG;
+  if (c->metric_mode != KVC_L2 && c->metric_mode != KVC_L1) return KVC_ERR_ARG;
+  // index arithmetic is 32-bit for head instances and table cells, 64-bit for slots
+  const int64_t G = (int64_t)c->num_seqs * c->num_layers * c->num_kv_heads;
+  if (G > (1ll << 28)) return KVC_ERR_UNSUPPORTED;
+  if (G * c->max_blocks_per_head > (1ll << 40)) return KVC_ERR_UNSUPPORTED;
+  if ((int64_t)c->num_blocks * c->block_size > (1ll << 40)) return KVC_ERR_UNSUPPORTED;
+  if (c->group_size > 16 || c->head_dim > 512) return KVC_ERR_UNSUPPORTED;
+  const int esz = c->kv_dtype == KVC_BF16 ? 2 : 4;
+  if ((c->head_dim * esz) % 16 != 0) return KVC_ERR_UNSUPPORTED;  // rows are read 16 bytes at a time
+  if (st) {
+    if (!st->k_cache || !st->v_cache || !st->metric || !st->block_table || !st->ctx_len ||
+        !st->free_map)
+      return KVC_ERR_ARG;
+    if (((uintptr_t)st->k_cache | (uintptr_t)st->v_cache) & 15) return KVC_ERR_ARG;
+    if (((uintptr_t)st->metric | (uintptr_t)st->block_table | (uintptr_t)st->ctx_len) & 3)
+      return KVC_ERR_ARG;
+    if (st->pos && ((uintptr_t)st->pos & 3)) return KVC_ERR_ARG;
+  }
+  return KVC_OK;
+}
+
+}  // namespace kvc
+
+using namespace kvc;
+
+extern "C" {
+
+size_t kvc_workspace_bytes(const kvc_config* cfg) {
+  if (validate(cfg, nullptr) != KVC_OK) return 0;
+  Dims D = dims_of(cfg);
+  return carve(D, nullptr).bytes;
+}
+
+int kvc_validate(const kvc_config* cfg, const kvc_state* st) { return validate(cfg, st); }
+
+const char* kvc_status_string(int status) {
+  switch (status) {
+    case KVC_OK: return "ok";
+    case KVC_ERR_ARG: return "invalid argument";
+    case KVC_ERR_OOM: return "not enough free blocks";
+    case KVC_ERR_TABLE_FULL: return "block table row full";
+    case KVC_ERR_BUDGET: return "eviction budget error";
+    case KVC_ERR_NUMERIC: return "NaN, infinite or negative block key";
+    case KVC_ERR_HIP: return "HIP runtime error";
+    case KVC_ERR_UNSUPPORTED: return "shape not supported";
+    default: return "unknown status";
+  }
+}
+
+int kvc_workspace_reset(const kvc_config* cfg, void* ws, void* stream) {
+  int rc = validate(cfg, nullptr);
+  if (rc != KVC_OK) return rc;
+  if (!ws || ((uintptr_t)ws & 255)) return KVC_ERR_ARG;
+  Workspace W = carve(dims_of(cfg), ws);
+  // a fill kernel rather than a memset node: safe to record into a HIP graph
+  hipLaunchKernelGGL(zero_words_kernel, dim3(1), dim3(64), 0, (hipStream_t)stream, W.header, HW_WORDS);
+  KVC_LAUNCH_CHECK();
+  return KVC_OK;
+}
+
+int kvc_poll_status(const kvc_config* cfg, void* ws, void* stream, int* status) {
+  int rc = validate(cfg, nullptr);
+  if (rc != KVC_OK) return rc;
+  if (!ws || !status || ((uintptr_t)ws & 255)) return KVC_ERR_ARG;
+  Workspace W = carve(dims_of(cfg), ws);
+  int32_t w = 0;
+  rc = read_words(W.header + HW_STATUS, &w, 1, (hipStream_t)stream);
+  if (rc != KVC_OK) return rc;
+  *status = w;
+  return KVC_OK;
+}
+
+}  // extern "C"

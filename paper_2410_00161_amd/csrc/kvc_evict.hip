@@ -1,0 +1,432 @@
+// Eviction path: block-level metric reduction, lowest-metric block selection
+// across layers and heads, and MoveCache compaction with the free step
+// (KV-Compress, Method, "Evicting from a Paged KV Cache" and Algorithm 1).
+//
+// Selection never sorts: per segment an 8-bit-per-pass radix select over the
+// f32 keys (non-negative, so their bit patterns order like the values) finds
+// the threshold key and how many ties at the threshold are still wanted; ties
+// are then granted in ascending (s, l, h, u).  All counting is integer, so the
+// result is the one a stable sort by (key, s, l, h, u) would give.
+#include "kvc_common.h"
+
+namespace kvc {
+
+enum { SS_PREFIX = 0, SS_REMAIN = 1, SS_CAND = 2, SS_TAKE = 3, SS_FIRSTG = 4 };
+
+// ---------------------------------------------------------------------------
+// block keys
+// ---------------------------------------------------------------------------
+// One wavefront per head instance; lane -> logical block.  The b metrics of a
+// block are contiguous (64 bytes at b = 16) and are added left to right in f32.
+__global__ void __launch_bounds__(256) block_key_kernel(Dims D, const float* __restrict__ metric,
+                                                        const int32_t* __restrict__ table,
+                                                        const int32_t* __restrict__ ctx,
+                                                        float* __restrict__ key) {
+  const int g = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (g >= D.G) return;
+  const int lane = threadIdx.x & 63;
+  const int C = ctx[g];
+  const int nb = (C + D.b - 1) / D.b;
+  const int32_t* row = table + (size_t)g * D.maxb;
+  float* krow = key + (size_t)g * D.maxb;
+  for (int u = lane; u < D.maxb; u += 64) {
+    float acc = 0.0f;
+    if (u < nb) {
+      const float* m = metric + (size_t)row[u] * D.b;
+      const int fill = min(D.b, C - u * D.b);
+      for (int o = 0; o < fill; ++o) acc = acc + m[o];
+    }
+    krow[u] = acc;
+  }
+}
+
+// ---------------------------------------------------------------------------
+// selection
+// ---------------------------------------------------------------------------
+
+__global__ void __launch_bounds__(256) select_init_kernel(Dims D, const int32_t* __restrict__ seg_offsets,
+                                                          int nseg, int32_t* __restrict__ seq_seg,
+                                                          int32_t* __restrict__ seg_hist,
+                                                          int32_t* __restrict__ seg_state,
+                                                          int32_t* __restrict__ evict_count,
+                                                          int32_t* __restrict__ selected,
+                                                          int32_t* __restrict__ header) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < D.S) {
+    int sg = i;
+    if (seg_offsets) {  // last segment whose first sequence is <= i
+      int lo = 0, hi = nseg;
+      while (hi - lo > 1) { int mid = (lo + hi) >> 1; if (seg_offsets[mid] <= i) lo = mid; else hi = mid; }
+      sg = lo;
+    }
+    seq_seg[i] = sg;
+  }
+  if (i < nseg * 256) seg_hist[i] = 0;
+  if (i < nseg) {
+    selected[i] = 0;
+    for (int k = 0; k < 8; ++k) seg_state[i * 8 + k] = 0;
+    const int first_seq = seg_offsets ? seg_offsets[i] : i;
+    seg_state[i * 8 + SS_FIRSTG] = first_seq * D.Lyr * D.Hk;
+    if (seg_offsets) {
+      const int a = seg_offsets[i], b2 = seg_offsets[i + 1];
+      bool bad = a > b2 || (i == 0 && a != 0) || (i == nseg - 1 && b2 != D.S);
+      if (bad) atomicOr(&header[HW_SCRATCH0], EB_ARG);
+    }
+  }
+  if (i < D.G) evict_count[i] = 0;
+}
+
+__global__ void __launch_bounds__(256) zero_bytes_kernel(uint8_t* p, size_t n) {
+  size_t i = ((size_t)blockIdx.x * 256 + threadIdx.x) * 16;
+  if (i + 16 <= n) {
+    if (((uintptr_t)(p + i) & 15) == 0) { *(uint4*)(p + i) = make_uint4(0, 0, 0, 0); return; }
+  }
+  for (size_t k = i; k < n && k < i + 16; ++k) p[k] = 0;
+}
+
+__device__ __forceinline__ uint32_t key_bits(float f) {
+  uint32_t k = __float_as_uint(f);
+  return k == 0x80000000u ? 0u : k;  // -0 orders as +0
+}
+
+// Histogram of the current 8-bit digit over the candidates that still match the
+// prefix found so far.  Four head instances per workgroup, one wavefront each;
+// pass 0 also counts candidates and checks the keys.
+__global__ void __launch_bounds__(256) select_hist_kernel(Dims D, int pass, int protect,
+                                                          const float* __restrict__ key,
+                                                          const int32_t* __restrict__ ctx,
+                                                          const int32_t* __restrict__ seq_seg,
+                                                          int32_t* __restrict__ seg_hist,
+                                                          int32_t* __restrict__ seg_state,
+                                                          int32_t* __restrict__ header) {
+  __shared__ int hist[4][256];
+  const int wid = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  for (int i = lane; i < 256; i += 64) hist[wid][i] = 0;
+  __syncthreads();
+  const int g = blockIdx.x * 4 + wid;
+  int sg = 0;
+  if (g < D.G) {
+    sg = seq_seg[g / (D.Lyr * D.Hk)];
+    const int C = ctx[g];
+    const int ncand = max(0, (C + D.b - 1) / D.b - protect);
+    const int shift = 24 - 8 * pass;
+    const uint32_t prefix = (uint32_t)seg_state[sg * 8 + SS_PREFIX];
+    const bool live = pass == 0 || seg_state[sg * 8 + SS_TAKE] > 0;
+    const float* krow = key + (size_t)g * D.maxb;
+    bool bad = false;
+    if (live) {
+      for (int u = lane; u < ncand; u += 64) {
+        const uint32_t k = key_bits(krow[u]);
+        if (pass == 0) bad |= k >= 0x7f800000u;
+        if (pass == 0 || (k >> (shift + 8)) == prefix) atomicAdd(&hist[wid][(k >> shift) & 255], 1);
+      }
+    }
+    if (pass == 0) {
+      if (lane == 0 && ncand > 0) atomicAdd(&seg_state[sg * 8 + SS_CAND], ncand);
+      if (__any(bad) && lane == 0) atomicOr(&header[HW_SCRATCH0], EB_NUMERIC);
+    }
+  }
+  __syncthreads();
+  if (g < D.G) {
+    for (int i = lane; i < 256; i += 64) {
+      int c = hist[wid][i];
+      if (c) atomicAdd(&seg_hist[sg * 256 + i], c);
+    }
+  }
+}
+
+// One workgroup per segment: choose the digit that holds the E-th smallest key.
+__global__ void __launch_bounds__(256) select_pick_kernel(int pass, const int32_t* __restrict__ budget,
+                                                          int32_t* __restrict__ seg_hist,
+                                                          int32_t* __restrict__ seg_state,
+                                                          int32_t* __restrict__ header) {
+  __shared__ int smem[256 / 64 + 1];
+  __shared__ int chosen;
+  const int sg = blockIdx.x;
+  int32_t* stt = seg_state + sg * 8;
+  if (pass == 0 && threadIdx.x == 0) {
+    int bud = budget[sg];
+    if (bud < 0) { atomicOr(&header[HW_SCRATCH0], EB_ARG); bud = 0; }
+    const int take = min(bud, stt[SS_CAND]);
+    stt[SS_TAKE] = take;
+    stt[SS_REMAIN] = take;
+  }
+  __syncthreads();
+  const int take = stt[SS_TAKE];
+  const int remain = stt[SS_REMAIN];
+  const int c = seg_hist[sg * 256 + threadIdx.x];
+  int tot;
+  const int ex = block_exclusive_scan<256>(c, smem, &tot);
+  if (threadIdx.x == 0) chosen = -1;
+  __syncthreads();
+  if (take > 0 && ex < remain && remain <= ex + c) chosen = threadIdx.x;  // exactly one thread
+  __syncthreads();
+  if (take > 0 && threadIdx.x == chosen) {
+    stt[SS_PREFIX] = (int32_t)(((uint32_t)stt[SS_PREFIX] << 8) | (uint32_t)chosen);
+    stt[SS_REMAIN] = remain - ex;  // still wanted among keys equal on all digits so far
+  }
+  seg_hist[sg * 256 + threadIdx.x] = 0;
+}
+
+// Ties at the threshold key, per head instance.
+__global__ void __launch_bounds__(256) select_tie_count_kernel(Dims D, int protect,
+                                                               const float* __restrict__ key,
+                                                               const int32_t* __restrict__ ctx,
+                                                               const int32_t* __restrict__ seq_seg,
+                                                               const int32_t* __restrict__ seg_state,
+                                                               int32_t* __restrict__ tie_cnt) {
+  const int g = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (g >= D.G) return;
+  const int lane = threadIdx.x & 63;
+  const int sg = seq_seg[g / (D.Lyr * D.Hk)];
+  int n = 0;
+  if (seg_state[sg * 8 + SS_TAKE] > 0) {
+    const uint32_t thr = (uint32_t)seg_state[sg * 8 + SS_PREFIX];
+    const int ncand = max(0, (ctx[g] + D.b - 1) / D.b - protect);
+    const float* krow = key + (size_t)g * D.maxb;
+    for (int u = lane; u < ncand; u += 64) n += key_bits(krow[u]) == thr;
+  }
+  n = wave_sum_i(n);
+  if (lane == 0) tie_cnt[g] = n;
+}
+
+struct TieFn {
+  const int32_t* cnt;
+  __device__ int operator()(int i) const { return cnt[i]; }
+};
+
+__global__ void __launch_bounds__(256) select_mark_kernel(Dims D, int protect, const float* __restrict__ key,
+                                                          const int32_t* __restrict__ ctx,
+                                                          const int32_t* __restrict__ seq_seg,
+                                                          const int32_t* __restrict__ seg_state,
+                                                          const int32_t* __restrict__ tie_off,
+                                                          uint8_t* __restrict__ flag,
+                                                          int32_t* __restrict__ evict_count,
+                                                          int32_t* __restrict__ selected,
+                                                          const int32_t* __restrict__ header) {
+  if (header[HW_STATUS] != KVC_OK) return;
+  const int g = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (g >= D.G) return;
+  const int lane = threadIdx.x & 63;
+  const int sg = seq_seg[g / (D.Lyr * D.Hk)];
+  const int32_t* stt = seg_state + sg * 8;
+  const int take = stt[SS_TAKE];
+  if (g == stt[SS_FIRSTG] && lane == 0) selected[sg] = take;
+  if (take <= 0) return;
+  const uint32_t thr = (uint32_t)stt[SS_PREFIX];
+  // ties granted to this head: those whose rank inside the segment is below SS_REMAIN
+  int ties_before = tie_off[g] - tie_off[stt[SS_FIRSTG]];
+  const int want = stt[SS_REMAIN];
+  const int ncand = max(0, (ctx[g] + D.b - 1) / D.b - protect);
+  const float* krow = key + (size_t)g * D.maxb;
+  uint8_t* frow = flag + (size_t)g * D.maxb;
+  int cnt = 0;
+  for (int base = 0; base < ncand; base += 64) {
+    const int u = base + lane;
+    uint32_t k = 0xffffffffu;
+    if (u < ncand) k = key_bits(krow[u]);
+    const bool tie = k == thr;
+    const unsigned long long tm = __ballot(tie);
+    const int my_rank = ties_before + __popcll(tm & ((1ull << lane) - 1ull));
+    const bool ev = (u < ncand) && (k < thr || (tie && my_rank < want));
+    if (ev) frow[u] = 1;
+    cnt += __popcll(__ballot(ev));
+    ties_before += __popcll(tm);
+  }
+  if (lane == 0) evict_count[g] = cnt;
+}
+
+// ---------------------------------------------------------------------------
+// compaction
+// ---------------------------------------------------------------------------
+
+// Per head: inclusive prefix count of flagged blocks; checks flags against the
+// head's block count and against evict_count.
+__global__ void __launch_bounds__(256) compact_scan_kernel(Dims D, const uint8_t* __restrict__ flag,
+                                                           const int32_t* __restrict__ evict_count,
+                                                           const int32_t* __restrict__ ctx,
+                                                           int32_t* __restrict__ flag_scan,
+                                                           int32_t* __restrict__ header) {
+  const int g = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (g >= D.G) return;
+  const int lane = threadIdx.x & 63;
+  const int nb = (ctx[g] + D.b - 1) / D.b;
+  const uint8_t* frow = flag + (size_t)g * D.maxb;
+  int32_t* srow = flag_scan + (size_t)g * D.maxb;
+  int run = 0;
+  bool bad = false;
+  for (int base = 0; base < D.maxb; base += 64) {
+    const int u = base + lane;
+    const bool f = (u < D.maxb) && frow[u] != 0;
+    bad |= f && u >= nb;
+    const unsigned long long m = __ballot(f);
+    const int inc = run + __popcll(m & ((2ull << lane) - 1ull));
+    if (u < nb) srow[u] = inc;
+    run += __popcll(m);
+  }
+  bad |= run != evict_count[g];
+  if (__any(bad) && lane == 0) atomicOr(&header[HW_SCRATCH0], EB_ARG);
+}
+
+// One workgroup per head instance.  A 16-lane group moves one KV: its key row,
+// value row, metric and logical index.  Sources lie in [T, C), destinations in
+// [0, T), so moves of one head never overlap; heads own disjoint blocks.
+__global__ void __launch_bounds__(256) compact_move_kernel(Dims D, char* __restrict__ kc,
+                                                           char* __restrict__ vc,
+                                                           float* __restrict__ metric,
+                                                           int32_t* __restrict__ pos,
+                                                           int32_t* __restrict__ table,
+                                                           int32_t* __restrict__ ctx,
+                                                           uint8_t* __restrict__ free_map,
+                                                           const uint8_t* __restrict__ flag,
+                                                           const int32_t* __restrict__ evict_count,
+                                                           const int32_t* __restrict__ flag_scan,
+                                                           int32_t* __restrict__ header) {
+  if (header[HW_STATUS] != KVC_OK) return;
+  const int g = blockIdx.x;
+  const int e = evict_count[g];
+  if (e <= 0) return;
+  const int b = D.b;
+  const int C = ctx[g];
+  const int nb = (C + b - 1) / b;
+  const uint8_t* frow = flag + (size_t)g * D.maxb;
+  const int32_t* pi = flag_scan + (size_t)g * D.maxb;  // inclusive prefix of flags
+  int32_t* row = table + (size_t)g * D.maxb;
+  // evicted real KVs: flagged blocks are full except possibly the last one
+  const int n_ev = e * b - (frow[nb - 1] ? nb * b - C : 0);
+  const int T = C - n_ev;
+  const size_t row_bytes = (size_t)D.d * (D.dtype == KVC_BF16 ? 2 : 4);
+  const int pieces = (int)(row_bytes / 16);
+  const int grp = threadIdx.x >> 4, gl = threadIdx.x & 15;
+  for (int j = T + grp; j < C; j += 16) {
+    const int uj = j / b;
+    if (frow[uj]) continue;  // evicted, nothing to keep
+    // evicted real slots in [0, j+1): whole flagged blocks before block uj (uj itself is kept)
+    const int ev_below = (uj ? pi[uj - 1] : 0) * b;
+    const int k = (C - 1 - j) - (n_ev - ev_below);  // kept slots above j = rank among movers
+    // k-th hole: offset k % b of the (k / b)-th flagged block
+    const int want = k / b + 1;
+    int lo = 0, hi = nb - 1;  // smallest u with pi[u] >= want
+    while (lo < hi) { int mid = (lo + hi) >> 1; if (pi[mid] >= want) hi = mid; else lo = mid + 1; }
+    const size_t src = (size_t)row[uj] * b + (j - uj * b);
+    const size_t dst = (size_t)row[lo] * b + (k % b);
+    for (int c = gl; c < pieces; c += 16) {
+      ((uint4*)(kc + dst * row_bytes))[c] = ((const uint4*)(kc + src * row_bytes))[c];
+      ((uint4*)(vc + dst * row_bytes))[c] = ((const uint4*)(vc + src * row_bytes))[c];
+    }
+    if (gl == 0) {
+      metric[dst] = metric[src];
+      if (pos) pos[dst] = pos[src];
+    }
+  }
+  __syncthreads();  // all moves of this head read the table before it shrinks
+  const int nb2 = (T + b - 1) / b;
+  for (int u = nb2 + threadIdx.x; u < nb; u += 256) {
+    free_map[row[u]] = 1;
+    row[u] = -1;
+  }
+  if (threadIdx.x == 0) {
+    ctx[g] = T;
+    atomicAdd(&header[HW_FREED], nb - nb2);
+  }
+}
+
+__global__ void publish_freed_kernel(const int32_t* header, int64_t* out) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) out[0] = header[HW_STATUS] == KVC_OK ? header[HW_FREED] : 0;
+}
+
+}  // namespace kvc
+
+using namespace kvc;
+
+extern "C" {
+
+int kvc_metric_reduce(const kvc_config* cfg, const kvc_state* st, float* block_key, void* ws,
+                      void* stream) {
+  int rc = validate(cfg, st);
+  if (rc != KVC_OK) return rc;
+  if (!block_key || ((uintptr_t)block_key & 3)) return KVC_ERR_ARG;
+  (void)ws;
+  Dims D = dims_of(cfg);
+  hipLaunchKernelGGL(block_key_kernel, dim3((D.G + 3) / 4), dim3(256), 0, (hipStream_t)stream, D,
+                     st->metric, st->block_table, st->ctx_len, block_key);
+  KVC_LAUNCH_CHECK();
+  return KVC_OK;
+}
+
+int kvc_evict_select(const kvc_config* cfg, const kvc_state* st, const float* block_key,
+                     const int32_t* seg_offsets, const int32_t* budget, int nseg,
+                     int protect_tail_blocks, uint8_t* evict_flag, int32_t* evict_count,
+                     int32_t* selected, void* ws, void* stream, int flags) {
+  int rc = validate(cfg, st);
+  if (rc != KVC_OK) return rc;
+  if (!block_key || !budget || !evict_flag || !evict_count || !selected || !ws ||
+      ((uintptr_t)ws & 255))
+    return KVC_ERR_ARG;
+  Dims D = dims_of(cfg);
+  if (nseg <= 0 || nseg > D.S || protect_tail_blocks < 0) return KVC_ERR_ARG;
+  if (!seg_offsets && nseg != D.S) return KVC_ERR_ARG;
+  Workspace W = carve(D, ws);
+  hipStream_t s = (hipStream_t)stream;
+  int32_t* seq_seg = W.held;  // [S] fits in the [G] array
+  const int gw = (D.G + 3) / 4;
+  int n_init = D.G > nseg * 256 ? D.G : nseg * 256;
+  hipLaunchKernelGGL(select_init_kernel, dim3((n_init + 255) / 256), dim3(256), 0, s, D, seg_offsets, nseg,
+                     seq_seg, W.seg_hist, W.seg_state, evict_count, selected, W.header);
+  KVC_LAUNCH_CHECK();
+  const size_t nflag = (size_t)D.G * D.maxb;
+  hipLaunchKernelGGL(zero_bytes_kernel, dim3((unsigned)((nflag / 16 + 256) / 256)), dim3(256), 0, s,
+                     evict_flag, nflag);
+  KVC_LAUNCH_CHECK();
+  for (int pass = 0; pass < 4; ++pass) {
+    hipLaunchKernelGGL(select_hist_kernel, dim3(gw), dim3(256), 0, s, D, pass, protect_tail_blocks,
+                       block_key, st->ctx_len, seq_seg, W.seg_hist, W.seg_state, W.header);
+    KVC_LAUNCH_CHECK();
+    hipLaunchKernelGGL(select_pick_kernel, dim3(nseg), dim3(256), 0, s, pass, budget, W.seg_hist,
+                       W.seg_state, W.header);
+    KVC_LAUNCH_CHECK();
+    if (pass == 0) {  // keys checked, budgets checked: settle the status before any output is written
+      hipLaunchKernelGGL(resolve_kernel, dim3(1), dim3(64), 0, s, W.header, 0);
+      KVC_LAUNCH_CHECK();
+    }
+  }
+  hipLaunchKernelGGL(select_tie_count_kernel, dim3(gw), dim3(256), 0, s, D, protect_tail_blocks, block_key,
+                     st->ctx_len, seq_seg, W.seg_state, W.off_b);
+  KVC_LAUNCH_CHECK();
+  rc = device_exclusive_scan(TieFn{W.off_b}, D.G, W.tile_sums, W.off_a, nullptr, s);
+  if (rc != KVC_OK) return rc;
+  hipLaunchKernelGGL(select_mark_kernel, dim3(gw), dim3(256), 0, s, D, protect_tail_blocks, block_key,
+                     st->ctx_len, seq_seg, W.seg_state, W.off_a, evict_flag, evict_count, selected,
+                     W.header);
+  KVC_LAUNCH_CHECK();
+  return (flags & KVC_ASYNC) ? KVC_OK : finish_sync(W, s);
+}
+
+int kvc_compact(const kvc_config* cfg, const kvc_state* st, const uint8_t* evict_flag,
+                const int32_t* evict_count, int64_t* blocks_freed, void* ws, void* stream, int flags) {
+  int rc = validate(cfg, st);
+  if (rc != KVC_OK) return rc;
+  if (!evict_flag || !evict_count || !ws || ((uintptr_t)ws & 255)) return KVC_ERR_ARG;
+  if (blocks_freed && ((uintptr_t)blocks_freed & 7)) return KVC_ERR_ARG;
+  Dims D = dims_of(cfg);
+  Workspace W = carve(D, ws);
+  hipStream_t s = (hipStream_t)stream;
+  hipLaunchKernelGGL(zero_words_kernel, dim3(1), dim3(64), 0, s, W.header + HW_FREED, 1);
+  KVC_LAUNCH_CHECK();
+  hipLaunchKernelGGL(compact_scan_kernel, dim3((D.G + 3) / 4), dim3(256), 0, s, D, evict_flag, evict_count,
+                     st->ctx_len, W.flag_scan, W.header);
+  KVC_LAUNCH_CHECK();
+  hipLaunchKernelGGL(resolve_kernel, dim3(1), dim3(64), 0, s, W.header, 0);
+  KVC_LAUNCH_CHECK();
+  hipLaunchKernelGGL(compact_move_kernel, dim3(D.G), dim3(256), 0, s, D, (char*)st->k_cache,
+                     (char*)st->v_cache, st->metric, st->pos, st->block_table, st->ctx_len, st->free_map,
+                     evict_flag, evict_count, W.flag_scan, W.header);
+  KVC_LAUNCH_CHECK();
+  if (blocks_freed) {
+    hipLaunchKernelGGL(publish_freed_kernel, dim3(1), dim3(64), 0, s, W.header, blocks_freed);
+    KVC_LAUNCH_CHECK();
+  }
+  return (flags & KVC_ASYNC) ? KVC_OK : finish_sync(W, s);
+}
+
+}  // extern "C"

@@ -1,0 +1,94 @@
+"""CPU-side checks of the C ABI: the library loads without a GPU, exports every
+symbol include/kvc.h declares, and rejects bad arguments on the host before any
+HIP call."""
+import ctypes as C
+import os
+import re
+
+import pytest
+import torch
+
+from paper_2410_00161_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    src = open(os.path.join(ROOT, "include", "kvc.h")).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(kvc_[a-z_]+)\s*\(", src)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = B.lib()
+    names = declared_functions()
+    assert len(names) >= 12
+    for n in names:
+        assert hasattr(L, n), f"{n} declared in kvc.h but not exported"
+    assert sorted(B.EXPORTS) == names
+
+
+def good_cfg(**kw):
+    base = dict(num_seqs=2, num_layers=2, num_kv_heads=2, group_size=4, head_dim=128, block_size=16,
+                num_blocks=64, max_blocks_per_head=8, kv_dtype="bf16")
+    base.update(kw)
+    return B.make_config(**base)
+
+
+def test_validate_and_workspace_size():
+    cfg = good_cfg()
+    assert B.kvc_validate(cfg) == B.KVC_OK
+    n = B.kvc_workspace_bytes(cfg)
+    assert n > 0 and n % 256 == 0
+    assert B.kvc_workspace_bytes(good_cfg(num_blocks=128)) > n
+    for bad in (dict(num_seqs=0), dict(head_dim=-1), dict(kv_dtype=7), dict(block_size=0),
+                dict(metric_mode=3)):
+        c = good_cfg(**bad)
+        assert B.kvc_validate(c) == B.KVC_ERR_ARG
+        assert B.kvc_workspace_bytes(c) == 0
+    assert B.kvc_validate(good_cfg(group_size=32)) == B.KVC_ERR_UNSUPPORTED
+    assert B.kvc_validate(good_cfg(head_dim=100, kv_dtype="bf16")) == B.KVC_ERR_UNSUPPORTED
+
+
+def test_status_strings_and_chunk_knob():
+    seen = {B.status_string(c) for c in range(8)}
+    assert len(seen) == 8 and "ok" in seen
+    assert B.status_string(99) == "unknown status"
+    L = B.lib()
+    assert L.kvc_set_decode_chunk(100) == B.KVC_ERR_ARG
+    assert L.kvc_set_decode_chunk(16384) == B.KVC_ERR_ARG
+    assert L.kvc_set_decode_chunk(512) == B.KVC_OK
+    assert L.kvc_set_decode_chunk(0) == B.KVC_OK
+
+
+def test_entry_points_reject_bad_arguments_on_the_host():
+    """Null state pointers, a misaligned workspace and a bad layer range are
+    refused before anything is launched (so this runs without a GPU)."""
+    L = B.lib()
+    cfg = good_cfg()
+    st = B.kvc_state()  # all NULL
+    one = C.c_void_p(4096)
+    assert L.kvc_block_alloc(C.byref(cfg), C.byref(st), one, one, None, 0) == B.KVC_ERR_ARG
+    assert L.kvc_paged_decode(C.byref(cfg), C.byref(st), one, one, 0, 1, 1, one, None) == B.KVC_ERR_ARG
+    assert L.kvc_compact(C.byref(cfg), C.byref(st), one, one, None, one, None, 0) == B.KVC_ERR_ARG
+    # a plausible state (never dereferenced: the calls fail on later checks)
+    st = B.kvc_state(4096, 8192, 4096, None, 4096, 4096, 4096)
+    assert B.kvc_validate(cfg, st) == B.KVC_OK
+    assert L.kvc_paged_decode(C.byref(cfg), C.byref(st), one, one, 0, 3, 1, one, None) == B.KVC_ERR_ARG  # layers
+    assert L.kvc_paged_decode(C.byref(cfg), C.byref(st), one, one, 1, 1, 1, one, None) == B.KVC_ERR_ARG
+    assert L.kvc_paged_decode(C.byref(cfg), C.byref(st), None, one, 0, 1, 1, one, None) == B.KVC_ERR_ARG
+    assert L.kvc_paged_decode(C.byref(cfg), C.byref(st), one, one, 0, 1, 1, C.c_void_p(4100), None) == B.KVC_ERR_ARG
+    assert L.kvc_append(C.byref(cfg), C.byref(st), one, C.c_void_p(4104), None, 0, 1, one, None, 0) == B.KVC_ERR_ARG
+    assert L.kvc_evict_select(C.byref(cfg), C.byref(st), one, None, one, 1, 1, one, one, one, one, None, 0) == B.KVC_ERR_ARG  # nseg != S
+    assert L.kvc_evict_select(C.byref(cfg), C.byref(st), one, one, one, 3, 1, one, one, one, one, None, 0) == B.KVC_ERR_ARG  # nseg > S
+    assert L.kvc_metric_reduce(C.byref(cfg), C.byref(st), None, one, None) == B.KVC_ERR_ARG
+    st_bad = B.kvc_state(4097, 8192, 4096, None, 4096, 4096, 4096)
+    assert B.kvc_validate(cfg, st_bad) == B.KVC_ERR_ARG
+
+
+def test_binding_refuses_wrong_dtypes_and_strides():
+    t = torch.zeros(4, 4)
+    with pytest.raises(TypeError):
+        B._ptr(t, torch.int32)
+    with pytest.raises(ValueError):
+        B._ptr(t.t())

@@ -1,0 +1,386 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on
+the same seeded inputs.  Floating point within 2e-3 max-abs (outputs and
+metrics, fp32 accumulation on the GPU, fp64 in the oracle); tables, free maps,
+context lengths, block keys, selections and compacted caches bit-exact."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import kvc_oracle as O
+from paper_2410_00161_amd import binding as B
+from paper_2410_00161_amd import workloads as W
+from helpers import oracle_state, check_allocator_invariants
+
+pytestmark = pytest.mark.gpu
+TOL = 2e-3
+
+
+def session(cache, mode=B.KVC_L2):
+    from paper_2410_00161_amd.session import KvcSession
+    return KvcSession(cache, metric_mode=mode)
+
+
+def say(*a):
+    print("[case]", *a, flush=True)
+
+
+def assert_state_equal(sess, st: O.State, kv_exact=True):
+    c = sess.cache
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(c.block_table.cpu().numpy().astype(np.int64), st.block_table)
+    np.testing.assert_array_equal(c.ctx_len.cpu().numpy().astype(np.int64), st.ctx_len)
+    np.testing.assert_array_equal(c.free_map.cpu().numpy(), st.free_map)
+    if kv_exact:  # compare only slots that hold a KV: the rest is unspecified
+        k = c.k_cache.float().cpu().numpy().astype(np.float64)
+        v = c.v_cache.float().cpu().numpy().astype(np.float64)
+        m = c.metric.cpu().numpy().astype(np.float64)
+        p = c.pos.cpu().numpy().astype(np.int64)
+        for g in range(st.G):
+            n, o = O.slots_of(st, g)
+            np.testing.assert_array_equal(k[n, o], st.k_cache[n, o])
+            np.testing.assert_array_equal(v[n, o], st.v_cache[n, o])
+            np.testing.assert_array_equal(p[n, o], st.pos[n, o])
+            np.testing.assert_allclose(m[n, o], st.metric[n, o], rtol=0, atol=TOL)
+
+
+# ---------------------------------------------------------------------------
+# decode + metric
+# ---------------------------------------------------------------------------
+
+DECODE_CASES = [
+    # name, small_mixed kwargs, chunk tokens (0 = default), mode
+    ("bf16_d128_r4", dict(r=4, d=128, kv_dtype="bf16", L=700), 0, B.KVC_L2),
+    ("bf16_d128_r4_split", dict(r=4, d=128, kv_dtype="bf16", L=700), 128, B.KVC_L2),
+    ("bf16_d128_r8_split", dict(r=8, d=128, kv_dtype="bf16", L=500), 64, B.KVC_L2),
+    ("bf16_d128_r1", dict(r=1, d=128, kv_dtype="bf16", L=300), 0, B.KVC_L2),
+    ("bf16_d128_r2_L1", dict(r=2, d=128, kv_dtype="bf16", L=300), 64, B.KVC_L1),
+    ("bf16_d64_r4", dict(r=4, d=64, kv_dtype="bf16", L=400), 128, B.KVC_L2),
+    ("f32_d64_r2", dict(r=2, d=64, kv_dtype="f32", L=512), 0, B.KVC_L2),
+    ("f32_d128_r4_split", dict(r=4, d=128, kv_dtype="f32", L=400), 64, B.KVC_L2),
+    ("bf16_b32", dict(r=4, d=128, kv_dtype="bf16", L=400, b=32), 128, B.KVC_L2),
+    ("bf16_b4", dict(r=4, d=128, kv_dtype="bf16", L=200, b=4), 64, B.KVC_L2),
+    ("generic_b2", dict(r=4, d=128, kv_dtype="bf16", L=120, b=2), 0, B.KVC_L2),
+    ("generic_r3", dict(r=3, d=64, kv_dtype="f32", L=200), 0, B.KVC_L1),
+    ("generic_d32", dict(r=2, d=32, kv_dtype="bf16", L=200), 0, B.KVC_L2),
+]
+
+
+@pytest.mark.parametrize("name,kw,chunk,mode", DECODE_CASES, ids=[c[0] for c in DECODE_CASES])
+def test_decode_matches_oracle(name, kw, chunk, mode):
+    say("decode", name, kw, "chunk", chunk)
+    shape, ctx, seed = W.small_mixed(41, **kw)
+    ctx[1] = 0                       # a head with no KV at all
+    ctx[2] = 1                       # a single KV
+    ctx[3] = shape.block_size * 3    # ends exactly on a block boundary
+    cache = W.make_cache(shape, ctx, seed, placement="fragmented", init_metric="prefill")
+    # poison every slot that holds no KV: the kernels must never let it through
+    owner_real = torch.zeros_like(cache.metric, dtype=torch.bool)
+    st0 = oracle_state(cache)
+    for g in range(st0.G):
+        n, o = O.slots_of(st0, g)
+        owner_real[torch.from_numpy(n), torch.from_numpy(o)] = True
+    cache.v_cache[~owner_real] = float("nan")
+    cache.k_cache[~owner_real] = float("nan")
+    st = oracle_state(cache)
+    q = W.make_query(shape, seed)
+    want = O.paged_decode(st, q.double().numpy(), metric_mode="L2" if mode == B.KVC_L2 else "L1")
+    B.kvc_set_decode_chunk(chunk)
+    try:
+        sess = session(cache, mode)
+        sess.out.fill_(7.0)
+        out = sess.paged_decode(q.to(sess.device))
+        torch.cuda.synchronize()
+    finally:
+        B.kvc_set_decode_chunk(0)
+    got = out.cpu().numpy().astype(np.float64)
+    assert np.isfinite(got).all()
+    np.testing.assert_allclose(got, want, rtol=0, atol=TOL)
+    m = sess.cache.metric.cpu().numpy().astype(np.float64)
+    real = owner_real.numpy()
+    np.testing.assert_allclose(m[real], st.metric[real], rtol=0, atol=TOL)
+    # slots that hold no KV keep their old metric bit for bit
+    np.testing.assert_array_equal(m[~real], cache.metric.numpy().astype(np.float64)[~real])
+
+
+def test_decode_layer_range_and_no_metric():
+    say("decode layer range")
+    shape, ctx, seed = W.small_mixed(43, S=2, Lyr=3, Hk=2, r=4, d=128, L=300)
+    cache = W.make_cache(shape, ctx, seed, init_metric="prefill")
+    st = oracle_state(cache)
+    q = W.make_query(shape, seed)
+    sess = session(cache)
+    sess.out.fill_(-5.0)
+    m_before = sess.cache.metric.clone()
+    out = sess.paged_decode(q.to(sess.device), accumulate_metric=False, layer_begin=1, layer_end=2)
+    torch.cuda.synchronize()
+    want = O.paged_decode(st, q.double().numpy(), accumulate_metric=False, layer_begin=1, layer_end=2)
+    got = out.cpu().numpy()
+    np.testing.assert_allclose(got[:, 1], want[:, 1], rtol=0, atol=TOL)
+    assert (got[:, 0] == -5.0).all() and (got[:, 2] == -5.0).all()   # other layers untouched
+    assert torch.equal(sess.cache.metric, m_before)
+    # per-layer calls with accumulation == one call over all layers
+    for l in range(shape.num_layers):
+        sess.paged_decode(q.to(sess.device), accumulate_metric=True, layer_begin=l, layer_end=l + 1)
+    torch.cuda.synchronize()
+    want = O.paged_decode(st, q.double().numpy())
+    np.testing.assert_allclose(sess.out.cpu().numpy(), want, rtol=0, atol=TOL)
+    np.testing.assert_allclose(sess.cache.metric.cpu().numpy(), st.metric, rtol=0, atol=TOL)
+
+
+def test_decode_steps_accumulate_with_append():
+    say("append + decode x 20")
+    shape, ctx, seed = W.small_mixed(47, S=2, Lyr=2, Hk=2, r=4, d=128, L=100, extra_blocks=3)
+    cache = W.make_cache(shape, ctx, seed)
+    st = oracle_state(cache)
+    sess = session(cache)
+    for step in range(20):
+        k, v = W.make_new_kv(shape, seed, step)
+        q = W.make_query(shape, seed, step)
+        O.append(st, k.double().numpy(), v.double().numpy())
+        want = O.paged_decode(st, q.double().numpy())
+        sess.append(k.to(sess.device), v.to(sess.device))
+        out = sess.paged_decode(q.to(sess.device))
+        torch.cuda.synchronize()
+        np.testing.assert_allclose(out.cpu().numpy(), want, rtol=0, atol=TOL)
+    assert_state_equal(sess, st)
+    check_allocator_invariants(st)
+
+
+# ---------------------------------------------------------------------------
+# allocator
+# ---------------------------------------------------------------------------
+
+def test_alloc_free_match_oracle_bit_exactly():
+    say("alloc/free")
+    shape, ctx, seed = W.small_mixed(51, S=4, Lyr=3, Hk=4, L=260, slack=2.0)
+    cache = W.make_cache(shape, ctx, seed, placement="fragmented")
+    st = oracle_state(cache)
+    sess = session(cache)
+    rng = np.random.default_rng(0)
+    for it in range(4):
+        n_new = torch.from_numpy(rng.integers(0, 3, size=shape.G).astype(np.int32))
+        O.block_alloc(st, n_new.numpy())
+        sess.block_alloc(n_new)
+        assert_state_equal(sess, st, kv_exact=False)
+        held = np.array([O.num_blocks_held(st, g) for g in range(st.G)])
+        n_drop = torch.from_numpy(np.minimum(rng.integers(0, 3, size=shape.G), held).astype(np.int32))
+        freed_want = O.block_free(st, n_drop.numpy())
+        assert sess.block_free(n_drop) == freed_want
+        assert_state_equal(sess, st, kv_exact=False)
+    check_allocator_invariants(st)
+    # prefill from an empty pool: every head takes its blocks in one call
+    shape2, ctx2, _ = W.small_mixed(52, S=3, Lyr=2, Hk=2, L=5000, rho=6.0)
+    cache2 = W.make_cache(shape2, torch.zeros_like(ctx2), 52)
+    st2 = oracle_state(cache2)
+    sess2 = session(cache2)
+    nb = W.blocks_needed(ctx2, shape2.block_size).to(torch.int32)
+    O.block_alloc(st2, nb.numpy())
+    sess2.block_alloc(nb)
+    assert_state_equal(sess2, st2, kv_exact=False)
+
+
+def test_alloc_errors_leave_state_untouched():
+    say("alloc errors")
+    shape, ctx, seed = W.small_mixed(53, S=2, Lyr=2, Hk=2, L=200, extra_blocks=2)
+    total = int(W.blocks_needed(ctx, shape.block_size).sum())
+    shape = W.Shape(**{**shape.__dict__, "num_blocks": total + 5})       # five free blocks
+    cache = W.make_cache(shape, ctx, seed)
+    st = oracle_state(cache)
+    sess = session(cache)
+    big = torch.ones(shape.G, dtype=torch.int32)                          # 8 wanted, 5 free
+    cases = [(big, B.KVC_ERR_OOM)]
+    full = torch.zeros(shape.G, dtype=torch.int32); full[3] = shape.max_blocks_per_head
+    cases.append((full, B.KVC_ERR_TABLE_FULL))
+    neg = torch.zeros(shape.G, dtype=torch.int32); neg[1] = -1
+    cases.append((neg, B.KVC_ERR_ARG))
+    for req, code in cases:
+        with pytest.raises(O.OracleError) as eo:
+            O.block_alloc(st, req.numpy())
+        assert eo.value.code == code
+        with pytest.raises(B.KvcError) as e:
+            sess.block_alloc(req)
+        assert e.value.code == code
+        assert_state_equal(sess, st, kv_exact=False)
+    # asynchronous form: the error waits in the status word and later steps are no-ops
+    sess.block_alloc(big, flags=B.KVC_ASYNC)
+    assert B.kvc_poll_status(sess.cfg, sess.ws) == B.KVC_ERR_OOM
+    ok = torch.zeros(shape.G, dtype=torch.int32); ok[0] = 1
+    sess.block_alloc(ok, flags=B.KVC_ASYNC)
+    assert_state_equal(sess, st, kv_exact=False)       # still untouched: the error is sticky
+    B.kvc_workspace_reset(sess.cfg, sess.ws)
+    sess.block_alloc(ok)
+    O.block_alloc(st, ok.numpy())
+    assert_state_equal(sess, st, kv_exact=False)
+    # drop more than held
+    over = torch.zeros(shape.G, dtype=torch.int32); over[2] = 10 ** 6
+    with pytest.raises(B.KvcError) as e:
+        sess.block_free(over)
+    assert e.value.code == B.KVC_ERR_ARG
+    assert_state_equal(sess, st, kv_exact=False)
+    # append with the table row full
+    shape3, ctx3, _ = W.small_mixed(54, S=1, Lyr=1, Hk=2, L=64, rho=1.0, extra_blocks=0)
+    shape3 = W.Shape(**{**shape3.__dict__, "max_blocks_per_head": 4})
+    ctx3[:] = 64
+    cache3 = W.make_cache(shape3, ctx3, 54)
+    st3 = oracle_state(cache3); sess3 = session(cache3)
+    k, v = W.make_new_kv(shape3, 54)
+    with pytest.raises(O.OracleError):
+        O.append(st3, k.double().numpy(), v.double().numpy())
+    with pytest.raises(B.KvcError) as e:
+        sess3.append(k.to(sess3.device), v.to(sess3.device))
+    assert e.value.code == B.KVC_ERR_TABLE_FULL
+    assert_state_equal(sess3, st3)
+
+
+# ---------------------------------------------------------------------------
+# block keys, selection, compaction
+# ---------------------------------------------------------------------------
+
+def test_block_keys_bit_exact():
+    say("block keys")
+    shape, ctx, seed = W.small_mixed(61, S=3, Lyr=2, Hk=3, L=900)
+    cache = W.make_cache(shape, ctx, seed, placement="fragmented", init_metric="prefill")
+    st0 = oracle_state(cache)
+    real = np.zeros((shape.num_blocks, shape.block_size), dtype=bool)
+    for g in range(st0.G):
+        n, o = O.slots_of(st0, g); real[n, o] = True
+    cache.metric[torch.from_numpy(~real)] = float("nan")
+    st = oracle_state(cache)
+    want, _ = O.block_keys(st, cache.metric.numpy())
+    sess = session(cache)
+    sess.block_key.fill_(123.0)
+    got = sess.metric_reduce().cpu().numpy()
+    np.testing.assert_array_equal(got.view(np.uint32), want.view(np.uint32))
+
+
+SELECT_CASES = [
+    ("per_seq_protect1", dict(pooled=False, protect=1, ties=False, frac=0.5)),
+    ("per_seq_protect0", dict(pooled=False, protect=0, ties=False, frac=0.3)),
+    ("pooled", dict(pooled=True, protect=1, ties=False, frac=0.4)),
+    ("heavy_ties", dict(pooled=False, protect=1, ties=True, frac=0.5)),
+    ("pooled_ties_protect0", dict(pooled=True, protect=0, ties=True, frac=0.6)),
+    ("budget_zero_and_huge", dict(pooled=False, protect=1, ties=False, frac=None)),
+]
+
+
+@pytest.mark.parametrize("name,kw", SELECT_CASES, ids=[c[0] for c in SELECT_CASES])
+def test_select_and_compact_bit_exact(name, kw):
+    say("select+compact", name)
+    shape, ctx, seed = W.small_mixed(71, S=4, Lyr=3, Hk=2, r=2, d=64, L=1200, rho=2.0)
+    cache = W.make_cache(shape, ctx, seed, placement="fragmented", init_metric="prefill")
+    if kw["ties"]:
+        g = torch.Generator().manual_seed(5)
+        cache.metric = torch.randint(0, 2, cache.metric.shape, generator=g).float()
+    st = oracle_state(cache)
+    sess = session(cache)
+    key = sess.metric_reduce()
+    want_key, _ = O.block_keys(st, cache.metric.numpy())
+    nb = -(-st.lens() // st.b)
+    per_seq = nb.reshape(st.S, -1).sum(1)
+    if kw["pooled"]:
+        seg = torch.tensor([0, 1, 1, st.S], dtype=torch.int32)  # one empty segment in the middle
+        tot = [int(per_seq[:1].sum()), 0, int(per_seq[1:].sum())]
+        budget = torch.tensor([int(kw["frac"] * t) for t in tot], dtype=torch.int32)
+        if budget[1] == 0:
+            budget[1] = 3  # asks for blocks from a segment that has none
+    else:
+        seg = None
+        if kw["frac"] is None:
+            budget = torch.tensor([0, 10 ** 6, 1, int(per_seq[3])], dtype=torch.int32)
+        else:
+            budget = torch.tensor([int(kw["frac"] * t) for t in per_seq], dtype=torch.int32)
+    flag_w, count_w, sel_w = O.evict_select(st, want_key, budget.numpy(),
+                                            None if seg is None else seg.numpy(), kw["protect"])
+    flag, count, sel = sess.evict_select(budget, seg, kw["protect"])
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(key.cpu().numpy().view(np.uint32), want_key.view(np.uint32))
+    np.testing.assert_array_equal(sel.cpu().numpy(), sel_w)
+    np.testing.assert_array_equal(count.cpu().numpy(), count_w)
+    np.testing.assert_array_equal(flag.cpu().numpy(), flag_w)
+    freed_w = O.compact(st, flag_w, count_w)
+    freed = sess.compact()
+    torch.cuda.synchronize()
+    assert int(freed.item()) == freed_w == int(sel_w.sum())
+    assert_state_equal(sess, st)
+    check_allocator_invariants(st)
+    # the compacted cache still decodes to the oracle's result
+    q = W.make_query(shape, seed, 9)
+    want = O.paged_decode(st, q.double().numpy())
+    out = sess.paged_decode(q.to(sess.device))
+    torch.cuda.synchronize()
+    np.testing.assert_allclose(out.cpu().numpy(), want, rtol=0, atol=TOL)
+
+
+def test_select_numeric_error_and_compact_argument_error():
+    say("select/compact errors")
+    shape, ctx, seed = W.small_mixed(73, S=2, Lyr=2, Hk=2, r=2, d=64, L=300)
+    cache = W.make_cache(shape, ctx, seed, init_metric="prefill")
+    st = oracle_state(cache)
+    sess = session(cache)
+    key = sess.metric_reduce().clone()
+    budget = torch.tensor([3, 3], dtype=torch.int32)
+    for bad in (float("nan"), -1.0, float("inf")):
+        k2 = key.clone(); k2[0, 0] = bad
+        with pytest.raises(B.KvcError) as e:
+            sess.evict_select(budget, block_key=k2)
+        assert e.value.code == B.KVC_ERR_NUMERIC
+        assert int(sess.evict_flag.sum()) == 0 and int(sess.evict_count.sum()) == 0
+    k2 = key.clone(); k2[0, 0] = -0.0     # minus zero is a valid key equal to zero
+    sess.evict_select(budget, block_key=k2)
+    neg = torch.tensor([3, -1], dtype=torch.int32)
+    with pytest.raises(B.KvcError) as e:
+        sess.evict_select(neg)
+    assert e.value.code == B.KVC_ERR_ARG
+    # compact: a flag beyond the head's blocks, and a count that disagrees
+    flag, count, sel = sess.evict_select(budget)
+    f2 = flag.clone(); f2[0, shape.max_blocks_per_head - 1] = 1
+    with pytest.raises(B.KvcError) as e:
+        sess.compact(f2, count)
+    assert e.value.code == B.KVC_ERR_ARG
+    c2 = count.clone(); c2[1] += 1
+    with pytest.raises(B.KvcError) as e:
+        sess.compact(flag, c2)
+    assert e.value.code == B.KVC_ERR_ARG
+    assert_state_equal(sess, st)
+
+
+def test_tiny_reference_config_end_to_end():
+    """Configuration 1: one decode step from zero metrics, evict half the blocks
+    (per sequence, then pooled), compact; everything compared."""
+    for pooled in (False, True):
+        say("tiny ref pooled=", pooled)
+        shape, ctx, seed = W.tiny_ref()
+        cache = W.make_cache(shape, ctx, seed)
+        st = oracle_state(cache)
+        sess = session(cache)
+        q = W.make_query(shape, seed)
+        want = O.paged_decode(st, q.double().numpy())
+        out = sess.paged_decode(q.to(sess.device))
+        torch.cuda.synchronize()
+        np.testing.assert_allclose(out.cpu().numpy(), want, rtol=0, atol=TOL)
+        key = sess.metric_reduce()
+        torch.cuda.synchronize()
+        # selection parity is defined on identical metric inputs: the oracle ranks the GPU's keys
+        want_key, want_key64 = O.block_keys(st, sess.cache.metric.cpu().numpy())
+        np.testing.assert_array_equal(key.cpu().numpy().view(np.uint32), want_key.view(np.uint32))
+        np.testing.assert_allclose(want_key, O.block_keys(st)[1], rtol=0, atol=TOL * 16)
+        nb_seq = (-(-st.lens() // st.b)).reshape(st.S, -1).sum(1)
+        if pooled:
+            seg = torch.tensor([0, st.S], dtype=torch.int32)
+            budget = torch.tensor([int(nb_seq.sum()) // 2], dtype=torch.int32)
+        else:
+            seg, budget = None, torch.tensor(nb_seq // 2, dtype=torch.int32)
+        flag_w, count_w, sel_w = O.evict_select(st, want_key, budget.numpy(),
+                                                None if seg is None else seg.numpy(), 1)
+        flag, count, sel = sess.evict_select(budget, seg, 1)
+        np.testing.assert_array_equal(flag.cpu().numpy(), flag_w)
+        np.testing.assert_array_equal(sel.cpu().numpy(), sel_w)
+        st.metric = sess.cache.metric.cpu().numpy().astype(np.float64)   # same metric inputs
+        free_before = int(sess.cache.free_map.sum())
+        freed_w = O.compact(st, flag_w, count_w)
+        freed = int(sess.compact().item())
+        assert freed == freed_w == int(budget.sum())
+        # memory freed = evicted blocks x block bytes
+        assert (int(sess.cache.free_map.sum()) - free_before) * shape.block_size * shape.head_dim * 4 * 2 \
+            == freed * 2 * shape.block_size * shape.head_dim * shape.kv_bytes
+        assert_state_equal(sess, st)
