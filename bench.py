@@ -1,0 +1,230 @@
+#!/usr/bin/env python3
+"""Benchmark of the KV-Compress hot path on one MI355X.
+
+A step = one pass of the path over the batch: append the new token's k, v for
+every (sequence, layer, KV head), then one paged decode over all layers with
+metric accumulation; every --evict-every steps a compression round (block keys
+-> selection -> compaction) returns as many blocks as were appended since the
+last round, so the cache stays at its compression rate.
+
+Workload at N = 1: the Llama-3.1-8B-shaped decode (32 layers, 32 q / 8 KV
+heads, d = 128, bf16, b = 16, 64 sequences of 8192 prompt tokens, per-head
+retention log-uniform with mean 8x), synthetic data, inputs resident in HBM.
+
+Prints ONE JSON line.  value = algorithmic decode bytes moved per second over
+the whole timed region (append and compression rounds included in the time).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
+
+
+def algorithmic_bytes_per_kv(shape):
+    """K row + V row read, metric read + write (f32), one table entry per b KVs."""
+    return 2 * shape.head_dim * shape.kv_bytes + 8 + 4.0 / shape.block_size
+
+
+def read_traffic_note(name):
+    """HBM bytes per launch measured with rocprofv3 --pmc, kept as text under profiles/."""
+    p = os.path.join(ROOT, "profiles", name)
+    if not os.path.exists(p):
+        return None
+    for line in open(p):
+        if line.startswith("traffic_bytes_per_launch:"):
+            return float(line.split(":")[1])
+    return None
+
+
+def cpu_baseline(sess, q, shape, n_heads, seed):
+    """Times the CPU oracle, as it stands, on a sample of head instances."""
+    import numpy as np
+    import torch
+    from threadpoolctl import threadpool_limits
+    from oracle import kvc_oracle as O
+    from paper_2410_00161_amd import workloads as W
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+    from helpers import oracle_state
+    g = torch.Generator().manual_seed(seed)
+    heads = torch.randperm(shape.G, generator=g)[:n_heads].tolist()
+    small, q_small = W.gather_heads(sess.cache, heads, q)
+    st = oracle_state(small)
+    kvs = int(st.lens().sum())
+    with threadpool_limits(limits=1):
+        t0 = time.perf_counter()
+        O.paged_decode(st, q_small.double().numpy())
+        key, _ = O.block_keys(st)
+        dt = time.perf_counter() - t0
+    gbs = kvs * algorithmic_bytes_per_kv(shape) / dt / 1e9
+    return {"value": gbs, "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "sample": f"{n_heads} of {shape.G} head instances ({kvs} KVs), one decode step with "
+                      f"metric accumulation + block keys, {dt:.1f} s, numpy fp64 oracle, BLAS limited to 1 thread"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=64)
+    ap.add_argument("--warmup", type=int, default=8)
+    ap.add_argument("--evict-every", type=int, default=16)
+    ap.add_argument("--num-seqs", type=int, default=64)
+    ap.add_argument("--prompt", type=int, default=8192)
+    ap.add_argument("--rho", type=float, default=8.0, help="mean compression rate")
+    ap.add_argument("--placement", default="fresh", choices=["fresh", "fragmented"])
+    ap.add_argument("--chunk", type=int, default=0, help="decode chunk tokens (0 = library default)")
+    ap.add_argument("--cpu-heads", type=int, default=512, help="head instances timed on the CPU oracle (0 = skip)")
+    ap.add_argument("--workload", default="llama8b", choices=["llama8b", "llama70b"])
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
+              "(every step is independent per head instance and would shard without communication).",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2410_00161_amd import binding as B, workloads as W
+    from paper_2410_00161_amd.session import KvcSession
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    B.lib()
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    total_steps = args.steps + args.warmup
+    extra = total_steps + 2 * args.evict_every + 16
+    if args.workload == "llama8b":
+        shape, ctx, seed = W.llama8b_decode(num_seqs=args.num_seqs, prompt=args.prompt, rho=args.rho,
+                                            extra_tokens=extra)
+        name = (f"Llama-3.1-8B-shaped decode: 32 layers, 32q/8kv heads, d=128, bf16 KV, b=16, "
+                f"{args.num_seqs} seqs x {args.prompt} prompt tokens, per-head retention log-uniform mean {args.rho:g}x")
+    else:
+        shape, ctx, seed = W.llama70b_decode(num_seqs=args.num_seqs, prompt=args.prompt, rho=args.rho,
+                                             extra_tokens=extra)
+        name = (f"Llama-3.1-70B-shaped decode: 80 layers, 64q/8kv heads, d=128, bf16 KV, b=16, "
+                f"{args.num_seqs} seqs x {args.prompt} prompt tokens, per-head retention log-uniform mean {args.rho:g}x")
+    t_setup = time.perf_counter()
+    cache = W.make_cache(shape, ctx, seed, device=dev, placement=args.placement, init_metric="prefill")
+    sess = KvcSession(cache, device=dev)
+    del cache
+    B.kvc_set_decode_chunk(args.chunk)
+    bytes_kv = algorithmic_bytes_per_kv(shape)
+    G = shape.G
+    per_seq = shape.num_layers * shape.num_kv_heads
+    print(f"[bench] {name}", file=sys.stderr)
+    print(f"[bench] G={G} head instances, {int(ctx.sum())} KVs, {shape.num_blocks} blocks in the pool, "
+          f"realised compression {args.prompt * G / float(ctx.sum()):.2f}x, "
+          f"setup {time.perf_counter() - t_setup:.1f}s", file=sys.stderr, flush=True)
+
+    # pre-generated inputs for a few steps, reused round-robin (they stay in HBM)
+    n_in = 4
+    qs = [W.make_query(shape, seed, i, dev) for i in range(n_in)]
+    kvs_new = [W.make_new_kv(shape, seed, i, dev) for i in range(n_in)]
+    ctx_log = torch.zeros((total_steps, G), dtype=torch.int32, device=dev)
+    budget = torch.full((shape.num_seqs,), per_seq * args.evict_every // shape.block_size,
+                        dtype=torch.int32, device=dev)
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    evict_events = []
+
+    def step(i, timed):
+        k, v = kvs_new[i % n_in]
+        sess.append(k, v, flags=B.KVC_ASYNC)
+        sess.paged_decode(qs[i % n_in], accumulate_metric=True)
+        ctx_log[i].copy_(sess.cache.ctx_len.reshape(-1))
+        if args.evict_every > 0 and (i + 1) % args.evict_every == 0:
+            e = [ev() for _ in range(4)]
+            e[0].record()
+            sess.metric_reduce()
+            e[1].record()
+            sess.evict_select(budget, flags=B.KVC_ASYNC)
+            e[2].record()
+            sess.compact(flags=B.KVC_ASYNC)
+            e[3].record()
+            if timed:
+                evict_events.append(e)
+
+    for i in range(args.warmup):
+        step(i, False)
+    torch.cuda.synchronize()
+    assert B.kvc_poll_status(sess.cfg, sess.ws) == B.KVC_OK
+    B.kvc_profile_begin(args.steps)
+    t0, t1 = ev(), ev()
+    torch.cuda.synchronize()
+    wall0 = time.perf_counter()
+    t0.record()
+    for i in range(args.warmup, total_steps):
+        step(i, True)
+    t1.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - wall0
+    status = B.kvc_poll_status(sess.cfg, sess.ws)
+    if status != B.KVC_OK:
+        print(f"bench.py: device-side error {status} ({B.status_string(status)})", file=sys.stderr)
+        sys.exit(1)
+    ms_total = t0.elapsed_time(t1)
+    chunk_ms, combine_ms = B.kvc_profile_collect(args.steps)
+    B.kvc_profile_begin(0)
+
+    ctx_t = ctx_log[args.warmup:].to(torch.int64)
+    kv_per_step = ctx_t.sum(1).cpu().numpy().astype(np.float64)
+    # tokens the chunk kernel finalises itself (heads of one chunk) vs those left to the combine kernel
+    chunk_T = args.chunk if args.chunk else (1024 if shape.group_size >= 8 else 2048)
+    single = (ctx_t * (ctx_t <= chunk_T)).sum(1).cpu().numpy().astype(np.float64)
+    total_bytes = float(kv_per_step.sum()) * bytes_kv
+    value = total_bytes / (ms_total * 1e-3) / 1e9
+    ms_step = ms_total / args.steps
+
+    # dominant kernel: decode_chunk_kernel (streams K and V once; metric RMW for heads of one chunk)
+    chunk_alg = kv_per_step * (2 * shape.head_dim * shape.kv_bytes + 4.0 / shape.block_size) + 8.0 * single
+    chunk_ms = np.array(chunk_ms[:args.steps], dtype=np.float64)
+    combine_ms = np.array(combine_ms[:args.steps], dtype=np.float64)
+    ach = float(chunk_alg.mean() / (chunk_ms.mean() * 1e-3) / 1e9)
+    traffic = read_traffic_note("decode_chunk_kernel_llama8b_pmc.txt") if args.workload == "llama8b" else None
+    roofline = {"bound": "hbm", "kernel": "decode_chunk_kernel<2,128,%d>" % shape.group_size,
+                "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
+                "traffic": traffic, "avg_kernel_ms": float(chunk_ms.mean()),
+                "algorithmic_bytes_per_launch": float(chunk_alg.mean()),
+                "decode_call_GBps": float((kv_per_step * bytes_kv).mean() /
+                                          ((chunk_ms + combine_ms).mean() * 1e-3) / 1e9),
+                "combine_kernel_ms": float(combine_ms.mean())}
+
+    evict = None
+    if evict_events:
+        r = np.array([[e[j].elapsed_time(e[j + 1]) for j in range(3)] for e in evict_events])
+        evict = {"rounds": len(evict_events), "reduce_ms": float(r[:, 0].mean()),
+                 "select_ms": float(r[:, 1].mean()), "compact_ms": float(r[:, 2].mean()),
+                 "total_ms": float(r.sum(1).mean()), "blocks_per_round": int(budget.sum().item())}
+
+    cpu = None
+    if args.cpu_heads > 0:
+        cpu = cpu_baseline(sess, qs[0], shape, args.cpu_heads, seed)
+
+    out = {
+        "metric": "decode-attn HBM GB/s (% of peak) at 8x compression; eviction+compaction ms",
+        "value": value, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": name, "placement": args.placement, "evict_every": args.evict_every,
+                   "chunk_tokens": chunk_T, "head_instances": G,
+                   "mean_kvs_per_step": float(kv_per_step.mean())},
+        "frac_of_hbm_peak": value / HBM_PEAK_GBS,
+        "decode_steps_per_s": 1e3 / ms_step,
+        "wall_s": wall,
+        "eviction": evict,
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+        "gpu": torch.cuda.get_device_name(0), "host_cpus": os.cpu_count(),
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

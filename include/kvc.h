@@ -194,6 +194,17 @@ int kvc_compact(const kvc_config* cfg, const kvc_state* st, const uint8_t* evict
  * host only.  KVC_ERR_ARG unless 0 or a multiple of 64 in [64, 8192].          */
 int kvc_set_decode_chunk(int tokens);
 
+/* Kernel timing for benchmarks.  kvc_profile_begin(n) makes the next n calls of
+ * kvc_paged_decode record a HIP event pair on their stream around the chunk
+ * kernel (the kernel that streams K and V) and another around the combine
+ * kernel; n = 0 switches recording off and releases the events.  Host only
+ * state, process-wide, at most 4096 pairs.  kvc_profile_collect waits for the
+ * recorded events and writes up to `cap` durations in milliseconds to the host
+ * arrays chunk_ms and combine_ms (either may be NULL), returning the number of
+ * recorded calls in *count (host).                                             */
+int kvc_profile_begin(int n);
+int kvc_profile_collect(float* chunk_ms, float* combine_ms, int cap, int* count);
+
 #ifdef __cplusplus
 }
 #endif

@@ -25,6 +25,7 @@ EXPORTS = [
     "kvc_workspace_bytes", "kvc_validate", "kvc_status_string", "kvc_workspace_reset",
     "kvc_poll_status", "kvc_block_alloc", "kvc_block_free", "kvc_append", "kvc_paged_decode",
     "kvc_metric_reduce", "kvc_evict_select", "kvc_compact", "kvc_set_decode_chunk",
+    "kvc_profile_begin", "kvc_profile_collect",
 ]
 
 
@@ -73,6 +74,8 @@ def lib() -> C.CDLL:
         L.kvc_evict_select.argtypes = [cfgp, stp, P, P, P, I, I, P, P, P, P, P, I]
         L.kvc_compact.argtypes = [cfgp, stp, P, P, P, P, P, I]
         L.kvc_set_decode_chunk.argtypes = [I]
+        L.kvc_profile_begin.argtypes = [I]
+        L.kvc_profile_collect.argtypes = [P, P, I, C.POINTER(C.c_int)]
         for n in EXPORTS:
             if n not in ("kvc_workspace_bytes", "kvc_status_string"):
                 getattr(L, n).restype = I
@@ -204,3 +207,17 @@ def kvc_compact(cfg, st, evict_flag, evict_count, blocks_freed, ws, stream=None,
 
 def kvc_set_decode_chunk(tokens: int):
     _check(lib().kvc_set_decode_chunk(int(tokens)), "kvc_set_decode_chunk")
+
+
+def kvc_profile_begin(n: int):
+    _check(lib().kvc_profile_begin(int(n)), "kvc_profile_begin")
+
+
+def kvc_profile_collect(cap: int = 4096):
+    """Returns (chunk_ms, combine_ms) lists of the recorded decode calls."""
+    a = (C.c_float * cap)()
+    b = (C.c_float * cap)()
+    n = C.c_int(0)
+    _check(lib().kvc_profile_collect(a, b, cap, C.byref(n)), "kvc_profile_collect")
+    k = min(n.value, cap)
+    return list(a[:k]), list(b[:k])

@@ -27,6 +27,11 @@ namespace kvc {
 
 static int g_chunk_tokens = 0;  // 0 = default; set by kvc_set_decode_chunk
 
+// optional event pairs around the two decode kernels (kvc_profile_begin / _collect)
+struct ProfilePair { hipEvent_t a0, a1, b0, b1; };
+static ProfilePair* g_prof = nullptr;
+static int g_prof_cap = 0, g_prof_used = 0;
+
 struct DecodeArgs {
   Dims D;
   const char* kc;
@@ -500,10 +505,14 @@ __global__ void __launch_bounds__(256) decode_generic_kernel(DecodeArgs A) {
 template <int ESZ, int HD, int R>
 static int launch_tiled(const DecodeArgs& A, int grid, size_t lds, hipStream_t s) {
   auto kern = decode_chunk_kernel<ESZ, HD, R>;
+  ProfilePair* pp = (g_prof && g_prof_used < g_prof_cap) ? &g_prof[g_prof_used++] : nullptr;
+  if (pp) KVC_HIP(hipEventRecord(pp->a0, s));
   hipLaunchKernelGGL(kern, dim3(grid), dim3(kDecodeThreads), lds, s, A);
   KVC_LAUNCH_CHECK();
+  if (pp) { KVC_HIP(hipEventRecord(pp->a1, s)); KVC_HIP(hipEventRecord(pp->b0, s)); }
   hipLaunchKernelGGL(decode_combine_kernel<R>, dim3(grid), dim3(256), 0, s, A);
   KVC_LAUNCH_CHECK();
+  if (pp) KVC_HIP(hipEventRecord(pp->b1, s));
   return KVC_OK;
 }
 
@@ -525,6 +534,39 @@ constexpr size_t kLdsLimit = 64 * 1024;
 using namespace kvc;
 
 extern "C" {
+
+int kvc_profile_begin(int n) {
+  if (n < 0 || n > 4096) return KVC_ERR_ARG;
+  if (g_prof) {
+    for (int i = 0; i < g_prof_cap; ++i) {
+      hipEventDestroy(g_prof[i].a0); hipEventDestroy(g_prof[i].a1);
+      hipEventDestroy(g_prof[i].b0); hipEventDestroy(g_prof[i].b1);
+    }
+    delete[] g_prof;
+    g_prof = nullptr;
+  }
+  g_prof_cap = g_prof_used = 0;
+  if (n == 0) return KVC_OK;
+  g_prof = new ProfilePair[n];
+  for (int i = 0; i < n; ++i) {
+    KVC_HIP(hipEventCreate(&g_prof[i].a0)); KVC_HIP(hipEventCreate(&g_prof[i].a1));
+    KVC_HIP(hipEventCreate(&g_prof[i].b0)); KVC_HIP(hipEventCreate(&g_prof[i].b1));
+  }
+  g_prof_cap = n;
+  return KVC_OK;
+}
+
+int kvc_profile_collect(float* chunk_ms, float* combine_ms, int cap, int* count) {
+  if (!count || cap < 0) return KVC_ERR_ARG;
+  *count = g_prof_used;
+  for (int i = 0; i < g_prof_used && i < cap; ++i) {
+    KVC_HIP(hipEventSynchronize(g_prof[i].b1));
+    float ms = 0.0f;
+    if (chunk_ms) { KVC_HIP(hipEventElapsedTime(&ms, g_prof[i].a0, g_prof[i].a1)); chunk_ms[i] = ms; }
+    if (combine_ms) { KVC_HIP(hipEventElapsedTime(&ms, g_prof[i].b0, g_prof[i].b1)); combine_ms[i] = ms; }
+  }
+  return KVC_OK;
+}
 
 int kvc_set_decode_chunk(int tokens) {
   if (tokens != 0 && (tokens < kMinChunk || tokens > kMaxChunk || tokens % 64 != 0)) return KVC_ERR_ARG;

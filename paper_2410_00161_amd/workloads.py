@@ -291,3 +291,39 @@ def small_mixed(seed: int, S=3, Lyr=2, Hk=2, r=4, d=128, b=16, L=700, rho=3.0,
     maxb = (L + b - 1) // b + extra_blocks
     shape = Shape(S, Lyr, Hk, r, d, b, N, maxb, kv_dtype)
     return shape, ctx, seed
+
+
+def gather_heads(cache: Cache, heads, q: torch.Tensor | None = None):
+    """Copies the chosen head instances into a small CPU cache of its own.
+
+    The result has S' = len(heads), one layer, one KV head; its blocks are
+    renumbered 0, 1, 2, ... in table order.  Returns (small_cache, q_small)
+    where q_small [S', 1, r, d] holds the query rows of those heads.  Pure data
+    movement: lets a CPU check run on a sample of a cache too large for the host.
+    """
+    sh = cache.shape
+    heads = [int(g) for g in heads]
+    G, maxb, b = sh.G, sh.max_blocks_per_head, sh.block_size
+    table = cache.block_table.reshape(G, maxb)
+    ctx = cache.ctx_len.reshape(G)
+    idx = torch.tensor(heads, dtype=torch.long, device=table.device)
+    rows = table[idx].cpu()
+    lens = ctx[idx].cpu()
+    held = (rows >= 0).sum(1)
+    total = int(held.sum())
+    new_table = torch.full((len(heads), maxb), -1, dtype=torch.int32)
+    src_ids = rows[rows >= 0].long()
+    new_table[rows >= 0] = torch.arange(total, dtype=torch.int32)
+    small_shape = Shape(len(heads), 1, 1, sh.group_size, sh.head_dim, b, max(total, 1), maxb, sh.kv_dtype)
+    dev_ids = src_ids.to(cache.k_cache.device)
+    take = lambda t: t[dev_ids].cpu() if total else t[:1].cpu()
+    small = Cache(small_shape, take(cache.k_cache), take(cache.v_cache), take(cache.metric),
+                  take(cache.pos), new_table.reshape(len(heads), 1, 1, maxb),
+                  lens.to(torch.int32).reshape(len(heads), 1, 1),
+                  torch.zeros(max(total, 1), dtype=torch.uint8) if total else torch.ones(1, dtype=torch.uint8),
+                  None)
+    q_small = None
+    if q is not None:
+        r, d = sh.group_size, sh.head_dim
+        q_small = q.reshape(G, r, d)[idx.to(q.device)].cpu().reshape(len(heads), 1, r, d)
+    return small, q_small
