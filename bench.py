@@ -81,6 +81,10 @@ def main():
     ap.add_argument("--chunk", type=int, default=0, help="decode chunk tokens (0 = library default)")
     ap.add_argument("--cpu-heads", type=int, default=512, help="head instances timed on the CPU oracle (0 = skip)")
     ap.add_argument("--workload", default="llama8b", choices=["llama8b", "llama70b"])
+    ap.add_argument("--uniform", action="store_true", help="diagnostic: every head holds prompt/rho KVs")
+    ap.add_argument("--no-metric", action="store_true", help="diagnostic: decode without metric accumulation")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy (a kernel of known traffic, for scaling rocprofv3 counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
@@ -111,6 +115,9 @@ def main():
                                              extra_tokens=extra)
         name = (f"Llama-3.1-70B-shaped decode: 80 layers, 64q/8kv heads, d=128, bf16 KV, b=16, "
                 f"{args.num_seqs} seqs x {args.prompt} prompt tokens, per-head retention log-uniform mean {args.rho:g}x")
+    if args.uniform:
+        ctx = W.uniform_lengths(shape.G, int(args.prompt / args.rho))
+        name += " [diagnostic: uniform lengths]"
     t_setup = time.perf_counter()
     cache = W.make_cache(shape, ctx, seed, device=dev, placement=args.placement, init_metric="prefill")
     sess = KvcSession(cache, device=dev)
@@ -128,7 +135,9 @@ def main():
     n_in = 4
     qs = [W.make_query(shape, seed, i, dev) for i in range(n_in)]
     kvs_new = [W.make_new_kv(shape, seed, i, dev) for i in range(n_in)]
-    ctx_log = torch.zeros((total_steps, G), dtype=torch.int32, device=dev)
+    snaps = {}   # step -> context lengths the decode of that step saw
+    snap_every = args.evict_every if args.evict_every > 0 else 16
+    prof_every = 4
     budget = torch.full((shape.num_seqs,), per_seq * args.evict_every // shape.block_size,
                         dtype=torch.int32, device=dev)
     ev = lambda: torch.cuda.Event(enable_timing=True)
@@ -137,8 +146,11 @@ def main():
     def step(i, timed):
         k, v = kvs_new[i % n_in]
         sess.append(k, v, flags=B.KVC_ASYNC)
-        sess.paged_decode(qs[i % n_in], accumulate_metric=True)
-        ctx_log[i].copy_(sess.cache.ctx_len.reshape(-1))
+        if timed:
+            B.kvc_profile_enable((i - args.warmup) % prof_every == 0)
+        sess.paged_decode(qs[i % n_in], accumulate_metric=not args.no_metric)
+        if i % snap_every == 0 or i == args.warmup:
+            snaps[i] = sess.cache.ctx_len.reshape(-1).clone()
         if args.evict_every > 0 and (i + 1) % args.evict_every == 0:
             e = [ev() for _ in range(4)]
             e[0].record()
@@ -155,7 +167,7 @@ def main():
         step(i, False)
     torch.cuda.synchronize()
     assert B.kvc_poll_status(sess.cfg, sess.ws) == B.KVC_OK
-    B.kvc_profile_begin(args.steps)
+    B.kvc_profile_begin((args.steps + prof_every - 1) // prof_every)
     t0, t1 = ev(), ev()
     torch.cuda.synchronize()
     wall0 = time.perf_counter()
@@ -170,31 +182,64 @@ def main():
         print(f"bench.py: device-side error {status} ({B.status_string(status)})", file=sys.stderr)
         sys.exit(1)
     ms_total = t0.elapsed_time(t1)
-    chunk_ms, combine_ms = B.kvc_profile_collect(args.steps)
+    chunk_ms, combine_ms = B.kvc_profile_collect(4096)
     B.kvc_profile_begin(0)
 
-    ctx_t = ctx_log[args.warmup:].to(torch.int64)
-    kv_per_step = ctx_t.sum(1).cpu().numpy().astype(np.float64)
-    # tokens the chunk kernel finalises itself (heads of one chunk) vs those left to the combine kernel
-    chunk_T = args.chunk if args.chunk else (1024 if shape.group_size >= 8 else 2048)
-    single = (ctx_t * (ctx_t <= chunk_T)).sum(1).cpu().numpy().astype(np.float64)
+    # Between two compression rounds every head grows by exactly one KV per step, so the
+    # lengths each decode saw follow from the snapshot taken at the start of the period.
+    chunk_T = B.kvc_get_decode_chunk(sess.cfg)
+    kv_per_step, single = [], []
+    keys = sorted(snaps)
+    for i in range(args.warmup, total_steps):
+        s0 = max(k for k in keys if k <= i)
+        c = snaps[s0].to(torch.int64) + (i - s0)
+        kv_per_step.append(float(c.sum()))
+        single.append(float((c * (c <= chunk_T)).sum()))   # KVs whose metric the chunk kernel updates itself
+    kv_per_step = np.array(kv_per_step)
+    single = np.array(single)
     total_bytes = float(kv_per_step.sum()) * bytes_kv
     value = total_bytes / (ms_total * 1e-3) / 1e9
     ms_step = ms_total / args.steps
 
     # dominant kernel: decode_chunk_kernel (streams K and V once; metric RMW for heads of one chunk)
     chunk_alg = kv_per_step * (2 * shape.head_dim * shape.kv_bytes + 4.0 / shape.block_size) + 8.0 * single
-    chunk_ms = np.array(chunk_ms[:args.steps], dtype=np.float64)
-    combine_ms = np.array(combine_ms[:args.steps], dtype=np.float64)
-    ach = float(chunk_alg.mean() / (chunk_ms.mean() * 1e-3) / 1e9)
+    chunk_ms = np.array(chunk_ms, dtype=np.float64)
+    combine_ms = np.array(combine_ms, dtype=np.float64)
+    chunk_alg_s = chunk_alg[::prof_every][:len(chunk_ms)]          # the steps that were timed
+    ach = float(chunk_alg_s.mean() / (chunk_ms.mean() * 1e-3) / 1e9)
     traffic = read_traffic_note("decode_chunk_kernel_llama8b_pmc.txt") if args.workload == "llama8b" else None
     roofline = {"bound": "hbm", "kernel": "decode_chunk_kernel<2,128,%d>" % shape.group_size,
                 "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
                 "traffic": traffic, "avg_kernel_ms": float(chunk_ms.mean()),
-                "algorithmic_bytes_per_launch": float(chunk_alg.mean()),
-                "decode_call_GBps": float((kv_per_step * bytes_kv).mean() /
+                "algorithmic_bytes_per_launch": float(chunk_alg_s.mean()),
+                "timed_launches": int(len(chunk_ms)),
+                "decode_call_GBps": float((kv_per_step[::prof_every][:len(chunk_ms)] * bytes_kv).mean() /
                                           ((chunk_ms + combine_ms).mean() * 1e-3) / 1e9),
                 "combine_kernel_ms": float(combine_ms.mean())}
+
+    # measured streaming-read ceiling of this GPU: the K cache read once with plain 16-byte loads
+    nbytes = sess.cache.k_cache.numel() * sess.cache.k_cache.element_size()
+    nbytes -= nbytes % 16
+    sink = torch.zeros(65536, dtype=torch.int32, device=dev)
+    best = 0.0
+    for wgs in (2048, 4096, 8192, 16384):
+        for _ in range(3):
+            a, b_ = ev(), ev()
+            a.record()
+            B.kvc_stream_read_probe(sess.cache.k_cache, nbytes, sink, wgs)
+            b_.record()
+            torch.cuda.synchronize()
+            best = max(best, nbytes / (a.elapsed_time(b_) * 1e-3) / 1e9)
+    roofline["measured_stream_read_GBps"] = best
+    roofline["frac_of_measured_stream_read"] = ach / best
+
+    if args.calibrate_copy:
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).fill_(1.0)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)          # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
 
     evict = None
     if evict_events:

@@ -194,6 +194,10 @@ int kvc_compact(const kvc_config* cfg, const kvc_state* st, const uint8_t* evict
  * host only.  KVC_ERR_ARG unless 0 or a multiple of 64 in [64, 8192].          */
 int kvc_set_decode_chunk(int tokens);
 
+/* The chunk length kvc_paged_decode uses for this config (host out-param), 0 when the shape
+ * takes the general fallback kernel, which does not split heads.  Host only.    */
+int kvc_get_decode_chunk(const kvc_config* cfg, int* tokens);
+
 /* Kernel timing for benchmarks.  kvc_profile_begin(n) makes the next n calls of
  * kvc_paged_decode record a HIP event pair on their stream around the chunk
  * kernel (the kernel that streams K and V) and another around the combine
@@ -202,7 +206,17 @@ int kvc_set_decode_chunk(int tokens);
  * recorded events and writes up to `cap` durations in milliseconds to the host
  * arrays chunk_ms and combine_ms (either may be NULL), returning the number of
  * recorded calls in *count (host).                                             */
+/* Bandwidth probe for benchmarks: reads `bytes` (a multiple of 16) of device
+ * memory at `src` once with 16-byte loads, grid-stride, and writes one 32-bit
+ * checksum per workgroup to `sink` (device, at least `workgroups` words).
+ * Gives the streaming-read rate this GPU reaches, to set beside the kernels'.   */
+int kvc_stream_read_probe(const void* src, size_t bytes, uint32_t* sink, int workgroups,
+                          void* stream);
+
 int kvc_profile_begin(int n);
+/* Pauses (0) or resumes (non-zero) the recording without releasing anything, so that a
+ * benchmark can time every k-th call only.  Host only.                            */
+int kvc_profile_enable(int on);
 int kvc_profile_collect(float* chunk_ms, float* combine_ms, int cap, int* count);
 
 #ifdef __cplusplus

@@ -25,7 +25,8 @@ EXPORTS = [
     "kvc_workspace_bytes", "kvc_validate", "kvc_status_string", "kvc_workspace_reset",
     "kvc_poll_status", "kvc_block_alloc", "kvc_block_free", "kvc_append", "kvc_paged_decode",
     "kvc_metric_reduce", "kvc_evict_select", "kvc_compact", "kvc_set_decode_chunk",
-    "kvc_profile_begin", "kvc_profile_collect",
+    "kvc_get_decode_chunk",
+    "kvc_profile_begin", "kvc_profile_enable", "kvc_profile_collect", "kvc_stream_read_probe",
 ]
 
 
@@ -74,7 +75,10 @@ def lib() -> C.CDLL:
         L.kvc_evict_select.argtypes = [cfgp, stp, P, P, P, I, I, P, P, P, P, P, I]
         L.kvc_compact.argtypes = [cfgp, stp, P, P, P, P, P, I]
         L.kvc_set_decode_chunk.argtypes = [I]
+        L.kvc_get_decode_chunk.argtypes = [cfgp, C.POINTER(C.c_int)]
         L.kvc_profile_begin.argtypes = [I]
+        L.kvc_profile_enable.argtypes = [I]
+        L.kvc_stream_read_probe.argtypes = [P, C.c_size_t, P, I, P]
         L.kvc_profile_collect.argtypes = [P, P, I, C.POINTER(C.c_int)]
         for n in EXPORTS:
             if n not in ("kvc_workspace_bytes", "kvc_status_string"):
@@ -221,3 +225,18 @@ def kvc_profile_collect(cap: int = 4096):
     _check(lib().kvc_profile_collect(a, b, cap, C.byref(n)), "kvc_profile_collect")
     k = min(n.value, cap)
     return list(a[:k]), list(b[:k])
+
+
+def kvc_stream_read_probe(src, nbytes, sink, workgroups, stream=None):
+    _check(lib().kvc_stream_read_probe(_ptr(src), int(nbytes), _ptr(sink, torch.int32), int(workgroups),
+                                       _stream(stream)), "kvc_stream_read_probe")
+
+
+def kvc_profile_enable(on: bool):
+    _check(lib().kvc_profile_enable(int(bool(on))), "kvc_profile_enable")
+
+
+def kvc_get_decode_chunk(cfg) -> int:
+    out = C.c_int(0)
+    _check(lib().kvc_get_decode_chunk(C.byref(cfg), C.byref(out)), "kvc_get_decode_chunk")
+    return out.value

@@ -51,6 +51,104 @@ __global__ void __launch_bounds__(256) count_kernel(Dims D, const int32_t* __res
   if (bits) atomicOr(&header[HW_SCRATCH0], bits);
 }
 
+// Launch 1 of an allocation: workgroups [0, gb) count requests per head instance (as
+// count_kernel), workgroups [gb, gb + ntiles) count the free blocks of one tile of the map.
+__global__ void __launch_bounds__(256) count_and_free_tiles_kernel(Dims D, const int32_t* __restrict__ table,
+                                                                   const int32_t* __restrict__ ctx,
+                                                                   const int32_t* __restrict__ n, int mode,
+                                                                   int l0, int l1, int gb,
+                                                                   const uint8_t* __restrict__ free_map,
+                                                                   int32_t* __restrict__ held,
+                                                                   int32_t* __restrict__ req,
+                                                                   int32_t* __restrict__ tile_sums,
+                                                                   int32_t* __restrict__ header) {
+  if ((int)blockIdx.x < gb) {
+    const int g = blockIdx.x * 256 + threadIdx.x;
+    if (g >= D.G) return;
+    const int C = ctx[g];
+    const int h = held_blocks(table + (size_t)g * D.maxb, C, D.b, D.maxb);
+    held[g] = h;
+    int want = 0, bits = 0;
+    if (mode == 0) {
+      want = n[g];
+      if (want < 0) { bits |= EB_ARG; want = 0; }
+      else if (h + want > D.maxb) bits |= EB_TABLE;
+    } else {
+      const int l = (g / D.Hk) % D.Lyr;
+      if (l >= l0 && l < l1 && C == h * D.b) {
+        want = 1;
+        if (h + 1 > D.maxb) bits |= EB_TABLE;
+      }
+    }
+    req[g] = want;
+    if (bits) atomicOr(&header[HW_SCRATCH0], bits);
+    return;
+  }
+  __shared__ int red[kScanThreads / 64];
+  const int tile = blockIdx.x - gb;
+  const int base = tile * kScanTile + threadIdx.x * kScanItems;
+  int s = 0;
+#pragma unroll
+  for (int k = 0; k < kScanItems; ++k) if (base + k < D.N) s += free_map[base + k] != 0;
+  s = wave_sum_i(s);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = s;
+  __syncthreads();
+  if (threadIdx.x == 0) tile_sums[tile] = red[0] + red[1] + red[2] + red[3];
+}
+
+// Launch 2, one workgroup: exclusive scan of the requests (off[g], off[G] = total), the owner
+// of every request (owner[k] = head instance that gets the k-th block), exclusive scan of the
+// free-tile counts, and the status word.
+__global__ void __launch_bounds__(1024) alloc_scan_kernel(Dims D, const int32_t* __restrict__ req,
+                                                          int32_t* __restrict__ off,
+                                                          int32_t* __restrict__ owner,
+                                                          int32_t* __restrict__ tile_sums, int ntiles,
+                                                          int32_t* __restrict__ header) {
+  __shared__ int smem[1024 / 64 + 1];
+  __shared__ int carry_s;
+  if (threadIdx.x == 0) carry_s = 0;
+  __syncthreads();
+  for (int base = 0; base < D.G; base += 1024) {
+    const int g = base + threadIdx.x;
+    const int v = (g < D.G) ? req[g] : 0;
+    int tot;
+    const int ex = block_exclusive_scan<1024>(v, smem, &tot) + carry_s;
+    if (g < D.G) {
+      off[g] = ex;
+      if (ex + v <= D.N)  // more requests than blocks exist is an error found below
+        for (int i = 0; i < v; ++i) owner[ex + i] = g;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) carry_s += tot;
+    __syncthreads();
+  }
+  const int total_req = carry_s;
+  __syncthreads();
+  if (threadIdx.x == 0) { off[D.G] = total_req; header[HW_TOTAL_REQ] = total_req; carry_s = 0; }
+  __syncthreads();
+  for (int base = 0; base < ntiles; base += 1024) {
+    const int i = base + threadIdx.x;
+    const int v = (i < ntiles) ? tile_sums[i] : 0;
+    int tot;
+    const int ex = block_exclusive_scan<1024>(v, smem, &tot) + carry_s;
+    if (i < ntiles) tile_sums[i] = ex;
+    __syncthreads();
+    if (threadIdx.x == 0) carry_s += tot;
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    const int total_free = carry_s;
+    header[HW_TOTAL_FREE] = total_free;
+    const int bits = header[HW_SCRATCH0];
+    int st = KVC_OK;
+    if (bits & EB_ARG) st = KVC_ERR_ARG;
+    else if (bits & EB_TABLE) st = KVC_ERR_TABLE_FULL;
+    else if (total_req > total_free) st = KVC_ERR_OOM;
+    if (st != KVC_OK && header[HW_STATUS] == KVC_OK) header[HW_STATUS] = st;
+    header[HW_SCRATCH0] = 0;
+  }
+}
+
 struct ReqFn {
   const int32_t* req;
   __device__ int operator()(int i) const { return req[i]; }
@@ -60,45 +158,37 @@ struct FreeFn {
   __device__ int operator()(int i) const { return free_map[i] != 0; }
 };
 
-// Third phase of the scan over the free map: rank of every free block; the
-// first `total_req` of them are written to picked[] in ascending id.
-__global__ void __launch_bounds__(kScanThreads) pick_free_kernel(const uint8_t* __restrict__ free_map,
-                                                                 int N,
-                                                                 const int32_t* __restrict__ tile_sums,
-                                                                 const int32_t* __restrict__ header,
-                                                                 int32_t* __restrict__ picked) {
+// Third phase of the scan over the free map, fused with the hand-out: the free block of
+// rank k (ascending id) goes to owner[k], the head instance g with off[g] <= k < off[g + 1],
+// as its (k - off[g])-th new block.
+__global__ void __launch_bounds__(kScanThreads) pick_scatter_kernel(Dims D, int32_t* __restrict__ table,
+                                                                    uint8_t* __restrict__ free_map,
+                                                                    const int32_t* __restrict__ tile_sums,
+                                                                    const int32_t* __restrict__ held,
+                                                                    const int32_t* __restrict__ off,
+                                                                    const int32_t* __restrict__ owner,
+                                                                    const int32_t* __restrict__ header) {
   __shared__ int smem[kScanThreads / 64 + 1];
   const int total_req = header[HW_TOTAL_REQ];
-  int base = blockIdx.x * kScanTile + threadIdx.x * kScanItems;
+  const bool ok = header[HW_STATUS] == KVC_OK;
+  const int tile0 = tile_sums[blockIdx.x];
+  if (!ok || tile0 >= total_req) return;  // uniform over the workgroup
+  const int base = blockIdx.x * kScanTile + threadIdx.x * kScanItems;
   int v[kScanItems];
   int s = 0;
 #pragma unroll
-  for (int k = 0; k < kScanItems; ++k) { v[k] = (base + k < N) ? (free_map[base + k] != 0) : 0; s += v[k]; }
-  int ex = block_exclusive_scan<kScanThreads>(s, smem, nullptr) + tile_sums[blockIdx.x];
+  for (int k = 0; k < kScanItems; ++k) { v[k] = (base + k < D.N) ? (free_map[base + k] != 0) : 0; s += v[k]; }
+  int ex = block_exclusive_scan<kScanThreads>(s, smem, nullptr) + tile0;
 #pragma unroll
   for (int k = 0; k < kScanItems; ++k) {
-    if (v[k]) { if (ex < total_req) picked[ex] = base + k; ++ex; }
-  }
-}
-
-__global__ void __launch_bounds__(256) scatter_alloc_kernel(Dims D, int32_t* __restrict__ table,
-                                                            uint8_t* __restrict__ free_map,
-                                                            const int32_t* __restrict__ held,
-                                                            const int32_t* __restrict__ req,
-                                                            const int32_t* __restrict__ off,
-                                                            const int32_t* __restrict__ picked,
-                                                            const int32_t* __restrict__ header) {
-  if (header[HW_STATUS] != KVC_OK) return;
-  int g = blockIdx.x * 256 + threadIdx.x;
-  if (g >= D.G) return;
-  int n = req[g];
-  if (n <= 0) return;
-  int32_t* row = table + (size_t)g * D.maxb + held[g];
-  const int32_t* src = picked + off[g];
-  for (int i = 0; i < n; ++i) {
-    int id = src[i];
-    row[i] = id;
-    free_map[id] = 0;
+    if (v[k]) {
+      if (ex < total_req) {
+        const int lo = owner[ex];
+        table[(size_t)lo * D.maxb + held[lo] + (ex - off[lo])] = base + k;
+        free_map[base + k] = 0;
+      }
+      ++ex;
+    }
   }
 }
 
@@ -169,26 +259,15 @@ __global__ void __launch_bounds__(64) append_write_kernel(Dims D, int l0, int l1
 static int alloc_common(const Dims& D, const kvc_state* st, const Workspace& W, const int32_t* n,
                         int mode, int l0, int l1, hipStream_t s) {
   const int gb = (D.G + 255) / 256;
-  hipLaunchKernelGGL(count_kernel, dim3(gb), dim3(256), 0, s, D, st->block_table, st->ctx_len, n, mode,
-                     l0, l1, W.held, W.off_b, W.header);
-  KVC_LAUNCH_CHECK();
-  int rc = device_exclusive_scan(ReqFn{W.off_b}, D.G, W.tile_sums, W.off_a, W.header + HW_TOTAL_REQ, s);
-  if (rc != KVC_OK) return rc;
-  // scan of the free map: tile sums, their scan (total -> HW_TOTAL_FREE), then the pick pass
   const int ntiles = (D.N + kScanTile - 1) / kScanTile;
-  hipLaunchKernelGGL(scan_tile_reduce<FreeFn>, dim3(ntiles), dim3(kScanThreads), 0, s,
-                     FreeFn{st->free_map}, D.N, W.tile_sums);
+  hipLaunchKernelGGL(count_and_free_tiles_kernel, dim3(gb + ntiles), dim3(256), 0, s, D, st->block_table,
+                     st->ctx_len, n, mode, l0, l1, gb, st->free_map, W.held, W.off_b, W.tile_sums, W.header);
   KVC_LAUNCH_CHECK();
-  hipLaunchKernelGGL(scan_tile_sums, dim3(1), dim3(1024), 0, s, W.tile_sums, ntiles,
-                     W.header + HW_TOTAL_FREE);
+  hipLaunchKernelGGL(alloc_scan_kernel, dim3(1), dim3(1024), 0, s, D, W.off_b, W.off_a, W.picked, W.tile_sums,
+                     ntiles, W.header);
   KVC_LAUNCH_CHECK();
-  hipLaunchKernelGGL(resolve_kernel, dim3(1), dim3(64), 0, s, W.header, 1);
-  KVC_LAUNCH_CHECK();
-  hipLaunchKernelGGL(pick_free_kernel, dim3(ntiles), dim3(kScanThreads), 0, s, st->free_map, D.N,
-                     W.tile_sums, W.header, W.picked);
-  KVC_LAUNCH_CHECK();
-  hipLaunchKernelGGL(scatter_alloc_kernel, dim3(gb), dim3(256), 0, s, D, st->block_table, st->free_map,
-                     W.held, W.off_b, W.off_a, W.picked, W.header);
+  hipLaunchKernelGGL(pick_scatter_kernel, dim3(ntiles), dim3(kScanThreads), 0, s, D, st->block_table,
+                     st->free_map, W.tile_sums, W.held, W.off_a, W.picked, W.header);
   KVC_LAUNCH_CHECK();
   return KVC_OK;
 }

@@ -31,6 +31,20 @@ int validate(const kvc_config* c, const kvc_state* st) {
   return KVC_OK;
 }
 
+__global__ void __launch_bounds__(256) stream_read_kernel(const uint4* __restrict__ src, size_t n16,
+                                                          uint32_t* __restrict__ sink) {
+  uint32_t acc = 0;
+  const size_t stride = (size_t)gridDim.x * 256;
+  size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  for (; i + 3 * stride < n16; i += 4 * stride) {  // four independent loads in flight per lane
+    const uint4 a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
+    acc ^= a.x ^ a.y ^ a.z ^ a.w ^ b.x ^ b.y ^ b.z ^ b.w ^ c.x ^ c.y ^ c.z ^ c.w ^ d.x ^ d.y ^ d.z ^ d.w;
+  }
+  for (; i < n16; i += stride) { const uint4 a = src[i]; acc ^= a.x ^ a.y ^ a.z ^ a.w; }
+  for (int m = 32; m >= 1; m >>= 1) acc ^= __shfl_xor(acc, m);
+  if ((threadIdx.x & 63) == 0) atomicXor(&sink[blockIdx.x], acc);
+}
+
 }  // namespace kvc
 
 using namespace kvc;
@@ -65,7 +79,16 @@ int kvc_workspace_reset(const kvc_config* cfg, void* ws, void* stream) {
   if (!ws || ((uintptr_t)ws & 255)) return KVC_ERR_ARG;
   Workspace W = carve(dims_of(cfg), ws);
   // a fill kernel rather than a memset node: safe to record into a HIP graph
-  hipLaunchKernelGGL(zero_words_kernel, dim3(1), dim3(64), 0, (hipStream_t)stream, W.header, HW_WORDS);
+  hipLaunchKernelGGL(zero_words_kernel, dim3((HW_WORDS + 63) / 64), dim3(64), 0, (hipStream_t)stream, W.header,
+                     HW_WORDS);
+  KVC_LAUNCH_CHECK();
+  return KVC_OK;
+}
+
+int kvc_stream_read_probe(const void* src, size_t bytes, uint32_t* sink, int workgroups, void* stream) {
+  if (!src || !sink || workgroups <= 0 || (bytes & 15) || ((uintptr_t)src & 15)) return KVC_ERR_ARG;
+  hipLaunchKernelGGL(stream_read_kernel, dim3(workgroups), dim3(256), 0, (hipStream_t)stream,
+                     (const uint4*)src, bytes / 16, sink);
   KVC_LAUNCH_CHECK();
   return KVC_OK;
 }

@@ -24,7 +24,14 @@ enum HeaderWord {
   HW_FREED = 4,       // blocks freed by the call in flight
   HW_SCRATCH0 = 5,
   HW_SCRATCH1 = 6,
-  HW_WORDS = 64
+  HW_SMALL_ITEMS = 7,  // decode work items in the small size classes
+  // decode work-list block: item counts per size class, per-class cursors, cursor of the
+  // per-chunk partial results.  All zero between calls (the chunk kernel clears it).
+  HW_DEC_BINS = 32,    // [16]
+  HW_DEC_CUR = 48,     // [16]
+  HW_DEC_PCUR = 64,    // [1]
+  HW_DEC_END = 65,
+  HW_WORDS = 128
 };
 
 struct Dims {
@@ -53,6 +60,7 @@ struct Workspace {
   int32_t* off_b;      // [G + 1]
   int32_t* held;       // [G]      blocks held per head instance
   int32_t* picked;     // [N]      k-th lowest free block id
+  int32_t* items;      // [max_items][8]      decode work items (see DecodeItem)
   float*   part_ml;    // [max_items][r][2]   chunk max and sum per query head
   float*   part_acc;   // [max_items][r][d]   chunk un-normalised output
   float*   stash;      // [N*b][r]            chunk-relative exp of every logit
@@ -81,6 +89,7 @@ inline Workspace carve(const Dims& D, void* base) {
   w.held = (int32_t*)take((size_t)D.G * 4);
   w.picked = (int32_t*)take((size_t)D.N * 4);
   size_t items = max_items_of(D);
+  w.items = (int32_t*)take(items * 32);
   w.part_ml = (float*)take(items * D.r * 2 * 4);
   w.part_acc = (float*)take(items * D.r * D.d * 4);
   w.stash = (float*)take((size_t)D.N * D.b * D.r * 4);

@@ -30,7 +30,16 @@ static int g_chunk_tokens = 0;  // 0 = default; set by kvc_set_decode_chunk
 // optional event pairs around the two decode kernels (kvc_profile_begin / _collect)
 struct ProfilePair { hipEvent_t a0, a1, b0, b1; };
 static ProfilePair* g_prof = nullptr;
-static int g_prof_cap = 0, g_prof_used = 0;
+static int g_prof_cap = 0, g_prof_used = 0, g_prof_on = 1;
+
+struct DecodeItem {   // 32 bytes
+  int g;        // head instance
+  int t0;       // first token of the chunk
+  int n_tok;    // tokens in the chunk
+  int nch;      // chunks of the head
+  int pbase;    // first partial-result slot of the head (heads of more than one chunk)
+  int pad[3];
+};
 
 struct DecodeArgs {
   Dims D;
@@ -43,11 +52,13 @@ struct DecodeArgs {
   float* out;
   int l0, nl, gsel;       // first layer, layer count, head instances selected
   int accumulate, T;      // metric on/off, chunk tokens
-  const int32_t* chunk_off;  // [gsel + 1]
+  int log2b;              // block size is a power of two on the tiled path
+  int cap;                // item records and partial-result slots the workspace holds
+  DecodeItem* items;
   float* part_ml;
   float* part_acc;
   float* stash;
-  const int32_t* header;
+  int32_t* header;
   float scale_log2;       // log2(e) / sqrt(d)
 };
 
@@ -58,34 +69,120 @@ __device__ __forceinline__ int sel_to_g(const Dims& D, int l0, int nl, int gi) {
   return (s * D.Lyr + l) * D.Hk + h;
 }
 
-struct ChunkFn {
-  const int32_t* ctx;
-  Dims D;
-  int l0, nl, T;
-  __device__ int operator()(int gi) const {
-    const int C = ctx[sel_to_g(D, l0, nl, gi)];
-    return (C + T - 1) / T;
-  }
-};
-
-// A head instance with no KV gets a zero output row for each of its query heads.
-__global__ void __launch_bounds__(256) zero_empty_kernel(DecodeArgs A) {
-  const int gi = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (gi >= A.gsel) return;
-  const int g = sel_to_g(A.D, A.l0, A.nl, gi);
-  if (A.ctx[g] != 0) return;
-  float* o = A.out + (size_t)g * A.D.r * A.D.d;
-  for (int i = threadIdx.x & 63; i < A.D.r * A.D.d; i += 64) o[i] = 0.0f;
+// Work items are ordered by size class, largest first, so that the short ones fill the end
+// of the launch.  Class 0 = a full chunk of T tokens; class k >= 1 = (T / 2^k, T / 2^(k-1)).
+__device__ __forceinline__ int size_class(int n, int T) {
+  if (n >= T) return 0;
+  int cls = 1, t = T >> 1;
+  while (n <= t && cls < 15) { ++cls; t >>= 1; }
+  return cls;
 }
 
-// largest i in [0, n) with off[i] <= item, given off[n] > item
-__device__ __forceinline__ int find_owner(const int32_t* __restrict__ off, int n, int item) {
-  int lo = 0, hi = n;
-  while (hi - lo > 1) {
-    const int mid = (lo + hi) >> 1;
-    if (off[mid] <= item) lo = mid; else hi = mid;
+// Items are stored largest class first.  Workgroup i does not take item i: the small classes
+// (at most T / 2^(kSmallClass-1) tokens, latency-bound work) are dealt out from the back of
+// the list in proportion, so that at any time the chip holds a mix of long streaming items
+// and short ones, and the two ends meet at the medium sizes.
+constexpr int kSmallClass = 5;
+__device__ __forceinline__ int item_of_workgroup(int i, int total, int small) {
+  const long long s0 = (long long)i * small / total;
+  const long long s1 = (long long)(i + 1) * small / total;
+  return s1 > s0 ? total - 1 - (int)s0 : i - (int)s0;
+}
+
+// Pass 1 of the work list: number of items per size class.
+__global__ void __launch_bounds__(256) decode_count_kernel(DecodeArgs A) {
+  __shared__ int bins[16];
+  if (threadIdx.x < 16) bins[threadIdx.x] = 0;
+  __syncthreads();
+  const int gi = blockIdx.x * 256 + threadIdx.x;
+  if (gi < A.gsel) {
+    const int C = A.ctx[sel_to_g(A.D, A.l0, A.nl, gi)];
+    const int nfull = C / A.T, rem = C - nfull * A.T;
+    if (nfull) atomicAdd(&bins[0], nfull);
+    if (rem) atomicAdd(&bins[size_class(rem, A.T)], 1);
   }
-  return lo;
+  __syncthreads();
+  if (threadIdx.x < 16 && bins[threadIdx.x]) atomicAdd(&A.header[HW_DEC_BINS + threadIdx.x], bins[threadIdx.x]);
+}
+
+// Pass 2: every head instance claims its places and writes its items; a head that holds no
+// KV gets its zero output rows here.  Places are claimed per workgroup (one global atomic
+// per class) and handed out inside it through LDS, so the global counters see few updates.
+__global__ void __launch_bounds__(256) decode_items_kernel(DecodeArgs A) {
+  __shared__ int base[16], want[17], got[17];
+  const int tid = threadIdx.x;
+  if (tid < 17) want[tid] = 0;
+  if (tid == 0) {
+    int run = 0;
+    int small = 0;
+    for (int k = 0; k < 16; ++k) {
+      const int c = A.header[HW_DEC_BINS + k];
+      base[k] = run;
+      run += c;
+      if (k >= kSmallClass) small += c;
+    }
+    if (blockIdx.x == 0) { A.header[HW_TOTAL_ITEMS] = run; A.header[HW_SMALL_ITEMS] = small; }
+  }
+  __syncthreads();
+  const int gi = blockIdx.x * 256 + tid;
+  const int T = A.T;
+  int g = 0, C = 0, nfull = 0, rem = 0, nch = 0, cls = 0;
+  int my_full = 0, my_rem = 0, my_p = 0;  // offsets inside this workgroup's claims
+  if (gi < A.gsel) {
+    g = sel_to_g(A.D, A.l0, A.nl, gi);
+    C = A.ctx[g];
+    nfull = C / T;
+    rem = C - nfull * T;
+    nch = nfull + (rem ? 1 : 0);
+    cls = rem ? size_class(rem, T) : 0;
+    if (nfull) my_full = atomicAdd(&want[0], nfull);
+    if (rem) my_rem = atomicAdd(&want[cls], 1);       // class 0 never holds a remainder
+    if (nch > 1) my_p = atomicAdd(&want[16], nch);
+  }
+  __syncthreads();
+  if (tid < 17 && want[tid])
+    got[tid] = atomicAdd(&A.header[tid < 16 ? HW_DEC_CUR + tid : HW_DEC_PCUR], want[tid]);
+  __syncthreads();
+  if (gi >= A.gsel) return;
+  if (C == 0) {
+    float* o = A.out + (size_t)g * A.D.r * A.D.d;
+    for (int i = 0; i < A.D.r * A.D.d; ++i) o[i] = 0.0f;
+    return;
+  }
+  const int pbase = nch > 1 ? got[16] + my_p : 0;
+  // the counters start from zero, so these bounds hold by construction; a workspace that was
+  // never reset is the one way to break them, and then nothing is written
+  if (pbase < 0 || pbase + nch > A.cap) return;
+  if (nfull) {
+    const int at = base[0] + got[0] + my_full;
+    if (at < 0 || at + nfull > A.cap) return;
+    for (int c = 0; c < nfull; ++c) {
+      DecodeItem it = {g, c * T, T, nch, pbase, {0, 0, 0}};
+      A.items[at + c] = it;
+    }
+  }
+  if (rem) {
+    const int at = base[cls] + got[cls] + my_rem;
+    if (at < 0 || at >= A.cap) return;
+    DecodeItem it = {g, nfull * T, rem, nch, pbase, {0, 0, 0}};
+    A.items[at] = it;
+  }
+}
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, true));
+}
+// Value held by lane (l ^ MASK).  Masks below 16 stay inside a row of 16 lanes and use
+// data-parallel primitives: quad permutes for 1 and 2, a quad reverse followed by a half-row
+// mirror for 4 (i ^ 3 ^ 7 = i ^ 4), a rotation by 8 for 8.
+template <int MASK>
+__device__ __forceinline__ float lane_xor(float v) {
+  if constexpr (MASK == 1) return dpp_move<0xB1>(v);
+  else if constexpr (MASK == 2) return dpp_move<0x4E>(v);
+  else if constexpr (MASK == 4) return dpp_move<0x141>(dpp_move<0x1B>(v));
+  else if constexpr (MASK == 8) return dpp_move<0x128>(v);
+  else return __shfl_xor(v, MASK);
 }
 
 template <int N, int MASK>
@@ -101,11 +198,11 @@ struct Butterfly {
         for (int i = 0; i < H; ++i) {
           const float keep = up ? v[H + i] : v[i];
           const float send = up ? v[i] : v[H + i];
-          v[i] = keep + __shfl_xor(send, MASK);
+          v[i] = keep + lane_xor<MASK>(send);
         }
         Butterfly<H, MASK / 2>::run(v, lane);
       } else {
-        v[0] += __shfl_xor(v[0], MASK);
+        v[0] += lane_xor<MASK>(v[0]);
         Butterfly<1, MASK / 2>::run(v, lane);
       }
     }
@@ -144,15 +241,66 @@ template <> struct Row<4> {  // f32: 4 elements in 16 bytes
   }
 };
 
+// A head of more than one chunk leaves, for every KV and query head, e = exp2(logit - chunk
+// max) in [0, 1] for the combine kernel.  It is kept as 16-bit fixed point: the error of e, and
+// so of the probability it turns into (p = e * weight, weight <= 1), is at most 2^-17, which
+// moves a metric increment (sum over r heads of p^2 or p) by at most r * 2^-16.
+__device__ __forceinline__ uint32_t q16(float e) { return (uint32_t)(e * 65535.0f + 0.5f); }
+__device__ __forceinline__ float unq16(uint32_t q) { return (float)q * (1.0f / 65535.0f); }
+
+template <int R>
+__device__ __forceinline__ void stash_store(float* stash, size_t slot, const float* e) {
+  uint16_t* base = (uint16_t*)stash + slot * R;
+  if constexpr (R == 1) {
+    *base = (uint16_t)q16(e[0]);
+  } else {
+    uint32_t wds[R / 2];
+#pragma unroll
+    for (int i = 0; i < R / 2; ++i) wds[i] = q16(e[2 * i]) | (q16(e[2 * i + 1]) << 16);
+    if constexpr (R == 2) *(uint32_t*)base = wds[0];
+    else if constexpr (R == 4) *(uint2*)base = make_uint2(wds[0], wds[1]);
+    else *(uint4*)base = make_uint4(wds[0], wds[1], wds[2], wds[3]);
+  }
+}
+template <int R>
+__device__ __forceinline__ void stash_load(const float* stash, size_t slot, float* e) {
+  const uint16_t* base = (const uint16_t*)stash + slot * R;
+  if constexpr (R == 1) {
+    e[0] = unq16(*base);
+  } else {
+    uint32_t wds[R / 2];
+    if constexpr (R == 2) wds[0] = *(const uint32_t*)base;
+    else if constexpr (R == 4) { const uint2 t = *(const uint2*)base; wds[0] = t.x; wds[1] = t.y; }
+    else { const uint4 t = *(const uint4*)base; wds[0] = t.x; wds[1] = t.y; wds[2] = t.z; wds[3] = t.w; }
+#pragma unroll
+    for (int i = 0; i < R / 2; ++i) { e[2 * i] = unq16(wds[i] & 0xffffu); e[2 * i + 1] = unq16(wds[i] >> 16); }
+  }
+}
+
 constexpr int kDecodeThreads = 256;
 constexpr int kDecodeWaves = kDecodeThreads / 64;
 
 __host__ __device__ inline size_t decode_lds_bytes(int T, int R, int HD, int b) {
-  return (size_t)T * R * 4 + (size_t)kDecodeWaves * R * HD * 4 + 2 * kDecodeWaves * R * 4 +
-         ((size_t)T / b + 1) * 4;
+  return (size_t)T * R * 2                       // exp of every logit against its group's running max, 16-bit
+         + (size_t)(T / 16) * R * 4              // that running max, per 16-token group and head
+         + (size_t)kDecodeWaves * R * HD * 4     // per-wavefront un-normalised output
+         + (size_t)kDecodeWaves * 16 * R * 4     // per-wavefront exp of the current group, f32
+         + 2 * kDecodeWaves * R * 4              // per-wavefront max and sum
+         + ((size_t)T / b + 1) * 4;              // block ids of the chunk
 }
 
-template <int ESZ, int HD, int R>
+// One workgroup = one chunk of up to T tokens of one head instance; one pass.
+//
+// Each wavefront walks its 16-token groups with the next group's K and V rows
+// already in flight.  Per group: r dot products per token (butterfly over the
+// lanes of a token), running max per query head (online softmax), exp of the
+// group against the running max, rescale of the output accumulator when a max
+// moved, then acc += p * v.  What the metric needs later, the exp of every
+// logit, stays in LDS as 16-bit fixed point next to the running max it was
+// taken against (one f32 per group and head): once the wavefronts have been
+// merged, the normalised probability of every KV follows without touching K
+// again.  The quantisation moves a probability by at most 2^-17.
+template <int ESZ, int HD, int R, bool B16>
 __global__ void __launch_bounds__(kDecodeThreads) decode_chunk_kernel(DecodeArgs A) {
   constexpr int EPL = Row<ESZ>::EPL;
   constexpr int LPT = HD / EPL;        // lanes per token
@@ -161,32 +309,33 @@ __global__ void __launch_bounds__(kDecodeThreads) decode_chunk_kernel(DecodeArgs
   constexpr int NV = R * U;            // partial logits per lane before the butterfly
   constexpr int PER = NV >= LPT ? NV / LPT : 1;  // logits per lane after it
   constexpr size_t ROWB = (size_t)HD * ESZ;
-  static_assert(LPT >= 2 && LPT <= 64 && (16 % TPI) == 0, "row geometry");
-
-  const int item = blockIdx.x;
-  if (item >= A.header[HW_TOTAL_ITEMS]) return;
-  const int gi = find_owner(A.chunk_off, A.gsel, item);
-  const int first = A.chunk_off[gi];
-  const int c = item - first;
-  const int nch = A.chunk_off[gi + 1] - first;
-  const int g = sel_to_g(A.D, A.l0, A.nl, gi);
-  const int b = A.D.b, T = A.T;
-  const int C = A.ctx[g];
-  const int t0 = c * T;
-  const int n_tok = min(T, C - t0);
-
-  extern __shared__ __align__(16) char smem_raw[];
-  float* s_log = (float*)smem_raw;                     // [T][R]
-  float* s_acc = s_log + (size_t)T * R;                // [waves][R][HD]
-  float* s_red = s_acc + kDecodeWaves * R * HD;        // [2][waves][R]
-  int* s_tab = (int*)(s_red + 2 * kDecodeWaves * R);   // [T / b + 1]
+  static_assert(LPT >= 4 && LPT <= 32 && (16 % TPI) == 0, "row geometry");
 
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int total_items = A.header[HW_TOTAL_ITEMS];
+  if (blockIdx.x == 0 && tid < HW_DEC_END - HW_DEC_BINS) A.header[HW_DEC_BINS + tid] = 0;  // work-list block back to zero
+  if ((int)blockIdx.x >= total_items || total_items > A.cap) return;
+  const int item = item_of_workgroup(blockIdx.x, total_items, A.header[HW_SMALL_ITEMS]);
+  const DecodeItem it = A.items[item];
+  const int g = it.g, t0 = it.t0, n_tok = it.n_tok, nch = it.nch;
+  if ((unsigned)g >= (unsigned)A.D.G || n_tok <= 0 || n_tok > A.T || t0 < 0 || nch <= 0 ||
+      (nch > 1 && (it.pbase < 0 || it.pbase + nch > A.cap)))
+    return;  // not a record this call wrote
+  const int b = A.D.b, lb = A.log2b, T = A.T;
+
+  extern __shared__ __align__(16) char smem_raw[];
+  float* s_acc = (float*)smem_raw;                     // [waves][R][HD]
+  float* s_e = s_acc + kDecodeWaves * R * HD;          // [waves][16][R]
+  float* s_red = s_e + kDecodeWaves * 16 * R;          // [2][waves][R]
+  float* s_gm = s_red + 2 * kDecodeWaves * R;          // [T / 16][R]
+  uint16_t* s_q = (uint16_t*)(s_gm + (T / 16) * R);    // [T][R]
+  int* s_tab = (int*)(s_q + (size_t)T * R);            // [T / b + 1]
+
   const int sub = lane / LPT, seg = lane % LPT;
 
   {
-    const int nblk = (n_tok + b - 1) / b;
-    const int32_t* row = A.table + (size_t)g * A.D.maxb + t0 / b;
+    const int nblk = (n_tok + b - 1) >> lb;
+    const int32_t* row = A.table + (size_t)g * A.D.maxb + (t0 >> lb);
     for (int i = tid; i < nblk; i += kDecodeThreads) s_tab[i] = row[i];
   }
   uint4 qv[R];
@@ -195,110 +344,143 @@ __global__ void __launch_bounds__(kDecodeThreads) decode_chunk_kernel(DecodeArgs
     qv[hh] = *(const uint4*)(A.q + ((size_t)g * R + hh) * ROWB + (size_t)seg * 16);
   __syncthreads();
 
-  // ---- pass over K: logits (scaled for exp2) into LDS ----
-  for (int base = w * 16; base < n_tok; base += 16 * kDecodeWaves) {
-    uint4 kv[U];
+  // One 16-token group = U wavefront loads of 1 KiB each.  With b a multiple of 16 a group
+  // lies in one block, so one table lookup serves it and the slots past the end of the head
+  // (still inside the block) are read and masked later.  Otherwise every load looks its
+  // block up and tokens past the end re-read the last token.
+  const int last = n_tok - 1;
+  auto load_group = [&](const char* __restrict__ basep, int grp, uint4 (&buf)[U]) {
+    if constexpr (B16) {
+      const int tk = grp * 16;
+      const size_t slot = ((size_t)s_tab[tk >> lb] << lb) + (tk & (b - 1));
+      const char* p = basep + slot * ROWB + (size_t)lane * 16;
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int tok = base + u * TPI + sub;
-      if (base + u * TPI < n_tok) {
-        const size_t slot = (size_t)s_tab[tok / b] * b + (tok % b);
-        kv[u] = *(const uint4*)(A.kc + slot * ROWB + (size_t)seg * 16);
-      } else {
-        kv[u] = make_uint4(0, 0, 0, 0);
+      for (int u = 0; u < U; ++u) buf[u] = *(const uint4*)(p + (size_t)u * 1024);
+    } else {
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int tok = min(grp * 16 + u * TPI + sub, last);
+        const size_t slot = ((size_t)s_tab[tok >> lb] << lb) + (tok & (b - 1));
+        buf[u] = *(const uint4*)(basep + slot * ROWB + (size_t)seg * 16);
       }
     }
-    float part[NV];
-#pragma unroll
-    for (int u = 0; u < U; ++u)
-#pragma unroll
-      for (int hh = 0; hh < R; ++hh) part[u * R + hh] = Row<ESZ>::dot(kv[u], qv[hh]);
-    Butterfly<NV, LPT / 2>::run(part, lane);
-    const int idx0 = (seg * NV) / LPT;
-#pragma unroll
-    for (int i = 0; i < PER; ++i) {
-      const int idx = idx0 + i;
-      const int u = idx / R, hh = idx % R;
-      const int tok = base + u * TPI + sub;
-      s_log[tok * R + hh] = tok < n_tok ? part[i] * A.scale_log2 : -INFINITY;
-    }
-  }
-  __syncthreads();
+  };
+  const int ngroups = (n_tok + 15) >> 4;
 
-  // ---- chunk max and sum per query head; logits become exp2(s - max) ----
-  float mx[R], sm[R];
-#pragma unroll
-  for (int hh = 0; hh < R; ++hh) mx[hh] = -INFINITY;
-  for (int tok = tid; tok < n_tok; tok += kDecodeThreads)
-#pragma unroll
-    for (int hh = 0; hh < R; ++hh) mx[hh] = fmaxf(mx[hh], s_log[tok * R + hh]);
-#pragma unroll
-  for (int hh = 0; hh < R; ++hh) {
-    mx[hh] = wave_max_f(mx[hh]);
-    if (lane == 0) s_red[w * R + hh] = mx[hh];
-  }
-  __syncthreads();
-#pragma unroll
-  for (int hh = 0; hh < R; ++hh) {
-    float m = s_red[hh];
-#pragma unroll
-    for (int ww = 1; ww < kDecodeWaves; ++ww) m = fmaxf(m, s_red[ww * R + hh]);
-    mx[hh] = m;
-    sm[hh] = 0.0f;
-  }
-  for (int tok = tid; tok < n_tok; tok += kDecodeThreads)
-#pragma unroll
-    for (int hh = 0; hh < R; ++hh) {
-      const float e = __builtin_amdgcn_exp2f(s_log[tok * R + hh] - mx[hh]);
-      s_log[tok * R + hh] = e;
-      sm[hh] += e;
-    }
-#pragma unroll
-  for (int hh = 0; hh < R; ++hh) {
-    sm[hh] = wave_sum_f(sm[hh]);
-    if (lane == 0) s_red[(kDecodeWaves + w) * R + hh] = sm[hh];
-  }
-  __syncthreads();
-#pragma unroll
-  for (int hh = 0; hh < R; ++hh) {
-    float l = 0.0f;
-#pragma unroll
-    for (int ww = 0; ww < kDecodeWaves; ++ww) l += s_red[(kDecodeWaves + ww) * R + hh];
-    sm[hh] = l;
-  }
-
-  // ---- pass over V ----
   float acc[R][EPL];
 #pragma unroll
   for (int hh = 0; hh < R; ++hh)
 #pragma unroll
     for (int k = 0; k < EPL; ++k) acc[hh][k] = 0.0f;
-  for (int base = w * 16; base < n_tok; base += 16 * kDecodeWaves) {
-    uint4 vv[U];
+  float m_run[R];            // running max per query head, the same in every lane
+  float m_own[PER], l_own[PER];  // this lane's head(s): running max and partial sum
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int tok = base + u * TPI + sub;
-      if (tok < n_tok) {  // an empty slot may hold anything, NaN included: never touch it
-        const size_t slot = (size_t)s_tab[tok / b] * b + (tok % b);
-        vv[u] = *(const uint4*)(A.vc + slot * ROWB + (size_t)seg * 16);
-      } else {
-        vv[u] = make_uint4(0, 0, 0, 0);
+  for (int hh = 0; hh < R; ++hh) m_run[hh] = -INFINITY;
+#pragma unroll
+  for (int i = 0; i < PER; ++i) { m_own[i] = -INFINITY; l_own[i] = 0.0f; }
+  const int idx0 = (seg * NV) / LPT;
+  float* my_e = s_e + w * 16 * R;
+  const bool gm_writer = (lane & 60) == 0;  // lanes 0..3 hold every head between them
+
+  {
+    uint4 kcur[U], vcur[U], knxt[U], vnxt[U];
+    int grp = w;
+    if (grp < ngroups) { load_group(A.kc, grp, kcur); load_group(A.vc, grp, vcur); }
+    for (; grp < ngroups; grp += kDecodeWaves) {
+      const bool more = grp + kDecodeWaves < ngroups;
+      if (more) { load_group(A.kc, grp + kDecodeWaves, knxt); load_group(A.vc, grp + kDecodeWaves, vnxt); }
+      // logits of the group
+      float part[NV];
+#pragma unroll
+      for (int u = 0; u < U; ++u)
+#pragma unroll
+        for (int hh = 0; hh < R; ++hh) part[u * R + hh] = Row<ESZ>::dot(kcur[u], qv[hh]);
+      Butterfly<NV, LPT / 2>::run(part, lane);
+      float gm[PER];
+#pragma unroll
+      for (int i = 0; i < PER; ++i) {
+        const int u = (idx0 + i) / R;
+        const int tok = grp * 16 + u * TPI + sub;
+        part[i] = tok < n_tok ? part[i] * A.scale_log2 : -INFINITY;
+        // max over the group's tokens: the lanes that hold one head differ in lane bits 2..5
+        float m = part[i];
+        m = fmaxf(m, lane_xor<4>(m));
+        m = fmaxf(m, lane_xor<8>(m));
+        m = fmaxf(m, __shfl_xor(m, 16));
+        m = fmaxf(m, __shfl_xor(m, 32));
+        gm[i] = fmaxf(m, m_own[i]);
       }
-    }
+      // exp of the group against the new running max; partial sums rescaled
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int tok = base + u * TPI + sub;
-      float vf[EPL];
-      Row<ESZ>::widen(vv[u], vf);
+      for (int i = 0; i < PER; ++i) {
+        const int idx = idx0 + i;
+        const int u = idx / R, hh = idx % R;
+        const int tl = u * TPI + sub;
+        const float e = __builtin_amdgcn_exp2f(part[i] - gm[i]);
+        l_own[i] = l_own[i] * __builtin_amdgcn_exp2f(m_own[i] - gm[i]) + e;
+        m_own[i] = gm[i];
+        my_e[tl * R + hh] = e;
+        s_q[(grp * 16 + tl) * R + hh] = (uint16_t)q16(e);
+        if (gm_writer) s_gm[grp * R + hh] = gm[i];
+      }
+      // new running max of every head, read from the lane that owns it; rescale on change
+      bool moved = false;
+      float m_new[R];
 #pragma unroll
       for (int hh = 0; hh < R; ++hh) {
-        const float p = tok < n_tok ? s_log[tok * R + hh] : 0.0f;
+        m_new[hh] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, gm[hh % PER]), (hh * 4) / R));
+        moved |= m_new[hh] > m_run[hh];
+      }
+      if (moved) {
 #pragma unroll
-        for (int k = 0; k < EPL; ++k) acc[hh][k] = fmaf(p, vf[k], acc[hh][k]);
+        for (int hh = 0; hh < R; ++hh) {
+          const float alpha = __builtin_amdgcn_exp2f(m_run[hh] - m_new[hh]);
+#pragma unroll
+          for (int k = 0; k < EPL; ++k) acc[hh][k] *= alpha;
+          m_run[hh] = m_new[hh];
+        }
+      }
+      // acc += p * v
+      const bool tail = B16 && grp * 16 + 16 > n_tok;
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int tl = u * TPI + sub;
+        if (tail && grp * 16 + tl >= n_tok) vcur[u] = make_uint4(0, 0, 0, 0);  // empty slot: may hold anything
+        float vf[EPL];
+        Row<ESZ>::widen(vcur[u], vf);
+#pragma unroll
+        for (int hh = 0; hh < R; ++hh) {
+          const float p = my_e[tl * R + hh];
+#pragma unroll
+          for (int k = 0; k < EPL; ++k) acc[hh][k] = fmaf(p, vf[k], acc[hh][k]);
+        }
+      }
+      if (more) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) { kcur[u] = knxt[u]; vcur[u] = vnxt[u]; }
       }
     }
   }
-  // token groups of one wavefront, then the wavefronts
+  // ---- merge: token groups of one wavefront, then the wavefronts ----
+#pragma unroll
+  for (int i = 0; i < PER; ++i) {
+    float l = l_own[i];
+    l += lane_xor<4>(l);
+    l += lane_xor<8>(l);
+    l += __shfl_xor(l, 16);
+    l += __shfl_xor(l, 32);
+    l_own[i] = l;
+  }
+  if (lane < 4) {
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+      const int hh = (idx0 + i) % R;
+      if ((hh * 4) / R == lane) {
+        s_red[w * R + hh] = m_own[i];
+        s_red[(kDecodeWaves + w) * R + hh] = l_own[i];
+      }
+    }
+  }
 #pragma unroll
   for (int m = LPT; m < 64; m <<= 1)
 #pragma unroll
@@ -313,51 +495,67 @@ __global__ void __launch_bounds__(kDecodeThreads) decode_chunk_kernel(DecodeArgs
   }
   __syncthreads();
 
+  // chunk max and sum per head from the wavefronts' pairs
   const bool single = nch == 1;
-  for (int i = tid; i < R * HD; i += kDecodeThreads) {
-    float s = 0.0f;
+  float cm[R], cl[R], wsc[kDecodeWaves][R];
 #pragma unroll
-    for (int ww = 0; ww < kDecodeWaves; ++ww) s += s_acc[ww * R * HD + i];
-    if (single) {
-      const int hh = i / HD;
-      float l = 0.0f;
+  for (int hh = 0; hh < R; ++hh) {
+    float m = s_red[hh];
 #pragma unroll
-      for (int ww = 0; ww < kDecodeWaves; ++ww) l += s_red[(kDecodeWaves + ww) * R + hh];
-      A.out[(size_t)g * R * HD + i] = s / l;
-    } else {
-      A.part_acc[(size_t)item * R * HD + i] = s;
-    }
-  }
-  if (!single && tid < R) {
-    float m = s_red[tid];
-#pragma unroll
-    for (int ww = 1; ww < kDecodeWaves; ++ww) m = fmaxf(m, s_red[ww * R + tid]);
+    for (int ww = 1; ww < kDecodeWaves; ++ww) m = fmaxf(m, s_red[ww * R + hh]);
     float l = 0.0f;
 #pragma unroll
-    for (int ww = 0; ww < kDecodeWaves; ++ww) l += s_red[(kDecodeWaves + ww) * R + tid];
-    A.part_ml[((size_t)item * R + tid) * 2 + 0] = m;
-    A.part_ml[((size_t)item * R + tid) * 2 + 1] = l;
+    for (int ww = 0; ww < kDecodeWaves; ++ww) {
+      wsc[ww][hh] = __builtin_amdgcn_exp2f(s_red[ww * R + hh] - m);
+      l += s_red[(kDecodeWaves + ww) * R + hh] * wsc[ww][hh];
+    }
+    cm[hh] = m;
+    cl[hh] = l;
+  }
+  const size_t pslot = (size_t)it.pbase + (size_t)(t0 / T);  // partial-result slot of this chunk
+#pragma unroll
+  for (int hh = 0; hh < R; ++hh) {
+    for (int k = tid; k < HD; k += kDecodeThreads) {
+      float s = 0.0f;
+#pragma unroll
+      for (int ww = 0; ww < kDecodeWaves; ++ww) s += s_acc[(ww * R + hh) * HD + k] * wsc[ww][hh];
+      if (single) A.out[((size_t)g * R + hh) * HD + k] = s / cl[hh];
+      else A.part_acc[(pslot * R + hh) * HD + k] = s;
+    }
+  }
+  if (!single && tid == 0) {
+#pragma unroll
+    for (int hh = 0; hh < R; ++hh) {
+      A.part_ml[(pslot * R + hh) * 2 + 0] = cm[hh];
+      A.part_ml[(pslot * R + hh) * 2 + 1] = cl[hh];
+    }
   }
   if (!A.accumulate) return;
-  if (single) {
-    float inv[R];
+  // The stored 16-bit value of a KV times 2^(its group's running max - chunk max) is the exp of
+  // its logit against the chunk max; for a head of one chunk, divided by the sum, its
+  // probability.  That factor is the same for the 16 tokens of a group: formed once, in place.
+  for (int i = tid; i < ngroups * R; i += kDecodeThreads) {
+    const int hh = i % R;
+    float f = 0.0f;
 #pragma unroll
-    for (int hh = 0; hh < R; ++hh) inv[hh] = 1.0f / sm[hh];
-    for (int tok = tid; tok < n_tok; tok += kDecodeThreads) {
-      const size_t slot = (size_t)s_tab[tok / b] * b + (tok % b);
+    for (int h2 = 0; h2 < R; ++h2)
+      if (h2 == hh) f = __builtin_amdgcn_exp2f(s_gm[i] - cm[h2]) * (single ? 1.0f / cl[h2] : 1.0f) * (1.0f / 65535.0f);
+    s_gm[i] = f;
+  }
+  __syncthreads();
+  for (int tok = tid; tok < n_tok; tok += kDecodeThreads) {
+    const size_t slot = ((size_t)s_tab[tok >> lb] << lb) + (tok & (b - 1));
+    float e[R];
+#pragma unroll
+    for (int hh = 0; hh < R; ++hh) e[hh] = (float)s_q[tok * R + hh] * s_gm[(tok >> 4) * R + hh];
+    if (single) {
       float inc = 0.0f;
 #pragma unroll
-      for (int hh = 0; hh < R; ++hh) {
-        const float p = s_log[tok * R + hh] * inv[hh];
-        inc += A.D.mode == KVC_L2 ? p * p : p;
-      }
-      A.metric[slot] += inc;
-    }
-  } else {
-    for (int i = tid; i < n_tok * R; i += kDecodeThreads) {
-      const int tok = i / R, hh = i % R;
-      const size_t slot = (size_t)s_tab[tok / b] * b + (tok % b);
-      A.stash[slot * R + hh] = s_log[i];
+      for (int hh = 0; hh < R; ++hh) inc += A.D.mode == KVC_L2 ? e[hh] * e[hh] : e[hh];
+      // one writer per slot in a launch, so the hardware add gives the same bits as load-add-store
+      unsafeAtomicAdd(&A.metric[slot], inc);
+    } else {
+      stash_store<R>(A.stash, slot, e);
     }
   }
 }
@@ -369,51 +567,72 @@ __global__ void __launch_bounds__(kDecodeThreads) decode_chunk_kernel(DecodeArgs
 template <int R>
 __global__ void __launch_bounds__(256) decode_combine_kernel(DecodeArgs A) {
   const int item = blockIdx.x;
-  if (item >= A.header[HW_TOTAL_ITEMS]) return;
-  const int gi = find_owner(A.chunk_off, A.gsel, item);
-  const int first = A.chunk_off[gi];
-  const int nch = A.chunk_off[gi + 1] - first;
-  if (nch == 1) return;
-  const int c = item - first;
-  const int g = sel_to_g(A.D, A.l0, A.nl, gi);
-  const int b = A.D.b, T = A.T, HD = A.D.d;
-  const int C = A.ctx[g];
-  const int t0 = c * T;
-  const int n_tok = min(T, C - t0);
-  __shared__ float s_m[R], s_il[R], s_w[R];
+  if (item >= A.header[HW_TOTAL_ITEMS] || item >= A.cap) return;
+  const DecodeItem it = A.items[item];
+  const int nch = it.nch;
+  if (nch <= 1) return;
+  if ((unsigned)it.g >= (unsigned)A.D.G || it.n_tok <= 0 || it.n_tok > A.T || it.t0 < 0 || it.pbase < 0 ||
+      it.pbase + nch > A.cap)
+    return;  // not a record this call wrote
+  const int g = it.g, t0 = it.t0, n_tok = it.n_tok;
+  const int c = t0 / A.T;
+  const int first = it.pbase;                // partial-result slots first .. first + nch - 1
+  const int b = A.D.b, lb = A.log2b, HD = A.D.d;
+  constexpr int kMaxCh = 64;                 // chunk weights kept in LDS; longer heads recompute
+  __shared__ float s_m[R], s_il[R], s_w[R], s_wc[kMaxCh][R];
   const int tid = threadIdx.x;
+  // one thread per (chunk, head) pair fetches its max and sum; the head's max and sum follow
+  __shared__ float s_pm[kMaxCh][R], s_pl[kMaxCh][R];
+  const int ncl = min(nch, kMaxCh);
+  for (int i = tid; i < ncl * R; i += 256) {
+    const float2 ml = *(const float2*)(A.part_ml + ((size_t)first * R + i) * 2);
+    s_pm[i / R][i % R] = ml.x;
+    s_pl[i / R][i % R] = ml.y;
+  }
+  __syncthreads();
   if (tid < R) {
     float m = -INFINITY;
-    for (int cc = 0; cc < nch; ++cc) m = fmaxf(m, A.part_ml[((size_t)(first + cc) * R + tid) * 2]);
+    for (int cc = 0; cc < nch; ++cc)
+      m = fmaxf(m, cc < kMaxCh ? s_pm[cc][tid] : A.part_ml[((size_t)(first + cc) * R + tid) * 2]);
     float l = 0.0f;
     for (int cc = 0; cc < nch; ++cc) {
-      const float* ml = A.part_ml + ((size_t)(first + cc) * R + tid) * 2;
-      l += ml[1] * __builtin_amdgcn_exp2f(ml[0] - m);
+      const float pm = cc < kMaxCh ? s_pm[cc][tid] : A.part_ml[((size_t)(first + cc) * R + tid) * 2];
+      const float pl = cc < kMaxCh ? s_pl[cc][tid] : A.part_ml[((size_t)(first + cc) * R + tid) * 2 + 1];
+      const float wgt = __builtin_amdgcn_exp2f(pm - m);
+      if (cc < kMaxCh) s_wc[cc][tid] = wgt;
+      l += pl * wgt;
     }
     s_m[tid] = m;
     s_il[tid] = 1.0f / l;
-    s_w[tid] = __builtin_amdgcn_exp2f(A.part_ml[((size_t)item * R + tid) * 2] - m) / l;
+    s_w[tid] = __builtin_amdgcn_exp2f((c < kMaxCh ? s_pm[c][tid] : A.part_ml[((size_t)(first + c) * R + tid) * 2]) - m) / l;
   }
   __syncthreads();
   if (A.accumulate) {
     const int32_t* row = A.table + (size_t)g * A.D.maxb;
+    float wv[R];
+#pragma unroll
+    for (int hh = 0; hh < R; ++hh) wv[hh] = s_w[hh];
     for (int tok = tid; tok < n_tok; tok += 256) {
       const int j = t0 + tok;
-      const size_t slot = (size_t)row[j / b] * b + (j % b);
+      const size_t slot = ((size_t)row[j >> lb] << lb) + (j & (b - 1));
+      float e[R];
+      stash_load<R>(A.stash, slot, e);
       float inc = 0.0f;
 #pragma unroll
       for (int hh = 0; hh < R; ++hh) {
-        const float p = A.stash[slot * R + hh] * s_w[hh];
+        const float p = e[hh] * wv[hh];
         inc += A.D.mode == KVC_L2 ? p * p : p;
       }
-      A.metric[slot] += inc;
+      unsafeAtomicAdd(&A.metric[slot], inc);
     }
   }
   if (c == 0) {
     for (int i = tid; i < R * HD; i += 256) {
       const int hh = i / HD;
       float s = 0.0f;
-      for (int cc = 0; cc < nch; ++cc) {
+#pragma unroll 4
+      for (int cc = 0; cc < ncl; ++cc) s += A.part_acc[(size_t)(first + cc) * R * HD + i] * s_wc[cc][hh];
+      for (int cc = kMaxCh; cc < nch; ++cc) {
         const float wgt = __builtin_amdgcn_exp2f(A.part_ml[((size_t)(first + cc) * R + hh) * 2] - s_m[hh]);
         s += A.part_acc[(size_t)(first + cc) * R * HD + i] * wgt;
       }
@@ -430,7 +649,11 @@ __global__ void __launch_bounds__(256) decode_generic_kernel(DecodeArgs A) {
   const int g = sel_to_g(A.D, A.l0, A.nl, gi);
   const int R = A.D.r, HD = A.D.d, b = A.D.b;
   const int C = A.ctx[g];
-  if (C == 0) return;  // zero_empty_kernel wrote the zeros
+  if (C == 0) {  // a head with no KV: zero output rows
+    float* o = A.out + (size_t)g * R * HD;
+    for (int i = threadIdx.x; i < R * HD; i += 256) o[i] = 0.0f;
+    return;
+  }
   extern __shared__ __align__(16) char smem_raw[];
   float* s_q = (float*)smem_raw;      // [R][HD]
   float* s_red = s_q + R * HD;        // [4][16]
@@ -504,9 +727,17 @@ __global__ void __launch_bounds__(256) decode_generic_kernel(DecodeArgs A) {
 
 template <int ESZ, int HD, int R>
 static int launch_tiled(const DecodeArgs& A, int grid, size_t lds, hipStream_t s) {
-  auto kern = decode_chunk_kernel<ESZ, HD, R>;
-  ProfilePair* pp = (g_prof && g_prof_used < g_prof_cap) ? &g_prof[g_prof_used++] : nullptr;
+  auto kern = (A.D.b % 16 == 0) ? decode_chunk_kernel<ESZ, HD, R, true> : decode_chunk_kernel<ESZ, HD, R, false>;
+  ProfilePair* pp = (g_prof && g_prof_on && g_prof_used < g_prof_cap) ? &g_prof[g_prof_used++] : nullptr;
   if (pp) KVC_HIP(hipEventRecord(pp->a0, s));
+  if (lds > 64 * 1024) {  // above the default cap the kernel must be told once how much it may take
+    static size_t allowed[2] = {0, 0};
+    size_t& a = allowed[A.D.b % 16 == 0];
+    if (lds > a) {
+      KVC_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+      a = lds;
+    }
+  }
   hipLaunchKernelGGL(kern, dim3(grid), dim3(kDecodeThreads), lds, s, A);
   KVC_LAUNCH_CHECK();
   if (pp) { KVC_HIP(hipEventRecord(pp->a1, s)); KVC_HIP(hipEventRecord(pp->b0, s)); }
@@ -527,7 +758,25 @@ static int launch_tiled_r(const DecodeArgs& A, int grid, size_t lds, hipStream_t
   return KVC_ERR_UNSUPPORTED;
 }
 
-constexpr size_t kLdsLimit = 64 * 1024;
+constexpr size_t kLdsLimit = 160 * 1024;  // gfx950: 160 KiB of LDS per workgroup
+
+// Whether the tiled kernels cover this shape, and with which chunk length and LDS size.
+static bool choose_chunk(const Dims& D, int* T_out, size_t* lds_out) {
+  const int esz = D.dtype == KVC_BF16 ? 2 : 4;
+  const int lpt = D.d * esz / 16;
+  const int tpi = (lpt >= 1 && lpt <= 64) ? 64 / lpt : 0;
+  bool tiled = (D.r == 1 || D.r == 2 || D.r == 4 || D.r == 8) && (D.d == 64 || D.d == 128) &&
+               tpi >= 1 && D.b % tpi == 0 && 64 % D.b == 0;
+  if (!tiled) return false;
+  // default: the longest chunk that still lets three (r <= 4) or two (r = 8) workgroups share a CU
+  int T = g_chunk_tokens ? g_chunk_tokens : (D.r >= 8 ? 2048 : 4096);
+  while (T > kMinChunk && decode_lds_bytes(T, D.r, D.d, D.b) > kLdsLimit) T -= 64;
+  const size_t lds = decode_lds_bytes(T, D.r, D.d, D.b);
+  if (lds > kLdsLimit) return false;
+  *T_out = T;
+  *lds_out = lds;
+  return true;
+}
 
 }  // namespace kvc
 
@@ -546,6 +795,7 @@ int kvc_profile_begin(int n) {
     g_prof = nullptr;
   }
   g_prof_cap = g_prof_used = 0;
+  g_prof_on = 1;
   if (n == 0) return KVC_OK;
   g_prof = new ProfilePair[n];
   for (int i = 0; i < n; ++i) {
@@ -553,6 +803,11 @@ int kvc_profile_begin(int n) {
     KVC_HIP(hipEventCreate(&g_prof[i].b0)); KVC_HIP(hipEventCreate(&g_prof[i].b1));
   }
   g_prof_cap = n;
+  return KVC_OK;
+}
+
+int kvc_profile_enable(int on) {
+  g_prof_on = on != 0;
   return KVC_OK;
 }
 
@@ -565,6 +820,16 @@ int kvc_profile_collect(float* chunk_ms, float* combine_ms, int cap, int* count)
     if (chunk_ms) { KVC_HIP(hipEventElapsedTime(&ms, g_prof[i].a0, g_prof[i].a1)); chunk_ms[i] = ms; }
     if (combine_ms) { KVC_HIP(hipEventElapsedTime(&ms, g_prof[i].b0, g_prof[i].b1)); combine_ms[i] = ms; }
   }
+  return KVC_OK;
+}
+
+int kvc_get_decode_chunk(const kvc_config* cfg, int* tokens) {
+  int rc = validate(cfg, nullptr);
+  if (rc != KVC_OK) return rc;
+  if (!tokens) return KVC_ERR_ARG;
+  int T = 0;
+  size_t lds = 0;
+  *tokens = choose_chunk(dims_of(cfg), &T, &lds) ? T : 0;
   return KVC_OK;
 }
 
@@ -592,36 +857,29 @@ int kvc_paged_decode(const kvc_config* cfg, const kvc_state* st, const void* q, 
   A.q = (const char*)q; A.out = out;
   A.l0 = layer_begin; A.nl = layer_end - layer_begin; A.gsel = D.S * A.nl * D.Hk;
   A.accumulate = accumulate_metric != 0;
-  A.chunk_off = W.off_a; A.part_ml = W.part_ml; A.part_acc = W.part_acc; A.stash = W.stash;
+  A.cap = (int)(max_items_of(D) < 0x7fffffffull ? max_items_of(D) : 0x7fffffffull);
+  A.items = (DecodeItem*)W.items; A.part_ml = W.part_ml; A.part_acc = W.part_acc; A.stash = W.stash;
   A.header = W.header;
   A.scale_log2 = (float)(1.4426950408889634 / sqrt((double)D.d));
 
-  const int esz = D.dtype == KVC_BF16 ? 2 : 4;
-  const int lpt = D.d * esz / 16;
-  const int tpi = lpt <= 64 ? 64 / lpt : 0;
-  bool tiled = (D.r == 1 || D.r == 2 || D.r == 4 || D.r == 8) && (D.d == 64 || D.d == 128) &&
-               tpi >= 1 && D.b % tpi == 0 && 64 % D.b == 0;
   int T = 0;
   size_t lds = 0;
-  if (tiled) {
-    T = g_chunk_tokens ? g_chunk_tokens : (D.r >= 8 ? 1024 : 2048);
-    while (T > kMinChunk && decode_lds_bytes(T, D.r, D.d, D.b) > kLdsLimit) T /= 2;
-    lds = decode_lds_bytes(T, D.r, D.d, D.b);
-    if (lds > kLdsLimit) tiled = false;
-  }
+  bool tiled = choose_chunk(D, &T, &lds);
+  const int esz = D.dtype == KVC_BF16 ? 2 : 4;
   A.T = tiled ? T : (1 << 30);  // generic path: one "chunk" per head
+  A.log2b = 0;
+  while ((1 << A.log2b) < D.b) ++A.log2b;
 
-  hipLaunchKernelGGL(zero_empty_kernel, dim3((A.gsel + 3) / 4), dim3(256), 0, s, A);
-  KVC_LAUNCH_CHECK();
   if (!tiled) {
     const size_t gl = ((size_t)D.r * D.d + 4 * 16 + 2 * 16) * 4;
     hipLaunchKernelGGL(decode_generic_kernel, dim3(A.gsel), dim3(256), gl, s, A);
     KVC_LAUNCH_CHECK();
     return KVC_OK;
   }
-  rc = device_exclusive_scan(ChunkFn{st->ctx_len, D, A.l0, A.nl, T}, A.gsel, W.tile_sums, W.off_a,
-                             W.header + HW_TOTAL_ITEMS, s);
-  if (rc != KVC_OK) return rc;
+  hipLaunchKernelGGL(decode_count_kernel, dim3((A.gsel + 255) / 256), dim3(256), 0, s, A);
+  KVC_LAUNCH_CHECK();
+  hipLaunchKernelGGL(decode_items_kernel, dim3((A.gsel + 255) / 256), dim3(256), 0, s, A);
+  KVC_LAUNCH_CHECK();
   // items <= (slots in the pool) / T + heads, and <= heads * chunks a full row can hold
   const size_t bound_pool = (size_t)D.N * D.b / T + (size_t)A.gsel;
   const size_t bound_row = (size_t)A.gsel * (((size_t)D.maxb * D.b + T - 1) / T);
