@@ -86,6 +86,8 @@ def main():
     ap.add_argument("--workload", default="llama8b", choices=["llama8b", "llama70b"])
     ap.add_argument("--uniform", action="store_true", help="diagnostic: every head holds prompt/rho KVs")
     ap.add_argument("--no-metric", action="store_true", help="diagnostic: decode without metric accumulation")
+    ap.add_argument("--per-layer-steps", type=int, default=4,
+                    help="extra untimed-region steps that call the decode once per layer (0 = skip)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (a kernel of known traffic, for scaling rocprofv3 counters)")
     args = ap.parse_args()
@@ -244,6 +246,20 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    # the same decode issued the way a model runs it: one call per layer (no append, no metric
+    # writes skipped), a few steps, reported beside the all-layers launch
+    per_layer_ms = None
+    if args.per_layer_steps > 0:
+        a, b_ = ev(), ev()
+        torch.cuda.synchronize()
+        a.record()
+        for i in range(args.per_layer_steps):
+            for l in range(shape.num_layers):
+                sess.paged_decode(qs[i % n_in], accumulate_metric=not args.no_metric, layer_begin=l, layer_end=l + 1)
+        b_.record()
+        torch.cuda.synchronize()
+        per_layer_ms = a.elapsed_time(b_) / args.per_layer_steps
+
     evict = None
     if evict_events:
         r = np.array([[e[j].elapsed_time(e[j + 1]) for j in range(3)] for e in evict_events])
@@ -265,6 +281,7 @@ def main():
                    "mean_kvs_per_step": float(kv_per_step.mean())},
         "frac_of_hbm_peak": value / HBM_PEAK_GBS,
         "decode_steps_per_s": 1e3 / ms_step,
+        "decode_only_ms_per_step_one_call_per_layer": per_layer_ms,
         "wall_s": wall,
         "eviction": evict,
         "roofline": roofline,

@@ -194,8 +194,9 @@ int kvc_compact(const kvc_config* cfg, const kvc_state* st, const uint8_t* evict
  * host only.  KVC_ERR_ARG unless 0 or a multiple of 64 in [64, 8192].          */
 int kvc_set_decode_chunk(int tokens);
 
-/* The chunk length kvc_paged_decode uses for this config (host out-param), 0 when the shape
- * takes the general fallback kernel, which does not split heads.  Host only.    */
+/* The chunk length kvc_paged_decode uses for this config when called over all layers (host
+ * out-param; calls over fewer layers may use shorter chunks), 0 when the shape takes the
+ * general fallback kernel, which does not split heads.  Host only.              */
 int kvc_get_decode_chunk(const kvc_config* cfg, int* tokens);
 
 /* Kernel timing for benchmarks.  kvc_profile_begin(n) makes the next n calls of
@@ -212,6 +213,13 @@ int kvc_get_decode_chunk(const kvc_config* cfg, int* tokens);
  * Gives the streaming-read rate this GPU reaches, to set beside the kernels'.   */
 int kvc_stream_read_probe(const void* src, size_t bytes, uint32_t* sink, int workgroups,
                           void* stream);
+
+/* The same probe with a trickle of writes mixed in: every lane stores 16 bytes to `dst`
+ * (device, dst_bytes, a multiple of 16; stores past its end are dropped) after every `every`
+ * rounds of four 16-byte loads, i.e. 16 bytes written per 64 * every bytes read.  Shows what
+ * small writes cost a saturated read stream on this GPU.                          */
+int kvc_stream_rw_probe(const void* src, size_t bytes, void* dst, size_t dst_bytes, int every,
+                        uint32_t* sink, int workgroups, void* stream);
 
 int kvc_profile_begin(int n);
 /* Pauses (0) or resumes (non-zero) the recording without releasing anything, so that a

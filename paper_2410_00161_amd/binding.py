@@ -26,7 +26,7 @@ EXPORTS = [
     "kvc_poll_status", "kvc_block_alloc", "kvc_block_free", "kvc_append", "kvc_paged_decode",
     "kvc_metric_reduce", "kvc_evict_select", "kvc_compact", "kvc_set_decode_chunk",
     "kvc_get_decode_chunk",
-    "kvc_profile_begin", "kvc_profile_enable", "kvc_profile_collect", "kvc_stream_read_probe",
+    "kvc_profile_begin", "kvc_profile_enable", "kvc_profile_collect", "kvc_stream_read_probe", "kvc_stream_rw_probe",
 ]
 
 
@@ -79,6 +79,7 @@ def lib() -> C.CDLL:
         L.kvc_profile_begin.argtypes = [I]
         L.kvc_profile_enable.argtypes = [I]
         L.kvc_stream_read_probe.argtypes = [P, C.c_size_t, P, I, P]
+        L.kvc_stream_rw_probe.argtypes = [P, C.c_size_t, P, C.c_size_t, I, P, I, P]
         L.kvc_profile_collect.argtypes = [P, P, I, C.POINTER(C.c_int)]
         for n in EXPORTS:
             if n not in ("kvc_workspace_bytes", "kvc_status_string"):
@@ -240,3 +241,9 @@ def kvc_get_decode_chunk(cfg) -> int:
     out = C.c_int(0)
     _check(lib().kvc_get_decode_chunk(C.byref(cfg), C.byref(out)), "kvc_get_decode_chunk")
     return out.value
+
+
+def kvc_stream_rw_probe(src, nbytes, dst, dst_bytes, every, sink, workgroups, stream=None):
+    _check(lib().kvc_stream_rw_probe(_ptr(src), int(nbytes), _ptr(dst), int(dst_bytes), int(every),
+                                     _ptr(sink, torch.int32), int(workgroups), _stream(stream)),
+           "kvc_stream_rw_probe")

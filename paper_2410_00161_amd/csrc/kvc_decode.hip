@@ -761,7 +761,7 @@ static int launch_tiled_r(const DecodeArgs& A, int grid, size_t lds, hipStream_t
 constexpr size_t kLdsLimit = 160 * 1024;  // gfx950: 160 KiB of LDS per workgroup
 
 // Whether the tiled kernels cover this shape, and with which chunk length and LDS size.
-static bool choose_chunk(const Dims& D, int* T_out, size_t* lds_out) {
+static bool choose_chunk(const Dims& D, int gsel, int* T_out, size_t* lds_out) {
   const int esz = D.dtype == KVC_BF16 ? 2 : 4;
   const int lpt = D.d * esz / 16;
   const int tpi = (lpt >= 1 && lpt <= 64) ? 64 / lpt : 0;
@@ -770,6 +770,12 @@ static bool choose_chunk(const Dims& D, int* T_out, size_t* lds_out) {
   if (!tiled) return false;
   // default: the longest chunk that still lets three (r <= 4) or two (r = 8) workgroups share a CU
   int T = g_chunk_tokens ? g_chunk_tokens : (D.r >= 8 ? 2048 : 4096);
+  if (!g_chunk_tokens) {
+    // a call over few head instances (one layer at a time) has too few long chunks to fill the
+    // chip: shorten them until full rows would give a few thousand work items
+    const long long want_items = 6144;
+    while (T > 256 && (long long)gsel * (((long long)D.maxb * D.b + T - 1) / T) < want_items) T /= 2;
+  }
   while (T > kMinChunk && decode_lds_bytes(T, D.r, D.d, D.b) > kLdsLimit) T -= 64;
   const size_t lds = decode_lds_bytes(T, D.r, D.d, D.b);
   if (lds > kLdsLimit) return false;
@@ -829,7 +835,8 @@ int kvc_get_decode_chunk(const kvc_config* cfg, int* tokens) {
   if (!tokens) return KVC_ERR_ARG;
   int T = 0;
   size_t lds = 0;
-  *tokens = choose_chunk(dims_of(cfg), &T, &lds) ? T : 0;
+  const Dims D = dims_of(cfg);
+  *tokens = choose_chunk(D, D.G, &T, &lds) ? T : 0;
   return KVC_OK;
 }
 
@@ -864,7 +871,7 @@ int kvc_paged_decode(const kvc_config* cfg, const kvc_state* st, const void* q, 
 
   int T = 0;
   size_t lds = 0;
-  bool tiled = choose_chunk(D, &T, &lds);
+  bool tiled = choose_chunk(D, D.S * (layer_end - layer_begin) * D.Hk, &T, &lds);
   const int esz = D.dtype == KVC_BF16 ? 2 : 4;
   A.T = tiled ? T : (1 << 30);  // generic path: one "chunk" per head
   A.log2b = 0;

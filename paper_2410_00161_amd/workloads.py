@@ -200,8 +200,14 @@ def make_cache(shape: Shape, ctx_len: torch.Tensor, seed: int, device="cpu",
     table, free_map = table.to(dev), free_map.to(dev)
     g = _gen(seed, dev)
     dt = shape.torch_dtype
-    k = torch.randn((N, b, d), generator=g, device=dev, dtype=torch.float32).to(dt)
-    v = torch.randn((N, b, d), generator=g, device=dev, dtype=torch.float32).to(dt)
+    # filled in slabs so that the f32 draw of a very large pool never exists whole
+    k = torch.empty((N, b, d), device=dev, dtype=dt)
+    v = torch.empty((N, b, d), device=dev, dtype=dt)
+    slab = 1 << 17
+    for t in (k, v):
+        for lo in range(0, N, slab):
+            hi = min(N, lo + slab)
+            t[lo:hi] = torch.randn((hi - lo, b, d), generator=g, device=dev, dtype=torch.float32).to(dt)
     heavy = torch.rand((N, b), generator=g, device=dev) < heavy_frac
     u = torch.randn((shape.G, d), generator=g, device=dev, dtype=torch.float32)
     u = u / u.norm(dim=1, keepdim=True)
