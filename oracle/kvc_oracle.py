@@ -26,6 +26,9 @@ Where each function comes from (sections of the KV-Compress paper):
                                blocks; domain 1 <= e < ceil(C_h / b)
   compact .................... Algorithm 1 (MoveCache) in closed form, and
                                movecache_sequential = the two-pointer loop
+  rank_schedule .............. the same section's schedule as printed: per-head
+                               sort, rows of b, m(h, e) = last column, rows
+                               ordered across heads, first E_s marked
 
 Readings taken where the paper is silent or inconsistent:
   * a "block" in block_keys/select is a physical block as it lies in a head's
@@ -318,24 +321,108 @@ def compact(st: State, flag, count=None) -> int:
         C = int(lens[g])
         if C == 0 or not flag[g].any():
             continue
-        w = _evicted_slots(st, g, flag[g])
-        T = C - int(w.sum())
-        holes = [i for i in range(T) if w[i]]
-        movers = [j for j in range(C - 1, T - 1, -1) if not w[j]]
-        assert len(holes) == len(movers)
-        for i, j in zip(holes, movers):
-            ns, os_ = tab[g, j // st.b], j % st.b
-            nd, od = tab[g, i // st.b], i % st.b
-            st.k_cache[nd, od] = st.k_cache[ns, os_]
-            st.v_cache[nd, od] = st.v_cache[ns, os_]
-            st.metric[nd, od] = st.metric[ns, os_]
-            st.pos[nd, od] = st.pos[ns, os_]
-        nb, nb2 = -(-C // st.b), -(-T // st.b)
-        for u in range(nb2, nb):
-            st.free_map[tab[g, u]] = 1
-            tab[g, u] = -1
-            freed += 1
-        lens[g] = T
+        freed += _move_and_free(st, g, _evicted_slots(st, g, flag[g]))
+    return freed
+
+
+def _move_and_free(st: State, g: int, w) -> int:
+    """MoveCache on head g for the slot mask w (True = evicted), then the free step."""
+    tab, lens = st.table(), st.lens()
+    C = int(lens[g])
+    T = C - int(np.sum(w))
+    holes = [i for i in range(T) if w[i]]
+    movers = [j for j in range(C - 1, T - 1, -1) if not w[j]]
+    assert len(holes) == len(movers)
+    for i, j in zip(holes, movers):
+        ns, os_ = tab[g, j // st.b], j % st.b
+        nd, od = tab[g, i // st.b], i % st.b
+        st.k_cache[nd, od] = st.k_cache[ns, os_]
+        st.v_cache[nd, od] = st.v_cache[ns, os_]
+        st.metric[nd, od] = st.metric[ns, os_]
+        st.pos[nd, od] = st.pos[ns, os_]
+    nb, nb2 = -(-C // st.b), -(-T // st.b)
+    for u in range(nb2, nb):
+        st.free_map[tab[g, u]] = 1
+        tab[g, u] = -1
+    lens[g] = T
+    return nb - nb2
+
+
+# --------------------------------------------------------------------------
+# the paper's own eviction schedule (rank blocks)
+# --------------------------------------------------------------------------
+
+def rank_schedule(st: State, budget, seg_offsets=None, protect_tail_blocks=1, metric=None):
+    """The schedule of "Evicting from a Paged KV Cache", step by step.
+
+    Per head: its metrics sorted ascending, the empty slots of its last block
+    first (they count as zero and come before every real metric); the sorted
+    list cut into rows of b; row e-1 holds what evicting the e-th block would
+    remove, and its last column is m(h, e), the largest metric evicted with
+    it.  Candidate rows of a head: e < ceil(C_h / b) (protect_tail_blocks = 1;
+    0 lets a head lose every block).  Per segment the candidate rows of all its
+    heads are ordered by that last column (ties: sequence, layer, head, row)
+    and the first E rows are marked; the KVs of a marked row are evicted.
+    Metrics are compared as f32; equal metrics of one head go in logical order.
+
+    Returns (rows [G] i32 = blocks each head loses, masks = list of G boolean
+    arrays over logical slots, selected [nseg] i32)."""
+    M = st.metric if metric is None else np.asarray(metric).reshape(st.N, st.b)
+    M32 = M.astype(np.float32)
+    if seg_offsets is None:
+        seg_offsets = np.arange(st.S + 1)
+    seg_offsets = np.asarray(seg_offsets, dtype=np.int64)
+    nseg = seg_offsets.size - 1
+    budget = np.asarray(budget, dtype=np.int64).reshape(nseg)
+    if seg_offsets[0] != 0 or seg_offsets[-1] != st.S or (np.diff(seg_offsets) < 0).any():
+        raise OracleError(ERR_ARG, "bad segment offsets")
+    if (budget < 0).any() or protect_tail_blocks < 0:
+        raise OracleError(ERR_ARG)
+    lens = st.lens()
+    per_seq = st.Lyr * st.Hk
+    rows = np.zeros(st.G, dtype=np.int32)
+    masks = [np.zeros(int(lens[g]), dtype=bool) for g in range(st.G)]
+    selected = np.zeros(nseg, dtype=np.int32)
+    sorted_rows = {}   # g -> list of rows, each a list of (is_real, metric, logical index)
+    for g in range(st.G):
+        C = int(lens[g])
+        if C == 0:
+            sorted_rows[g] = []
+            continue
+        n, o = slots_of(st, g)
+        vals = M32[n, o]
+        if not (vals >= 0).all() or not np.isfinite(vals).all():
+            raise OracleError(ERR_NUMERIC, "negative, NaN or infinite metric")
+        nb = -(-C // st.b)
+        entries = [(0, np.float32(0.0), -1)] * (nb * st.b - C) + \
+                  sorted((1, vals[j], j) for j in range(C))
+        sorted_rows[g] = [entries[e * st.b:(e + 1) * st.b] for e in range(nb)]
+    for sg in range(nseg):
+        cands = []
+        for g in range(seg_offsets[sg] * per_seq, seg_offsets[sg + 1] * per_seq):
+            r = sorted_rows[g]
+            for e in range(max(0, len(r) - protect_tail_blocks)):
+                cands.append((float(r[e][-1][1]), g, e))
+        cands.sort()
+        take = min(int(budget[sg]), len(cands))
+        for _, g, e in cands[:take]:
+            rows[g] += 1
+            for is_real, _, j in sorted_rows[g][e]:
+                if is_real:
+                    masks[g][j] = True
+        selected[sg] = take
+    return rows, masks, selected
+
+
+def compact_slots(st: State, masks) -> int:
+    """MoveCache + free for an eviction mask over logical slots (one boolean array per head)."""
+    freed = 0
+    for g in range(st.G):
+        w = np.asarray(masks[g], dtype=bool)
+        if w.size != int(st.lens()[g]):
+            raise OracleError(ERR_ARG, "mask length")
+        if w.any():
+            freed += _move_and_free(st, g, w)
     return freed
 
 
