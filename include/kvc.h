@@ -189,6 +189,28 @@ int kvc_compact(const kvc_config* cfg, const kvc_state* st, const uint8_t* evict
                 const int32_t* evict_count, int64_t* blocks_freed, void* ws, void* stream,
                 int flags);
 
+/* The paper's own eviction schedule ("Evicting from a Paged KV Cache": metrics sorted per
+ * head, rows of b with the empty slots of the last block first as zeros, m(h, e) = last
+ * column of row e-1, rows of all heads of a sequence ordered by it, first E_s rows marked),
+ * computed without sorting.  Candidate rows of head g: e <= ceil(ctx_len/b) -
+ * protect_tail_blocks.  Per segment the min(budget, candidates) rows smallest in
+ * (m, s, l, h, e) are chosen.  seg_offsets / budget / nseg / selected as kvc_evict_select.
+ * Output evict_rows [G] i32: blocks each head loses.  KVC_ERR_NUMERIC when a metric of a
+ * candidate head is NaN, infinite or negative (outputs all zero).  Reads metric, block_table
+ * and ctx_len; changes no state.  Synchronises unless KVC_ASYNC.                  */
+int kvc_evict_rank_select(const kvc_config* cfg, const kvc_state* st, const int32_t* seg_offsets,
+                          const int32_t* budget, int nseg, int protect_tail_blocks,
+                          int32_t* evict_rows, int32_t* selected, void* ws, void* stream, int flags);
+
+/* Carries a rank schedule out: head g loses its evict_rows[g]*b - (empty slots of its last
+ * block) KVs of smallest (metric, logical index) — the KVs of its first evict_rows[g] rows —
+ * then MoveCache (Algorithm 1) closes the holes below the new length with the kept KVs above
+ * it, ctx_len becomes (ceil(ctx_len/b) - evict_rows[g]) * b and the tail blocks are freed.
+ * blocks_freed: device int64, may be NULL.  KVC_ERR_ARG (nothing modified) when a count is
+ * negative or exceeds the head's blocks.  Synchronises unless KVC_ASYNC.          */
+int kvc_compact_rank(const kvc_config* cfg, const kvc_state* st, const int32_t* evict_rows,
+                     int64_t* blocks_freed, void* ws, void* stream, int flags);
+
 /* Tuning knob of kvc_paged_decode: tokens handled by one workgroup before a
  * head is split across workgroups.  0 restores the default.  Process-wide,
  * host only.  KVC_ERR_ARG unless 0 or a multiple of 64 in [64, 8192].          */

@@ -25,7 +25,7 @@ EXPORTS = [
     "kvc_workspace_bytes", "kvc_validate", "kvc_status_string", "kvc_workspace_reset",
     "kvc_poll_status", "kvc_block_alloc", "kvc_block_free", "kvc_append", "kvc_paged_decode",
     "kvc_metric_reduce", "kvc_evict_select", "kvc_compact", "kvc_set_decode_chunk",
-    "kvc_get_decode_chunk",
+    "kvc_get_decode_chunk", "kvc_evict_rank_select", "kvc_compact_rank",
     "kvc_profile_begin", "kvc_profile_enable", "kvc_profile_collect", "kvc_stream_read_probe", "kvc_stream_rw_probe",
 ]
 
@@ -75,6 +75,8 @@ def lib() -> C.CDLL:
         L.kvc_evict_select.argtypes = [cfgp, stp, P, P, P, I, I, P, P, P, P, P, I]
         L.kvc_compact.argtypes = [cfgp, stp, P, P, P, P, P, I]
         L.kvc_set_decode_chunk.argtypes = [I]
+        L.kvc_evict_rank_select.argtypes = [cfgp, stp, P, P, I, I, P, P, P, P, I]
+        L.kvc_compact_rank.argtypes = [cfgp, stp, P, P, P, P, I]
         L.kvc_get_decode_chunk.argtypes = [cfgp, C.POINTER(C.c_int)]
         L.kvc_profile_begin.argtypes = [I]
         L.kvc_profile_enable.argtypes = [I]
@@ -247,3 +249,18 @@ def kvc_stream_rw_probe(src, nbytes, dst, dst_bytes, every, sink, workgroups, st
     _check(lib().kvc_stream_rw_probe(_ptr(src), int(nbytes), _ptr(dst), int(dst_bytes), int(every),
                                      _ptr(sink, torch.int32), int(workgroups), _stream(stream)),
            "kvc_stream_rw_probe")
+
+
+def kvc_evict_rank_select(cfg, st, seg_offsets, budget, nseg, protect_tail_blocks, evict_rows, selected, ws,
+                          stream=None, flags=0):
+    _check(lib().kvc_evict_rank_select(C.byref(cfg), C.byref(st),
+                                       _ptr(seg_offsets, torch.int32) if seg_offsets is not None else None,
+                                       _ptr(budget, torch.int32), nseg, protect_tail_blocks,
+                                       _ptr(evict_rows, torch.int32), _ptr(selected, torch.int32), _ptr(ws),
+                                       _stream(stream), flags), "kvc_evict_rank_select")
+
+
+def kvc_compact_rank(cfg, st, evict_rows, blocks_freed, ws, stream=None, flags=0):
+    _check(lib().kvc_compact_rank(C.byref(cfg), C.byref(st), _ptr(evict_rows, torch.int32),
+                                  _ptr(blocks_freed, torch.int64) if blocks_freed is not None else None,
+                                  _ptr(ws), _stream(stream), flags), "kvc_compact_rank")

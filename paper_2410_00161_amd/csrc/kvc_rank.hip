@@ -1,0 +1,413 @@
+// The paper's own eviction schedule ("Evicting from a Paged KV Cache", steps
+// M1..W7) without any sort.
+//
+// In the paper each head's metrics are sorted, cut into rows of b (the empty
+// slots of its last block first, as zeros), row e-1 is what evicting the head's
+// e-th block removes and its last column m(h, e) orders the rows of all heads.
+// Two facts make sorting unnecessary:
+//   * row k of a head has m <= x exactly when the head has at least (k+1)*b
+//     entries <= x, so the number of candidate rows of a head with m <= x is
+//     min(candidates, floor(count(<= x) / b)).  Summed over the heads of a
+//     segment this is monotone in x, and an 8-bit-per-pass radix descent on the
+//     f32 bit pattern finds the E-th smallest m and how many rows tie with it;
+//   * once a head knows how many rows e it loses, the KVs it loses are its
+//     e*b - (empty slots) smallest by (metric, logical index): a per-head
+//     radix select gives the threshold metric and the number of ties to take.
+// The compaction is MoveCache (Algorithm 1) for a slot-granular mask: holes and
+// movers are ranked with ordered prefix counts and paired k-th to k-th.
+#include "kvc_common.h"
+
+namespace kvc {
+
+enum { RS_PREFIX = 0, RS_REMAIN = 1, RS_CAND = 2, RS_TAKE = 3, RS_FIRSTG = 4 };
+
+__device__ __forceinline__ uint32_t metric_bits(float f) {
+  const uint32_t k = __float_as_uint(f);
+  return k == 0x80000000u ? 0u : k;  // -0 orders as +0
+}
+
+__global__ void __launch_bounds__(256) rank_init_kernel(Dims D, const int32_t* __restrict__ seg_offsets,
+                                                        int nseg, int32_t* __restrict__ seq_seg,
+                                                        int32_t* __restrict__ seg_hist,
+                                                        int32_t* __restrict__ seg_state,
+                                                        int32_t* __restrict__ evict_rows,
+                                                        int32_t* __restrict__ selected,
+                                                        int32_t* __restrict__ header) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < D.S) {
+    int sg = i;
+    if (seg_offsets) {
+      int lo = 0, hi = nseg;
+      while (hi - lo > 1) { const int mid = (lo + hi) >> 1; if (seg_offsets[mid] <= i) lo = mid; else hi = mid; }
+      sg = lo;
+    }
+    seq_seg[i] = sg;
+  }
+  if (i < nseg * 256) seg_hist[i] = 0;
+  if (i < nseg) {
+    selected[i] = 0;
+    for (int k = 0; k < 8; ++k) seg_state[i * 8 + k] = 0;
+    const int first_seq = seg_offsets ? seg_offsets[i] : i;
+    seg_state[i * 8 + RS_FIRSTG] = first_seq * D.Lyr * D.Hk;
+    if (seg_offsets) {
+      const int a = seg_offsets[i], b2 = seg_offsets[i + 1];
+      if (a > b2 || (i == 0 && a != 0) || (i == nseg - 1 && b2 != D.S)) atomicOr(&header[HW_SCRATCH0], EB_ARG);
+    }
+  }
+  if (i < D.G) evict_rows[i] = 0;
+}
+
+// One workgroup per head instance.  Counts the head's entries below the prefix found so far
+// and histograms the next digit of those that match it; turns the running counts into rows
+// per digit and adds them to the segment's histogram.
+__global__ void __launch_bounds__(256) rank_hist_kernel(Dims D, int pass, int protect,
+                                                        const float* __restrict__ metric,
+                                                        const int32_t* __restrict__ table,
+                                                        const int32_t* __restrict__ ctx,
+                                                        const int32_t* __restrict__ seq_seg,
+                                                        int32_t* __restrict__ seg_hist,
+                                                        int32_t* __restrict__ seg_state,
+                                                        int32_t* __restrict__ header) {
+  __shared__ int hist[256];
+  __shared__ int below_s, bad_s;
+  __shared__ int smem[256 / 64 + 1];
+  const int g = blockIdx.x, tid = threadIdx.x;
+  const int sg = seq_seg[g / (D.Lyr * D.Hk)];
+  const int C = ctx[g];
+  const int nb = (C + D.b - 1) / D.b;
+  const int ncand = max(0, nb - protect);
+  if (pass == 0 && tid == 0 && ncand > 0) atomicAdd(&seg_state[sg * 8 + RS_CAND], ncand);
+  if (ncand == 0) return;
+  if (pass > 0 && seg_state[sg * 8 + RS_TAKE] <= 0) return;
+  hist[tid] = 0;
+  if (tid == 0) { below_s = 0; bad_s = 0; }
+  __syncthreads();
+  const int shift = 24 - 8 * pass;
+  const uint32_t prefix = (uint32_t)seg_state[sg * 8 + RS_PREFIX];
+  const int32_t* row = table + (size_t)g * D.maxb;
+  int below = 0;
+  bool bad = false;
+  for (int j = tid; j < C; j += 256) {
+    const uint32_t k = metric_bits(metric[(size_t)row[j / D.b] * D.b + (j % D.b)]);
+    if (pass == 0) bad |= k >= 0x7f800000u;
+    const uint32_t top = pass == 0 ? 0u : (k >> (shift + 8));
+    if (top < prefix) ++below;
+    else if (top == prefix) atomicAdd(&hist[(k >> shift) & 255], 1);
+  }
+  const int z = nb * D.b - C;  // the empty slots count as zeros, ahead of every real metric
+  if (tid == 0 && z) {
+    if (prefix == 0) atomicAdd(&hist[0], z); else below += z;
+  }
+  below = wave_sum_i(below);
+  if ((tid & 63) == 0 && below) atomicAdd(&below_s, below);
+  if (bad) bad_s = 1;
+  __syncthreads();
+  if (pass == 0 && tid == 0 && bad_s) atomicOr(&header[HW_SCRATCH0], EB_NUMERIC);
+  const int c = hist[tid];
+  const int ex = block_exclusive_scan<256>(c, smem, nullptr) + below_s;
+  const int rows_before = min(ncand, ex / D.b);
+  const int rows_upto = min(ncand, (ex + c) / D.b);
+  if (rows_upto > rows_before) atomicAdd(&seg_hist[sg * 256 + tid], rows_upto - rows_before);
+}
+
+// One workgroup per segment: the digit that holds the E-th smallest row key (same rule as the
+// block-key selection).
+__global__ void __launch_bounds__(256) rank_pick_kernel(int pass, const int32_t* __restrict__ budget,
+                                                        int32_t* __restrict__ seg_hist,
+                                                        int32_t* __restrict__ seg_state,
+                                                        int32_t* __restrict__ header) {
+  __shared__ int smem[256 / 64 + 1];
+  __shared__ int chosen;
+  const int sg = blockIdx.x;
+  int32_t* stt = seg_state + sg * 8;
+  if (pass == 0 && threadIdx.x == 0) {
+    int bud = budget[sg];
+    if (bud < 0) { atomicOr(&header[HW_SCRATCH0], EB_ARG); bud = 0; }
+    const int take = min(bud, stt[RS_CAND]);
+    stt[RS_TAKE] = take;
+    stt[RS_REMAIN] = take;
+  }
+  __syncthreads();
+  const int take = stt[RS_TAKE];
+  const int remain = stt[RS_REMAIN];
+  const int c = seg_hist[sg * 256 + threadIdx.x];
+  const int ex = block_exclusive_scan<256>(c, smem, nullptr);
+  if (threadIdx.x == 0) chosen = -1;
+  __syncthreads();
+  if (take > 0 && ex < remain && remain <= ex + c) chosen = threadIdx.x;
+  __syncthreads();
+  if (take > 0 && (int)threadIdx.x == chosen) {
+    stt[RS_PREFIX] = (int32_t)(((uint32_t)stt[RS_PREFIX] << 8) | (uint32_t)chosen);
+    stt[RS_REMAIN] = remain - ex;
+  }
+  seg_hist[sg * 256 + threadIdx.x] = 0;
+}
+
+// Rows strictly below the threshold key, and rows that tie with it, per head.
+__global__ void __launch_bounds__(256) rank_tie_kernel(Dims D, int protect, const float* __restrict__ metric,
+                                                       const int32_t* __restrict__ table,
+                                                       const int32_t* __restrict__ ctx,
+                                                       const int32_t* __restrict__ seq_seg,
+                                                       const int32_t* __restrict__ seg_state,
+                                                       int32_t* __restrict__ rows_lt,
+                                                       int32_t* __restrict__ rows_tie) {
+  __shared__ int lt_s, le_s;
+  const int g = blockIdx.x, tid = threadIdx.x;
+  const int sg = seq_seg[g / (D.Lyr * D.Hk)];
+  const int C = ctx[g];
+  const int nb = (C + D.b - 1) / D.b;
+  const int ncand = max(0, nb - protect);
+  if (ncand == 0 || seg_state[sg * 8 + RS_TAKE] <= 0) {
+    if (tid == 0) { rows_lt[g] = 0; rows_tie[g] = 0; }
+    return;
+  }
+  if (tid == 0) { lt_s = 0; le_s = 0; }
+  __syncthreads();
+  const uint32_t thr = (uint32_t)seg_state[sg * 8 + RS_PREFIX];
+  const int32_t* row = table + (size_t)g * D.maxb;
+  int lt = 0, le = 0;
+  for (int j = tid; j < C; j += 256) {
+    const uint32_t k = metric_bits(metric[(size_t)row[j / D.b] * D.b + (j % D.b)]);
+    lt += k < thr;
+    le += k <= thr;
+  }
+  if (tid == 0) {
+    const int z = nb * D.b - C;
+    le += z;
+    if (thr > 0) lt += z;
+  }
+  lt = wave_sum_i(lt);
+  le = wave_sum_i(le);
+  if ((tid & 63) == 0) { atomicAdd(&lt_s, lt); atomicAdd(&le_s, le); }
+  __syncthreads();
+  if (tid == 0) {
+    const int a = min(ncand, lt_s / D.b), c = min(ncand, le_s / D.b);
+    rows_lt[g] = a;
+    rows_tie[g] = c - a;
+  }
+}
+
+struct RowTieFn {
+  const int32_t* cnt;
+  __device__ int operator()(int i) const { return cnt[i]; }
+};
+
+__global__ void __launch_bounds__(256) rank_grant_kernel(Dims D, const int32_t* __restrict__ seq_seg,
+                                                         const int32_t* __restrict__ seg_state,
+                                                         const int32_t* __restrict__ rows_tie,
+                                                         const int32_t* __restrict__ tie_off,
+                                                         int32_t* __restrict__ evict_rows,
+                                                         int32_t* __restrict__ selected,
+                                                         const int32_t* __restrict__ header) {
+  const int g = blockIdx.x * 256 + threadIdx.x;
+  if (g >= D.G) return;
+  if (header[HW_STATUS] != KVC_OK) { evict_rows[g] = 0; return; }
+  const int sg = seq_seg[g / (D.Lyr * D.Hk)];
+  const int32_t* stt = seg_state + sg * 8;
+  const int take = stt[RS_TAKE];
+  if (g == stt[RS_FIRSTG]) selected[sg] = take;
+  if (take <= 0) { evict_rows[g] = 0; return; }
+  const int before = tie_off[g] - tie_off[stt[RS_FIRSTG]];
+  const int granted = max(0, min(rows_tie[g], stt[RS_REMAIN] - before));
+  evict_rows[g] += granted;  // evict_rows holds the rows strictly below the threshold
+}
+
+// ---------------------------------------------------------------------------
+// compaction for a head that loses e rows
+// ---------------------------------------------------------------------------
+
+__global__ void __launch_bounds__(256) rank_check_kernel(Dims D, const int32_t* __restrict__ ctx,
+                                                         const int32_t* __restrict__ evict_rows,
+                                                         int32_t* __restrict__ header) {
+  const int g = blockIdx.x * 256 + threadIdx.x;
+  if (g >= D.G) return;
+  const int nb = (ctx[g] + D.b - 1) / D.b;
+  const int e = evict_rows[g];
+  if (e < 0 || e > nb) atomicOr(&header[HW_SCRATCH0], EB_ARG);
+}
+
+// One workgroup per head.  scratch is an int array shaped like the metric ([N, b]); the head
+// uses the cells of its own blocks: hole k at logical cell k, mover k at logical cell C-1-k.
+__global__ void __launch_bounds__(256) rank_compact_kernel(Dims D, char* __restrict__ kc, char* __restrict__ vc,
+                                                           float* __restrict__ metric,
+                                                           int32_t* __restrict__ pos,
+                                                           int32_t* __restrict__ table,
+                                                           int32_t* __restrict__ ctx,
+                                                           uint8_t* __restrict__ free_map,
+                                                           const int32_t* __restrict__ evict_rows,
+                                                           int32_t* __restrict__ scratch,
+                                                           int32_t* __restrict__ header) {
+  if (header[HW_STATUS] != KVC_OK) return;
+  const int g = blockIdx.x, tid = threadIdx.x;
+  const int e = evict_rows[g];
+  if (e <= 0) return;
+  __shared__ int hist[256];
+  __shared__ int smem[256 / 64 + 1];
+  __shared__ int chosen_s, prefix_s, remain_s, carry_tie, carry_ev, nholes_s;
+  const int b = D.b;
+  const int C = ctx[g];
+  const int nb = (C + b - 1) / b;
+  const int n_ev = e * b - (nb * b - C);  // real KVs in the first e rows
+  const int T = C - n_ev;                 // = (nb - e) * b
+  int32_t* row = table + (size_t)g * D.maxb;
+  auto phys = [&](int j) -> size_t { return (size_t)row[j / b] * b + (j % b); };
+
+  // ---- threshold metric: the n_ev-th smallest by (metric, logical index) ----
+  if (tid == 0) { prefix_s = 0; remain_s = n_ev; }
+  __syncthreads();
+  for (int pass = 0; pass < 4; ++pass) {
+    hist[tid] = 0;
+    __syncthreads();
+    const int shift = 24 - 8 * pass;
+    const uint32_t prefix = (uint32_t)prefix_s;
+    for (int j = tid; j < C; j += 256) {
+      const uint32_t k = metric_bits(metric[phys(j)]);
+      if (pass == 0 || (k >> (shift + 8)) == prefix) atomicAdd(&hist[(k >> shift) & 255], 1);
+    }
+    __syncthreads();
+    const int c = hist[tid];
+    const int ex = block_exclusive_scan<256>(c, smem, nullptr);
+    const int remain = remain_s;
+    if (tid == 0) chosen_s = -1;
+    __syncthreads();
+    if (ex < remain && remain <= ex + c) chosen_s = tid;
+    __syncthreads();
+    if (tid == chosen_s) {
+      prefix_s = (int)((prefix << 8) | (uint32_t)tid);
+      remain_s = remain - ex;
+    }
+    __syncthreads();
+  }
+  const uint32_t thr = (uint32_t)prefix_s;
+  const int ties_take = remain_s;
+
+  // ---- ordered pass: who is evicted, hole and mover ranks ----
+  if (tid == 0) { carry_tie = 0; carry_ev = 0; nholes_s = 0; }
+  __syncthreads();
+  for (int base = 0; base < C; base += 256) {
+    const int j = base + tid;
+    uint32_t k = 0xffffffffu;
+    if (j < C) k = metric_bits(metric[phys(j)]);
+    const int is_tie = (j < C) && k == thr;
+    int tot_tie;
+    const int tie_rank = block_exclusive_scan<256>(is_tie, smem, &tot_tie) + carry_tie;
+    const int ev = (j < C) && (k < thr || (is_tie && tie_rank < ties_take));
+    int tot_ev;
+    const int ev_before = block_exclusive_scan<256>(ev, smem, &tot_ev) + carry_ev;
+    if (j < C) {
+      if (ev) {
+        if (j < T) { scratch[phys(ev_before)] = j; atomicAdd(&nholes_s, 1); }
+      } else if (j >= T) {
+        const int kk = (C - 1 - j) - (n_ev - ev_before);  // kept slots above j
+        scratch[phys(C - 1 - kk)] = j;
+      }
+    }
+    __syncthreads();
+    if (tid == 0) { carry_tie += tot_tie; carry_ev += tot_ev; }
+    __syncthreads();
+  }
+  const int n_moves = nholes_s;
+  const size_t row_bytes = (size_t)D.d * (D.dtype == KVC_BF16 ? 2 : 4);
+  const int pieces = (int)(row_bytes / 16);
+  const int grp = tid >> 4, gl = tid & 15;
+  for (int kk = grp; kk < n_moves; kk += 16) {
+    const size_t dst = phys(scratch[phys(kk)]);
+    const size_t src = phys(scratch[phys(C - 1 - kk)]);
+    for (int c = gl; c < pieces; c += 16) {
+      ((uint4*)(kc + dst * row_bytes))[c] = ((const uint4*)(kc + src * row_bytes))[c];
+      ((uint4*)(vc + dst * row_bytes))[c] = ((const uint4*)(vc + src * row_bytes))[c];
+    }
+    if (gl == 0) {
+      metric[dst] = metric[src];
+      if (pos) pos[dst] = pos[src];
+    }
+  }
+  __syncthreads();
+  const int nb2 = nb - e;
+  for (int u = nb2 + tid; u < nb; u += 256) {
+    free_map[row[u]] = 1;
+    row[u] = -1;
+  }
+  if (tid == 0) {
+    ctx[g] = T;
+    atomicAdd(&header[HW_FREED], e);
+  }
+}
+
+__global__ void rank_publish_freed_kernel(const int32_t* header, int64_t* out) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) out[0] = header[HW_STATUS] == KVC_OK ? header[HW_FREED] : 0;
+}
+
+}  // namespace kvc
+
+using namespace kvc;
+
+extern "C" {
+
+int kvc_evict_rank_select(const kvc_config* cfg, const kvc_state* st, const int32_t* seg_offsets,
+                          const int32_t* budget, int nseg, int protect_tail_blocks, int32_t* evict_rows,
+                          int32_t* selected, void* ws, void* stream, int flags) {
+  int rc = validate(cfg, st);
+  if (rc != KVC_OK) return rc;
+  if (!budget || !evict_rows || !selected || !ws || ((uintptr_t)ws & 255)) return KVC_ERR_ARG;
+  Dims D = dims_of(cfg);
+  if (nseg <= 0 || nseg > D.S || protect_tail_blocks < 0) return KVC_ERR_ARG;
+  if (!seg_offsets && nseg != D.S) return KVC_ERR_ARG;
+  Workspace W = carve(D, ws);
+  hipStream_t s = (hipStream_t)stream;
+  int32_t* seq_seg = W.held;
+  const int n_init = D.G > nseg * 256 ? D.G : nseg * 256;
+  hipLaunchKernelGGL(rank_init_kernel, dim3((n_init + 255) / 256), dim3(256), 0, s, D, seg_offsets, nseg, seq_seg,
+                     W.seg_hist, W.seg_state, evict_rows, selected, W.header);
+  KVC_LAUNCH_CHECK();
+  for (int pass = 0; pass < 4; ++pass) {
+    hipLaunchKernelGGL(rank_hist_kernel, dim3(D.G), dim3(256), 0, s, D, pass, protect_tail_blocks, st->metric,
+                       st->block_table, st->ctx_len, seq_seg, W.seg_hist, W.seg_state, W.header);
+    KVC_LAUNCH_CHECK();
+    hipLaunchKernelGGL(rank_pick_kernel, dim3(nseg), dim3(256), 0, s, pass, budget, W.seg_hist, W.seg_state,
+                       W.header);
+    KVC_LAUNCH_CHECK();
+    if (pass == 0) {
+      hipLaunchKernelGGL(resolve_kernel, dim3(1), dim3(64), 0, s, W.header, 0);
+      KVC_LAUNCH_CHECK();
+    }
+  }
+  hipLaunchKernelGGL(rank_tie_kernel, dim3(D.G), dim3(256), 0, s, D, protect_tail_blocks, st->metric,
+                     st->block_table, st->ctx_len, seq_seg, W.seg_state, evict_rows, W.off_b);
+  KVC_LAUNCH_CHECK();
+  rc = device_exclusive_scan(RowTieFn{W.off_b}, D.G, W.tile_sums, W.off_a, nullptr, s);
+  if (rc != KVC_OK) return rc;
+  hipLaunchKernelGGL(rank_grant_kernel, dim3((D.G + 255) / 256), dim3(256), 0, s, D, seq_seg, W.seg_state,
+                     W.off_b, W.off_a, evict_rows, selected, W.header);
+  KVC_LAUNCH_CHECK();
+  return (flags & KVC_ASYNC) ? KVC_OK : finish_sync(W, s);
+}
+
+int kvc_compact_rank(const kvc_config* cfg, const kvc_state* st, const int32_t* evict_rows,
+                     int64_t* blocks_freed, void* ws, void* stream, int flags) {
+  int rc = validate(cfg, st);
+  if (rc != KVC_OK) return rc;
+  if (!evict_rows || !ws || ((uintptr_t)ws & 255)) return KVC_ERR_ARG;
+  if (blocks_freed && ((uintptr_t)blocks_freed & 7)) return KVC_ERR_ARG;
+  Dims D = dims_of(cfg);
+  Workspace W = carve(D, ws);
+  hipStream_t s = (hipStream_t)stream;
+  hipLaunchKernelGGL(zero_words_kernel, dim3(1), dim3(64), 0, s, W.header + HW_FREED, 1);
+  KVC_LAUNCH_CHECK();
+  hipLaunchKernelGGL(rank_check_kernel, dim3((D.G + 255) / 256), dim3(256), 0, s, D, st->ctx_len, evict_rows,
+                     W.header);
+  KVC_LAUNCH_CHECK();
+  hipLaunchKernelGGL(resolve_kernel, dim3(1), dim3(64), 0, s, W.header, 0);
+  KVC_LAUNCH_CHECK();
+  hipLaunchKernelGGL(rank_compact_kernel, dim3(D.G), dim3(256), 0, s, D, (char*)st->k_cache, (char*)st->v_cache,
+                     st->metric, st->pos, st->block_table, st->ctx_len, st->free_map, evict_rows,
+                     (int32_t*)W.stash, W.header);
+  KVC_LAUNCH_CHECK();
+  if (blocks_freed) {
+    hipLaunchKernelGGL(rank_publish_freed_kernel, dim3(1), dim3(64), 0, s, W.header, blocks_freed);
+    KVC_LAUNCH_CHECK();
+  }
+  return (flags & KVC_ASYNC) ? KVC_OK : finish_sync(W, s);
+}
+
+}  // extern "C"

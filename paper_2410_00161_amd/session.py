@@ -72,3 +72,18 @@ class KvcSession:
                       self.evict_count if evict_count is None else evict_count, self.blocks_freed,
                       self.ws, flags=flags)
         return self.blocks_freed
+
+    def evict_rank_select(self, budget, seg_offsets=None, protect_tail_blocks=1, flags=0):
+        budget = budget.to(self.device, torch.int32).contiguous()
+        nseg = budget.numel()
+        if seg_offsets is not None:
+            seg_offsets = seg_offsets.to(self.device, torch.int32).contiguous()
+        selected = torch.zeros((nseg,), dtype=torch.int32, device=self.device)
+        B.kvc_evict_rank_select(self.cfg, self.st, seg_offsets, budget, nseg, protect_tail_blocks,
+                                self.evict_count, selected, self.ws, flags=flags)
+        return self.evict_count, selected
+
+    def compact_rank(self, evict_rows=None, flags=0):
+        B.kvc_compact_rank(self.cfg, self.st, self.evict_count if evict_rows is None else evict_rows,
+                           self.blocks_freed, self.ws, flags=flags)
+        return self.blocks_freed
