@@ -84,6 +84,8 @@ def main():
     ap.add_argument("--chunk", type=int, default=0, help="decode chunk tokens (0 = library default)")
     ap.add_argument("--cpu-heads", type=int, default=1024, help="head instances timed on the CPU oracle (0 = skip)")
     ap.add_argument("--workload", default="llama8b", choices=["llama8b", "llama70b"])
+    ap.add_argument("--evict-mode", default="block", choices=["block", "rank"],
+                    help="block: physical blocks by summed metric; rank: the paper's rank-block schedule")
     ap.add_argument("--uniform", action="store_true", help="diagnostic: every head holds prompt/rho KVs")
     ap.add_argument("--no-metric", action="store_true", help="diagnostic: decode without metric accumulation")
     ap.add_argument("--per-layer-steps", type=int, default=4,
@@ -159,11 +161,17 @@ def main():
         if args.evict_every > 0 and (i + 1) % args.evict_every == 0:
             e = [ev() for _ in range(4)]
             e[0].record()
-            sess.metric_reduce()
-            e[1].record()
-            sess.evict_select(budget, flags=B.KVC_ASYNC)
-            e[2].record()
-            sess.compact(flags=B.KVC_ASYNC)
+            if args.evict_mode == "block":
+                sess.metric_reduce()
+                e[1].record()
+                sess.evict_select(budget, flags=B.KVC_ASYNC)
+                e[2].record()
+                sess.compact(flags=B.KVC_ASYNC)
+            else:
+                e[1].record()
+                sess.evict_rank_select(budget, flags=B.KVC_ASYNC)
+                e[2].record()
+                sess.compact_rank(flags=B.KVC_ASYNC)
             e[3].record()
             if timed:
                 evict_events.append(e)
@@ -263,7 +271,7 @@ def main():
     evict = None
     if evict_events:
         r = np.array([[e[j].elapsed_time(e[j + 1]) for j in range(3)] for e in evict_events])
-        evict = {"rounds": len(evict_events), "reduce_ms": float(r[:, 0].mean()),
+        evict = {"mode": args.evict_mode, "rounds": len(evict_events), "reduce_ms": float(r[:, 0].mean()),
                  "select_ms": float(r[:, 1].mean()), "compact_ms": float(r[:, 2].mean()),
                  "total_ms": float(r.sum(1).mean()), "blocks_per_round": int(budget.sum().item())}
 
@@ -277,6 +285,7 @@ def main():
         "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": name, "placement": args.placement, "evict_every": args.evict_every,
+                   "evict_mode": args.evict_mode,
                    "chunk_tokens": chunk_T, "head_instances": G,
                    "mean_kvs_per_step": float(kv_per_step.mean())},
         "frac_of_hbm_peak": value / HBM_PEAK_GBS,

@@ -124,3 +124,51 @@ def test_llama8b_shape_sampled_parity_and_invariants():
     assert ids.numel() == torch.unique(ids).numel()
     assert int((sess.cache.free_map == 0).sum()) == ids.numel()
     assert int(sess.cache.free_map[ids].sum()) == 0
+
+
+def test_llama8b_shape_rank_schedule_on_one_sequence():
+    """The rank-block schedule at full size; one whole sequence (256 head instances) is copied
+    back and scheduled by the oracle from the same metrics."""
+    from paper_2410_00161_amd.session import KvcSession
+    print("[case] full-size llama8b rank-block eviction", flush=True)
+    shape, ctx, seed = W.llama8b_decode(extra_tokens=64)
+    dev = torch.device("cuda:0")
+    cache = W.make_cache(shape, ctx, seed, device=dev, placement="fragmented", init_metric="prefill")
+    sess = KvcSession(cache, device=dev)
+    del cache
+    G, b = shape.G, shape.block_size
+    per = shape.num_layers * shape.num_kv_heads
+    q = W.make_query(shape, seed, 0, dev)
+    sess.paged_decode(q)                                   # metrics as a decode step leaves them
+    ctx_now = sess.cache.ctx_len.reshape(G).long()
+    nb = (ctx_now + b - 1) // b
+    budget = (nb.reshape(shape.num_seqs, -1).sum(1) // 8).to(torch.int32)
+    s = 11
+    heads = list(range(s * per, (s + 1) * per))
+    small, _ = W.gather_heads(sess.cache, heads)
+    one = oracle_state(small)
+    st = O.State(1, shape.num_layers, shape.num_kv_heads, shape.group_size, shape.head_dim, b, one.N,
+                 one.max_blocks, one.k_cache, one.v_cache, one.metric, one.pos, one.block_table, one.ctx_len,
+                 one.free_map)
+    rows, sel = sess.evict_rank_select(budget)
+    torch.cuda.synchronize()
+    assert torch.equal(sel.cpu(), budget.cpu()) and int(rows.sum()) == int(budget.sum())
+    rows_w, masks_w, sel_w = O.rank_schedule(st, [int(budget[s])], metric=small.metric.numpy())
+    np.testing.assert_array_equal(rows[s * per:(s + 1) * per].cpu().numpy(), rows_w)
+    free_before = int(sess.cache.free_map.sum())
+    freed = int(sess.compact_rank().item())
+    assert freed == int(budget.sum()) == int(sess.cache.free_map.sum()) - free_before
+    O.compact_slots(st, masks_w)
+    post, _ = W.gather_heads(sess.cache, heads)
+    stp = oracle_state(post)
+    np.testing.assert_array_equal(stp.lens(), st.lens())
+    for i in range(len(heads)):
+        n, o = O.slots_of(st, i)
+        n2, o2 = O.slots_of(stp, i)
+        np.testing.assert_array_equal(stp.k_cache[n2, o2], st.k_cache[n, o])
+        np.testing.assert_array_equal(stp.metric[n2, o2], st.metric[n, o])
+        np.testing.assert_array_equal(stp.pos[n2, o2], st.pos[n, o])
+    ctx_after = sess.cache.ctx_len.reshape(G).long()
+    changed = rows.long() > 0
+    assert bool((ctx_after[changed] % b == 0).all())        # heads that lost rows end on whole blocks
+    assert torch.equal((ctx_after + b - 1) // b, nb - rows.long())
