@@ -1,0 +1,137 @@
+"""Scaled-down versions of the other benchmark configurations, every step compared with the
+oracle: periodic eviction inside a decode loop at high compression, prefill-end compression
+from an observation window, and the group-of-8 shape."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import kvc_oracle as O
+from paper_2410_00161_amd import binding as B
+from paper_2410_00161_amd import workloads as W
+from helpers import oracle_state, check_allocator_invariants
+from test_gpu_parity import session, say, assert_state_equal, TOL
+
+pytestmark = pytest.mark.gpu
+
+
+def evict_round(sess, st, frac, mode):
+    """One compression round on both sides, the oracle ranking the device's metric."""
+    torch.cuda.synchronize()
+    st.metric = sess.cache.metric.cpu().numpy().astype(np.float64)   # identical metric inputs
+    nb = -(-st.lens() // st.b)
+    budget = torch.tensor((nb.reshape(st.S, -1).sum(1) * frac).astype(np.int64), dtype=torch.int32)
+    if mode == "block":
+        key = sess.metric_reduce()
+        want_key, _ = O.block_keys(st)
+        np.testing.assert_array_equal(key.cpu().numpy().view(np.uint32), want_key.view(np.uint32))
+        flag_w, count_w, sel_w = O.evict_select(st, want_key, budget.numpy())
+        flag, count, sel = sess.evict_select(budget)
+        np.testing.assert_array_equal(flag.cpu().numpy(), flag_w)
+        freed_w = O.compact(st, flag_w, count_w)
+        freed = int(sess.compact().item())
+    else:
+        rows_w, masks_w, sel_w = O.rank_schedule(st, budget.numpy())
+        rows, sel = sess.evict_rank_select(budget)
+        np.testing.assert_array_equal(rows.cpu().numpy(), rows_w)
+        freed_w = O.compact_slots(st, masks_w)
+        freed = int(sess.compact_rank().item())
+    np.testing.assert_array_equal(sel.cpu().numpy(), sel_w)
+    assert freed == freed_w
+    return freed
+
+
+@pytest.mark.parametrize("mode", ["block", "rank"])
+def test_periodic_eviction_in_a_decode_loop_at_high_compression(mode):
+    """Many short, unevenly compressed heads; every 4th step the cheapest 10 % of each
+    sequence's blocks go and the cache is compacted into the freed blocks."""
+    say("periodic eviction", mode)
+    shape, ctx, seed = W.small_mixed(91, S=6, Lyr=2, Hk=4, r=4, d=128, L=2048, rho=32.0, extra_blocks=3)
+    cache = W.make_cache(shape, ctx, seed, placement="fragmented", init_metric="prefill")
+    st = oracle_state(cache)
+    sess = session(cache)
+    total_freed = 0
+    for step in range(12):
+        k, v = W.make_new_kv(shape, seed, step)
+        q = W.make_query(shape, seed, step)
+        O.append(st, k.double().numpy(), v.double().numpy())
+        want = O.paged_decode(st, q.double().numpy())
+        sess.append(k.to(sess.device), v.to(sess.device))
+        out = sess.paged_decode(q.to(sess.device))
+        torch.cuda.synchronize()
+        np.testing.assert_allclose(out.cpu().numpy(), want, rtol=0, atol=TOL)
+        np.testing.assert_allclose(sess.cache.metric.cpu().numpy()[st.free_map == 0],
+                                   st.metric[st.free_map == 0], rtol=0, atol=TOL)
+        if (step + 1) % 4 == 0:
+            total_freed += evict_round(sess, st, 0.10, mode)
+            assert_state_equal(sess, st)
+            check_allocator_invariants(st)
+    assert total_freed > 0
+
+
+def test_prefill_end_compression_from_an_observation_window():
+    """A full-length prompt; the metric is the squared attention of the last w prompt queries
+    (query i sees keys 0 .. L-w+i), gathered by running the decode once per window query with
+    the context lengths set accordingly; then eviction to 8x and a few decode steps."""
+    say("observation window -> 8x")
+    S, Lyr, Hk, r, d, b, L, w = 1, 4, 2, 4, 128, 16, 768, 8
+    ctx = W.uniform_lengths(S * Lyr * Hk, L)
+    N = W.pool_size(ctx, b, 1.2, 16)
+    shape = W.Shape(S, Lyr, Hk, r, d, b, N, L // b + 2, "bf16")
+    cache = W.make_cache(shape, ctx, 95)
+    st = oracle_state(cache)
+    sess = session(cache)
+    for i in range(w):
+        seen = L - w + i + 1
+        st.ctx_len[...] = seen
+        sess.cache.ctx_len.fill_(seen)
+        q = W.make_query(shape, 95, i)
+        want = O.paged_decode(st, q.double().numpy())
+        out = sess.paged_decode(q.to(sess.device))
+        torch.cuda.synchronize()
+        np.testing.assert_allclose(out.cpu().numpy(), want, rtol=0, atol=TOL)
+    # the window metric equals the column sums of the w x L squared attention matrix
+    np.testing.assert_allclose(sess.cache.metric.cpu().numpy(), st.metric, rtol=0, atol=TOL)
+    g0 = 3
+    n, o = O.slots_of(st, g0)
+    assert (st.metric[n, o][-1] > 0) and st.metric[n, o][: L - w].min() >= 0
+    for mode in ("block",):
+        freed = evict_round(sess, st, 7.0 / 8.0, mode)
+        assert freed > 0
+    assert_state_equal(sess, st)
+    kept = st.lens().sum()
+    assert kept <= L * S * Lyr * Hk / 8 + S * Lyr * Hk * b * 2     # about 8x, up to block rounding
+    assert len(set(st.lens().tolist())) > 1                         # rates differ per head
+    for step in range(6):
+        k, v = W.make_new_kv(shape, 95, 100 + step)
+        q = W.make_query(shape, 95, 100 + step)
+        O.append(st, k.double().numpy(), v.double().numpy())
+        want = O.paged_decode(st, q.double().numpy())
+        sess.append(k.to(sess.device), v.to(sess.device))
+        out = sess.paged_decode(q.to(sess.device))
+        torch.cuda.synchronize()
+        np.testing.assert_allclose(out.cpu().numpy(), want, rtol=0, atol=TOL)
+    assert_state_equal(sess, st)
+
+
+def test_group_of_eight_shape_with_long_heads():
+    """70B-like grouping (8 query heads per KV head) with heads long enough to be split into
+    several chunks at the default chunk length, then a rank-block round."""
+    say("r = 8, long heads")
+    shape, ctx, seed = W.small_mixed(97, S=2, Lyr=2, Hk=2, r=8, d=128, L=6000, rho=2.0, extra_blocks=2)
+    cache = W.make_cache(shape, ctx, seed, placement="fragmented", init_metric="prefill")
+    st = oracle_state(cache)
+    sess = session(cache)
+    assert int(ctx.max()) > B.kvc_get_decode_chunk(sess.cfg) > 0
+    for step in range(2):
+        k, v = W.make_new_kv(shape, seed, step)
+        q = W.make_query(shape, seed, step)
+        O.append(st, k.double().numpy(), v.double().numpy())
+        want = O.paged_decode(st, q.double().numpy())
+        sess.append(k.to(sess.device), v.to(sess.device))
+        out = sess.paged_decode(q.to(sess.device))
+        torch.cuda.synchronize()
+        np.testing.assert_allclose(out.cpu().numpy(), want, rtol=0, atol=TOL)
+    np.testing.assert_allclose(sess.cache.metric.cpu().numpy()[st.free_map == 0],
+                               st.metric[st.free_map == 0], rtol=0, atol=TOL)
+    evict_round(sess, st, 0.25, "rank")
+    assert_state_equal(sess, st)
