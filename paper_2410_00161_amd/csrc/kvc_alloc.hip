@@ -19,40 +19,25 @@ __device__ __forceinline__ int held_blocks(const int32_t* row, int C, int b, int
   return u;
 }
 
-// mode 0: explicit request counts n[g]; mode 1: append (one block when full and
-// the layer is in range); mode 2: drop counts n[g] (must be <= held).
-__global__ void __launch_bounds__(256) count_kernel(Dims D, const int32_t* __restrict__ table,
-                                                    const int32_t* __restrict__ ctx,
-                                                    const int32_t* __restrict__ n, int mode, int l0,
-                                                    int l1, int32_t* __restrict__ held,
-                                                    int32_t* __restrict__ req,
-                                                    int32_t* __restrict__ header) {
-  int g = blockIdx.x * 256 + threadIdx.x;
+// Drop counts n[g] of kvc_block_free: blocks held per head instance, checked request.
+__global__ void __launch_bounds__(256) count_drop_kernel(Dims D, const int32_t* __restrict__ table,
+                                                         const int32_t* __restrict__ ctx,
+                                                         const int32_t* __restrict__ n,
+                                                         int32_t* __restrict__ held,
+                                                         int32_t* __restrict__ req,
+                                                         int32_t* __restrict__ header) {
+  const int g = blockIdx.x * 256 + threadIdx.x;
   if (g >= D.G) return;
-  const int C = ctx[g];
-  const int h = held_blocks(table + (size_t)g * D.maxb, C, D.b, D.maxb);
+  const int h = held_blocks(table + (size_t)g * D.maxb, ctx[g], D.b, D.maxb);
   held[g] = h;
-  int want = 0, bits = 0;
-  if (mode == 0) {
-    want = n[g];
-    if (want < 0) { bits |= EB_ARG; want = 0; }
-    else if (h + want > D.maxb) bits |= EB_TABLE;
-  } else if (mode == 1) {
-    int l = (g / D.Hk) % D.Lyr;
-    if (l >= l0 && l < l1 && C == h * D.b) {
-      want = 1;
-      if (h + 1 > D.maxb) bits |= EB_TABLE;
-    }
-  } else {
-    want = n[g];
-    if (want < 0 || want > h) { bits |= EB_ARG; want = 0; }
-  }
+  int want = n[g];
+  if (want < 0 || want > h) { atomicOr(&header[HW_SCRATCH0], EB_ARG); want = 0; }
   req[g] = want;
-  if (bits) atomicOr(&header[HW_SCRATCH0], bits);
 }
 
-// Launch 1 of an allocation: workgroups [0, gb) count requests per head instance (as
-// count_kernel), workgroups [gb, gb + ntiles) count the free blocks of one tile of the map.
+// Launch 1 of an allocation: workgroups [0, gb) count requests per head instance (mode 0:
+// the caller's counts n[g]; mode 1: append, one block when the head's blocks are full and its
+// layer is in range), workgroups [gb, gb + ntiles) count the free blocks of one tile of the map.
 __global__ void __launch_bounds__(256) count_and_free_tiles_kernel(Dims D, const int32_t* __restrict__ table,
                                                                    const int32_t* __restrict__ ctx,
                                                                    const int32_t* __restrict__ n, int mode,
@@ -148,15 +133,6 @@ __global__ void __launch_bounds__(1024) alloc_scan_kernel(Dims D, const int32_t*
     header[HW_SCRATCH0] = 0;
   }
 }
-
-struct ReqFn {
-  const int32_t* req;
-  __device__ int operator()(int i) const { return req[i]; }
-};
-struct FreeFn {
-  const uint8_t* free_map;
-  __device__ int operator()(int i) const { return free_map[i] != 0; }
-};
 
 // Third phase of the scan over the free map, fused with the hand-out: the free block of
 // rank k (ascending id) goes to owner[k], the head instance g with off[g] <= k < off[g + 1],
@@ -302,8 +278,8 @@ int kvc_block_free(const kvc_config* cfg, const kvc_state* st, const int32_t* n_
   const int gb = (D.G + 255) / 256;
   hipLaunchKernelGGL(zero_words_kernel, dim3(1), dim3(64), 0, s, W.header + HW_FREED, 1);
   KVC_LAUNCH_CHECK();
-  hipLaunchKernelGGL(count_kernel, dim3(gb), dim3(256), 0, s, D, st->block_table, st->ctx_len, n_drop, 2,
-                     0, D.Lyr, W.held, W.off_b, W.header);
+  hipLaunchKernelGGL(count_drop_kernel, dim3(gb), dim3(256), 0, s, D, st->block_table, st->ctx_len, n_drop,
+                     W.held, W.off_b, W.header);
   KVC_LAUNCH_CHECK();
   hipLaunchKernelGGL(resolve_kernel, dim3(1), dim3(64), 0, s, W.header, 0);
   KVC_LAUNCH_CHECK();
