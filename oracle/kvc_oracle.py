@@ -18,6 +18,9 @@ Where each function comes from (sections of the KV-Compress paper):
                                Attention Metric" (sum of A^2; L1 = sum of A),
                                "Continual Compression" (decode queries add
                                into the metrics already held)
+  window_metric .............. Preliminaries "KV Cache Compression" (observation
+                               window, max-pooling), Method "Metric Calculation"
+                               (KVC-w: squared before summation)
   alloc / free / append ...... "Block Layout and Parallel Allocation" (flat
                                length-N allocation tensor, per-head context
                                lengths)
@@ -217,6 +220,53 @@ def paged_decode(st: State, q, accumulate_metric=True, metric_mode="L2",
                 if accumulate_metric:
                     st.metric[n, o] += inc
     return out
+
+
+def window_metric(st: State, q_win, w, pool=7, metric_mode="L2", accumulate=False,
+                  layer_begin=0, layer_end=None):
+    """Prefill-end metric from an observation window (Preliminaries, "KV Cache
+    Compression": sum over the last w prompt queries; Method, "Query Group
+    Compression": also over the query heads of the group; "Metric Calculation":
+    squared attention, KVC-w; max-pooling over the sequence with size `pool`).
+
+    q_win [S, Lyr, Hq, w, d]: window query i of a head with C KVs sits at
+    position C - w + i and attends to keys 0 .. C - w + i (causal).  raw[j] =
+    sum over the group's heads and the window queries of p^2 (p with "L1").
+    Keys before the window get the maximum of raw over the pool//2 neighbours
+    on either side, the neighbourhood cut at the ends of that prefix; keys
+    inside the window keep raw.  The result replaces the metric of the head's
+    slots (or is added when accumulate)."""
+    layer_end = st.Lyr if layer_end is None else layer_end
+    Hq = st.Hk * st.r
+    q_win = np.asarray(q_win, dtype=np.float64).reshape(st.S, st.Lyr, Hq, w, st.d)
+    half = pool // 2
+    for s in range(st.S):
+        for l in range(layer_begin, layer_end):
+            for h in range(st.Hk):
+                g = (s * st.Lyr + l) * st.Hk + h
+                C = int(st.lens()[g])
+                if C == 0:
+                    continue
+                n, o = slots_of(st, g)
+                K = st.k_cache[n, o]
+                raw = np.zeros(C)
+                for hq in range(st.r * h, st.r * (h + 1)):
+                    for i in range(w):
+                        last = C - w + i
+                        if last < 0:
+                            continue
+                        sc = (K[:last + 1] @ q_win[s, l, hq, i]) / np.sqrt(float(st.d))
+                        e = np.exp(sc - sc.max())
+                        p = e / e.sum()
+                        raw[:last + 1] += p * p if metric_mode == "L2" else p
+                P = max(0, C - w)
+                pooled = raw.copy()
+                for j in range(P):
+                    pooled[j] = raw[max(0, j - half):min(P, j + half + 1)].max()
+                if accumulate:
+                    st.metric[n, o] += pooled
+                else:
+                    st.metric[n, o] = pooled
 
 
 # --------------------------------------------------------------------------

@@ -1,0 +1,86 @@
+"""Pins for the oracle's observation-window metric."""
+import math
+
+import numpy as np
+import torch
+import torch.nn.functional as F
+
+from oracle import kvc_oracle as O
+from paper_2410_00161_amd import workloads as W
+from helpers import oracle_state
+from test_oracle_pins import _one_head_state, _metric_of
+
+
+def test_window_metric_equals_library_softmax_and_max_pool():
+    rng = np.random.default_rng(2)
+    r, d, b, C, w, pool = 2, 16, 4, 37, 5, 7
+    K = rng.standard_normal((C, d)); V = np.zeros((C, d))
+    Q = rng.standard_normal((r, w, d))
+    st = _one_head_state(K, V, r, b)
+    n, o = O.slots_of(st, 0)
+    st.metric[n, o] = 123.0                                  # replaced, not added to
+    O.window_metric(st, Q.reshape(1, 1, r, w, d), w, pool)
+    # library route: masked scores -> softmax -> square -> sum over queries and heads -> max_pool1d
+    scores = torch.from_numpy(np.einsum("hwd,cd->hwc", Q, K)) / math.sqrt(d)
+    pos = torch.arange(C).view(1, 1, C)
+    qpos = (C - w + torch.arange(w)).view(1, w, 1)
+    scores = scores.masked_fill(pos > qpos, float("-inf"))
+    A = torch.softmax(scores, dim=-1)
+    raw = (A ** 2).sum(dim=(0, 1))
+    prefix = raw[:C - w].view(1, 1, -1)
+    pooled = F.max_pool1d(prefix, kernel_size=pool, stride=1, padding=pool // 2).view(-1)
+    want = torch.cat([pooled, raw[C - w:]]).numpy()
+    np.testing.assert_allclose(_metric_of(st), want, rtol=1e-12, atol=1e-15)
+    # pool = 1 leaves the raw sums; L1 sums probabilities: every window query's row sums to 1
+    st = _one_head_state(K, V, r, b)
+    O.window_metric(st, Q.reshape(1, 1, r, w, d), w, 1, metric_mode="L1")
+    np.testing.assert_allclose(_metric_of(st), A.sum(dim=(0, 1)).numpy(), rtol=1e-12)
+    assert abs(_metric_of(st).sum() - r * w) < 1e-9
+    # accumulate adds to what is there
+    st2 = _one_head_state(K, V, r, b)
+    n, o = O.slots_of(st2, 0); st2.metric[n, o] = 1.0
+    O.window_metric(st2, Q.reshape(1, 1, r, w, d), w, 1, metric_mode="L1", accumulate=True)
+    np.testing.assert_allclose(_metric_of(st2), 1.0 + A.sum(dim=(0, 1)).numpy(), rtol=1e-12)
+
+
+def test_window_metric_closed_form_and_short_heads():
+    r, d, b, C, w = 3, 8, 4, 10, 4
+    K = np.tile(np.random.default_rng(0).standard_normal(d), (C, 1))     # identical keys: uniform rows
+    st = _one_head_state(K, np.zeros((C, d)), r, b)
+    O.window_metric(st, np.ones((1, 1, r, w, d)), w, 1)
+    want = np.zeros(C)
+    for i in range(w):
+        vis = C - w + i + 1
+        want[:vis] += r / vis ** 2
+    np.testing.assert_allclose(_metric_of(st), want, rtol=1e-12)
+    # a head shorter than the window: queries that would sit before position 0 do not exist
+    C2 = 3
+    st = _one_head_state(K[:C2], np.zeros((C2, d)), r, b)
+    O.window_metric(st, np.ones((1, 1, r, w, d)), w, 7)
+    want = np.zeros(C2)
+    for i in range(w):
+        last = C2 - w + i
+        if last >= 0:
+            want[:last + 1] += r / (last + 1) ** 2
+    np.testing.assert_allclose(_metric_of(st), want, rtol=1e-12)
+
+
+def test_window_metric_equals_one_decode_per_window_query():
+    """The same numbers as running the decode once per window query with the context length
+    that query sees (how a caller without the window kernel gathers the metric)."""
+    shape, ctx, seed = W.small_mixed(5, S=2, Lyr=1, Hk=2, r=2, d=32, L=90, b=4)
+    cache = W.make_cache(shape, ctx, seed)
+    st = oracle_state(cache); st2 = oracle_state(cache)
+    w = 6
+    rng = np.random.default_rng(1)
+    qw = rng.standard_normal((shape.num_seqs, shape.num_layers, shape.num_q_heads, w, shape.head_dim))
+    O.window_metric(st, qw, w, 1)
+    lens = st2.lens().copy()
+    st2.metric[...] = 0.0
+    for i in range(w):
+        st2.ctx_len[...] = np.maximum(lens - w + i + 1, 0).reshape(st2.ctx_len.shape)
+        O.paged_decode(st2, qw[:, :, :, i, :])
+    st2.ctx_len[...] = lens.reshape(st2.ctx_len.shape)
+    for g in range(st.G):
+        n, o = O.slots_of(st, g)
+        np.testing.assert_allclose(st.metric[n, o], st2.metric[n, o], rtol=1e-10, atol=1e-14)
