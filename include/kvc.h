@@ -211,6 +211,22 @@ int kvc_evict_rank_select(const kvc_config* cfg, const kvc_state* st, const int3
 int kvc_compact_rank(const kvc_config* cfg, const kvc_state* st, const int32_t* evict_rows,
                      int64_t* blocks_freed, void* ws, void* stream, int flags);
 
+/* Prefill-end metric from an observation window (Preliminaries "KV Cache Compression":
+ * attention summed over the last w prompt queries, max-pooled over the sequence; "Query Group
+ * Compression": and over the query heads of the group; "Metric Calculation", KVC-w: squared
+ * before summation, p itself with KVC_L1) over layers [layer_begin, layer_end).
+ * q_win [S, Lyr, Hq, w, d] kv_dtype: window query i of a head with C = ctx_len KVs sits at
+ * position C - w + i and attends to keys 0 .. C - w + i; queries that would sit before
+ * position 0 are ignored.  raw[j] = sum over the r heads and w queries of p^2.  Keys before
+ * the window get max(raw[j - pool/2 .. j + pool/2]) with the range cut at the ends of that
+ * prefix (pool odd; 1 = no pooling); keys inside the window keep raw.  The result replaces
+ * metric[slot] of every KV of those layers, or is added to it when accumulate != 0.
+ * Runs on the matrix cores; covers kv_dtype = KVC_BF16, head_dim = 128, block_size in
+ * {16, 32, 64}, w * group_size <= 256, else KVC_ERR_UNSUPPORTED (such callers can gather the
+ * same sums with one kvc_paged_decode per window query).  Asynchronous.            */
+int kvc_window_metric(const kvc_config* cfg, const kvc_state* st, const void* q_win, int w, int pool,
+                      int accumulate, int layer_begin, int layer_end, void* ws, void* stream);
+
 /* Tuning knob of kvc_paged_decode: tokens handled by one workgroup before a
  * head is split across workgroups.  0 restores the default.  Process-wide,
  * host only.  KVC_ERR_ARG unless 0 or a multiple of 64 in [64, 8192].          */

@@ -18,7 +18,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(ROOT, "_build")
 LIB = os.path.join(HERE, "libkvc.so")
 
-SOURCES = ["kvc_api.hip", "kvc_alloc.hip", "kvc_decode.hip", "kvc_evict.hip", "kvc_rank.hip"]
+SOURCES = ["kvc_api.hip", "kvc_alloc.hip", "kvc_decode.hip", "kvc_evict.hip", "kvc_rank.hip", "kvc_window.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
@@ -48,7 +48,7 @@ def build_library(verbose: bool = True) -> str:
         if verbose:
             print(f"[kvc build] {src}", flush=True)
 
-    with ThreadPoolExecutor(max_workers=min(5, len(SOURCES))) as ex:
+    with ThreadPoolExecutor(max_workers=min(6, len(SOURCES))) as ex:
         list(ex.map(one, zip(SOURCES, objs)))
     _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC",
           "-o", LIB, *objs])

@@ -1,0 +1,190 @@
+// Work list shared by the kernels that walk every head instance in chunks of T tokens (the
+// decode and the observation-window metric): item records built on the device from the
+// context lengths, ordered by size class, plus the cross-lane helpers those kernels use.
+#pragma once
+
+#include "kvc_common.h"
+
+namespace kvc {
+
+struct DecodeItem {   // 32 bytes
+  int g;        // head instance
+  int t0;       // first token of the chunk
+  int n_tok;    // tokens in the chunk
+  int nch;      // chunks of the head
+  int pbase;    // first partial-result slot of the head (heads of more than one chunk)
+  int pad[3];
+};
+
+struct DecodeArgs {
+  Dims D;
+  const char* kc;
+  const char* vc;
+  float* metric;
+  const int32_t* table;
+  const int32_t* ctx;
+  const char* q;
+  float* out;
+  int l0, nl, gsel;       // first layer, layer count, head instances selected
+  int accumulate, T;      // metric on/off, chunk tokens
+  int log2b;              // block size is a power of two on the tiled path
+  int cap;                // item records and partial-result slots the workspace holds
+  int all_partials;       // give every head a partial-result slot range, not only split heads
+  DecodeItem* items;
+  float* part_ml;
+  float* part_acc;
+  float* stash;
+  int32_t* header;
+  float scale_log2;       // log2(e) / sqrt(d)
+};
+
+__device__ __forceinline__ int sel_to_g(const Dims& D, int l0, int nl, int gi) {
+  const int s = gi / (nl * D.Hk);
+  const int l = l0 + (gi / D.Hk) % nl;
+  const int h = gi % D.Hk;
+  return (s * D.Lyr + l) * D.Hk + h;
+}
+
+// Work items are ordered by size class, largest first, so that the short ones fill the end
+// of the launch.  Class 0 = a full chunk of T tokens; class k >= 1 = (T / 2^k, T / 2^(k-1)).
+__device__ __forceinline__ int size_class(int n, int T) {
+  if (n >= T) return 0;
+  int cls = 1, t = T >> 1;
+  while (n <= t && cls < 15) { ++cls; t >>= 1; }
+  return cls;
+}
+
+// Items are stored largest class first.  Workgroup i does not take item i: the small classes
+// (at most T / 2^(kSmallClass-1) tokens, latency-bound work) are dealt out from the back of
+// the list in proportion, so that at any time the chip holds a mix of long streaming items
+// and short ones, and the two ends meet at the medium sizes.
+constexpr int kSmallClass = 5;
+__device__ __forceinline__ int item_of_workgroup(int i, int total, int small) {
+  const long long s0 = (long long)i * small / total;
+  const long long s1 = (long long)(i + 1) * small / total;
+  return s1 > s0 ? total - 1 - (int)s0 : i - (int)s0;
+}
+
+// Pass 1 of the work list: number of items per size class.
+static __global__ void __launch_bounds__(256) decode_count_kernel(DecodeArgs A) {
+  __shared__ int bins[16];
+  if (threadIdx.x < 16) bins[threadIdx.x] = 0;
+  __syncthreads();
+  const int gi = blockIdx.x * 256 + threadIdx.x;
+  if (gi < A.gsel) {
+    const int C = A.ctx[sel_to_g(A.D, A.l0, A.nl, gi)];
+    const int nfull = C / A.T, rem = C - nfull * A.T;
+    if (nfull) atomicAdd(&bins[0], nfull);
+    if (rem) atomicAdd(&bins[size_class(rem, A.T)], 1);
+  }
+  __syncthreads();
+  if (threadIdx.x < 16 && bins[threadIdx.x]) atomicAdd(&A.header[HW_DEC_BINS + threadIdx.x], bins[threadIdx.x]);
+}
+
+// Pass 2: every head instance claims its places and writes its items; a head that holds no
+// KV gets its zero output rows here.  Places are claimed per workgroup (one global atomic
+// per class) and handed out inside it through LDS, so the global counters see few updates.
+static __global__ void __launch_bounds__(256) decode_items_kernel(DecodeArgs A) {
+  __shared__ int base[16], want[17], got[17];
+  const int tid = threadIdx.x;
+  if (tid < 17) want[tid] = 0;
+  if (tid == 0) {
+    int run = 0;
+    int small = 0;
+    for (int k = 0; k < 16; ++k) {
+      const int c = A.header[HW_DEC_BINS + k];
+      base[k] = run;
+      run += c;
+      if (k >= kSmallClass) small += c;
+    }
+    if (blockIdx.x == 0) { A.header[HW_TOTAL_ITEMS] = run; A.header[HW_SMALL_ITEMS] = small; }
+  }
+  __syncthreads();
+  const int gi = blockIdx.x * 256 + tid;
+  const int T = A.T;
+  int g = 0, C = 0, nfull = 0, rem = 0, nch = 0, cls = 0;
+  int my_full = 0, my_rem = 0, my_p = 0;  // offsets inside this workgroup's claims
+  if (gi < A.gsel) {
+    g = sel_to_g(A.D, A.l0, A.nl, gi);
+    C = A.ctx[g];
+    nfull = C / T;
+    rem = C - nfull * T;
+    nch = nfull + (rem ? 1 : 0);
+    cls = rem ? size_class(rem, T) : 0;
+    if (nfull) my_full = atomicAdd(&want[0], nfull);
+    if (rem) my_rem = atomicAdd(&want[cls], 1);       // class 0 never holds a remainder
+    if (nch > 1 || (A.all_partials && nch > 0)) my_p = atomicAdd(&want[16], nch);
+  }
+  __syncthreads();
+  if (tid < 17 && want[tid])
+    got[tid] = atomicAdd(&A.header[tid < 16 ? HW_DEC_CUR + tid : HW_DEC_PCUR], want[tid]);
+  __syncthreads();
+  if (gi >= A.gsel) return;
+  if (C == 0) {
+    if (A.out) {
+      float* o = A.out + (size_t)g * A.D.r * A.D.d;
+      for (int i = 0; i < A.D.r * A.D.d; ++i) o[i] = 0.0f;
+    }
+    return;
+  }
+  const int pbase = (nch > 1 || A.all_partials) ? got[16] + my_p : 0;
+  // the counters start from zero, so these bounds hold by construction; a workspace that was
+  // never reset is the one way to break them, and then nothing is written
+  if (pbase < 0 || pbase + nch > A.cap) return;
+  if (nfull) {
+    const int at = base[0] + got[0] + my_full;
+    if (at < 0 || at + nfull > A.cap) return;
+    for (int c = 0; c < nfull; ++c) {
+      DecodeItem it = {g, c * T, T, nch, pbase, {0, 0, 0}};
+      A.items[at + c] = it;
+    }
+  }
+  if (rem) {
+    const int at = base[cls] + got[cls] + my_rem;
+    if (at < 0 || at >= A.cap) return;
+    DecodeItem it = {g, nfull * T, rem, nch, pbase, {0, 0, 0}};
+    A.items[at] = it;
+  }
+}
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, true));
+}
+// Value held by lane (l ^ MASK).  Masks below 16 stay inside a row of 16 lanes and use
+// data-parallel primitives: quad permutes for 1 and 2, a quad reverse followed by a half-row
+// mirror for 4 (i ^ 3 ^ 7 = i ^ 4), a rotation by 8 for 8.
+template <int MASK>
+__device__ __forceinline__ float lane_xor(float v) {
+  if constexpr (MASK == 1) return dpp_move<0xB1>(v);
+  else if constexpr (MASK == 2) return dpp_move<0x4E>(v);
+  else if constexpr (MASK == 4) return dpp_move<0x141>(dpp_move<0x1B>(v));
+  else if constexpr (MASK == 8) return dpp_move<0x128>(v);
+  else return __shfl_xor(v, MASK);
+}
+
+template <int N, int MASK>
+struct Butterfly {
+  // Sums v[0..N) across the lanes that differ in the bits at and below MASK, halving the
+  // number of live values at each step while more than one is left.
+  static __device__ __forceinline__ void run(float* v, int lane) {
+    if constexpr (MASK >= 1) {
+      if constexpr (N > 1) {
+        constexpr int H = N / 2;
+        const bool up = (lane & MASK) != 0;
+#pragma unroll
+        for (int i = 0; i < H; ++i) {
+          const float keep = up ? v[H + i] : v[i];
+          const float send = up ? v[i] : v[H + i];
+          v[i] = keep + lane_xor<MASK>(send);
+        }
+        Butterfly<H, MASK / 2>::run(v, lane);
+      } else {
+        v[0] += lane_xor<MASK>(v[0]);
+        Butterfly<1, MASK / 2>::run(v, lane);
+      }
+    }
+  }
+};
+
+}  // namespace kvc

@@ -87,3 +87,8 @@ class KvcSession:
         B.kvc_compact_rank(self.cfg, self.st, self.evict_count if evict_rows is None else evict_rows,
                            self.blocks_freed, self.ws, flags=flags)
         return self.blocks_freed
+
+    def window_metric(self, q_win, w, pool=7, accumulate=False, layer_begin=0, layer_end=None):
+        layer_end = self.shape.num_layers if layer_end is None else layer_end
+        B.kvc_window_metric(self.cfg, self.st, q_win, w, pool, accumulate, layer_begin, layer_end, self.ws)
+        return self.cache.metric

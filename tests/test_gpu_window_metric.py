@@ -1,0 +1,92 @@
+"""GPU parity of the observation-window metric (matrix-core kernels) against the oracle."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import kvc_oracle as O
+from paper_2410_00161_amd import binding as B
+from paper_2410_00161_amd import workloads as W
+from helpers import oracle_state
+from test_gpu_parity import session, say, TOL
+
+pytestmark = pytest.mark.gpu
+
+CASES = [
+    ("w8_r4", dict(r=4, L=2600, rho=1.5), 8, 7, B.KVC_L2),
+    ("w32_r4", dict(r=4, L=1500, rho=1.5), 32, 7, B.KVC_L2),
+    ("w8_r8_b32", dict(r=8, L=1300, rho=2.0, b=32), 8, 7, B.KVC_L2),
+    ("w32_r8", dict(r=8, L=1100, rho=2.0), 32, 5, B.KVC_L2),
+    ("w5_r2_L1_nopool", dict(r=2, L=1200, rho=2.0), 5, 1, B.KVC_L1),
+    ("w16_r1", dict(r=1, L=1200, rho=2.0), 16, 3, B.KVC_L2),
+]
+
+
+def window_queries(shape, w, seed, device):
+    g = torch.Generator(device=device).manual_seed(seed)
+    q = torch.randn((shape.num_seqs, shape.num_layers, shape.num_q_heads, w, shape.head_dim),
+                    generator=g, device=device, dtype=torch.float32)
+    return q.to(shape.torch_dtype)
+
+
+@pytest.mark.parametrize("name,kw,w,pool,mode", CASES, ids=[c[0] for c in CASES])
+def test_window_metric_matches_oracle(name, kw, w, pool, mode):
+    say("window metric", name)
+    shape, ctx, seed = W.small_mixed(101, S=2, Lyr=2, Hk=2, d=128, kv_dtype="bf16", **kw)
+    ctx[1] = 0            # no KV at all
+    ctx[2] = 3            # shorter than the window
+    ctx[3] = w            # exactly the window
+    ctx[4] = 1024 + 16    # just past one chunk
+    cache = W.make_cache(shape, ctx, seed, placement="fragmented", init_metric="prefill")
+    st0 = oracle_state(cache)
+    real = torch.zeros_like(cache.metric, dtype=torch.bool)
+    for g in range(st0.G):
+        n, o = O.slots_of(st0, g)
+        real[torch.from_numpy(n), torch.from_numpy(o)] = True
+    cache.k_cache[~real] = float("nan")          # slots that hold no KV must never leak in
+    st = oracle_state(cache)
+    qw = window_queries(shape, w, seed, "cpu")
+    O.window_metric(st, qw.double().numpy(), w, pool, "L2" if mode == B.KVC_L2 else "L1")
+    sess = session(cache, mode)
+    sess.window_metric(qw.to(sess.device), w, pool)
+    torch.cuda.synchronize()
+    m = sess.cache.metric.cpu().numpy().astype(np.float64)
+    rm = real.numpy()
+    assert np.isfinite(m[rm]).all()
+    np.testing.assert_allclose(m[rm], st.metric[rm], rtol=0, atol=TOL)
+    np.testing.assert_array_equal(m[~rm], cache.metric.numpy().astype(np.float64)[~rm])
+    # relative check too: the sums span orders of magnitude
+    big = rm & (st.metric > 1e-3)
+    np.testing.assert_allclose(m[big], st.metric[big], rtol=2e-2, atol=0)
+
+
+def test_window_metric_layer_range_accumulate_and_unsupported():
+    say("window metric layer range")
+    shape, ctx, seed = W.small_mixed(103, S=2, Lyr=3, Hk=2, r=4, d=128, kv_dtype="bf16", L=500, rho=1.5)
+    cache = W.make_cache(shape, ctx, seed, init_metric="prefill")
+    st = oracle_state(cache)
+    w = 8
+    qw = window_queries(shape, w, seed, "cpu")
+    sess = session(cache)
+    before = sess.cache.metric.clone()
+    O.window_metric(st, qw.double().numpy(), w, 7, accumulate=True, layer_begin=1, layer_end=2)
+    sess.window_metric(qw.to(sess.device), w, 7, accumulate=True, layer_begin=1, layer_end=2)
+    torch.cuda.synchronize()
+    m = sess.cache.metric.cpu().numpy()
+    np.testing.assert_allclose(m[st.free_map == 0], st.metric[st.free_map == 0], rtol=0, atol=TOL)
+    for g in range(st.G):          # other layers untouched, bit for bit
+        if (g // st.Hk) % st.Lyr != 1:
+            n, o = O.slots_of(st, g)
+            np.testing.assert_array_equal(m[n, o], before.cpu().numpy()[n, o])
+    # then the eviction path runs on it as on any metric
+    key = sess.metric_reduce()
+    want_key, _ = O.block_keys(st, sess.cache.metric.cpu().numpy())
+    np.testing.assert_array_equal(key.cpu().numpy().view(np.uint32), want_key.view(np.uint32))
+    # shapes the matrix-core kernels do not cover are refused, nothing is touched
+    shape2, ctx2, _ = W.small_mixed(104, S=1, Lyr=1, Hk=2, r=2, d=64, kv_dtype="f32", L=100)
+    sess2 = session(W.make_cache(shape2, ctx2, 104))
+    with pytest.raises(B.KvcError) as e:
+        sess2.window_metric(torch.zeros((1, 1, 4, 4, 64), device=sess2.device), 4, 7)
+    assert e.value.code == B.KVC_ERR_UNSUPPORTED
+    with pytest.raises(B.KvcError) as e:
+        sess.window_metric(qw.to(sess.device), w, 4)          # even pool size
+    assert e.value.code == B.KVC_ERR_ARG
