@@ -227,6 +227,18 @@ int kvc_compact_rank(const kvc_config* cfg, const kvc_state* st, const int32_t* 
 int kvc_window_metric(const kvc_config* cfg, const kvc_state* st, const void* q_win, int w, int pool,
                       int accumulate, int layer_begin, int layer_end, void* ws, void* stream);
 
+/* Building block of the all-queries metric ("Metric Calculation", KVC-full: squared attention
+ * aggregated over all observed queries, one block of queries at a time, leaving out the first v
+ * queries after each key).  q_blk [S, Lyr, Hq, w, d]: query i sits at position first_pos + i
+ * (the same for every head; a prefill), attends to keys 0 .. min(position, ctx_len - 1), and
+ * adds p^2 (p with KVC_L1) to metric[slot of key j] only when j <= position - exclude.
+ * Always accumulates; no pooling.  Calling it for consecutive blocks of a prompt's queries
+ * builds M_full[j] = sum over i >= j + v and the group's heads of A_ij^2.  Shapes and errors as
+ * kvc_window_metric.  Asynchronous.                                               */
+int kvc_query_block_metric(const kvc_config* cfg, const kvc_state* st, const void* q_blk, int w,
+                           int first_pos, int exclude, int layer_begin, int layer_end, void* ws,
+                           void* stream);
+
 /* Tuning knob of kvc_paged_decode: tokens handled by one workgroup before a
  * head is split across workgroups.  0 restores the default.  Process-wide,
  * host only.  KVC_ERR_ARG unless 0 or a multiple of 64 in [64, 8192].          */

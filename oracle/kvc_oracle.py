@@ -269,6 +269,39 @@ def window_metric(st: State, q_win, w, pool=7, metric_mode="L2", accumulate=Fals
                     st.metric[n, o] = pooled
 
 
+def query_block_metric(st: State, q_blk, w, first_pos, exclude=0, metric_mode="L2",
+                       layer_begin=0, layer_end=None):
+    """One block of the all-queries metric ("Metric Calculation", KVC-full):
+    query i of the block sits at position first_pos + i, attends causally to
+    keys 0 .. min(position, C - 1), and adds p^2 to the metric of key j only
+    when position - j >= exclude (the first `exclude` queries after a key are
+    left out).  Always accumulates."""
+    layer_end = st.Lyr if layer_end is None else layer_end
+    Hq = st.Hk * st.r
+    q_blk = np.asarray(q_blk, dtype=np.float64).reshape(st.S, st.Lyr, Hq, w, st.d)
+    for s in range(st.S):
+        for l in range(layer_begin, layer_end):
+            for h in range(st.Hk):
+                g = (s * st.Lyr + l) * st.Hk + h
+                C = int(st.lens()[g])
+                if C == 0:
+                    continue
+                n, o = slots_of(st, g)
+                K = st.k_cache[n, o]
+                inc = np.zeros(C)
+                for hq in range(st.r * h, st.r * (h + 1)):
+                    for i in range(w):
+                        pos = first_pos + i
+                        last = min(pos, C - 1)
+                        sc = (K[:last + 1] @ q_blk[s, l, hq, i]) / np.sqrt(float(st.d))
+                        e = np.exp(sc - sc.max())
+                        p = e / e.sum()
+                        cnt = min(last, pos - exclude) + 1
+                        if cnt > 0:
+                            inc[:cnt] += (p * p if metric_mode == "L2" else p)[:cnt]
+                st.metric[n, o] += inc
+
+
 # --------------------------------------------------------------------------
 # block keys and selection
 # --------------------------------------------------------------------------

@@ -25,7 +25,7 @@ EXPORTS = [
     "kvc_workspace_bytes", "kvc_validate", "kvc_status_string", "kvc_workspace_reset",
     "kvc_poll_status", "kvc_block_alloc", "kvc_block_free", "kvc_append", "kvc_paged_decode",
     "kvc_metric_reduce", "kvc_evict_select", "kvc_compact", "kvc_set_decode_chunk",
-    "kvc_get_decode_chunk", "kvc_evict_rank_select", "kvc_compact_rank", "kvc_window_metric",
+    "kvc_get_decode_chunk", "kvc_evict_rank_select", "kvc_compact_rank", "kvc_window_metric", "kvc_query_block_metric",
     "kvc_profile_begin", "kvc_profile_enable", "kvc_profile_collect", "kvc_stream_read_probe", "kvc_stream_rw_probe",
 ]
 
@@ -78,6 +78,7 @@ def lib() -> C.CDLL:
         L.kvc_evict_rank_select.argtypes = [cfgp, stp, P, P, I, I, P, P, P, P, I]
         L.kvc_compact_rank.argtypes = [cfgp, stp, P, P, P, P, I]
         L.kvc_window_metric.argtypes = [cfgp, stp, P, I, I, I, I, I, P, P]
+        L.kvc_query_block_metric.argtypes = [cfgp, stp, P, I, I, I, I, I, P, P]
         L.kvc_get_decode_chunk.argtypes = [cfgp, C.POINTER(C.c_int)]
         L.kvc_profile_begin.argtypes = [I]
         L.kvc_profile_enable.argtypes = [I]
@@ -270,3 +271,9 @@ def kvc_compact_rank(cfg, st, evict_rows, blocks_freed, ws, stream=None, flags=0
 def kvc_window_metric(cfg, st, q_win, w, pool, accumulate, layer_begin, layer_end, ws, stream=None):
     _check(lib().kvc_window_metric(C.byref(cfg), C.byref(st), _ptr(q_win), int(w), int(pool), int(accumulate),
                                    layer_begin, layer_end, _ptr(ws), _stream(stream)), "kvc_window_metric")
+
+
+def kvc_query_block_metric(cfg, st, q_blk, w, first_pos, exclude, layer_begin, layer_end, ws, stream=None):
+    _check(lib().kvc_query_block_metric(C.byref(cfg), C.byref(st), _ptr(q_blk), int(w), int(first_pos),
+                                        int(exclude), layer_begin, layer_end, _ptr(ws), _stream(stream)),
+           "kvc_query_block_metric")

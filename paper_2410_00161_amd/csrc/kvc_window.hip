@@ -34,6 +34,8 @@ struct WindowArgs {
   int w, rows;         // window queries; query rows = w * r
   int pool;            // max-pool size over the sequence
   int add;             // add to the metric instead of replacing it
+  int first_pos;       // position of query 0, the same for every head; -1 = the head's C - w
+  int exclude;         // a query at position x adds to key j only when j <= x - exclude
   float* part;         // [partial slot][rows_pad][2]
   float* raw;          // [N * b] un-pooled sums, by physical slot
 };
@@ -112,18 +114,20 @@ __global__ void __launch_bounds__(kWinThreads) window_stats_kernel(WindowArgs W)
   // over column tiles stays a loop (registers: one K tile and one Q tile at a time)
   float2* my_st = s_st + (size_t)wv * NT * 64 + lane;
   for (int ct = 0; ct < NT; ++ct) my_st[ct * 64] = make_float2(-INFINITY, 0.0f);
-  const int first_free = C - W.w;  // keys up to here are visible to every window query
-  for (int tt = wv * 64; tt < n_tok; tt += 64 * kWinWaves) {
+  const int first_free = W.first_pos >= 0 ? W.first_pos : C - W.w;  // query i sits at first_free + i
+  const int free_lim = min(first_free, C - 1);   // keys up to here are visible to every query
+  const bool dead = t0 > min(first_free + W.w - 1, C - 1);  // no query of the block sees this chunk
+  for (int tt = wv * 64; tt < n_tok && !dead; tt += 64 * kWinWaves) {
     uint4 k[4][4];
     load_tile(W, s_tab, tt, n_tok, lane, k);
-    const bool masked = t0 + tt + 63 > first_free;
+    const bool masked = t0 + tt + 63 > free_lim;
 #pragma unroll 1
     for (int ct = 0; ct < NT; ++ct) {
       uint4 q[4];
 #pragma unroll
       for (int kk = 0; kk < 4; ++kk) q[kk] = s_q[(ct * 4 + kk) * 64 + lane];
       const int rho = ct * 16 + (lane & 15);
-      const int last_vis = first_free + rho / A.D.r;  // window query i sees keys 0 .. C - w + i
+      const int last_vis = min(first_free + rho / A.D.r, C - 1);  // query i sees keys 0 .. its position
       const float2 old = my_st[ct * 64];
       float s[16];
       float mx = old.x;
@@ -219,12 +223,19 @@ __global__ void __launch_bounds__(kWinThreads) window_sum_kernel(WindowArgs W) {
     s_ml[rho * 2 + 1] = (rho < W.rows && ll > 0.0f) ? 1.0f / ll : 0.0f;
   }
   __syncthreads();
-  const int first_free = C - W.w;
+  const int first_free = W.first_pos >= 0 ? W.first_pos : C - W.w;
+  const int free_lim = min(first_free, C - 1) - W.exclude;   // keys up to here count for every query
+  const bool dead = t0 > min(first_free + W.w - 1, C - 1) - W.exclude;  // the chunk gets nothing
   const bool l2 = A.D.mode == KVC_L2;
+  if (dead) {
+    for (int t = tid; t < n_tok; t += kWinThreads)
+      if (t0 + t < C) W.raw[((size_t)s_tab[t >> lb] << lb) + (t & (b - 1))] = 0.0f;
+    return;
+  }
   for (int tt = wv * 64; tt < n_tok; tt += 64 * kWinWaves) {
     uint4 k[4][4];
     load_tile(W, s_tab, tt, n_tok, lane, k);
-    const bool masked = t0 + tt + 63 > first_free;
+    const bool masked = t0 + tt + 63 > free_lim;
     float tok[16];
 #pragma unroll
     for (int e = 0; e < 16; ++e) tok[e] = 0.0f;
@@ -234,7 +245,7 @@ __global__ void __launch_bounds__(kWinThreads) window_sum_kernel(WindowArgs W) {
 #pragma unroll
       for (int kk = 0; kk < 4; ++kk) q[kk] = s_q[(ct * 4 + kk) * 64 + lane];
       const int rho = ct * 16 + (lane & 15);
-      const int last_vis = first_free + rho / A.D.r;
+      const int last_vis = min(first_free + rho / A.D.r, C - 1) - W.exclude;
       const float m_row = s_ml[rho * 2], il_row = s_ml[rho * 2 + 1];
 #pragma unroll
       for (int tg = 0; tg < 4; ++tg) {
@@ -272,7 +283,7 @@ __global__ void __launch_bounds__(256) window_pool_kernel(WindowArgs W) {
   const int C = A.ctx[g];
   const int b = A.D.b;
   const int32_t* row = A.table + (size_t)g * A.D.maxb;
-  const int P = max(0, C - W.w), half = W.pool / 2;
+  const int P = W.first_pos >= 0 ? 0 : max(0, C - W.w), half = W.pool / 2;
   for (int j = threadIdx.x; j < C; j += 256) {
     const size_t slot = (size_t)row[j / b] * b + (j % b);
     float v = W.raw[slot];
@@ -307,14 +318,15 @@ using namespace kvc;
 
 extern "C" {
 
-int kvc_window_metric(const kvc_config* cfg, const kvc_state* st, const void* q_win, int w, int pool,
-                      int accumulate, int layer_begin, int layer_end, void* ws, void* stream) {
+static int window_common(const kvc_config* cfg, const kvc_state* st, const void* q_win, int w, int pool,
+                         int accumulate, int first_pos, int exclude, int layer_begin, int layer_end, void* ws,
+                         void* stream) {
   int rc = validate(cfg, st);
   if (rc != KVC_OK) return rc;
   if (!q_win || !ws || ((uintptr_t)ws & 255) || ((uintptr_t)q_win & 15)) return KVC_ERR_ARG;
   Dims D = dims_of(cfg);
   if (layer_begin < 0 || layer_end > D.Lyr || layer_begin >= layer_end) return KVC_ERR_ARG;
-  if (w <= 0 || pool <= 0 || (pool & 1) == 0) return KVC_ERR_ARG;
+  if (w <= 0 || pool <= 0 || (pool & 1) == 0 || exclude < 0) return KVC_ERR_ARG;
   // the matrix-core kernels cover bf16, d = 128, blocks of a multiple of 16 tokens, up to 256 query rows
   if (D.dtype != KVC_BF16 || D.d != 128 || D.b % 16 != 0 || 64 % D.b != 0) return KVC_ERR_UNSUPPORTED;
   const int rows = w * D.r;
@@ -339,6 +351,7 @@ int kvc_window_metric(const kvc_config* cfg, const kvc_state* st, const void* q_
   A.header = Wk.header;
   A.scale_log2 = (float)(1.4426950408889634 / 11.313708498984761);  // log2(e) / sqrt(128)
   W.w = w; W.rows = rows; W.pool = pool; W.add = accumulate != 0;
+  W.first_pos = first_pos; W.exclude = exclude;
   W.part = Wk.part_acc; W.raw = Wk.stash;
   // a head that holds no KV has no output here: the item kernel's zero rows must not be written
   hipLaunchKernelGGL(decode_count_kernel, dim3((A.gsel + 255) / 256), dim3(256), 0, s, A);
@@ -359,6 +372,17 @@ int kvc_window_metric(const kvc_config* cfg, const kvc_state* st, const void* q_
   hipLaunchKernelGGL(window_pool_kernel, dim3(A.gsel), dim3(256), 0, s, W);
   KVC_LAUNCH_CHECK();
   return KVC_OK;
+}
+
+int kvc_window_metric(const kvc_config* cfg, const kvc_state* st, const void* q_win, int w, int pool,
+                      int accumulate, int layer_begin, int layer_end, void* ws, void* stream) {
+  return window_common(cfg, st, q_win, w, pool, accumulate, -1, 0, layer_begin, layer_end, ws, stream);
+}
+
+int kvc_query_block_metric(const kvc_config* cfg, const kvc_state* st, const void* q_blk, int w, int first_pos,
+                           int exclude, int layer_begin, int layer_end, void* ws, void* stream) {
+  if (first_pos < 0) return KVC_ERR_ARG;
+  return window_common(cfg, st, q_blk, w, 1, 1, first_pos, exclude, layer_begin, layer_end, ws, stream);
 }
 
 }  // extern "C"

@@ -92,3 +92,8 @@ class KvcSession:
         layer_end = self.shape.num_layers if layer_end is None else layer_end
         B.kvc_window_metric(self.cfg, self.st, q_win, w, pool, accumulate, layer_begin, layer_end, self.ws)
         return self.cache.metric
+
+    def query_block_metric(self, q_blk, w, first_pos, exclude=0, layer_begin=0, layer_end=None):
+        layer_end = self.shape.num_layers if layer_end is None else layer_end
+        B.kvc_query_block_metric(self.cfg, self.st, q_blk, w, first_pos, exclude, layer_begin, layer_end, self.ws)
+        return self.cache.metric

@@ -90,3 +90,29 @@ def test_window_metric_layer_range_accumulate_and_unsupported():
     with pytest.raises(B.KvcError) as e:
         sess.window_metric(qw.to(sess.device), w, 4)          # even pool size
     assert e.value.code == B.KVC_ERR_ARG
+
+
+def test_query_block_metric_builds_kvc_full():
+    """All-queries metric with an excluded window, one block of queries at a time, against the
+    oracle's block function (itself pinned to the dense definition)."""
+    say("query block metric (all queries, excluded window)")
+    S, Lyr, Hk, r, d, b, L, v, blk = 1, 2, 2, 4, 128, 16, 1400, 10, 64
+    ctx = W.uniform_lengths(S * Lyr * Hk, L)
+    shape = W.Shape(S, Lyr, Hk, r, d, b, W.pool_size(ctx, b, 1.1, 4), L // b + 2, "bf16")
+    cache = W.make_cache(shape, ctx, 107, placement="fragmented")
+    st = oracle_state(cache)
+    sess = session(cache)
+    g = torch.Generator().manual_seed(107)
+    Q = torch.randn((S, Lyr, Hk * r, L, d), generator=g).to(torch.bfloat16)
+    for start in list(range(0, L, blk)):
+        w = min(blk, L - start)
+        qb = Q[:, :, :, start:start + w].contiguous()
+        if start % (5 * blk) == 0 or start + blk >= L:          # the oracle on a subset of blocks ...
+            O.query_block_metric(st, qb.double().numpy(), w, start, v)
+            sess.query_block_metric(qb.to(sess.device), w, start, v)
+    torch.cuda.synchronize()
+    m = sess.cache.metric.cpu().numpy().astype(np.float64)
+    used = st.free_map == 0
+    np.testing.assert_allclose(m[used], st.metric[used], rtol=0, atol=TOL)
+    big = used[:, None] & (st.metric > 1e-3)
+    np.testing.assert_allclose(m[big], st.metric[big], rtol=2e-2, atol=0)

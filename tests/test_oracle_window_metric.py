@@ -84,3 +84,22 @@ def test_window_metric_equals_one_decode_per_window_query():
     for g in range(st.G):
         n, o = O.slots_of(st, g)
         np.testing.assert_allclose(st.metric[n, o], st2.metric[n, o], rtol=1e-10, atol=1e-14)
+
+
+def test_query_blocks_build_the_all_queries_metric_with_excluded_window():
+    """Calling the block function over a prompt's queries in blocks gives
+    M_full[j] = sum over i >= j + v of A_ij^2 (summed over the group), A the causal attention
+    matrix of the prompt, computed here with a library softmax."""
+    rng = np.random.default_rng(4)
+    r, d, b, L, v, blk = 2, 16, 4, 29, 3, 8
+    K = rng.standard_normal((L, d)); Q = rng.standard_normal((r, L, d))
+    st = _one_head_state(K, np.zeros((L, d)), r, b)
+    for start in range(0, L, blk):
+        w = min(blk, L - start)
+        O.query_block_metric(st, Q[:, start:start + w].reshape(1, 1, r, w, d), w, start, v)
+    scores = torch.from_numpy(np.einsum("hid,jd->hij", Q, K)) / math.sqrt(d)
+    i = torch.arange(L).view(1, L, 1); j = torch.arange(L).view(1, 1, L)
+    A = torch.softmax(scores.masked_fill(j > i, float("-inf")), dim=-1)
+    want = ((A ** 2) * (i >= j + v)).sum(dim=(0, 1)).numpy()
+    np.testing.assert_allclose(_metric_of(st), want, rtol=1e-12, atol=1e-15)
+    assert (want[L - v:] == 0).all()              # the last v keys have no query far enough away
