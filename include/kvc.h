@@ -124,6 +124,29 @@ int kvc_block_alloc(const kvc_config* cfg, const kvc_state* st, const int32_t* n
 int kvc_block_free(const kvc_config* cfg, const kvc_state* st, const int32_t* n_drop,
                    int64_t* blocks_freed, void* ws, void* stream, int flags);
 
+/* Scheduling counts, computed in parallel on the device ("Block Layout and Parallel
+ * Allocation": required additional blocks of running sequences from the context lengths;
+ * blocks a preemption would free, per sequence).  needed [S] i32 (device, may be NULL): blocks
+ * sequence s must get before the next decode step over layers [layer_begin, layer_end) - one
+ * per head instance whose blocks are all full.  held [S] i32 (device, may be NULL): blocks it
+ * holds over all layers.  Asynchronous.                                           */
+int kvc_count_blocks(const kvc_config* cfg, const kvc_state* st, int layer_begin, int layer_end,
+                     int32_t* needed, int32_t* held, void* ws, void* stream);
+
+/* Prefill scheduling (same section: blocks follow from the token length alone, every head of
+ * a sequence starts with the same number).  seq_tokens [S] i32 (device): every head instance
+ * of a sequence with tokens > 0 is brought up to ceil(tokens / b) blocks and its ctx_len set
+ * to tokens (the caller then writes the keys and values); sequences with 0 are left alone.
+ * Errors and order rule as kvc_block_alloc.  Synchronises unless KVC_ASYNC.       */
+int kvc_prefill_alloc(const kvc_config* cfg, const kvc_state* st, const int32_t* seq_tokens,
+                      void* ws, void* stream, int flags);
+
+/* Preemption: every block of the sequences with seq_mask[s] != 0 (device [S] u8) goes back to
+ * free_map, their table rows become -1 and their ctx_len 0.  blocks_freed: host int64
+ * out-param, may be NULL.  Synchronises unless KVC_ASYNC or blocks_freed is NULL.  */
+int kvc_preempt(const kvc_config* cfg, const kvc_state* st, const uint8_t* seq_mask,
+                int64_t* blocks_freed, void* ws, void* stream, int flags);
+
 /* Appends one new token's key and value to every head instance of layers
  * [layer_begin, layer_end).  k_new, v_new [S, Lyr, Hk, d] kv_dtype.  A head
  * whose blocks are all full first takes one block (same order rule as

@@ -152,6 +152,48 @@ def block_free(st: State, n_drop) -> int:
     return int(n_drop.sum())
 
 
+def count_blocks(st: State, layer_begin=0, layer_end=None):
+    """Per sequence: blocks needed before the next decode step over the chosen
+    layers (one per head instance whose blocks are all full) and blocks held."""
+    layer_end = st.Lyr if layer_end is None else layer_end
+    needed = np.zeros(st.S, dtype=np.int64); held = np.zeros(st.S, dtype=np.int64)
+    for g in range(st.G):
+        s, l = g // (st.Lyr * st.Hk), (g // st.Hk) % st.Lyr
+        h = num_blocks_held(st, g)
+        held[s] += h
+        if layer_begin <= l < layer_end and st.lens()[g] == h * st.b:
+            needed[s] += 1
+    return needed, held
+
+
+def prefill_alloc(st: State, seq_tokens) -> None:
+    """Every head of a sequence with tokens > 0 is brought up to ceil(tokens / b)
+    blocks and its length set to tokens."""
+    seq_tokens = np.asarray(seq_tokens, dtype=np.int64).reshape(st.S)
+    if (seq_tokens < 0).any():
+        raise OracleError(ERR_ARG)
+    want = np.zeros(st.G, dtype=np.int64)
+    for g in range(st.G):
+        t = seq_tokens[g // (st.Lyr * st.Hk)]
+        if t > 0:
+            want[g] = max(0, -(-t // st.b) - num_blocks_held(st, g))
+    block_alloc(st, want)
+    for g in range(st.G):
+        t = seq_tokens[g // (st.Lyr * st.Hk)]
+        if t > 0:
+            st.lens()[g] = t
+
+
+def preempt(st: State, seq_mask) -> int:
+    """Frees every block of the masked sequences; returns blocks freed."""
+    seq_mask = np.asarray(seq_mask).reshape(st.S)
+    drop = np.zeros(st.G, dtype=np.int64)
+    for g in range(st.G):
+        if seq_mask[g // (st.Lyr * st.Hk)]:
+            drop[g] = num_blocks_held(st, g)
+    return block_free(st, drop)
+
+
 def append(st: State, k_new, v_new, new_pos=None, layer_begin=0, layer_end=None) -> None:
     """Store one new token's k, v for every head instance of the chosen layers."""
     layer_end = st.Lyr if layer_end is None else layer_end

@@ -25,7 +25,7 @@ EXPORTS = [
     "kvc_workspace_bytes", "kvc_validate", "kvc_status_string", "kvc_workspace_reset",
     "kvc_poll_status", "kvc_block_alloc", "kvc_block_free", "kvc_append", "kvc_paged_decode",
     "kvc_metric_reduce", "kvc_evict_select", "kvc_compact", "kvc_set_decode_chunk",
-    "kvc_get_decode_chunk", "kvc_evict_rank_select", "kvc_compact_rank", "kvc_window_metric", "kvc_query_block_metric",
+    "kvc_get_decode_chunk", "kvc_evict_rank_select", "kvc_compact_rank", "kvc_window_metric", "kvc_query_block_metric", "kvc_count_blocks", "kvc_prefill_alloc", "kvc_preempt",
     "kvc_profile_begin", "kvc_profile_enable", "kvc_profile_collect", "kvc_stream_read_probe", "kvc_stream_rw_probe",
 ]
 
@@ -77,6 +77,9 @@ def lib() -> C.CDLL:
         L.kvc_set_decode_chunk.argtypes = [I]
         L.kvc_evict_rank_select.argtypes = [cfgp, stp, P, P, I, I, P, P, P, P, I]
         L.kvc_compact_rank.argtypes = [cfgp, stp, P, P, P, P, I]
+        L.kvc_count_blocks.argtypes = [cfgp, stp, I, I, P, P, P, P]
+        L.kvc_prefill_alloc.argtypes = [cfgp, stp, P, P, P, I]
+        L.kvc_preempt.argtypes = [cfgp, stp, P, C.POINTER(C.c_int64), P, P, I]
         L.kvc_window_metric.argtypes = [cfgp, stp, P, I, I, I, I, I, P, P]
         L.kvc_query_block_metric.argtypes = [cfgp, stp, P, I, I, I, I, I, P, P]
         L.kvc_get_decode_chunk.argtypes = [cfgp, C.POINTER(C.c_int)]
@@ -277,3 +280,22 @@ def kvc_query_block_metric(cfg, st, q_blk, w, first_pos, exclude, layer_begin, l
     _check(lib().kvc_query_block_metric(C.byref(cfg), C.byref(st), _ptr(q_blk), int(w), int(first_pos),
                                         int(exclude), layer_begin, layer_end, _ptr(ws), _stream(stream)),
            "kvc_query_block_metric")
+
+
+def kvc_count_blocks(cfg, st, layer_begin, layer_end, needed, held, ws, stream=None):
+    _check(lib().kvc_count_blocks(C.byref(cfg), C.byref(st), layer_begin, layer_end,
+                                  _ptr(needed, torch.int32) if needed is not None else None,
+                                  _ptr(held, torch.int32) if held is not None else None, _ptr(ws),
+                                  _stream(stream)), "kvc_count_blocks")
+
+
+def kvc_prefill_alloc(cfg, st, seq_tokens, ws, stream=None, flags=0):
+    _check(lib().kvc_prefill_alloc(C.byref(cfg), C.byref(st), _ptr(seq_tokens, torch.int32), _ptr(ws),
+                                   _stream(stream), flags), "kvc_prefill_alloc")
+
+
+def kvc_preempt(cfg, st, seq_mask, ws, stream=None, flags=0) -> int:
+    freed = C.c_int64(0)
+    _check(lib().kvc_preempt(C.byref(cfg), C.byref(st), _ptr(seq_mask, torch.uint8), C.byref(freed), _ptr(ws),
+                             _stream(stream), flags), "kvc_preempt")
+    return freed.value

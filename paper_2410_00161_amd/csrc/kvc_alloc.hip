@@ -248,6 +248,81 @@ static int alloc_common(const Dims& D, const kvc_state* st, const Workspace& W, 
   return KVC_OK;
 }
 
+// ---- scheduling helpers: counts per sequence, prefill allocation, preemption --------------
+
+// needed[s] = blocks sequence s must get before its next decode step (head instances of the
+// chosen layers whose blocks are all full); held[s] = blocks it holds over all layers.
+__global__ void __launch_bounds__(256) count_blocks_kernel(Dims D, const int32_t* __restrict__ table,
+                                                           const int32_t* __restrict__ ctx, int l0, int l1,
+                                                           int32_t* __restrict__ needed,
+                                                           int32_t* __restrict__ held_out) {
+  const int g = blockIdx.x * 256 + threadIdx.x;
+  const bool in = g < D.G;
+  const int gg = in ? g : D.G - 1;
+  const int s = gg / (D.Lyr * D.Hk), l = (gg / D.Hk) % D.Lyr;
+  const int C = ctx[gg];
+  const int h = held_blocks(table + (size_t)gg * D.maxb, C, D.b, D.maxb);
+  int need = in && l >= l0 && l < l1 && C == h * D.b;
+  int hh = in ? h : 0;
+  // one atomic per wavefront when all its lanes belong to one sequence
+  const int s0 = __builtin_amdgcn_readfirstlane(s);
+  if (__all(s == s0)) {
+    need = wave_sum_i(need);
+    hh = wave_sum_i(hh);
+    if ((threadIdx.x & 63) == 0) {
+      if (needed && need) atomicAdd(&needed[s0], need);
+      if (held_out && hh) atomicAdd(&held_out[s0], hh);
+    }
+  } else if (in) {
+    if (needed && need) atomicAdd(&needed[s], need);
+    if (held_out && hh) atomicAdd(&held_out[s], hh);
+  }
+}
+
+// Requests of a prefill: every head of sequence s wants ceil(tokens[s] / b) blocks in all.
+__global__ void __launch_bounds__(256) prefill_want_kernel(Dims D, const int32_t* __restrict__ table,
+                                                           const int32_t* __restrict__ ctx,
+                                                           const int32_t* __restrict__ seq_tokens,
+                                                           int32_t* __restrict__ n_new,
+                                                           int32_t* __restrict__ header) {
+  const int g = blockIdx.x * 256 + threadIdx.x;
+  if (g >= D.G) return;
+  const int t = seq_tokens[g / (D.Lyr * D.Hk)];
+  int want = 0;
+  if (t < 0) atomicOr(&header[HW_SCRATCH0], EB_ARG);
+  else if (t > 0) {
+    const int h = held_blocks(table + (size_t)g * D.maxb, ctx[g], D.b, D.maxb);
+    want = max(0, (t + D.b - 1) / D.b - h);
+  }
+  n_new[g] = want;
+}
+
+__global__ void __launch_bounds__(256) prefill_len_kernel(Dims D, const int32_t* __restrict__ seq_tokens,
+                                                          int32_t* __restrict__ ctx,
+                                                          const int32_t* __restrict__ header) {
+  if (header[HW_STATUS] != KVC_OK) return;
+  const int g = blockIdx.x * 256 + threadIdx.x;
+  if (g >= D.G) return;
+  const int t = seq_tokens[g / (D.Lyr * D.Hk)];
+  if (t > 0) ctx[g] = t;
+}
+
+__global__ void __launch_bounds__(256) preempt_kernel(Dims D, int32_t* __restrict__ table,
+                                                      int32_t* __restrict__ ctx, uint8_t* __restrict__ free_map,
+                                                      const uint8_t* __restrict__ seq_mask,
+                                                      int32_t* __restrict__ header) {
+  const int g = blockIdx.x * 256 + threadIdx.x;
+  int n = 0;
+  if (g < D.G && seq_mask[g / (D.Lyr * D.Hk)]) {
+    int32_t* row = table + (size_t)g * D.maxb;
+    n = held_blocks(row, ctx[g], D.b, D.maxb);
+    for (int u = 0; u < n; ++u) { free_map[row[u]] = 1; row[u] = -1; }
+    ctx[g] = 0;
+  }
+  n = wave_sum_i(n);
+  if ((threadIdx.x & 63) == 0 && n) atomicAdd(&header[HW_FREED], n);
+}
+
 }  // namespace kvc
 
 using namespace kvc;
@@ -317,6 +392,64 @@ int kvc_append(const kvc_config* cfg, const kvc_state* st, const void* k_new, co
                      st->ctx_len, (const char*)k_new, (const char*)v_new, new_pos, W.header);
   KVC_LAUNCH_CHECK();
   return (flags & KVC_ASYNC) ? KVC_OK : finish_sync(W, s);
+}
+
+int kvc_count_blocks(const kvc_config* cfg, const kvc_state* st, int layer_begin, int layer_end,
+                     int32_t* needed, int32_t* held, void* ws, void* stream) {
+  int rc = validate(cfg, st);
+  if (rc != KVC_OK) return rc;
+  (void)ws;
+  Dims D = dims_of(cfg);
+  if (layer_begin < 0 || layer_end > D.Lyr || layer_begin >= layer_end) return KVC_ERR_ARG;
+  if (!needed && !held) return KVC_ERR_ARG;
+  hipStream_t s = (hipStream_t)stream;
+  if (needed) { hipLaunchKernelGGL(zero_words_kernel, dim3((D.S + 63) / 64), dim3(64), 0, s, needed, D.S); KVC_LAUNCH_CHECK(); }
+  if (held) { hipLaunchKernelGGL(zero_words_kernel, dim3((D.S + 63) / 64), dim3(64), 0, s, held, D.S); KVC_LAUNCH_CHECK(); }
+  hipLaunchKernelGGL(count_blocks_kernel, dim3((D.G + 255) / 256), dim3(256), 0, s, D, st->block_table, st->ctx_len,
+                     layer_begin, layer_end, needed, held);
+  KVC_LAUNCH_CHECK();
+  return KVC_OK;
+}
+
+int kvc_prefill_alloc(const kvc_config* cfg, const kvc_state* st, const int32_t* seq_tokens, void* ws,
+                      void* stream, int flags) {
+  int rc = validate(cfg, st);
+  if (rc != KVC_OK) return rc;
+  if (!seq_tokens || !ws || ((uintptr_t)ws & 255)) return KVC_ERR_ARG;
+  Dims D = dims_of(cfg);
+  Workspace W = carve(D, ws);
+  hipStream_t s = (hipStream_t)stream;
+  const int gb = (D.G + 255) / 256;
+  int32_t* n_new = W.flag_scan;  // [G] fits in the [G][maxb] array
+  hipLaunchKernelGGL(prefill_want_kernel, dim3(gb), dim3(256), 0, s, D, st->block_table, st->ctx_len, seq_tokens,
+                     n_new, W.header);
+  KVC_LAUNCH_CHECK();
+  rc = alloc_common(D, st, W, n_new, 0, 0, D.Lyr, s);
+  if (rc != KVC_OK) return rc;
+  hipLaunchKernelGGL(prefill_len_kernel, dim3(gb), dim3(256), 0, s, D, seq_tokens, st->ctx_len, W.header);
+  KVC_LAUNCH_CHECK();
+  return (flags & KVC_ASYNC) ? KVC_OK : finish_sync(W, s);
+}
+
+int kvc_preempt(const kvc_config* cfg, const kvc_state* st, const uint8_t* seq_mask, int64_t* blocks_freed,
+                void* ws, void* stream, int flags) {
+  int rc = validate(cfg, st);
+  if (rc != KVC_OK) return rc;
+  if (!seq_mask || !ws || ((uintptr_t)ws & 255)) return KVC_ERR_ARG;
+  Dims D = dims_of(cfg);
+  Workspace W = carve(D, ws);
+  hipStream_t s = (hipStream_t)stream;
+  hipLaunchKernelGGL(zero_words_kernel, dim3(1), dim3(64), 0, s, W.header + HW_FREED, 1);
+  KVC_LAUNCH_CHECK();
+  hipLaunchKernelGGL(preempt_kernel, dim3((D.G + 255) / 256), dim3(256), 0, s, D, st->block_table, st->ctx_len,
+                     st->free_map, seq_mask, W.header);
+  KVC_LAUNCH_CHECK();
+  if ((flags & KVC_ASYNC) || !blocks_freed) return KVC_OK;
+  int32_t f = 0;
+  rc = read_words(W.header + HW_FREED, &f, 1, s);
+  if (rc != KVC_OK) return rc;
+  *blocks_freed = f;
+  return KVC_OK;
 }
 
 }  // extern "C"

@@ -384,3 +384,38 @@ def test_tiny_reference_config_end_to_end():
         assert (int(sess.cache.free_map.sum()) - free_before) * shape.block_size * shape.head_dim * 4 * 2 \
             == freed * 2 * shape.block_size * shape.head_dim * shape.kv_bytes
         assert_state_equal(sess, st)
+
+
+def test_scheduling_helpers_match_oracle():
+    say("count / prefill alloc / preempt")
+    shape, ctx, seed = W.small_mixed(57, S=5, Lyr=3, Hk=2, L=300, slack=3.0, extra_blocks=6)
+    ctx[6:12] = 0                        # sequence 1 not yet prefetched
+    ctx[0] = 3 * shape.block_size        # a head exactly on a block boundary
+    cache = W.make_cache(shape, ctx, seed, placement="fragmented")
+    st = oracle_state(cache)
+    sess = session(cache)
+    dev = sess.device
+    needed = torch.full((shape.num_seqs,), -7, dtype=torch.int32, device=dev)
+    held = torch.full((shape.num_seqs,), -7, dtype=torch.int32, device=dev)
+    for l0, l1 in ((0, shape.num_layers), (1, 2)):
+        B.kvc_count_blocks(sess.cfg, sess.st, l0, l1, needed, held, sess.ws)
+        torch.cuda.synchronize()
+        nw, hw = O.count_blocks(st, l0, l1)
+        np.testing.assert_array_equal(needed.cpu().numpy(), nw)
+        np.testing.assert_array_equal(held.cpu().numpy(), hw)
+    tokens = torch.tensor([0, 137, 0, 0, 0], dtype=torch.int32)
+    O.prefill_alloc(st, tokens.numpy())
+    B.kvc_prefill_alloc(sess.cfg, sess.st, tokens.to(dev), sess.ws)
+    assert_state_equal(sess, st, kv_exact=False)
+    mask = torch.tensor([1, 0, 0, 1, 0], dtype=torch.uint8)
+    freed_w = O.preempt(st, mask.numpy())
+    assert B.kvc_preempt(sess.cfg, sess.st, mask.to(dev), sess.ws) == freed_w > 0
+    assert_state_equal(sess, st, kv_exact=False)
+    check_allocator_invariants(st)
+    # a prefill that cannot fit leaves everything as it was
+    huge = torch.tensor([0, 0, 0, 10 ** 6, 0], dtype=torch.int32)
+    with pytest.raises(O.OracleError):
+        O.prefill_alloc(st, huge.numpy())
+    with pytest.raises(B.KvcError):
+        B.kvc_prefill_alloc(sess.cfg, sess.st, huge.to(dev), sess.ws)
+    assert_state_equal(sess, st, kv_exact=False)

@@ -469,3 +469,31 @@ def test_compact_rejects_bad_flags_without_touching_state():
         O.compact(st, flag)
     np.testing.assert_array_equal(st.block_table, snap.block_table)
     np.testing.assert_array_equal(st.ctx_len, snap.ctx_len)
+
+
+def test_scheduling_helpers_by_hand():
+    """Two sequences, one layer, two heads, b = 4: counts, prefill allocation and preemption
+    worked out by hand."""
+    S, Lyr, Hk, b, N, maxb = 2, 1, 2, 4, 16, 4
+    table = -np.ones((S * Lyr * Hk, maxb), dtype=np.int64)
+    table[0, :2] = [3, 9]      # seq 0 head 0: 8 KVs, both blocks full
+    table[1, :1] = [5]         # seq 0 head 1: 2 KVs
+    lens = np.array([8, 2, 0, 0])
+    free = np.ones(N, dtype=np.uint8); free[[3, 9, 5]] = 0
+    st = O.State(S, Lyr, Hk, 1, 2, b, N, maxb, np.zeros((N, b, 2)), np.zeros((N, b, 2)), np.zeros((N, b)),
+                 np.zeros((N, b)), table, lens, free)
+    needed, held = O.count_blocks(st)
+    assert list(needed) == [1, 2] and list(held) == [3, 0]     # empty heads need their first block too
+    O.prefill_alloc(st, [0, 9])                                # seq 1: ceil(9/4) = 3 blocks per head
+    assert list(st.lens()) == [8, 2, 9, 9]
+    np.testing.assert_array_equal(st.table()[2, :3], [0, 1, 2])   # lowest free ids, ascending g
+    np.testing.assert_array_equal(st.table()[3, :3], [4, 6, 7])
+    check_allocator_invariants(st)
+    needed, held = O.count_blocks(st)
+    assert list(needed) == [1, 0] and list(held) == [3, 6]
+    assert O.preempt(st, [1, 0]) == 3
+    assert list(st.lens()) == [0, 0, 9, 9] and (st.table()[:2] == -1).all()
+    assert sorted(np.flatnonzero(st.free_map == 0)) == [0, 1, 2, 4, 6, 7]
+    check_allocator_invariants(st)
+    with pytest.raises(O.OracleError):
+        O.prefill_alloc(st, [1000, 0])                         # row too short / pool too small
