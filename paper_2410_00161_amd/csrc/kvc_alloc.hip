@@ -81,6 +81,43 @@ __global__ void __launch_bounds__(256) count_and_free_tiles_kernel(Dims D, const
   if (threadIdx.x == 0) tile_sums[tile] = red[0] + red[1] + red[2] + red[3];
 }
 
+constexpr int kScanRun = 8;                    // elements per thread and tile in alloc_scan_kernel
+constexpr int kScanWide = 1024 * kScanRun;     // elements per tile
+
+// Exclusive scan of n ints in place over one workgroup of 1024 threads: a tile is read with
+// coalesced loads into LDS, every thread scans a run of 8 from there (padded against bank
+// conflicts), one workgroup scan joins the runs.  `visit(i, value, exclusive)` sees every element.
+template <class Visit>
+__device__ __forceinline__ int wide_exclusive_scan(const int32_t* __restrict__ in, int n, int* lds, int* smem,
+                                                   Visit visit) {
+  __shared__ int carry_s;
+  if (threadIdx.x == 0) carry_s = 0;
+  __syncthreads();
+  auto at = [](int i) { return i + (i >> 5); };
+  for (int base = 0; base < n; base += kScanWide) {
+    for (int k = 0; k < kScanRun; ++k) {
+      const int i = k * 1024 + threadIdx.x;
+      lds[at(i)] = (base + i < n) ? in[base + i] : 0;
+    }
+    __syncthreads();
+    int v[kScanRun], sum = 0;
+#pragma unroll
+    for (int k = 0; k < kScanRun; ++k) { v[k] = lds[at(threadIdx.x * kScanRun + k)]; sum += v[k]; }
+    int tot;
+    int ex = block_exclusive_scan<1024>(sum, smem, &tot) + carry_s;
+#pragma unroll
+    for (int k = 0; k < kScanRun; ++k) {
+      const int i = base + threadIdx.x * kScanRun + k;
+      if (i < n) visit(i, v[k], ex);
+      ex += v[k];
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) carry_s += tot;
+    __syncthreads();
+  }
+  return carry_s;
+}
+
 // Launch 2, one workgroup: exclusive scan of the requests (off[g], off[G] = total), the owner
 // of every request (owner[k] = head instance that gets the k-th block), exclusive scan of the
 // free-tile counts, and the status word.
@@ -90,39 +127,18 @@ __global__ void __launch_bounds__(1024) alloc_scan_kernel(Dims D, const int32_t*
                                                           int32_t* __restrict__ tile_sums, int ntiles,
                                                           int32_t* __restrict__ header) {
   __shared__ int smem[1024 / 64 + 1];
-  __shared__ int carry_s;
-  if (threadIdx.x == 0) carry_s = 0;
-  __syncthreads();
-  for (int base = 0; base < D.G; base += 1024) {
-    const int g = base + threadIdx.x;
-    const int v = (g < D.G) ? req[g] : 0;
-    int tot;
-    const int ex = block_exclusive_scan<1024>(v, smem, &tot) + carry_s;
-    if (g < D.G) {
-      off[g] = ex;
-      if (ex + v <= D.N)  // more requests than blocks exist is an error found below
-        for (int i = 0; i < v; ++i) owner[ex + i] = g;
-    }
-    __syncthreads();
-    if (threadIdx.x == 0) carry_s += tot;
-    __syncthreads();
-  }
-  const int total_req = carry_s;
-  __syncthreads();
-  if (threadIdx.x == 0) { off[D.G] = total_req; header[HW_TOTAL_REQ] = total_req; carry_s = 0; }
-  __syncthreads();
-  for (int base = 0; base < ntiles; base += 1024) {
-    const int i = base + threadIdx.x;
-    const int v = (i < ntiles) ? tile_sums[i] : 0;
-    int tot;
-    const int ex = block_exclusive_scan<1024>(v, smem, &tot) + carry_s;
-    if (i < ntiles) tile_sums[i] = ex;
-    __syncthreads();
-    if (threadIdx.x == 0) carry_s += tot;
-    __syncthreads();
-  }
+  __shared__ int lds[kScanWide + kScanWide / 32 + 1];
+  const int N = D.N;
+  const int total_req = wide_exclusive_scan(req, D.G, lds, smem, [&](int g, int v, int ex) {
+    off[g] = ex;
+    if (ex + v <= N)  // more requests than blocks exist is an error found below
+      for (int i = 0; i < v; ++i) owner[ex + i] = g;
+  });
+  const int total_free = wide_exclusive_scan(tile_sums, ntiles, lds, smem,
+                                             [&](int t, int v, int ex) { tile_sums[t] = ex; });
   if (threadIdx.x == 0) {
-    const int total_free = carry_s;
+    off[D.G] = total_req;
+    header[HW_TOTAL_REQ] = total_req;
     header[HW_TOTAL_FREE] = total_free;
     const int bits = header[HW_SCRATCH0];
     int st = KVC_OK;
@@ -191,9 +207,9 @@ __global__ void __launch_bounds__(256) drop_kernel(Dims D, int32_t* __restrict__
   if ((threadIdx.x & 63) == 0 && tot) atomicAdd(&header[HW_FREED], tot);
 }
 
-// One workgroup of 64 threads per head instance: copy the new key and value in
+// One wavefront per head instance (four per workgroup): copy the new key and value in
 // 16-byte pieces, zero the metric, set the logical index, bump the length.
-__global__ void __launch_bounds__(64) append_write_kernel(Dims D, int l0, int l1, char* __restrict__ kc,
+__global__ void __launch_bounds__(256) append_write_kernel(Dims D, int l0, int l1, char* __restrict__ kc,
                                                           char* __restrict__ vc,
                                                           float* __restrict__ metric,
                                                           int32_t* __restrict__ pos,
@@ -205,7 +221,10 @@ __global__ void __launch_bounds__(64) append_write_kernel(Dims D, int l0, int l1
                                                           const int32_t* __restrict__ header) {
   if (header[HW_STATUS] != KVC_OK) return;
   const int nl = l1 - l0;
-  const int idx = blockIdx.x;                 // over S * nl * Hk
+  const int idx = blockIdx.x * 4 + (threadIdx.x >> 6);   // over S * nl * Hk
+  const bool live = idx < D.S * nl * D.Hk;
+  const int lane = threadIdx.x & 63;
+  if (!live) return;   // whole wavefront; no workgroup barrier below
   const int s = idx / (nl * D.Hk);
   const int l = l0 + (idx / D.Hk) % nl;
   const int h = idx % D.Hk;
@@ -216,15 +235,15 @@ __global__ void __launch_bounds__(64) append_write_kernel(Dims D, int l0, int l1
   const size_t row_bytes = (size_t)D.d * (D.dtype == KVC_BF16 ? 2 : 4);
   const size_t slot = (size_t)blk * D.b + o;
   const int pieces = (int)(row_bytes / 16);
-  for (int c = threadIdx.x; c < 2 * pieces; c += 64) {
+  for (int c = lane; c < 2 * pieces; c += 64) {
     const bool is_v = c >= pieces;
     const int cc = is_v ? c - pieces : c;
     const uint4* src = (const uint4*)((is_v ? v_new : k_new) + (size_t)g * row_bytes) + cc;
     uint4* dst = (uint4*)((is_v ? vc : kc) + slot * row_bytes) + cc;
     *dst = *src;
   }
-  __syncthreads();  // every thread has read ctx[g]
-  if (threadIdx.x == 0) {
+  // every lane of the wavefront has read ctx[g] by now (one instruction stream)
+  if (lane == 0) {
     metric[slot] = 0.0f;
     if (pos) pos[slot] = new_pos ? new_pos[s] : C;
     ctx[g] = C + 1;
@@ -387,7 +406,7 @@ int kvc_append(const kvc_config* cfg, const kvc_state* st, const void* k_new, co
   rc = alloc_common(D, st, W, nullptr, 1, layer_begin, layer_end, s);
   if (rc != KVC_OK) return rc;
   const int nsel = D.S * (layer_end - layer_begin) * D.Hk;
-  hipLaunchKernelGGL(append_write_kernel, dim3(nsel), dim3(64), 0, s, D, layer_begin, layer_end,
+  hipLaunchKernelGGL(append_write_kernel, dim3((nsel + 3) / 4), dim3(256), 0, s, D, layer_begin, layer_end,
                      (char*)st->k_cache, (char*)st->v_cache, st->metric, st->pos, st->block_table,
                      st->ctx_len, (const char*)k_new, (const char*)v_new, new_pos, W.header);
   KVC_LAUNCH_CHECK();
