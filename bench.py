@@ -259,7 +259,7 @@ def main():
 
     # the same decode issued the way a model runs it: one call per layer (no append, no metric
     # writes skipped), a few steps, reported beside the all-layers launch
-    per_layer_ms = None
+    per_layer_ms = per_layer_graph_ms = None
     if args.per_layer_steps > 0:
         a, b_ = ev(), ev()
         torch.cuda.synchronize()
@@ -270,6 +270,22 @@ def main():
         b_.record()
         torch.cuda.synchronize()
         per_layer_ms = a.elapsed_time(b_) / args.per_layer_steps
+        # the same 32 calls captured once into a HIP graph and replayed
+        graph = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.graph(graph, stream=side):
+            for l in range(shape.num_layers):
+                sess.paged_decode(qs[0], accumulate_metric=not args.no_metric, layer_begin=l, layer_end=l + 1)
+        torch.cuda.synchronize()
+        a, b_ = ev(), ev()
+        a.record()
+        for i in range(args.per_layer_steps):
+            graph.replay()
+        b_.record()
+        torch.cuda.synchronize()
+        per_layer_graph_ms = a.elapsed_time(b_) / args.per_layer_steps
+        del graph
 
     # prefill-end compression, Mistral-7B shape: one 16384-token prompt, metric from the last 32
     # prompt queries on the matrix cores, then rank-block eviction to 8x
@@ -331,6 +347,7 @@ def main():
         "frac_of_hbm_peak": value / HBM_PEAK_GBS,
         "decode_steps_per_s": 1e3 / ms_step,
         "decode_only_ms_per_step_one_call_per_layer": per_layer_ms,
+        "decode_only_ms_per_step_one_call_per_layer_hip_graph": per_layer_graph_ms,
         "wall_s": wall,
         "eviction": evict,
         "prefill_end": prefill_end,

@@ -135,3 +135,44 @@ def test_group_of_eight_shape_with_long_heads():
                                st.metric[st.free_map == 0], rtol=0, atol=TOL)
     evict_round(sess, st, 0.25, "rank")
     assert_state_equal(sess, st)
+
+
+def test_append_and_decode_replay_from_a_hip_graph():
+    """The asynchronous entry points hold no host synchronisation and no memset nodes, so a
+    caller can capture append + decode into a HIP graph; every replay is checked against the
+    oracle taking the same step, with eager work and synchronisations between replays."""
+    say("graph capture of append + decode")
+    shape, ctx, seed = W.small_mixed(111, S=2, Lyr=2, Hk=2, r=4, d=128, L=5000, rho=3.0, extra_blocks=3)
+    cache = W.make_cache(shape, ctx, seed, placement="fragmented", init_metric="prefill")
+    st = oracle_state(cache)
+    sess = session(cache)
+    k, v = W.make_new_kv(shape, seed, 0)
+    q = W.make_query(shape, seed, 0)
+    kd, vd, qd = k.to(sess.device), v.to(sess.device), q.to(sess.device)
+
+    def oracle_step():
+        O.append(st, k.double().numpy(), v.double().numpy())
+        return O.paged_decode(st, q.double().numpy())
+
+    # one eager step first (also warms up everything the capture must not do for the first time)
+    want = oracle_step()
+    sess.append(kd, vd, flags=B.KVC_ASYNC)
+    sess.paged_decode(qd)
+    torch.cuda.synchronize()
+    np.testing.assert_allclose(sess.out.cpu().numpy(), want, rtol=0, atol=TOL)
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.graph(graph, stream=side):
+        sess.append(kd, vd, flags=B.KVC_ASYNC)
+        sess.paged_decode(qd)
+    torch.cuda.synchronize()
+    for rep in range(4):
+        want = oracle_step()
+        graph.replay()
+        torch.cuda.synchronize()
+        np.testing.assert_allclose(sess.out.cpu().numpy(), want, rtol=0, atol=TOL)
+        scratch = torch.randn(1 << 16, device=sess.device).sum().item()   # eager work in between
+        assert np.isfinite(scratch)
+    assert B.kvc_poll_status(sess.cfg, sess.ws) == B.KVC_OK
+    assert_state_equal(sess, st)
