@@ -126,6 +126,9 @@ __host__ __device__ inline size_t decode_lds_bytes(int T, int R, int HD, int b) 
 // again.  The quantisation moves a probability by at most 2^-17.
 template <int ESZ, int HD, int R, bool B16>
 __global__ void __launch_bounds__(kDecodeThreads) decode_chunk_kernel(DecodeArgs A) {
+  // register buffers for K and V groups: three for 16-bit rows under up to four query heads (two
+  // workgroups of long chunks per CU, two groups in flight behind the current one), else two
+  constexpr int DEPTH = (ESZ == 2 && R <= 4) ? 3 : 2;
   constexpr int EPL = Row<ESZ>::EPL;
   constexpr int LPT = HD / EPL;        // lanes per token
   constexpr int TPI = 64 / LPT;        // tokens per wavefront load
@@ -206,13 +209,7 @@ __global__ void __launch_bounds__(kDecodeThreads) decode_chunk_kernel(DecodeArgs
   float* my_e = s_e + w * 16 * R;
   const bool gm_writer = (lane & 60) == 0;  // lanes 0..3 hold every head between them
 
-  {
-    uint4 kcur[U], vcur[U], knxt[U], vnxt[U];
-    int grp = w;
-    if (grp < ngroups) { load_group(A.kc, grp, kcur); load_group(A.vc, grp, vcur); }
-    for (; grp < ngroups; grp += kDecodeWaves) {
-      const bool more = grp + kDecodeWaves < ngroups;
-      if (more) { load_group(A.kc, grp + kDecodeWaves, knxt); load_group(A.vc, grp + kDecodeWaves, vnxt); }
+  auto process = [&](uint4 (&kcur)[U], uint4 (&vcur)[U], int grp) {
       // logits of the group
       float part[NV];
 #pragma unroll
@@ -279,9 +276,27 @@ __global__ void __launch_bounds__(kDecodeThreads) decode_chunk_kernel(DecodeArgs
           for (int k = 0; k < EPL; ++k) acc[hh][k] = fmaf(p, vf[k], acc[hh][k]);
         }
       }
-      if (more) {
+  };
+  {
+    // DEPTH register buffers used in rotation (the loop is unrolled DEPTH times so that no
+    // buffer is ever copied): DEPTH - 1 groups in flight behind the one being worked on
+    uint4 kb[DEPTH][U], vb[DEPTH][U];
 #pragma unroll
-        for (int u = 0; u < U; ++u) { kcur[u] = knxt[u]; vcur[u] = vnxt[u]; }
+    for (int st = 0; st < DEPTH - 1; ++st) {
+      const int g2 = w + st * kDecodeWaves;
+      if (g2 < ngroups) { load_group(A.kc, g2, kb[st]); load_group(A.vc, g2, vb[st]); }
+    }
+    for (int base = w; base < ngroups; base += DEPTH * kDecodeWaves) {
+#pragma unroll
+      for (int st = 0; st < DEPTH; ++st) {
+        const int grp = base + st * kDecodeWaves;
+        if (grp >= ngroups) break;
+        const int gp = grp + (DEPTH - 1) * kDecodeWaves;
+        if (gp < ngroups) {
+          load_group(A.kc, gp, kb[(st + DEPTH - 1) % DEPTH]);
+          load_group(A.vc, gp, vb[(st + DEPTH - 1) % DEPTH]);
+        }
+        process(kb[st], vb[st], grp);
       }
     }
   }
@@ -592,8 +607,8 @@ static bool choose_chunk(const Dims& D, int gsel, int* T_out, size_t* lds_out) {
   bool tiled = (D.r == 1 || D.r == 2 || D.r == 4 || D.r == 8) && (D.d == 64 || D.d == 128) &&
                tpi >= 1 && D.b % tpi == 0 && 64 % D.b == 0;
   if (!tiled) return false;
-  // default: the longest chunk that still lets three (r <= 4) or two (r = 8) workgroups share a CU
-  int T = g_chunk_tokens ? g_chunk_tokens : (D.r >= 8 ? 2048 : 4096);
+  // default: a chunk that lets two workgroups share a CU
+  int T = g_chunk_tokens ? g_chunk_tokens : (D.r >= 8 ? 2048 : 6144);
   if (!g_chunk_tokens) {
     // a call over few head instances (one layer at a time) has too few long chunks to fill the
     // chip: shorten them until full rows would give a few thousand work items

@@ -27,9 +27,19 @@ def pick_heads(ctx, chunk, n_random, seed):
     return sorted(picks)
 
 
-def test_llama8b_shape_sampled_parity_and_invariants():
+@pytest.fixture
+def forced_chunk(request):
+    """0 = the library's own choice (what bench.py times); otherwise a shorter chunk so that long
+    heads are split over several workgroups and finished by the combine kernel."""
+    B.kvc_set_decode_chunk(request.param)
+    yield request.param
+    B.kvc_set_decode_chunk(0)
+
+
+@pytest.mark.parametrize("forced_chunk", [0, 2048], indirect=True)
+def test_llama8b_shape_sampled_parity_and_invariants(forced_chunk):
     from paper_2410_00161_amd.session import KvcSession
-    print("[case] full-size llama8b decode + eviction", flush=True)
+    print(f"[case] full-size llama8b decode + eviction, chunk setting {forced_chunk}", flush=True)
     shape, ctx, seed = W.llama8b_decode(extra_tokens=64)
     dev = torch.device("cuda:0")
     cache = W.make_cache(shape, ctx, seed, device=dev, placement="fragmented", init_metric="prefill")
@@ -45,7 +55,9 @@ def test_llama8b_shape_sampled_parity_and_invariants():
     sess.append(k, v)
     assert free0 - int(sess.cache.free_map.sum()) == crossing
     heads = pick_heads(sess.cache.ctx_len, chunk, 40, seed)
-    assert any(int(sess.cache.ctx_len.reshape(-1)[g]) > chunk for g in heads)   # a split head is in the sample
+    if int(sess.cache.ctx_len.max()) > chunk:      # then a split head is in the sample
+        assert any(int(sess.cache.ctx_len.reshape(-1)[g]) > chunk for g in heads)
+    assert forced_chunk == 0 or int(sess.cache.ctx_len.max()) > 2 * chunk
     small, q_small = W.gather_heads(sess.cache, heads, q)
     st = oracle_state(small)
     m_before = sess.cache.metric.clone()
