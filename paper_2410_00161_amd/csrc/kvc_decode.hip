@@ -182,13 +182,13 @@ __global__ void __launch_bounds__(kDecodeThreads) decode_chunk_kernel(DecodeArgs
       const size_t slot = ((size_t)s_tab[tk >> lb] << lb) + (tk & (b - 1));
       const char* p = basep + slot * ROWB + (size_t)lane * 16;
 #pragma unroll
-      for (int u = 0; u < U; ++u) buf[u] = *(const uint4*)(p + (size_t)u * 1024);
+      for (int u = 0; u < U; ++u) buf[u] = load_stream16(p + (size_t)u * 1024);
     } else {
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         const int tok = min(grp * 16 + u * TPI + sub, last);
         const size_t slot = ((size_t)s_tab[tok >> lb] << lb) + (tok & (b - 1));
-        buf[u] = *(const uint4*)(basep + slot * ROWB + (size_t)seg * 16);
+        buf[u] = load_stream16(basep + slot * ROWB + (size_t)seg * 16);
       }
     }
   };
