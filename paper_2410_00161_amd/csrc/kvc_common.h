@@ -25,6 +25,7 @@ enum HeaderWord {
   HW_SCRATCH0 = 5,
   HW_SCRATCH1 = 6,
   HW_SMALL_ITEMS = 7,  // decode work items in the small size classes
+  HW_SHORT_ITEMS = 8,  // decode work items short enough for the one-wavefront launch
   // decode work-list block: item counts per size class, per-class cursors, cursor of the
   // per-chunk partial results.  All zero between calls (the chunk kernel clears it).
   HW_DEC_BINS = 32,    // [16]

@@ -104,12 +104,12 @@ __device__ __forceinline__ void stash_load(const float* stash, size_t slot, floa
 constexpr int kDecodeThreads = 256;
 constexpr int kDecodeWaves = kDecodeThreads / 64;
 
-__host__ __device__ inline size_t decode_lds_bytes(int T, int R, int HD, int b) {
+__host__ __device__ inline size_t decode_lds_bytes(int T, int R, int HD, int b, int waves = kDecodeWaves) {
   return (size_t)T * R * 2                       // exp of every logit against its group's running max, 16-bit
          + (size_t)(T / 16) * R * 4              // that running max, per 16-token group and head
-         + (size_t)kDecodeWaves * R * HD * 4     // per-wavefront un-normalised output
-         + (size_t)kDecodeWaves * 16 * R * 4     // per-wavefront exp of the current group, f32
-         + 2 * kDecodeWaves * R * 4              // per-wavefront max and sum
+         + (size_t)waves * R * HD * 4            // per-wavefront un-normalised output
+         + (size_t)waves * 16 * R * 4            // per-wavefront exp of the current group, f32
+         + 2 * waves * R * 4                     // per-wavefront max and sum
          + ((size_t)T / b + 1) * 4;              // block ids of the chunk
 }
 
@@ -124,11 +124,17 @@ __host__ __device__ inline size_t decode_lds_bytes(int T, int R, int HD, int b) 
 // taken against (one f32 per group and head): once the wavefronts have been
 // merged, the normalised probability of every KV follows without touching K
 // again.  The quantisation moves a probability by at most 2^-17.
-template <int ESZ, int HD, int R, bool B16>
-__global__ void __launch_bounds__(kDecodeThreads) decode_chunk_kernel(DecodeArgs A) {
+//
+// NW = 4 wavefronts share a chunk.  The short items at the end of the work list (at most
+// A.Ts tokens) are latency-bound, a chain of dependent loads (item, block table, K and V) in
+// front of a few groups of arithmetic: they get a launch of their own with NW = 1, small LDS
+// and fewer registers, so that a CU holds many of those chains at once.
+template <int ESZ, int HD, int R, bool B16, int NW>
+__global__ void __launch_bounds__(NW * 64) decode_chunk_kernel(DecodeArgs A) {
+  constexpr int NT = NW * 64;
   // register buffers for K and V groups: three for 16-bit rows under up to four query heads (two
   // workgroups of long chunks per CU, two groups in flight behind the current one), else two
-  constexpr int DEPTH = (ESZ == 2 && R <= 4) ? 3 : 2;
+  constexpr int DEPTH = (ESZ == 2 && R <= 4 && NW == 4) ? 3 : 2;
   constexpr int EPL = Row<ESZ>::EPL;
   constexpr int LPT = HD / EPL;        // lanes per token
   constexpr int TPI = 64 / LPT;        // tokens per wavefront load
@@ -138,23 +144,27 @@ __global__ void __launch_bounds__(kDecodeThreads) decode_chunk_kernel(DecodeArgs
   constexpr size_t ROWB = (size_t)HD * ESZ;
   static_assert(LPT >= 4 && LPT <= 32 && (16 % TPI) == 0, "row geometry");
 
-  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63, w = NW == 1 ? 0 : tid >> 6;
   const int total_items = A.header[HW_TOTAL_ITEMS];
-  if (blockIdx.x == 0 && tid < HW_DEC_END - HW_DEC_BINS) A.header[HW_DEC_BINS + tid] = 0;  // work-list block back to zero
-  if ((int)blockIdx.x >= total_items || total_items > A.cap) return;
-  const int item = item_of_workgroup(blockIdx.x, total_items, A.header[HW_SMALL_ITEMS]);
+  const int short_items = A.header[HW_SHORT_ITEMS];
+  if (NW == 4 && blockIdx.x == 0 && tid < HW_DEC_END - HW_DEC_BINS) A.header[HW_DEC_BINS + tid] = 0;  // work-list block back to zero
+  if (total_items > A.cap || short_items < 0 || short_items > total_items) return;
+  const int n_long = total_items - short_items;
+  if ((int)blockIdx.x >= (NW == 4 ? n_long : short_items)) return;
+  const int item = NW == 4 ? blockIdx.x : n_long + blockIdx.x;   // the short items end the list
   const DecodeItem it = A.items[item];
   const int g = it.g, t0 = it.t0, n_tok = it.n_tok, nch = it.nch;
-  if ((unsigned)g >= (unsigned)A.D.G || n_tok <= 0 || n_tok > A.T || t0 < 0 || nch <= 0 ||
+  const int T = NW == 4 ? A.T : A.Ts;    // tokens this launch sizes its LDS arrays for
+  if ((unsigned)g >= (unsigned)A.D.G || n_tok <= 0 || n_tok > T || t0 < 0 || nch <= 0 ||
       (nch > 1 && (it.pbase < 0 || it.pbase + nch > A.cap)))
     return;  // not a record this call wrote
-  const int b = A.D.b, lb = A.log2b, T = A.T;
+  const int b = A.D.b, lb = A.log2b;
 
   extern __shared__ __align__(16) char smem_raw[];
   float* s_acc = (float*)smem_raw;                     // [waves][R][HD]
-  float* s_e = s_acc + kDecodeWaves * R * HD;          // [waves][16][R]
-  float* s_red = s_e + kDecodeWaves * 16 * R;          // [2][waves][R]
-  float* s_gm = s_red + 2 * kDecodeWaves * R;          // [T / 16][R]
+  float* s_e = s_acc + NW * R * HD;          // [waves][16][R]
+  float* s_red = s_e + NW * 16 * R;          // [2][waves][R]
+  float* s_gm = s_red + 2 * NW * R;          // [T / 16][R]
   uint16_t* s_q = (uint16_t*)(s_gm + (T / 16) * R);    // [T][R]
   int* s_tab = (int*)(s_q + (size_t)T * R);            // [T / b + 1]
 
@@ -163,7 +173,7 @@ __global__ void __launch_bounds__(kDecodeThreads) decode_chunk_kernel(DecodeArgs
   {
     const int nblk = (n_tok + b - 1) >> lb;
     const int32_t* row = A.table + (size_t)g * A.D.maxb + (t0 >> lb);
-    for (int i = tid; i < nblk; i += kDecodeThreads) s_tab[i] = row[i];
+    for (int i = tid; i < nblk; i += NT) s_tab[i] = row[i];
   }
   uint4 qv[R];
 #pragma unroll
@@ -283,15 +293,15 @@ __global__ void __launch_bounds__(kDecodeThreads) decode_chunk_kernel(DecodeArgs
     uint4 kb[DEPTH][U], vb[DEPTH][U];
 #pragma unroll
     for (int st = 0; st < DEPTH - 1; ++st) {
-      const int g2 = w + st * kDecodeWaves;
+      const int g2 = w + st * NW;
       if (g2 < ngroups) { load_group(A.kc, g2, kb[st]); load_group(A.vc, g2, vb[st]); }
     }
-    for (int base = w; base < ngroups; base += DEPTH * kDecodeWaves) {
+    for (int base = w; base < ngroups; base += DEPTH * NW) {
 #pragma unroll
       for (int st = 0; st < DEPTH; ++st) {
-        const int grp = base + st * kDecodeWaves;
+        const int grp = base + st * NW;
         if (grp >= ngroups) break;
-        const int gp = grp + (DEPTH - 1) * kDecodeWaves;
+        const int gp = grp + (DEPTH - 1) * NW;
         if (gp < ngroups) {
           load_group(A.kc, gp, kb[(st + DEPTH - 1) % DEPTH]);
           load_group(A.vc, gp, vb[(st + DEPTH - 1) % DEPTH]);
@@ -316,7 +326,7 @@ __global__ void __launch_bounds__(kDecodeThreads) decode_chunk_kernel(DecodeArgs
       const int hh = (idx0 + i) % R;
       if ((hh * 4) / R == lane) {
         s_red[w * R + hh] = m_own[i];
-        s_red[(kDecodeWaves + w) * R + hh] = l_own[i];
+        s_red[(NW + w) * R + hh] = l_own[i];
       }
     }
   }
@@ -336,28 +346,28 @@ __global__ void __launch_bounds__(kDecodeThreads) decode_chunk_kernel(DecodeArgs
 
   // chunk max and sum per head from the wavefronts' pairs
   const bool single = nch == 1;
-  float cm[R], cl[R], wsc[kDecodeWaves][R];
+  float cm[R], cl[R], wsc[NW][R];
 #pragma unroll
   for (int hh = 0; hh < R; ++hh) {
     float m = s_red[hh];
 #pragma unroll
-    for (int ww = 1; ww < kDecodeWaves; ++ww) m = fmaxf(m, s_red[ww * R + hh]);
+    for (int ww = 1; ww < NW; ++ww) m = fmaxf(m, s_red[ww * R + hh]);
     float l = 0.0f;
 #pragma unroll
-    for (int ww = 0; ww < kDecodeWaves; ++ww) {
+    for (int ww = 0; ww < NW; ++ww) {
       wsc[ww][hh] = __builtin_amdgcn_exp2f(s_red[ww * R + hh] - m);
-      l += s_red[(kDecodeWaves + ww) * R + hh] * wsc[ww][hh];
+      l += s_red[(NW + ww) * R + hh] * wsc[ww][hh];
     }
     cm[hh] = m;
     cl[hh] = l;
   }
-  const size_t pslot = (size_t)it.pbase + (size_t)(t0 / T);  // partial-result slot of this chunk
+  const size_t pslot = (size_t)it.pbase + (size_t)(t0 / A.T);  // partial-result slot of this chunk
 #pragma unroll
   for (int hh = 0; hh < R; ++hh) {
-    for (int k = tid; k < HD; k += kDecodeThreads) {
+    for (int k = tid; k < HD; k += NT) {
       float s = 0.0f;
 #pragma unroll
-      for (int ww = 0; ww < kDecodeWaves; ++ww) s += s_acc[(ww * R + hh) * HD + k] * wsc[ww][hh];
+      for (int ww = 0; ww < NW; ++ww) s += s_acc[(ww * R + hh) * HD + k] * wsc[ww][hh];
       if (single) A.out[((size_t)g * R + hh) * HD + k] = s / cl[hh];
       else A.part_acc[(pslot * R + hh) * HD + k] = s;
     }
@@ -373,7 +383,7 @@ __global__ void __launch_bounds__(kDecodeThreads) decode_chunk_kernel(DecodeArgs
   // The stored 16-bit value of a KV times 2^(its group's running max - chunk max) is the exp of
   // its logit against the chunk max; for a head of one chunk, divided by the sum, its
   // probability.  That factor is the same for the 16 tokens of a group: formed once, in place.
-  for (int i = tid; i < ngroups * R; i += kDecodeThreads) {
+  for (int i = tid; i < ngroups * R; i += NT) {
     const int hh = i % R;
     float f = 0.0f;
 #pragma unroll
@@ -382,7 +392,7 @@ __global__ void __launch_bounds__(kDecodeThreads) decode_chunk_kernel(DecodeArgs
     s_gm[i] = f;
   }
   __syncthreads();
-  for (int tok = tid; tok < n_tok; tok += kDecodeThreads) {
+  for (int tok = tid; tok < n_tok; tok += NT) {
     const size_t slot = ((size_t)s_tab[tok >> lb] << lb) + (tok & (b - 1));
     float e[R];
 #pragma unroll
@@ -565,8 +575,9 @@ __global__ void __launch_bounds__(256) decode_generic_kernel(DecodeArgs A) {
 }
 
 template <int ESZ, int HD, int R>
-static int launch_tiled(const DecodeArgs& A, int grid, size_t lds, hipStream_t s) {
-  auto kern = (A.D.b % 16 == 0) ? decode_chunk_kernel<ESZ, HD, R, true> : decode_chunk_kernel<ESZ, HD, R, false>;
+static int launch_tiled(const DecodeArgs& A, int grid, size_t lds, int grid_short, hipStream_t s) {
+  auto kern = (A.D.b % 16 == 0) ? decode_chunk_kernel<ESZ, HD, R, true, 4> : decode_chunk_kernel<ESZ, HD, R, false, 4>;
+  auto kern_short = (A.D.b % 16 == 0) ? decode_chunk_kernel<ESZ, HD, R, true, 1> : decode_chunk_kernel<ESZ, HD, R, false, 1>;
   ProfilePair* pp = (g_prof && g_prof_on && g_prof_used < g_prof_cap) ? &g_prof[g_prof_used++] : nullptr;
   if (pp) KVC_HIP(hipEventRecord(pp->a0, s));
   if (lds > 64 * 1024) {  // above the default cap the kernel must be told once how much it may take
@@ -579,6 +590,8 @@ static int launch_tiled(const DecodeArgs& A, int grid, size_t lds, hipStream_t s
   }
   hipLaunchKernelGGL(kern, dim3(grid), dim3(kDecodeThreads), lds, s, A);
   KVC_LAUNCH_CHECK();
+  hipLaunchKernelGGL(kern_short, dim3(grid_short), dim3(64), decode_lds_bytes(A.Ts, R, HD, A.D.b, 1), s, A);
+  KVC_LAUNCH_CHECK();
   if (pp) { KVC_HIP(hipEventRecord(pp->a1, s)); KVC_HIP(hipEventRecord(pp->b0, s)); }
   hipLaunchKernelGGL(decode_combine_kernel<R>, dim3(grid), dim3(256), 0, s, A);
   KVC_LAUNCH_CHECK();
@@ -587,12 +600,12 @@ static int launch_tiled(const DecodeArgs& A, int grid, size_t lds, hipStream_t s
 }
 
 template <int ESZ, int HD>
-static int launch_tiled_r(const DecodeArgs& A, int grid, size_t lds, hipStream_t s) {
+static int launch_tiled_r(const DecodeArgs& A, int grid, size_t lds, int grid_short, hipStream_t s) {
   switch (A.D.r) {
-    case 1: return launch_tiled<ESZ, HD, 1>(A, grid, lds, s);
-    case 2: return launch_tiled<ESZ, HD, 2>(A, grid, lds, s);
-    case 4: return launch_tiled<ESZ, HD, 4>(A, grid, lds, s);
-    case 8: return launch_tiled<ESZ, HD, 8>(A, grid, lds, s);
+    case 1: return launch_tiled<ESZ, HD, 1>(A, grid, lds, grid_short, s);
+    case 2: return launch_tiled<ESZ, HD, 2>(A, grid, lds, grid_short, s);
+    case 4: return launch_tiled<ESZ, HD, 4>(A, grid, lds, grid_short, s);
+    case 8: return launch_tiled<ESZ, HD, 8>(A, grid, lds, grid_short, s);
   }
   return KVC_ERR_UNSUPPORTED;
 }
@@ -714,6 +727,10 @@ int kvc_paged_decode(const kvc_config* cfg, const kvc_state* st, const void* q, 
   bool tiled = choose_chunk(D, D.S * (layer_end - layer_begin) * D.Hk, &T, &lds);
   const int esz = D.dtype == KVC_BF16 ? 2 : 4;
   A.T = tiled ? T : (1 << 30);  // generic path: one "chunk" per head
+  // items of at most Ts <= 512 tokens go to the one-wavefront launch: size classes short_class and up
+  A.short_class = 1;
+  while (tiled && A.short_class < 15 && (T >> (A.short_class - 1)) > 512) ++A.short_class;
+  A.Ts = tiled ? ((T >> (A.short_class - 1)) + 63) & ~63 : 0;   // LDS arrays come in 16-token strips
   A.log2b = 0;
   while ((1 << A.log2b) < D.b) ++A.log2b;
 
@@ -732,8 +749,9 @@ int kvc_paged_decode(const kvc_config* cfg, const kvc_state* st, const void* q, 
   const size_t bound_row = (size_t)A.gsel * (((size_t)D.maxb * D.b + T - 1) / T);
   const size_t grid = bound_pool < bound_row ? bound_pool : bound_row;
   if (grid > 0x7fffffffull) return KVC_ERR_UNSUPPORTED;
-  if (esz == 2) return D.d == 64 ? launch_tiled_r<2, 64>(A, (int)grid, lds, s) : launch_tiled_r<2, 128>(A, (int)grid, lds, s);
-  return D.d == 64 ? launch_tiled_r<4, 64>(A, (int)grid, lds, s) : launch_tiled_r<4, 128>(A, (int)grid, lds, s);
+  const int gs = A.gsel;   // a head ends in at most one item shorter than a chunk
+  if (esz == 2) return D.d == 64 ? launch_tiled_r<2, 64>(A, (int)grid, lds, gs, s) : launch_tiled_r<2, 128>(A, (int)grid, lds, gs, s);
+  return D.d == 64 ? launch_tiled_r<4, 64>(A, (int)grid, lds, gs, s) : launch_tiled_r<4, 128>(A, (int)grid, lds, gs, s);
 }
 
 }  // extern "C"

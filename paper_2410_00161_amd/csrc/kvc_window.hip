@@ -346,6 +346,8 @@ static int window_common(const kvc_config* cfg, const kvc_state* st, const void*
   A.log2b = 0;
   while ((1 << A.log2b) < D.b) ++A.log2b;
   A.all_partials = 1;
+  A.short_class = 16;  // no separate launch for short items here
+  A.Ts = 0;
   A.cap = (int)(max_items_of(D) < 0x7fffffffull ? max_items_of(D) : 0x7fffffffull);
   A.items = (DecodeItem*)Wk.items; A.part_ml = Wk.part_ml; A.part_acc = Wk.part_acc; A.stash = Wk.stash;
   A.header = Wk.header;

@@ -30,6 +30,7 @@ struct DecodeArgs {
   int log2b;              // block size is a power of two on the tiled path
   int cap;                // item records and partial-result slots the workspace holds
   int all_partials;       // give every head a partial-result slot range, not only split heads
+  int short_class, Ts;    // size classes from short_class up (at most Ts tokens) are "short" items; 16 = none
   DecodeItem* items;
   float* part_ml;
   float* part_acc;
@@ -90,14 +91,19 @@ static __global__ void __launch_bounds__(256) decode_items_kernel(DecodeArgs A) 
   if (tid < 17) want[tid] = 0;
   if (tid == 0) {
     int run = 0;
-    int small = 0;
+    int small = 0, pack = 0;
     for (int k = 0; k < 16; ++k) {
       const int c = A.header[HW_DEC_BINS + k];
       base[k] = run;
       run += c;
       if (k >= kSmallClass) small += c;
+      if (k >= A.short_class) pack += c;
     }
-    if (blockIdx.x == 0) { A.header[HW_TOTAL_ITEMS] = run; A.header[HW_SMALL_ITEMS] = small; }
+    if (blockIdx.x == 0) {
+      A.header[HW_TOTAL_ITEMS] = run;
+      A.header[HW_SMALL_ITEMS] = small;
+      A.header[HW_SHORT_ITEMS] = pack;
+    }
   }
   __syncthreads();
   const int gi = blockIdx.x * 256 + tid;
