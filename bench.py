@@ -198,39 +198,55 @@ def main():
         print(f"bench.py: device-side error {status} ({B.status_string(status)})", file=sys.stderr)
         sys.exit(1)
     ms_total = t0.elapsed_time(t1)
-    chunk_ms, combine_ms = B.kvc_profile_collect(4096)
+    chunk_ms, short_ms, combine_ms = B.kvc_profile_collect(4096)
     B.kvc_profile_begin(0)
 
     # Between two compression rounds every head grows by exactly one KV per step, so the
     # lengths each decode saw follow from the snapshot taken at the start of the period.
+    # A head of C tokens is cut into chunks of chunk_T; a last chunk (or whole head) of at most
+    # short_T tokens runs in the short-item launch, everything else in the long-item launch.  A
+    # head of one chunk gets its metric from the launch that streams it, others from the combine.
     chunk_T = B.kvc_get_decode_chunk(sess.cfg)
-    kv_per_step, single = [], []
+    short_T = B.kvc_get_decode_short(sess.cfg)
+    kv_per_step, long_kv, long_single, short_single = [], [], [], []
     keys = sorted(snaps)
     for i in range(args.warmup, total_steps):
         s0 = max(k for k in keys if k <= i)
         c = snaps[s0].to(torch.int64) + (i - s0)
+        rem = c % chunk_T
+        in_short = rem * ((rem > 0) & (rem <= short_T))
         kv_per_step.append(float(c.sum()))
-        single.append(float((c * (c <= chunk_T)).sum()))   # KVs whose metric the chunk kernel updates itself
-    kv_per_step = np.array(kv_per_step)
-    single = np.array(single)
+        long_kv.append(float((c - in_short).sum()))
+        long_single.append(float((c * ((c <= chunk_T) & (c > short_T))).sum()))
+        short_single.append(float((c * (c <= min(short_T, chunk_T))).sum()))
+    kv_per_step, long_kv = np.array(kv_per_step), np.array(long_kv)
+    long_single, short_single = np.array(long_single), np.array(short_single)
     total_bytes = float(kv_per_step.sum()) * bytes_kv
     value = total_bytes / (ms_total * 1e-3) / 1e9
     ms_step = ms_total / args.steps
 
-    # dominant kernel: decode_chunk_kernel (streams K and V once; metric RMW for heads of one chunk)
-    chunk_alg = kv_per_step * (2 * shape.head_dim * shape.kv_bytes + 4.0 / shape.block_size) + 8.0 * single
+    # dominant kernel: decode_chunk_kernel over the long items (four wavefronts per item): streams
+    # their K and V once, metric RMW for heads of one chunk
+    per_kv = 2 * shape.head_dim * shape.kv_bytes + 4.0 / shape.block_size
+    chunk_alg = long_kv * per_kv + 8.0 * long_single
+    short_alg = (kv_per_step - long_kv) * per_kv + 8.0 * short_single
     chunk_ms = np.array(chunk_ms, dtype=np.float64)
+    short_ms = np.array(short_ms, dtype=np.float64)
     combine_ms = np.array(combine_ms, dtype=np.float64)
     chunk_alg_s = chunk_alg[::prof_every][:len(chunk_ms)]          # the steps that were timed
+    short_alg_s = short_alg[::prof_every][:len(chunk_ms)]
     ach = float(chunk_alg_s.mean() / (chunk_ms.mean() * 1e-3) / 1e9)
     traffic = read_traffic_note("decode_chunk_kernel_llama8b_pmc.txt") if args.workload == "llama8b" else None
-    roofline = {"bound": "hbm", "kernel": "decode_chunk_kernel<2,128,%d>" % shape.group_size,
+    roofline = {"bound": "hbm", "kernel": "decode_chunk_kernel<2,128,%d,b16,4> (long items)" % shape.group_size,
                 "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
                 "traffic": traffic, "avg_kernel_ms": float(chunk_ms.mean()),
                 "algorithmic_bytes_per_launch": float(chunk_alg_s.mean()),
                 "timed_launches": int(len(chunk_ms)),
+                "short_items_kernel_ms": float(short_ms.mean()),
+                "short_items_GBps": float(short_alg_s.mean() / (short_ms.mean() * 1e-3) / 1e9),
+                "short_items_max_tokens": short_T,
                 "decode_call_GBps": float((kv_per_step[::prof_every][:len(chunk_ms)] * bytes_kv).mean() /
-                                          ((chunk_ms + combine_ms).mean() * 1e-3) / 1e9),
+                                          ((chunk_ms + short_ms + combine_ms).mean() * 1e-3) / 1e9),
                 "combine_kernel_ms": float(combine_ms.mean())}
 
     # measured streaming-read ceiling of this GPU: the K cache read once with plain 16-byte loads

@@ -272,16 +272,22 @@ int kvc_set_decode_chunk(int tokens);
  * general fallback kernel, which does not split heads.  Host only.              */
 int kvc_get_decode_chunk(const kvc_config* cfg, int* tokens);
 
+/* kvc_paged_decode runs the last chunk of a head (or a whole short head) in a second launch,
+ * one wavefront per item, when it holds at most this many tokens (host out-param; for a call
+ * over all layers; 0 on the fallback path).  Host only.                          */
+int kvc_get_decode_short(const kvc_config* cfg, int* tokens);
+
 /* Kernel timing for benchmarks.  kvc_profile_begin(n) makes the next n calls of
- * kvc_paged_decode record a HIP event pair on their stream around the chunk
- * kernel (the kernel that streams K and V) and another around the combine
- * kernel; n = 0 switches recording off and releases the events.  Host only
- * state, process-wide, at most 4096 pairs.  kvc_profile_collect waits for the
- * recorded events and writes up to `cap` durations in milliseconds to the host
- * arrays chunk_ms and combine_ms (either may be NULL), returning the number of
+ * kvc_paged_decode record HIP event pairs on their stream around each of its
+ * three launches: the chunk kernel over the long items (it streams nearly all
+ * of K and V), the same kernel over the short items, and the combine kernel;
+ * n = 0 switches recording off and releases the events.  Host only state,
+ * process-wide, at most 4096 calls.  kvc_profile_collect waits for the recorded
+ * events and writes up to `cap` durations in milliseconds to the host arrays
+ * chunk_ms, short_ms and combine_ms (each may be NULL), returning the number of
  * recorded calls in *count (host).                                             */
 /* Bandwidth probe for benchmarks: reads `bytes` (a multiple of 16) of device
- * memory at `src` once with 16-byte loads, grid-stride, and writes one 32-bit
+ * memory at `src` once with 16-byte non-temporal loads, grid-stride, and writes one 32-bit
  * checksum per workgroup to `sink` (device, at least `workgroups` words).
  * Gives the streaming-read rate this GPU reaches, to set beside the kernels'.   */
 int kvc_stream_read_probe(const void* src, size_t bytes, uint32_t* sink, int workgroups,
@@ -298,7 +304,7 @@ int kvc_profile_begin(int n);
 /* Pauses (0) or resumes (non-zero) the recording without releasing anything, so that a
  * benchmark can time every k-th call only.  Host only.                            */
 int kvc_profile_enable(int on);
-int kvc_profile_collect(float* chunk_ms, float* combine_ms, int cap, int* count);
+int kvc_profile_collect(float* chunk_ms, float* short_ms, float* combine_ms, int cap, int* count);
 
 #ifdef __cplusplus
 }

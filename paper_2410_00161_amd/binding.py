@@ -25,7 +25,7 @@ EXPORTS = [
     "kvc_workspace_bytes", "kvc_validate", "kvc_status_string", "kvc_workspace_reset",
     "kvc_poll_status", "kvc_block_alloc", "kvc_block_free", "kvc_append", "kvc_paged_decode",
     "kvc_metric_reduce", "kvc_evict_select", "kvc_compact", "kvc_set_decode_chunk",
-    "kvc_get_decode_chunk", "kvc_evict_rank_select", "kvc_compact_rank", "kvc_window_metric", "kvc_query_block_metric", "kvc_count_blocks", "kvc_prefill_alloc", "kvc_preempt",
+    "kvc_get_decode_chunk", "kvc_get_decode_short", "kvc_evict_rank_select", "kvc_compact_rank", "kvc_window_metric", "kvc_query_block_metric", "kvc_count_blocks", "kvc_prefill_alloc", "kvc_preempt",
     "kvc_profile_begin", "kvc_profile_enable", "kvc_profile_collect", "kvc_stream_read_probe", "kvc_stream_rw_probe",
 ]
 
@@ -83,11 +83,12 @@ def lib() -> C.CDLL:
         L.kvc_window_metric.argtypes = [cfgp, stp, P, I, I, I, I, I, P, P]
         L.kvc_query_block_metric.argtypes = [cfgp, stp, P, I, I, I, I, I, P, P]
         L.kvc_get_decode_chunk.argtypes = [cfgp, C.POINTER(C.c_int)]
+        L.kvc_get_decode_short.argtypes = [cfgp, C.POINTER(C.c_int)]
         L.kvc_profile_begin.argtypes = [I]
         L.kvc_profile_enable.argtypes = [I]
         L.kvc_stream_read_probe.argtypes = [P, C.c_size_t, P, I, P]
         L.kvc_stream_rw_probe.argtypes = [P, C.c_size_t, P, C.c_size_t, I, P, I, P]
-        L.kvc_profile_collect.argtypes = [P, P, I, C.POINTER(C.c_int)]
+        L.kvc_profile_collect.argtypes = [P, P, P, I, C.POINTER(C.c_int)]
         for n in EXPORTS:
             if n not in ("kvc_workspace_bytes", "kvc_status_string"):
                 getattr(L, n).restype = I
@@ -226,13 +227,14 @@ def kvc_profile_begin(n: int):
 
 
 def kvc_profile_collect(cap: int = 4096):
-    """Returns (chunk_ms, combine_ms) lists of the recorded decode calls."""
+    """Returns (chunk_ms, short_ms, combine_ms) lists of the recorded decode calls."""
     a = (C.c_float * cap)()
+    sh = (C.c_float * cap)()
     b = (C.c_float * cap)()
     n = C.c_int(0)
-    _check(lib().kvc_profile_collect(a, b, cap, C.byref(n)), "kvc_profile_collect")
+    _check(lib().kvc_profile_collect(a, sh, b, cap, C.byref(n)), "kvc_profile_collect")
     k = min(n.value, cap)
-    return list(a[:k]), list(b[:k])
+    return list(a[:k]), list(sh[:k]), list(b[:k])
 
 
 def kvc_stream_read_probe(src, nbytes, sink, workgroups, stream=None):
@@ -247,6 +249,12 @@ def kvc_profile_enable(on: bool):
 def kvc_get_decode_chunk(cfg) -> int:
     out = C.c_int(0)
     _check(lib().kvc_get_decode_chunk(C.byref(cfg), C.byref(out)), "kvc_get_decode_chunk")
+    return out.value
+
+
+def kvc_get_decode_short(cfg) -> int:
+    out = C.c_int(0)
+    _check(lib().kvc_get_decode_short(C.byref(cfg), C.byref(out)), "kvc_get_decode_short")
     return out.value
 
 

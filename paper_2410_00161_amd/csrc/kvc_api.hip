@@ -37,10 +37,11 @@ __global__ void __launch_bounds__(256) stream_read_kernel(const uint4* __restric
   const size_t stride = (size_t)gridDim.x * 256;
   size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
   for (; i + 3 * stride < n16; i += 4 * stride) {  // four independent loads in flight per lane
-    const uint4 a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
+    const uint4 a = load_stream16(src + i), b = load_stream16(src + i + stride);
+    const uint4 c = load_stream16(src + i + 2 * stride), d = load_stream16(src + i + 3 * stride);
     acc ^= a.x ^ a.y ^ a.z ^ a.w ^ b.x ^ b.y ^ b.z ^ b.w ^ c.x ^ c.y ^ c.z ^ c.w ^ d.x ^ d.y ^ d.z ^ d.w;
   }
-  for (; i < n16; i += stride) { const uint4 a = src[i]; acc ^= a.x ^ a.y ^ a.z ^ a.w; }
+  for (; i < n16; i += stride) { const uint4 a = load_stream16(src + i); acc ^= a.x ^ a.y ^ a.z ^ a.w; }
   for (int m = 32; m >= 1; m >>= 1) acc ^= __shfl_xor(acc, m);
   if ((threadIdx.x & 63) == 0) atomicXor(&sink[blockIdx.x], acc);
 }

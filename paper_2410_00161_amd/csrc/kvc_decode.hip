@@ -29,7 +29,7 @@ namespace kvc {
 static int g_chunk_tokens = 0;  // 0 = default; set by kvc_set_decode_chunk
 
 // optional event pairs around the two decode kernels (kvc_profile_begin / _collect)
-struct ProfilePair { hipEvent_t a0, a1, b0, b1; };
+struct ProfilePair { hipEvent_t a0, a1, s0, s1, b0, b1; };  // long-item, short-item, combine launches
 static ProfilePair* g_prof = nullptr;
 static int g_prof_cap = 0, g_prof_used = 0, g_prof_on = 1;
 
@@ -590,9 +590,10 @@ static int launch_tiled(const DecodeArgs& A, int grid, size_t lds, int grid_shor
   }
   hipLaunchKernelGGL(kern, dim3(grid), dim3(kDecodeThreads), lds, s, A);
   KVC_LAUNCH_CHECK();
+  if (pp) { KVC_HIP(hipEventRecord(pp->a1, s)); KVC_HIP(hipEventRecord(pp->s0, s)); }
   hipLaunchKernelGGL(kern_short, dim3(grid_short), dim3(64), decode_lds_bytes(A.Ts, R, HD, A.D.b, 1), s, A);
   KVC_LAUNCH_CHECK();
-  if (pp) { KVC_HIP(hipEventRecord(pp->a1, s)); KVC_HIP(hipEventRecord(pp->b0, s)); }
+  if (pp) { KVC_HIP(hipEventRecord(pp->s1, s)); KVC_HIP(hipEventRecord(pp->b0, s)); }
   hipLaunchKernelGGL(decode_combine_kernel<R>, dim3(grid), dim3(256), 0, s, A);
   KVC_LAUNCH_CHECK();
   if (pp) KVC_HIP(hipEventRecord(pp->b1, s));
@@ -636,6 +637,16 @@ static bool choose_chunk(const Dims& D, int gsel, int* T_out, size_t* lds_out) {
   return true;
 }
 
+// Items of at most 512 tokens go to the one-wavefront launch: the size classes from *cls up,
+// whose items hold at most *max_tokens tokens; *lds_tokens is that bound in whole 64-token strips.
+static void short_split(int T, int* cls, int* max_tokens, int* lds_tokens) {
+  int k = 1;
+  while (k < 15 && (T >> (k - 1)) > 512) ++k;
+  *cls = k;
+  *max_tokens = T >> (k - 1);
+  *lds_tokens = (*max_tokens + 63) & ~63;
+}
+
 }  // namespace kvc
 
 using namespace kvc;
@@ -647,6 +658,7 @@ int kvc_profile_begin(int n) {
   if (g_prof) {
     for (int i = 0; i < g_prof_cap; ++i) {
       hipEventDestroy(g_prof[i].a0); hipEventDestroy(g_prof[i].a1);
+      hipEventDestroy(g_prof[i].s0); hipEventDestroy(g_prof[i].s1);
       hipEventDestroy(g_prof[i].b0); hipEventDestroy(g_prof[i].b1);
     }
     delete[] g_prof;
@@ -658,6 +670,7 @@ int kvc_profile_begin(int n) {
   g_prof = new ProfilePair[n];
   for (int i = 0; i < n; ++i) {
     KVC_HIP(hipEventCreate(&g_prof[i].a0)); KVC_HIP(hipEventCreate(&g_prof[i].a1));
+    KVC_HIP(hipEventCreate(&g_prof[i].s0)); KVC_HIP(hipEventCreate(&g_prof[i].s1));
     KVC_HIP(hipEventCreate(&g_prof[i].b0)); KVC_HIP(hipEventCreate(&g_prof[i].b1));
   }
   g_prof_cap = n;
@@ -669,13 +682,14 @@ int kvc_profile_enable(int on) {
   return KVC_OK;
 }
 
-int kvc_profile_collect(float* chunk_ms, float* combine_ms, int cap, int* count) {
+int kvc_profile_collect(float* chunk_ms, float* short_ms, float* combine_ms, int cap, int* count) {
   if (!count || cap < 0) return KVC_ERR_ARG;
   *count = g_prof_used;
   for (int i = 0; i < g_prof_used && i < cap; ++i) {
     KVC_HIP(hipEventSynchronize(g_prof[i].b1));
     float ms = 0.0f;
     if (chunk_ms) { KVC_HIP(hipEventElapsedTime(&ms, g_prof[i].a0, g_prof[i].a1)); chunk_ms[i] = ms; }
+    if (short_ms) { KVC_HIP(hipEventElapsedTime(&ms, g_prof[i].s0, g_prof[i].s1)); short_ms[i] = ms; }
     if (combine_ms) { KVC_HIP(hipEventElapsedTime(&ms, g_prof[i].b0, g_prof[i].b1)); combine_ms[i] = ms; }
   }
   return KVC_OK;
@@ -689,6 +703,21 @@ int kvc_get_decode_chunk(const kvc_config* cfg, int* tokens) {
   size_t lds = 0;
   const Dims D = dims_of(cfg);
   *tokens = choose_chunk(D, D.G, &T, &lds) ? T : 0;
+  return KVC_OK;
+}
+
+int kvc_get_decode_short(const kvc_config* cfg, int* tokens) {
+  int rc = validate(cfg, nullptr);
+  if (rc != KVC_OK) return rc;
+  if (!tokens) return KVC_ERR_ARG;
+  int T = 0;
+  size_t lds = 0;
+  const Dims D = dims_of(cfg);
+  *tokens = 0;
+  if (choose_chunk(D, D.G, &T, &lds)) {
+    int cls = 0, lds_tokens = 0;
+    short_split(T, &cls, tokens, &lds_tokens);
+  }
   return KVC_OK;
 }
 
@@ -727,10 +756,12 @@ int kvc_paged_decode(const kvc_config* cfg, const kvc_state* st, const void* q, 
   bool tiled = choose_chunk(D, D.S * (layer_end - layer_begin) * D.Hk, &T, &lds);
   const int esz = D.dtype == KVC_BF16 ? 2 : 4;
   A.T = tiled ? T : (1 << 30);  // generic path: one "chunk" per head
-  // items of at most Ts <= 512 tokens go to the one-wavefront launch: size classes short_class and up
-  A.short_class = 1;
-  while (tiled && A.short_class < 15 && (T >> (A.short_class - 1)) > 512) ++A.short_class;
-  A.Ts = tiled ? ((T >> (A.short_class - 1)) + 63) & ~63 : 0;   // LDS arrays come in 16-token strips
+  A.short_class = 16;
+  A.Ts = 0;
+  if (tiled) {
+    int short_max = 0;
+    short_split(T, &A.short_class, &short_max, &A.Ts);
+  }
   A.log2b = 0;
   while ((1 << A.log2b) < D.b) ++A.log2b;
 

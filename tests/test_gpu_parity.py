@@ -52,6 +52,7 @@ DECODE_CASES = [
     ("bf16_d128_r4", dict(r=4, d=128, kv_dtype="bf16", L=700), 0, B.KVC_L2),
     ("bf16_d128_r4_split", dict(r=4, d=128, kv_dtype="bf16", L=700), 128, B.KVC_L2),
     ("bf16_d128_r8_split", dict(r=8, d=128, kv_dtype="bf16", L=500), 64, B.KVC_L2),
+    ("bf16_odd_chunk", dict(r=4, d=128, kv_dtype="bf16", L=1500, rho=2.0, S=2), 1088, B.KVC_L2),
     ("bf16_d128_r1", dict(r=1, d=128, kv_dtype="bf16", L=300), 0, B.KVC_L2),
     ("bf16_d128_r2_L1", dict(r=2, d=128, kv_dtype="bf16", L=300), 64, B.KVC_L1),
     ("bf16_d64_r4", dict(r=4, d=64, kv_dtype="bf16", L=400), 128, B.KVC_L2),
