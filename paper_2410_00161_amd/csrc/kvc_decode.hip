@@ -591,8 +591,10 @@ static int launch_tiled(const DecodeArgs& A, int grid, size_t lds, int grid_shor
   hipLaunchKernelGGL(kern, dim3(grid), dim3(kDecodeThreads), lds, s, A);
   KVC_LAUNCH_CHECK();
   if (pp) { KVC_HIP(hipEventRecord(pp->a1, s)); KVC_HIP(hipEventRecord(pp->s0, s)); }
-  hipLaunchKernelGGL(kern_short, dim3(grid_short), dim3(64), decode_lds_bytes(A.Ts, R, HD, A.D.b, 1), s, A);
-  KVC_LAUNCH_CHECK();
+  if (A.short_class < 16) {
+    hipLaunchKernelGGL(kern_short, dim3(grid_short), dim3(64), decode_lds_bytes(A.Ts, R, HD, A.D.b, 1), s, A);
+    KVC_LAUNCH_CHECK();
+  }
   if (pp) { KVC_HIP(hipEventRecord(pp->s1, s)); KVC_HIP(hipEventRecord(pp->b0, s)); }
   hipLaunchKernelGGL(decode_combine_kernel<R>, dim3(grid), dim3(256), 0, s, A);
   KVC_LAUNCH_CHECK();
@@ -614,7 +616,7 @@ static int launch_tiled_r(const DecodeArgs& A, int grid, size_t lds, int grid_sh
 constexpr size_t kLdsLimit = 160 * 1024;  // gfx950: 160 KiB of LDS per workgroup
 
 // Whether the tiled kernels cover this shape, and with which chunk length and LDS size.
-static bool choose_chunk(const Dims& D, int gsel, int* T_out, size_t* lds_out) {
+static bool choose_chunk(const Dims& D, int gsel, int* T_out, size_t* lds_out, bool* small_call = nullptr) {
   const int esz = D.dtype == KVC_BF16 ? 2 : 4;
   const int lpt = D.d * esz / 16;
   const int tpi = (lpt >= 1 && lpt <= 64) ? 64 / lpt : 0;
@@ -623,6 +625,7 @@ static bool choose_chunk(const Dims& D, int gsel, int* T_out, size_t* lds_out) {
   if (!tiled) return false;
   // default: a chunk that lets two workgroups share a CU
   int T = g_chunk_tokens ? g_chunk_tokens : (D.r >= 8 ? 2048 : 6144);
+  const int T_default = T;
   if (!g_chunk_tokens) {
     // a call over few head instances (one layer at a time) has too few long chunks to fill the
     // chip: shorten them until full rows would give a few thousand work items
@@ -634,6 +637,7 @@ static bool choose_chunk(const Dims& D, int gsel, int* T_out, size_t* lds_out) {
   if (lds > kLdsLimit) return false;
   *T_out = T;
   *lds_out = lds;
+  if (small_call) *small_call = T < T_default;
   return true;
 }
 
@@ -753,12 +757,15 @@ int kvc_paged_decode(const kvc_config* cfg, const kvc_state* st, const void* q, 
 
   int T = 0;
   size_t lds = 0;
-  bool tiled = choose_chunk(D, D.S * (layer_end - layer_begin) * D.Hk, &T, &lds);
+  bool small_call = false;
+  bool tiled = choose_chunk(D, D.S * (layer_end - layer_begin) * D.Hk, &T, &lds, &small_call);
   const int esz = D.dtype == KVC_BF16 ? 2 : 4;
   A.T = tiled ? T : (1 << 30);  // generic path: one "chunk" per head
   A.short_class = 16;
   A.Ts = 0;
-  if (tiled) {
+  // A small call (one layer of a model) is bound by the time of its slowest item, not by
+  // throughput: there every item gets four wavefronts and the short-item launch is left out.
+  if (tiled && !small_call) {
     int short_max = 0;
     short_split(T, &A.short_class, &short_max, &A.Ts);
   }
@@ -771,10 +778,15 @@ int kvc_paged_decode(const kvc_config* cfg, const kvc_state* st, const void* q, 
     KVC_LAUNCH_CHECK();
     return KVC_OK;
   }
-  hipLaunchKernelGGL(decode_count_kernel, dim3((A.gsel + 255) / 256), dim3(256), 0, s, A);
-  KVC_LAUNCH_CHECK();
-  hipLaunchKernelGGL(decode_items_kernel, dim3((A.gsel + 255) / 256), dim3(256), 0, s, A);
-  KVC_LAUNCH_CHECK();
+  if (A.gsel <= 1024) {
+    hipLaunchKernelGGL(decode_worklist_small_kernel, dim3(1), dim3(1024), 0, s, A);
+    KVC_LAUNCH_CHECK();
+  } else {
+    hipLaunchKernelGGL(decode_count_kernel, dim3((A.gsel + 255) / 256), dim3(256), 0, s, A);
+    KVC_LAUNCH_CHECK();
+    hipLaunchKernelGGL(decode_items_kernel, dim3((A.gsel + 255) / 256), dim3(256), 0, s, A);
+    KVC_LAUNCH_CHECK();
+  }
   // items <= (slots in the pool) / T + heads, and <= heads * chunks a full row can hold
   const size_t bound_pool = (size_t)D.N * D.b / T + (size_t)A.gsel;
   const size_t bound_row = (size_t)A.gsel * (((size_t)D.maxb * D.b + T - 1) / T);

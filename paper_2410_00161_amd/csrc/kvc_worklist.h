@@ -153,6 +153,66 @@ static __global__ void __launch_bounds__(256) decode_items_kernel(DecodeArgs A) 
   }
 }
 
+// Both passes in one workgroup, for calls over at most 1024 head instances (one layer of a
+// model): one launch instead of two.  Leaves the header words as the two-pass pair does.
+static __global__ void __launch_bounds__(1024) decode_worklist_small_kernel(DecodeArgs A) {
+  __shared__ int bins[16], base[16], cur[17];
+  const int tid = threadIdx.x;
+  if (tid < 16) bins[tid] = 0;
+  if (tid < 17) cur[tid] = 0;
+  __syncthreads();
+  const int T = A.T;
+  int g = 0, C = 0, nfull = 0, rem = 0, nch = 0, cls = 0;
+  if (tid < A.gsel) {
+    g = sel_to_g(A.D, A.l0, A.nl, tid);
+    C = A.ctx[g];
+    nfull = C / T;
+    rem = C - nfull * T;
+    nch = nfull + (rem ? 1 : 0);
+    cls = rem ? size_class(rem, T) : 0;
+    if (nfull) atomicAdd(&bins[0], nfull);
+    if (rem) atomicAdd(&bins[cls], 1);
+  }
+  __syncthreads();
+  if (tid == 0) {
+    int run = 0, small = 0, pack = 0;
+    for (int k = 0; k < 16; ++k) {
+      base[k] = run;
+      run += bins[k];
+      if (k >= kSmallClass) small += bins[k];
+      if (k >= A.short_class) pack += bins[k];
+    }
+    A.header[HW_TOTAL_ITEMS] = run;
+    A.header[HW_SMALL_ITEMS] = small;
+    A.header[HW_SHORT_ITEMS] = pack;
+  }
+  __syncthreads();
+  if (tid >= A.gsel) return;
+  if (C == 0) {
+    if (A.out) {
+      float* o = A.out + (size_t)g * A.D.r * A.D.d;
+      for (int i = 0; i < A.D.r * A.D.d; ++i) o[i] = 0.0f;
+    }
+    return;
+  }
+  const int pbase = (nch > 1 || A.all_partials) ? atomicAdd(&cur[16], nch) : 0;
+  if (pbase < 0 || pbase + nch > A.cap) return;
+  if (nfull) {
+    const int at = base[0] + atomicAdd(&cur[0], nfull);
+    if (at < 0 || at + nfull > A.cap) return;
+    for (int c = 0; c < nfull; ++c) {
+      DecodeItem it = {g, c * T, T, nch, pbase, {0, 0, 0}};
+      A.items[at + c] = it;
+    }
+  }
+  if (rem) {
+    const int at = base[cls] + atomicAdd(&cur[cls], 1);
+    if (at < 0 || at >= A.cap) return;
+    DecodeItem it = {g, nfull * T, rem, nch, pbase, {0, 0, 0}};
+    A.items[at] = it;
+  }
+}
+
 template <int CTRL>
 __device__ __forceinline__ float dpp_move(float v) {
   return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, true));
