@@ -55,6 +55,7 @@ typedef enum {
 
 enum { KVC_F32 = 0, KVC_BF16 = 1 };  /* kv_dtype                                  */
 enum { KVC_L2 = 0, KVC_L1 = 1 };     /* metric_mode: sum of p^2 (default) or of p */
+enum { KVC_KEY_SUM = 0, KVC_KEY_MAX = 1 };  /* key_mode of kvc_metric_reduce               */
 enum { KVC_ASYNC = 1 };              /* flags                                     */
 
 /* Immutable description of the cache (paper: Method, "Block Layout and Parallel
@@ -172,13 +173,15 @@ int kvc_paged_decode(const kvc_config* cfg, const kvc_state* st, const void* q, 
                      int layer_begin, int layer_end, int accumulate_metric,
                      void* ws, void* stream);
 
-/* Block-level reduction of the metric ("Evicting from a Paged KV Cache": blocks
- * are ordered by the SUM of their KVs' metrics).  block_key [G, max_blocks] f32:
- * block_key[g][u] = M[n][0] + M[n][1] + ... over the filled slots of logical
- * block u (n = block_table[g][u]), added left to right in f32; a partial last
+/* Block-level reduction of the metric ("Evicting from a Paged KV Cache": the
+ * requirement orders blocks by the SUM of their KVs' metrics; the matrix the
+ * same section builds takes the last column of a row, its MAX).  block_key
+ * [G, max_blocks] f32.  KVC_KEY_SUM: block_key[g][u] = M[n][0] + M[n][1] + ...
+ * over the filled slots of logical block u (n = block_table[g][u]), added left
+ * to right in f32.  KVC_KEY_MAX: the largest of those metrics.  A partial last
  * block contributes only its real slots.  Cells with u >= ceil(ctx_len/b) are
- * set to 0.  Asynchronous.                                                     */
-int kvc_metric_reduce(const kvc_config* cfg, const kvc_state* st, float* block_key,
+ * set to 0.  KVC_ERR_ARG for any other key_mode.  Asynchronous.                 */
+int kvc_metric_reduce(const kvc_config* cfg, const kvc_state* st, float* block_key, int key_mode,
                       void* ws, void* stream);
 
 /* Lowest-metric block selection across layers and heads (same section: each

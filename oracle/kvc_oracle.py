@@ -348,16 +348,21 @@ def query_block_metric(st: State, q_blk, w, first_pos, exclude=0, metric_mode="L
 # block keys and selection
 # --------------------------------------------------------------------------
 
-def block_keys(st: State, metric=None):
-    """key[g, u] = sum of the metrics held in logical block u of head instance g.
+def block_keys(st: State, metric=None, key="sum"):
+    """key[g, u] = sum (or, with key="max", maximum) of the metrics held in
+    logical block u of head instance g.  "Evicting from a Paged KV Cache" asks
+    for the order by sum; the matrix it builds reads a row's last column, its
+    maximum.
 
     fp32, added left to right over the filled slots only (a partial last block
     contributes its C_g - u*b real slots; whatever sits in empty slots is
     ignored).  Entries with u >= ceil(C_g / b) are 0.  Also returns the same
-    sums in fp64."""
+    keys in fp64."""
+    if key not in ("sum", "max"):
+        raise OracleError(ERR_ARG, "key is 'sum' or 'max'")
     M = st.metric if metric is None else np.asarray(metric).reshape(st.N, st.b)
     M32 = M.astype(np.float32)
-    key = np.zeros((st.G, st.max_blocks), dtype=np.float32)
+    key_arr = np.zeros((st.G, st.max_blocks), dtype=np.float32)
     key64 = np.zeros((st.G, st.max_blocks), dtype=np.float64)
     tab, lens = st.table(), st.lens()
     for g in range(st.G):
@@ -365,12 +370,16 @@ def block_keys(st: State, metric=None):
         nb = -(-C // st.b)
         for u in range(nb):
             fill = min(st.b, C - u * st.b)
+            if key == "max":
+                key_arr[g, u] = M32[tab[g, u], :fill].max()
+                key64[g, u] = M[tab[g, u], :fill].astype(np.float64).max()
+                continue
             acc = np.float32(0.0)
             for o in range(fill):
                 acc = np.float32(acc + M32[tab[g, u], o])
-            key[g, u] = acc
+            key_arr[g, u] = acc
             key64[g, u] = M[tab[g, u], :fill].astype(np.float64).sum()
-    return key, key64
+    return key_arr, key64
 
 
 def evict_select(st: State, key, budget, seg_offsets=None, protect_tail_blocks=1):

@@ -19,6 +19,7 @@ KVC_OK, KVC_ERR_ARG, KVC_ERR_OOM, KVC_ERR_TABLE_FULL = 0, 1, 2, 3
 KVC_ERR_BUDGET, KVC_ERR_NUMERIC, KVC_ERR_HIP, KVC_ERR_UNSUPPORTED = 4, 5, 6, 7
 KVC_F32, KVC_BF16 = 0, 1
 KVC_L2, KVC_L1 = 0, 1
+KVC_KEY_SUM, KVC_KEY_MAX = 0, 1
 KVC_ASYNC = 1
 
 EXPORTS = [
@@ -71,7 +72,7 @@ def lib() -> C.CDLL:
         L.kvc_block_free.argtypes = [cfgp, stp, P, C.POINTER(C.c_int64), P, P, I]
         L.kvc_append.argtypes = [cfgp, stp, P, P, P, I, I, P, P, I]
         L.kvc_paged_decode.argtypes = [cfgp, stp, P, P, I, I, I, P, P]
-        L.kvc_metric_reduce.argtypes = [cfgp, stp, P, P, P]
+        L.kvc_metric_reduce.argtypes = [cfgp, stp, P, I, P, P]
         L.kvc_evict_select.argtypes = [cfgp, stp, P, P, P, I, I, P, P, P, P, P, I]
         L.kvc_compact.argtypes = [cfgp, stp, P, P, P, P, P, I]
         L.kvc_set_decode_chunk.argtypes = [I]
@@ -196,9 +197,9 @@ def kvc_paged_decode(cfg, st, q, out, layer_begin, layer_end, accumulate_metric,
                                   _stream(stream)), "kvc_paged_decode")
 
 
-def kvc_metric_reduce(cfg, st, block_key, ws, stream=None):
-    _check(lib().kvc_metric_reduce(C.byref(cfg), C.byref(st), _ptr(block_key, torch.float32), _ptr(ws),
-                                   _stream(stream)), "kvc_metric_reduce")
+def kvc_metric_reduce(cfg, st, block_key, ws, stream=None, key_mode=KVC_KEY_SUM):
+    _check(lib().kvc_metric_reduce(C.byref(cfg), C.byref(st), _ptr(block_key, torch.float32), int(key_mode),
+                                   _ptr(ws), _stream(stream)), "kvc_metric_reduce")
 
 
 def kvc_evict_select(cfg, st, block_key, seg_offsets, budget, nseg, protect_tail_blocks, evict_flag,

@@ -17,8 +17,9 @@ enum { SS_PREFIX = 0, SS_REMAIN = 1, SS_CAND = 2, SS_TAKE = 3, SS_FIRSTG = 4 };
 // block keys
 // ---------------------------------------------------------------------------
 // One wavefront per head instance; lane -> logical block.  The b metrics of a
-// block are contiguous (64 bytes at b = 16) and are added left to right in f32.
-__global__ void __launch_bounds__(256) block_key_kernel(Dims D, const float* __restrict__ metric,
+// block are contiguous (64 bytes at b = 16) and are added left to right in f32
+// (key_mode KVC_KEY_SUM) or reduced to their maximum (KVC_KEY_MAX).
+__global__ void __launch_bounds__(256) block_key_kernel(Dims D, int key_mode, const float* __restrict__ metric,
                                                         const int32_t* __restrict__ table,
                                                         const int32_t* __restrict__ ctx,
                                                         float* __restrict__ key) {
@@ -34,7 +35,12 @@ __global__ void __launch_bounds__(256) block_key_kernel(Dims D, const float* __r
     if (u < nb) {
       const float* m = metric + (size_t)row[u] * D.b;
       const int fill = min(D.b, C - u * D.b);
-      for (int o = 0; o < fill; ++o) acc = acc + m[o];
+      if (key_mode == KVC_KEY_SUM) {
+        for (int o = 0; o < fill; ++o) acc = acc + m[o];
+      } else {
+        acc = m[0];
+        for (int o = 1; o < fill; ++o) acc = fmaxf(acc, m[o]);
+      }
     }
     krow[u] = acc;
   }
@@ -341,14 +347,15 @@ using namespace kvc;
 
 extern "C" {
 
-int kvc_metric_reduce(const kvc_config* cfg, const kvc_state* st, float* block_key, void* ws,
-                      void* stream) {
+int kvc_metric_reduce(const kvc_config* cfg, const kvc_state* st, float* block_key, int key_mode,
+                      void* ws, void* stream) {
   int rc = validate(cfg, st);
   if (rc != KVC_OK) return rc;
   if (!block_key || ((uintptr_t)block_key & 3)) return KVC_ERR_ARG;
+  if (key_mode != KVC_KEY_SUM && key_mode != KVC_KEY_MAX) return KVC_ERR_ARG;
   (void)ws;
   Dims D = dims_of(cfg);
-  hipLaunchKernelGGL(block_key_kernel, dim3((D.G + 3) / 4), dim3(256), 0, (hipStream_t)stream, D,
+  hipLaunchKernelGGL(block_key_kernel, dim3((D.G + 3) / 4), dim3(256), 0, (hipStream_t)stream, D, key_mode,
                      st->metric, st->block_table, st->ctx_len, block_key);
   KVC_LAUNCH_CHECK();
   return KVC_OK;

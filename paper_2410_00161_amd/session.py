@@ -52,8 +52,8 @@ class KvcSession:
         B.kvc_paged_decode(self.cfg, self.st, q, out, layer_begin, layer_end, accumulate_metric, self.ws)
         return out
 
-    def metric_reduce(self):
-        B.kvc_metric_reduce(self.cfg, self.st, self.block_key, self.ws)
+    def metric_reduce(self, key_mode=B.KVC_KEY_SUM):
+        B.kvc_metric_reduce(self.cfg, self.st, self.block_key, self.ws, key_mode=key_mode)
         return self.block_key
 
     def evict_select(self, budget, seg_offsets=None, protect_tail_blocks=1, block_key=None, flags=0):

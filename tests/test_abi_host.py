@@ -81,7 +81,8 @@ def test_entry_points_reject_bad_arguments_on_the_host():
     assert L.kvc_append(C.byref(cfg), C.byref(st), one, C.c_void_p(4104), None, 0, 1, one, None, 0) == B.KVC_ERR_ARG
     assert L.kvc_evict_select(C.byref(cfg), C.byref(st), one, None, one, 1, 1, one, one, one, one, None, 0) == B.KVC_ERR_ARG  # nseg != S
     assert L.kvc_evict_select(C.byref(cfg), C.byref(st), one, one, one, 3, 1, one, one, one, one, None, 0) == B.KVC_ERR_ARG  # nseg > S
-    assert L.kvc_metric_reduce(C.byref(cfg), C.byref(st), None, one, None) == B.KVC_ERR_ARG
+    assert L.kvc_metric_reduce(C.byref(cfg), C.byref(st), None, B.KVC_KEY_SUM, one, None) == B.KVC_ERR_ARG
+    assert L.kvc_metric_reduce(C.byref(cfg), C.byref(st), one, 7, one, None) == B.KVC_ERR_ARG
     st_bad = B.kvc_state(4097, 8192, 4096, None, 4096, 4096, 4096)
     assert B.kvc_validate(cfg, st_bad) == B.KVC_ERR_ARG
 

@@ -252,6 +252,9 @@ def test_block_keys_bit_exact():
     sess.block_key.fill_(123.0)
     got = sess.metric_reduce().cpu().numpy()
     np.testing.assert_array_equal(got.view(np.uint32), want.view(np.uint32))
+    want_max, _ = O.block_keys(st, cache.metric.numpy(), key="max")
+    got = sess.metric_reduce(key_mode=B.KVC_KEY_MAX).cpu().numpy()
+    np.testing.assert_array_equal(got.view(np.uint32), want_max.view(np.uint32))
 
 
 SELECT_CASES = [
@@ -261,6 +264,7 @@ SELECT_CASES = [
     ("heavy_ties", dict(pooled=False, protect=1, ties=True, frac=0.5)),
     ("pooled_ties_protect0", dict(pooled=True, protect=0, ties=True, frac=0.6)),
     ("budget_zero_and_huge", dict(pooled=False, protect=1, ties=False, frac=None)),
+    ("max_keys", dict(pooled=False, protect=1, ties=False, frac=0.5, key="max")),
 ]
 
 
@@ -274,8 +278,8 @@ def test_select_and_compact_bit_exact(name, kw):
         cache.metric = torch.randint(0, 2, cache.metric.shape, generator=g).float()
     st = oracle_state(cache)
     sess = session(cache)
-    key = sess.metric_reduce()
-    want_key, _ = O.block_keys(st, cache.metric.numpy())
+    key = sess.metric_reduce(key_mode=B.KVC_KEY_MAX if kw.get("key") == "max" else B.KVC_KEY_SUM)
+    want_key, _ = O.block_keys(st, cache.metric.numpy(), key=kw.get("key", "sum"))
     nb = -(-st.lens() // st.b)
     per_seq = nb.reshape(st.S, -1).sum(1)
     if kw["pooled"]:

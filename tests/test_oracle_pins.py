@@ -299,6 +299,48 @@ def test_block_keys_fill_rule_and_fp32_order():
         assert O.block_keys(s1)[0][0, 0] == np.float32(want)
 
 
+def test_block_keys_maximum_mode():
+    """Max keys: the largest metric among a block's real slots; and the bridge to the paper's
+    own schedule: when a head stores its KVs in ascending metric order (equal values aside),
+    block u IS row u of the sorted metric matrix, so its max key is that row's last column and
+    selecting blocks by max key evicts, head by head, as many blocks as the rank schedule
+    evicts rows."""
+    shape, cache, st = small_state(seed=9, L=150)
+    rng = np.random.default_rng(4)
+    real = np.zeros_like(st.metric, dtype=bool)
+    for g in range(st.G):
+        n, o = O.slots_of(st, g); real[n, o] = True
+    st.metric = rng.random(st.metric.shape)
+    st.metric[~real] = np.nan
+    key, key64 = O.block_keys(st, key="max")
+    for g in range(st.G):
+        n, o = O.slots_of(st, g)
+        vals = st.metric[n, o]
+        nb = -(-len(vals) // st.b)
+        for u in range(nb):
+            chunk = vals[u * st.b:(u + 1) * st.b]
+            assert key[g, u] == np.float32(max(chunk)) and key64[g, u] == max(chunk)
+        assert (key[g, nb:] == 0).all()
+    with pytest.raises(O.OracleError):
+        O.block_keys(st, key="mean")
+    # sorted heads of whole blocks: physical blocks by max key == rank rows
+    for g in range(st.G):
+        n, o = O.slots_of(st, g)
+        keep = (len(n) // st.b) * st.b          # whole blocks only, so no empty slots enter the rows
+        st.ctx_len.reshape(-1)[g] = keep
+        n, o = n[:keep], o[:keep]
+        st.metric[n, o] = np.sort(rng.random(keep))
+    key, _ = O.block_keys(st, key="max")
+    nb = st.lens() // st.b
+    budget = (nb.reshape(st.S, -1).sum(1) * 0.4).astype(np.int64)
+    flag, count, sel = O.evict_select(st, key, budget, None, 1)
+    rows, _, sel_r = O.rank_schedule(st, budget, None, 1)
+    np.testing.assert_array_equal(count, rows)
+    np.testing.assert_array_equal(sel, sel_r)
+    for g in range(st.G):                       # and they are each head's first blocks
+        assert flag[g, :count[g]].all() and not flag[g, count[g]:].any()
+
+
 # --- selection ----------------------------------------------------------------
 
 def _brute_force_select(cands, E):
