@@ -84,6 +84,8 @@ def main():
     ap.add_argument("--chunk", type=int, default=0, help="decode chunk tokens (0 = library default)")
     ap.add_argument("--cpu-heads", type=int, default=1024, help="head instances timed on the CPU oracle (0 = skip)")
     ap.add_argument("--workload", default="llama8b", choices=["llama8b", "llama70b"])
+    ap.add_argument("--kv-dtype", default="bf16", choices=["bf16", "fp8"],
+                    help="variant: K and V stored as OCP e4m3 bytes (queries stay bf16)")
     ap.add_argument("--evict-mode", default="block", choices=["block", "rank"],
                     help="block: physical blocks by summed metric; rank: the paper's rank-block schedule")
     ap.add_argument("--uniform", action="store_true", help="diagnostic: every head holds prompt/rho KVs")
@@ -118,13 +120,16 @@ def main():
     if args.workload == "llama8b":
         shape, ctx, seed = W.llama8b_decode(num_seqs=args.num_seqs, prompt=args.prompt, rho=args.rho,
                                             extra_tokens=extra)
-        name = (f"Llama-3.1-8B-shaped decode: 32 layers, 32q/8kv heads, d=128, bf16 KV, b=16, "
+        name = (f"Llama-3.1-8B-shaped decode: 32 layers, 32q/8kv heads, d=128, {args.kv_dtype} KV, b=16, "
                 f"{args.num_seqs} seqs x {args.prompt} prompt tokens, per-head retention log-uniform mean {args.rho:g}x")
     else:
         shape, ctx, seed = W.llama70b_decode(num_seqs=args.num_seqs, prompt=args.prompt, rho=args.rho,
                                              extra_tokens=extra)
-        name = (f"Llama-3.1-70B-shaped decode: 80 layers, 64q/8kv heads, d=128, bf16 KV, b=16, "
+        name = (f"Llama-3.1-70B-shaped decode: 80 layers, 64q/8kv heads, d=128, {args.kv_dtype} KV, b=16, "
                 f"{args.num_seqs} seqs x {args.prompt} prompt tokens, per-head retention log-uniform mean {args.rho:g}x")
+    if args.kv_dtype != "bf16":
+        import dataclasses
+        shape = dataclasses.replace(shape, kv_dtype=args.kv_dtype)
     if args.uniform:
         ctx = W.uniform_lengths(shape.G, int(args.prompt / args.rho))
         name += " [diagnostic: uniform lengths]"
@@ -237,7 +242,7 @@ def main():
     short_alg_s = short_alg[::prof_every][:len(chunk_ms)]
     ach = float(chunk_alg_s.mean() / (chunk_ms.mean() * 1e-3) / 1e9)
     traffic = read_traffic_note("decode_chunk_kernel_llama8b_pmc.txt") if args.workload == "llama8b" else None
-    roofline = {"bound": "hbm", "kernel": "decode_chunk_kernel<2,128,%d,b16,4> (long items)" % shape.group_size,
+    roofline = {"bound": "hbm", "kernel": "decode_chunk_kernel<%d,128,%d,b16,4> (long items)" % (shape.kv_bytes, shape.group_size),
                 "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
                 "traffic": traffic, "avg_kernel_ms": float(chunk_ms.mean()),
                 "algorithmic_bytes_per_launch": float(chunk_alg_s.mean()),
@@ -355,7 +360,7 @@ def main():
         "metric": "decode-attn HBM GB/s (% of peak) at 8x compression; eviction+compaction ms",
         "value": value, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16", "data": "synthetic",
+        "dtype": "bf16" if args.kv_dtype == "bf16" else "fp8 K/V (e4m3), bf16 q, f32 accumulation", "data": "synthetic",
         "config": {"workload": name, "placement": args.placement, "evict_every": args.evict_every,
                    "evict_mode": args.evict_mode,
                    "chunk_tokens": chunk_T, "head_instances": G,

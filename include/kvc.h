@@ -53,7 +53,10 @@ typedef enum {
   KVC_ERR_UNSUPPORTED = 7 /* shape outside what the kernels cover                */
 } kvc_status;
 
-enum { KVC_F32 = 0, KVC_BF16 = 1 };  /* kv_dtype                                  */
+/* kv_dtype.  KVC_FP8_E4M3: K and V (cache rows and appended rows) are OCP 8-bit floats,
+ * 4 exponent bits (bias 7), 3 mantissa bits, no infinities, 0x7f / 0xff = NaN, taken at
+ * face value (a caller with scale factors folds them into q and out); queries are bf16.  */
+enum { KVC_F32 = 0, KVC_BF16 = 1, KVC_FP8_E4M3 = 2 };
 enum { KVC_L2 = 0, KVC_L1 = 1 };     /* metric_mode: sum of p^2 (default) or of p */
 enum { KVC_KEY_SUM = 0, KVC_KEY_MAX = 1 };  /* key_mode of kvc_metric_reduce               */
 enum { KVC_ASYNC = 1 };              /* flags                                     */
@@ -69,7 +72,7 @@ typedef struct kvc_config {
   int32_t block_size;          /* b                                             */
   int32_t num_blocks;          /* N                                             */
   int32_t max_blocks_per_head; /* Lmax / b                                      */
-  int32_t kv_dtype;            /* KVC_F32 | KVC_BF16; q has the same type       */
+  int32_t kv_dtype;            /* KVC_F32 | KVC_BF16 (q has the same type) | KVC_FP8_E4M3 (q is bf16) */
   int32_t metric_mode;         /* KVC_L2 | KVC_L1                               */
 } kvc_config;
 
@@ -162,7 +165,7 @@ int kvc_append(const kvc_config* cfg, const kvc_state* st, const void* k_new,
 /* One decode step of paged attention with per-head tables (Preliminaries:
  * A = softmax(q K^T / sqrt d), out = A V; Method: "Block Layout and Parallel
  * Allocation") over layers [layer_begin, layer_end).
- * q [S, Lyr, Hq, d] kv_dtype, out [S, Lyr, Hq, d] f32; rows of other layers are
+ * q [S, Lyr, Hq, d] kv_dtype (bf16 for an 8-bit cache), out [S, Lyr, Hq, d] f32; rows of other layers are
  * neither read nor written.  Head instance g attends to its own ctx_len[g]
  * KVs; a head with no KV gets zeros.  When accumulate_metric != 0 every
  * attended slot's metric grows by the sum over the r query heads of its group

@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(HERE, "libkvc.so")
 
 KVC_OK, KVC_ERR_ARG, KVC_ERR_OOM, KVC_ERR_TABLE_FULL = 0, 1, 2, 3
 KVC_ERR_BUDGET, KVC_ERR_NUMERIC, KVC_ERR_HIP, KVC_ERR_UNSUPPORTED = 4, 5, 6, 7
-KVC_F32, KVC_BF16 = 0, 1
+KVC_F32, KVC_BF16, KVC_FP8_E4M3 = 0, 1, 2
 KVC_L2, KVC_L1 = 0, 1
 KVC_KEY_SUM, KVC_KEY_MAX = 0, 1
 KVC_ASYNC = 1
@@ -129,7 +129,7 @@ def _check(rc: int, where: str):
 def make_config(num_seqs, num_layers, num_kv_heads, group_size, head_dim, block_size,
                 num_blocks, max_blocks_per_head, kv_dtype, metric_mode=KVC_L2) -> kvc_config:
     if isinstance(kv_dtype, str):
-        kv_dtype = {"bf16": KVC_BF16, "f32": KVC_F32}[kv_dtype]
+        kv_dtype = {"bf16": KVC_BF16, "f32": KVC_F32, "fp8": KVC_FP8_E4M3}[kv_dtype]
     return kvc_config(num_seqs, num_layers, num_kv_heads, group_size, head_dim, block_size,
                       num_blocks, max_blocks_per_head, kv_dtype, metric_mode)
 

@@ -232,7 +232,7 @@ __global__ void __launch_bounds__(256) append_write_kernel(Dims D, int l0, int l
   const int C = ctx[g];
   const int blk = table[(size_t)g * D.maxb + C / D.b];
   const int o = C % D.b;
-  const size_t row_bytes = (size_t)D.d * (D.dtype == KVC_BF16 ? 2 : 4);
+  const size_t row_bytes = (size_t)D.d * kv_esz(D.dtype);
   const size_t slot = (size_t)blk * D.b + o;
   const int pieces = (int)(row_bytes / 16);
   for (int c = lane; c < 2 * pieces; c += 64) {

@@ -9,7 +9,7 @@ int validate(const kvc_config* c, const kvc_state* st) {
   if (c->num_seqs <= 0 || c->num_layers <= 0 || c->num_kv_heads <= 0 || c->group_size <= 0 ||
       c->head_dim <= 0 || c->block_size <= 0 || c->num_blocks <= 0 || c->max_blocks_per_head <= 0)
     return KVC_ERR_ARG;
-  if (c->kv_dtype != KVC_F32 && c->kv_dtype != KVC_BF16) return KVC_ERR_ARG;
+  if (c->kv_dtype != KVC_F32 && c->kv_dtype != KVC_BF16 && c->kv_dtype != KVC_FP8_E4M3) return KVC_ERR_ARG;
   if (c->metric_mode != KVC_L2 && c->metric_mode != KVC_L1) return KVC_ERR_ARG;
   // index arithmetic is 32-bit for head instances and table cells, 64-bit for slots
   const int64_t G = (int64_t)c->num_seqs * c->num_layers * c->num_kv_heads;
@@ -17,7 +17,7 @@ int validate(const kvc_config* c, const kvc_state* st) {
   if (G * c->max_blocks_per_head > (1ll << 40)) return KVC_ERR_UNSUPPORTED;
   if ((int64_t)c->num_blocks * c->block_size > (1ll << 40)) return KVC_ERR_UNSUPPORTED;
   if (c->group_size > 16 || c->head_dim > 512) return KVC_ERR_UNSUPPORTED;
-  const int esz = c->kv_dtype == KVC_BF16 ? 2 : 4;
+  const int esz = kv_esz(c->kv_dtype);
   if ((c->head_dim * esz) % 16 != 0) return KVC_ERR_UNSUPPORTED;  // rows are read 16 bytes at a time
   if (st) {
     if (!st->k_cache || !st->v_cache || !st->metric || !st->block_table || !st->ctx_len ||

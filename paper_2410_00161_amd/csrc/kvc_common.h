@@ -130,6 +130,10 @@ __device__ __forceinline__ uint4 load_stream16(const void* p) {
   return make_uint4(t.x, t.y, t.z, t.w);
 }
 
+// bytes of one K/V element, and of one query element (queries of an 8-bit cache are bf16)
+__host__ __device__ inline int kv_esz(int dtype) { return dtype == KVC_F32 ? 4 : dtype == KVC_BF16 ? 2 : 1; }
+__host__ __device__ inline int q_esz(int dtype) { return dtype == KVC_F32 ? 4 : 2; }
+
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
 __device__ __forceinline__ float bf16_to_f32(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }

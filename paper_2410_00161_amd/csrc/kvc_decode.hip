@@ -36,8 +36,12 @@ static int g_prof_cap = 0, g_prof_used = 0, g_prof_on = 1;
 typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 
 template <int ESZ> struct Row;
+// Q: the query elements that face one 16-byte piece of a K row; QSZ: bytes of a query element.
 template <> struct Row<2> {  // bf16: 8 elements in 16 bytes
   static constexpr int EPL = 8;
+  static constexpr int QSZ = 2;
+  typedef uint4 Q;
+  static __device__ __forceinline__ Q load_q(const char* qrow, int seg) { return *(const uint4*)(qrow + (size_t)seg * 16); }
   static __device__ __forceinline__ float dot(const uint4& a, const uint4& b) {
     float s = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a.x), __builtin_bit_cast(bf16x2_t, b.x), 0.0f, false);
     s = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a.y), __builtin_bit_cast(bf16x2_t, b.y), s, false);
@@ -52,6 +56,9 @@ template <> struct Row<2> {  // bf16: 8 elements in 16 bytes
 };
 template <> struct Row<4> {  // f32: 4 elements in 16 bytes
   static constexpr int EPL = 4;
+  static constexpr int QSZ = 4;
+  typedef uint4 Q;
+  static __device__ __forceinline__ Q load_q(const char* qrow, int seg) { return *(const uint4*)(qrow + (size_t)seg * 16); }
   static __device__ __forceinline__ float dot(const uint4& a, const uint4& b) {
     float s = __uint_as_float(a.x) * __uint_as_float(b.x);
     s = fmaf(__uint_as_float(a.y), __uint_as_float(b.y), s);
@@ -62,6 +69,42 @@ template <> struct Row<4> {  // f32: 4 elements in 16 bytes
   static __device__ __forceinline__ void widen(const uint4& a, float* f) {
     f[0] = __uint_as_float(a.x); f[1] = __uint_as_float(a.y);
     f[2] = __uint_as_float(a.z); f[3] = __uint_as_float(a.w);
+  }
+};
+
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+template <> struct Row<1> {  // OCP e4m3: 16 elements in 16 bytes, facing 16 bf16 query elements
+  static constexpr int EPL = 16;
+  static constexpr int QSZ = 2;
+  struct Q { uint4 lo, hi; };
+  static __device__ __forceinline__ Q load_q(const char* qrow, int seg) {
+    const uint4* p = (const uint4*)(qrow + (size_t)seg * 32);
+    return Q{p[0], p[1]};
+  }
+  // four 8-bit floats -> two packed bf16 pairs (exact: 3 mantissa bits fit in 7), then the
+  // same packed dot product as for a bf16 cache
+  static __device__ __forceinline__ float dot4(uint32_t k, uint32_t q01, uint32_t q23, float s) {
+    const f32x2_t a = __builtin_amdgcn_cvt_pk_f32_fp8((int)k, false);
+    const f32x2_t b = __builtin_amdgcn_cvt_pk_f32_fp8((int)k, true);
+    const uint32_t p01 = __builtin_amdgcn_perm(__float_as_uint(a.y), __float_as_uint(a.x), 0x07060302u);
+    const uint32_t p23 = __builtin_amdgcn_perm(__float_as_uint(b.y), __float_as_uint(b.x), 0x07060302u);
+    s = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, p01), __builtin_bit_cast(bf16x2_t, q01), s, false);
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, p23), __builtin_bit_cast(bf16x2_t, q23), s, false);
+  }
+  static __device__ __forceinline__ float dot(const uint4& a, const Q& q) {
+    float s = dot4(a.x, q.lo.x, q.lo.y, 0.0f);
+    s = dot4(a.y, q.lo.z, q.lo.w, s);
+    s = dot4(a.z, q.hi.x, q.hi.y, s);
+    return dot4(a.w, q.hi.z, q.hi.w, s);
+  }
+  static __device__ __forceinline__ void widen(const uint4& a, float* f) {
+    const uint32_t w[4] = {a.x, a.y, a.z, a.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const f32x2_t lo = __builtin_amdgcn_cvt_pk_f32_fp8((int)w[i], false);
+      const f32x2_t hi = __builtin_amdgcn_cvt_pk_f32_fp8((int)w[i], true);
+      f[4 * i] = lo.x; f[4 * i + 1] = lo.y; f[4 * i + 2] = hi.x; f[4 * i + 3] = hi.y;
+    }
   }
 };
 
@@ -142,6 +185,7 @@ __global__ void __launch_bounds__(NW * 64) decode_chunk_kernel(DecodeArgs A) {
   constexpr int NV = R * U;            // partial logits per lane before the butterfly
   constexpr int PER = NV >= LPT ? NV / LPT : 1;  // logits per lane after it
   constexpr size_t ROWB = (size_t)HD * ESZ;
+  constexpr size_t QROWB = (size_t)HD * Row<ESZ>::QSZ;
   static_assert(LPT >= 4 && LPT <= 32 && (16 % TPI) == 0, "row geometry");
 
   const int tid = threadIdx.x, lane = tid & 63, w = NW == 1 ? 0 : tid >> 6;
@@ -175,10 +219,9 @@ __global__ void __launch_bounds__(NW * 64) decode_chunk_kernel(DecodeArgs A) {
     const int32_t* row = A.table + (size_t)g * A.D.maxb + (t0 >> lb);
     for (int i = tid; i < nblk; i += NT) s_tab[i] = row[i];
   }
-  uint4 qv[R];
+  typename Row<ESZ>::Q qv[R];
 #pragma unroll
-  for (int hh = 0; hh < R; ++hh)
-    qv[hh] = *(const uint4*)(A.q + ((size_t)g * R + hh) * ROWB + (size_t)seg * 16);
+  for (int hh = 0; hh < R; ++hh) qv[hh] = Row<ESZ>::load_q(A.q + ((size_t)g * R + hh) * QROWB, seg);
   __syncthreads();
 
   // One 16-token group = U wavefront loads of 1 KiB each.  With b a multiple of 16 a group
@@ -508,12 +551,17 @@ __global__ void __launch_bounds__(256) decode_generic_kernel(DecodeArgs A) {
   float* s_red = s_q + R * HD;        // [4][16]
   float* s_ml = s_red + 4 * 16;       // [2][16]
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-  const bool bf = A.D.dtype == KVC_BF16;
-  const size_t rowb = (size_t)HD * (bf ? 2 : 4);
+  const int dt = A.D.dtype;
+  const size_t rowb = (size_t)HD * kv_esz(dt), qrowb = (size_t)HD * q_esz(dt);
   auto elem = [&](const char* base, size_t row_off, int k) -> float {
-    return bf ? bf16_to_f32(((const uint16_t*)(base + row_off))[k]) : ((const float*)(base + row_off))[k];
+    if (dt == KVC_BF16) return bf16_to_f32(((const uint16_t*)(base + row_off))[k]);
+    if (dt == KVC_F32) return ((const float*)(base + row_off))[k];
+    return __builtin_amdgcn_cvt_pk_f32_fp8((int)((const uint8_t*)(base + row_off))[k], false)[0];
   };
-  for (int i = tid; i < R * HD; i += 256) s_q[i] = elem(A.q, ((size_t)g * R + i / HD) * rowb, i % HD);
+  for (int i = tid; i < R * HD; i += 256) {
+    const char* qr = A.q + ((size_t)g * R + i / HD) * qrowb;
+    s_q[i] = dt == KVC_F32 ? ((const float*)qr)[i % HD] : bf16_to_f32(((const uint16_t*)qr)[i % HD]);
+  }
   __syncthreads();
   const int32_t* row = A.table + (size_t)g * A.D.maxb;
   float mx[16];
@@ -617,7 +665,7 @@ constexpr size_t kLdsLimit = 160 * 1024;  // gfx950: 160 KiB of LDS per workgrou
 
 // Whether the tiled kernels cover this shape, and with which chunk length and LDS size.
 static bool choose_chunk(const Dims& D, int gsel, int* T_out, size_t* lds_out, bool* small_call = nullptr) {
-  const int esz = D.dtype == KVC_BF16 ? 2 : 4;
+  const int esz = kv_esz(D.dtype);
   const int lpt = D.d * esz / 16;
   const int tpi = (lpt >= 1 && lpt <= 64) ? 64 / lpt : 0;
   bool tiled = (D.r == 1 || D.r == 2 || D.r == 4 || D.r == 8) && (D.d == 64 || D.d == 128) &&
@@ -759,7 +807,7 @@ int kvc_paged_decode(const kvc_config* cfg, const kvc_state* st, const void* q, 
   size_t lds = 0;
   bool small_call = false;
   bool tiled = choose_chunk(D, D.S * (layer_end - layer_begin) * D.Hk, &T, &lds, &small_call);
-  const int esz = D.dtype == KVC_BF16 ? 2 : 4;
+  const int esz = kv_esz(D.dtype);
   A.T = tiled ? T : (1 << 30);  // generic path: one "chunk" per head
   A.short_class = 16;
   A.Ts = 0;
@@ -793,6 +841,7 @@ int kvc_paged_decode(const kvc_config* cfg, const kvc_state* st, const void* q, 
   const size_t grid = bound_pool < bound_row ? bound_pool : bound_row;
   if (grid > 0x7fffffffull) return KVC_ERR_UNSUPPORTED;
   const int gs = A.gsel;   // a head ends in at most one item shorter than a chunk
+  if (esz == 1) return D.d == 64 ? launch_tiled_r<1, 64>(A, (int)grid, lds, gs, s) : launch_tiled_r<1, 128>(A, (int)grid, lds, gs, s);
   if (esz == 2) return D.d == 64 ? launch_tiled_r<2, 64>(A, (int)grid, lds, gs, s) : launch_tiled_r<2, 128>(A, (int)grid, lds, gs, s);
   return D.d == 64 ? launch_tiled_r<4, 64>(A, (int)grid, lds, gs, s) : launch_tiled_r<4, 128>(A, (int)grid, lds, gs, s);
 }

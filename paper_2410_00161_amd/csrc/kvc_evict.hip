@@ -301,7 +301,7 @@ __global__ void __launch_bounds__(256) compact_move_kernel(Dims D, char* __restr
   // evicted real KVs: flagged blocks are full except possibly the last one
   const int n_ev = e * b - (frow[nb - 1] ? nb * b - C : 0);
   const int T = C - n_ev;
-  const size_t row_bytes = (size_t)D.d * (D.dtype == KVC_BF16 ? 2 : 4);
+  const size_t row_bytes = (size_t)D.d * kv_esz(D.dtype);
   const int pieces = (int)(row_bytes / 16);
   const int grp = threadIdx.x >> 4, gl = threadIdx.x & 15;
   for (int j = T + grp; j < C; j += 16) {

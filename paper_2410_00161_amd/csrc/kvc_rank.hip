@@ -307,7 +307,7 @@ __global__ void __launch_bounds__(256) rank_compact_kernel(Dims D, char* __restr
     __syncthreads();
   }
   const int n_moves = nholes_s;
-  const size_t row_bytes = (size_t)D.d * (D.dtype == KVC_BF16 ? 2 : 4);
+  const size_t row_bytes = (size_t)D.d * kv_esz(D.dtype);
   const int pieces = (int)(row_bytes / 16);
   const int grp = tid >> 4, gl = tid & 15;
   for (int kk = grp; kk < n_moves; kk += 16) {

@@ -32,7 +32,7 @@ class Shape:
     block_size: int
     num_blocks: int
     max_blocks_per_head: int
-    kv_dtype: str = "bf16"  # "bf16" | "f32"
+    kv_dtype: str = "bf16"  # "bf16" | "f32" | "fp8" (OCP e4m3 K and V, bf16 queries)
 
     @property
     def G(self) -> int:
@@ -44,11 +44,15 @@ class Shape:
 
     @property
     def torch_dtype(self) -> torch.dtype:
-        return torch.bfloat16 if self.kv_dtype == "bf16" else torch.float32
+        return {"bf16": torch.bfloat16, "f32": torch.float32, "fp8": torch.float8_e4m3fn}[self.kv_dtype]
+
+    @property
+    def q_torch_dtype(self) -> torch.dtype:
+        return torch.float32 if self.kv_dtype == "f32" else torch.bfloat16
 
     @property
     def kv_bytes(self) -> int:
-        return 2 if self.kv_dtype == "bf16" else 4
+        return {"bf16": 2, "f32": 4, "fp8": 1}[self.kv_dtype]
 
 
 @dataclass
@@ -215,7 +219,11 @@ def make_cache(shape: Shape, ctx_len: torch.Tensor, seed: int, device="cpu",
     rows = heavy & (owner >= 0).unsqueeze(1)
     if bool(rows.any()):
         own = owner.unsqueeze(1).expand(N, b)[rows]
-        k[rows] = (heavy_scale * u[own]).to(dt)
+        vals = (heavy_scale * u[own]).to(dt)
+        if shape.kv_dtype == "fp8":   # 8-bit floats are moved as bytes: indexing knows no such type
+            k.view(torch.uint8)[rows] = vals.view(torch.uint8)
+        else:
+            k[rows] = vals
     if init_metric == "zero":
         metric = torch.zeros((N, b), device=dev, dtype=torch.float32)
     elif init_metric == "prefill":
@@ -235,12 +243,12 @@ def make_cache(shape: Shape, ctx_len: torch.Tensor, seed: int, device="cpu",
 
 
 def make_query(shape: Shape, seed: int, step: int = 0, device="cpu") -> torch.Tensor:
-    """Decode-step queries [S, Lyr, Hq, d] ~ N(0, 1) in the cache dtype."""
+    """Decode-step queries [S, Lyr, Hq, d] ~ N(0, 1) in the query dtype of the cache."""
     dev = torch.device(device)
     g = _gen(seed * 1_000_003 + 17 * step + 1, dev)
     q = torch.randn((shape.num_seqs, shape.num_layers, shape.num_q_heads, shape.head_dim),
                     generator=g, device=dev, dtype=torch.float32)
-    return q.to(shape.torch_dtype)
+    return q.to(shape.q_torch_dtype)
 
 
 def make_new_kv(shape: Shape, seed: int, step: int = 0, device="cpu"):
@@ -322,7 +330,10 @@ def gather_heads(cache: Cache, heads, q: torch.Tensor | None = None):
     new_table[rows >= 0] = torch.arange(total, dtype=torch.int32)
     small_shape = Shape(len(heads), 1, 1, sh.group_size, sh.head_dim, b, max(total, 1), maxb, sh.kv_dtype)
     dev_ids = src_ids.to(cache.k_cache.device)
-    take = lambda t: t[dev_ids].cpu() if total else t[:1].cpu()
+    def take(t):
+        if t.dtype == torch.float8_e4m3fn:   # moved as bytes
+            return take(t.view(torch.uint8)).view(torch.float8_e4m3fn)
+        return t[dev_ids].cpu() if total else t[:1].cpu()
     small = Cache(small_shape, take(cache.k_cache), take(cache.v_cache), take(cache.metric),
                   take(cache.pos), new_table.reshape(len(heads), 1, 1, maxb),
                   lens.to(torch.int32).reshape(len(heads), 1, 1),

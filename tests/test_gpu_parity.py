@@ -63,7 +63,22 @@ DECODE_CASES = [
     ("generic_b2", dict(r=4, d=128, kv_dtype="bf16", L=120, b=2), 0, B.KVC_L2),
     ("generic_r3", dict(r=3, d=64, kv_dtype="f32", L=200), 0, B.KVC_L1),
     ("generic_d32", dict(r=2, d=32, kv_dtype="bf16", L=200), 0, B.KVC_L2),
+    ("fp8_d128_r4", dict(r=4, d=128, kv_dtype="fp8", L=700), 0, B.KVC_L2),
+    ("fp8_d128_r4_split", dict(r=4, d=128, kv_dtype="fp8", L=700), 128, B.KVC_L2),
+    ("fp8_d128_r8", dict(r=8, d=128, kv_dtype="fp8", L=300), 64, B.KVC_L2),
+    ("fp8_d128_r1_L1", dict(r=1, d=128, kv_dtype="fp8", L=300), 0, B.KVC_L1),
+    ("fp8_d64_r2", dict(r=2, d=64, kv_dtype="fp8", L=400), 64, B.KVC_L2),
+    ("fp8_b8", dict(r=4, d=128, kv_dtype="fp8", L=200, b=8), 64, B.KVC_L2),
+    ("fp8_generic_b2", dict(r=4, d=128, kv_dtype="fp8", L=120, b=2), 0, B.KVC_L2),
 ]
+
+
+def poison(t, mask):
+    """NaN into the masked rows; 8-bit floats are written as the byte 0x7f, their NaN."""
+    if t.dtype == torch.float8_e4m3fn:
+        t.view(torch.uint8)[mask] = 0x7F
+    else:
+        t[mask] = float("nan")
 
 
 @pytest.mark.parametrize("name,kw,chunk,mode", DECODE_CASES, ids=[c[0] for c in DECODE_CASES])
@@ -80,8 +95,8 @@ def test_decode_matches_oracle(name, kw, chunk, mode):
     for g in range(st0.G):
         n, o = O.slots_of(st0, g)
         owner_real[torch.from_numpy(n), torch.from_numpy(o)] = True
-    cache.v_cache[~owner_real] = float("nan")
-    cache.k_cache[~owner_real] = float("nan")
+    poison(cache.v_cache, ~owner_real)
+    poison(cache.k_cache, ~owner_real)
     st = oracle_state(cache)
     q = W.make_query(shape, seed)
     want = O.paged_decode(st, q.double().numpy(), metric_mode="L2" if mode == B.KVC_L2 else "L1")
@@ -128,9 +143,10 @@ def test_decode_layer_range_and_no_metric():
     np.testing.assert_allclose(sess.cache.metric.cpu().numpy(), st.metric, rtol=0, atol=TOL)
 
 
-def test_decode_steps_accumulate_with_append():
-    say("append + decode x 20")
-    shape, ctx, seed = W.small_mixed(47, S=2, Lyr=2, Hk=2, r=4, d=128, L=100, extra_blocks=3)
+@pytest.mark.parametrize("kv_dtype", ["bf16", "fp8"])
+def test_decode_steps_accumulate_with_append(kv_dtype):
+    say("append + decode x 20", kv_dtype)
+    shape, ctx, seed = W.small_mixed(47, S=2, Lyr=2, Hk=2, r=4, d=128, L=100, extra_blocks=3, kv_dtype=kv_dtype)
     cache = W.make_cache(shape, ctx, seed)
     st = oracle_state(cache)
     sess = session(cache)

@@ -19,6 +19,7 @@ CASES = [
     ("ties_protect0_b2", dict(b=2, L=150), dict(pooled=False, protect=0, ties=True, frac=0.6)),
     ("budget_zero_and_huge", dict(b=16), dict(pooled=False, protect=1, ties=False, frac=None)),
     ("f32_d64", dict(b=16, kv_dtype="f32", d=64), dict(pooled=False, protect=1, ties=False, frac=0.3)),
+    ("fp8_d128", dict(b=16, kv_dtype="fp8"), dict(pooled=False, protect=1, ties=False, frac=0.4)),
 ]
 
 

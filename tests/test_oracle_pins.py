@@ -539,3 +539,20 @@ def test_scheduling_helpers_by_hand():
     check_allocator_invariants(st)
     with pytest.raises(O.OracleError):
         O.prefill_alloc(st, [1000, 0])                         # row too short / pool too small
+
+
+# --- 8-bit inputs -----------------------------------------------------------------
+
+def test_e4m3_bytes_decode_as_the_format_defines():
+    """The tests hand 8-bit caches to the oracle through torch's float8_e4m3fn conversion; this
+    pins that conversion to the format itself: 1 sign, 4 exponent (bias 7), 3 mantissa bits,
+    subnormals at exponent 0, no infinities, 0x7f and 0xff the only NaNs, largest value 448."""
+    got = torch.arange(256, dtype=torch.uint8).view(torch.float8_e4m3fn).to(torch.float64).numpy()
+    for byte in range(256):
+        s, e, m = byte >> 7, (byte >> 3) & 15, byte & 7
+        if e == 15 and m == 7:
+            assert math.isnan(got[byte])
+            continue
+        mag = (m / 8.0) * 2.0 ** -6 if e == 0 else (1.0 + m / 8.0) * 2.0 ** (e - 7)
+        assert got[byte] == (-mag if s else mag), byte
+    assert got[0x7E] == 448.0 and math.copysign(1.0, got[0x80]) == -1.0
