@@ -184,3 +184,53 @@ def test_llama8b_shape_rank_schedule_on_one_sequence():
     changed = rows.long() > 0
     assert bool((ctx_after[changed] % b == 0).all())        # heads that lost rows end on whole blocks
     assert torch.equal((ctx_after + b - 1) // b, nb - rows.long())
+
+
+@pytest.mark.parametrize("forced_chunk", [0, 1024], indirect=True)
+def test_llama70b_shape_long_heads_sampled(forced_chunk):
+    """One sequence of the 70B shape (80 layers x 8 KV heads, groups of 8 query heads, 131072
+    prompt tokens, mean 8x): heads of up to 131 K tokens are split into 64 chunks at the default
+    chunk length and into 128 with the forced one, past what the combine kernel keeps in LDS.
+    The longest, the shortest and a few random head instances are recomputed by the oracle."""
+    from paper_2410_00161_amd.session import KvcSession
+    print(f"[case] llama70b shape, one sequence, chunk setting {forced_chunk}", flush=True)
+    shape, ctx, seed = W.llama70b_decode(num_seqs=1, extra_tokens=32)
+    ctx[5] = 131072                         # a head that kept everything
+    dev = torch.device("cuda:0")
+    cache = W.make_cache(shape, ctx, seed, device=dev, placement="fragmented", init_metric="prefill")
+    sess = KvcSession(cache, device=dev)
+    del cache
+    chunk = B.kvc_get_decode_chunk(sess.cfg)
+    G, r, d = shape.G, shape.group_size, shape.head_dim
+    assert int(sess.cache.ctx_len.max()) >= 64 * chunk
+    c = sess.cache.ctx_len.reshape(-1).cpu()
+    order = torch.argsort(c)
+    g0 = torch.Generator().manual_seed(seed)
+    heads = sorted(set([5] + order[:2].tolist() + order[-2:].tolist() +
+                       torch.randperm(G, generator=g0)[:6].tolist()))
+    q = W.make_query(shape, seed, 0, dev)
+    small, q_small = W.gather_heads(sess.cache, heads, q)
+    st = oracle_state(small)
+    m_before = sess.cache.metric.clone()
+    out = sess.paged_decode(q)
+    torch.cuda.synchronize()
+    want = O.paged_decode(st, q_small.double().numpy())
+    got = out.reshape(G, r, d)[torch.tensor(heads, device=dev)].cpu().numpy()
+    np.testing.assert_allclose(got, want.reshape(len(heads), r, d), rtol=0, atol=TOL)
+    after, _ = W.gather_heads(sess.cache, heads)
+    for i in range(len(heads)):
+        n, o = O.slots_of(st, i)
+        np.testing.assert_allclose(after.metric.numpy()[n, o], st.metric[n, o], rtol=0, atol=TOL)
+    # every head's increments sum to between r / C and r; nothing lost metric
+    delta = (sess.cache.metric - m_before).double()
+    assert float(delta.min()) >= 0.0
+    table = sess.cache.block_table.reshape(G, -1).long()
+    owner = torch.full((shape.num_blocks,), G, dtype=torch.long, device=dev)
+    valid = table >= 0
+    owner[table[valid]] = torch.arange(G, device=dev).unsqueeze(1).expand_as(table)[valid]
+    per_head = torch.zeros(G + 1, dtype=torch.float64, device=dev)
+    per_head.index_add_(0, owner, delta.sum(1))
+    ctx_now = sess.cache.ctx_len.reshape(G).double()
+    assert bool((per_head[:G] <= r + 1e-3).all()) and bool((per_head[:G] >= r / ctx_now - 1e-3).all())
+    assert float(per_head[G]) == 0.0
+    assert bool(torch.isfinite(out).all())
