@@ -331,14 +331,7 @@ __global__ void __launch_bounds__(256) compact_move_kernel(Dims D, char* __restr
     free_map[row[u]] = 1;
     row[u] = -1;
   }
-  if (threadIdx.x == 0) {
-    ctx[g] = T;
-    atomicAdd(&header[HW_FREED], nb - nb2);
-  }
-}
-
-__global__ void publish_freed_kernel(const int32_t* header, int64_t* out) {
-  if (threadIdx.x == 0 && blockIdx.x == 0) out[0] = header[HW_STATUS] == KVC_OK ? header[HW_FREED] : 0;
+  if (threadIdx.x == 0) ctx[g] = T;   // nb - nb2 = e blocks went back
 }
 
 }  // namespace kvc
@@ -418,8 +411,6 @@ int kvc_compact(const kvc_config* cfg, const kvc_state* st, const uint8_t* evict
   Dims D = dims_of(cfg);
   Workspace W = carve(D, ws);
   hipStream_t s = (hipStream_t)stream;
-  hipLaunchKernelGGL(zero_words_kernel, dim3(1), dim3(64), 0, s, W.header + HW_FREED, 1);
-  KVC_LAUNCH_CHECK();
   hipLaunchKernelGGL(compact_scan_kernel, dim3((D.G + 3) / 4), dim3(256), 0, s, D, evict_flag, evict_count,
                      st->ctx_len, W.flag_scan, W.header);
   KVC_LAUNCH_CHECK();
@@ -430,7 +421,7 @@ int kvc_compact(const kvc_config* cfg, const kvc_state* st, const uint8_t* evict
                      evict_flag, evict_count, W.flag_scan, W.header);
   KVC_LAUNCH_CHECK();
   if (blocks_freed) {
-    hipLaunchKernelGGL(publish_freed_kernel, dim3(1), dim3(64), 0, s, W.header, blocks_freed);
+    hipLaunchKernelGGL(publish_freed_kernel, dim3(1), dim3(1024), 0, s, W.header, evict_count, D.G, blocks_freed);
     KVC_LAUNCH_CHECK();
   }
   return (flags & KVC_ASYNC) ? KVC_OK : finish_sync(W, s);
