@@ -34,6 +34,8 @@ static ProfilePair* g_prof = nullptr;
 static int g_prof_cap = 0, g_prof_used = 0, g_prof_on = 1;
 
 typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
 
 template <int ESZ> struct Row;
 // Q: the query elements that face one 16-byte piece of a K row; QSZ: bytes of a query element.
@@ -147,8 +149,16 @@ __device__ __forceinline__ void stash_load(const float* stash, size_t slot, floa
 constexpr int kDecodeThreads = 256;
 constexpr int kDecodeWaves = kDecodeThreads / 64;
 
-__host__ __device__ inline size_t decode_lds_bytes(int T, int R, int HD, int b, int waves = kDecodeWaves) {
-  return (size_t)T * R * 2                       // exp of every logit against its group's running max, 16-bit
+// A shape takes Q K^T to the matrix cores where the plain ALUs are the bound: 16-bit rows, eight
+// query heads per KV head, d = 128, blocks of a multiple of 16 tokens.
+__host__ __device__ constexpr bool decode_uses_mfma(int esz, int R, int HD, int b) {
+  return esz == 2 && R == 8 && HD == 128 && b % 16 == 0;
+}
+
+__host__ __device__ inline size_t decode_lds_bytes(int T, int R, int HD, int b, int waves = kDecodeWaves,
+                                                   bool mfma = false) {
+  return (mfma ? (size_t)waves * 16 * HD * 2 : 0)  // per-wavefront K tile on its way into operand order
+         + (size_t)T * R * 2                     // exp of every logit against its group's running max, 16-bit
          + (size_t)(T / 16) * R * 4              // that running max, per 16-token group and head
          + (size_t)waves * R * HD * 4            // per-wavefront un-normalised output
          + (size_t)waves * 16 * R * 4            // per-wavefront exp of the current group, f32
@@ -187,6 +197,15 @@ __global__ void __launch_bounds__(NW * 64) decode_chunk_kernel(DecodeArgs A) {
   constexpr size_t ROWB = (size_t)HD * ESZ;
   constexpr size_t QROWB = (size_t)HD * Row<ESZ>::QSZ;
   static_assert(LPT >= 4 && LPT <= 32 && (16 % TPI) == 0, "row geometry");
+  // Q K^T of a 16-token group on the matrix cores (v_mfma_f32_16x16x32_bf16: rows = query heads,
+  // columns = tokens, four steps of 32 dimensions).  K still arrives by contiguous 1 KiB loads
+  // (a load shaped like the operand is 12 % slower); a wavefront turns its tile into operand
+  // order through 4 KiB of LDS, cells XOR-swizzled so that neither side has a bank conflict.
+  // Head h sits in operand row 4 (h % 4) + h / 4, which leaves lane 16 a + t with the logits of
+  // token t against heads a and a + 4.
+  constexpr bool MF = B16 && decode_uses_mfma(ESZ, R, HD, 16);
+  constexpr int NVH = (R + 3) / 4;     // MF: logits per lane
+  constexpr int OWN = MF ? NVH : PER;
 
   const int tid = threadIdx.x, lane = tid & 63, w = NW == 1 ? 0 : tid >> 6;
   const int total_items = A.header[HW_TOTAL_ITEMS];
@@ -205,7 +224,8 @@ __global__ void __launch_bounds__(NW * 64) decode_chunk_kernel(DecodeArgs A) {
   const int b = A.D.b, lb = A.log2b;
 
   extern __shared__ __align__(16) char smem_raw[];
-  float* s_acc = (float*)smem_raw;                     // [waves][R][HD]
+  uint4* s_kt = (uint4*)smem_raw;                      // MF: [waves][16 tokens][16 cells of 16 bytes]
+  float* s_acc = (float*)(smem_raw + (MF ? (size_t)NW * 16 * HD * 2 : 0));  // [waves][R][HD]
   float* s_e = s_acc + NW * R * HD;          // [waves][16][R]
   float* s_red = s_e + NW * 16 * R;          // [2][waves][R]
   float* s_gm = s_red + 2 * NW * R;          // [T / 16][R]
@@ -219,9 +239,20 @@ __global__ void __launch_bounds__(NW * 64) decode_chunk_kernel(DecodeArgs A) {
     const int32_t* row = A.table + (size_t)g * A.D.maxb + (t0 >> lb);
     for (int i = tid; i < nblk; i += NT) s_tab[i] = row[i];
   }
-  typename Row<ESZ>::Q qv[R];
+  // VALU path: every head's q at this lane's dimensions.  MFMA path: A operand of step st: lane =
+  // (row lane % 16, dimensions 32 st + 8 (lane / 16) .. + 8); rows without a head are zero.
+  typename Row<ESZ>::Q qv[MF ? U : R];
+  if constexpr (MF) {
+    const int arow = lane & 15, ahead = (arow >> 2) + 4 * (arow & 3);
 #pragma unroll
-  for (int hh = 0; hh < R; ++hh) qv[hh] = Row<ESZ>::load_q(A.q + ((size_t)g * R + hh) * QROWB, seg);
+    for (int st = 0; st < U; ++st) {
+      const uint4 z = make_uint4(0, 0, 0, 0);
+      qv[st] = ahead < R ? *(const uint4*)(A.q + ((size_t)g * R + ahead) * QROWB + (size_t)st * 64 + (size_t)(lane >> 4) * 16) : z;
+    }
+  } else {
+#pragma unroll
+    for (int hh = 0; hh < R; ++hh) qv[hh] = Row<ESZ>::load_q(A.q + ((size_t)g * R + hh) * QROWB, seg);
+  }
   __syncthreads();
 
   // One 16-token group = U wavefront loads of 1 KiB each.  With b a multiple of 16 a group
@@ -253,57 +284,108 @@ __global__ void __launch_bounds__(NW * 64) decode_chunk_kernel(DecodeArgs A) {
 #pragma unroll
     for (int k = 0; k < EPL; ++k) acc[hh][k] = 0.0f;
   float m_run[R];            // running max per query head, the same in every lane
-  float m_own[PER], l_own[PER];  // this lane's head(s): running max and partial sum
+  float m_own[OWN], l_own[OWN];  // this lane's head(s): running max and partial sum
 #pragma unroll
   for (int hh = 0; hh < R; ++hh) m_run[hh] = -INFINITY;
 #pragma unroll
-  for (int i = 0; i < PER; ++i) { m_own[i] = -INFINITY; l_own[i] = 0.0f; }
+  for (int i = 0; i < OWN; ++i) { m_own[i] = -INFINITY; l_own[i] = 0.0f; }
   const int idx0 = (seg * NV) / LPT;
   float* my_e = s_e + w * 16 * R;
   const bool gm_writer = (lane & 60) == 0;  // lanes 0..3 hold every head between them
 
   auto process = [&](uint4 (&kcur)[U], uint4 (&vcur)[U], int grp) {
-      // logits of the group
-      float part[NV];
-#pragma unroll
-      for (int u = 0; u < U; ++u)
-#pragma unroll
-        for (int hh = 0; hh < R; ++hh) part[u * R + hh] = Row<ESZ>::dot(kcur[u], qv[hh]);
-      Butterfly<NV, LPT / 2>::run(part, lane);
-      float gm[PER];
-#pragma unroll
-      for (int i = 0; i < PER; ++i) {
-        const int u = (idx0 + i) / R;
-        const int tok = grp * 16 + u * TPI + sub;
-        part[i] = tok < n_tok ? part[i] * A.scale_log2 : -INFINITY;
-        // max over the group's tokens: the lanes that hold one head differ in lane bits 2..5
-        float m = part[i];
-        m = fmaxf(m, lane_xor<4>(m));
-        m = fmaxf(m, lane_xor<8>(m));
-        m = fmaxf(m, __shfl_xor(m, 16));
-        m = fmaxf(m, __shfl_xor(m, 32));
-        gm[i] = fmaxf(m, m_own[i]);
-      }
-      // exp of the group against the new running max; partial sums rescaled
-#pragma unroll
-      for (int i = 0; i < PER; ++i) {
-        const int idx = idx0 + i;
-        const int u = idx / R, hh = idx % R;
-        const int tl = u * TPI + sub;
-        const float e = __builtin_amdgcn_exp2f(part[i] - gm[i]);
-        l_own[i] = l_own[i] * __builtin_amdgcn_exp2f(m_own[i] - gm[i]) + e;
-        m_own[i] = gm[i];
-        my_e[tl * R + hh] = e;
-        s_q[(grp * 16 + tl) * R + hh] = (uint16_t)q16(e);
-        if (gm_writer) s_gm[grp * R + hh] = gm[i];
-      }
-      // new running max of every head, read from the lane that owns it; rescale on change
-      bool moved = false;
       float m_new[R];
+      bool moved = false;
+      if constexpr (MF) {
+        // this wavefront's K tile into operand order: cell (token, 16-byte piece c) sits at
+        // position c ^ token of the token's row
+        uint4* kt = s_kt + w * 256;
 #pragma unroll
-      for (int hh = 0; hh < R; ++hh) {
-        m_new[hh] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, gm[hh % PER]), (hh * 4) / R));
-        moved |= m_new[hh] > m_run[hh];
+        for (int u = 0; u < U; ++u) {
+          const int t = u * TPI + sub;
+          kt[t * 16 + (seg ^ t)] = kcur[u];
+        }
+        const int tl = lane & 15, hrow = lane >> 4;
+        f32x4_t sacc = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+        for (int st = 0; st < U; ++st) {
+          const uint4 kb = kt[tl * 16 + ((4 * st + hrow) ^ tl)];
+          sacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, qv[st]),
+                                                         __builtin_bit_cast(bf16x8_t, kb), sacc, 0, 0, 0);
+        }
+        const bool live = grp * 16 + tl < n_tok;
+        float x[NVH], gm[NVH], e[NVH];
+#pragma unroll
+        for (int v = 0; v < NVH; ++v) {
+          x[v] = live ? sacc[v] * A.scale_log2 : -INFINITY;
+          float m = x[v];   // max over the 16 tokens = over the 16 lanes of this row of lanes
+          m = fmaxf(m, lane_xor<1>(m));
+          m = fmaxf(m, lane_xor<2>(m));
+          m = fmaxf(m, lane_xor<4>(m));
+          m = fmaxf(m, lane_xor<8>(m));
+          gm[v] = fmaxf(m, m_own[v]);
+        }
+#pragma unroll
+        for (int v = 0; v < NVH; ++v) {
+          e[v] = __builtin_amdgcn_exp2f(x[v] - gm[v]);
+          l_own[v] = l_own[v] * __builtin_amdgcn_exp2f(m_own[v] - gm[v]) + e[v];
+          m_own[v] = gm[v];
+        }
+#pragma unroll
+        for (int v = 0; v < NVH; ++v) {
+          const int hh = hrow + 4 * v;
+          if (hh < R) {
+            my_e[tl * R + hh] = e[v];
+            s_q[(grp * 16 + tl) * R + hh] = (uint16_t)q16(e[v]);
+            if (tl == 0) s_gm[grp * R + hh] = gm[v];
+          }
+        }
+#pragma unroll
+        for (int hh = 0; hh < R; ++hh) {
+          m_new[hh] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, gm[hh / 4]), 16 * (hh % 4)));
+          moved |= m_new[hh] > m_run[hh];
+        }
+      } else {
+        // logits of the group
+        float part[NV];
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+          for (int hh = 0; hh < R; ++hh) part[u * R + hh] = Row<ESZ>::dot(kcur[u], qv[hh]);
+        Butterfly<NV, LPT / 2>::run(part, lane);
+        float gm[PER];
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
+          const int u = (idx0 + i) / R;
+          const int tok = grp * 16 + u * TPI + sub;
+          part[i] = tok < n_tok ? part[i] * A.scale_log2 : -INFINITY;
+          // max over the group's tokens: the lanes that hold one head differ in lane bits 2..5
+          float m = part[i];
+          m = fmaxf(m, lane_xor<4>(m));
+          m = fmaxf(m, lane_xor<8>(m));
+          m = fmaxf(m, __shfl_xor(m, 16));
+          m = fmaxf(m, __shfl_xor(m, 32));
+          gm[i] = fmaxf(m, m_own[i]);
+        }
+        // exp of the group against the new running max; partial sums rescaled
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
+          const int idx = idx0 + i;
+          const int u = idx / R, hh = idx % R;
+          const int tl = u * TPI + sub;
+          const float e = __builtin_amdgcn_exp2f(part[i] - gm[i]);
+          l_own[i] = l_own[i] * __builtin_amdgcn_exp2f(m_own[i] - gm[i]) + e;
+          m_own[i] = gm[i];
+          my_e[tl * R + hh] = e;
+          s_q[(grp * 16 + tl) * R + hh] = (uint16_t)q16(e);
+          if (gm_writer) s_gm[grp * R + hh] = gm[i];
+        }
+        // new running max of every head, read from the lane that owns it
+#pragma unroll
+        for (int hh = 0; hh < R; ++hh) {
+          m_new[hh] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, gm[hh % PER]), (hh * 4) / R));
+          moved |= m_new[hh] > m_run[hh];
+        }
       }
       if (moved) {
 #pragma unroll
@@ -354,22 +436,44 @@ __global__ void __launch_bounds__(NW * 64) decode_chunk_kernel(DecodeArgs A) {
     }
   }
   // ---- merge: token groups of one wavefront, then the wavefronts ----
+  if constexpr (MF) {
 #pragma unroll
-  for (int i = 0; i < PER; ++i) {
-    float l = l_own[i];
-    l += lane_xor<4>(l);
-    l += lane_xor<8>(l);
-    l += __shfl_xor(l, 16);
-    l += __shfl_xor(l, 32);
-    l_own[i] = l;
-  }
-  if (lane < 4) {
+    for (int v = 0; v < NVH; ++v) {   // sums over the 16 token lanes of a row of lanes
+      float l = l_own[v];
+      l += lane_xor<1>(l);
+      l += lane_xor<2>(l);
+      l += lane_xor<4>(l);
+      l += lane_xor<8>(l);
+      l_own[v] = l;
+    }
+    if ((lane & 15) == 0) {
+#pragma unroll
+      for (int v = 0; v < NVH; ++v) {
+        const int hh = (lane >> 4) + 4 * v;
+        if (hh < R) {
+          s_red[w * R + hh] = m_own[v];
+          s_red[(NW + w) * R + hh] = l_own[v];
+        }
+      }
+    }
+  } else {
 #pragma unroll
     for (int i = 0; i < PER; ++i) {
-      const int hh = (idx0 + i) % R;
-      if ((hh * 4) / R == lane) {
-        s_red[w * R + hh] = m_own[i];
-        s_red[(NW + w) * R + hh] = l_own[i];
+      float l = l_own[i];
+      l += lane_xor<4>(l);
+      l += lane_xor<8>(l);
+      l += __shfl_xor(l, 16);
+      l += __shfl_xor(l, 32);
+      l_own[i] = l;
+    }
+    if (lane < 4) {
+#pragma unroll
+      for (int i = 0; i < PER; ++i) {
+        const int hh = (idx0 + i) % R;
+        if ((hh * 4) / R == lane) {
+          s_red[w * R + hh] = m_own[i];
+          s_red[(NW + w) * R + hh] = l_own[i];
+        }
       }
     }
   }
@@ -640,7 +744,8 @@ static int launch_tiled(const DecodeArgs& A, int grid, size_t lds, int grid_shor
   KVC_LAUNCH_CHECK();
   if (pp) { KVC_HIP(hipEventRecord(pp->a1, s)); KVC_HIP(hipEventRecord(pp->s0, s)); }
   if (A.short_class < 16) {
-    hipLaunchKernelGGL(kern_short, dim3(grid_short), dim3(64), decode_lds_bytes(A.Ts, R, HD, A.D.b, 1), s, A);
+    hipLaunchKernelGGL(kern_short, dim3(grid_short), dim3(64),
+                       decode_lds_bytes(A.Ts, R, HD, A.D.b, 1, decode_uses_mfma(ESZ, R, HD, A.D.b)), s, A);
     KVC_LAUNCH_CHECK();
   }
   if (pp) { KVC_HIP(hipEventRecord(pp->s1, s)); KVC_HIP(hipEventRecord(pp->b0, s)); }
@@ -680,8 +785,9 @@ static bool choose_chunk(const Dims& D, int gsel, int* T_out, size_t* lds_out, b
     const long long want_items = 6144;
     while (T > 256 && (long long)gsel * (((long long)D.maxb * D.b + T - 1) / T) < want_items) T /= 2;
   }
-  while (T > kMinChunk && decode_lds_bytes(T, D.r, D.d, D.b) > kLdsLimit) T -= 64;
-  const size_t lds = decode_lds_bytes(T, D.r, D.d, D.b);
+  const bool mf = decode_uses_mfma(esz, D.r, D.d, D.b);
+  while (T > kMinChunk && decode_lds_bytes(T, D.r, D.d, D.b, kDecodeWaves, mf) > kLdsLimit) T -= 64;
+  const size_t lds = decode_lds_bytes(T, D.r, D.d, D.b, kDecodeWaves, mf);
   if (lds > kLdsLimit) return false;
   *T_out = T;
   *lds_out = lds;
