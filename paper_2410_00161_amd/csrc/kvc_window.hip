@@ -128,6 +128,8 @@ __global__ void __launch_bounds__(kWinThreads) window_stats_kernel(WindowArgs W)
       for (int kk = 0; kk < 4; ++kk) q[kk] = s_q[(ct * 4 + kk) * 64 + lane];
       const int rho = ct * 16 + (lane & 15);
       const int last_vis = min(first_free + rho / A.D.r, C - 1);  // query i sees keys 0 .. its position
+      // the running max stays in raw dot-product units inside the loop: the scale goes into one
+      // multiply-add per logit (max, fma, exp2, add)
       const float2 old = my_st[ct * 64];
       float s[16];
       float mx = old.x;
@@ -138,7 +140,7 @@ __global__ void __launch_bounds__(kWinThreads) window_stats_kernel(WindowArgs W)
         for (int kk = 0; kk < 4; ++kk) acc = mfma16(k[tg][kk], q[kk], acc);
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
-          float x = acc[v] * A.scale_log2;
+          float x = acc[v];
           if (masked) {
             const int j = t0 + tt + tg * 16 + 4 * (lane >> 4) + v;
             if (j > last_vis) x = -INFINITY;
@@ -148,9 +150,10 @@ __global__ void __launch_bounds__(kWinThreads) window_stats_kernel(WindowArgs W)
         }
       }
       if (mx > -INFINITY) {
-        float sum = old.y * __builtin_amdgcn_exp2f(old.x - mx);
+        const float off = -mx * A.scale_log2;
+        float sum = old.y * __builtin_amdgcn_exp2f(fmaf(old.x, A.scale_log2, off));
 #pragma unroll
-        for (int e = 0; e < 16; ++e) sum += __builtin_amdgcn_exp2f(s[e] - mx);
+        for (int e = 0; e < 16; ++e) sum += __builtin_amdgcn_exp2f(fmaf(s[e], A.scale_log2, off));
         my_st[ct * 64] = make_float2(mx, sum);
       }
     }
@@ -158,6 +161,7 @@ __global__ void __launch_bounds__(kWinThreads) window_stats_kernel(WindowArgs W)
   // merge the four lanes that share a query row, then the wavefronts, then write the chunk's pair
   for (int ct = 0; ct < NT; ++ct) {
     float2 st = my_st[ct * 64];
+    st.x *= A.scale_log2;   // from here on maxima are in scaled log2 units
 #pragma unroll
     for (int msk = 16; msk <= 32; msk <<= 1) {
       const float om = __shfl_xor(st.x, msk), ol = __shfl_xor(st.y, msk);
@@ -186,7 +190,7 @@ __global__ void __launch_bounds__(kWinThreads) window_stats_kernel(WindowArgs W)
 }
 
 // Pass 2: raw[j] = sum over query rows of p^2 (or p), p normalised with the head's max and sum.
-template <int NT>
+template <int NT, bool L2>
 __global__ void __launch_bounds__(kWinThreads) window_sum_kernel(WindowArgs W) {
   const DecodeArgs& A = W.A;
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
@@ -200,7 +204,7 @@ __global__ void __launch_bounds__(kWinThreads) window_sum_kernel(WindowArgs W) {
     return;
   extern __shared__ __align__(16) char smem_raw[];
   uint4* s_q = (uint4*)smem_raw;                        // [NT * 4 * 64]
-  float* s_ml = (float*)(s_q + NT * 4 * 64);            // [NT * 16][2]: max, 1 / sum (0 for rows that see nothing)
+  float* s_ml = (float*)(s_q + NT * 4 * 64);            // [NT * 16]: max + log2(sum) per query row (inf: the row adds nothing)
   int* s_tab = (int*)((float2*)(s_ml + kWinWaves * NT * 16 * 2) + kWinWaves * NT * 64);  // same carve as pass 1
   const int b = A.D.b, lb = A.log2b;
   const int C = A.ctx[g];
@@ -219,14 +223,14 @@ __global__ void __launch_bounds__(kWinThreads) window_sum_kernel(WindowArgs W) {
       if (nm > -INFINITY) ll = ll * __builtin_amdgcn_exp2f(mm - nm) + ol * __builtin_amdgcn_exp2f(om - nm);
       mm = nm;
     }
-    s_ml[rho * 2 + 0] = mm;
-    s_ml[rho * 2 + 1] = (rho < W.rows && ll > 0.0f) ? 1.0f / ll : 0.0f;
+    // p = exp2(logit - max) / sum = exp2(logit - (max + log2 sum)); padded rows and rows that see
+    // no key get +inf there, so that their p is exactly 0
+    s_ml[rho] = (rho < W.rows && ll > 0.0f) ? mm + __builtin_amdgcn_logf(ll) : INFINITY;
   }
   __syncthreads();
   const int first_free = W.first_pos >= 0 ? W.first_pos : C - W.w;
   const int free_lim = min(first_free, C - 1) - W.exclude;   // keys up to here count for every query
   const bool dead = t0 > min(first_free + W.w - 1, C - 1) - W.exclude;  // the chunk gets nothing
-  const bool l2 = A.D.mode == KVC_L2;
   if (dead) {
     for (int t = tid; t < n_tok; t += kWinThreads)
       if (t0 + t < C) W.raw[((size_t)s_tab[t >> lb] << lb) + (t & (b - 1))] = 0.0f;
@@ -246,7 +250,7 @@ __global__ void __launch_bounds__(kWinThreads) window_sum_kernel(WindowArgs W) {
       for (int kk = 0; kk < 4; ++kk) q[kk] = s_q[(ct * 4 + kk) * 64 + lane];
       const int rho = ct * 16 + (lane & 15);
       const int last_vis = min(first_free + rho / A.D.r, C - 1) - W.exclude;
-      const float m_row = s_ml[rho * 2], il_row = s_ml[rho * 2 + 1];
+      const float c_row = s_ml[rho];
 #pragma unroll
       for (int tg = 0; tg < 4; ++tg) {
         f32x4_t acc = {0.0f, 0.0f, 0.0f, 0.0f};
@@ -254,13 +258,12 @@ __global__ void __launch_bounds__(kWinThreads) window_sum_kernel(WindowArgs W) {
         for (int kk = 0; kk < 4; ++kk) acc = mfma16(k[tg][kk], q[kk], acc);
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
-          float p = __builtin_amdgcn_exp2f(acc[v] * A.scale_log2 - m_row) * il_row;
+          float p = __builtin_amdgcn_exp2f(fmaf(acc[v], A.scale_log2, -c_row));
           if (masked) {
             const int j = t0 + tt + tg * 16 + 4 * (lane >> 4) + v;
             if (j > last_vis) p = 0.0f;
           }
-          if (il_row == 0.0f) p = 0.0f;  // padded rows, and rows that see no key (NaN from inf - inf)
-          tok[tg * 4 + v] += l2 ? p * p : p;
+          tok[tg * 4 + v] = L2 ? fmaf(p, p, tok[tg * 4 + v]) : tok[tg * 4 + v] + p;
         }
       }
     }
@@ -302,12 +305,14 @@ static int launch_window(const WindowArgs& W, int grid, hipStream_t s) {
   static bool told = false;
   if (lds > 64 * 1024 && !told) {
     KVC_HIP(hipFuncSetAttribute((const void*)window_stats_kernel<NT>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    KVC_HIP(hipFuncSetAttribute((const void*)window_sum_kernel<NT>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    KVC_HIP(hipFuncSetAttribute((const void*)window_sum_kernel<NT, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    KVC_HIP(hipFuncSetAttribute((const void*)window_sum_kernel<NT, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     told = true;
   }
   hipLaunchKernelGGL(window_stats_kernel<NT>, dim3(grid), dim3(kWinThreads), lds, s, W);
   KVC_LAUNCH_CHECK();
-  hipLaunchKernelGGL(window_sum_kernel<NT>, dim3(grid), dim3(kWinThreads), lds, s, W);
+  if (W.A.D.mode == KVC_L2) hipLaunchKernelGGL((window_sum_kernel<NT, true>), dim3(grid), dim3(kWinThreads), lds, s, W);
+  else hipLaunchKernelGGL((window_sum_kernel<NT, false>), dim3(grid), dim3(kWinThreads), lds, s, W);
   KVC_LAUNCH_CHECK();
   return KVC_OK;
 }
