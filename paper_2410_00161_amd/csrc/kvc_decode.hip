@@ -126,9 +126,9 @@ __device__ __forceinline__ void stash_store(float* stash, size_t slot, const flo
     uint32_t wds[R / 2];
 #pragma unroll
     for (int i = 0; i < R / 2; ++i) wds[i] = q16(e[2 * i]) | (q16(e[2 * i + 1]) << 16);
-    if constexpr (R == 2) *(uint32_t*)base = wds[0];
-    else if constexpr (R == 4) *(uint2*)base = make_uint2(wds[0], wds[1]);
-    else *(uint4*)base = make_uint4(wds[0], wds[1], wds[2], wds[3]);
+    if constexpr (R == 2) __builtin_nontemporal_store(wds[0], (uint32_t*)base);
+    else if constexpr (R == 4) { typedef unsigned int u2 __attribute__((ext_vector_type(2))); u2 t = {wds[0], wds[1]}; __builtin_nontemporal_store(t, (u2*)base); }
+    else { typedef unsigned int u4 __attribute__((ext_vector_type(4))); u4 t = {wds[0], wds[1], wds[2], wds[3]}; __builtin_nontemporal_store(t, (u4*)base); }
   }
 }
 template <int R>
@@ -138,9 +138,9 @@ __device__ __forceinline__ void stash_load(const float* stash, size_t slot, floa
     e[0] = unq16(*base);
   } else {
     uint32_t wds[R / 2];
-    if constexpr (R == 2) wds[0] = *(const uint32_t*)base;
-    else if constexpr (R == 4) { const uint2 t = *(const uint2*)base; wds[0] = t.x; wds[1] = t.y; }
-    else { const uint4 t = *(const uint4*)base; wds[0] = t.x; wds[1] = t.y; wds[2] = t.z; wds[3] = t.w; }
+    if constexpr (R == 2) wds[0] = __builtin_nontemporal_load((const uint32_t*)base);
+    else if constexpr (R == 4) { typedef unsigned int u2 __attribute__((ext_vector_type(2))); const u2 t = __builtin_nontemporal_load((const u2*)base); wds[0] = t.x; wds[1] = t.y; }
+    else { const uint4 t = load_stream16(base); wds[0] = t.x; wds[1] = t.y; wds[2] = t.z; wds[3] = t.w; }
 #pragma unroll
     for (int i = 0; i < R / 2; ++i) { e[2 * i] = unq16(wds[i] & 0xffffu); e[2 * i + 1] = unq16(wds[i] >> 16); }
   }
@@ -515,8 +515,8 @@ __global__ void __launch_bounds__(NW * 64) decode_chunk_kernel(DecodeArgs A) {
       float s = 0.0f;
 #pragma unroll
       for (int ww = 0; ww < NW; ++ww) s += s_acc[(ww * R + hh) * HD + k] * wsc[ww][hh];
-      if (single) A.out[((size_t)g * R + hh) * HD + k] = s / cl[hh];
-      else A.part_acc[(pslot * R + hh) * HD + k] = s;
+      if (single) __builtin_nontemporal_store(s / cl[hh], &A.out[((size_t)g * R + hh) * HD + k]);
+      else __builtin_nontemporal_store(s, &A.part_acc[(pslot * R + hh) * HD + k]);
     }
   }
   if (!single && tid == 0) {
@@ -777,7 +777,7 @@ static bool choose_chunk(const Dims& D, int gsel, int* T_out, size_t* lds_out, b
                tpi >= 1 && D.b % tpi == 0 && 64 % D.b == 0;
   if (!tiled) return false;
   // default: a chunk that lets two workgroups share a CU
-  int T = g_chunk_tokens ? g_chunk_tokens : (D.r >= 8 ? 2048 : 6144);
+  int T = g_chunk_tokens ? g_chunk_tokens : (D.r >= 8 ? 2560 : 6144);
   const int T_default = T;
   if (!g_chunk_tokens) {
     // a call over few head instances (one layer at a time) has too few long chunks to fill the
