@@ -366,6 +366,7 @@ def main():
                    "chunk_tokens": chunk_T, "head_instances": G,
                    "mean_kvs_per_step": float(kv_per_step.mean())},
         "frac_of_hbm_peak": value / HBM_PEAK_GBS,
+        "kv_only_GBps": float(kv_per_step.sum()) * 2 * shape.head_dim * shape.kv_bytes / (ms_total * 1e-3) / 1e9,
         "decode_steps_per_s": 1e3 / ms_step,
         "decode_only_ms_per_step_one_call_per_layer": per_layer_ms,
         "decode_only_ms_per_step_one_call_per_layer_hip_graph": per_layer_graph_ms,
