@@ -440,3 +440,48 @@ def test_scheduling_helpers_match_oracle():
     with pytest.raises(B.KvcError):
         B.kvc_prefill_alloc(sess.cfg, sess.st, huge.to(dev), sess.ws)
     assert_state_equal(sess, st, kv_exact=False)
+
+
+# ---------------------------------------------------------------------------
+# degenerate: nothing cached at all
+# ---------------------------------------------------------------------------
+
+def test_empty_cache_every_call_then_first_tokens():
+    """No head holds a KV: decode writes zero rows and leaves the metric alone, block keys are
+    zero, selection and both compactions take and free nothing; then the first tokens arrive
+    (every head allocates its first block) and a decode over one KV per head returns that V."""
+    say("all heads empty")
+    shape, ctx, seed = W.small_mixed(83, S=2, Lyr=2, Hk=3, r=4, d=128, L=100)
+    cache = W.make_cache(shape, torch.zeros_like(ctx), seed, init_metric="prefill")
+    st = oracle_state(cache)
+    sess = session(cache)
+    q = W.make_query(shape, seed)
+    sess.out.fill_(3.0)
+    m0 = sess.cache.metric.clone()
+    out = sess.paged_decode(q.to(sess.device))
+    torch.cuda.synchronize()
+    assert float(out.abs().max()) == 0.0 and torch.equal(sess.cache.metric, m0)
+    np.testing.assert_array_equal(out.cpu().numpy(), O.paged_decode(st, q.double().numpy()))
+    assert float(sess.metric_reduce().abs().max()) == 0.0
+    budget = torch.full((shape.num_seqs,), 5, dtype=torch.int32)
+    flag, count, sel = sess.evict_select(budget)
+    assert int(flag.sum()) == 0 and int(count.sum()) == 0 and int(sel.sum()) == 0
+    assert int(sess.compact().item()) == 0
+    rows, sel = sess.evict_rank_select(budget)
+    assert int(rows.sum()) == 0 and int(sel.sum()) == 0
+    assert int(sess.compact_rank().item()) == 0
+    assert_state_equal(sess, st)
+    for step in range(2):
+        k, v = W.make_new_kv(shape, seed, step)
+        O.append(st, k.double().numpy(), v.double().numpy())
+        sess.append(k.to(sess.device), v.to(sess.device))
+        want = O.paged_decode(st, q.double().numpy())
+        out = sess.paged_decode(q.to(sess.device))
+        torch.cuda.synchronize()
+        np.testing.assert_allclose(out.cpu().numpy(), want, rtol=0, atol=TOL)
+        if step == 0:   # one KV per head: the output is that V row, whatever q is
+            r = shape.group_size
+            vv = v.float().unsqueeze(3).expand(-1, -1, -1, r, -1).reshape(out.shape)
+            np.testing.assert_allclose(out.cpu().numpy(), vv.numpy(), rtol=0, atol=1e-6)
+    assert_state_equal(sess, st)
+    check_allocator_invariants(st)
