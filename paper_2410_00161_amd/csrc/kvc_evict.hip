@@ -96,9 +96,12 @@ __device__ __forceinline__ uint32_t key_bits(float f) {
 }
 
 // Histogram of the current 8-bit digit over the candidates that still match the
-// prefix found so far.  Four head instances per workgroup, one wavefront each;
-// pass 0 also counts candidates and checks the keys.
-__global__ void __launch_bounds__(256) select_hist_kernel(Dims D, int pass, int protect,
+// prefix found so far.  A wavefront takes heads_per_wave consecutive head instances (four
+// wavefronts per workgroup) and adds their digits to the segment's histogram together; pass 0
+// also counts candidates and checks the keys.  In pass 0 (the exponent byte) nearly all keys of
+// a segment share one digit, and adds to one global word from all over the chip run one after
+// the other: there a wavefront takes several heads, later passes one.
+__global__ void __launch_bounds__(256) select_hist_kernel(Dims D, int pass, int protect, int heads_per_wave,
                                                           const float* __restrict__ key,
                                                           const int32_t* __restrict__ ctx,
                                                           const int32_t* __restrict__ seq_seg,
@@ -107,38 +110,41 @@ __global__ void __launch_bounds__(256) select_hist_kernel(Dims D, int pass, int 
                                                           int32_t* __restrict__ header) {
   __shared__ int hist[4][256];
   const int wid = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  for (int i = lane; i < 256; i += 64) hist[wid][i] = 0;
-  __syncthreads();
-  const int g = blockIdx.x * 4 + wid;
-  int sg = 0;
-  if (g < D.G) {
-    sg = seq_seg[g / (D.Lyr * D.Hk)];
+  int* my = hist[wid];   // written and read by this wavefront only
+  for (int i = lane; i < 256; i += 64) my[i] = 0;
+  const int g_first = (blockIdx.x * 4 + wid) * heads_per_wave;
+  const int g_end = min(D.G, g_first + heads_per_wave);
+  const int shift = 24 - 8 * pass;
+  int cur_sg = -1, cand_acc = 0;
+  bool bad = false;
+  auto flush = [&]() {
+    if (cur_sg < 0) return;
+    for (int i = lane; i < 256; i += 64) {
+      const int c = my[i];
+      if (c) { atomicAdd(&seg_hist[cur_sg * 256 + i], c); my[i] = 0; }
+    }
+    if (pass == 0 && lane == 0 && cand_acc) atomicAdd(&seg_state[cur_sg * 8 + SS_CAND], cand_acc);
+    cand_acc = 0;
+  };
+  for (int g = g_first; g < g_end; ++g) {
+    const int sg = seq_seg[g / (D.Lyr * D.Hk)];
+    if (sg != cur_sg) { flush(); cur_sg = sg; }
     const int C = ctx[g];
     const int ncand = max(0, (C + D.b - 1) / D.b - protect);
-    const int shift = 24 - 8 * pass;
+    cand_acc += ncand;
     const uint32_t prefix = (uint32_t)seg_state[sg * 8 + SS_PREFIX];
     const bool live = pass == 0 || seg_state[sg * 8 + SS_TAKE] > 0;
     const float* krow = key + (size_t)g * D.maxb;
-    bool bad = false;
     if (live) {
       for (int u = lane; u < ncand; u += 64) {
         const uint32_t k = key_bits(krow[u]);
         if (pass == 0) bad |= k >= 0x7f800000u;
-        if (pass == 0 || (k >> (shift + 8)) == prefix) atomicAdd(&hist[wid][(k >> shift) & 255], 1);
+        if (pass == 0 || (k >> (shift + 8)) == prefix) atomicAdd(&my[(k >> shift) & 255], 1);
       }
     }
-    if (pass == 0) {
-      if (lane == 0 && ncand > 0) atomicAdd(&seg_state[sg * 8 + SS_CAND], ncand);
-      if (__any(bad) && lane == 0) atomicOr(&header[HW_SCRATCH0], EB_NUMERIC);
-    }
   }
-  __syncthreads();
-  if (g < D.G) {
-    for (int i = lane; i < 256; i += 64) {
-      int c = hist[wid][i];
-      if (c) atomicAdd(&seg_hist[sg * 256 + i], c);
-    }
-  }
+  flush();
+  if (pass == 0 && __any(bad) && lane == 0) atomicOr(&header[HW_SCRATCH0], EB_NUMERIC);
 }
 
 // One workgroup per segment: choose the digit that holds the E-th smallest key.
@@ -379,8 +385,9 @@ int kvc_evict_select(const kvc_config* cfg, const kvc_state* st, const float* bl
                      evict_flag, nflag);
   KVC_LAUNCH_CHECK();
   for (int pass = 0; pass < 4; ++pass) {
-    hipLaunchKernelGGL(select_hist_kernel, dim3(gw), dim3(256), 0, s, D, pass, protect_tail_blocks,
-                       block_key, st->ctx_len, seq_seg, W.seg_hist, W.seg_state, W.header);
+    const int hpw = pass == 0 ? 8 : 1;
+    hipLaunchKernelGGL(select_hist_kernel, dim3((D.G + 4 * hpw - 1) / (4 * hpw)), dim3(256), 0, s, D, pass,
+                       protect_tail_blocks, hpw, block_key, st->ctx_len, seq_seg, W.seg_hist, W.seg_state, W.header);
     KVC_LAUNCH_CHECK();
     hipLaunchKernelGGL(select_pick_kernel, dim3(nseg), dim3(256), 0, s, pass, budget, W.seg_hist,
                        W.seg_state, W.header);
