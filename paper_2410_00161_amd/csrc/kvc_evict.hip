@@ -35,7 +35,15 @@ __global__ void __launch_bounds__(256) block_key_kernel(Dims D, int key_mode, co
     if (u < nb) {
       const float* m = metric + (size_t)row[u] * D.b;
       const int fill = min(D.b, C - u * D.b);
-      if (key_mode == KVC_KEY_SUM) {
+      if (fill == D.b && (D.b & 3) == 0) {   // a full block: 16-byte loads, the same order of additions
+        const bool sum = key_mode == KVC_KEY_SUM;
+        acc = sum ? 0.0f : m[0];
+        for (int o = 0; o < fill; o += 4) {
+          const float4 v = *(const float4*)(m + o);
+          if (sum) acc = (((acc + v.x) + v.y) + v.z) + v.w;
+          else acc = fmaxf(fmaxf(acc, v.x), fmaxf(v.y, fmaxf(v.z, v.w)));
+        }
+      } else if (key_mode == KVC_KEY_SUM) {
         for (int o = 0; o < fill; ++o) acc = acc + m[o];
       } else {
         acc = m[0];
