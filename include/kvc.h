@@ -26,6 +26,9 @@
  *     KVC_ASYNC in `flags` skips that wait: the call returns KVC_OK at once,
  *     later launches that depend on a failed step become no-ops, and the code
  *     is read later with kvc_poll_status().
+ *   - Host side, the library keeps a little process-wide state (the tuning and
+ *     profiling switches below, what it has told the runtime about its kernels):
+ *     call it from one host thread at a time.
  *   - Head instance g = (s * num_layers + l) * num_kv_heads + h; G = S*Lyr*Hk.
  *     Query head hq of a layer belongs to KV head hq / group_size.
  *   - A head instance holds the blocks block_table[g][0 .. held), held = the
