@@ -84,6 +84,8 @@ def main():
     ap.add_argument("--chunk", type=int, default=0, help="decode chunk tokens (0 = library default)")
     ap.add_argument("--cpu-heads", type=int, default=1024, help="head instances timed on the CPU oracle (0 = skip)")
     ap.add_argument("--workload", default="llama8b", choices=["llama8b", "llama70b"])
+    ap.add_argument("--block-size", type=int, default=16, choices=[16, 32, 64],
+                    help="variant (llama8b workload): tokens per cache block")
     ap.add_argument("--kv-dtype", default="bf16", choices=["bf16", "fp8"],
                     help="variant: K and V stored as OCP e4m3 bytes (queries stay bf16)")
     ap.add_argument("--evict-mode", default="block", choices=["block", "rank"],
@@ -119,8 +121,8 @@ def main():
     extra = total_steps + 2 * args.evict_every + 16
     if args.workload == "llama8b":
         shape, ctx, seed = W.llama8b_decode(num_seqs=args.num_seqs, prompt=args.prompt, rho=args.rho,
-                                            extra_tokens=extra)
-        name = (f"Llama-3.1-8B-shaped decode: 32 layers, 32q/8kv heads, d=128, {args.kv_dtype} KV, b=16, "
+                                            extra_tokens=extra, block_size=args.block_size)
+        name = (f"Llama-3.1-8B-shaped decode: 32 layers, 32q/8kv heads, d=128, {args.kv_dtype} KV, b={args.block_size}, "
                 f"{args.num_seqs} seqs x {args.prompt} prompt tokens, per-head retention log-uniform mean {args.rho:g}x")
     else:
         shape, ctx, seed = W.llama70b_decode(num_seqs=args.num_seqs, prompt=args.prompt, rho=args.rho,

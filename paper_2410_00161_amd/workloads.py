@@ -275,9 +275,9 @@ def tiny_ref(seed: int = 1001):
 
 
 def llama8b_decode(seed: int = 1002, num_seqs: int = 64, prompt: int = 8192,
-                   rho: float = 8.0, extra_tokens: int = 160):
-    """32 layers, 32 q / 8 KV heads, d = 128, bf16, b = 16; log-uniform retention."""
-    S, Lyr, Hk, r, d, b = num_seqs, 32, 8, 4, 128, 16
+                   rho: float = 8.0, extra_tokens: int = 160, block_size: int = 16):
+    """32 layers, 32 q / 8 KV heads, d = 128, bf16, b = 16 (or block_size); log-uniform retention."""
+    S, Lyr, Hk, r, d, b = num_seqs, 32, 8, 4, 128, block_size
     ctx = loguniform_lengths(S * Lyr * Hk, prompt, rho, b, seed)
     maxb = (prompt + extra_tokens + b - 1) // b + 1
     N = pool_size(ctx, b, 1.25, S * Lyr * Hk * ((extra_tokens + b - 1) // b))
