@@ -36,11 +36,18 @@ def forced_chunk(request):
     B.kvc_set_decode_chunk(0)
 
 
-@pytest.mark.parametrize("forced_chunk", [0, 2048], indirect=True)
-def test_llama8b_shape_sampled_parity_and_invariants(forced_chunk):
+# (sequences, prompt tokens, mean compression): the benchmark's configuration, and the high
+# compression one (256 long prompts kept at 1/64: mostly short heads, 17 GB of K and V)
+FULL_SIZES = [(64, 8192, 8.0, 0), (64, 8192, 8.0, 2048), (256, 32768, 64.0, 0)]
+
+
+@pytest.mark.parametrize("num_seqs,prompt,rho,forced_chunk", FULL_SIZES, indirect=["forced_chunk"],
+                         ids=["8x", "8x_chunk2048", "64x"])
+def test_llama8b_shape_sampled_parity_and_invariants(num_seqs, prompt, rho, forced_chunk):
     from paper_2410_00161_amd.session import KvcSession
-    print(f"[case] full-size llama8b decode + eviction, chunk setting {forced_chunk}", flush=True)
-    shape, ctx, seed = W.llama8b_decode(extra_tokens=64)
+    print(f"[case] full-size llama8b decode + eviction, {num_seqs} x {prompt} at {rho:g}x, "
+          f"chunk setting {forced_chunk}", flush=True)
+    shape, ctx, seed = W.llama8b_decode(num_seqs=num_seqs, prompt=prompt, rho=rho, extra_tokens=64)
     dev = torch.device("cuda:0")
     cache = W.make_cache(shape, ctx, seed, device=dev, placement="fragmented", init_metric="prefill")
     sess = KvcSession(cache, device=dev)
