@@ -194,6 +194,33 @@ def preempt(st: State, seq_mask) -> int:
     return block_free(st, drop)
 
 
+def compression_batch(st: State, last_compressed, kv_limit, running=None):
+    """The sequences one round of compression takes ("Experiments", scheduling of compression).
+
+    The running sequences are visited in order of the time of their last
+    compression, those never compressed (negative time) first, equal times by
+    sequence index.  A running total of the KVs allocated to the batch
+    (blocks held x block size, summed over the sequence's head instances) is
+    kept; the first sequence that would push it past kv_limit is discarded and
+    the batch is closed there.  Returns (in_batch [S] bool, allocated KVs of the
+    batch)."""
+    last = np.asarray(last_compressed, dtype=np.int64).reshape(st.S)
+    run = np.ones(st.S, dtype=bool) if running is None else np.asarray(running).reshape(st.S).astype(bool)
+    if kv_limit < 0:
+        raise OracleError(ERR_ARG, "negative limit")
+    per = st.Lyr * st.Hk
+    alloc = [sum(num_blocks_held(st, g) for g in range(s * per, (s + 1) * per)) * st.b for s in range(st.S)]
+    order = sorted((s for s in range(st.S) if run[s]), key=lambda s: (-1 if last[s] < 0 else int(last[s]), s))
+    in_batch = np.zeros(st.S, dtype=bool)
+    total = 0
+    for s in order:
+        if total + alloc[s] > kv_limit:
+            break
+        in_batch[s] = True
+        total += alloc[s]
+    return in_batch, total
+
+
 def append(st: State, k_new, v_new, new_pos=None, layer_begin=0, layer_end=None) -> None:
     """Store one new token's k, v for every head instance of the chosen layers."""
     layer_end = st.Lyr if layer_end is None else layer_end

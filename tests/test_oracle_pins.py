@@ -541,6 +541,51 @@ def test_scheduling_helpers_by_hand():
         O.prefill_alloc(st, [1000, 0])                         # row too short / pool too small
 
 
+def test_compression_batch_by_hand_and_against_a_prefix_search():
+    """Five sequences, one head each, b = 4, holding 2, 5, 1, 3, 4 blocks (8, 20, 4, 12, 16 KV
+    slots).  Never-compressed sequences come first, then older compressions first; the batch is
+    the longest prefix of that order whose allocated KVs stay within the limit, and a sequence
+    that does not fit ends it even if a later one would."""
+    S, b, N, maxb = 5, 4, 32, 8
+    blocks = [2, 5, 1, 3, 4]
+    table = -np.ones((S, maxb), dtype=np.int64)
+    nxt = 0
+    for s_, nb in enumerate(blocks):
+        table[s_, :nb] = range(nxt, nxt + nb); nxt += nb
+    lens = np.array([nb * b - 1 for nb in blocks])            # last block partly filled: slots count, not KVs
+    free = np.ones(N, dtype=np.uint8); free[:nxt] = 0
+    st = O.State(S, 1, 1, 1, 2, b, N, maxb, np.zeros((N, b, 2)), np.zeros((N, b, 2)), np.zeros((N, b)),
+                 np.zeros((N, b)), table, lens, free)
+    last = [7, -1, 3, -5, 3]                                   # order: 1, 3 (never), then 2, 4 (time 3), then 0
+    got, total = O.compression_batch(st, last, 40)
+    assert list(got) == [False, True, True, True, False] and total == 36     # 20 + 12 + 4; 16 more would be 52
+    got, total = O.compression_batch(st, last, 35)
+    assert list(got) == [False, True, False, True, False] and total == 32    # seq 2 (4 more slots) is over the limit and closes the batch
+    got, total = O.compression_batch(st, last, 19)
+    assert not got.any() and total == 0                        # the first in line does not fit: nothing is compressed
+    got, total = O.compression_batch(st, last, 10 ** 9)
+    assert got.all() and total == 60
+    got, total = O.compression_batch(st, last, 40, running=[1, 0, 1, 0, 1])  # order: 2, 4, 0
+    assert list(got) == [True, False, True, False, True] and total == 28
+    with pytest.raises(O.OracleError):
+        O.compression_batch(st, last, -1)
+    # against a search over prefixes of the explicitly sorted order, random cases
+    rng = np.random.default_rng(3)
+    alloc = np.array(blocks) * b
+    for _ in range(200):
+        last = rng.integers(-2, 4, S)
+        run = rng.integers(0, 2, S).astype(bool)
+        limit = int(rng.integers(0, 70))
+        order = sorted(np.flatnonzero(run), key=lambda s_: (max(int(last[s_]), -1), s_))
+        best = 0
+        while best < len(order) and alloc[order[:best + 1]].sum() <= limit:
+            best += 1
+        want = np.zeros(S, dtype=bool); want[order[:best]] = True
+        got, total = O.compression_batch(st, last, limit, running=run)
+        np.testing.assert_array_equal(got, want)
+        assert total == alloc[want].sum()
+
+
 # --- 8-bit inputs -----------------------------------------------------------------
 
 def test_e4m3_bytes_decode_as_the_format_defines():
