@@ -131,6 +131,20 @@ int kvc_block_alloc(const kvc_config* cfg, const kvc_state* st, const int32_t* n
 int kvc_block_free(const kvc_config* cfg, const kvc_state* st, const int32_t* n_drop,
                    int64_t* blocks_freed, void* ws, void* stream, int flags);
 
+/* Which sequences a round of compression takes (Experiments, where the scheduling of
+ * compression is described): the running sequences are taken in order of the time of their last
+ * compression, never-compressed ones first, equal times by sequence index, while the KVs
+ * allocated to the batch (blocks held x block_size per sequence) stay within kv_limit; the
+ * first sequence that would exceed it is left out and closes the batch.  last_compressed [S]
+ * i64 (device): any clock that grows, negative = never.  running [S] u8 (device) or NULL = all.
+ * in_batch [S] u8 (device, out); batch_kvs: device i64 scalar (out, may be NULL), the KVs
+ * allocated to the batch.  A caller turns in_batch into per-sequence budgets for
+ * kvc_evict_select / kvc_evict_rank_select (0 for the sequences left out).  KVC_ERR_ARG for a
+ * negative limit, KVC_ERR_UNSUPPORTED above 8192 sequences.  Asynchronous.            */
+int kvc_compression_batch(const kvc_config* cfg, const kvc_state* st, const int64_t* last_compressed,
+                          const uint8_t* running, int64_t kv_limit, uint8_t* in_batch, int64_t* batch_kvs,
+                          void* ws, void* stream);
+
 /* Scheduling counts, computed in parallel on the device ("Block Layout and Parallel
  * Allocation": required additional blocks of running sequences from the context lengths;
  * blocks a preemption would free, per sequence).  needed [S] i32 (device, may be NULL): blocks

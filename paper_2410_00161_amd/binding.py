@@ -26,7 +26,7 @@ EXPORTS = [
     "kvc_workspace_bytes", "kvc_validate", "kvc_status_string", "kvc_workspace_reset",
     "kvc_poll_status", "kvc_block_alloc", "kvc_block_free", "kvc_append", "kvc_paged_decode",
     "kvc_metric_reduce", "kvc_evict_select", "kvc_compact", "kvc_set_decode_chunk",
-    "kvc_get_decode_chunk", "kvc_get_decode_short", "kvc_evict_rank_select", "kvc_compact_rank", "kvc_window_metric", "kvc_query_block_metric", "kvc_count_blocks", "kvc_prefill_alloc", "kvc_preempt",
+    "kvc_get_decode_chunk", "kvc_get_decode_short", "kvc_evict_rank_select", "kvc_compact_rank", "kvc_window_metric", "kvc_query_block_metric", "kvc_count_blocks", "kvc_prefill_alloc", "kvc_preempt", "kvc_compression_batch",
     "kvc_profile_begin", "kvc_profile_enable", "kvc_profile_collect", "kvc_stream_read_probe", "kvc_stream_rw_probe",
 ]
 
@@ -81,6 +81,7 @@ def lib() -> C.CDLL:
         L.kvc_count_blocks.argtypes = [cfgp, stp, I, I, P, P, P, P]
         L.kvc_prefill_alloc.argtypes = [cfgp, stp, P, P, P, I]
         L.kvc_preempt.argtypes = [cfgp, stp, P, C.POINTER(C.c_int64), P, P, I]
+        L.kvc_compression_batch.argtypes = [cfgp, stp, P, P, C.c_int64, P, P, P, P]
         L.kvc_window_metric.argtypes = [cfgp, stp, P, I, I, I, I, I, P, P]
         L.kvc_query_block_metric.argtypes = [cfgp, stp, P, I, I, I, I, I, P, P]
         L.kvc_get_decode_chunk.argtypes = [cfgp, C.POINTER(C.c_int)]
@@ -301,6 +302,14 @@ def kvc_count_blocks(cfg, st, layer_begin, layer_end, needed, held, ws, stream=N
 def kvc_prefill_alloc(cfg, st, seq_tokens, ws, stream=None, flags=0):
     _check(lib().kvc_prefill_alloc(C.byref(cfg), C.byref(st), _ptr(seq_tokens, torch.int32), _ptr(ws),
                                    _stream(stream), flags), "kvc_prefill_alloc")
+
+
+def kvc_compression_batch(cfg, st, last_compressed, running, kv_limit, in_batch, batch_kvs, ws, stream=None):
+    _check(lib().kvc_compression_batch(C.byref(cfg), C.byref(st), _ptr(last_compressed, torch.int64),
+                                       _ptr(running, torch.uint8) if running is not None else None,
+                                       int(kv_limit), _ptr(in_batch, torch.uint8),
+                                       _ptr(batch_kvs, torch.int64) if batch_kvs is not None else None,
+                                       _ptr(ws), _stream(stream)), "kvc_compression_batch")
 
 
 def kvc_preempt(cfg, st, seq_mask, ws, stream=None, flags=0) -> int:

@@ -298,6 +298,71 @@ __global__ void __launch_bounds__(256) count_blocks_kernel(Dims D, const int32_t
   }
 }
 
+// The batch of a compression round, one workgroup.  Rank of every running sequence in the order
+// (time of last compression, never = first; then index) by counting, the order written out,
+// a 64-bit running total of allocated KVs along it, and the cut at the first sequence that does
+// not fit.  held[s] = blocks the sequence holds (from count_blocks_kernel); order: S ints.
+__global__ void __launch_bounds__(1024) compression_batch_kernel(int S, int b, const int32_t* __restrict__ held,
+                                                                 const int64_t* __restrict__ last,
+                                                                 const uint8_t* __restrict__ running,
+                                                                 long long limit, int32_t* __restrict__ order,
+                                                                 uint8_t* __restrict__ in_batch,
+                                                                 int64_t* __restrict__ batch_kvs) {
+  __shared__ long long wave_tot[1024 / 64];
+  __shared__ long long carry_s, total_s;
+  __shared__ int cut_s, nrun_s;
+  const int tid = threadIdx.x;
+  if (tid == 0) { carry_s = 0; total_s = 0; cut_s = 0x7fffffff; nrun_s = 0; }
+  __syncthreads();
+  auto key = [&](int s) -> long long { const long long t = last[s]; return t < 0 ? -1 : t; };
+  auto runs = [&](int s) -> bool { return running == nullptr || running[s] != 0; };
+  for (int s = tid; s < S; s += 1024) {
+    in_batch[s] = 0;
+    if (!runs(s)) continue;
+    const long long ks = key(s);
+    int rank = 0;
+    for (int t = 0; t < S; ++t) {
+      if (!runs(t)) continue;
+      const long long kt = key(t);
+      rank += (kt < ks) || (kt == ks && t < s);
+    }
+    order[rank] = s;
+    atomicAdd(&nrun_s, 1);
+  }
+  __syncthreads();   // the order is complete (global writes of this workgroup are visible to it)
+  const int nrun = nrun_s;
+  for (int base = 0; base < nrun; base += 1024) {
+    const int p = base + tid;
+    const int s = p < nrun ? order[p] : -1;
+    const long long v = s >= 0 ? (long long)held[s] * b : 0;
+    long long inc = v;   // inclusive scan over the wavefront
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const long long t = __shfl_up(inc, o);
+      if ((tid & 63) >= o) inc += t;
+    }
+    if ((tid & 63) == 63) wave_tot[tid >> 6] = inc;
+    __syncthreads();
+    long long before = carry_s;
+    for (int w = 0; w < (tid >> 6); ++w) before += wave_tot[w];
+    const long long cum = before + inc;
+    if (s >= 0 && cum > limit) atomicMin(&cut_s, p);
+    __syncthreads();
+    if (tid == 1023) carry_s = cum;
+    __syncthreads();
+    // positions before the cut of this or an earlier tile are in; a cut found in this tile is final
+    const int cut = cut_s;
+    if (s >= 0 && p < cut) in_batch[s] = 1;
+    // the last position taken so far, if it lies in this tile, knows the batch's total
+    const int last_in = min(min(cut, nrun), base + 1024) - 1;
+    if (p == last_in && last_in >= base) total_s = cum;
+    __syncthreads();
+    if (cut != 0x7fffffff) break;
+  }
+  __syncthreads();
+  if (tid == 0 && batch_kvs) *batch_kvs = total_s;
+}
+
 // Requests of a prefill: every head of sequence s wants ceil(tokens[s] / b) blocks in all.
 __global__ void __launch_bounds__(256) prefill_want_kernel(Dims D, const int32_t* __restrict__ table,
                                                            const int32_t* __restrict__ ctx,
@@ -426,6 +491,30 @@ int kvc_count_blocks(const kvc_config* cfg, const kvc_state* st, int layer_begin
   if (held) { hipLaunchKernelGGL(zero_words_kernel, dim3((D.S + 63) / 64), dim3(64), 0, s, held, D.S); KVC_LAUNCH_CHECK(); }
   hipLaunchKernelGGL(count_blocks_kernel, dim3((D.G + 255) / 256), dim3(256), 0, s, D, st->block_table, st->ctx_len,
                      layer_begin, layer_end, needed, held);
+  KVC_LAUNCH_CHECK();
+  return KVC_OK;
+}
+
+int kvc_compression_batch(const kvc_config* cfg, const kvc_state* st, const int64_t* last_compressed,
+                          const uint8_t* running, int64_t kv_limit, uint8_t* in_batch, int64_t* batch_kvs,
+                          void* ws, void* stream) {
+  int rc = validate(cfg, st);
+  if (rc != KVC_OK) return rc;
+  if (!last_compressed || !in_batch || !ws || ((uintptr_t)ws & 255) || kv_limit < 0) return KVC_ERR_ARG;
+  if (((uintptr_t)last_compressed & 7) || (batch_kvs && ((uintptr_t)batch_kvs & 7))) return KVC_ERR_ARG;
+  Dims D = dims_of(cfg);
+  if (D.S > 8192) return KVC_ERR_UNSUPPORTED;   // ranks are found by counting, S^2 comparisons in one workgroup
+  Workspace W = carve(D, ws);
+  hipStream_t s = (hipStream_t)stream;
+  int32_t* held = W.off_b;    // [S] fits in the [G + 1] array
+  int32_t* order = W.off_a;
+  hipLaunchKernelGGL(zero_words_kernel, dim3((D.S + 63) / 64), dim3(64), 0, s, held, D.S);
+  KVC_LAUNCH_CHECK();
+  hipLaunchKernelGGL(count_blocks_kernel, dim3((D.G + 255) / 256), dim3(256), 0, s, D, st->block_table, st->ctx_len,
+                     0, D.Lyr, (int32_t*)nullptr, held);
+  KVC_LAUNCH_CHECK();
+  hipLaunchKernelGGL(compression_batch_kernel, dim3(1), dim3(1024), 0, s, D.S, D.b, held, last_compressed, running,
+                     (long long)kv_limit, order, in_batch, batch_kvs);
   KVC_LAUNCH_CHECK();
   return KVC_OK;
 }

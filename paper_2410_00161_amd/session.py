@@ -88,6 +88,15 @@ class KvcSession:
                            self.blocks_freed, self.ws, flags=flags)
         return self.blocks_freed
 
+    def compression_batch(self, last_compressed, kv_limit, running=None):
+        S = self.shape.num_seqs
+        in_batch = torch.zeros(S, dtype=torch.uint8, device=self.device)
+        kvs = torch.zeros(1, dtype=torch.int64, device=self.device)
+        B.kvc_compression_batch(self.cfg, self.st, last_compressed.to(self.device, torch.int64).contiguous(),
+                                None if running is None else running.to(self.device, torch.uint8).contiguous(),
+                                kv_limit, in_batch, kvs, self.ws)
+        return in_batch, kvs
+
     def window_metric(self, q_win, w, pool=7, accumulate=False, layer_begin=0, layer_end=None):
         layer_end = self.shape.num_layers if layer_end is None else layer_end
         B.kvc_window_metric(self.cfg, self.st, q_win, w, pool, accumulate, layer_begin, layer_end, self.ws)

@@ -485,3 +485,35 @@ def test_empty_cache_every_call_then_first_tokens():
             np.testing.assert_allclose(out.cpu().numpy(), vv.numpy(), rtol=0, atol=1e-6)
     assert_state_equal(sess, st)
     check_allocator_invariants(st)
+
+
+@pytest.mark.parametrize("skw", [dict(S=37, Lyr=2, Hk=2, L=300), dict(S=2500, Lyr=1, Hk=1, L=48)],
+                         ids=["37_seqs", "2500_seqs"])
+def test_compression_batch_matches_oracle(skw):
+    say("compression batch", skw)
+    shape, ctx, seed = W.small_mixed(91, r=1, d=64, rho=2.0, **skw)
+    ctx[4:8] = 0                                  # a sequence (or a few) that holds nothing
+    cache = W.make_cache(shape, ctx, seed, placement="fragmented")
+    st = oracle_state(cache)
+    sess = session(cache)
+    rng = np.random.default_rng(5)
+    per = shape.num_layers * shape.num_kv_heads
+    held = [sum(O.num_blocks_held(st, g) for g in range(s * per, (s + 1) * per)) for s in range(shape.num_seqs)]
+    total = sum(held) * shape.block_size
+    in_batch = torch.zeros(shape.num_seqs, dtype=torch.uint8, device=sess.device)
+    kvs = torch.zeros(1, dtype=torch.int64, device=sess.device)
+    for case in range(14):
+        last = rng.integers(-3, 6, shape.num_seqs)
+        run = None if case % 3 == 0 else rng.integers(0, 2, shape.num_seqs).astype(np.uint8)
+        limit = [0, total, total // 2, total // 5, 10 ** 15, 1, (total * 9) // 10][case % 7]
+        want, want_kvs = O.compression_batch(st, last, limit, running=run)
+        in_batch.fill_(9)
+        B.kvc_compression_batch(sess.cfg, sess.st, torch.from_numpy(last).to(sess.device),
+                                None if run is None else torch.from_numpy(run).to(sess.device),
+                                limit, in_batch, kvs, sess.ws)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(in_batch.cpu().numpy().astype(bool), want)
+        assert int(kvs.item()) == want_kvs
+    with pytest.raises(B.KvcError):
+        B.kvc_compression_batch(sess.cfg, sess.st, torch.zeros(shape.num_seqs, dtype=torch.int64, device=sess.device),
+                                None, -1, in_batch, kvs, sess.ws)
