@@ -24,7 +24,6 @@ enum HeaderWord {
   HW_FREED = 4,       // blocks freed by the call in flight
   HW_SCRATCH0 = 5,
   HW_SCRATCH1 = 6,
-  HW_SMALL_ITEMS = 7,  // decode work items in the small size classes
   HW_SHORT_ITEMS = 8,  // decode work items short enough for the one-wavefront launch
   // decode work-list block: item counts per size class, per-class cursors, cursor of the
   // per-chunk partial results.  All zero between calls (the chunk kernel clears it).

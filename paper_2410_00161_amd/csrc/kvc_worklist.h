@@ -55,17 +55,6 @@ __device__ __forceinline__ int size_class(int n, int T) {
   return cls;
 }
 
-// Items are stored largest class first.  Workgroup i does not take item i: the small classes
-// (at most T / 2^(kSmallClass-1) tokens, latency-bound work) are dealt out from the back of
-// the list in proportion, so that at any time the chip holds a mix of long streaming items
-// and short ones, and the two ends meet at the medium sizes.
-constexpr int kSmallClass = 5;
-__device__ __forceinline__ int item_of_workgroup(int i, int total, int small) {
-  const long long s0 = (long long)i * small / total;
-  const long long s1 = (long long)(i + 1) * small / total;
-  return s1 > s0 ? total - 1 - (int)s0 : i - (int)s0;
-}
-
 // Pass 1 of the work list: number of items per size class.
 static __global__ void __launch_bounds__(256) decode_count_kernel(DecodeArgs A) {
   __shared__ int bins[16];
@@ -91,18 +80,16 @@ static __global__ void __launch_bounds__(256) decode_items_kernel(DecodeArgs A) 
   if (tid < 17) want[tid] = 0;
   if (tid == 0) {
     int run = 0;
-    int small = 0, pack = 0;
+    int shorts = 0;
     for (int k = 0; k < 16; ++k) {
       const int c = A.header[HW_DEC_BINS + k];
       base[k] = run;
       run += c;
-      if (k >= kSmallClass) small += c;
-      if (k >= A.short_class) pack += c;
+      if (k >= A.short_class) shorts += c;
     }
     if (blockIdx.x == 0) {
       A.header[HW_TOTAL_ITEMS] = run;
-      A.header[HW_SMALL_ITEMS] = small;
-      A.header[HW_SHORT_ITEMS] = pack;
+      A.header[HW_SHORT_ITEMS] = shorts;
     }
   }
   __syncthreads();
@@ -175,16 +162,14 @@ static __global__ void __launch_bounds__(1024) decode_worklist_small_kernel(Deco
   }
   __syncthreads();
   if (tid == 0) {
-    int run = 0, small = 0, pack = 0;
+    int run = 0, shorts = 0;
     for (int k = 0; k < 16; ++k) {
       base[k] = run;
       run += bins[k];
-      if (k >= kSmallClass) small += bins[k];
-      if (k >= A.short_class) pack += bins[k];
+      if (k >= A.short_class) shorts += bins[k];
     }
     A.header[HW_TOTAL_ITEMS] = run;
-    A.header[HW_SMALL_ITEMS] = small;
-    A.header[HW_SHORT_ITEMS] = pack;
+    A.header[HW_SHORT_ITEMS] = shorts;
   }
   __syncthreads();
   if (tid >= A.gsel) return;
