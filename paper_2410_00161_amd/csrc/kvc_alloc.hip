@@ -81,34 +81,38 @@ __global__ void __launch_bounds__(256) count_and_free_tiles_kernel(Dims D, const
   if (threadIdx.x == 0) tile_sums[tile] = red[0] + red[1] + red[2] + red[3];
 }
 
-constexpr int kScanRun = 8;                    // elements per thread and tile in alloc_scan_kernel
+constexpr int kScanRun = 16;                   // elements per thread and tile in alloc_scan_kernel
 constexpr int kScanWide = 1024 * kScanRun;     // elements per tile
 
-// Exclusive scan of n ints in place over one workgroup of 1024 threads: a tile is read with
-// coalesced loads into LDS, every thread scans a run of 8 from there (padded against bank
-// conflicts), one workgroup scan joins the runs.  `visit(i, value, exclusive)` sees every element.
+// Exclusive scan of n ints over one workgroup of 1024 threads: every thread takes a run of 16
+// consecutive elements (four 16-byte loads when the array is 16-byte aligned, which workspace
+// arrays are), one workgroup scan joins the runs.  `visit(i, value, exclusive)` sees every element.
 template <class Visit>
-__device__ __forceinline__ int wide_exclusive_scan(const int32_t* __restrict__ in, int n, int* lds, int* smem,
-                                                   Visit visit) {
+__device__ __forceinline__ int wide_exclusive_scan(const int32_t* __restrict__ in, int n, int* smem, Visit visit) {
   __shared__ int carry_s;
   if (threadIdx.x == 0) carry_s = 0;
   __syncthreads();
-  auto at = [](int i) { return i + (i >> 5); };
+  const bool aligned = ((uintptr_t)in & 15) == 0;
   for (int base = 0; base < n; base += kScanWide) {
-    for (int k = 0; k < kScanRun; ++k) {
-      const int i = k * 1024 + threadIdx.x;
-      lds[at(i)] = (base + i < n) ? in[base + i] : 0;
-    }
-    __syncthreads();
+    const int first = base + threadIdx.x * kScanRun;
     int v[kScanRun], sum = 0;
+    if (aligned && first + kScanRun <= n) {
 #pragma unroll
-    for (int k = 0; k < kScanRun; ++k) { v[k] = lds[at(threadIdx.x * kScanRun + k)]; sum += v[k]; }
+      for (int k = 0; k < kScanRun; k += 4) {
+        const int4 t = *(const int4*)(in + first + k);
+        v[k] = t.x; v[k + 1] = t.y; v[k + 2] = t.z; v[k + 3] = t.w;
+      }
+    } else {
+#pragma unroll
+      for (int k = 0; k < kScanRun; ++k) v[k] = first + k < n ? in[first + k] : 0;
+    }
+#pragma unroll
+    for (int k = 0; k < kScanRun; ++k) sum += v[k];
     int tot;
     int ex = block_exclusive_scan<1024>(sum, smem, &tot) + carry_s;
 #pragma unroll
     for (int k = 0; k < kScanRun; ++k) {
-      const int i = base + threadIdx.x * kScanRun + k;
-      if (i < n) visit(i, v[k], ex);
+      if (first + k < n) visit(first + k, v[k], ex);
       ex += v[k];
     }
     __syncthreads();
@@ -127,14 +131,13 @@ __global__ void __launch_bounds__(1024) alloc_scan_kernel(Dims D, const int32_t*
                                                           int32_t* __restrict__ tile_sums, int ntiles,
                                                           int32_t* __restrict__ header) {
   __shared__ int smem[1024 / 64 + 1];
-  __shared__ int lds[kScanWide + kScanWide / 32 + 1];
   const int N = D.N;
-  const int total_req = wide_exclusive_scan(req, D.G, lds, smem, [&](int g, int v, int ex) {
+  const int total_req = wide_exclusive_scan(req, D.G, smem, [&](int g, int v, int ex) {
     off[g] = ex;
     if (ex + v <= N)  // more requests than blocks exist is an error found below
       for (int i = 0; i < v; ++i) owner[ex + i] = g;
   });
-  const int total_free = wide_exclusive_scan(tile_sums, ntiles, lds, smem,
+  const int total_free = wide_exclusive_scan(tile_sums, ntiles, smem,
                                              [&](int t, int v, int ex) { tile_sums[t] = ex; });
   if (threadIdx.x == 0) {
     off[D.G] = total_req;
