@@ -128,6 +128,11 @@ __device__ __forceinline__ uint4 load_stream16(const void* p) {
   const u32x4 t = __builtin_nontemporal_load((const u32x4*)p);
   return make_uint4(t.x, t.y, t.z, t.w);
 }
+__device__ __forceinline__ uint2 load_stream8(const void* p) {
+  typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+  const u32x2 t = __builtin_nontemporal_load((const u32x2*)p);
+  return make_uint2(t.x, t.y);
+}
 
 // bytes of one K/V element, and of one query element (queries of an 8-bit cache are bf16)
 __host__ __device__ inline int kv_esz(int dtype) { return dtype == KVC_F32 ? 4 : dtype == KVC_BF16 ? 2 : 1; }

@@ -38,11 +38,16 @@ typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
 
 template <int ESZ> struct Row;
-// Q: the query elements that face one 16-byte piece of a K row; QSZ: bytes of a query element.
+// P: the piece of a K or V row one lane loads (PB bytes, EPL elements); Q: the query elements
+// that face it; QSZ: bytes of a query element.
 template <> struct Row<2> {  // bf16: 8 elements in 16 bytes
   static constexpr int EPL = 8;
   static constexpr int QSZ = 2;
+  static constexpr int PB = 16;
+  typedef uint4 P;
   typedef uint4 Q;
+  static __device__ __forceinline__ P load(const void* p) { return load_stream16(p); }
+  static __device__ __forceinline__ P zero() { return make_uint4(0, 0, 0, 0); }
   static __device__ __forceinline__ Q load_q(const char* qrow, int seg) { return *(const uint4*)(qrow + (size_t)seg * 16); }
   static __device__ __forceinline__ float dot(const uint4& a, const uint4& b) {
     float s = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a.x), __builtin_bit_cast(bf16x2_t, b.x), 0.0f, false);
@@ -51,6 +56,7 @@ template <> struct Row<2> {  // bf16: 8 elements in 16 bytes
     s = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a.w), __builtin_bit_cast(bf16x2_t, b.w), s, false);
     return s;
   }
+  static __device__ __forceinline__ uint4 as_bf16x8(const uint4& a) { return a; }
   static __device__ __forceinline__ void widen(const uint4& a, float* f) {
     f[0] = bf16_lo(a.x); f[1] = bf16_hi(a.x); f[2] = bf16_lo(a.y); f[3] = bf16_hi(a.y);
     f[4] = bf16_lo(a.z); f[5] = bf16_hi(a.z); f[6] = bf16_lo(a.w); f[7] = bf16_hi(a.w);
@@ -59,7 +65,11 @@ template <> struct Row<2> {  // bf16: 8 elements in 16 bytes
 template <> struct Row<4> {  // f32: 4 elements in 16 bytes
   static constexpr int EPL = 4;
   static constexpr int QSZ = 4;
+  static constexpr int PB = 16;
+  typedef uint4 P;
   typedef uint4 Q;
+  static __device__ __forceinline__ P load(const void* p) { return load_stream16(p); }
+  static __device__ __forceinline__ P zero() { return make_uint4(0, 0, 0, 0); }
   static __device__ __forceinline__ Q load_q(const char* qrow, int seg) { return *(const uint4*)(qrow + (size_t)seg * 16); }
   static __device__ __forceinline__ float dot(const uint4& a, const uint4& b) {
     float s = __uint_as_float(a.x) * __uint_as_float(b.x);
@@ -75,34 +85,38 @@ template <> struct Row<4> {  // f32: 4 elements in 16 bytes
 };
 
 typedef float f32x2_t __attribute__((ext_vector_type(2)));
-template <> struct Row<1> {  // OCP e4m3: 16 elements in 16 bytes, facing 16 bf16 query elements
-  static constexpr int EPL = 16;
+template <> struct Row<1> {  // OCP e4m3: 8 elements in 8 bytes, facing 8 bf16 query elements
+  // Pieces of 8 bytes, not 16: a d = 128 row is then spread over 16 lanes as for bf16, and the
+  // output accumulator of a lane (r x EPL floats) stays at the size the registers hold.
+  static constexpr int EPL = 8;
   static constexpr int QSZ = 2;
-  struct Q { uint4 lo, hi; };
-  static __device__ __forceinline__ Q load_q(const char* qrow, int seg) {
-    const uint4* p = (const uint4*)(qrow + (size_t)seg * 32);
-    return Q{p[0], p[1]};
-  }
-  // four 8-bit floats -> two packed bf16 pairs (exact: 3 mantissa bits fit in 7), then the
-  // same packed dot product as for a bf16 cache
+  static constexpr int PB = 8;
+  typedef uint2 P;
+  typedef uint4 Q;
+  static __device__ __forceinline__ P load(const void* p) { return load_stream8(p); }
+  static __device__ __forceinline__ P zero() { return make_uint2(0, 0); }
+  static __device__ __forceinline__ Q load_q(const char* qrow, int seg) { return *(const uint4*)(qrow + (size_t)seg * 16); }
+  // four 8-bit floats -> two packed bf16 pairs (exact: 3 mantissa bits fit in 7; one instruction
+  // per pair, scale 1), then the same packed dot product as for a bf16 cache
   static __device__ __forceinline__ float dot4(uint32_t k, uint32_t q01, uint32_t q23, float s) {
-    const f32x2_t a = __builtin_amdgcn_cvt_pk_f32_fp8((int)k, false);
-    const f32x2_t b = __builtin_amdgcn_cvt_pk_f32_fp8((int)k, true);
-    const uint32_t p01 = __builtin_amdgcn_perm(__float_as_uint(a.y), __float_as_uint(a.x), 0x07060302u);
-    const uint32_t p23 = __builtin_amdgcn_perm(__float_as_uint(b.y), __float_as_uint(b.x), 0x07060302u);
-    s = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, p01), __builtin_bit_cast(bf16x2_t, q01), s, false);
-    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, p23), __builtin_bit_cast(bf16x2_t, q23), s, false);
+    const bf16x2_t p01 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(k, 1.0f, false);
+    const bf16x2_t p23 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(k, 1.0f, true);
+    s = __builtin_amdgcn_fdot2_f32_bf16(p01, __builtin_bit_cast(bf16x2_t, q01), s, false);
+    return __builtin_amdgcn_fdot2_f32_bf16(p23, __builtin_bit_cast(bf16x2_t, q23), s, false);
   }
-  static __device__ __forceinline__ float dot(const uint4& a, const Q& q) {
-    float s = dot4(a.x, q.lo.x, q.lo.y, 0.0f);
-    s = dot4(a.y, q.lo.z, q.lo.w, s);
-    s = dot4(a.z, q.hi.x, q.hi.y, s);
-    return dot4(a.w, q.hi.z, q.hi.w, s);
+  static __device__ __forceinline__ uint4 as_bf16x8(const uint2& a) {
+    return make_uint4(__builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(a.x, 1.0f, false)),
+                      __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(a.x, 1.0f, true)),
+                      __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(a.y, 1.0f, false)),
+                      __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(a.y, 1.0f, true)));
   }
-  static __device__ __forceinline__ void widen(const uint4& a, float* f) {
-    const uint32_t w[4] = {a.x, a.y, a.z, a.w};
+  static __device__ __forceinline__ float dot(const uint2& a, const Q& q) {
+    return dot4(a.y, q.z, q.w, dot4(a.x, q.x, q.y, 0.0f));
+  }
+  static __device__ __forceinline__ void widen(const uint2& a, float* f) {
+    const uint32_t w[2] = {a.x, a.y};
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < 2; ++i) {
       const f32x2_t lo = __builtin_amdgcn_cvt_pk_f32_fp8((int)w[i], false);
       const f32x2_t hi = __builtin_amdgcn_cvt_pk_f32_fp8((int)w[i], true);
       f[4 * i] = lo.x; f[4 * i + 1] = lo.y; f[4 * i + 2] = hi.x; f[4 * i + 3] = hi.y;
@@ -149,10 +163,11 @@ __device__ __forceinline__ void stash_load(const float* stash, size_t slot, floa
 constexpr int kDecodeThreads = 256;
 constexpr int kDecodeWaves = kDecodeThreads / 64;
 
-// A shape takes Q K^T to the matrix cores where the plain ALUs are the bound: 16-bit rows, eight
-// query heads per KV head, d = 128, blocks of a multiple of 16 tokens.
+// A shape takes Q K^T to the matrix cores where the plain ALUs are the bound: 16-bit or 8-bit
+// rows (the latter widened to bf16 on their way into the operand tile), eight query heads per KV
+// head, d = 128, blocks of a multiple of 16 tokens.
 __host__ __device__ constexpr bool decode_uses_mfma(int esz, int R, int HD, int b) {
-  return esz == 2 && R == 8 && HD == 128 && b % 16 == 0;
+  return esz <= 2 && R == 8 && HD == 128 && b % 16 == 0;
 }
 
 __host__ __device__ inline size_t decode_lds_bytes(int T, int R, int HD, int b, int waves = kDecodeWaves,
@@ -187,8 +202,10 @@ __global__ void __launch_bounds__(NW * 64) decode_chunk_kernel(DecodeArgs A) {
   constexpr int NT = NW * 64;
   // register buffers for K and V groups: three for 16-bit rows under up to four query heads (two
   // workgroups of long chunks per CU, two groups in flight behind the current one), else two
-  constexpr int DEPTH = (ESZ == 2 && R <= 4 && NW == 4) ? 3 : 2;
+  constexpr int DEPTH = (ESZ <= 2 && R <= 4 && NW == 4) ? 3 : 2;
   constexpr int EPL = Row<ESZ>::EPL;
+  constexpr int PB = Row<ESZ>::PB;     // bytes a lane loads at once
+  typedef typename Row<ESZ>::P Piece;
   constexpr int LPT = HD / EPL;        // lanes per token
   constexpr int TPI = 64 / LPT;        // tokens per wavefront load
   constexpr int U = 16 / TPI;          // loads per 16-token group
@@ -255,24 +272,24 @@ __global__ void __launch_bounds__(NW * 64) decode_chunk_kernel(DecodeArgs A) {
   }
   __syncthreads();
 
-  // One 16-token group = U wavefront loads of 1 KiB each.  With b a multiple of 16 a group
-  // lies in one block, so one table lookup serves it and the slots past the end of the head
-  // (still inside the block) are read and masked later.  Otherwise every load looks its
-  // block up and tokens past the end re-read the last token.
+  // One 16-token group = U wavefront loads of 64 pieces each (1 KiB; 512 bytes for 8-bit
+  // rows).  With b a multiple of 16 a group lies in one block, so one table lookup serves it
+  // and the slots past the end of the head (still inside the block) are read and masked later.
+  // Otherwise every load looks its block up and tokens past the end re-read the last token.
   const int last = n_tok - 1;
-  auto load_group = [&](const char* __restrict__ basep, int grp, uint4 (&buf)[U]) {
+  auto load_group = [&](const char* __restrict__ basep, int grp, Piece (&buf)[U]) {
     if constexpr (B16) {
       const int tk = grp * 16;
       const size_t slot = ((size_t)s_tab[tk >> lb] << lb) + (tk & (b - 1));
-      const char* p = basep + slot * ROWB + (size_t)lane * 16;
+      const char* p = basep + slot * ROWB + (size_t)lane * PB;
 #pragma unroll
-      for (int u = 0; u < U; ++u) buf[u] = load_stream16(p + (size_t)u * 1024);
+      for (int u = 0; u < U; ++u) buf[u] = Row<ESZ>::load(p + (size_t)u * (64 * PB));
     } else {
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         const int tok = min(grp * 16 + u * TPI + sub, last);
         const size_t slot = ((size_t)s_tab[tok >> lb] << lb) + (tok & (b - 1));
-        buf[u] = load_stream16(basep + slot * ROWB + (size_t)seg * 16);
+        buf[u] = Row<ESZ>::load(basep + slot * ROWB + (size_t)seg * PB);
       }
     }
   };
@@ -293,7 +310,7 @@ __global__ void __launch_bounds__(NW * 64) decode_chunk_kernel(DecodeArgs A) {
   float* my_e = s_e + w * 16 * R;
   const bool gm_writer = (lane & 60) == 0;  // lanes 0..3 hold every head between them
 
-  auto process = [&](uint4 (&kcur)[U], uint4 (&vcur)[U], int grp) {
+  auto process = [&](Piece (&kcur)[U], Piece (&vcur)[U], int grp) {
       float m_new[R];
       bool moved = false;
       if constexpr (MF) {
@@ -303,7 +320,7 @@ __global__ void __launch_bounds__(NW * 64) decode_chunk_kernel(DecodeArgs A) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
           const int t = u * TPI + sub;
-          kt[t * 16 + (seg ^ t)] = kcur[u];
+          kt[t * 16 + (seg ^ t)] = Row<ESZ>::as_bf16x8(kcur[u]);
         }
         const int tl = lane & 15, hrow = lane >> 4;
         f32x4_t sacc = {0.0f, 0.0f, 0.0f, 0.0f};
@@ -401,7 +418,7 @@ __global__ void __launch_bounds__(NW * 64) decode_chunk_kernel(DecodeArgs A) {
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         const int tl = u * TPI + sub;
-        if (tail && grp * 16 + tl >= n_tok) vcur[u] = make_uint4(0, 0, 0, 0);  // empty slot: may hold anything
+        if (tail && grp * 16 + tl >= n_tok) vcur[u] = Row<ESZ>::zero();  // empty slot: may hold anything
         float vf[EPL];
         Row<ESZ>::widen(vcur[u], vf);
 #pragma unroll
@@ -415,7 +432,7 @@ __global__ void __launch_bounds__(NW * 64) decode_chunk_kernel(DecodeArgs A) {
   {
     // DEPTH register buffers used in rotation (the loop is unrolled DEPTH times so that no
     // buffer is ever copied): DEPTH - 1 groups in flight behind the one being worked on
-    uint4 kb[DEPTH][U], vb[DEPTH][U];
+    Piece kb[DEPTH][U], vb[DEPTH][U];
 #pragma unroll
     for (int st = 0; st < DEPTH - 1; ++st) {
       const int g2 = w + st * NW;
