@@ -29,6 +29,12 @@ HIPCC_FLAGS = [
 ]
 
 
+# Per-source additions.  The decode kernels keep their matrix-core accumulators in ordinary
+# vector registers: they are rescaled by plain multiplies whenever a running maximum moves, and
+# in the accumulator file every such multiply costs a copy out and a copy back.
+EXTRA_FLAGS = {"kvc_decode.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
+
+
 def _run(cmd):
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
@@ -44,7 +50,7 @@ def build_library(verbose: bool = True) -> str:
 
     def one(pair):
         src, obj = pair
-        _run([hipcc, *HIPCC_FLAGS, "-c", os.path.join(CSRC, src), "-o", obj])
+        _run([hipcc, *HIPCC_FLAGS, *EXTRA_FLAGS.get(src, []), "-c", os.path.join(CSRC, src), "-o", obj])
         if verbose:
             print(f"[kvc build] {src}", flush=True)
 

@@ -36,6 +36,7 @@ static int g_prof_cap = 0, g_prof_used = 0, g_prof_on = 1;
 typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
+typedef short i16x4_t __attribute__((ext_vector_type(4)));
 
 template <int ESZ> struct Row;
 // P: the piece of a K or V row one lane loads (PB bytes, EPL elements); Q: the query elements
@@ -170,6 +171,14 @@ __host__ __device__ constexpr bool decode_uses_mfma(int esz, int R, int HD, int 
   return esz <= 2 && R == 8 && HD == 128 && b % 16 == 0;
 }
 
+// Register buffers of K and V groups a wavefront rotates through (one less is in flight behind
+// the group being worked on): three for rows of at most 16 bits when four wavefronts share a
+// long chunk (up to four query heads, or the matrix-core shapes), else two.
+__host__ __device__ constexpr int decode_depth(int esz, int R, int HD, bool b16, int nw) {
+  if (nw != 4 || esz > 2) return 2;
+  return (R <= 4 || (b16 && decode_uses_mfma(esz, R, HD, 16))) ? 3 : 2;
+}
+
 __host__ __device__ inline size_t decode_lds_bytes(int T, int R, int HD, int b, int waves = kDecodeWaves,
                                                    bool mfma = false) {
   return (mfma ? (size_t)waves * 16 * HD * 2 : 0)  // per-wavefront K tile on its way into operand order
@@ -200,9 +209,7 @@ __host__ __device__ inline size_t decode_lds_bytes(int T, int R, int HD, int b, 
 template <int ESZ, int HD, int R, bool B16, int NW>
 __global__ void __launch_bounds__(NW * 64) decode_chunk_kernel(DecodeArgs A) {
   constexpr int NT = NW * 64;
-  // register buffers for K and V groups: three for 16-bit rows under up to four query heads (two
-  // workgroups of long chunks per CU, two groups in flight behind the current one), else two
-  constexpr int DEPTH = (ESZ <= 2 && R <= 4 && NW == 4) ? 3 : 2;
+  constexpr int DEPTH = decode_depth(ESZ, R, HD, B16, NW);
   constexpr int EPL = Row<ESZ>::EPL;
   constexpr int PB = Row<ESZ>::PB;     // bytes a lane loads at once
   typedef typename Row<ESZ>::P Piece;
@@ -263,8 +270,9 @@ __global__ void __launch_bounds__(NW * 64) decode_chunk_kernel(DecodeArgs A) {
     const int arow = lane & 15, ahead = (arow >> 2) + 4 * (arow & 3);
 #pragma unroll
     for (int st = 0; st < U; ++st) {
-      const uint4 z = make_uint4(0, 0, 0, 0);
-      qv[st] = ahead < R ? *(const uint4*)(A.q + ((size_t)g * R + ahead) * QROWB + (size_t)st * 64 + (size_t)(lane >> 4) * 16) : z;
+      // (rows without a head read the last head and are zeroed: a select between values)
+      const uint4 t = *(const uint4*)(A.q + ((size_t)g * R + min(ahead, R - 1)) * QROWB + (size_t)st * 64 + (size_t)(lane >> 4) * 16);
+      qv[st] = ahead < R ? t : make_uint4(0, 0, 0, 0);
     }
   } else {
 #pragma unroll
@@ -295,11 +303,20 @@ __global__ void __launch_bounds__(NW * 64) decode_chunk_kernel(DecodeArgs A) {
   };
   const int ngroups = (n_tok + 15) >> 4;
 
-  float acc[R][EPL];
+  float acc[R][EPL];         // VALU path: un-normalised output, this lane's dimensions and tokens
 #pragma unroll
   for (int hh = 0; hh < R; ++hh)
 #pragma unroll
     for (int k = 0; k < EPL; ++k) acc[hh][k] = 0.0f;
+  // MFMA path: P V as v_mfma_f32_16x16x16_bf16 per 16 dimensions (rows = heads, columns =
+  // dimensions, k = the 16 tokens of a group).  A probability goes in as two bf16 halves,
+  // hi = its upper 16 bits in row h, lo = (p - hi) in row h + 8, so that the product carries
+  // 16 bits of p (one half alone misses the output tolerance when one key dominates).
+  constexpr int NDT = HD / 16;
+  static_assert(!MF || R == 8, "the two halves of eight heads fill the 16 operand rows");
+  f32x4_t pacc[MF ? NDT : 1];
+#pragma unroll
+  for (int i = 0; i < (MF ? NDT : 1); ++i) pacc[i] = f32x4_t{0.0f, 0.0f, 0.0f, 0.0f};
   float m_run[R];            // running max per query head, the same in every lane
   float m_own[OWN], l_own[OWN];  // this lane's head(s): running max and partial sum
 #pragma unroll
@@ -352,7 +369,7 @@ __global__ void __launch_bounds__(NW * 64) decode_chunk_kernel(DecodeArgs A) {
         for (int v = 0; v < NVH; ++v) {
           const int hh = hrow + 4 * v;
           if (hh < R) {
-            my_e[tl * R + hh] = e[v];
+            my_e[hh * 16 + tl] = e[v];      // [head][token] here: the P V operand reads four tokens of a head
             s_q[(grp * 16 + tl) * R + hh] = (uint16_t)q16(e[v]);
             if (tl == 0) s_gm[grp * R + hh] = gm[v];
           }
@@ -404,28 +421,81 @@ __global__ void __launch_bounds__(NW * 64) decode_chunk_kernel(DecodeArgs A) {
           moved |= m_new[hh] > m_run[hh];
         }
       }
-      if (moved) {
-#pragma unroll
-        for (int hh = 0; hh < R; ++hh) {
-          const float alpha = __builtin_amdgcn_exp2f(m_run[hh] - m_new[hh]);
-#pragma unroll
-          for (int k = 0; k < EPL; ++k) acc[hh][k] *= alpha;
-          m_run[hh] = m_new[hh];
-        }
-      }
-      // acc += p * v
       const bool tail = B16 && grp * 16 + 16 > n_tok;
+      if constexpr (MF) {
+        if (moved) {
+          // this lane's product rows 4 (lane / 16) + v belong to heads 4 ((lane / 16) % 2) + v
+          const bool upper = (lane & 16) != 0;
 #pragma unroll
-      for (int u = 0; u < U; ++u) {
-        const int tl = u * TPI + sub;
-        if (tail && grp * 16 + tl >= n_tok) vcur[u] = Row<ESZ>::zero();  // empty slot: may hold anything
-        float vf[EPL];
-        Row<ESZ>::widen(vcur[u], vf);
+          for (int v = 0; v < 4; ++v) {
+            const float a_lo = __builtin_amdgcn_exp2f(m_run[v] - m_new[v]);
+            const float a_hi = __builtin_amdgcn_exp2f(m_run[4 + v] - m_new[4 + v]);
+            const float a = upper ? a_hi : a_lo;
 #pragma unroll
-        for (int hh = 0; hh < R; ++hh) {
-          const float p = my_e[tl * R + hh];
+            for (int dt = 0; dt < NDT; ++dt) pacc[dt][v] *= a;
+          }
 #pragma unroll
-          for (int k = 0; k < EPL; ++k) acc[hh][k] = fmaf(p, vf[k], acc[hh][k]);
+          for (int hh = 0; hh < R; ++hh) m_run[hh] = m_new[hh];
+        }
+        // The K tile has been consumed: its 4 KiB now take the V tile, row-major [token][d] in
+        // bf16, the 16-byte cell c of token t at position c ^ 2 (t % 8) of the row, which keeps
+        // the transposing reads below (8 tokens x 32 bytes per half wavefront) off each other's banks.
+        uint4* vt = s_kt + w * 256;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          const int t = u * TPI + sub;
+          const bool dead = tail && grp * 16 + t >= n_tok;   // empty slot: may hold anything
+          vt[t * 16 + (seg ^ (2 * (t & 7)))] = Row<ESZ>::as_bf16x8(dead ? Row<ESZ>::zero() : vcur[u]);
+        }
+        // A operand: lane = (row lane % 16, tokens 4 (lane / 16) .. + 3)
+        const int rho = lane & 15, kap = lane >> 4;
+        const float4 pe = *(const float4*)(my_e + (rho & 7) * 16 + 4 * kap);
+        const bool hi_row = rho < 8;
+        auto half_of = [&](float p) {   // the float whose upper 16 bits are this row's half of p
+          const uint32_t bits = __float_as_uint(p);
+          const float lo = p - __uint_as_float(bits & 0xffff0000u);   // exact
+          return hi_row ? bits : __float_as_uint(lo);
+        };
+        const uint32_t hb0 = half_of(pe.x), hb1 = half_of(pe.y), hb2 = half_of(pe.z), hb3 = half_of(pe.w);
+        const uint2 apack = make_uint2(__builtin_amdgcn_perm(hb1, hb0, 0x07060302u),
+                                       __builtin_amdgcn_perm(hb3, hb2, 0x07060302u));
+        const i16x4_t aop = __builtin_bit_cast(i16x4_t, apack);
+        // B operand of dimension tile dt: lane = (column lane % 16, tokens 4 (lane / 16) .. + 3).
+        // The transposing read delivers it when lane j of a group of 16 points at token
+        // 4 (lane / 16) + j / 4, dimensions 16 dt + 4 (j % 4) .. + 3.
+        const int tt = 4 * kap + (rho >> 2);
+        const char* vrow = (const char*)vt + tt * 256 + 8 * (rho & 1);
+        const int csw = 2 * (tt & 7), chalf = (rho & 3) >> 1;
+#pragma unroll
+        for (int dt = 0; dt < NDT; ++dt) {
+          const int c = (2 * dt + chalf) ^ csw;
+          const i16x4_t bop = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+              (i16x4_t __attribute__((address_space(3)))*)(vrow + c * 16));
+          pacc[dt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(aop, bop, pacc[dt], 0, 0, 0);
+        }
+      } else {
+        if (moved) {
+#pragma unroll
+          for (int hh = 0; hh < R; ++hh) {
+            const float alpha = __builtin_amdgcn_exp2f(m_run[hh] - m_new[hh]);
+#pragma unroll
+            for (int k = 0; k < EPL; ++k) acc[hh][k] *= alpha;
+            m_run[hh] = m_new[hh];
+          }
+        }
+        // acc += p * v
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          const int tl = u * TPI + sub;
+          if (tail && grp * 16 + tl >= n_tok) vcur[u] = Row<ESZ>::zero();  // empty slot: may hold anything
+          float vf[EPL];
+          Row<ESZ>::widen(vcur[u], vf);
+#pragma unroll
+          for (int hh = 0; hh < R; ++hh) {
+            const float p = my_e[tl * R + hh];
+#pragma unroll
+            for (int k = 0; k < EPL; ++k) acc[hh][k] = fmaf(p, vf[k], acc[hh][k]);
+          }
         }
       }
   };
@@ -494,17 +564,28 @@ __global__ void __launch_bounds__(NW * 64) decode_chunk_kernel(DecodeArgs A) {
       }
     }
   }
+  if constexpr (MF) {
+    // rows h and h + 8 of the product (lanes 32 apart) are the two halves of head h
 #pragma unroll
-  for (int m = LPT; m < 64; m <<= 1)
+    for (int dt = 0; dt < NDT; ++dt)
 #pragma unroll
-    for (int hh = 0; hh < R; ++hh)
+      for (int v = 0; v < 4; ++v) {
+        const float a = pacc[dt][v] + __shfl_xor(pacc[dt][v], 32);
+        if (lane < 32) s_acc[(w * R + 4 * (lane >> 4) + v) * HD + 16 * dt + (lane & 15)] = a;
+      }
+  } else {
 #pragma unroll
-      for (int k = 0; k < EPL; ++k) acc[hh][k] += __shfl_xor(acc[hh][k], m);
-  if (sub == 0) {
+    for (int m = LPT; m < 64; m <<= 1)
 #pragma unroll
-    for (int hh = 0; hh < R; ++hh)
+      for (int hh = 0; hh < R; ++hh)
 #pragma unroll
-      for (int k = 0; k < EPL; ++k) s_acc[(w * R + hh) * HD + seg * EPL + k] = acc[hh][k];
+        for (int k = 0; k < EPL; ++k) acc[hh][k] += __shfl_xor(acc[hh][k], m);
+    if (sub == 0) {
+#pragma unroll
+      for (int hh = 0; hh < R; ++hh)
+#pragma unroll
+        for (int k = 0; k < EPL; ++k) s_acc[(w * R + hh) * HD + seg * EPL + k] = acc[hh][k];
+    }
   }
   __syncthreads();
 
