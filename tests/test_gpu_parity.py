@@ -118,6 +118,62 @@ def test_decode_matches_oracle(name, kw, chunk, mode):
     np.testing.assert_array_equal(m[~real], cache.metric.numpy().astype(np.float64)[~real])
 
 
+DOMINANT_CASES = [
+    ("bf16_r8", dict(r=8, d=128, kv_dtype="bf16", L=600), 128),
+    ("fp8_r8", dict(r=8, d=128, kv_dtype="fp8", L=600), 128),
+    ("bf16_r4", dict(r=4, d=128, kv_dtype="bf16", L=600), 0),
+    ("fp8_r4", dict(r=4, d=128, kv_dtype="fp8", L=600), 0),
+    ("f32_r2_d64", dict(r=2, d=64, kv_dtype="f32", L=400), 64),
+]
+
+
+@pytest.mark.parametrize("name,kw,chunk", DOMINANT_CASES, ids=[c[0] for c in DOMINANT_CASES])
+def test_decode_with_a_dominant_key(name, kw, chunk):
+    """One key per head instance is aligned with a query head of its group (probability close to
+    one for that head) and carries a large value row: the regime in which a probability that
+    entered the P V product with fewer than 16 bits would miss the tolerance."""
+    say("decode dominant key", name, kw, "chunk", chunk)
+    shape, ctx, seed = W.small_mixed(47, **kw)
+    cache = W.make_cache(shape, ctx, seed, placement="fragmented", init_metric="prefill")
+    q = W.make_query(shape, seed)
+    st0 = oracle_state(cache)
+    r = shape.num_q_heads // shape.num_kv_heads
+    kdt = cache.k_cache.dtype
+
+    def put(t, n, o, row):   # 8-bit tensors take no indexed assignment: move the bytes
+        if kdt == torch.float8_e4m3fn:
+            t.view(torch.uint8)[n, o] = row.to(kdt).view(torch.uint8)
+        else:
+            t[n, o] = row.to(kdt)
+
+    for g in range(st0.G):
+        n, o = O.slots_of(st0, g)
+        if len(n) < 3:
+            continue
+        s_, l_, h_ = np.unravel_index(g, (shape.num_seqs, shape.num_layers, shape.num_kv_heads))
+        j = (7 * g + 3) % len(n)                    # anywhere in the head, also in later chunks
+        hq = r * h_ + (g % r)                       # the query head it is aligned with
+        qrow = q[s_, l_, hq].float()
+        put(cache.k_cache, int(n[j]), int(o[j]), 2.0 * qrow)
+        vrow = cache.v_cache[int(n[j]), int(o[j])].float() if kdt != torch.float8_e4m3fn else \
+            cache.v_cache.view(torch.uint8)[int(n[j]), int(o[j])].view(kdt).float()
+        put(cache.v_cache, int(n[j]), int(o[j]), 3.0 * vrow + 1.0)
+    st = oracle_state(cache)
+    want = O.paged_decode(st, q.double().numpy())
+    B.kvc_set_decode_chunk(chunk)
+    try:
+        sess = session(cache)
+        out = sess.paged_decode(q.to(sess.device))
+        torch.cuda.synchronize()
+    finally:
+        B.kvc_set_decode_chunk(0)
+    # the setup did what it was meant to: some metric increment is close to its maximum of one per head
+    inc = st.metric - st0.metric
+    assert inc.max() > 0.9
+    np.testing.assert_allclose(out.cpu().numpy().astype(np.float64), want, rtol=0, atol=TOL)
+    np.testing.assert_allclose(sess.cache.metric.cpu().numpy().astype(np.float64), st.metric, rtol=0, atol=TOL)
+
+
 def test_decode_layer_range_and_no_metric():
     say("decode layer range")
     shape, ctx, seed = W.small_mixed(43, S=2, Lyr=3, Hk=2, r=4, d=128, L=300)
