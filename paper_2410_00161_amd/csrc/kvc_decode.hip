@@ -181,10 +181,13 @@ __host__ __device__ constexpr int decode_depth(int esz, int R, int HD, bool b16,
 
 __host__ __device__ inline size_t decode_lds_bytes(int T, int R, int HD, int b, int waves = kDecodeWaves,
                                                    bool mfma = false) {
-  return (mfma ? (size_t)waves * 16 * HD * 2 : 0)  // per-wavefront K tile on its way into operand order
-         + (size_t)T * R * 2                     // exp of every logit against its group's running max, 16-bit
+  // per-wavefront un-normalised output; on the matrix-core path the same bytes serve, while
+  // the main loop runs, as the wavefront's operand tile (16 tokens of d 16-bit elements)
+  const size_t per_wave_out = mfma ? ((size_t)R * HD * 4 > (size_t)16 * HD * 2 ? (size_t)R * HD * 4 : (size_t)16 * HD * 2)
+                                   : (size_t)R * HD * 4;
+  return (size_t)T * R * 2                       // exp of every logit against its group's running max, 16-bit
          + (size_t)(T / 16) * R * 4              // that running max, per 16-token group and head
-         + (size_t)waves * R * HD * 4            // per-wavefront un-normalised output
+         + (size_t)waves * per_wave_out
          + (size_t)waves * 16 * R * 4            // per-wavefront exp of the current group, f32
          + 2 * waves * R * 4                     // per-wavefront max and sum
          + ((size_t)T / b + 1) * 4;              // block ids of the chunk
@@ -249,7 +252,10 @@ __global__ void __launch_bounds__(NW * 64) decode_chunk_kernel(DecodeArgs A) {
 
   extern __shared__ __align__(16) char smem_raw[];
   uint4* s_kt = (uint4*)smem_raw;                      // MF: [waves][16 tokens][16 cells of 16 bytes]
-  float* s_acc = (float*)(smem_raw + (MF ? (size_t)NW * 16 * HD * 2 : 0));  // [waves][R][HD]
+  // [waves][R][HD]; on the matrix-core path a wavefront's 4 KiB of it are its operand tile until
+  // its main loop ends (R * HD * 4 = 16 * HD * 2 there, so no wavefront touches another's tile)
+  float* s_acc = (float*)smem_raw;
+  static_assert(!MF || (size_t)R * HD * 4 == (size_t)16 * HD * 2, "output rows alias the operand tile wavefront by wavefront");
   float* s_e = s_acc + NW * R * HD;          // [waves][16][R]
   float* s_red = s_e + NW * 16 * R;          // [2][waves][R]
   float* s_gm = s_red + 2 * NW * R;          // [T / 16][R]
@@ -874,19 +880,22 @@ static bool choose_chunk(const Dims& D, int gsel, int* T_out, size_t* lds_out, b
   bool tiled = (D.r == 1 || D.r == 2 || D.r == 4 || D.r == 8) && (D.d == 64 || D.d == 128) &&
                tpi >= 1 && D.b % tpi == 0 && 64 % D.b == 0;
   if (!tiled) return false;
-  // default: a chunk that lets two workgroups share a CU
-  int T = g_chunk_tokens ? g_chunk_tokens : (D.r >= 8 ? 2560 : 6144);
+  // default: a chunk that lets two workgroups share a CU (at r = 8, d = 128, 16-bit rows: 3456
+  // tokens x 16 bytes of exps + the rest = 81 764 of the 81 920 bytes a half CU has)
+  int T = g_chunk_tokens ? g_chunk_tokens : (D.r >= 8 ? 3456 : 6144);
   const int T_default = T;
   if (!g_chunk_tokens) {
     // a call over few head instances (one layer at a time) has too few long chunks to fill the
     // chip: shorten them until full rows would give a few thousand work items
     const long long want_items = 6144;
-    while (T > 256 && (long long)gsel * (((long long)D.maxb * D.b + T - 1) / T) < want_items) T /= 2;
+    // (halved and rounded up to whole 64-token strips: a chunk starts on a block boundary)
+    while (T > 256 && (long long)gsel * (((long long)D.maxb * D.b + T - 1) / T) < want_items)
+      T = ((T / 2) + 63) & ~63;
   }
   const bool mf = decode_uses_mfma(esz, D.r, D.d, D.b);
   while (T > kMinChunk && decode_lds_bytes(T, D.r, D.d, D.b, kDecodeWaves, mf) > kLdsLimit) T -= 64;
   const size_t lds = decode_lds_bytes(T, D.r, D.d, D.b, kDecodeWaves, mf);
-  if (lds > kLdsLimit) return false;
+  if (lds > kLdsLimit || T % 64 != 0) return false;
   *T_out = T;
   *lds_out = lds;
   if (small_call) *small_call = T < T_default;

@@ -61,6 +61,24 @@ def test_status_strings_and_chunk_knob():
     assert L.kvc_set_decode_chunk(0) == B.KVC_OK
 
 
+def test_chunk_length_is_whole_strips_for_every_shape():
+    """The chunk length the library picks (shortened for calls over few head instances, capped by
+    the LDS) is a whole number of 64-token strips, so that a chunk starts on a block boundary."""
+    for r in (1, 2, 4, 8):
+        for d in (64, 128):
+            for dt in ("bf16", "f32", "fp8"):
+                for b in (4, 16, 64):
+                    for seqs, layers, maxb in ((1, 1, 8), (2, 2, 400), (3, 1, 2000), (64, 32, 512), (16, 80, 8192 // b * 16)):
+                        cfg = B.make_config(seqs, layers, 2, r, d, b, 64, maxb, dt)
+                        if B.kvc_validate(cfg) != B.KVC_OK:
+                            continue
+                        t = B.kvc_get_decode_chunk(cfg)
+                        s_ = B.kvc_get_decode_short(cfg)
+                        assert t % 64 == 0 and t >= 0, (r, d, dt, b, seqs, layers, maxb, t)
+                        if t:
+                            assert 0 < s_ <= min(t, 512)
+
+
 def test_entry_points_reject_bad_arguments_on_the_host():
     """Null state pointers, a misaligned workspace and a bad layer range are
     refused before anything is launched (so this runs without a GPU)."""

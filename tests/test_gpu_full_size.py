@@ -209,7 +209,7 @@ def test_llama70b_shape_long_heads_sampled(forced_chunk):
     del cache
     chunk = B.kvc_get_decode_chunk(sess.cfg)
     G, r, d = shape.G, shape.group_size, shape.head_dim
-    assert int(sess.cache.ctx_len.max()) >= 50 * chunk    # dozens of chunks per head either way
+    assert int(sess.cache.ctx_len.max()) >= 32 * chunk    # dozens of chunks per head either way
     c = sess.cache.ctx_len.reshape(-1).cpu()
     order = torch.argsort(c)
     g0 = torch.Generator().manual_seed(seed)

@@ -53,6 +53,11 @@ DECODE_CASES = [
     ("bf16_d128_r4_split", dict(r=4, d=128, kv_dtype="bf16", L=700), 128, B.KVC_L2),
     ("bf16_d128_r8_split", dict(r=8, d=128, kv_dtype="bf16", L=500), 64, B.KVC_L2),
     ("bf16_odd_chunk", dict(r=4, d=128, kv_dtype="bf16", L=1500, rho=2.0, S=2), 1088, B.KVC_L2),
+    # few head instances: the library shortens its chunks by itself; blocks of 64 tokens and
+    # r = 8 are the cases in which a halved chunk must still start on a block boundary
+    ("bf16_b64_default_chunk", dict(r=4, d=128, kv_dtype="bf16", L=1500, rho=2.0, S=2, b=64), 0, B.KVC_L2),
+    ("bf16_r8_default_chunk", dict(r=8, d=128, kv_dtype="bf16", L=1500, rho=2.0, S=2), 0, B.KVC_L2),
+    ("fp8_r8_b32_default_chunk", dict(r=8, d=128, kv_dtype="fp8", L=1500, rho=2.0, S=2, b=32), 0, B.KVC_L2),
     ("bf16_d128_r1", dict(r=1, d=128, kv_dtype="bf16", L=300), 0, B.KVC_L2),
     ("bf16_d128_r2_L1", dict(r=2, d=128, kv_dtype="bf16", L=300), 64, B.KVC_L1),
     ("bf16_d64_r4", dict(r=4, d=64, kv_dtype="bf16", L=400), 128, B.KVC_L2),
