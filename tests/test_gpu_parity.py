@@ -123,6 +123,46 @@ def test_decode_matches_oracle(name, kw, chunk, mode):
     np.testing.assert_array_equal(m[~real], cache.metric.numpy().astype(np.float64)[~real])
 
 
+def _shape_matrix():
+    """Every query-group size x row type x head dimension, each with a block size and a chunk
+    setting taken in rotation (0 = the library's own choice for a call over few heads)."""
+    cases, i = [], 0
+    blocks = (16, 64, 8, 32, 4)
+    chunks = (0, 64, 0, 192, 0, 1088)
+    for r in (1, 2, 4, 8):
+        for dt in ("bf16", "f32", "fp8"):
+            for d in (64, 128):
+                for rep in range(2):
+                    b, chunk = blocks[i % len(blocks)], chunks[i % len(chunks)]
+                    i += 1
+                    cases.append((f"r{r}_{dt}_d{d}_b{b}_c{chunk}", dict(r=r, d=d, kv_dtype=dt, b=b), chunk))
+    return cases
+
+
+SHAPE_MATRIX = _shape_matrix()
+
+
+@pytest.mark.parametrize("name,kw,chunk", SHAPE_MATRIX, ids=[c[0] for c in SHAPE_MATRIX])
+def test_decode_over_the_matrix_of_shapes(name, kw, chunk):
+    say("decode shape matrix", name)
+    shape, ctx, seed = W.small_mixed(59, S=2, Lyr=1, Hk=2, L=1300, rho=2.0, **kw)
+    ctx[0] = 1300                    # one head at the full length: several chunks at every setting
+    cache = W.make_cache(shape, ctx, seed, placement="fragmented", init_metric="prefill")
+    st = oracle_state(cache)
+    q = W.make_query(shape, seed)
+    want = O.paged_decode(st, q.double().numpy())
+    B.kvc_set_decode_chunk(chunk)
+    try:
+        sess = session(cache)
+        out = sess.paged_decode(q.to(sess.device))
+        torch.cuda.synchronize()
+    finally:
+        B.kvc_set_decode_chunk(0)
+    np.testing.assert_allclose(out.cpu().numpy().astype(np.float64), want, rtol=0, atol=TOL)
+    live = st.free_map == 0
+    np.testing.assert_allclose(sess.cache.metric.cpu().numpy().astype(np.float64)[live], st.metric[live], rtol=0, atol=TOL)
+
+
 DOMINANT_CASES = [
     ("bf16_r8", dict(r=8, d=128, kv_dtype="bf16", L=600), 128),
     ("fp8_r8", dict(r=8, d=128, kv_dtype="fp8", L=600), 128),
