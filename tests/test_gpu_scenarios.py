@@ -113,6 +113,45 @@ def test_prefill_end_compression_from_an_observation_window():
     assert_state_equal(sess, st)
 
 
+def _round_matrix():
+    cases, i = [], 0
+    for b in (1, 2, 4, 8, 16, 32, 64):
+        for dt in ("bf16", "f32", "fp8"):
+            d, r = ((64, 2), (128, 4), (128, 8), (64, 1))[i % 4]
+            i += 1
+            cases.append((f"b{b}_{dt}_d{d}_r{r}", dict(b=b, kv_dtype=dt, d=d, r=r)))
+    return cases
+
+
+ROUND_MATRIX = _round_matrix()
+
+
+@pytest.mark.parametrize("name,kw", ROUND_MATRIX, ids=[c[0] for c in ROUND_MATRIX])
+def test_compression_rounds_over_block_sizes_and_row_types(name, kw):
+    """Append + decode, a physical-block round, append + decode, a rank-block round, decode:
+    every block size from 1 to 64 tokens with every row type."""
+    say("rounds over shapes", name)
+    L = 40 * max(kw["b"], 4)
+    shape, ctx, seed = W.small_mixed(131, S=3, Lyr=2, Hk=2, L=L, rho=2.0, extra_blocks=3, **kw)
+    cache = W.make_cache(shape, ctx, seed, placement="fragmented", init_metric="prefill")
+    st = oracle_state(cache)
+    sess = session(cache)
+    for step, mode in enumerate(("block", "rank", None)):
+        k, v = W.make_new_kv(shape, seed, step)
+        q = W.make_query(shape, seed, step)
+        O.append(st, k.double().numpy(), v.double().numpy())
+        want = O.paged_decode(st, q.double().numpy())
+        sess.append(k.to(sess.device), v.to(sess.device))
+        out = sess.paged_decode(q.to(sess.device))
+        torch.cuda.synchronize()
+        np.testing.assert_allclose(out.cpu().numpy(), want, rtol=0, atol=TOL)
+        if mode:
+            freed = evict_round(sess, st, 0.3, mode)
+            assert freed > 0
+            assert_state_equal(sess, st)
+            check_allocator_invariants(st)
+
+
 def test_group_of_eight_shape_with_long_heads():
     """70B-like grouping (8 query heads per KV head) with heads long enough to be split into
     several chunks at the default chunk length, then a rank-block round."""
