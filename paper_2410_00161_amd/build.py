@@ -32,7 +32,8 @@ HIPCC_FLAGS = [
 # Per-source additions.  The decode kernels keep their matrix-core accumulators in ordinary
 # vector registers: they are rescaled by plain multiplies whenever a running maximum moves, and
 # in the accumulator file every such multiply costs a copy out and a copy back.
-EXTRA_FLAGS = {"kvc_decode.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
+EXTRA_FLAGS = {"kvc_decode.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
+               "kvc_window.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
 
 
 def _run(cmd):

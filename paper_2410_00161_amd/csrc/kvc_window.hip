@@ -17,6 +17,8 @@
 // keys (online, then merged over lanes, wavefronts and chunks); (2) normalised
 // probabilities, squared, summed over the query rows per key.  V is never
 // read.  A last light pass max-pools over the logical sequence.
+#include <type_traits>
+
 #include "kvc_common.h"
 #include "kvc_worklist.h"
 
@@ -98,8 +100,8 @@ __global__ void __launch_bounds__(kWinThreads) window_stats_kernel(WindowArgs W)
     return;
   extern __shared__ __align__(16) char smem_raw[];
   uint4* s_q = (uint4*)smem_raw;                        // [NT * 4 * 64]
-  float* s_ml = (float*)(s_q + NT * 4 * 64);            // [waves][NT * 16][2]
-  float2* s_st = (float2*)(s_ml + kWinWaves * NT * 16 * 2);  // [waves][NT][64]
+  float* s_ml = (float*)s_q;                            // [waves][NT * 16][2], once the main loops are over
+  float2* s_st = (float2*)(s_q + NT * 4 * 64);          // [waves][NT][64]
   int* s_tab = (int*)(s_st + kWinWaves * NT * 64);      // [T / b + 1]
   const int b = A.D.b, lb = A.log2b;
   const int C = A.ctx[g];
@@ -120,44 +122,53 @@ __global__ void __launch_bounds__(kWinThreads) window_stats_kernel(WindowArgs W)
   for (int tt = wv * 64; tt < n_tok && !dead; tt += 64 * kWinWaves) {
     uint4 k[4][4];
     load_tile(W, s_tab, tt, n_tok, lane, k);
-    const bool masked = t0 + tt + 63 > free_lim;
+    // most tiles lie wholly in front of the window: they run the loop without the causal mask
+    auto column_tiles = [&](auto masked_c) {
+      constexpr bool kMasked = decltype(masked_c)::value;
 #pragma unroll 1
-    for (int ct = 0; ct < NT; ++ct) {
-      uint4 q[4];
+      for (int ct = 0; ct < NT; ++ct) {
+        uint4 q[4];
 #pragma unroll
-      for (int kk = 0; kk < 4; ++kk) q[kk] = s_q[(ct * 4 + kk) * 64 + lane];
-      const int rho = ct * 16 + (lane & 15);
-      const int last_vis = min(first_free + rho / A.D.r, C - 1);  // query i sees keys 0 .. its position
-      // the running max stays in raw dot-product units inside the loop: the scale goes into one
-      // multiply-add per logit (max, fma, exp2, add)
-      const float2 old = my_st[ct * 64];
-      float s[16];
-      float mx = old.x;
+        for (int kk = 0; kk < 4; ++kk) q[kk] = s_q[(ct * 4 + kk) * 64 + lane];
+        int last_vis = 0;
+        if constexpr (kMasked) {
+          const int rho = ct * 16 + (lane & 15);
+          last_vis = min(first_free + rho / A.D.r, C - 1);  // query i sees keys 0 .. its position
+        }
+        // the running max stays in raw dot-product units inside the loop: the scale goes into one
+        // multiply-add per logit (max, fma, exp2, add)
+        const float2 old = my_st[ct * 64];
+        float s[16];
+        float mx = old.x;
 #pragma unroll
-      for (int tg = 0; tg < 4; ++tg) {
-        f32x4_t acc = {0.0f, 0.0f, 0.0f, 0.0f};
+        for (int tg = 0; tg < 4; ++tg) {
+          f32x4_t acc = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) acc = mfma16(k[tg][kk], q[kk], acc);
+          for (int kk = 0; kk < 4; ++kk) acc = mfma16(k[tg][kk], q[kk], acc);
 #pragma unroll
-        for (int v = 0; v < 4; ++v) {
-          float x = acc[v];
-          if (masked) {
-            const int j = t0 + tt + tg * 16 + 4 * (lane >> 4) + v;
-            if (j > last_vis) x = -INFINITY;
+          for (int v = 0; v < 4; ++v) {
+            float x = acc[v];
+            if constexpr (kMasked) {
+              const int j = t0 + tt + tg * 16 + 4 * (lane >> 4) + v;
+              if (j > last_vis) x = -INFINITY;
+            }
+            s[tg * 4 + v] = x;
+            mx = fmaxf(mx, x);
           }
-          s[tg * 4 + v] = x;
-          mx = fmaxf(mx, x);
+        }
+        if (mx > -INFINITY) {
+          const float off = -mx * A.scale_log2;
+          float sum = old.y * __builtin_amdgcn_exp2f(fmaf(old.x, A.scale_log2, off));
+#pragma unroll
+          for (int e = 0; e < 16; ++e) sum += __builtin_amdgcn_exp2f(fmaf(s[e], A.scale_log2, off));
+          my_st[ct * 64] = make_float2(mx, sum);
         }
       }
-      if (mx > -INFINITY) {
-        const float off = -mx * A.scale_log2;
-        float sum = old.y * __builtin_amdgcn_exp2f(fmaf(old.x, A.scale_log2, off));
-#pragma unroll
-        for (int e = 0; e < 16; ++e) sum += __builtin_amdgcn_exp2f(fmaf(s[e], A.scale_log2, off));
-        my_st[ct * 64] = make_float2(mx, sum);
-      }
-    }
+    };
+    if (t0 + tt + 63 > free_lim) column_tiles(std::true_type{});
+    else column_tiles(std::false_type{});
   }
+  __syncthreads();   // every wavefront is done with Q: its bytes now take the per-wavefront pairs
   // merge the four lanes that share a query row, then the wavefronts, then write the chunk's pair
   for (int ct = 0; ct < NT; ++ct) {
     float2 st = my_st[ct * 64];
@@ -189,6 +200,29 @@ __global__ void __launch_bounds__(kWinThreads) window_stats_kernel(WindowArgs W)
   }
 }
 
+// Between the passes, once per head instance (the workgroup of its first chunk): the head's max
+// and sum per query row from the per-chunk pairs, left as max + log2(sum) in the first chunk's
+// slot, so that p = exp2(logit - that).  Padded rows and rows that see no key get +inf there:
+// their p is exactly 0.  (Done here, not by every chunk's workgroup in pass 2: there the walk
+// over the chunks' pairs, one dependent load after the other, was most of a workgroup's life.)
+__global__ void __launch_bounds__(256) window_rows_kernel(WindowArgs W, int rows_pad) {
+  const DecodeArgs& A = W.A;
+  const int total_items = A.header[HW_TOTAL_ITEMS];
+  if ((int)blockIdx.x >= total_items || total_items > A.cap) return;
+  const DecodeItem it = A.items[blockIdx.x];
+  if (it.t0 != 0 || (unsigned)it.g >= (unsigned)A.D.G || it.nch <= 0 || it.pbase < 0 || it.pbase + it.nch > A.cap) return;
+  for (int rho = threadIdx.x; rho < rows_pad; rho += 256) {
+    float mm = -INFINITY, ll = 0.0f;
+    for (int cc = 0; cc < it.nch; ++cc) {
+      const float2 ml = *(const float2*)(W.part + (((size_t)it.pbase + cc) * rows_pad + rho) * 2);
+      const float nm = fmaxf(mm, ml.x);
+      if (nm > -INFINITY) ll = ll * __builtin_amdgcn_exp2f(mm - nm) + ml.y * __builtin_amdgcn_exp2f(ml.x - nm);
+      mm = nm;
+    }
+    W.part[((size_t)it.pbase * rows_pad + rho) * 2] = (rho < W.rows && ll > 0.0f) ? mm + __builtin_amdgcn_logf(ll) : INFINITY;
+  }
+}
+
 // Pass 2: raw[j] = sum over query rows of p^2 (or p), p normalised with the head's max and sum.
 template <int NT, bool L2>
 __global__ void __launch_bounds__(kWinThreads) window_sum_kernel(WindowArgs W) {
@@ -205,7 +239,7 @@ __global__ void __launch_bounds__(kWinThreads) window_sum_kernel(WindowArgs W) {
   extern __shared__ __align__(16) char smem_raw[];
   uint4* s_q = (uint4*)smem_raw;                        // [NT * 4 * 64]
   float* s_ml = (float*)(s_q + NT * 4 * 64);            // [NT * 16]: max + log2(sum) per query row (inf: the row adds nothing)
-  int* s_tab = (int*)((float2*)(s_ml + kWinWaves * NT * 16 * 2) + kWinWaves * NT * 64);  // same carve as pass 1
+  int* s_tab = (int*)(s_ml + NT * 16);                  // [T / b + 1]
   const int b = A.D.b, lb = A.log2b;
   const int C = A.ctx[g];
   {
@@ -214,19 +248,7 @@ __global__ void __launch_bounds__(kWinThreads) window_sum_kernel(WindowArgs W) {
     for (int i = tid; i < nblk; i += kWinThreads) s_tab[i] = row[i];
   }
   stage_queries<NT>(W, g, s_q);
-  for (int rho = tid; rho < NT * 16; rho += kWinThreads) {
-    float mm = -INFINITY, ll = 0.0f;
-    for (int cc = 0; cc < nch; ++cc) {
-      const float* p = W.part + (((size_t)it.pbase + cc) * NT * 16 + rho) * 2;
-      const float om = p[0], ol = p[1];
-      const float nm = fmaxf(mm, om);
-      if (nm > -INFINITY) ll = ll * __builtin_amdgcn_exp2f(mm - nm) + ol * __builtin_amdgcn_exp2f(om - nm);
-      mm = nm;
-    }
-    // p = exp2(logit - max) / sum = exp2(logit - (max + log2 sum)); padded rows and rows that see
-    // no key get +inf there, so that their p is exactly 0
-    s_ml[rho] = (rho < W.rows && ll > 0.0f) ? mm + __builtin_amdgcn_logf(ll) : INFINITY;
-  }
+  for (int rho = tid; rho < NT * 16; rho += kWinThreads) s_ml[rho] = W.part[((size_t)it.pbase * NT * 16 + rho) * 2];
   __syncthreads();
   const int first_free = W.first_pos >= 0 ? W.first_pos : C - W.w;
   const int free_lim = min(first_free, C - 1) - W.exclude;   // keys up to here count for every query
@@ -239,34 +261,39 @@ __global__ void __launch_bounds__(kWinThreads) window_sum_kernel(WindowArgs W) {
   for (int tt = wv * 64; tt < n_tok; tt += 64 * kWinWaves) {
     uint4 k[4][4];
     load_tile(W, s_tab, tt, n_tok, lane, k);
-    const bool masked = t0 + tt + 63 > free_lim;
     float tok[16];
 #pragma unroll
     for (int e = 0; e < 16; ++e) tok[e] = 0.0f;
+    auto column_tiles = [&](auto masked_c) {
+      constexpr bool kMasked = decltype(masked_c)::value;
 #pragma unroll 1
-    for (int ct = 0; ct < NT; ++ct) {
-      uint4 q[4];
+      for (int ct = 0; ct < NT; ++ct) {
+        uint4 q[4];
 #pragma unroll
-      for (int kk = 0; kk < 4; ++kk) q[kk] = s_q[(ct * 4 + kk) * 64 + lane];
-      const int rho = ct * 16 + (lane & 15);
-      const int last_vis = min(first_free + rho / A.D.r, C - 1) - W.exclude;
-      const float c_row = s_ml[rho];
+        for (int kk = 0; kk < 4; ++kk) q[kk] = s_q[(ct * 4 + kk) * 64 + lane];
+        const int rho = ct * 16 + (lane & 15);
+        int last_vis = 0;
+        if constexpr (kMasked) last_vis = min(first_free + rho / A.D.r, C - 1) - W.exclude;
+        const float c_row = s_ml[rho];
 #pragma unroll
-      for (int tg = 0; tg < 4; ++tg) {
-        f32x4_t acc = {0.0f, 0.0f, 0.0f, 0.0f};
+        for (int tg = 0; tg < 4; ++tg) {
+          f32x4_t acc = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) acc = mfma16(k[tg][kk], q[kk], acc);
+          for (int kk = 0; kk < 4; ++kk) acc = mfma16(k[tg][kk], q[kk], acc);
 #pragma unroll
-        for (int v = 0; v < 4; ++v) {
-          float p = __builtin_amdgcn_exp2f(fmaf(acc[v], A.scale_log2, -c_row));
-          if (masked) {
-            const int j = t0 + tt + tg * 16 + 4 * (lane >> 4) + v;
-            if (j > last_vis) p = 0.0f;
+          for (int v = 0; v < 4; ++v) {
+            float p = __builtin_amdgcn_exp2f(fmaf(acc[v], A.scale_log2, -c_row));
+            if constexpr (kMasked) {
+              const int j = t0 + tt + tg * 16 + 4 * (lane >> 4) + v;
+              if (j > last_vis) p = 0.0f;
+            }
+            tok[tg * 4 + v] = L2 ? fmaf(p, p, tok[tg * 4 + v]) : tok[tg * 4 + v] + p;
           }
-          tok[tg * 4 + v] = L2 ? fmaf(p, p, tok[tg * 4 + v]) : tok[tg * 4 + v] + p;
         }
       }
-    }
+    };
+    if (t0 + tt + 63 > free_lim) column_tiles(std::true_type{});
+    else column_tiles(std::false_type{});
     // sum over the 16 lanes of a row group: lane % 16 == e ends up with value e
     Butterfly<16, 8>::run(tok, lane);
     const int e = lane & 15;
@@ -278,21 +305,39 @@ __global__ void __launch_bounds__(kWinThreads) window_sum_kernel(WindowArgs W) {
   }
 }
 
-// Max-pool over the logical sequence and the write into the metric.  One workgroup per head.
+// Max-pool over the logical sequence and the write into the metric.  One workgroup per head
+// instance and tile of 2048 logical positions: the tile's un-pooled sums and a halo of pool / 2
+// on either side are gathered into LDS once (a pool wider than the halo the LDS array has room
+// for reads its neighbours from global memory instead).
+constexpr int kPoolTile = 2048;
+constexpr int kPoolHalo = 64;
 __global__ void __launch_bounds__(256) window_pool_kernel(WindowArgs W) {
   const DecodeArgs& A = W.A;
   const int gi = blockIdx.x;
   const int g = sel_to_g(A.D, A.l0, A.nl, gi);
   const int C = A.ctx[g];
-  const int b = A.D.b;
+  const int j0 = blockIdx.y * kPoolTile;
+  if (j0 >= C) return;
+  const int j1 = min(C, j0 + kPoolTile);
+  const int b = A.D.b, lb = A.log2b;
   const int32_t* row = A.table + (size_t)g * A.D.maxb;
   const int P = W.first_pos >= 0 ? 0 : max(0, C - W.w), half = W.pool / 2;
-  for (int j = threadIdx.x; j < C; j += 256) {
-    const size_t slot = (size_t)row[j / b] * b + (j % b);
-    float v = W.raw[slot];
+  __shared__ float s_raw[kPoolTile + 2 * kPoolHalo];
+  const bool staged = half <= kPoolHalo;
+  const int lo0 = staged ? max(0, j0 - half) : j0, hi0 = staged ? min(C, j1 + half) : j1;
+  for (int j = lo0 + threadIdx.x; j < hi0; j += 256)
+    s_raw[j - lo0] = W.raw[((size_t)row[j >> lb] << lb) + (j & (b - 1))];
+  __syncthreads();
+  for (int j = j0 + threadIdx.x; j < j1; j += 256) {
+    const size_t slot = ((size_t)row[j >> lb] << lb) + (j & (b - 1));
+    float v = s_raw[j - lo0];
     if (j < P) {
       const int lo = max(0, j - half), hi = min(P - 1, j + half);
-      for (int t = lo; t <= hi; ++t) v = fmaxf(v, W.raw[(size_t)row[t / b] * b + (t % b)]);
+      if (staged) {
+        for (int t = lo; t <= hi; ++t) v = fmaxf(v, s_raw[t - lo0]);
+      } else {
+        for (int t = lo; t <= hi; ++t) v = fmaxf(v, W.raw[((size_t)row[t >> lb] << lb) + (t & (b - 1))]);
+      }
     }
     A.metric[slot] = W.add ? A.metric[slot] + v : v;
   }
@@ -300,19 +345,25 @@ __global__ void __launch_bounds__(256) window_pool_kernel(WindowArgs W) {
 
 template <int NT>
 static int launch_window(const WindowArgs& W, int grid, hipStream_t s) {
-  const size_t lds = (size_t)NT * 4 * 64 * 16 + (size_t)kWinWaves * NT * 16 * 2 * 4 + (size_t)kWinWaves * NT * 64 * 8 +
-                     ((size_t)kWinChunk / W.A.D.b + 1) * 4;
+  // pass 1: Q (later the per-wavefront pairs), running pairs per lane and column tile, block ids;
+  // pass 2: Q, one float per query row, block ids.  Three and four workgroups per CU at 128 rows.
+  const size_t tab = ((size_t)kWinChunk / W.A.D.b + 1) * 4;
+  const size_t lds = (size_t)NT * 4 * 64 * 16 + (size_t)kWinWaves * NT * 64 * 8 + tab;
+  const size_t lds2 = (size_t)NT * 4 * 64 * 16 + (size_t)NT * 16 * 4 + tab;
+  static_assert((size_t)kWinWaves * NT * 16 * 2 * 4 <= (size_t)NT * 4 * 64 * 16, "pairs fit where Q was");
   static bool told = false;
-  if (lds > 64 * 1024 && !told) {
+  if ((lds > 64 * 1024 || lds2 > 64 * 1024) && !told) {  // above the default cap a kernel must be told once
     KVC_HIP(hipFuncSetAttribute((const void*)window_stats_kernel<NT>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    KVC_HIP(hipFuncSetAttribute((const void*)window_sum_kernel<NT, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    KVC_HIP(hipFuncSetAttribute((const void*)window_sum_kernel<NT, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    KVC_HIP(hipFuncSetAttribute((const void*)window_sum_kernel<NT, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds2));
+    KVC_HIP(hipFuncSetAttribute((const void*)window_sum_kernel<NT, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds2));
     told = true;
   }
   hipLaunchKernelGGL(window_stats_kernel<NT>, dim3(grid), dim3(kWinThreads), lds, s, W);
   KVC_LAUNCH_CHECK();
-  if (W.A.D.mode == KVC_L2) hipLaunchKernelGGL((window_sum_kernel<NT, true>), dim3(grid), dim3(kWinThreads), lds, s, W);
-  else hipLaunchKernelGGL((window_sum_kernel<NT, false>), dim3(grid), dim3(kWinThreads), lds, s, W);
+  hipLaunchKernelGGL(window_rows_kernel, dim3(grid), dim3(256), 0, s, W, NT * 16);
+  KVC_LAUNCH_CHECK();
+  if (W.A.D.mode == KVC_L2) hipLaunchKernelGGL((window_sum_kernel<NT, true>), dim3(grid), dim3(kWinThreads), lds2, s, W);
+  else hipLaunchKernelGGL((window_sum_kernel<NT, false>), dim3(grid), dim3(kWinThreads), lds2, s, W);
   KVC_LAUNCH_CHECK();
   return KVC_OK;
 }
@@ -376,7 +427,9 @@ static int window_common(const kvc_config* cfg, const kvc_state* st, const void*
     default: rc = launch_window<16>(W, (int)grid, s); break;
   }
   if (rc != KVC_OK) return rc;
-  hipLaunchKernelGGL(window_pool_kernel, dim3(A.gsel), dim3(256), 0, s, W);
+  const int pool_tiles = (int)(((size_t)D.maxb * D.b + kPoolTile - 1) / kPoolTile);
+  if (pool_tiles > 65535) return KVC_ERR_UNSUPPORTED;
+  hipLaunchKernelGGL(window_pool_kernel, dim3(A.gsel, pool_tiles), dim3(256), 0, s, W);
   KVC_LAUNCH_CHECK();
   return KVC_OK;
 }
