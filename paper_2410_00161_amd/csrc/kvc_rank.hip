@@ -57,13 +57,15 @@ __global__ void __launch_bounds__(256) rank_init_kernel(Dims D, const int32_t* _
   if (i < D.G) evict_rows[i] = 0;
 }
 
-// One workgroup per heads_per_wg consecutive head instances, one after the other.  Counts a
+// One workgroup (NTH threads: 256, or 1024 when there are few, long heads) per heads_per_wg
+// consecutive head instances, one after the other.  Counts a
 // head's entries below the prefix found so far and histograms the next digit of those that
 // match it; turns the running counts into rows per digit; the rows of all its heads go to the
 // segment's histogram together (thread = digit), so that one address sees G / heads_per_wg
 // adds per pass instead of G: adds to one word from all over the chip run one after the other,
 // and in the first pass (the exponent byte) nearly every head lands on the same digit.
-__global__ void __launch_bounds__(256) rank_hist_kernel(Dims D, int pass, int protect, int heads_per_wg,
+template <int NTH>
+__global__ void __launch_bounds__(NTH) rank_hist_kernel(Dims D, int pass, int protect, int heads_per_wg,
                                                         const float* __restrict__ metric,
                                                         const int32_t* __restrict__ table,
                                                         const int32_t* __restrict__ ctx,
@@ -73,15 +75,17 @@ __global__ void __launch_bounds__(256) rank_hist_kernel(Dims D, int pass, int pr
                                                         int32_t* __restrict__ header) {
   __shared__ int hist[256];
   __shared__ int below_s;
-  __shared__ int smem[256 / 64 + 1];
+  __shared__ int smem[NTH / 64 + 1];
   const int tid = threadIdx.x;
   const int g_first = blockIdx.x * heads_per_wg;
   const int g_end = min(D.G, g_first + heads_per_wg);
   const int shift = 24 - 8 * pass;
+  int lb = 0;
+  while ((1 << lb) < D.b) ++lb;   // block sizes are powers of two
   int cur_sg = -1, rows_acc = 0, cand_acc = 0;
   auto flush = [&]() {
     if (cur_sg < 0) return;
-    if (rows_acc) atomicAdd(&seg_hist[cur_sg * 256 + tid], rows_acc);
+    if (tid < 256 && rows_acc) atomicAdd(&seg_hist[cur_sg * 256 + tid], rows_acc);
     if (pass == 0 && tid == 0 && cand_acc) atomicAdd(&seg_state[cur_sg * 8 + RS_CAND], cand_acc);
     rows_acc = 0;
     cand_acc = 0;
@@ -95,15 +99,15 @@ __global__ void __launch_bounds__(256) rank_hist_kernel(Dims D, int pass, int pr
     cand_acc += ncand;
     if (ncand == 0) continue;
     if (pass > 0 && seg_state[sg * 8 + RS_TAKE] <= 0) continue;
-    hist[tid] = 0;
+    if (tid < 256) hist[tid] = 0;
     if (tid == 0) below_s = 0;
     __syncthreads();
     const uint32_t prefix = (uint32_t)seg_state[sg * 8 + RS_PREFIX];
     const int32_t* row = table + (size_t)g * D.maxb;
     int below = 0;
     bool bad = false;
-    for (int j = tid; j < C; j += 256) {
-      const uint32_t k = metric_bits(metric[(size_t)row[j / D.b] * D.b + (j % D.b)]);
+    for (int j = tid; j < C; j += NTH) {
+      const uint32_t k = metric_bits(metric[((size_t)row[j >> lb] << lb) + (j & (D.b - 1))]);
       if (pass == 0) bad |= k >= 0x7f800000u;
       const uint32_t top = pass == 0 ? 0u : (k >> (shift + 8));
       if (top < prefix) ++below;
@@ -117,9 +121,9 @@ __global__ void __launch_bounds__(256) rank_hist_kernel(Dims D, int pass, int pr
     if ((tid & 63) == 0 && below) atomicAdd(&below_s, below);
     if (bad) atomicOr(&header[HW_SCRATCH0], EB_NUMERIC);
     __syncthreads();
-    const int c = hist[tid];
-    const int ex = block_exclusive_scan<256>(c, smem, nullptr) + below_s;
-    rows_acc += min(ncand, (ex + c) / D.b) - min(ncand, ex / D.b);
+    const int c = tid < 256 ? hist[tid] : 0;
+    const int ex = block_exclusive_scan<NTH>(c, smem, nullptr) + below_s;
+    if (tid < 256) rows_acc += min(ncand, (ex + c) >> lb) - min(ncand, ex >> lb);
     __syncthreads();   // hist and below_s are reused by the next head
   }
   flush();
@@ -243,7 +247,10 @@ __global__ void __launch_bounds__(256) rank_check_kernel(Dims D, const int32_t* 
 
 // One workgroup per head.  scratch is an int array shaped like the metric ([N, b]); the head
 // uses the cells of its own blocks: hole k at logical cell k, mover k at logical cell C-1-k.
-__global__ void __launch_bounds__(256) rank_compact_kernel(Dims D, char* __restrict__ kc, char* __restrict__ vc,
+// NTH threads: 256 when there are many head instances, 1024 when there are few (a prompt's
+// worth of long heads), so that a head's passes over its metrics run four times as wide.
+template <int NTH>
+__global__ void __launch_bounds__(NTH) rank_compact_kernel(Dims D, char* __restrict__ kc, char* __restrict__ vc,
                                                            float* __restrict__ metric,
                                                            int32_t* __restrict__ pos,
                                                            int32_t* __restrict__ table,
@@ -257,35 +264,37 @@ __global__ void __launch_bounds__(256) rank_compact_kernel(Dims D, char* __restr
   const int e = evict_rows[g];
   if (e <= 0) return;
   __shared__ int hist[256];
-  __shared__ int smem[256 / 64 + 1];
+  __shared__ int smem[NTH / 64 + 1];
   __shared__ int chosen_s, prefix_s, remain_s, carry_tie, carry_ev, nholes_s;
   const int b = D.b;
+  int lb = 0;
+  while ((1 << lb) < b) ++lb;   // block sizes are powers of two
   const int C = ctx[g];
   const int nb = (C + b - 1) / b;
   const int n_ev = e * b - (nb * b - C);  // real KVs in the first e rows
   const int T = C - n_ev;                 // = (nb - e) * b
   int32_t* row = table + (size_t)g * D.maxb;
-  auto phys = [&](int j) -> size_t { return (size_t)row[j / b] * b + (j % b); };
+  auto phys = [&](int j) -> size_t { return ((size_t)row[j >> lb] << lb) + (j & (b - 1)); };
 
   // ---- threshold metric: the n_ev-th smallest by (metric, logical index) ----
   if (tid == 0) { prefix_s = 0; remain_s = n_ev; }
   __syncthreads();
   for (int pass = 0; pass < 4; ++pass) {
-    hist[tid] = 0;
+    if (tid < 256) hist[tid] = 0;
     __syncthreads();
     const int shift = 24 - 8 * pass;
     const uint32_t prefix = (uint32_t)prefix_s;
-    for (int j = tid; j < C; j += 256) {
+    for (int j = tid; j < C; j += NTH) {
       const uint32_t k = metric_bits(metric[phys(j)]);
       if (pass == 0 || (k >> (shift + 8)) == prefix) atomicAdd(&hist[(k >> shift) & 255], 1);
     }
     __syncthreads();
-    const int c = hist[tid];
-    const int ex = block_exclusive_scan<256>(c, smem, nullptr);
+    const int c = tid < 256 ? hist[tid] : 0;
+    const int ex = block_exclusive_scan<NTH>(c, smem, nullptr);
     const int remain = remain_s;
     if (tid == 0) chosen_s = -1;
     __syncthreads();
-    if (ex < remain && remain <= ex + c) chosen_s = tid;
+    if (tid < 256 && ex < remain && remain <= ex + c) chosen_s = tid;
     __syncthreads();
     if (tid == chosen_s) {
       prefix_s = (int)((prefix << 8) | (uint32_t)tid);
@@ -299,16 +308,16 @@ __global__ void __launch_bounds__(256) rank_compact_kernel(Dims D, char* __restr
   // ---- ordered pass: who is evicted, hole and mover ranks ----
   if (tid == 0) { carry_tie = 0; carry_ev = 0; nholes_s = 0; }
   __syncthreads();
-  for (int base = 0; base < C; base += 256) {
+  for (int base = 0; base < C; base += NTH) {
     const int j = base + tid;
     uint32_t k = 0xffffffffu;
     if (j < C) k = metric_bits(metric[phys(j)]);
     const int is_tie = (j < C) && k == thr;
     int tot_tie;
-    const int tie_rank = block_exclusive_scan<256>(is_tie, smem, &tot_tie) + carry_tie;
+    const int tie_rank = block_exclusive_scan<NTH>(is_tie, smem, &tot_tie) + carry_tie;
     const int ev = (j < C) && (k < thr || (is_tie && tie_rank < ties_take));
     int tot_ev;
-    const int ev_before = block_exclusive_scan<256>(ev, smem, &tot_ev) + carry_ev;
+    const int ev_before = block_exclusive_scan<NTH>(ev, smem, &tot_ev) + carry_ev;
     if (j < C) {
       if (ev) {
         if (j < T) { scratch[phys(ev_before)] = j; atomicAdd(&nholes_s, 1); }
@@ -325,7 +334,7 @@ __global__ void __launch_bounds__(256) rank_compact_kernel(Dims D, char* __restr
   const size_t row_bytes = (size_t)D.d * kv_esz(D.dtype);
   const int pieces = (int)(row_bytes / 16);
   const int grp = tid >> 4, gl = tid & 15;
-  for (int kk = grp; kk < n_moves; kk += 16) {
+  for (int kk = grp; kk < n_moves; kk += NTH / 16) {
     const size_t dst = phys(scratch[phys(kk)]);
     const size_t src = phys(scratch[phys(C - 1 - kk)]);
     for (int c = gl; c < pieces; c += 16) {
@@ -339,7 +348,7 @@ __global__ void __launch_bounds__(256) rank_compact_kernel(Dims D, char* __restr
   }
   __syncthreads();
   const int nb2 = nb - e;
-  for (int u = nb2 + tid; u < nb; u += 256) {
+  for (int u = nb2 + tid; u < nb; u += NTH) {
     free_map[row[u]] = 1;
     row[u] = -1;
   }
@@ -372,9 +381,13 @@ int kvc_evict_rank_select(const kvc_config* cfg, const kvc_state* st, const int3
     // first pass (the exponent byte): nearly every head lands on the same digit of its segment's
     // histogram, and four heads per workgroup (a quarter of the adds) measured fastest
     const int hpw = pass == 0 ? 4 : 1;
-    hipLaunchKernelGGL(rank_hist_kernel, dim3((D.G + hpw - 1) / hpw), dim3(256), 0, s, D, pass,
-                       protect_tail_blocks, hpw, st->metric,
-                       st->block_table, st->ctx_len, seq_seg, W.seg_hist, W.seg_state, W.header);
+    if (D.G <= 1024)
+      hipLaunchKernelGGL(rank_hist_kernel<1024>, dim3(D.G), dim3(1024), 0, s, D, pass, protect_tail_blocks, 1,
+                         st->metric, st->block_table, st->ctx_len, seq_seg, W.seg_hist, W.seg_state, W.header);
+    else
+      hipLaunchKernelGGL(rank_hist_kernel<256>, dim3((D.G + hpw - 1) / hpw), dim3(256), 0, s, D, pass,
+                         protect_tail_blocks, hpw, st->metric,
+                         st->block_table, st->ctx_len, seq_seg, W.seg_hist, W.seg_state, W.header);
     KVC_LAUNCH_CHECK();
     hipLaunchKernelGGL(rank_pick_kernel, dim3(nseg), dim3(256), 0, s, pass, budget, W.seg_hist, W.seg_state,
                        W.header);
@@ -409,9 +422,14 @@ int kvc_compact_rank(const kvc_config* cfg, const kvc_state* st, const int32_t* 
   KVC_LAUNCH_CHECK();
   hipLaunchKernelGGL(resolve_kernel, dim3(1), dim3(64), 0, s, W.header, 0);
   KVC_LAUNCH_CHECK();
-  hipLaunchKernelGGL(rank_compact_kernel, dim3(D.G), dim3(256), 0, s, D, (char*)st->k_cache, (char*)st->v_cache,
-                     st->metric, st->pos, st->block_table, st->ctx_len, st->free_map, evict_rows,
-                     (int32_t*)W.stash, W.header);
+  if (D.G <= 1024)
+    hipLaunchKernelGGL(rank_compact_kernel<1024>, dim3(D.G), dim3(1024), 0, s, D, (char*)st->k_cache, (char*)st->v_cache,
+                       st->metric, st->pos, st->block_table, st->ctx_len, st->free_map, evict_rows,
+                       (int32_t*)W.stash, W.header);
+  else
+    hipLaunchKernelGGL(rank_compact_kernel<256>, dim3(D.G), dim3(256), 0, s, D, (char*)st->k_cache, (char*)st->v_cache,
+                       st->metric, st->pos, st->block_table, st->ctx_len, st->free_map, evict_rows,
+                       (int32_t*)W.stash, W.header);
   KVC_LAUNCH_CHECK();
   if (blocks_freed) {
     hipLaunchKernelGGL(publish_freed_kernel, dim3(1), dim3(1024), 0, s, W.header, evict_rows, D.G, blocks_freed);

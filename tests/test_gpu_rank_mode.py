@@ -20,6 +20,10 @@ CASES = [
     ("budget_zero_and_huge", dict(b=16), dict(pooled=False, protect=1, ties=False, frac=None)),
     ("f32_d64", dict(b=16, kv_dtype="f32", d=64), dict(pooled=False, protect=1, ties=False, frac=0.3)),
     ("fp8_d128", dict(b=16, kv_dtype="fp8"), dict(pooled=False, protect=1, ties=False, frac=0.4)),
+    # more than 1024 head instances: the kernels run in their 256-thread form (below that, with few
+    # and possibly long heads, a workgroup has 1024 threads)
+    ("many_heads", dict(S=24, Lyr=7, Hk=8, L=150, b=16), dict(pooled=False, protect=1, ties=False, frac=0.4)),
+    ("many_heads_ties_b4", dict(S=24, Lyr=7, Hk=8, L=60, b=4), dict(pooled=True, protect=0, ties=True, frac=0.5)),
 ]
 
 
