@@ -291,6 +291,10 @@ __global__ void __launch_bounds__(256) compact_scan_kernel(Dims D, const uint8_t
 // One workgroup per head instance.  A 16-lane group moves one KV: its key row,
 // value row, metric and logical index.  Sources lie in [T, C), destinations in
 // [0, T), so moves of one head never overlap; heads own disjoint blocks.
+// STAGED: the head's prefix counts of flags and its block ids are copied into LDS first (one
+// round of loads), so that a mover's walk - its block's flag, the flags before it, a binary
+// search for its hole - no longer is a chain of a dozen dependent global loads.
+template <bool STAGED>
 __global__ void __launch_bounds__(256) compact_move_kernel(Dims D, char* __restrict__ kc,
                                                            char* __restrict__ vc,
                                                            float* __restrict__ metric,
@@ -298,7 +302,6 @@ __global__ void __launch_bounds__(256) compact_move_kernel(Dims D, char* __restr
                                                            int32_t* __restrict__ table,
                                                            int32_t* __restrict__ ctx,
                                                            uint8_t* __restrict__ free_map,
-                                                           const uint8_t* __restrict__ flag,
                                                            const int32_t* __restrict__ evict_count,
                                                            const int32_t* __restrict__ flag_scan,
                                                            int32_t* __restrict__ header) {
@@ -307,29 +310,43 @@ __global__ void __launch_bounds__(256) compact_move_kernel(Dims D, char* __restr
   const int e = evict_count[g];
   if (e <= 0) return;
   const int b = D.b;
+  int lb = 0;
+  while ((1 << lb) < b) ++lb;   // block sizes are powers of two
   const int C = ctx[g];
-  const int nb = (C + b - 1) / b;
-  const uint8_t* frow = flag + (size_t)g * D.maxb;
-  const int32_t* pi = flag_scan + (size_t)g * D.maxb;  // inclusive prefix of flags
+  const int nb = (C + b - 1) >> lb;
   int32_t* row = table + (size_t)g * D.maxb;
+  extern __shared__ int32_t s_stage[];   // STAGED: [nb] inclusive prefix of flags, [nb] block ids
+  const int32_t* pi = flag_scan + (size_t)g * D.maxb;  // inclusive prefix of flags: block u is flagged when it steps there
+  const int32_t* ids = row;
+  if constexpr (STAGED) {
+    for (int u = threadIdx.x; u < nb; u += 256) {
+      s_stage[u] = pi[u];
+      s_stage[D.maxb + u] = row[u];
+    }
+    __syncthreads();
+    pi = s_stage;
+    ids = s_stage + D.maxb;
+  }
+  const int last_flag = pi[nb - 1] - (nb > 1 ? pi[nb - 2] : 0);
   // evicted real KVs: flagged blocks are full except possibly the last one
-  const int n_ev = e * b - (frow[nb - 1] ? nb * b - C : 0);
+  const int n_ev = e * b - (last_flag ? nb * b - C : 0);
   const int T = C - n_ev;
   const size_t row_bytes = (size_t)D.d * kv_esz(D.dtype);
   const int pieces = (int)(row_bytes / 16);
   const int grp = threadIdx.x >> 4, gl = threadIdx.x & 15;
   for (int j = T + grp; j < C; j += 16) {
-    const int uj = j / b;
-    if (frow[uj]) continue;  // evicted, nothing to keep
+    const int uj = j >> lb;
+    const int before = uj ? pi[uj - 1] : 0;
+    if (pi[uj] != before) continue;  // its block is flagged: evicted, nothing to keep
     // evicted real slots in [0, j+1): whole flagged blocks before block uj (uj itself is kept)
-    const int ev_below = (uj ? pi[uj - 1] : 0) * b;
+    const int ev_below = before << lb;
     const int k = (C - 1 - j) - (n_ev - ev_below);  // kept slots above j = rank among movers
     // k-th hole: offset k % b of the (k / b)-th flagged block
-    const int want = k / b + 1;
+    const int want = (k >> lb) + 1;
     int lo = 0, hi = nb - 1;  // smallest u with pi[u] >= want
     while (lo < hi) { int mid = (lo + hi) >> 1; if (pi[mid] >= want) hi = mid; else lo = mid + 1; }
-    const size_t src = (size_t)row[uj] * b + (j - uj * b);
-    const size_t dst = (size_t)row[lo] * b + (k % b);
+    const size_t src = ((size_t)ids[uj] << lb) + (j & (b - 1));
+    const size_t dst = ((size_t)ids[lo] << lb) + (k & (b - 1));
     for (int c = gl; c < pieces; c += 16) {
       ((uint4*)(kc + dst * row_bytes))[c] = ((const uint4*)(kc + src * row_bytes))[c];
       ((uint4*)(vc + dst * row_bytes))[c] = ((const uint4*)(vc + src * row_bytes))[c];
@@ -340,9 +357,9 @@ __global__ void __launch_bounds__(256) compact_move_kernel(Dims D, char* __restr
     }
   }
   __syncthreads();  // all moves of this head read the table before it shrinks
-  const int nb2 = (T + b - 1) / b;
+  const int nb2 = (T + b - 1) >> lb;
   for (int u = nb2 + threadIdx.x; u < nb; u += 256) {
-    free_map[row[u]] = 1;
+    free_map[ids[u]] = 1;
     row[u] = -1;
   }
   if (threadIdx.x == 0) ctx[g] = T;   // nb - nb2 = e blocks went back
@@ -431,9 +448,15 @@ int kvc_compact(const kvc_config* cfg, const kvc_state* st, const uint8_t* evict
   KVC_LAUNCH_CHECK();
   hipLaunchKernelGGL(resolve_kernel, dim3(1), dim3(64), 0, s, W.header, 0);
   KVC_LAUNCH_CHECK();
-  hipLaunchKernelGGL(compact_move_kernel, dim3(D.G), dim3(256), 0, s, D, (char*)st->k_cache,
-                     (char*)st->v_cache, st->metric, st->pos, st->block_table, st->ctx_len, st->free_map,
-                     evict_flag, evict_count, W.flag_scan, W.header);
+  const size_t stage_bytes = (size_t)D.maxb * 8;   // prefix counts and block ids of one head
+  if (stage_bytes <= 64 * 1024)
+    hipLaunchKernelGGL(compact_move_kernel<true>, dim3(D.G), dim3(256), stage_bytes, s, D, (char*)st->k_cache,
+                       (char*)st->v_cache, st->metric, st->pos, st->block_table, st->ctx_len, st->free_map,
+                       evict_count, W.flag_scan, W.header);
+  else
+    hipLaunchKernelGGL(compact_move_kernel<false>, dim3(D.G), dim3(256), 0, s, D, (char*)st->k_cache,
+                       (char*)st->v_cache, st->metric, st->pos, st->block_table, st->ctx_len, st->free_map,
+                       evict_count, W.flag_scan, W.header);
   KVC_LAUNCH_CHECK();
   if (blocks_freed) {
     hipLaunchKernelGGL(publish_freed_kernel, dim3(1), dim3(1024), 0, s, W.header, evict_count, D.G, blocks_freed);
