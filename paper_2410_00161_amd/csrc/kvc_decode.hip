@@ -171,6 +171,12 @@ __host__ __device__ constexpr bool decode_uses_mfma(int esz, int R, int HD, int 
   return esz <= 2 && R == 8 && HD == 128 && b % 16 == 0;
 }
 
+// P V alone goes to the matrix cores for 8-bit rows under four query heads: there the plain ALUs
+// are the bound, and the FMAs of P V are the largest part of their work.
+__host__ __device__ constexpr bool decode_pv_mfma(int esz, int R, int HD, int b) {
+  return decode_uses_mfma(esz, R, HD, b) || (esz == 1 && R == 4 && HD == 128 && b % 16 == 0);
+}
+
 // Register buffers of K and V groups a wavefront rotates through (one less is in flight behind
 // the group being worked on): three for rows of at most 16 bits when four wavefronts share a
 // long chunk (up to four query heads, or the matrix-core shapes), else two.
@@ -183,8 +189,7 @@ __host__ __device__ inline size_t decode_lds_bytes(int T, int R, int HD, int b, 
                                                    bool mfma = false) {
   // per-wavefront un-normalised output; on the matrix-core path the same bytes serve, while
   // the main loop runs, as the wavefront's operand tile (16 tokens of d 16-bit elements)
-  const size_t per_wave_out = mfma ? ((size_t)R * HD * 4 > (size_t)16 * HD * 2 ? (size_t)R * HD * 4 : (size_t)16 * HD * 2)
-                                   : (size_t)R * HD * 4;
+  const size_t per_wave_out = mfma ? (size_t)16 * HD * 2 : (size_t)R * HD * 4;
   return (size_t)T * R * 2                       // exp of every logit against its group's running max, 16-bit
          + (size_t)(T / 16) * R * 4              // that running max, per 16-token group and head
          + (size_t)waves * per_wave_out
@@ -231,6 +236,8 @@ __global__ void __launch_bounds__(NW * 64) decode_chunk_kernel(DecodeArgs A) {
   // Head h sits in operand row 4 (h % 4) + h / 4, which leaves lane 16 a + t with the logits of
   // token t against heads a and a + 4.
   constexpr bool MF = B16 && decode_uses_mfma(ESZ, R, HD, 16);
+  constexpr bool PVM = B16 && decode_pv_mfma(ESZ, R, HD, 16);   // P V on the matrix cores (with or without Q K^T)
+  constexpr int RW = PVM ? 8 : R;      // output rows a wavefront's LDS region has room for
   constexpr int NVH = (R + 3) / 4;     // MF: logits per lane
   constexpr int OWN = MF ? NVH : PER;
 
@@ -255,8 +262,8 @@ __global__ void __launch_bounds__(NW * 64) decode_chunk_kernel(DecodeArgs A) {
   // [waves][R][HD]; on the matrix-core path a wavefront's 4 KiB of it are its operand tile until
   // its main loop ends (R * HD * 4 = 16 * HD * 2 there, so no wavefront touches another's tile)
   float* s_acc = (float*)smem_raw;
-  static_assert(!MF || (size_t)R * HD * 4 == (size_t)16 * HD * 2, "output rows alias the operand tile wavefront by wavefront");
-  float* s_e = s_acc + NW * R * HD;          // [waves][16][R]
+  static_assert(!PVM || (size_t)RW * HD * 4 == (size_t)16 * HD * 2, "output rows alias the operand tile wavefront by wavefront");
+  float* s_e = s_acc + NW * RW * HD;         // [waves][16][R]
   float* s_red = s_e + NW * 16 * R;          // [2][waves][R]
   float* s_gm = s_red + 2 * NW * R;          // [T / 16][R]
   uint16_t* s_q = (uint16_t*)(s_gm + (T / 16) * R);    // [T][R]
@@ -319,10 +326,10 @@ __global__ void __launch_bounds__(NW * 64) decode_chunk_kernel(DecodeArgs A) {
   // hi = its upper 16 bits in row h, lo = (p - hi) in row h + 8, so that the product carries
   // 16 bits of p (one half alone misses the output tolerance when one key dominates).
   constexpr int NDT = HD / 16;
-  static_assert(!MF || R == 8, "the two halves of eight heads fill the 16 operand rows");
-  f32x4_t pacc[MF ? NDT : 1];
+  static_assert(!PVM || R == 8 || R == 4, "operand rows: heads 0..7 as upper halves, then as remainders");
+  f32x4_t pacc[PVM ? NDT : 1];
 #pragma unroll
-  for (int i = 0; i < (MF ? NDT : 1); ++i) pacc[i] = f32x4_t{0.0f, 0.0f, 0.0f, 0.0f};
+  for (int i = 0; i < (PVM ? NDT : 1); ++i) pacc[i] = f32x4_t{0.0f, 0.0f, 0.0f, 0.0f};
   float m_run[R];            // running max per query head, the same in every lane
   float m_own[OWN], l_own[OWN];  // this lane's head(s): running max and partial sum
 #pragma unroll
@@ -416,7 +423,7 @@ __global__ void __launch_bounds__(NW * 64) decode_chunk_kernel(DecodeArgs A) {
           const float e = __builtin_amdgcn_exp2f(part[i] - gm[i]);
           l_own[i] = l_own[i] * __builtin_amdgcn_exp2f(m_own[i] - gm[i]) + e;
           m_own[i] = gm[i];
-          my_e[tl * R + hh] = e;
+          my_e[PVM ? hh * 16 + tl : tl * R + hh] = e;   // [head][token] for the matrix-core P V
           s_q[(grp * 16 + tl) * R + hh] = (uint16_t)q16(e);
           if (gm_writer) s_gm[grp * R + hh] = gm[i];
         }
@@ -428,14 +435,14 @@ __global__ void __launch_bounds__(NW * 64) decode_chunk_kernel(DecodeArgs A) {
         }
       }
       const bool tail = B16 && grp * 16 + 16 > n_tok;
-      if constexpr (MF) {
+      if constexpr (PVM) {
         if (moved) {
           // this lane's product rows 4 (lane / 16) + v belong to heads 4 ((lane / 16) % 2) + v
           const bool upper = (lane & 16) != 0;
 #pragma unroll
           for (int v = 0; v < 4; ++v) {
             const float a_lo = __builtin_amdgcn_exp2f(m_run[v] - m_new[v]);
-            const float a_hi = __builtin_amdgcn_exp2f(m_run[4 + v] - m_new[4 + v]);
+            const float a_hi = R > 4 ? __builtin_amdgcn_exp2f(m_run[(4 + v) % R] - m_new[(4 + v) % R]) : 1.0f;
             const float a = upper ? a_hi : a_lo;
 #pragma unroll
             for (int dt = 0; dt < NDT; ++dt) pacc[dt][v] *= a;
@@ -443,7 +450,7 @@ __global__ void __launch_bounds__(NW * 64) decode_chunk_kernel(DecodeArgs A) {
 #pragma unroll
           for (int hh = 0; hh < R; ++hh) m_run[hh] = m_new[hh];
         }
-        // The K tile has been consumed: its 4 KiB now take the V tile, row-major [token][d] in
+        // The K tile (if Q K^T went through it) has been consumed: its 4 KiB take the V tile, row-major [token][d] in
         // bf16, the 16-byte cell c of token t at position c ^ 2 (t % 8) of the row, which keeps
         // the transposing reads below (8 tokens x 32 bytes per half wavefront) off each other's banks.
         uint4* vt = s_kt + w * 256;
@@ -455,7 +462,8 @@ __global__ void __launch_bounds__(NW * 64) decode_chunk_kernel(DecodeArgs A) {
         }
         // A operand: lane = (row lane % 16, tokens 4 (lane / 16) .. + 3)
         const int rho = lane & 15, kap = lane >> 4;
-        const float4 pe = *(const float4*)(my_e + (rho & 7) * 16 + 4 * kap);
+        float4 pe = *(const float4*)(my_e + (rho & (R - 1)) * 16 + 4 * kap);
+        if (R < 8 && (rho & 7) >= R) pe = make_float4(0.0f, 0.0f, 0.0f, 0.0f);   // operand rows without a head
         const bool hi_row = rho < 8;
         auto half_of = [&](float p) {   // the float whose upper 16 bits are this row's half of p
           const uint32_t bits = __float_as_uint(p);
@@ -570,14 +578,14 @@ __global__ void __launch_bounds__(NW * 64) decode_chunk_kernel(DecodeArgs A) {
       }
     }
   }
-  if constexpr (MF) {
+  if constexpr (PVM) {
     // rows h and h + 8 of the product (lanes 32 apart) are the two halves of head h
 #pragma unroll
     for (int dt = 0; dt < NDT; ++dt)
 #pragma unroll
       for (int v = 0; v < 4; ++v) {
         const float a = pacc[dt][v] + __shfl_xor(pacc[dt][v], 32);
-        if (lane < 32) s_acc[(w * R + 4 * (lane >> 4) + v) * HD + 16 * dt + (lane & 15)] = a;
+        if (lane < (R > 4 ? 32 : 16)) s_acc[(w * RW + 4 * (lane >> 4) + v) * HD + 16 * dt + (lane & 15)] = a;
       }
   } else {
 #pragma unroll
@@ -590,7 +598,7 @@ __global__ void __launch_bounds__(NW * 64) decode_chunk_kernel(DecodeArgs A) {
 #pragma unroll
       for (int hh = 0; hh < R; ++hh)
 #pragma unroll
-        for (int k = 0; k < EPL; ++k) s_acc[(w * R + hh) * HD + seg * EPL + k] = acc[hh][k];
+        for (int k = 0; k < EPL; ++k) s_acc[(w * RW + hh) * HD + seg * EPL + k] = acc[hh][k];
     }
   }
   __syncthreads();
@@ -618,7 +626,7 @@ __global__ void __launch_bounds__(NW * 64) decode_chunk_kernel(DecodeArgs A) {
     for (int k = tid; k < HD; k += NT) {
       float s = 0.0f;
 #pragma unroll
-      for (int ww = 0; ww < NW; ++ww) s += s_acc[(ww * R + hh) * HD + k] * wsc[ww][hh];
+      for (int ww = 0; ww < NW; ++ww) s += s_acc[(ww * RW + hh) * HD + k] * wsc[ww][hh];
       if (single) __builtin_nontemporal_store(s / cl[hh], &A.out[((size_t)g * R + hh) * HD + k]);
       else __builtin_nontemporal_store(s, &A.part_acc[(pslot * R + hh) * HD + k]);
     }
@@ -849,7 +857,7 @@ static int launch_tiled(const DecodeArgs& A, int grid, size_t lds, int grid_shor
   if (pp) { KVC_HIP(hipEventRecord(pp->a1, s)); KVC_HIP(hipEventRecord(pp->s0, s)); }
   if (A.short_class < 16) {
     hipLaunchKernelGGL(kern_short, dim3(grid_short), dim3(64),
-                       decode_lds_bytes(A.Ts, R, HD, A.D.b, 1, decode_uses_mfma(ESZ, R, HD, A.D.b)), s, A);
+                       decode_lds_bytes(A.Ts, R, HD, A.D.b, 1, decode_pv_mfma(ESZ, R, HD, A.D.b)), s, A);
     KVC_LAUNCH_CHECK();
   }
   if (pp) { KVC_HIP(hipEventRecord(pp->s1, s)); KVC_HIP(hipEventRecord(pp->b0, s)); }
@@ -892,7 +900,7 @@ static bool choose_chunk(const Dims& D, int gsel, int* T_out, size_t* lds_out, b
     while (T > 256 && (long long)gsel * (((long long)D.maxb * D.b + T - 1) / T) < want_items)
       T = ((T / 2) + 63) & ~63;
   }
-  const bool mf = decode_uses_mfma(esz, D.r, D.d, D.b);
+  const bool mf = decode_pv_mfma(esz, D.r, D.d, D.b);   // a per-wavefront operand tile in LDS
   while (T > kMinChunk && decode_lds_bytes(T, D.r, D.d, D.b, kDecodeWaves, mf) > kLdsLimit) T -= 64;
   const size_t lds = decode_lds_bytes(T, D.r, D.d, D.b, kDecodeWaves, mf);
   if (lds > kLdsLimit || T % 64 != 0) return false;
