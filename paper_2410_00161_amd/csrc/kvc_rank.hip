@@ -57,6 +57,30 @@ __global__ void __launch_bounds__(256) rank_init_kernel(Dims D, const int32_t* _
   if (i < D.G) evict_rows[i] = 0;
 }
 
+// A head's metrics as ordered bit patterns, four strided elements per thread at a time: the four
+// block ids are requested together, then the four metrics, so that a pass over a head waits for
+// two rounds of loads per four elements instead of two per element.  visit(j, bits) sees every
+// logical slot j < C once.
+template <int NTH, class Visit>
+__device__ __forceinline__ void for_each_metric(const float* __restrict__ metric, const int32_t* __restrict__ row,
+                                                int C, int lb, int bmask, Visit visit) {
+  for (int j0 = threadIdx.x; j0 < C; j0 += 4 * NTH) {
+    int id[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) id[i] = row[min(j0 + i * NTH, C - 1) >> lb];
+    float m[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int j = min(j0 + i * NTH, C - 1);
+      m[i] = metric[((size_t)id[i] << lb) + (j & bmask)];
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      if (j0 + i * NTH < C) visit(j0 + i * NTH, metric_bits(m[i]));
+  }
+}
+
+
 // One workgroup (NTH threads: 256, or 1024 when there are few, long heads) per heads_per_wg
 // consecutive head instances, one after the other.  Counts a
 // head's entries below the prefix found so far and histograms the next digit of those that
@@ -106,13 +130,12 @@ __global__ void __launch_bounds__(NTH) rank_hist_kernel(Dims D, int pass, int pr
     const int32_t* row = table + (size_t)g * D.maxb;
     int below = 0;
     bool bad = false;
-    for (int j = tid; j < C; j += NTH) {
-      const uint32_t k = metric_bits(metric[((size_t)row[j >> lb] << lb) + (j & (D.b - 1))]);
+    for_each_metric<NTH>(metric, row, C, lb, D.b - 1, [&](int, uint32_t k) {
       if (pass == 0) bad |= k >= 0x7f800000u;
       const uint32_t top = pass == 0 ? 0u : (k >> (shift + 8));
       if (top < prefix) ++below;
       else if (top == prefix) atomicAdd(&hist[(k >> shift) & 255], 1);
-    }
+    });
     const int z = nb * D.b - C;  // the empty slots count as zeros, ahead of every real metric
     if (tid == 0 && z) {
       if (prefix == 0) atomicAdd(&hist[0], z); else below += z;
@@ -185,11 +208,12 @@ __global__ void __launch_bounds__(256) rank_tie_kernel(Dims D, int protect, cons
   const uint32_t thr = (uint32_t)seg_state[sg * 8 + RS_PREFIX];
   const int32_t* row = table + (size_t)g * D.maxb;
   int lt = 0, le = 0;
-  for (int j = tid; j < C; j += 256) {
-    const uint32_t k = metric_bits(metric[(size_t)row[j / D.b] * D.b + (j % D.b)]);
+  int lb = 0;
+  while ((1 << lb) < D.b) ++lb;   // block sizes are powers of two
+  for_each_metric<256>(metric, row, C, lb, D.b - 1, [&](int, uint32_t k) {
     lt += k < thr;
     le += k <= thr;
-  }
+  });
   if (tid == 0) {
     const int z = nb * D.b - C;
     le += z;
@@ -284,10 +308,9 @@ __global__ void __launch_bounds__(NTH) rank_compact_kernel(Dims D, char* __restr
     __syncthreads();
     const int shift = 24 - 8 * pass;
     const uint32_t prefix = (uint32_t)prefix_s;
-    for (int j = tid; j < C; j += NTH) {
-      const uint32_t k = metric_bits(metric[phys(j)]);
+    for_each_metric<NTH>(metric, row, C, lb, b - 1, [&](int, uint32_t k) {
       if (pass == 0 || (k >> (shift + 8)) == prefix) atomicAdd(&hist[(k >> shift) & 255], 1);
-    }
+    });
     __syncthreads();
     const int c = tid < 256 ? hist[tid] : 0;
     const int ex = block_exclusive_scan<NTH>(c, smem, nullptr);
