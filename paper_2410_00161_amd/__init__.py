@@ -6,4 +6,4 @@ this package loads nothing; the library is loaded on first use and a missing
 library is an error, never a fallback.
 """
 
-__all__ = ["binding", "workloads", "build"]
+__all__ = ["binding", "session", "workloads", "build"]

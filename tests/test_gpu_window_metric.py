@@ -18,6 +18,9 @@ CASES = [
     ("w32_r8", dict(r=8, L=1100, rho=2.0), 32, 5, B.KVC_L2),
     ("w5_r2_L1_nopool", dict(r=2, L=1200, rho=2.0), 5, 1, B.KVC_L1),
     ("w16_r1", dict(r=1, L=1200, rho=2.0), 16, 3, B.KVC_L2),
+    # a pool wider than the halo the pooling kernel stages; heads longer than one pooling tile
+    ("w8_r4_wide_pool", dict(r=4, L=2600, rho=1.5), 8, 201, B.KVC_L2),
+    ("w4_r2_pool_129", dict(r=2, L=4500, rho=1.2), 4, 129, B.KVC_L2),
 ]
 
 
