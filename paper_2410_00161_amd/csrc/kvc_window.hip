@@ -351,12 +351,12 @@ static int launch_window(const WindowArgs& W, int grid, hipStream_t s) {
   const size_t lds = (size_t)NT * 4 * 64 * 16 + (size_t)kWinWaves * NT * 64 * 8 + tab;
   const size_t lds2 = (size_t)NT * 4 * 64 * 16 + (size_t)NT * 16 * 4 + tab;
   static_assert((size_t)kWinWaves * NT * 16 * 2 * 4 <= (size_t)NT * 4 * 64 * 16, "pairs fit where Q was");
-  static bool told = false;
-  if ((lds > 64 * 1024 || lds2 > 64 * 1024) && !told) {  // above the default cap a kernel must be told once
+  static size_t allowed = 0;   // above the default cap a kernel must be told how much it may take
+  if (lds > 64 * 1024 && lds > allowed) {   // (lds >= lds2; the block-id array grows as blocks shrink)
     KVC_HIP(hipFuncSetAttribute((const void*)window_stats_kernel<NT>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    KVC_HIP(hipFuncSetAttribute((const void*)window_sum_kernel<NT, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds2));
-    KVC_HIP(hipFuncSetAttribute((const void*)window_sum_kernel<NT, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds2));
-    told = true;
+    KVC_HIP(hipFuncSetAttribute((const void*)window_sum_kernel<NT, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    KVC_HIP(hipFuncSetAttribute((const void*)window_sum_kernel<NT, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    allowed = lds;
   }
   hipLaunchKernelGGL(window_stats_kernel<NT>, dim3(grid), dim3(kWinThreads), lds, s, W);
   KVC_LAUNCH_CHECK();
