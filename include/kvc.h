@@ -200,7 +200,9 @@ int kvc_paged_decode(const kvc_config* cfg, const kvc_state* st, const void* q, 
  * over the filled slots of logical block u (n = block_table[g][u]), added left
  * to right in f32.  KVC_KEY_MAX: the largest of those metrics.  A partial last
  * block contributes only its real slots.  Cells with u >= ceil(ctx_len/b) are
- * set to 0.  KVC_ERR_ARG for any other key_mode.  Asynchronous.                 */
+ * not written (tables are sized for the longest prompt, compressed heads use a
+ * fraction of their row, and nothing reads the keys of blocks a head does not
+ * hold).  KVC_ERR_ARG for any other key_mode.  Asynchronous.                    */
 int kvc_metric_reduce(const kvc_config* cfg, const kvc_state* st, float* block_key, int key_mode,
                       void* ws, void* stream);
 

@@ -30,9 +30,9 @@ __global__ void __launch_bounds__(256) block_key_kernel(Dims D, int key_mode, co
   const int nb = (C + D.b - 1) / D.b;
   const int32_t* row = table + (size_t)g * D.maxb;
   float* krow = key + (size_t)g * D.maxb;
-  for (int u = lane; u < D.maxb; u += 64) {
+  for (int u = lane; u < nb; u += 64) {   // cells of blocks the head does not hold are left alone
     float acc = 0.0f;
-    if (u < nb) {
+    {
       const float* m = metric + (size_t)row[u] * D.b;
       const int fill = min(D.b, C - u * D.b);
       if (fill == D.b && (D.b & 3) == 0) {   // a full block: 16-byte loads, the same order of additions

@@ -28,3 +28,14 @@ def check_allocator_invariants(st: O.State):
         n = O.num_blocks_held(st, g)
         assert (tab[g, n:] == -1).all(), "row not prefix-filled"
         assert n * st.b >= lens[g], "context longer than the blocks held"
+
+
+def assert_keys_equal(key, want_key, st: O.State):
+    """Block keys bit for bit over the blocks every head holds; the library leaves the cells of
+    blocks a head does not hold as they were."""
+    key = np.asarray(key.detach().cpu().numpy() if hasattr(key, "detach") else key)
+    nb = -(-st.lens() // st.b)
+    held = np.arange(st.max_blocks)[None, :] < nb[:, None]
+    np.testing.assert_array_equal(key.reshape(st.G, -1).view(np.uint32)[held],
+                                  np.asarray(want_key).reshape(st.G, -1).view(np.uint32)[held])
+    return held

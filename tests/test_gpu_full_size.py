@@ -9,7 +9,7 @@ import torch
 from oracle import kvc_oracle as O
 from paper_2410_00161_amd import binding as B
 from paper_2410_00161_amd import workloads as W
-from helpers import oracle_state
+from helpers import oracle_state, assert_keys_equal
 
 pytestmark = pytest.mark.gpu
 TOL = 2e-3
@@ -114,8 +114,9 @@ def test_llama8b_shape_sampled_parity_and_invariants(num_seqs, prompt, rho, forc
         np.testing.assert_array_equal(flag[lo:hi].cpu().numpy(), fw)
         np.testing.assert_array_equal(count[lo:hi].cpu().numpy(), cw)
     # block keys of the sampled heads, bit for bit
-    kw, _ = O.block_keys(oracle_state(after))
-    np.testing.assert_array_equal(key_h[heads].view(np.uint32), kw.view(np.uint32))
+    st_after = oracle_state(after)
+    kw, _ = O.block_keys(st_after)
+    assert_keys_equal(key_h[heads], kw, st_after)
     # compaction parity on the sampled heads, given the device's flags
     st2 = oracle_state(after)
     f_small = flag[torch.tensor(heads, device=dev)].cpu().numpy()

@@ -8,7 +8,7 @@ import torch
 from oracle import kvc_oracle as O
 from paper_2410_00161_amd import binding as B
 from paper_2410_00161_amd import workloads as W
-from helpers import oracle_state, check_allocator_invariants
+from helpers import oracle_state, check_allocator_invariants, assert_keys_equal
 from test_gpu_parity import session, say, assert_state_equal, TOL
 
 pytestmark = pytest.mark.gpu
@@ -23,7 +23,7 @@ def evict_round(sess, st, frac, mode):
     if mode == "block":
         key = sess.metric_reduce()
         want_key, _ = O.block_keys(st)
-        np.testing.assert_array_equal(key.cpu().numpy().view(np.uint32), want_key.view(np.uint32))
+        assert_keys_equal(key, want_key, st)
         flag_w, count_w, sel_w = O.evict_select(st, want_key, budget.numpy())
         flag, count, sel = sess.evict_select(budget)
         np.testing.assert_array_equal(flag.cpu().numpy(), flag_w)
