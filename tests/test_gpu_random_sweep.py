@@ -1,0 +1,97 @@
+"""Seeded random sweep over valid shapes: append, decode with metric accumulation, a
+physical-block round, a rank-block round, and the window metric, each step against the oracle.
+Shapes, lengths, chunk settings and placements are drawn at random; every draw is printed first."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import kvc_oracle as O
+from paper_2410_00161_amd import binding as B
+from paper_2410_00161_amd import workloads as W
+from helpers import oracle_state, check_allocator_invariants
+from test_gpu_parity import session, say, assert_state_equal, TOL
+from test_gpu_scenarios import evict_round
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("seed0", [11, 12, 13, 14])
+def test_decode_and_rounds_on_random_shapes(seed0):
+    rng = np.random.default_rng(seed0)
+    for case in range(30):
+        r = int(rng.choice([1, 2, 4, 8])); d = int(rng.choice([64, 128]))
+        dt = str(rng.choice(["bf16", "f32", "fp8"])); b = int(rng.choice([1, 2, 4, 8, 16, 32, 64]))
+        S, Lyr, Hk = int(rng.integers(1, 5)), int(rng.integers(1, 4)), int(rng.integers(1, 4))
+        L = int(rng.integers(max(3 * b, 40), 2600 if b >= 8 else 500))
+        rho = float(rng.uniform(1.0, 4.0))
+        chunk = int(rng.choice([0, 0, 64, 128, 192, 1088]))
+        placement = str(rng.choice(["fresh", "fragmented"]))
+        mode = int(rng.choice([B.KVC_L2, B.KVC_L1]))
+        say("random shape", dict(seed0=seed0, case=case, r=r, d=d, dt=dt, b=b, S=S, Lyr=Lyr, Hk=Hk, L=L,
+                                 rho=round(rho, 2), chunk=chunk, placement=placement, mode=mode))
+        shape, ctx, seed = W.small_mixed(1000 + seed0 * 1000 + case, S=S, Lyr=Lyr, Hk=Hk, r=r, d=d, b=b, L=L,
+                                         rho=rho, kv_dtype=dt, extra_blocks=3)
+        if rng.random() < 0.3:
+            ctx[int(rng.integers(0, len(ctx)))] = 0
+        if rng.random() < 0.3:
+            ctx[int(rng.integers(0, len(ctx)))] = 1
+        cache = W.make_cache(shape, ctx, seed, placement=placement, init_metric="prefill")
+        st = oracle_state(cache)
+        sess = session(cache, mode)
+        B.kvc_set_decode_chunk(chunk)
+        try:
+            for step, ev in enumerate(("block", "rank", None)):
+                k, v = W.make_new_kv(shape, seed, step)
+                q = W.make_query(shape, seed, step)
+                O.append(st, k.double().numpy(), v.double().numpy())
+                want = O.paged_decode(st, q.double().numpy(), metric_mode="L2" if mode == B.KVC_L2 else "L1")
+                sess.append(k.to(sess.device), v.to(sess.device))
+                out = sess.paged_decode(q.to(sess.device))
+                torch.cuda.synchronize()
+                np.testing.assert_allclose(out.cpu().numpy(), want, rtol=0, atol=TOL)
+                live = st.free_map == 0
+                np.testing.assert_allclose(sess.cache.metric.cpu().numpy()[live], st.metric[live], rtol=0, atol=TOL)
+                if ev:
+                    evict_round(sess, st, float(rng.uniform(0.05, 0.6)), ev)
+                    assert_state_equal(sess, st)
+                    check_allocator_invariants(st)
+        finally:
+            B.kvc_set_decode_chunk(0)
+
+
+@pytest.mark.parametrize("seed0", [21, 22])
+def test_window_metric_on_random_shapes(seed0):
+    rng = np.random.default_rng(seed0)
+    for case in range(30):
+        r = int(rng.choice([1, 2, 4, 8]))
+        w = int(rng.integers(1, min(32, 256 // r) + 1))
+        b = int(rng.choice([16, 32, 64]))
+        pool = int(rng.choice([1, 3, 5, 7, 9, 131]))
+        S, Lyr, Hk = int(rng.integers(1, 4)), int(rng.integers(1, 3)), int(rng.integers(1, 3))
+        L = int(rng.integers(64, 4200))
+        rho = float(rng.uniform(1.0, 3.0))
+        mode = int(rng.choice([B.KVC_L2, B.KVC_L1]))
+        acc = bool(rng.random() < 0.3)
+        say("random window", dict(seed0=seed0, case=case, r=r, w=w, b=b, pool=pool, S=S, Lyr=Lyr, Hk=Hk, L=L,
+                                  rho=round(rho, 2), mode=mode, acc=acc))
+        shape, ctx, seed = W.small_mixed(5000 + seed0 * 1000 + case, S=S, Lyr=Lyr, Hk=Hk, r=r, d=128, b=b, L=L,
+                                         rho=rho, kv_dtype="bf16")
+        if rng.random() < 0.3:
+            ctx[int(rng.integers(0, len(ctx)))] = 0
+        if rng.random() < 0.3:
+            ctx[int(rng.integers(0, len(ctx)))] = int(rng.integers(1, w + 1))
+        cache = W.make_cache(shape, ctx, seed, placement=str(rng.choice(["fresh", "fragmented"])),
+                             init_metric="prefill")
+        st = oracle_state(cache)
+        g = torch.Generator().manual_seed(seed + 3)
+        qw = torch.randn((S, Lyr, Hk * r, w, 128), generator=g).to(torch.bfloat16)
+        O.window_metric(st, qw.double().numpy(), w, pool, "L2" if mode == B.KVC_L2 else "L1", accumulate=acc)
+        sess = session(cache, mode)
+        sess.window_metric(qw.to(sess.device), w, pool, accumulate=acc)
+        torch.cuda.synchronize()
+        m = sess.cache.metric.cpu().numpy().astype(np.float64)
+        real = np.zeros(m.shape, dtype=bool)
+        for gi in range(st.G):
+            n, o = O.slots_of(st, gi)
+            real[n, o] = True
+        np.testing.assert_allclose(m[real], st.metric[real], rtol=0, atol=TOL)
