@@ -95,3 +95,81 @@ def test_window_metric_on_random_shapes(seed0):
             n, o = O.slots_of(st, gi)
             real[n, o] = True
         np.testing.assert_allclose(m[real], st.metric[real], rtol=0, atol=TOL)
+
+
+@pytest.mark.parametrize("seed0", [31, 32])
+def test_allocator_operations_in_random_order(seed0):
+    """Random sequences of alloc / free / append / preempt / prefill / count, some of them requests
+    that must be refused: both sides accept and refuse alike (same code), and the state matches
+    after every operation."""
+    rng = np.random.default_rng(seed0)
+    refused = 0
+    for case in range(60):
+        b = int(rng.choice([1, 4, 16, 64]))
+        S, Lyr, Hk = int(rng.integers(1, 6)), int(rng.integers(1, 4)), int(rng.integers(1, 4))
+        L = int(rng.integers(4 * b, 40 * b))
+        slack = float(rng.uniform(1.05, 2.5))
+        say("random allocator sequence", dict(seed0=seed0, case=case, b=b, S=S, Lyr=Lyr, Hk=Hk, L=L, slack=round(slack, 2)))
+        shape, ctx, seed = W.small_mixed(3000 + seed0 * 1000 + case, S=S, Lyr=Lyr, Hk=Hk, r=2, d=64, b=b, L=L,
+                                         rho=2.0, slack=slack, extra_blocks=int(rng.integers(0, 4)))
+        cache = W.make_cache(shape, ctx, seed, placement=str(rng.choice(["fresh", "fragmented"])))
+        st = oracle_state(cache)
+        sess = session(cache)
+        dev, G = sess.device, shape.G
+
+        def both(on_oracle, on_gpu):
+            eo = eg = ro = rg = None
+            try:
+                ro = on_oracle()
+            except O.OracleError as e:
+                eo = e
+            try:
+                rg = on_gpu()
+            except B.KvcError as e:
+                eg = e
+            assert (eo is None) == (eg is None), (eo, eg)
+            if eo is not None:
+                assert eo.code == eg.code
+            return ro, rg, eo is not None
+
+        for op_i in range(10):
+            op = str(rng.choice(["alloc", "free", "append", "preempt", "prefill", "count"]))
+            bad = False
+            if op == "alloc":
+                n = torch.from_numpy((rng.integers(0, 3, size=G) * (rng.random(G) < 0.5)).astype(np.int32))
+                _, _, bad = both(lambda: O.block_alloc(st, n.numpy()), lambda: sess.block_alloc(n))
+            elif op == "free":
+                held = np.array([O.num_blocks_held(st, g) for g in range(G)])
+                n = np.minimum(held, rng.integers(0, 3, size=G)) * (rng.random(G) < 0.5)
+                if rng.random() < 0.1:
+                    n[int(rng.integers(0, G))] += 1000   # more than the head holds
+                n = torch.from_numpy(n.astype(np.int32))
+                ro, rg, bad = both(lambda: O.block_free(st, n.numpy()), lambda: sess.block_free(n))
+                assert ro == rg
+            elif op == "append":
+                k, v = W.make_new_kv(shape, seed, op_i)
+                l0 = int(rng.integers(0, Lyr))
+                l1 = int(rng.integers(l0 + 1, Lyr + 1))
+                _, _, bad = both(lambda: O.append(st, k.double().numpy(), v.double().numpy(), None, l0, l1),
+                                 lambda: sess.append(k.to(dev), v.to(dev), None, l0, l1))
+            elif op == "preempt":
+                m = torch.from_numpy((rng.random(S) < 0.3).astype(np.uint8))
+                ro, rg, bad = both(lambda: O.preempt(st, m.numpy()),
+                                   lambda: B.kvc_preempt(sess.cfg, sess.st, m.to(dev), sess.ws))
+                assert ro == rg
+            elif op == "prefill":
+                t = torch.from_numpy((rng.integers(0, L, size=S) * (rng.random(S) < 0.4)).astype(np.int32))
+                _, _, bad = both(lambda: O.prefill_alloc(st, t.numpy()),
+                                 lambda: B.kvc_prefill_alloc(sess.cfg, sess.st, t.to(dev), sess.ws))
+            else:
+                needed = torch.zeros(S, dtype=torch.int32, device=dev)
+                held_t = torch.zeros(S, dtype=torch.int32, device=dev)
+                B.kvc_count_blocks(sess.cfg, sess.st, 0, Lyr, needed, held_t, sess.ws)
+                torch.cuda.synchronize()
+                nw, hw = O.count_blocks(st, 0, Lyr)
+                np.testing.assert_array_equal(needed.cpu().numpy(), nw)
+                np.testing.assert_array_equal(held_t.cpu().numpy(), hw)
+            refused += bad
+            assert_state_equal(sess, st, kv_exact=False)
+            check_allocator_invariants(st)
+    assert refused > 0   # the sweep did exercise refusals
