@@ -210,7 +210,8 @@ int kvc_metric_reduce(const kvc_config* cfg, const kvc_state* st, float* block_k
  * sequence s evicts its budget E_s of blocks, the cheapest first).
  * A segment is a run of consecutive sequences: seg_offsets [nseg + 1] i32
  * (device) in sequence units, seg_offsets[0] = 0, last = S; NULL = one segment
- * per sequence (then nseg must equal S).  budget [nseg] i32 (device).
+ * per sequence (then nseg must equal S).  1 <= nseg <= S (segments may be
+ * empty, but the workspace holds S of them).  budget [nseg] i32 (device).
  * Candidates of head g are its logical blocks u < ceil(ctx_len/b) -
  * protect_tail_blocks (1 keeps every head's last block, matching the domain
  * 1 <= e < ceil(C_h/b); 0 lets a head lose everything).  Per segment the
