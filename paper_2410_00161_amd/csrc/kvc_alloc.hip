@@ -85,18 +85,22 @@ constexpr int kScanRun = 16;                   // elements per thread and tile i
 constexpr int kScanWide = 1024 * kScanRun;     // elements per tile
 
 // Exclusive scan of n ints over one workgroup of 1024 threads: every thread takes a run of 16
-// consecutive elements (four 16-byte loads when the array is 16-byte aligned, which workspace
-// arrays are), one workgroup scan joins the runs.  `visit(i, value, exclusive)` sees every element.
+// consecutive elements (four 16-byte loads and, for the results, four 16-byte stores when the
+// arrays are 16-byte aligned, which workspace arrays are: a thread's run is 64 bytes, so with
+// 4-byte accesses every instruction of a wavefront touched 64 different lines), one workgroup
+// scan joins the runs.  out[i] = exclusive prefix (out may be `in`); `visit(i, value,
+// exclusive)` sees every element with a non-zero value.
 template <class Visit>
-__device__ __forceinline__ int wide_exclusive_scan(const int32_t* __restrict__ in, int n, int* smem, Visit visit) {
+__device__ __forceinline__ int wide_exclusive_scan(const int32_t* in, int n, int32_t* out, int* smem, Visit visit) {
   __shared__ int carry_s;
   if (threadIdx.x == 0) carry_s = 0;
   __syncthreads();
-  const bool aligned = ((uintptr_t)in & 15) == 0;
+  const bool aligned = (((uintptr_t)in | (uintptr_t)out) & 15) == 0;
   for (int base = 0; base < n; base += kScanWide) {
     const int first = base + threadIdx.x * kScanRun;
+    const bool whole = aligned && first + kScanRun <= n;
     int v[kScanRun], sum = 0;
-    if (aligned && first + kScanRun <= n) {
+    if (whole) {
 #pragma unroll
       for (int k = 0; k < kScanRun; k += 4) {
         const int4 t = *(const int4*)(in + first + k);
@@ -110,10 +114,19 @@ __device__ __forceinline__ int wide_exclusive_scan(const int32_t* __restrict__ i
     for (int k = 0; k < kScanRun; ++k) sum += v[k];
     int tot;
     int ex = block_exclusive_scan<1024>(sum, smem, &tot) + carry_s;
+    int o[kScanRun];
 #pragma unroll
     for (int k = 0; k < kScanRun; ++k) {
-      if (first + k < n) visit(first + k, v[k], ex);
+      o[k] = ex;
+      if (v[k] && first + k < n) visit(first + k, v[k], ex);
       ex += v[k];
+    }
+    if (whole) {
+#pragma unroll
+      for (int k = 0; k < kScanRun; k += 4) *(int4*)(out + first + k) = make_int4(o[k], o[k + 1], o[k + 2], o[k + 3]);
+    } else {
+#pragma unroll
+      for (int k = 0; k < kScanRun; ++k) if (first + k < n) out[first + k] = o[k];
     }
     __syncthreads();
     if (threadIdx.x == 0) carry_s += tot;
@@ -132,13 +145,11 @@ __global__ void __launch_bounds__(1024) alloc_scan_kernel(Dims D, const int32_t*
                                                           int32_t* __restrict__ header) {
   __shared__ int smem[1024 / 64 + 1];
   const int N = D.N;
-  const int total_req = wide_exclusive_scan(req, D.G, smem, [&](int g, int v, int ex) {
-    off[g] = ex;
+  const int total_req = wide_exclusive_scan(req, D.G, off, smem, [&](int g, int v, int ex) {
     if (ex + v <= N)  // more requests than blocks exist is an error found below
       for (int i = 0; i < v; ++i) owner[ex + i] = g;
   });
-  const int total_free = wide_exclusive_scan(tile_sums, ntiles, smem,
-                                             [&](int t, int v, int ex) { tile_sums[t] = ex; });
+  const int total_free = wide_exclusive_scan(tile_sums, ntiles, tile_sums, smem, [](int, int, int) {});
   if (threadIdx.x == 0) {
     off[D.G] = total_req;
     header[HW_TOTAL_REQ] = total_req;
@@ -210,9 +221,12 @@ __global__ void __launch_bounds__(256) drop_kernel(Dims D, int32_t* __restrict__
   if ((threadIdx.x & 63) == 0 && tot) atomicAdd(&header[HW_FREED], tot);
 }
 
-// One wavefront per head instance (four per workgroup): copy the new key and value in
-// 16-byte pieces, zero the metric, set the logical index, bump the length.
-__global__ void __launch_bounds__(256) append_write_kernel(Dims D, int l0, int l1, char* __restrict__ kc,
+// A group of lanes per head instance, as many as the new key and value have 16-byte pieces
+// (rounded up to a power of two, at most a wavefront; 32 lanes for 256-byte rows, so two heads
+// per wavefront): copy the rows, zero the metric, set the logical index, bump the length.  The
+// kernel is a chain of three dependent loads per head, so heads in flight are what counts.
+__global__ void __launch_bounds__(256) append_write_kernel(Dims D, int l0, int l1, int lanes_per_head,
+                                                          char* __restrict__ kc,
                                                           char* __restrict__ vc,
                                                           float* __restrict__ metric,
                                                           int32_t* __restrict__ pos,
@@ -224,10 +238,10 @@ __global__ void __launch_bounds__(256) append_write_kernel(Dims D, int l0, int l
                                                           const int32_t* __restrict__ header) {
   if (header[HW_STATUS] != KVC_OK) return;
   const int nl = l1 - l0;
-  const int idx = blockIdx.x * 4 + (threadIdx.x >> 6);   // over S * nl * Hk
-  const bool live = idx < D.S * nl * D.Hk;
-  const int lane = threadIdx.x & 63;
-  if (!live) return;   // whole wavefront; no workgroup barrier below
+  const int heads_per_wg = 256 / lanes_per_head;
+  const int idx = blockIdx.x * heads_per_wg + threadIdx.x / lanes_per_head;   // over S * nl * Hk
+  const int gl = threadIdx.x % lanes_per_head;
+  if (idx >= D.S * nl * D.Hk) return;   // no barrier below
   const int s = idx / (nl * D.Hk);
   const int l = l0 + (idx / D.Hk) % nl;
   const int h = idx % D.Hk;
@@ -238,15 +252,16 @@ __global__ void __launch_bounds__(256) append_write_kernel(Dims D, int l0, int l
   const size_t row_bytes = (size_t)D.d * kv_esz(D.dtype);
   const size_t slot = (size_t)blk * D.b + o;
   const int pieces = (int)(row_bytes / 16);
-  for (int c = lane; c < 2 * pieces; c += 64) {
+  for (int c = gl; c < 2 * pieces; c += lanes_per_head) {
     const bool is_v = c >= pieces;
     const int cc = is_v ? c - pieces : c;
     const uint4* src = (const uint4*)((is_v ? v_new : k_new) + (size_t)g * row_bytes) + cc;
     uint4* dst = (uint4*)((is_v ? vc : kc) + slot * row_bytes) + cc;
     *dst = *src;
   }
-  // every lane of the wavefront has read ctx[g] by now (one instruction stream)
-  if (lane == 0) {
+  // the lanes of a group belong to one wavefront (one instruction stream): all of them have read
+  // ctx[g] by the time one of them writes it
+  if (gl == 0) {
     metric[slot] = 0.0f;
     if (pos) pos[slot] = new_pos ? new_pos[s] : C;
     ctx[g] = C + 1;
@@ -474,7 +489,11 @@ int kvc_append(const kvc_config* cfg, const kvc_state* st, const void* k_new, co
   rc = alloc_common(D, st, W, nullptr, 1, layer_begin, layer_end, s);
   if (rc != KVC_OK) return rc;
   const int nsel = D.S * (layer_end - layer_begin) * D.Hk;
-  hipLaunchKernelGGL(append_write_kernel, dim3((nsel + 3) / 4), dim3(256), 0, s, D, layer_begin, layer_end,
+  int lanes_per_head = 8;   // 2 * pieces rounded up to a power of two, within [8, 64]
+  while (lanes_per_head < 64 && lanes_per_head < 2 * (D.d * kv_esz(D.dtype) / 16)) lanes_per_head *= 2;
+  const int heads_per_wg = 256 / lanes_per_head;
+  hipLaunchKernelGGL(append_write_kernel, dim3((nsel + heads_per_wg - 1) / heads_per_wg), dim3(256), 0, s, D,
+                     layer_begin, layer_end, lanes_per_head,
                      (char*)st->k_cache, (char*)st->v_cache, st->metric, st->pos, st->block_table,
                      st->ctx_len, (const char*)k_new, (const char*)v_new, new_pos, W.header);
   KVC_LAUNCH_CHECK();
