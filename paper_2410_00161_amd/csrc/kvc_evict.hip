@@ -275,14 +275,29 @@ __global__ void __launch_bounds__(256) compact_scan_kernel(Dims D, const uint8_t
   int32_t* srow = flag_scan + (size_t)g * D.maxb;
   int run = 0;
   bool bad = false;
-  for (int base = 0; base < D.maxb; base += 64) {
+  for (int base = 0; base < nb; base += 64) {
     const int u = base + lane;
-    const bool f = (u < D.maxb) && frow[u] != 0;
-    bad |= f && u >= nb;
+    const bool f = (u < nb) && frow[u] != 0;
     const unsigned long long m = __ballot(f);
     const int inc = run + __popcll(m & ((2ull << lane) - 1ull));
     if (u < nb) srow[u] = inc;
     run += __popcll(m);
+  }
+  // no flag may be set past the blocks the head holds: that stretch (most of the row when heads
+  // are compressed far below the length the table is sized for) is only looked at, 16 bytes a
+  // lane where the row is aligned, bytes at its two ends
+  {
+    const uint8_t* p = frow + nb;
+    const uint8_t* end = frow + D.maxb;
+    const uint8_t* body = (const uint8_t*)(((uintptr_t)p + 15) & ~(uintptr_t)15);
+    if (body > end) body = end;
+    const uint8_t* body_end = body + ((end - body) & ~(ptrdiff_t)15);
+    for (const uint8_t* q = p + lane; q < body; q += 64) bad |= *q != 0;
+    for (const uint8_t* q = body + (size_t)lane * 16; q < body_end; q += 1024) {
+      const uint4 v = *(const uint4*)q;
+      bad |= (v.x | v.y | v.z | v.w) != 0;
+    }
+    for (const uint8_t* q = body_end + lane; q < end; q += 64) bad |= *q != 0;
   }
   bad |= run != evict_count[g];
   if (__any(bad) && lane == 0) atomicOr(&header[HW_SCRATCH0], EB_ARG);

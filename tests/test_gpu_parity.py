@@ -456,10 +456,15 @@ def test_select_numeric_error_and_compact_argument_error():
     assert e.value.code == B.KVC_ERR_ARG
     # compact: a flag beyond the head's blocks, and a count that disagrees
     flag, count, sel = sess.evict_select(budget)
-    f2 = flag.clone(); f2[0, shape.max_blocks_per_head - 1] = 1
-    with pytest.raises(B.KvcError) as e:
-        sess.compact(f2, count)
-    assert e.value.code == B.KVC_ERR_ARG
+    nb0 = -(-int(st.lens()[0]) // shape.block_size)
+    maxb = shape.max_blocks_per_head
+    for g_bad, u_bad in ((0, maxb - 1), (0, nb0), (0, nb0 + 1), (0, (nb0 + maxb) // 2), (1, maxb - 2), (2, maxb - 17)):
+        nb_g = -(-int(st.lens()[g_bad]) // shape.block_size)
+        assert nb_g <= u_bad < maxb
+        f2 = flag.clone(); f2[g_bad, u_bad] = 1      # a block the head does not hold
+        with pytest.raises(B.KvcError) as e:
+            sess.compact(f2, count)
+        assert e.value.code == B.KVC_ERR_ARG
     c2 = count.clone(); c2[1] += 1
     with pytest.raises(B.KvcError) as e:
         sess.compact(flag, c2)
