@@ -25,12 +25,14 @@ enum HeaderWord {
   HW_SCRATCH0 = 5,
   HW_SCRATCH1 = 6,
   HW_SHORT_ITEMS = 8,  // decode work items short enough for the one-wavefront launch
+  HW_TOTAL_PARTIALS = 9,  // per-chunk partial-result slots in use = chunks of heads of more than one chunk
   // decode work-list block: item counts per size class, per-class cursors, cursor of the
   // per-chunk partial results.  All zero between calls (the chunk kernel clears it).
   HW_DEC_BINS = 32,    // [16]
   HW_DEC_CUR = 48,     // [16]
   HW_DEC_PCUR = 64,    // [1]
-  HW_DEC_END = 65,
+  HW_DEC_PTOT = 65,    // [1] partial-result slots wanted, counted in pass 1
+  HW_DEC_END = 66,
   HW_WORDS = 128
 };
 
@@ -61,6 +63,7 @@ struct Workspace {
   int32_t* held;       // [G]      blocks held per head instance
   int32_t* picked;     // [N]      k-th lowest free block id
   int32_t* items;      // [max_items][8]      decode work items (see DecodeItem)
+  int32_t* slot_item;  // [max_items]         work item of every partial-result slot in use
   float*   part_ml;    // [max_items][r][2]   chunk max and sum per query head
   float*   part_acc;   // [max_items][r][d]   chunk un-normalised output
   float*   stash;      // [N*b][r]            chunk-relative exp of every logit
@@ -90,6 +93,7 @@ inline Workspace carve(const Dims& D, void* base) {
   w.picked = (int32_t*)take((size_t)D.N * 4);
   size_t items = max_items_of(D);
   w.items = (int32_t*)take(items * 32);
+  w.slot_item = (int32_t*)take(items * 4);
   w.part_ml = (float*)take(items * D.r * 2 * 4);
   w.part_acc = (float*)take(items * D.r * D.d * 4);
   w.stash = (float*)take((size_t)D.N * D.b * D.r * 4);

@@ -674,8 +674,11 @@ __global__ void __launch_bounds__(NW * 64) decode_chunk_kernel(DecodeArgs A) {
 // the combined output.
 template <int R>
 __global__ void __launch_bounds__(256) decode_combine_kernel(DecodeArgs A) {
-  const int item = blockIdx.x;
-  if (item >= A.header[HW_TOTAL_ITEMS] || item >= A.cap) return;
+  // one workgroup per partial-result slot in use, i.e. per chunk of a head of more than one chunk
+  const int p = blockIdx.x;
+  if (p >= A.header[HW_TOTAL_PARTIALS] || p >= A.cap) return;
+  const int item = A.slot_item[p];
+  if (item < 0 || item >= A.header[HW_TOTAL_ITEMS] || item >= A.cap) return;
   const DecodeItem it = A.items[item];
   const int nch = it.nch;
   if (nch <= 1) return;
@@ -861,7 +864,11 @@ static int launch_tiled(const DecodeArgs& A, int grid, size_t lds, int grid_shor
     KVC_LAUNCH_CHECK();
   }
   if (pp) { KVC_HIP(hipEventRecord(pp->s1, s)); KVC_HIP(hipEventRecord(pp->b0, s)); }
-  hipLaunchKernelGGL(decode_combine_kernel<R>, dim3(grid), dim3(256), 0, s, A);
+  // heads of more than one chunk hold more than T tokens each: at most N b / T of them, and their
+  // chunks number at most tokens / T plus one per head
+  const size_t split_bound = 2 * ((size_t)A.D.N * A.D.b / A.T) + 1;
+  const int grid_combine = (size_t)grid < split_bound ? grid : (int)split_bound;
+  hipLaunchKernelGGL(decode_combine_kernel<R>, dim3(grid_combine), dim3(256), 0, s, A);
   KVC_LAUNCH_CHECK();
   if (pp) KVC_HIP(hipEventRecord(pp->b1, s));
   return KVC_OK;
@@ -1020,7 +1027,7 @@ int kvc_paged_decode(const kvc_config* cfg, const kvc_state* st, const void* q, 
   A.accumulate = accumulate_metric != 0;
   A.all_partials = 0;
   A.cap = (int)(max_items_of(D) < 0x7fffffffull ? max_items_of(D) : 0x7fffffffull);
-  A.items = (DecodeItem*)W.items; A.part_ml = W.part_ml; A.part_acc = W.part_acc; A.stash = W.stash;
+  A.items = (DecodeItem*)W.items; A.slot_item = W.slot_item; A.part_ml = W.part_ml; A.part_acc = W.part_acc; A.stash = W.stash;
   A.header = W.header;
   A.scale_log2 = (float)(1.4426950408889634 / sqrt((double)D.d));
 

@@ -405,7 +405,7 @@ static int window_common(const kvc_config* cfg, const kvc_state* st, const void*
   A.short_class = 16;  // no separate launch for short items here
   A.Ts = 0;
   A.cap = (int)(max_items_of(D) < 0x7fffffffull ? max_items_of(D) : 0x7fffffffull);
-  A.items = (DecodeItem*)Wk.items; A.part_ml = Wk.part_ml; A.part_acc = Wk.part_acc; A.stash = Wk.stash;
+  A.items = (DecodeItem*)Wk.items; A.slot_item = Wk.slot_item; A.part_ml = Wk.part_ml; A.part_acc = Wk.part_acc; A.stash = Wk.stash;
   A.header = Wk.header;
   A.scale_log2 = (float)(1.4426950408889634 / 11.313708498984761);  // log2(e) / sqrt(128)
   W.w = w; W.rows = rows; W.pool = pool; W.add = accumulate != 0;

@@ -32,6 +32,7 @@ struct DecodeArgs {
   int all_partials;       // give every head a partial-result slot range, not only split heads
   int short_class, Ts;    // size classes from short_class up (at most Ts tokens) are "short" items; 16 = none
   DecodeItem* items;
+  int32_t* slot_item;     // work item of partial-result slot p (heads of more than one chunk): what the combine kernel runs over
   float* part_ml;
   float* part_acc;
   float* stash;
@@ -57,18 +58,21 @@ __device__ __forceinline__ int size_class(int n, int T) {
 
 // Pass 1 of the work list: number of items per size class.
 static __global__ void __launch_bounds__(256) decode_count_kernel(DecodeArgs A) {
-  __shared__ int bins[16];
-  if (threadIdx.x < 16) bins[threadIdx.x] = 0;
+  __shared__ int bins[17];   // [16] = partial-result slots wanted
+  if (threadIdx.x < 17) bins[threadIdx.x] = 0;
   __syncthreads();
   const int gi = blockIdx.x * 256 + threadIdx.x;
   if (gi < A.gsel) {
     const int C = A.ctx[sel_to_g(A.D, A.l0, A.nl, gi)];
     const int nfull = C / A.T, rem = C - nfull * A.T;
+    const int nch = nfull + (rem ? 1 : 0);
     if (nfull) atomicAdd(&bins[0], nfull);
     if (rem) atomicAdd(&bins[size_class(rem, A.T)], 1);
+    if (nch > 1 || (A.all_partials && nch > 0)) atomicAdd(&bins[16], nch);
   }
   __syncthreads();
   if (threadIdx.x < 16 && bins[threadIdx.x]) atomicAdd(&A.header[HW_DEC_BINS + threadIdx.x], bins[threadIdx.x]);
+  if (threadIdx.x == 16 && bins[16]) atomicAdd(&A.header[HW_DEC_PTOT], bins[16]);
 }
 
 // Pass 2: every head instance claims its places and writes its items; a head that holds no
@@ -90,6 +94,7 @@ static __global__ void __launch_bounds__(256) decode_items_kernel(DecodeArgs A) 
     if (blockIdx.x == 0) {
       A.header[HW_TOTAL_ITEMS] = run;
       A.header[HW_SHORT_ITEMS] = shorts;
+      A.header[HW_TOTAL_PARTIALS] = A.header[HW_DEC_PTOT];
     }
   }
   __syncthreads();
@@ -120,7 +125,8 @@ static __global__ void __launch_bounds__(256) decode_items_kernel(DecodeArgs A) 
     }
     return;
   }
-  const int pbase = (nch > 1 || A.all_partials) ? got[16] + my_p : 0;
+  const bool slotted = nch > 1 || A.all_partials;
+  const int pbase = slotted ? got[16] + my_p : 0;
   // the counters start from zero, so these bounds hold by construction; a workspace that was
   // never reset is the one way to break them, and then nothing is written
   if (pbase < 0 || pbase + nch > A.cap) return;
@@ -130,6 +136,7 @@ static __global__ void __launch_bounds__(256) decode_items_kernel(DecodeArgs A) 
     for (int c = 0; c < nfull; ++c) {
       DecodeItem it = {g, c * T, T, nch, pbase, {0, 0, 0}};
       A.items[at + c] = it;
+      if (slotted) A.slot_item[pbase + c] = at + c;
     }
   }
   if (rem) {
@@ -137,14 +144,16 @@ static __global__ void __launch_bounds__(256) decode_items_kernel(DecodeArgs A) 
     if (at < 0 || at >= A.cap) return;
     DecodeItem it = {g, nfull * T, rem, nch, pbase, {0, 0, 0}};
     A.items[at] = it;
+    if (slotted) A.slot_item[pbase + nfull] = at;
   }
 }
 
 // Both passes in one workgroup, for calls over at most 1024 head instances (one layer of a
 // model): one launch instead of two.  Leaves the header words as the two-pass pair does.
 static __global__ void __launch_bounds__(1024) decode_worklist_small_kernel(DecodeArgs A) {
-  __shared__ int bins[16], base[16], cur[17];
+  __shared__ int bins[16], base[16], cur[17], ptot;
   const int tid = threadIdx.x;
+  if (tid == 0) ptot = 0;
   if (tid < 16) bins[tid] = 0;
   if (tid < 17) cur[tid] = 0;
   __syncthreads();
@@ -159,9 +168,11 @@ static __global__ void __launch_bounds__(1024) decode_worklist_small_kernel(Deco
     cls = rem ? size_class(rem, T) : 0;
     if (nfull) atomicAdd(&bins[0], nfull);
     if (rem) atomicAdd(&bins[cls], 1);
+    if (nch > 1 || (A.all_partials && nch > 0)) atomicAdd(&ptot, nch);
   }
   __syncthreads();
   if (tid == 0) {
+    A.header[HW_TOTAL_PARTIALS] = ptot;
     int run = 0, shorts = 0;
     for (int k = 0; k < 16; ++k) {
       base[k] = run;
@@ -180,7 +191,8 @@ static __global__ void __launch_bounds__(1024) decode_worklist_small_kernel(Deco
     }
     return;
   }
-  const int pbase = (nch > 1 || A.all_partials) ? atomicAdd(&cur[16], nch) : 0;
+  const bool slotted = nch > 1 || A.all_partials;
+  const int pbase = slotted ? atomicAdd(&cur[16], nch) : 0;
   if (pbase < 0 || pbase + nch > A.cap) return;
   if (nfull) {
     const int at = base[0] + atomicAdd(&cur[0], nfull);
@@ -188,6 +200,7 @@ static __global__ void __launch_bounds__(1024) decode_worklist_small_kernel(Deco
     for (int c = 0; c < nfull; ++c) {
       DecodeItem it = {g, c * T, T, nch, pbase, {0, 0, 0}};
       A.items[at + c] = it;
+      if (slotted) A.slot_item[pbase + c] = at + c;
     }
   }
   if (rem) {
@@ -195,6 +208,7 @@ static __global__ void __launch_bounds__(1024) decode_worklist_small_kernel(Deco
     if (at < 0 || at >= A.cap) return;
     DecodeItem it = {g, nfull * T, rem, nch, pbase, {0, 0, 0}};
     A.items[at] = it;
+    if (slotted) A.slot_item[pbase + nfull] = at;
   }
 }
 
