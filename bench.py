@@ -94,6 +94,8 @@ def main():
     ap.add_argument("--no-metric", action="store_true", help="diagnostic: decode without metric accumulation")
     ap.add_argument("--per-layer-steps", type=int, default=4,
                     help="extra untimed-region steps that call the decode once per layer (0 = skip)")
+    ap.add_argument("--all-queries-block", type=int, default=64, choices=[16, 32, 64],
+                    help="queries per call when the prefill-end probe gathers the metric over all prompt queries")
     ap.add_argument("--window-probe", type=int, default=1,
                     help="also time the observation-window metric and a rank-block eviction to 8x on a "
                          "Mistral-7B-shaped 16384-token prompt (0 = skip)")
@@ -321,6 +323,20 @@ def main():
         del c4
         g4 = torch.Generator(device=dev).manual_seed(1004)
         qw = torch.randn((1, 32, 32, wq, 128), generator=g4, device=dev, dtype=torch.float32).to(torch.bfloat16)
+        # the metric over ALL prompt queries (every query attends to the keys at least 10
+        # positions before it), gathered one block of 64 queries at a time; the same random
+        # block of queries stands in for every block of the prompt
+        wb, excl = args.all_queries_block, 10
+        qb = torch.randn((1, 32, 32, wb, 128), generator=g4, device=dev, dtype=torch.float32).to(torch.bfloat16)
+        s4.cache.metric.zero_()
+        a, b_ = ev(), ev()
+        a.record()
+        for start in range(0, Lp, wb):
+            s4.query_block_metric(qb, wb, start, excl)
+        b_.record()
+        torch.cuda.synchronize()
+        all_queries_ms = a.elapsed_time(b_)
+        del qb
         best = 1e9
         for _ in range(4):
             a, b_ = ev(), ev()
@@ -341,13 +357,32 @@ def main():
         c_.record()
         torch.cuda.synchronize()
         assert B.kvc_poll_status(s4.cfg, s4.ws) == B.KVC_OK
+        kvs_after = int(s4.cache.ctx_len.sum().item())
+        select_ms, compact_ms = a.elapsed_time(b_), b_.elapsed_time(c_)
+        # then 256 decode steps on what is left (append + decode + metric)
+        q4 = [W.make_query(shp, 1004, i, dev) for i in range(2)]
+        kv4 = [W.make_new_kv(shp, 1004, i, dev) for i in range(2)]
+        nd = 256
+        a, b_ = ev(), ev()
+        a.record()
+        for i in range(nd):
+            s4.append(*kv4[i % 2], flags=B.KVC_ASYNC)
+            s4.paged_decode(q4[i % 2])
+        b_.record()
+        torch.cuda.synchronize()
+        assert B.kvc_poll_status(s4.cfg, s4.ws) == B.KVC_OK
+        decode_ms = a.elapsed_time(b_) / nd
         prefill_end = {"workload": "Mistral-7B-shaped: 32 layers, 32q/8kv heads, d=128, bf16, one 16384-token prompt",
                        "window_queries": wq, "pool": 7, "window_metric_ms": best,
                        "window_metric_K_GBps": 2 * 256 * kvs4 / (best * 1e-3) / 1e9,
                        "window_metric_TFLOPs": 2 * 2 * (wq * 4) * 128 * kvs4 / (best * 1e-3) / 1e12,
-                       "rank_select_to_8x_ms": a.elapsed_time(b_), "rank_compact_ms": b_.elapsed_time(c_),
-                       "kvs_after": int(s4.cache.ctx_len.sum().item()), "kvs_before": kvs4}
-        del s4, qw
+                       "rank_select_to_8x_ms": select_ms, "rank_compact_ms": compact_ms,
+                       "kvs_after": kvs_after, "kvs_before": kvs4,
+                       "all_queries_metric_ms": all_queries_ms, "all_queries_block": wb, "all_queries_exclude": excl,
+                       "all_queries_TFLOPs": 2 * 2 * (4 * 128) * shp.G * (Lp * (Lp + wb) / 2) / (all_queries_ms * 1e-3) / 1e12,
+                       "decode_steps_after": nd, "decode_ms_per_step_after": decode_ms,
+                       "decode_GBps_after": (kvs_after + shp.G * nd / 2) * algorithmic_bytes_per_kv(shp) / (decode_ms * 1e-3) / 1e9}
+        del s4, qw, q4, kv4
 
     evict = None
     if evict_events:

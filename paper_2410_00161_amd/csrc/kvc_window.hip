@@ -86,9 +86,17 @@ __device__ __forceinline__ void load_tile(const WindowArgs& W, const int* s_tab,
   }
 }
 
+// Running (max, sum) pairs a wavefront keeps per column tile in pass 1.  One per lane (a lane
+// covers 16 of a tile's 64 tokens for its query row) up to 128 query rows; at 256 rows the four
+// lanes of a row merge theirs after every tile instead, four cross-lane moves per tile, which
+// brings the workgroup from 96 KB of LDS to 72 and a second workgroup onto the CU.
+__host__ __device__ constexpr int window_pairs_per_tile(int nt) { return nt >= 16 ? 16 : 64; }
+
 // Pass 1: per chunk and query row, max and sum of exp2 over the visible keys.
 template <int NT>
 __global__ void __launch_bounds__(kWinThreads) window_stats_kernel(WindowArgs W) {
+  constexpr int PPT = window_pairs_per_tile(NT);
+  constexpr bool kRowMerged = PPT == 16;
   const DecodeArgs& A = W.A;
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   const int total_items = A.header[HW_TOTAL_ITEMS];
@@ -101,8 +109,8 @@ __global__ void __launch_bounds__(kWinThreads) window_stats_kernel(WindowArgs W)
   extern __shared__ __align__(16) char smem_raw[];
   uint4* s_q = (uint4*)smem_raw;                        // [NT * 4 * 64]
   float* s_ml = (float*)s_q;                            // [waves][NT * 16][2], once the main loops are over
-  float2* s_st = (float2*)(s_q + NT * 4 * 64);          // [waves][NT][64]
-  int* s_tab = (int*)(s_st + kWinWaves * NT * 64);      // [T / b + 1]
+  float2* s_st = (float2*)(s_q + NT * 4 * 64);          // [waves][NT][PPT]
+  int* s_tab = (int*)(s_st + kWinWaves * NT * PPT);     // [T / b + 1]
   const int b = A.D.b, lb = A.log2b;
   const int C = A.ctx[g];
   {
@@ -114,8 +122,8 @@ __global__ void __launch_bounds__(kWinThreads) window_stats_kernel(WindowArgs W)
   __syncthreads();
   // running (max, sum) of this lane's query row per column tile: kept in LDS so that the loop
   // over column tiles stays a loop (registers: one K tile and one Q tile at a time)
-  float2* my_st = s_st + (size_t)wv * NT * 64 + lane;
-  for (int ct = 0; ct < NT; ++ct) my_st[ct * 64] = make_float2(-INFINITY, 0.0f);
+  float2* my_st = s_st + (size_t)wv * NT * PPT + (lane & (PPT - 1));
+  for (int ct = 0; ct < NT; ++ct) my_st[ct * PPT] = make_float2(-INFINITY, 0.0f);
   const int first_free = W.first_pos >= 0 ? W.first_pos : C - W.w;  // query i sits at first_free + i
   const int free_lim = min(first_free, C - 1);   // keys up to here are visible to every query
   const bool dead = t0 > min(first_free + W.w - 1, C - 1);  // no query of the block sees this chunk
@@ -137,7 +145,7 @@ __global__ void __launch_bounds__(kWinThreads) window_stats_kernel(WindowArgs W)
         }
         // the running max stays in raw dot-product units inside the loop: the scale goes into one
         // multiply-add per logit (max, fma, exp2, add)
-        const float2 old = my_st[ct * 64];
+        const float2 old = my_st[ct * PPT];
         float s[16];
         float mx = old.x;
 #pragma unroll
@@ -156,12 +164,21 @@ __global__ void __launch_bounds__(kWinThreads) window_stats_kernel(WindowArgs W)
             mx = fmaxf(mx, x);
           }
         }
-        if (mx > -INFINITY) {
+        if constexpr (kRowMerged) {   // the row's max over the tile's 64 tokens
+          mx = fmaxf(mx, __shfl_xor(mx, 16));
+          mx = fmaxf(mx, __shfl_xor(mx, 32));
+        }
+        if (mx > -INFINITY) {   // (the same in the four lanes of a row when they merge)
           const float off = -mx * A.scale_log2;
-          float sum = old.y * __builtin_amdgcn_exp2f(fmaf(old.x, A.scale_log2, off));
+          float sum = 0.0f;
 #pragma unroll
           for (int e = 0; e < 16; ++e) sum += __builtin_amdgcn_exp2f(fmaf(s[e], A.scale_log2, off));
-          my_st[ct * 64] = make_float2(mx, sum);
+          if constexpr (kRowMerged) {
+            sum += __shfl_xor(sum, 16);
+            sum += __shfl_xor(sum, 32);
+          }
+          sum += old.y * __builtin_amdgcn_exp2f(fmaf(old.x, A.scale_log2, off));
+          if (!kRowMerged || lane < 16) my_st[ct * PPT] = make_float2(mx, sum);
         }
       }
     };
@@ -171,10 +188,10 @@ __global__ void __launch_bounds__(kWinThreads) window_stats_kernel(WindowArgs W)
   __syncthreads();   // every wavefront is done with Q: its bytes now take the per-wavefront pairs
   // merge the four lanes that share a query row, then the wavefronts, then write the chunk's pair
   for (int ct = 0; ct < NT; ++ct) {
-    float2 st = my_st[ct * 64];
+    float2 st = my_st[ct * PPT];
     st.x *= A.scale_log2;   // from here on maxima are in scaled log2 units
 #pragma unroll
-    for (int msk = 16; msk <= 32; msk <<= 1) {
+    for (int msk = 16; msk <= (kRowMerged ? 0 : 32); msk <<= 1) {
       const float om = __shfl_xor(st.x, msk), ol = __shfl_xor(st.y, msk);
       const float nm = fmaxf(st.x, om);
       if (nm > -INFINITY) st.y = st.y * __builtin_amdgcn_exp2f(st.x - nm) + ol * __builtin_amdgcn_exp2f(om - nm);
@@ -345,10 +362,11 @@ __global__ void __launch_bounds__(256) window_pool_kernel(WindowArgs W) {
 
 template <int NT>
 static int launch_window(const WindowArgs& W, int grid, hipStream_t s) {
-  // pass 1: Q (later the per-wavefront pairs), running pairs per lane and column tile, block ids;
-  // pass 2: Q, one float per query row, block ids.  Three and four workgroups per CU at 128 rows.
+  // pass 1: Q (later the per-wavefront pairs), running pairs per column tile, block ids;
+  // pass 2: Q, one float per query row, block ids.  Three and four workgroups per CU at 128 rows,
+  // two and two at 256.
   const size_t tab = ((size_t)kWinChunk / W.A.D.b + 1) * 4;
-  const size_t lds = (size_t)NT * 4 * 64 * 16 + (size_t)kWinWaves * NT * 64 * 8 + tab;
+  const size_t lds = (size_t)NT * 4 * 64 * 16 + (size_t)kWinWaves * NT * window_pairs_per_tile(NT) * 8 + tab;
   const size_t lds2 = (size_t)NT * 4 * 64 * 16 + (size_t)NT * 16 * 4 + tab;
   static_assert((size_t)kWinWaves * NT * 16 * 2 * 4 <= (size_t)NT * 4 * 64 * 16, "pairs fit where Q was");
   static size_t allowed = 0;   // above the default cap a kernel must be told how much it may take
