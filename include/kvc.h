@@ -271,8 +271,8 @@ int kvc_compact_rank(const kvc_config* cfg, const kvc_state* st, const int32_t* 
  * prefix (pool odd; 1 = no pooling); keys inside the window keep raw.  The result replaces
  * metric[slot] of every KV of those layers, or is added to it when accumulate != 0.
  * Runs on the matrix cores; covers kv_dtype = KVC_BF16, head_dim = 128, block_size in
- * {16, 32, 64}, w * group_size <= 256, else KVC_ERR_UNSUPPORTED (such callers can gather the
- * same sums with one kvc_paged_decode per window query).  Asynchronous.            */
+ * {16, 32, 64}, w <= 64 and w * group_size <= 256, else KVC_ERR_UNSUPPORTED (such callers can
+ * gather the same sums with one kvc_paged_decode per window query).  Asynchronous. */
 int kvc_window_metric(const kvc_config* cfg, const kvc_state* st, const void* q_win, int w, int pool,
                       int accumulate, int layer_begin, int layer_end, void* ws, void* stream);
 

@@ -404,9 +404,10 @@ static int window_common(const kvc_config* cfg, const kvc_state* st, const void*
   // the matrix-core kernels cover bf16, d = 128, blocks of a multiple of 16 tokens, up to 256 query rows
   if (D.dtype != KVC_BF16 || D.d != 128 || D.b % 16 != 0 || 64 % D.b != 0) return KVC_ERR_UNSUPPORTED;
   const int rows = w * D.r;
-  if (rows > 256) return KVC_ERR_UNSUPPORTED;
+  // (w <= 64: a chunk's pairs, 8 bytes per padded query row, live in the decode's slot of r * d floats)
+  if (rows > 256 || w > 64) return KVC_ERR_UNSUPPORTED;
   const int nt = rows <= 32 ? 2 : rows <= 64 ? 4 : rows <= 128 ? 8 : 16;
-  if ((size_t)nt * 16 * 8 > (size_t)D.r * D.d * 4) return KVC_ERR_UNSUPPORTED;  // per-chunk pairs reuse the decode's slots
+  if ((size_t)nt * 16 * 8 > (size_t)D.r * D.d * 4) return KVC_ERR_UNSUPPORTED;
   Workspace Wk = carve(D, ws);
   hipStream_t s = (hipStream_t)stream;
   WindowArgs W;
