@@ -1054,7 +1054,7 @@ int kvc_paged_decode(const kvc_config* cfg, const kvc_state* st, const void* q, 
     KVC_LAUNCH_CHECK();
     return KVC_OK;
   }
-  if (A.gsel <= 1024) {
+  if (A.gsel <= kSmallWorklistHeads) {
     hipLaunchKernelGGL(decode_worklist_small_kernel, dim3(1), dim3(1024), 0, s, A);
     KVC_LAUNCH_CHECK();
   } else {

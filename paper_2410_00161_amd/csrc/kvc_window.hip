@@ -431,10 +431,15 @@ static int window_common(const kvc_config* cfg, const kvc_state* st, const void*
   W.first_pos = first_pos; W.exclude = exclude;
   W.part = Wk.part_acc; W.raw = Wk.stash;
   // a head that holds no KV has no output here: the item kernel's zero rows must not be written
-  hipLaunchKernelGGL(decode_count_kernel, dim3((A.gsel + 255) / 256), dim3(256), 0, s, A);
-  KVC_LAUNCH_CHECK();
-  hipLaunchKernelGGL(decode_items_kernel, dim3((A.gsel + 255) / 256), dim3(256), 0, s, A);
-  KVC_LAUNCH_CHECK();
+  if (A.gsel <= kSmallWorklistHeads) {
+    hipLaunchKernelGGL(decode_worklist_small_kernel, dim3(1), dim3(1024), 0, s, A);
+    KVC_LAUNCH_CHECK();
+  } else {
+    hipLaunchKernelGGL(decode_count_kernel, dim3((A.gsel + 255) / 256), dim3(256), 0, s, A);
+    KVC_LAUNCH_CHECK();
+    hipLaunchKernelGGL(decode_items_kernel, dim3((A.gsel + 255) / 256), dim3(256), 0, s, A);
+    KVC_LAUNCH_CHECK();
+  }
   const size_t bound_pool = (size_t)D.N * D.b / A.T + (size_t)A.gsel;
   const size_t bound_row = (size_t)A.gsel * (((size_t)D.maxb * D.b + A.T - 1) / A.T);
   const size_t grid = bound_pool < bound_row ? bound_pool : bound_row;
