@@ -1026,6 +1026,7 @@ int kvc_paged_decode(const kvc_config* cfg, const kvc_state* st, const void* q, 
   A.l0 = layer_begin; A.nl = layer_end - layer_begin; A.gsel = D.S * A.nl * D.Hk;
   A.accumulate = accumulate_metric != 0;
   A.all_partials = 0;
+  A.rotate_chunks = 0;
   A.cap = (int)(max_items_of(D) < 0x7fffffffull ? max_items_of(D) : 0x7fffffffull);
   A.items = (DecodeItem*)W.items; A.slot_item = W.slot_item; A.part_ml = W.part_ml; A.part_acc = W.part_acc; A.stash = W.stash;
   A.header = W.header;

@@ -5,10 +5,14 @@
 // Calculation", KVC-w - squared before summation).
 //
 // Unlike the decode this is a dense contraction: w * r query rows (32 .. 256)
-// against every key of the head, so it runs on the matrix cores.  Per
-// 16-token block: S^T[16 tokens x 16 query rows] += K[16 x 32] * Q^T[32 x 16]
-// with v_mfma_f32_16x16x32_bf16, four k-slices for d = 128.  A lane holds 64
-// contiguous bytes of one token (its four 16-byte loads are the four k-slices),
+// against every key of the head, so it runs on the matrix cores.  Up to 128
+// rows, per 16 tokens and 16 rows: S^T[16 x 16] += K[16 x 32] * Q^T[32 x 16]
+// with v_mfma_f32_16x16x32_bf16, four k-slices for d = 128; above, per 32
+// tokens and 32 rows, v_mfma_f32_32x32x16_bf16 with eight k-slices (that shape
+// issues at the full bf16 rate of this chip and the smaller one at half of it,
+// but its kernel needs more registers than three or four wavefronts per SIMD
+// leave; at 256 rows the LDS holds the CU to two per SIMD anyway).  A lane holds
+// 64 (128) contiguous bytes of one token, its 16-byte loads being the k-slices,
 // and Q is staged in LDS in exactly the register order of the B operand, so no
 // transposes and no bank conflicts.  The contraction over d does not care in
 // which order dimensions are assigned to k-slices as long as K and Q agree.
@@ -26,6 +30,7 @@ namespace kvc {
 
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
+typedef float f32x16_t __attribute__((ext_vector_type(16)));
 
 constexpr int kWinChunk = 1024;   // tokens per workgroup
 constexpr int kWinThreads = 256;
@@ -42,61 +47,110 @@ struct WindowArgs {
   float* raw;          // [N * b] un-pooled sums, by physical slot
 };
 
-__device__ __forceinline__ f32x4_t mfma16(const uint4& a, const uint4& b, f32x4_t c) {
-  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c,
-                                                 0, 0, 0);
+// Last key, in a head of C KVs, that any query of the call sees (lag = 0; query i sits at
+// first + i and sees keys 0 .. its position) or adds to (lag = the excluded window: only keys at
+// least that far behind the query).  Chunks that start behind it have no work in that pass, and
+// nothing reads what they would have left.
+__device__ __forceinline__ int last_key(const WindowArgs& W, int C, int lag) {
+  const int first = W.first_pos >= 0 ? W.first_pos : C - W.w;
+  return min(first + W.w - 1 - lag, C - 1);
 }
 
-// Q of one head instance into LDS, in B-operand order: entry ((ct * 4 + kk) * 64 + lane) holds,
-// for query row ct * 16 + lane % 16, the 8 dimensions 32 * (lane / 16) + 8 * kk .. + 8.
+// One matrix-core product: M tokens x M query rows.  Lane l holds query row l % M; `token` is
+// the token, among the product's M, of element i of that lane's result.
+template <int M> struct Mma;
+template <> struct Mma<16> {
+  typedef f32x4_t Acc;
+  static constexpr int NV = 4;
+  static __device__ __forceinline__ Acc run(const uint4& a, const uint4& b, Acc c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b),
+                                                   c, 0, 0, 0);
+  }
+  static __device__ __forceinline__ int token(int i, int lane) { return 4 * (lane >> 4) + i; }
+};
+template <> struct Mma<32> {
+  typedef f32x16_t Acc;
+  static constexpr int NV = 16;
+  static __device__ __forceinline__ Acc run(const uint4& a, const uint4& b, Acc c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b),
+                                                   c, 0, 0, 0);
+  }
+  static __device__ __forceinline__ int token(int i, int lane) { return (i & 3) + 8 * (i >> 2) + 4 * (lane >> 5); }
+};
+// lanes that share a query row; 16-byte k-slices of a lane's part of a 256-byte row; products
+// per 64-token tile
+template <int M> constexpr int kLanesPerRow = 64 / M;
+template <int M> constexpr int kSlices = 16 / kLanesPerRow<M>;
+template <int M> constexpr int kProducts = 64 / M;
+
+// Q of one head instance into LDS, in B-operand order: entry ((ct * KS + s) * 64 + lane) holds,
+// for query row ct * M + lane % M, the 8 dimensions at byte 16 KS (lane / M) + 16 s of the row.
 // Query row rho = i * r + hh (window query i, query head hh); rows past w * r are zero.
-template <int NT>
+// Read in runs of 64 bytes, four lanes to a run and 16 consecutive rows to a wavefront: with one
+// lane per LDS entry instead, every 16-byte read touches a line of its own, Q (up to 64 KB)
+// does not fit the 16 KB first-level cache, and each workgroup pulls its Q from L2 eight times
+// over - at 256 rows that was most of both passes.  The price is a 4-way bank conflict on the
+// LDS writes, a microsecond per workgroup.
+template <int M, int NT>
 __device__ __forceinline__ void stage_queries(const WindowArgs& W, int g, uint4* s_q) {
+  constexpr int KS = kSlices<M>, ROWS = NT * M;
+  constexpr int PER = ROWS * 16 / kWinThreads;   // pieces per thread
+  static_assert(PER * kWinThreads == ROWS * 16 && PER <= 16, "whole rounds of the workgroup");
   const int r = W.A.D.r, w = W.w;
   const char* qbase = W.A.q + (size_t)g * r * w * 256;  // [r][w][128] bf16
-  for (int e = threadIdx.x; e < NT * 4 * 64; e += kWinThreads) {
-    const int lane = e & 63, kk = (e >> 6) & 3, ct = e >> 8;
-    const int rho = ct * 16 + (lane & 15);
-    uint4 v = make_uint4(0, 0, 0, 0);
-    if (rho < W.rows) {
-      const int i = rho / r, hh = rho % r;
-      v = *(const uint4*)(qbase + ((size_t)hh * w + i) * 256 + 64 * (lane >> 4) + 16 * kk);
-    }
-    s_q[e] = v;
+  // all of a thread's loads first, then its stores: one trip to memory, not PER of them
+  uint4 v[PER];
+#pragma unroll
+  for (int it = 0; it < PER; ++it) {
+    const int e = threadIdx.x + it * kWinThreads;
+    const int rho = (e >> 2) % ROWS;
+    const int c = 4 * ((e >> 2) / ROWS) + (e & 3);   // 16-byte piece of the row
+    const int i = rho / r, hh = rho % r;
+    // (rows past w * r read row 0 and are zeroed: a select between values, no branch around a load)
+    const uint4 t = *(const uint4*)(qbase + (rho < W.rows ? (size_t)hh * w + i : 0) * 256 + 16 * c);
+    v[it] = rho < W.rows ? t : make_uint4(0, 0, 0, 0);
+  }
+#pragma unroll
+  for (int it = 0; it < PER; ++it) {
+    const int e = threadIdx.x + it * kWinThreads;
+    const int rho = (e >> 2) % ROWS;
+    const int c = 4 * ((e >> 2) / ROWS) + (e & 3);
+    s_q[((rho / M) * KS + c % KS) * 64 + (c / KS) * M + rho % M] = v[it];
   }
 }
 
-// Loads the 64-token tile starting at chunk token `tt`: four blocks, four k-slices each.
-// Blocks past the end of the chunk are not touched.
+// Loads the 64-token tile starting at chunk token `tt` as A operands of M tokens each: lane
+// (token lane % M, part lane / M of its row) holds that part's k-slices.  16-token blocks past
+// the end of the chunk are not touched and read as zero.
+template <int M>
 __device__ __forceinline__ void load_tile(const WindowArgs& W, const int* s_tab, int tt, int n_tok, int lane,
-                                          uint4 (&k)[4][4]) {
+                                          uint4 (&k)[kProducts<M>][kSlices<M>]) {
+  constexpr int KS = kSlices<M>;
   const int lb = W.A.log2b, b = W.A.D.b;
 #pragma unroll
-  for (int tg = 0; tg < 4; ++tg) {
-    const int t = tt + tg * 16;
-    if (t < n_tok) {
-      const size_t slot = ((size_t)s_tab[t >> lb] << lb) + (t & (b - 1)) + (lane & 15);
-      const char* p = W.A.kc + slot * 256 + 64 * (lane >> 4);
+  for (int pr = 0; pr < kProducts<M>; ++pr) {
+    const int t = tt + pr * M + (lane & (M - 16));   // first token of this lane's 16-token block
+    const bool live = t < n_tok;
+    const size_t slot = live ? ((size_t)s_tab[t >> lb] << lb) + (t & (b - 1)) + (lane & 15) : 0;
+    const char* p = W.A.kc + slot * 256 + 16 * KS * (lane / M);
 #pragma unroll
-      for (int kk = 0; kk < 4; ++kk) k[tg][kk] = *(const uint4*)(p + 16 * kk);
-    } else {
-#pragma unroll
-      for (int kk = 0; kk < 4; ++kk) k[tg][kk] = make_uint4(0, 0, 0, 0);
-    }
+    for (int sl = 0; sl < KS; ++sl) k[pr][sl] = live ? *(const uint4*)(p + 16 * sl) : make_uint4(0, 0, 0, 0);
   }
 }
 
 // Running (max, sum) pairs a wavefront keeps per column tile in pass 1.  One per lane (a lane
-// covers 16 of a tile's 64 tokens for its query row) up to 128 query rows; at 256 rows the four
-// lanes of a row merge theirs after every tile instead, four cross-lane moves per tile, which
+// covers 64 / kLanesPerRow tokens of a tile for its query row) up to 128 query rows; at 256 the
+// lanes of a row merge theirs after every tile instead, a few cross-lane moves per tile, which
 // brings the workgroup from 96 KB of LDS to 72 and a second workgroup onto the CU.
-__host__ __device__ constexpr int window_pairs_per_tile(int nt) { return nt >= 16 ? 16 : 64; }
+__host__ __device__ constexpr int window_pairs_per_tile(int m, int nt) { return nt * m >= 256 ? m : 64; }
 
 // Pass 1: per chunk and query row, max and sum of exp2 over the visible keys.
-template <int NT>
+template <int M, int NT>
 __global__ void __launch_bounds__(kWinThreads) window_stats_kernel(WindowArgs W) {
-  constexpr int PPT = window_pairs_per_tile(NT);
-  constexpr bool kRowMerged = PPT == 16;
+  typedef Mma<M> MM;
+  constexpr int KS = kSlices<M>, NP = kProducts<M>, ROWS = NT * M;
+  constexpr int PPT = window_pairs_per_tile(M, NT);
+  constexpr bool kRowMerged = PPT == M;
   const DecodeArgs& A = W.A;
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   const int total_items = A.header[HW_TOTAL_ITEMS];
@@ -107,113 +161,121 @@ __global__ void __launch_bounds__(kWinThreads) window_stats_kernel(WindowArgs W)
       it.pbase + it.nch > A.cap)
     return;
   extern __shared__ __align__(16) char smem_raw[];
-  uint4* s_q = (uint4*)smem_raw;                        // [NT * 4 * 64]
-  float* s_ml = (float*)s_q;                            // [waves][NT * 16][2], once the main loops are over
-  float2* s_st = (float2*)(s_q + NT * 4 * 64);          // [waves][NT][PPT]
+  uint4* s_q = (uint4*)smem_raw;                        // [NT * KS * 64]
+  float* s_ml = (float*)s_q;                            // [waves][ROWS][2], once the main loops are over
+  float2* s_st = (float2*)(s_q + NT * KS * 64);         // [waves][NT][PPT]
   int* s_tab = (int*)(s_st + kWinWaves * NT * PPT);     // [T / b + 1]
   const int b = A.D.b, lb = A.log2b;
   const int C = A.ctx[g];
+  const size_t pslot = (size_t)it.pbase + (size_t)(t0 / A.T);
+  const int first_free = W.first_pos >= 0 ? W.first_pos : C - W.w;  // query i sits at first_free + i
+  const int free_lim = min(first_free, C - 1);   // keys up to here are visible to every query
+  if (t0 > last_key(W, C, 0)) return;   // no query of the block sees this chunk
   {
     const int nblk = (n_tok + b - 1) >> lb;
     const int32_t* row = A.table + (size_t)g * A.D.maxb + (t0 >> lb);
     for (int i = tid; i < nblk; i += kWinThreads) s_tab[i] = row[i];
   }
-  stage_queries<NT>(W, g, s_q);
+  stage_queries<M, NT>(W, g, s_q);
   __syncthreads();
-  // running (max, sum) of this lane's query row per column tile: kept in LDS so that the loop
-  // over column tiles stays a loop (registers: one K tile and one Q tile at a time)
+  // running (max, sum) per column tile: kept in LDS so that the loop over column tiles stays a
+  // loop (registers: one K tile and one Q tile at a time)
   float2* my_st = s_st + (size_t)wv * NT * PPT + (lane & (PPT - 1));
   for (int ct = 0; ct < NT; ++ct) my_st[ct * PPT] = make_float2(-INFINITY, 0.0f);
-  const int first_free = W.first_pos >= 0 ? W.first_pos : C - W.w;  // query i sits at first_free + i
-  const int free_lim = min(first_free, C - 1);   // keys up to here are visible to every query
-  const bool dead = t0 > min(first_free + W.w - 1, C - 1);  // no query of the block sees this chunk
-  for (int tt = wv * 64; tt < n_tok && !dead; tt += 64 * kWinWaves) {
-    uint4 k[4][4];
-    load_tile(W, s_tab, tt, n_tok, lane, k);
+  auto tile = [&](uint4 (&k)[NP][KS], int tt) {
     // most tiles lie wholly in front of the window: they run the loop without the causal mask
     auto column_tiles = [&](auto masked_c) {
       constexpr bool kMasked = decltype(masked_c)::value;
 #pragma unroll 1
       for (int ct = 0; ct < NT; ++ct) {
-        uint4 q[4];
+        uint4 q[KS];
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) q[kk] = s_q[(ct * 4 + kk) * 64 + lane];
+        for (int sl = 0; sl < KS; ++sl) q[sl] = s_q[(ct * KS + sl) * 64 + lane];
         int last_vis = 0;
         if constexpr (kMasked) {
-          const int rho = ct * 16 + (lane & 15);
+          const int rho = ct * M + (lane & (M - 1));
           last_vis = min(first_free + rho / A.D.r, C - 1);  // query i sees keys 0 .. its position
         }
+        typename MM::Acc acc[NP];
+#pragma unroll
+        for (int pr = 0; pr < NP; ++pr)
+#pragma unroll
+          for (int i = 0; i < MM::NV; ++i) acc[pr][i] = 0.0f;
+#pragma unroll
+        for (int sl = 0; sl < KS; ++sl)   // NP independent accumulation chains
+#pragma unroll
+          for (int pr = 0; pr < NP; ++pr) acc[pr] = MM::run(k[pr][sl], q[sl], acc[pr]);
         // the running max stays in raw dot-product units inside the loop: the scale goes into one
         // multiply-add per logit (max, fma, exp2, add)
         const float2 old = my_st[ct * PPT];
-        float s[16];
         float mx = old.x;
 #pragma unroll
-        for (int tg = 0; tg < 4; ++tg) {
-          f32x4_t acc = {0.0f, 0.0f, 0.0f, 0.0f};
+        for (int pr = 0; pr < NP; ++pr)
 #pragma unroll
-          for (int kk = 0; kk < 4; ++kk) acc = mfma16(k[tg][kk], q[kk], acc);
-#pragma unroll
-          for (int v = 0; v < 4; ++v) {
-            float x = acc[v];
+          for (int i = 0; i < MM::NV; ++i) {
             if constexpr (kMasked) {
-              const int j = t0 + tt + tg * 16 + 4 * (lane >> 4) + v;
-              if (j > last_vis) x = -INFINITY;
+              const int j = t0 + tt + pr * M + MM::token(i, lane);
+              if (j > last_vis) acc[pr][i] = -INFINITY;
             }
-            s[tg * 4 + v] = x;
-            mx = fmaxf(mx, x);
+            mx = fmaxf(mx, acc[pr][i]);
           }
-        }
         if constexpr (kRowMerged) {   // the row's max over the tile's 64 tokens
-          mx = fmaxf(mx, __shfl_xor(mx, 16));
-          mx = fmaxf(mx, __shfl_xor(mx, 32));
+#pragma unroll
+          for (int msk = M; msk < 64; msk <<= 1) mx = fmaxf(mx, __shfl_xor(mx, msk));
         }
-        if (mx > -INFINITY) {   // (the same in the four lanes of a row when they merge)
+        if (mx > -INFINITY) {   // (the same in the lanes of a row when they merge)
           const float off = -mx * A.scale_log2;
           float sum = 0.0f;
 #pragma unroll
-          for (int e = 0; e < 16; ++e) sum += __builtin_amdgcn_exp2f(fmaf(s[e], A.scale_log2, off));
+          for (int pr = 0; pr < NP; ++pr)
+#pragma unroll
+            for (int i = 0; i < MM::NV; ++i) sum += __builtin_amdgcn_exp2f(fmaf(acc[pr][i], A.scale_log2, off));
           if constexpr (kRowMerged) {
-            sum += __shfl_xor(sum, 16);
-            sum += __shfl_xor(sum, 32);
+#pragma unroll
+            for (int msk = M; msk < 64; msk <<= 1) sum += __shfl_xor(sum, msk);
           }
           sum += old.y * __builtin_amdgcn_exp2f(fmaf(old.x, A.scale_log2, off));
-          if (!kRowMerged || lane < 16) my_st[ct * PPT] = make_float2(mx, sum);
+          if (!kRowMerged || lane < M) my_st[ct * PPT] = make_float2(mx, sum);
         }
       }
     };
     if (t0 + tt + 63 > free_lim) column_tiles(std::true_type{});
     else column_tiles(std::false_type{});
+  };
+  for (int tt = wv * 64; tt < n_tok; tt += 64 * kWinWaves) {
+    uint4 k[NP][KS];
+    load_tile<M>(W, s_tab, tt, n_tok, lane, k);
+    tile(k, tt);
   }
   __syncthreads();   // every wavefront is done with Q: its bytes now take the per-wavefront pairs
-  // merge the four lanes that share a query row, then the wavefronts, then write the chunk's pair
+  // merge the lanes that share a query row (if not done yet), then the wavefronts, then write
+  // the chunk's pair
   for (int ct = 0; ct < NT; ++ct) {
     float2 st = my_st[ct * PPT];
     st.x *= A.scale_log2;   // from here on maxima are in scaled log2 units
 #pragma unroll
-    for (int msk = 16; msk <= (kRowMerged ? 0 : 32); msk <<= 1) {
+    for (int msk = M; msk < (kRowMerged ? 0 : 64); msk <<= 1) {
       const float om = __shfl_xor(st.x, msk), ol = __shfl_xor(st.y, msk);
       const float nm = fmaxf(st.x, om);
       if (nm > -INFINITY) st.y = st.y * __builtin_amdgcn_exp2f(st.x - nm) + ol * __builtin_amdgcn_exp2f(om - nm);
       st.x = nm;
     }
-    if (lane < 16) {
-      s_ml[((wv * NT + ct) * 16 + lane) * 2 + 0] = st.x;
-      s_ml[((wv * NT + ct) * 16 + lane) * 2 + 1] = st.y;
+    if (lane < M) {
+      s_ml[((wv * NT + ct) * M + lane) * 2 + 0] = st.x;
+      s_ml[((wv * NT + ct) * M + lane) * 2 + 1] = st.y;
     }
   }
   __syncthreads();
-  const size_t pslot = (size_t)it.pbase + (size_t)(t0 / A.T);
-  for (int rho = tid; rho < NT * 16; rho += kWinThreads) {
+  for (int rho = tid; rho < ROWS; rho += kWinThreads) {
     float mm = -INFINITY, ll = 0.0f;
     for (int ww = 0; ww < kWinWaves; ++ww) {
-      const float om = s_ml[((ww * NT * 16) + rho) * 2], ol = s_ml[((ww * NT * 16) + rho) * 2 + 1];
+      const float om = s_ml[((ww * ROWS) + rho) * 2], ol = s_ml[((ww * ROWS) + rho) * 2 + 1];
       const float nm = fmaxf(mm, om);
       if (nm > -INFINITY) ll = ll * __builtin_amdgcn_exp2f(mm - nm) + ol * __builtin_amdgcn_exp2f(om - nm);
       mm = nm;
     }
-    W.part[(pslot * NT * 16 + rho) * 2 + 0] = mm;
-    W.part[(pslot * NT * 16 + rho) * 2 + 1] = ll;
+    W.part[(pslot * ROWS + rho) * 2 + 0] = mm;
+    W.part[(pslot * ROWS + rho) * 2 + 1] = ll;
   }
 }
 
@@ -228,9 +290,11 @@ __global__ void __launch_bounds__(256) window_rows_kernel(WindowArgs W, int rows
   if ((int)blockIdx.x >= total_items || total_items > A.cap) return;
   const DecodeItem it = A.items[blockIdx.x];
   if (it.t0 != 0 || (unsigned)it.g >= (unsigned)A.D.G || it.nch <= 0 || it.pbase < 0 || it.pbase + it.nch > A.cap) return;
+  const int seen = last_key(W, A.ctx[it.g], 0);
+  const int nch = seen < 0 ? 0 : min(it.nch, seen / A.T + 1);   // chunks that pass 1 worked on
   for (int rho = threadIdx.x; rho < rows_pad; rho += 256) {
     float mm = -INFINITY, ll = 0.0f;
-    for (int cc = 0; cc < it.nch; ++cc) {
+    for (int cc = 0; cc < nch; ++cc) {
       const float2 ml = *(const float2*)(W.part + (((size_t)it.pbase + cc) * rows_pad + rho) * 2);
       const float nm = fmaxf(mm, ml.x);
       if (nm > -INFINITY) ll = ll * __builtin_amdgcn_exp2f(mm - nm) + ml.y * __builtin_amdgcn_exp2f(ml.x - nm);
@@ -241,8 +305,10 @@ __global__ void __launch_bounds__(256) window_rows_kernel(WindowArgs W, int rows
 }
 
 // Pass 2: raw[j] = sum over query rows of p^2 (or p), p normalised with the head's max and sum.
-template <int NT, bool L2>
+template <int M, int NT, bool L2>
 __global__ void __launch_bounds__(kWinThreads) window_sum_kernel(WindowArgs W) {
+  typedef Mma<M> MM;
+  constexpr int KS = kSlices<M>, NP = kProducts<M>, ROWS = NT * M;
   const DecodeArgs& A = W.A;
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   const int total_items = A.header[HW_TOTAL_ITEMS];
@@ -254,71 +320,74 @@ __global__ void __launch_bounds__(kWinThreads) window_sum_kernel(WindowArgs W) {
       it.pbase + nch > A.cap)
     return;
   extern __shared__ __align__(16) char smem_raw[];
-  uint4* s_q = (uint4*)smem_raw;                        // [NT * 4 * 64]
-  float* s_ml = (float*)(s_q + NT * 4 * 64);            // [NT * 16]: max + log2(sum) per query row (inf: the row adds nothing)
-  int* s_tab = (int*)(s_ml + NT * 16);                  // [T / b + 1]
+  uint4* s_q = (uint4*)smem_raw;                        // [NT * KS * 64]
+  float* s_ml = (float*)(s_q + NT * KS * 64);           // [ROWS]: max + log2(sum) per query row (inf: the row adds nothing)
+  int* s_tab = (int*)(s_ml + ROWS);                     // [T / b + 1]
   const int b = A.D.b, lb = A.log2b;
   const int C = A.ctx[g];
+  if (t0 > last_key(W, C, W.exclude)) return;   // the chunk gets nothing
   {
     const int nblk = (n_tok + b - 1) >> lb;
     const int32_t* row = A.table + (size_t)g * A.D.maxb + (t0 >> lb);
     for (int i = tid; i < nblk; i += kWinThreads) s_tab[i] = row[i];
   }
-  stage_queries<NT>(W, g, s_q);
-  for (int rho = tid; rho < NT * 16; rho += kWinThreads) s_ml[rho] = W.part[((size_t)it.pbase * NT * 16 + rho) * 2];
-  __syncthreads();
   const int first_free = W.first_pos >= 0 ? W.first_pos : C - W.w;
-  const int free_lim = min(first_free, C - 1) - W.exclude;   // keys up to here count for every query
-  const bool dead = t0 > min(first_free + W.w - 1, C - 1) - W.exclude;  // the chunk gets nothing
-  if (dead) {
-    for (int t = tid; t < n_tok; t += kWinThreads)
-      if (t0 + t < C) W.raw[((size_t)s_tab[t >> lb] << lb) + (t & (b - 1))] = 0.0f;
-    return;
-  }
-  for (int tt = wv * 64; tt < n_tok; tt += 64 * kWinWaves) {
-    uint4 k[4][4];
-    load_tile(W, s_tab, tt, n_tok, lane, k);
-    float tok[16];
+  const int free_lim = min(first_free - W.exclude, C - 1);   // keys up to here count for every query
+  stage_queries<M, NT>(W, g, s_q);
+  for (int rho = tid; rho < ROWS; rho += kWinThreads) s_ml[rho] = W.part[((size_t)it.pbase * ROWS + rho) * 2];
+  __syncthreads();
+  auto tile = [&](uint4 (&k)[NP][KS], int tt) {
+    float tok[M];   // [product][element]
 #pragma unroll
-    for (int e = 0; e < 16; ++e) tok[e] = 0.0f;
+    for (int e = 0; e < M; ++e) tok[e] = 0.0f;
     auto column_tiles = [&](auto masked_c) {
       constexpr bool kMasked = decltype(masked_c)::value;
 #pragma unroll 1
       for (int ct = 0; ct < NT; ++ct) {
-        uint4 q[4];
+        uint4 q[KS];
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) q[kk] = s_q[(ct * 4 + kk) * 64 + lane];
-        const int rho = ct * 16 + (lane & 15);
+        for (int sl = 0; sl < KS; ++sl) q[sl] = s_q[(ct * KS + sl) * 64 + lane];
+        const int rho = ct * M + (lane & (M - 1));
         int last_vis = 0;
-        if constexpr (kMasked) last_vis = min(first_free + rho / A.D.r, C - 1) - W.exclude;
+        if constexpr (kMasked) last_vis = min(first_free + rho / A.D.r - W.exclude, C - 1);   // seen, and far enough behind
         const float c_row = s_ml[rho];
+        typename MM::Acc acc[NP];
 #pragma unroll
-        for (int tg = 0; tg < 4; ++tg) {
-          f32x4_t acc = {0.0f, 0.0f, 0.0f, 0.0f};
+        for (int pr = 0; pr < NP; ++pr)
 #pragma unroll
-          for (int kk = 0; kk < 4; ++kk) acc = mfma16(k[tg][kk], q[kk], acc);
+          for (int i = 0; i < MM::NV; ++i) acc[pr][i] = 0.0f;
 #pragma unroll
-          for (int v = 0; v < 4; ++v) {
-            float p = __builtin_amdgcn_exp2f(fmaf(acc[v], A.scale_log2, -c_row));
+        for (int sl = 0; sl < KS; ++sl)
+#pragma unroll
+          for (int pr = 0; pr < NP; ++pr) acc[pr] = MM::run(k[pr][sl], q[sl], acc[pr]);
+#pragma unroll
+        for (int pr = 0; pr < NP; ++pr)
+#pragma unroll
+          for (int i = 0; i < MM::NV; ++i) {
+            float p = __builtin_amdgcn_exp2f(fmaf(acc[pr][i], A.scale_log2, -c_row));
             if constexpr (kMasked) {
-              const int j = t0 + tt + tg * 16 + 4 * (lane >> 4) + v;
+              const int j = t0 + tt + pr * M + MM::token(i, lane);
               if (j > last_vis) p = 0.0f;
             }
-            tok[tg * 4 + v] = L2 ? fmaf(p, p, tok[tg * 4 + v]) : tok[tg * 4 + v] + p;
+            tok[pr * MM::NV + i] = L2 ? fmaf(p, p, tok[pr * MM::NV + i]) : tok[pr * MM::NV + i] + p;
           }
-        }
       }
     };
     if (t0 + tt + 63 > free_lim) column_tiles(std::true_type{});
     else column_tiles(std::false_type{});
-    // sum over the 16 lanes of a row group: lane % 16 == e ends up with value e
-    Butterfly<16, 8>::run(tok, lane);
-    const int e = lane & 15;
-    const int t = tt + (e >> 2) * 16 + 4 * (lane >> 4) + (e & 3);
+    // sum over the M lanes (query rows) of a row group: lane % M == e ends up with value e
+    Butterfly<M, M / 2>::run(tok, lane);
+    const int e = lane & (M - 1);
+    const int t = tt + (e / MM::NV) * M + MM::token(e % MM::NV, lane);
     if (t < n_tok && t0 + t < C) {
       const size_t slot = ((size_t)s_tab[t >> lb] << lb) + (t & (b - 1));
       W.raw[slot] = tok[0];
     }
+  };
+  for (int tt = wv * 64; tt < n_tok; tt += 64 * kWinWaves) {
+    uint4 k[NP][KS];
+    load_tile<M>(W, s_tab, tt, n_tok, lane, k);
+    tile(k, tt);
   }
 }
 
@@ -334,14 +403,17 @@ __global__ void __launch_bounds__(256) window_pool_kernel(WindowArgs W) {
   const int g = sel_to_g(A.D, A.l0, A.nl, gi);
   const int C = A.ctx[g];
   const int j0 = blockIdx.y * kPoolTile;
-  if (j0 >= C) return;
-  const int j1 = min(C, j0 + kPoolTile);
+  // positions behind the last chunk that pass 2 worked on get nothing (and hold nothing to read)
+  const int seen = last_key(W, C, W.exclude);
+  const int live = seen < 0 ? 0 : min(C, (seen / A.T + 1) * A.T);
+  if (j0 >= live) return;
+  const int j1 = min(live, j0 + kPoolTile);
   const int b = A.D.b, lb = A.log2b;
   const int32_t* row = A.table + (size_t)g * A.D.maxb;
   const int P = W.first_pos >= 0 ? 0 : max(0, C - W.w), half = W.pool / 2;
   __shared__ float s_raw[kPoolTile + 2 * kPoolHalo];
   const bool staged = half <= kPoolHalo;
-  const int lo0 = staged ? max(0, j0 - half) : j0, hi0 = staged ? min(C, j1 + half) : j1;
+  const int lo0 = staged ? max(0, j0 - half) : j0, hi0 = staged ? min(live, j1 + half) : j1;
   for (int j = lo0 + threadIdx.x; j < hi0; j += 256)
     s_raw[j - lo0] = W.raw[((size_t)row[j >> lb] << lb) + (j & (b - 1))];
   __syncthreads();
@@ -360,28 +432,29 @@ __global__ void __launch_bounds__(256) window_pool_kernel(WindowArgs W) {
   }
 }
 
-template <int NT>
+template <int M, int NT>
 static int launch_window(const WindowArgs& W, int grid, hipStream_t s) {
   // pass 1: Q (later the per-wavefront pairs), running pairs per column tile, block ids;
   // pass 2: Q, one float per query row, block ids.  Three and four workgroups per CU at 128 rows,
   // two and two at 256.
+  constexpr size_t q_bytes = (size_t)NT * M * 256, rows = (size_t)NT * M;
   const size_t tab = ((size_t)kWinChunk / W.A.D.b + 1) * 4;
-  const size_t lds = (size_t)NT * 4 * 64 * 16 + (size_t)kWinWaves * NT * window_pairs_per_tile(NT) * 8 + tab;
-  const size_t lds2 = (size_t)NT * 4 * 64 * 16 + (size_t)NT * 16 * 4 + tab;
-  static_assert((size_t)kWinWaves * NT * 16 * 2 * 4 <= (size_t)NT * 4 * 64 * 16, "pairs fit where Q was");
+  const size_t lds = q_bytes + (size_t)kWinWaves * NT * window_pairs_per_tile(M, NT) * 8 + tab;
+  const size_t lds2 = q_bytes + rows * 4 + tab;
+  static_assert((size_t)kWinWaves * rows * 2 * 4 <= q_bytes, "pairs fit where Q was");
   static size_t allowed = 0;   // above the default cap a kernel must be told how much it may take
   if (lds > 64 * 1024 && lds > allowed) {   // (lds >= lds2; the block-id array grows as blocks shrink)
-    KVC_HIP(hipFuncSetAttribute((const void*)window_stats_kernel<NT>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    KVC_HIP(hipFuncSetAttribute((const void*)window_sum_kernel<NT, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    KVC_HIP(hipFuncSetAttribute((const void*)window_sum_kernel<NT, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    KVC_HIP(hipFuncSetAttribute((const void*)window_stats_kernel<M, NT>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    KVC_HIP(hipFuncSetAttribute((const void*)window_sum_kernel<M, NT, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    KVC_HIP(hipFuncSetAttribute((const void*)window_sum_kernel<M, NT, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     allowed = lds;
   }
-  hipLaunchKernelGGL(window_stats_kernel<NT>, dim3(grid), dim3(kWinThreads), lds, s, W);
+  hipLaunchKernelGGL((window_stats_kernel<M, NT>), dim3(grid), dim3(kWinThreads), lds, s, W);
   KVC_LAUNCH_CHECK();
-  hipLaunchKernelGGL(window_rows_kernel, dim3(grid), dim3(256), 0, s, W, NT * 16);
+  hipLaunchKernelGGL(window_rows_kernel, dim3(grid), dim3(256), 0, s, W, (int)rows);
   KVC_LAUNCH_CHECK();
-  if (W.A.D.mode == KVC_L2) hipLaunchKernelGGL((window_sum_kernel<NT, true>), dim3(grid), dim3(kWinThreads), lds2, s, W);
-  else hipLaunchKernelGGL((window_sum_kernel<NT, false>), dim3(grid), dim3(kWinThreads), lds2, s, W);
+  if (W.A.D.mode == KVC_L2) hipLaunchKernelGGL((window_sum_kernel<M, NT, true>), dim3(grid), dim3(kWinThreads), lds2, s, W);
+  else hipLaunchKernelGGL((window_sum_kernel<M, NT, false>), dim3(grid), dim3(kWinThreads), lds2, s, W);
   KVC_LAUNCH_CHECK();
   return KVC_OK;
 }
@@ -406,8 +479,8 @@ static int window_common(const kvc_config* cfg, const kvc_state* st, const void*
   const int rows = w * D.r;
   // (w <= 64: a chunk's pairs, 8 bytes per padded query row, live in the decode's slot of r * d floats)
   if (rows > 256 || w > 64) return KVC_ERR_UNSUPPORTED;
-  const int nt = rows <= 32 ? 2 : rows <= 64 ? 4 : rows <= 128 ? 8 : 16;
-  if ((size_t)nt * 16 * 8 > (size_t)D.r * D.d * 4) return KVC_ERR_UNSUPPORTED;
+  const int rows_pad = rows <= 32 ? 32 : rows <= 64 ? 64 : rows <= 128 ? 128 : 256;
+  if ((size_t)rows_pad * 8 > (size_t)D.r * D.d * 4) return KVC_ERR_UNSUPPORTED;
   Workspace Wk = carve(D, ws);
   hipStream_t s = (hipStream_t)stream;
   WindowArgs W;
@@ -421,6 +494,7 @@ static int window_common(const kvc_config* cfg, const kvc_state* st, const void*
   A.log2b = 0;
   while ((1 << A.log2b) < D.b) ++A.log2b;
   A.all_partials = 1;
+  A.rotate_chunks = 1;
   A.short_class = 16;  // no separate launch for short items here
   A.Ts = 0;
   A.cap = (int)(max_items_of(D) < 0x7fffffffull ? max_items_of(D) : 0x7fffffffull);
@@ -444,11 +518,11 @@ static int window_common(const kvc_config* cfg, const kvc_state* st, const void*
   const size_t bound_row = (size_t)A.gsel * (((size_t)D.maxb * D.b + A.T - 1) / A.T);
   const size_t grid = bound_pool < bound_row ? bound_pool : bound_row;
   if (grid > 0x7fffffffull) return KVC_ERR_UNSUPPORTED;
-  switch (nt) {
-    case 2: rc = launch_window<2>(W, (int)grid, s); break;
-    case 4: rc = launch_window<4>(W, (int)grid, s); break;
-    case 8: rc = launch_window<8>(W, (int)grid, s); break;
-    default: rc = launch_window<16>(W, (int)grid, s); break;
+  switch (rows_pad) {
+    case 32: rc = launch_window<16, 2>(W, (int)grid, s); break;
+    case 64: rc = launch_window<16, 4>(W, (int)grid, s); break;
+    case 128: rc = launch_window<16, 8>(W, (int)grid, s); break;
+    default: rc = launch_window<32, 8>(W, (int)grid, s); break;
   }
   if (rc != KVC_OK) return rc;
   const int pool_tiles = (int)(((size_t)D.maxb * D.b + kPoolTile - 1) / kPoolTile);

@@ -30,6 +30,7 @@ struct DecodeArgs {
   int log2b;              // block size is a power of two on the tiled path
   int cap;                // item records and partial-result slots the workspace holds
   int all_partials;       // give every head a partial-result slot range, not only split heads
+  int rotate_chunks;      // a head's full chunks take their places rotated by the head's index (see decode_items_kernel)
   int short_class, Ts;    // size classes from short_class up (at most Ts tokens) are "short" items; 16 = none
   DecodeItem* items;
   int32_t* slot_item;     // work item of partial-result slot p (heads of more than one chunk): what the combine kernel runs over
@@ -76,7 +77,11 @@ static __global__ void __launch_bounds__(256) decode_count_kernel(DecodeArgs A) 
 }
 
 // Pass 2: every head instance claims its places and writes its items; a head that holds no
-// KV gets its zero output rows here.  Places are claimed per workgroup (one global atomic
+// KV gets its zero output rows here.  Workgroup x of a launch runs on XCD x % 8, so with
+// rotate_chunks a head's chunks are dealt to the XCDs starting from a different one for every
+// head: where only the first few chunks of every head have work (a block of queries early in a
+// prompt) and heads hold a multiple of eight chunks, that work would otherwise all land on the
+// same few XCDs.  Places are claimed per workgroup (one global atomic
 // per class) and handed out inside it through LDS, so the global counters see few updates.
 static __global__ void __launch_bounds__(256) decode_items_kernel(DecodeArgs A) {
   __shared__ int base[16], want[17], got[17];
@@ -135,8 +140,9 @@ static __global__ void __launch_bounds__(256) decode_items_kernel(DecodeArgs A) 
     if (at < 0 || at + nfull > A.cap) return;
     for (int c = 0; c < nfull; ++c) {
       DecodeItem it = {g, c * T, T, nch, pbase, {0, 0, 0}};
-      A.items[at + c] = it;
-      if (slotted) A.slot_item[pbase + c] = at + c;
+      const int place = at + (A.rotate_chunks ? (c + g) % nfull : c);
+      A.items[place] = it;
+      if (slotted) A.slot_item[pbase + c] = place;
     }
   }
   if (rem) {
@@ -201,8 +207,9 @@ static __global__ void __launch_bounds__(1024) decode_worklist_small_kernel(Deco
     if (at < 0 || at + nfull > A.cap) return;
     for (int c = 0; c < nfull; ++c) {
       DecodeItem it = {g, c * T, T, nch, pbase, {0, 0, 0}};
-      A.items[at + c] = it;
-      if (slotted) A.slot_item[pbase + c] = at + c;
+      const int place = at + (A.rotate_chunks ? (c + g) % nfull : c);
+      A.items[place] = it;
+      if (slotted) A.slot_item[pbase + c] = place;
     }
   }
   if (rem) {

@@ -97,6 +97,47 @@ def test_window_metric_on_random_shapes(seed0):
         np.testing.assert_allclose(m[real], st.metric[real], rtol=0, atol=TOL)
 
 
+@pytest.mark.parametrize("seed0", [41, 42])
+def test_query_block_metric_on_random_shapes(seed0):
+    """Blocks of queries at random positions of ragged heads: in front of, inside and past the end
+    of a head, chunks with and without visible keys, heads of a multiple of eight chunks, excluded
+    windows longer than the block; several blocks accumulate into one metric."""
+    rng = np.random.default_rng(seed0)
+    for case in range(24):
+        r = int(rng.choice([1, 2, 4, 8]))
+        w = int(rng.integers(1, min(64, 256 // r) + 1))
+        b = int(rng.choice([16, 32, 64]))
+        S, Lyr, Hk = int(rng.integers(1, 3)), int(rng.integers(1, 3)), int(rng.integers(1, 4))
+        L = int(rng.choice([int(rng.integers(64, 3000)), 2048, 8192]))
+        rho = float(rng.choice([1.0, rng.uniform(1.0, 3.0)]))
+        mode = int(rng.choice([B.KVC_L2, B.KVC_L1]))
+        excl = int(rng.choice([0, 1, 10, w + 5]))
+        say("random query blocks", dict(seed0=seed0, case=case, r=r, w=w, b=b, S=S, Lyr=Lyr, Hk=Hk, L=L,
+                                        rho=round(rho, 2), mode=mode, excl=excl))
+        shape, ctx, seed = W.small_mixed(7000 + seed0 * 1000 + case, S=S, Lyr=Lyr, Hk=Hk, r=r, d=128, b=b, L=L,
+                                         rho=rho, kv_dtype="bf16")
+        if rng.random() < 0.3:
+            ctx[int(rng.integers(0, len(ctx)))] = 0
+        cache = W.make_cache(shape, ctx, seed, placement=str(rng.choice(["fresh", "fragmented"])),
+                             init_metric="prefill")
+        st = oracle_state(cache)
+        sess = session(cache, mode)
+        g = torch.Generator().manual_seed(seed + 5)
+        starts = [0, int(rng.integers(0, L)), max(0, L - w), int(rng.integers(0, L))]
+        for start in starts[: 2 if L > 4096 else 4]:
+            qb = torch.randn((S, Lyr, Hk * r, w, 128), generator=g).to(torch.bfloat16)
+            O.query_block_metric(st, qb.double().numpy(), w, start, excl, "L2" if mode == B.KVC_L2 else "L1")
+            sess.query_block_metric(qb.to(sess.device), w, start, excl)
+        torch.cuda.synchronize()
+        m = sess.cache.metric.cpu().numpy().astype(np.float64)
+        real = np.zeros(m.shape, dtype=bool)
+        for gi in range(st.G):
+            n, o = O.slots_of(st, gi)
+            real[n, o] = True
+        np.testing.assert_allclose(m[real], st.metric[real], rtol=0, atol=TOL)
+        np.testing.assert_array_equal(m[~real], cache.metric.numpy().astype(np.float64)[~real])
+
+
 @pytest.mark.parametrize("seed0", [31, 32])
 def test_allocator_operations_in_random_order(seed0):
     """Random sequences of alloc / free / append / preempt / prefill / count, some of them requests
