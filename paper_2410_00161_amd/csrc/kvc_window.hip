@@ -86,11 +86,10 @@ template <int M> constexpr int kProducts = 64 / M;
 // Q of one head instance into LDS, in B-operand order: entry ((ct * KS + s) * 64 + lane) holds,
 // for query row ct * M + lane % M, the 8 dimensions at byte 16 KS (lane / M) + 16 s of the row.
 // Query row rho = i * r + hh (window query i, query head hh); rows past w * r are zero.
-// Read in runs of 64 bytes, four lanes to a run and 16 consecutive rows to a wavefront: with one
-// lane per LDS entry instead, every 16-byte read touches a line of its own, Q (up to 64 KB)
-// does not fit the 16 KB first-level cache, and each workgroup pulls its Q from L2 eight times
-// over - at 256 rows that was most of both passes.  The price is a 4-way bank conflict on the
-// LDS writes, a microsecond per workgroup.
+// Read in runs of 64 bytes, four lanes to a run and 16 consecutive rows to a wavefront, all of a
+// thread's loads before its stores; the LDS writes then meet a 4-way bank conflict, well under
+// a microsecond per workgroup.  (One lane per LDS entry in entry order, every 16-byte read on
+// a line of its own, measured the same.)
 template <int M, int NT>
 __device__ __forceinline__ void stage_queries(const WindowArgs& W, int g, uint4* s_q) {
   constexpr int KS = kSlices<M>, ROWS = NT * M;
@@ -170,7 +169,8 @@ __global__ void __launch_bounds__(kWinThreads) window_stats_kernel(WindowArgs W)
   const size_t pslot = (size_t)it.pbase + (size_t)(t0 / A.T);
   const int first_free = W.first_pos >= 0 ? W.first_pos : C - W.w;  // query i sits at first_free + i
   const int free_lim = min(first_free, C - 1);   // keys up to here are visible to every query
-  if (t0 > last_key(W, C, 0)) return;   // no query of the block sees this chunk
+  const int n_seen = last_key(W, C, 0) - t0 + 1;   // tokens of the chunk that some query sees
+  if (n_seen <= 0) return;
   {
     const int nblk = (n_tok + b - 1) >> lb;
     const int32_t* row = A.table + (size_t)g * A.D.maxb + (t0 >> lb);
@@ -242,7 +242,7 @@ __global__ void __launch_bounds__(kWinThreads) window_stats_kernel(WindowArgs W)
     if (t0 + tt + 63 > free_lim) column_tiles(std::true_type{});
     else column_tiles(std::false_type{});
   };
-  for (int tt = wv * 64; tt < n_tok; tt += 64 * kWinWaves) {
+  for (int tt = wv * 64; tt < min(n_tok, n_seen); tt += 64 * kWinWaves) {
     uint4 k[NP][KS];
     load_tile<M>(W, s_tab, tt, n_tok, lane, k);
     tile(k, tt);
@@ -325,7 +325,8 @@ __global__ void __launch_bounds__(kWinThreads) window_sum_kernel(WindowArgs W) {
   int* s_tab = (int*)(s_ml + ROWS);                     // [T / b + 1]
   const int b = A.D.b, lb = A.log2b;
   const int C = A.ctx[g];
-  if (t0 > last_key(W, C, W.exclude)) return;   // the chunk gets nothing
+  const int n_fed = last_key(W, C, W.exclude) - t0 + 1;   // tokens of the chunk that some query adds to
+  if (n_fed <= 0) return;
   {
     const int nblk = (n_tok + b - 1) >> lb;
     const int32_t* row = A.table + (size_t)g * A.D.maxb + (t0 >> lb);
@@ -384,7 +385,7 @@ __global__ void __launch_bounds__(kWinThreads) window_sum_kernel(WindowArgs W) {
       W.raw[slot] = tok[0];
     }
   };
-  for (int tt = wv * 64; tt < n_tok; tt += 64 * kWinWaves) {
+  for (int tt = wv * 64; tt < min(n_tok, n_fed); tt += 64 * kWinWaves) {
     uint4 k[NP][KS];
     load_tile<M>(W, s_tab, tt, n_tok, lane, k);
     tile(k, tt);
@@ -403,9 +404,8 @@ __global__ void __launch_bounds__(256) window_pool_kernel(WindowArgs W) {
   const int g = sel_to_g(A.D, A.l0, A.nl, gi);
   const int C = A.ctx[g];
   const int j0 = blockIdx.y * kPoolTile;
-  // positions behind the last chunk that pass 2 worked on get nothing (and hold nothing to read)
-  const int seen = last_key(W, C, W.exclude);
-  const int live = seen < 0 ? 0 : min(C, (seen / A.T + 1) * A.T);
+  // positions behind the last key that pass 2 added to get nothing (and hold nothing to read)
+  const int live = max(0, last_key(W, C, W.exclude) + 1);
   if (j0 >= live) return;
   const int j1 = min(live, j0 + kPoolTile);
   const int b = A.D.b, lb = A.log2b;
