@@ -112,6 +112,13 @@ int kvc_workspace_reset(const kvc_config* cfg, void* ws, void* stream);
  * Synchronises the stream.                                                     */
 int kvc_poll_status(const kvc_config* cfg, void* ws, void* stream, int* status);
 
+/* Checks what every other call takes for granted of a state (a caller that fills the tables
+ * itself can ask before it trusts them; the library's own calls keep all of it): every row of
+ * block_table is a run of ids in [0, N) followed by -1s; 0 <= ctx_len[g] <= (ids in row g) * b;
+ * no block is held twice; free_map is 0 for every held block.  Reads only.  KVC_OK, or
+ * KVC_ERR_ARG when any of it fails.  Synchronises unless KVC_ASYNC.                  */
+int kvc_check_state(const kvc_config* cfg, const kvc_state* st, void* ws, void* stream, int flags);
+
 /* On-device block allocator ("Block Layout and Parallel Allocation": a flat
  * tensor of length N tracks allocation; counting and allocation run in
  * parallel over all sequences, layers and heads).

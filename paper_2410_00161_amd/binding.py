@@ -24,7 +24,7 @@ KVC_ASYNC = 1
 
 EXPORTS = [
     "kvc_workspace_bytes", "kvc_validate", "kvc_status_string", "kvc_workspace_reset",
-    "kvc_poll_status", "kvc_block_alloc", "kvc_block_free", "kvc_append", "kvc_paged_decode",
+    "kvc_poll_status", "kvc_check_state", "kvc_block_alloc", "kvc_block_free", "kvc_append", "kvc_paged_decode",
     "kvc_metric_reduce", "kvc_evict_select", "kvc_compact", "kvc_set_decode_chunk",
     "kvc_get_decode_chunk", "kvc_get_decode_short", "kvc_evict_rank_select", "kvc_compact_rank", "kvc_window_metric", "kvc_query_block_metric", "kvc_count_blocks", "kvc_prefill_alloc", "kvc_preempt", "kvc_compression_batch",
     "kvc_profile_begin", "kvc_profile_enable", "kvc_profile_collect", "kvc_stream_read_probe", "kvc_stream_rw_probe",
@@ -81,6 +81,7 @@ def lib() -> C.CDLL:
         L.kvc_count_blocks.argtypes = [cfgp, stp, I, I, P, P, P, P]
         L.kvc_prefill_alloc.argtypes = [cfgp, stp, P, P, P, I]
         L.kvc_preempt.argtypes = [cfgp, stp, P, C.POINTER(C.c_int64), P, P, I]
+        L.kvc_check_state.argtypes = [cfgp, stp, P, P, I]
         L.kvc_compression_batch.argtypes = [cfgp, stp, P, P, C.c_int64, P, P, P, P]
         L.kvc_window_metric.argtypes = [cfgp, stp, P, I, I, I, I, I, P, P]
         L.kvc_query_block_metric.argtypes = [cfgp, stp, P, I, I, I, I, I, P, P]
@@ -172,6 +173,10 @@ def kvc_poll_status(cfg, ws, stream=None) -> int:
     out = C.c_int(0)
     _check(lib().kvc_poll_status(C.byref(cfg), _ptr(ws), _stream(stream), C.byref(out)), "kvc_poll_status")
     return out.value
+
+
+def kvc_check_state(cfg, st, ws, stream=None, flags=0):
+    _check(lib().kvc_check_state(C.byref(cfg), C.byref(st), _ptr(ws), _stream(stream), flags), "kvc_check_state")
 
 
 def kvc_block_alloc(cfg, st, n_new, ws, stream=None, flags=0):

@@ -425,11 +425,66 @@ __global__ void __launch_bounds__(256) preempt_kernel(Dims D, int32_t* __restric
   if ((threadIdx.x & 63) == 0 && n) atomicAdd(&header[HW_FREED], n);
 }
 
+// State check.  One wavefront per head instance walks its table row: ids in [0, N) as a prefix,
+// -1 after it, the length within what the prefix holds; every held block counted once in
+// `owner` (zeroed before the launch) and not marked free.
+__global__ void __launch_bounds__(256) check_state_kernel(Dims D, const int32_t* __restrict__ table,
+                                                          const int32_t* __restrict__ ctx,
+                                                          const uint8_t* __restrict__ free_map,
+                                                          int32_t* __restrict__ owner,
+                                                          int32_t* __restrict__ header) {
+  const int g = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (g >= D.G) return;
+  const int lane = threadIdx.x & 63;
+  const int32_t* row = table + (size_t)g * D.maxb;
+  bool bad = false;
+  int held = 0;
+  bool ended = false;   // a -1 has been seen (the same in every lane)
+  for (int base = 0; base < D.maxb; base += 64) {
+    const int u = base + lane;
+    const int id = u < D.maxb ? row[u] : -1;
+    const bool holds = id != -1;
+    if (holds) {
+      if (id < 0 || id >= D.N) bad = true;
+      else {
+        if (atomicAdd(&owner[id], 1) != 0) bad = true;   // held twice
+        if (free_map[id] != 0) bad = true;               // held and marked free
+      }
+    }
+    const unsigned long long m = __ballot(holds);
+    const int run = m == ~0ull ? 64 : __ffsll((long long)~m) - 1;   // ids at the front of these 64 cells
+    if (ended ? m != 0 : (run < 64 && (m >> run) != 0)) bad = true;   // an id behind a -1
+    if (!ended) held += run;
+    if (run < 64) ended = true;
+  }
+  const int C = ctx[g];
+  if (C < 0 || (long long)C > (long long)held * D.b) bad = true;
+  if (__any(bad) && lane == 0) atomicOr(&header[HW_SCRATCH0], EB_ARG);
+}
+
 }  // namespace kvc
 
 using namespace kvc;
 
 extern "C" {
+
+int kvc_check_state(const kvc_config* cfg, const kvc_state* st, void* ws, void* stream, int flags) {
+  int rc = validate(cfg, st);
+  if (rc != KVC_OK) return rc;
+  if (!ws || ((uintptr_t)ws & 255)) return KVC_ERR_ARG;
+  Dims D = dims_of(cfg);
+  Workspace W = carve(D, ws);
+  hipStream_t s = (hipStream_t)stream;
+  int32_t* owner = (int32_t*)W.stash;   // [N] fits where the decode keeps N * b * r floats
+  hipLaunchKernelGGL(zero_words_kernel, dim3((D.N + 255) / 256), dim3(256), 0, s, owner, D.N);
+  KVC_LAUNCH_CHECK();
+  hipLaunchKernelGGL(check_state_kernel, dim3((D.G + 3) / 4), dim3(256), 0, s, D, st->block_table, st->ctx_len,
+                     st->free_map, owner, W.header);
+  KVC_LAUNCH_CHECK();
+  hipLaunchKernelGGL(resolve_kernel, dim3(1), dim3(64), 0, s, W.header, 0);
+  KVC_LAUNCH_CHECK();
+  return (flags & KVC_ASYNC) ? KVC_OK : finish_sync(W, s);
+}
 
 int kvc_block_alloc(const kvc_config* cfg, const kvc_state* st, const int32_t* n_new, void* ws,
                     void* stream, int flags) {

@@ -41,6 +41,10 @@ class KvcSession:
         return B.kvc_block_free(self.cfg, self.st, n_drop.to(self.device, torch.int32).contiguous(),
                                 self.ws, flags=flags)
 
+    def check_state(self, flags=0):
+        """Raises KvcError(KVC_ERR_ARG) when the tables, lengths and free map contradict each other."""
+        B.kvc_check_state(self.cfg, self.st, self.ws, flags=flags)
+
     def append(self, k_new, v_new, new_pos=None, layer_begin=0, layer_end=None, flags=0):
         layer_end = self.shape.num_layers if layer_end is None else layer_end
         B.kvc_append(self.cfg, self.st, k_new, v_new, new_pos, layer_begin, layer_end, self.ws,

@@ -113,6 +113,63 @@ def test_prefill_end_compression_from_an_observation_window():
     assert_state_equal(sess, st)
 
 
+def test_state_check_passes_what_the_library_leaves_and_names_what_is_broken():
+    """kvc_check_state after appends and a compression round of each kind (the library's own
+    calls keep a state consistent), then one planted inconsistency at a time: each is refused
+    with KVC_ERR_ARG, nothing is modified, and the repaired state passes again."""
+    say("state check")
+    shape, ctx, seed = W.small_mixed(97, S=2, Lyr=2, Hk=2, r=2, d=64, b=16, L=300, rho=2.0, kv_dtype="bf16")
+    ctx[1] = 0
+    cache = W.make_cache(shape, ctx, seed, placement="fragmented", init_metric="prefill")
+    st = oracle_state(cache)
+    sess = session(cache)
+    sess.check_state()
+    for step in range(3):
+        k, v = W.make_new_kv(shape, seed, step)
+        O.append(st, k.double().numpy(), v.double().numpy())
+        sess.append(k.to(sess.device), v.to(sess.device))
+        sess.paged_decode(W.make_query(shape, seed, step).to(sess.device))
+    sess.check_state()
+    for mode in ("block", "rank"):
+        evict_round(sess, st, 0.3, mode)
+        sess.check_state()
+    c = sess.cache
+    table, lens, fmap = c.block_table.view(shape.G, -1), c.ctx_len.view(-1), c.free_map
+    g = 3                                            # a head with several blocks
+    held = int((table[g] >= 0).sum())
+    assert held >= 3
+    free_id = int(torch.nonzero(fmap == 1)[0])
+    plants = {
+        "length past the blocks held": lambda: lens.__setitem__(g, held * shape.block_size + 1),
+        "negative length": lambda: lens.__setitem__(g, -1),
+        "block id past the pool": lambda: table.__setitem__((g, 1), shape.num_blocks),
+        "negative block id": lambda: table.__setitem__((g, 1), -7),
+        "a hole in the row": lambda: table.__setitem__((g, 0), -1),
+        "a block held by two heads": lambda: table.__setitem__((g, 1), int(table[g + 1, 0])),
+        "a held block marked free": lambda: fmap.__setitem__(int(table[g, 2]), 1),
+        "an id behind the end of the row": lambda: table.__setitem__((g, shape.max_blocks_per_head - 1), free_id),
+    }
+    for what, plant in plants.items():
+        keep = (table.clone(), lens.clone(), fmap.clone())
+        plant()
+        broken = (table.clone(), lens.clone(), fmap.clone())
+        with pytest.raises(B.KvcError) as e:
+            sess.check_state()
+        assert e.value.code == B.KVC_ERR_ARG, what
+        for now, was in zip((table, lens, fmap), broken):     # the check reads only
+            assert torch.equal(now, was), what
+        table.copy_(keep[0]); lens.copy_(keep[1]); fmap.copy_(keep[2])
+        sess.check_state()
+    assert_state_equal(sess, st)
+    # the asynchronous form leaves its verdict in the status word
+    lens[g] = -1
+    sess.check_state(flags=B.KVC_ASYNC)
+    assert B.kvc_poll_status(sess.cfg, sess.ws) == B.KVC_ERR_ARG
+    lens[g] = int(st.ctx_len.reshape(-1)[g])
+    B.kvc_workspace_reset(sess.cfg, sess.ws)
+    sess.check_state()
+
+
 def _round_matrix():
     cases, i = [], 0
     for b in (1, 2, 4, 8, 16, 32, 64):
