@@ -94,7 +94,7 @@ def main():
     ap.add_argument("--no-metric", action="store_true", help="diagnostic: decode without metric accumulation")
     ap.add_argument("--per-layer-steps", type=int, default=4,
                     help="extra untimed-region steps that call the decode once per layer (0 = skip)")
-    ap.add_argument("--all-queries-block", type=int, default=64, choices=[16, 32, 64],
+    ap.add_argument("--all-queries-block", type=int, default=1024, choices=[32, 64, 256, 1024],
                     help="queries per call when the prefill-end probe gathers the metric over all prompt queries")
     ap.add_argument("--window-probe", type=int, default=1,
                     help="also time the observation-window metric and a rank-block eviction to 8x on a "
@@ -324,7 +324,7 @@ def main():
         g4 = torch.Generator(device=dev).manual_seed(1004)
         qw = torch.randn((1, 32, 32, wq, 128), generator=g4, device=dev, dtype=torch.float32).to(torch.bfloat16)
         # the metric over ALL prompt queries (every query attends to the keys at least 10
-        # positions before it), gathered one block of 64 queries at a time; the same random
+        # positions before it), gathered one block of 1024 queries at a time; the same random
         # block of queries stands in for every block of the prompt
         wb, excl = args.all_queries_block, 10
         qb = torch.randn((1, 32, 32, wb, 128), generator=g4, device=dev, dtype=torch.float32).to(torch.bfloat16)
@@ -379,7 +379,7 @@ def main():
                        "rank_select_to_8x_ms": select_ms, "rank_compact_ms": compact_ms,
                        "kvs_after": kvs_after, "kvs_before": kvs4,
                        "all_queries_metric_ms": all_queries_ms, "all_queries_block": wb, "all_queries_exclude": excl,
-                       "all_queries_TFLOPs": 2 * 2 * (4 * 128) * shp.G * (Lp * (Lp + wb) / 2) / (all_queries_ms * 1e-3) / 1e12,
+                       "all_queries_TFLOPs": 2 * 2 * (4 * 128) * shp.G * (Lp * (Lp + min(wb, 64)) / 2) / (all_queries_ms * 1e-3) / 1e12,
                        "decode_steps_after": nd, "decode_ms_per_step_after": decode_ms,
                        "decode_GBps_after": (kvs_after + shp.G * nd / 2) * algorithmic_bytes_per_kv(shp) / (decode_ms * 1e-3) / 1e9}
         del s4, qw, q4, kv4

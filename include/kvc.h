@@ -290,7 +290,8 @@ int kvc_window_metric(const kvc_config* cfg, const kvc_state* st, const void* q_
  * adds p^2 (p with KVC_L1) to metric[slot of key j] only when j <= position - exclude.
  * Always accumulates; no pooling.  Calling it for consecutive blocks of a prompt's queries
  * builds M_full[j] = sum over i >= j + v and the group's heads of A_ij^2.  Shapes and errors as
- * kvc_window_metric.  Asynchronous.                                               */
+ * kvc_window_metric, except that w may be any length (the paper aggregates 1024 queries at a
+ * time): a longer block is worked off 64 queries, or 256 query rows, at a time.  Asynchronous. */
 int kvc_query_block_metric(const kvc_config* cfg, const kvc_state* st, const void* q_blk, int w,
                            int first_pos, int exclude, int layer_begin, int layer_end, void* ws,
                            void* stream);

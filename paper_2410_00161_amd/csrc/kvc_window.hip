@@ -38,7 +38,8 @@ constexpr int kWinWaves = 4;
 
 struct WindowArgs {
   DecodeArgs A;        // cache, tables, work list (A.T = kWinChunk, A.q = window queries)
-  int w, rows;         // window queries; query rows = w * r
+  int w, rows;         // queries this pass handles; query rows = w * r
+  int q_first, q_count; // they are queries q_first .. q_first + w - 1 of the q_count the caller's tensor holds per head
   int pool;            // max-pool size over the sequence
   int add;             // add to the metric instead of replacing it
   int first_pos;       // position of query 0, the same for every head; -1 = the head's C - w
@@ -95,8 +96,8 @@ __device__ __forceinline__ void stage_queries(const WindowArgs& W, int g, uint4*
   constexpr int KS = kSlices<M>, ROWS = NT * M;
   constexpr int PER = ROWS * 16 / kWinThreads;   // pieces per thread
   static_assert(PER * kWinThreads == ROWS * 16 && PER <= 16, "whole rounds of the workgroup");
-  const int r = W.A.D.r, w = W.w;
-  const char* qbase = W.A.q + (size_t)g * r * w * 256;  // [r][w][128] bf16
+  const int r = W.A.D.r, w = W.q_count;
+  const char* qbase = W.A.q + ((size_t)g * r * w + W.q_first) * 256;  // [r][q_count][128] bf16, from query q_first
   // all of a thread's loads first, then its stores: one trip to memory, not PER of them
   uint4 v[PER];
 #pragma unroll
@@ -476,11 +477,13 @@ static int window_common(const kvc_config* cfg, const kvc_state* st, const void*
   if (w <= 0 || pool <= 0 || (pool & 1) == 0 || exclude < 0) return KVC_ERR_ARG;
   // the matrix-core kernels cover bf16, d = 128, blocks of a multiple of 16 tokens, up to 256 query rows
   if (D.dtype != KVC_BF16 || D.d != 128 || D.b % 16 != 0 || 64 % D.b != 0) return KVC_ERR_UNSUPPORTED;
-  const int rows = w * D.r;
-  // (w <= 64: a chunk's pairs, 8 bytes per padded query row, live in the decode's slot of r * d floats)
-  if (rows > 256 || w > 64) return KVC_ERR_UNSUPPORTED;
-  const int rows_pad = rows <= 32 ? 32 : rows <= 64 ? 64 : rows <= 128 ? 128 : 256;
-  if ((size_t)rows_pad * 8 > (size_t)D.r * D.d * 4) return KVC_ERR_UNSUPPORTED;
+  // One pass of the kernels takes at most 64 queries and 256 query rows (a chunk's pairs, 8 bytes
+  // per padded query row, live in the decode's slot of r * d floats).  A block of queries at a
+  // given position may be longer: it is worked off in such passes over one work list.
+  auto padded = [](int rows) { return rows <= 32 ? 32 : rows <= 64 ? 64 : rows <= 128 ? 128 : 256; };
+  int w_pass = w < 64 ? w : 64;
+  while (w_pass >= 1 && (w_pass * D.r > 256 || (size_t)padded(w_pass * D.r) * 8 > (size_t)D.r * D.d * 4)) --w_pass;
+  if (w_pass < 1 || (w > w_pass && first_pos < 0)) return KVC_ERR_UNSUPPORTED;
   Workspace Wk = carve(D, ws);
   hipStream_t s = (hipStream_t)stream;
   WindowArgs W;
@@ -501,8 +504,8 @@ static int window_common(const kvc_config* cfg, const kvc_state* st, const void*
   A.items = (DecodeItem*)Wk.items; A.slot_item = Wk.slot_item; A.part_ml = Wk.part_ml; A.part_acc = Wk.part_acc; A.stash = Wk.stash;
   A.header = Wk.header;
   A.scale_log2 = (float)(1.4426950408889634 / 11.313708498984761);  // log2(e) / sqrt(128)
-  W.w = w; W.rows = rows; W.pool = pool; W.add = accumulate != 0;
-  W.first_pos = first_pos; W.exclude = exclude;
+  W.pool = pool; W.add = accumulate != 0; W.exclude = exclude;
+  W.q_count = w;
   W.part = Wk.part_acc; W.raw = Wk.stash;
   // a head that holds no KV has no output here: the item kernel's zero rows must not be written
   if (A.gsel <= kSmallWorklistHeads) {
@@ -518,17 +521,23 @@ static int window_common(const kvc_config* cfg, const kvc_state* st, const void*
   const size_t bound_row = (size_t)A.gsel * (((size_t)D.maxb * D.b + A.T - 1) / A.T);
   const size_t grid = bound_pool < bound_row ? bound_pool : bound_row;
   if (grid > 0x7fffffffull) return KVC_ERR_UNSUPPORTED;
-  switch (rows_pad) {
-    case 32: rc = launch_window<16, 2>(W, (int)grid, s); break;
-    case 64: rc = launch_window<16, 4>(W, (int)grid, s); break;
-    case 128: rc = launch_window<16, 8>(W, (int)grid, s); break;
-    default: rc = launch_window<32, 8>(W, (int)grid, s); break;
-  }
-  if (rc != KVC_OK) return rc;
   const int pool_tiles = (int)(((size_t)D.maxb * D.b + kPoolTile - 1) / kPoolTile);
   if (pool_tiles > 65535) return KVC_ERR_UNSUPPORTED;
-  hipLaunchKernelGGL(window_pool_kernel, dim3(A.gsel, pool_tiles), dim3(256), 0, s, W);
-  KVC_LAUNCH_CHECK();
+  for (int q0 = 0; q0 < w; q0 += w_pass) {
+    W.q_first = q0;
+    W.w = w - q0 < w_pass ? w - q0 : w_pass;
+    W.rows = W.w * D.r;
+    W.first_pos = first_pos < 0 ? first_pos : first_pos + q0;
+    switch (padded(W.rows)) {
+      case 32: rc = launch_window<16, 2>(W, (int)grid, s); break;
+      case 64: rc = launch_window<16, 4>(W, (int)grid, s); break;
+      case 128: rc = launch_window<16, 8>(W, (int)grid, s); break;
+      default: rc = launch_window<32, 8>(W, (int)grid, s); break;
+    }
+    if (rc != KVC_OK) return rc;
+    hipLaunchKernelGGL(window_pool_kernel, dim3(A.gsel, pool_tiles), dim3(256), 0, s, W);
+    KVC_LAUNCH_CHECK();
+  }
   return KVC_OK;
 }
 

@@ -101,11 +101,14 @@ def test_window_metric_on_random_shapes(seed0):
 def test_query_block_metric_on_random_shapes(seed0):
     """Blocks of queries at random positions of ragged heads: in front of, inside and past the end
     of a head, chunks with and without visible keys, heads of a multiple of eight chunks, excluded
-    windows longer than the block; several blocks accumulate into one metric."""
+    windows longer than the block, blocks longer than one pass of the kernels takes; several blocks
+    accumulate into one metric."""
     rng = np.random.default_rng(seed0)
     for case in range(24):
         r = int(rng.choice([1, 2, 4, 8]))
         w = int(rng.integers(1, min(64, 256 // r) + 1))
+        if case % 4 == 3:
+            w = int(rng.integers(65, 300))       # a long block: several passes of the kernels
         b = int(rng.choice([16, 32, 64]))
         S, Lyr, Hk = int(rng.integers(1, 3)), int(rng.integers(1, 3)), int(rng.integers(1, 4))
         L = int(rng.choice([int(rng.integers(64, 3000)), 2048, 8192]))

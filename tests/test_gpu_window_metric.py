@@ -93,13 +93,17 @@ def test_window_metric_layer_range_accumulate_and_unsupported():
     with pytest.raises(B.KvcError) as e:
         sess.window_metric(qw.to(sess.device), w, 4)          # even pool size
     assert e.value.code == B.KVC_ERR_ARG
-    # more than 64 window queries, or more than 256 query rows, at any group size
+    # more than 64 window queries, or more than 256 query rows, at any group size (a block of the
+    # all-queries metric may be that long: it is worked off in passes)
     for r, w_bad in ((1, 65), (2, 65), (4, 65), (8, 33)):
         shape3, ctx3, _ = W.small_mixed(105, S=1, Lyr=1, Hk=1, r=r, d=128, kv_dtype="bf16", L=100)
         sess3 = session(W.make_cache(shape3, ctx3, 105))
+        q3 = torch.zeros((1, 1, r, w_bad, 128), device=sess3.device, dtype=torch.bfloat16)
         with pytest.raises(B.KvcError) as e:
-            sess3.window_metric(torch.zeros((1, 1, r, w_bad, 128), device=sess3.device, dtype=torch.bfloat16), w_bad, 7)
+            sess3.window_metric(q3, w_bad, 7)
         assert e.value.code == B.KVC_ERR_UNSUPPORTED, (r, w_bad)
+        sess3.query_block_metric(q3, w_bad, 0)
+        torch.cuda.synchronize()
 
 
 def test_query_block_metric_builds_kvc_full():
