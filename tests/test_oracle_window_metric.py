@@ -103,3 +103,27 @@ def test_query_blocks_build_the_all_queries_metric_with_excluded_window():
     want = ((A ** 2) * (i >= j + v)).sum(dim=(0, 1)).numpy()
     np.testing.assert_allclose(_metric_of(st), want, rtol=1e-12, atol=1e-15)
     assert (want[L - v:] == 0).all()              # the last v keys have no query far enough away
+
+
+def test_query_block_past_the_end_of_a_head():
+    """Queries that sit at or behind a head's last key (the head kept fewer KVs than the prompt is
+    long): each attends to all C keys and adds to key j only when its own position is at least v
+    past j — the excluded window is counted from the query, not from the head's end.  Against a
+    dense softmax over the C keys, query by query."""
+    rng = np.random.default_rng(9)
+    r, d, b, C, v, w, start = 2, 16, 4, 21, 5, 6, 18       # positions 18 .. 23, keys 0 .. 20
+    K = rng.standard_normal((C, d)); Q = rng.standard_normal((r, w, d))
+    st = _one_head_state(K, np.zeros((C, d)), r, b)
+    O.query_block_metric(st, Q.reshape(1, 1, r, w, d), w, start, v)
+    want = np.zeros(C)
+    for h in range(r):
+        for i in range(w):
+            x = start + i
+            seen = min(x, C - 1) + 1
+            a = torch.softmax(torch.from_numpy(K[:seen] @ Q[h, i]) / math.sqrt(d), dim=0).numpy()
+            for j in range(seen):
+                if x - j >= v:
+                    want[j] += a[j] ** 2
+    np.testing.assert_allclose(_metric_of(st), want, rtol=1e-12, atol=1e-15)
+    assert want[C - 1 - (v - (start + w - 1 - (C - 1))) + 1:].sum() == 0     # keys too close to every query
+    assert want[C - 3] > 0      # key 18 is 5 behind the last query (position 23): it does get its share
