@@ -302,8 +302,10 @@ int kvc_query_block_metric(const kvc_config* cfg, const kvc_state* st, const voi
 int kvc_set_decode_chunk(int tokens);
 
 /* The chunk length kvc_paged_decode uses for this config when called over all layers (host
- * out-param; calls over fewer layers may use shorter chunks), 0 when the shape takes the
- * general fallback kernel, which does not split heads.  Host only.              */
+ * out-param), 0 when the shape takes the general fallback kernel, which does not split heads.
+ * It is the most a chunk holds: a call over few head instances (fewer layers, few sequences)
+ * may use shorter chunks, and one over at most 1024 picks the length on the device from the
+ * lengths of the heads.  Host only.                                              */
 int kvc_get_decode_chunk(const kvc_config* cfg, int* tokens);
 
 /* kvc_paged_decode runs the last chunk of a head (or a whole short head) in a second launch,

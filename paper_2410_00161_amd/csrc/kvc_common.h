@@ -26,6 +26,7 @@ enum HeaderWord {
   HW_SCRATCH1 = 6,
   HW_SHORT_ITEMS = 8,  // decode work items short enough for the one-wavefront launch
   HW_TOTAL_PARTIALS = 9,  // per-chunk partial-result slots in use = chunks of heads of more than one chunk
+  HW_CHUNK_T = 10,     // chunk length the work list in place was cut with (tokens)
   // decode work-list block: item counts per size class, per-class cursors, cursor of the
   // per-chunk partial results.  All zero between calls (the chunk kernel clears it).
   HW_DEC_BINS = 32,    // [16]

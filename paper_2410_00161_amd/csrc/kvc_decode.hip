@@ -252,7 +252,8 @@ __global__ void __launch_bounds__(NW * 64) decode_chunk_kernel(DecodeArgs A) {
   const DecodeItem it = A.items[item];
   const int g = it.g, t0 = it.t0, n_tok = it.n_tok, nch = it.nch;
   const int T = NW == 4 ? A.T : A.Ts;    // tokens this launch sizes its LDS arrays for
-  if ((unsigned)g >= (unsigned)A.D.G || n_tok <= 0 || n_tok > T || t0 < 0 || nch <= 0 ||
+  const int Tc = A.header[HW_CHUNK_T];   // tokens the work list was cut at (<= A.T)
+  if ((unsigned)g >= (unsigned)A.D.G || n_tok <= 0 || n_tok > T || t0 < 0 || nch <= 0 || Tc < 64 || Tc > A.T ||
       (nch > 1 && (it.pbase < 0 || it.pbase + nch > A.cap)))
     return;  // not a record this call wrote
   const int b = A.D.b, lb = A.log2b;
@@ -620,7 +621,7 @@ __global__ void __launch_bounds__(NW * 64) decode_chunk_kernel(DecodeArgs A) {
     cm[hh] = m;
     cl[hh] = l;
   }
-  const size_t pslot = (size_t)it.pbase + (size_t)(t0 / A.T);  // partial-result slot of this chunk
+  const size_t pslot = (size_t)it.pbase + (size_t)(t0 / Tc);  // partial-result slot of this chunk
 #pragma unroll
   for (int hh = 0; hh < R; ++hh) {
     for (int k = tid; k < HD; k += NT) {
@@ -686,7 +687,10 @@ __global__ void __launch_bounds__(256) decode_combine_kernel(DecodeArgs A) {
       it.pbase + nch > A.cap)
     return;  // not a record this call wrote
   const int g = it.g, t0 = it.t0, n_tok = it.n_tok;
-  const int c = t0 / A.T;
+  const int Tc = A.header[HW_CHUNK_T];       // tokens the work list was cut at
+  if (Tc < 64 || Tc > A.T) return;
+  const int c = t0 / Tc;
+  if (c >= nch) return;
   const int first = it.pbase;                // partial-result slots first .. first + nch - 1
   const int b = A.D.b, lb = A.log2b, HD = A.D.d;
   constexpr int kMaxCh = 64;                 // chunk weights kept in LDS; longer heads recompute
@@ -865,8 +869,9 @@ static int launch_tiled(const DecodeArgs& A, int grid, size_t lds, int grid_shor
   }
   if (pp) { KVC_HIP(hipEventRecord(pp->s1, s)); KVC_HIP(hipEventRecord(pp->b0, s)); }
   // heads of more than one chunk hold more than T tokens each: at most N b / T of them, and their
-  // chunks number at most tokens / T plus one per head
-  const size_t split_bound = 2 * ((size_t)A.D.N * A.D.b / A.T) + 1;
+  // chunks number at most tokens / T plus one per head (a chunk length picked on the device: the
+  // bound on the work items serves)
+  const size_t split_bound = A.adapt_T ? (size_t)grid : 2 * ((size_t)A.D.N * A.D.b / A.T) + 1;
   const int grid_combine = (size_t)grid < split_bound ? grid : (int)split_bound;
   hipLaunchKernelGGL(decode_combine_kernel<R>, dim3(grid_combine), dim3(256), 0, s, A);
   KVC_LAUNCH_CHECK();
@@ -888,7 +893,8 @@ static int launch_tiled_r(const DecodeArgs& A, int grid, size_t lds, int grid_sh
 constexpr size_t kLdsLimit = 160 * 1024;  // gfx950: 160 KiB of LDS per workgroup
 
 // Whether the tiled kernels cover this shape, and with which chunk length and LDS size.
-static bool choose_chunk(const Dims& D, int gsel, int* T_out, size_t* lds_out, bool* small_call = nullptr) {
+static bool choose_chunk(const Dims& D, int gsel, int* T_out, size_t* lds_out, bool* small_call = nullptr,
+                         bool* on_device = nullptr) {
   const int esz = kv_esz(D.dtype);
   const int lpt = D.d * esz / 16;
   const int tpi = (lpt >= 1 && lpt <= 64) ? 64 / lpt : 0;
@@ -899,6 +905,7 @@ static bool choose_chunk(const Dims& D, int gsel, int* T_out, size_t* lds_out, b
   // tokens x 16 bytes of exps + the rest = 81 764 of the 81 920 bytes a half CU has)
   int T = g_chunk_tokens ? g_chunk_tokens : (D.r >= 8 ? 3456 : 6144);
   const int T_default = T;
+  bool shrunk = false, device_side = false;
   if (!g_chunk_tokens) {
     // a call over few head instances (one layer at a time) has too few long chunks to fill the
     // chip: shorten them until full rows would give a few thousand work items
@@ -906,6 +913,10 @@ static bool choose_chunk(const Dims& D, int gsel, int* T_out, size_t* lds_out, b
     // (halved and rounded up to whole 64-token strips: a chunk starts on a block boundary)
     while (T > 256 && (long long)gsel * (((long long)D.maxb * D.b + T - 1) / T) < want_items)
       T = ((T / 2) + 63) & ~63;
+    shrunk = T < T_default;
+    // ... unless the one-launch work list serves the call: it sees the lengths themselves, not
+    // just what the tables have room for, and picks the length (at most the default) on the device
+    if (shrunk && gsel <= kSmallWorklistHeads) { T = T_default; device_side = true; }
   }
   const bool mf = decode_pv_mfma(esz, D.r, D.d, D.b);   // a per-wavefront operand tile in LDS
   while (T > kMinChunk && decode_lds_bytes(T, D.r, D.d, D.b, kDecodeWaves, mf) > kLdsLimit) T -= 64;
@@ -913,7 +924,8 @@ static bool choose_chunk(const Dims& D, int gsel, int* T_out, size_t* lds_out, b
   if (lds > kLdsLimit || T % 64 != 0) return false;
   *T_out = T;
   *lds_out = lds;
-  if (small_call) *small_call = T < T_default;
+  if (small_call) *small_call = shrunk;
+  if (on_device) *on_device = device_side;
   return true;
 }
 
@@ -1034,8 +1046,9 @@ int kvc_paged_decode(const kvc_config* cfg, const kvc_state* st, const void* q, 
 
   int T = 0;
   size_t lds = 0;
-  bool small_call = false;
-  bool tiled = choose_chunk(D, D.S * (layer_end - layer_begin) * D.Hk, &T, &lds, &small_call);
+  bool small_call = false, on_device = false;
+  bool tiled = choose_chunk(D, D.S * (layer_end - layer_begin) * D.Hk, &T, &lds, &small_call, &on_device);
+  A.adapt_T = tiled && on_device;
   const int esz = kv_esz(D.dtype);
   A.T = tiled ? T : (1 << 30);  // generic path: one "chunk" per head
   A.short_class = 16;
@@ -1064,9 +1077,12 @@ int kvc_paged_decode(const kvc_config* cfg, const kvc_state* st, const void* q, 
     hipLaunchKernelGGL(decode_items_kernel, dim3((A.gsel + 255) / 256), dim3(256), 0, s, A);
     KVC_LAUNCH_CHECK();
   }
-  // items <= (slots in the pool) / T + heads, and <= heads * chunks a full row can hold
-  const size_t bound_pool = (size_t)D.N * D.b / T + (size_t)A.gsel;
-  const size_t bound_row = (size_t)A.gsel * (((size_t)D.maxb * D.b + T - 1) / T);
+  // items <= (slots in the pool) / T + heads, and <= heads * chunks a full row can hold.  A chunk
+  // length picked on the device is T or at least 1.25 / 512 of all tokens, which makes at most
+  // 512 / 1.25 full chunks (512 allowed for).
+  const size_t bound_pool = (size_t)D.N * D.b / T + (size_t)A.gsel + (A.adapt_T ? 512 : 0);
+  const size_t Tmin = A.adapt_T ? 256 : (size_t)T;
+  const size_t bound_row = (size_t)A.gsel * (((size_t)D.maxb * D.b + Tmin - 1) / Tmin);
   const size_t grid = bound_pool < bound_row ? bound_pool : bound_row;
   if (grid > 0x7fffffffull) return KVC_ERR_UNSUPPORTED;
   const int gs = A.gsel;   // a head ends in at most one item shorter than a chunk

@@ -493,7 +493,7 @@ static int window_common(const kvc_config* cfg, const kvc_state* st, const void*
   A.metric = st->metric; A.table = st->block_table; A.ctx = st->ctx_len;
   A.q = (const char*)q_win; A.out = nullptr;
   A.l0 = layer_begin; A.nl = layer_end - layer_begin; A.gsel = D.S * A.nl * D.Hk;
-  A.accumulate = 1; A.T = kWinChunk;
+  A.accumulate = 1; A.T = kWinChunk; A.adapt_T = 0;
   A.log2b = 0;
   while ((1 << A.log2b) < D.b) ++A.log2b;
   A.all_partials = 1;

@@ -26,7 +26,8 @@ struct DecodeArgs {
   const char* q;
   float* out;
   int l0, nl, gsel;       // first layer, layer count, head instances selected
-  int accumulate, T;      // metric on/off, chunk tokens
+  int accumulate, T;      // metric on/off, chunk tokens (the most a chunk may hold when adapt_T is set)
+  int adapt_T;            // the one-launch work list picks the chunk length from the lengths it sees (see there)
   int log2b;              // block size is a power of two on the tiled path
   int cap;                // item records and partial-result slots the workspace holds
   int all_partials;       // give every head a partial-result slot range, not only split heads
@@ -100,6 +101,7 @@ static __global__ void __launch_bounds__(256) decode_items_kernel(DecodeArgs A) 
       A.header[HW_TOTAL_ITEMS] = run;
       A.header[HW_SHORT_ITEMS] = shorts;
       A.header[HW_TOTAL_PARTIALS] = A.header[HW_DEC_PTOT];
+      A.header[HW_CHUNK_T] = A.T;
     }
   }
   __syncthreads();
@@ -160,16 +162,39 @@ static __global__ void __launch_bounds__(256) decode_items_kernel(DecodeArgs A) 
 constexpr int kSmallWorklistHeads = 1024;
 static __global__ void __launch_bounds__(1024) decode_worklist_small_kernel(DecodeArgs A) {
   __shared__ int bins[16], base[16], cur[17], ptot;
+  __shared__ unsigned long long tokens;
+  __shared__ int live;
   const int tid = threadIdx.x;
-  if (tid == 0) ptot = 0;
+  if (tid == 0) { ptot = 0; tokens = 0; live = 0; }
   if (tid < 16) bins[tid] = 0;
   if (tid < 17) cur[tid] = 0;
   __syncthreads();
-  const int T = A.T;
   int g = 0, C = 0, nfull = 0, rem = 0, nch = 0, cls = 0;
   if (tid < A.gsel) {
     g = sel_to_g(A.D, A.l0, A.nl, tid);
     C = A.ctx[g];
+  }
+  // Chunk length of a call over few heads.  Such a call is over when its slowest item is.  One
+  // workgroup alone on its CU streams ~25 GB/s, two that share one ~12 each, the chip ~6 TB/s:
+  // the slowest item and the whole call end together when a chunk is 1/256 of all the tokens
+  // with up to 256 heads, 1/512 from 512 heads on.  A quarter on top, so that heads of one
+  // length (each an item of that length then) are not cut just behind their first chunk;
+  // cutting costs (the exps of a split head go through the workspace), so nothing shorter than
+  // 256 tokens.
+  int T = A.T;
+  if (A.adapt_T) {
+    unsigned long long t = (unsigned long long)max(C, 0);
+    for (int m = 32; m >= 1; m >>= 1) t += __shfl_xor(t, m);
+    if ((tid & 63) == 0 && t) atomicAdd(&tokens, t);
+    if (C > 0) atomicAdd(&live, 1);
+    __syncthreads();
+    const int den = min(512, max(256, live));
+    const unsigned long long want = (tokens + tokens / 4) / den;
+    const int t64 = (int)((want < (unsigned long long)A.T ? want : (unsigned long long)A.T) + 63) & ~63;
+    T = min(A.T, max(256, t64));
+  }
+  if (tid == 0) A.header[HW_CHUNK_T] = T;
+  if (tid < A.gsel) {
     nfull = C / T;
     rem = C - nfull * T;
     nch = nfull + (rem ? 1 : 0);

@@ -163,6 +163,44 @@ def test_decode_over_the_matrix_of_shapes(name, kw, chunk):
     np.testing.assert_allclose(sess.cache.metric.cpu().numpy().astype(np.float64)[live], st.metric[live], rtol=0, atol=TOL)
 
 
+# Calls over at most 1024 head instances with the library's own chunk setting: the chunk length
+# is picked on the device from the lengths (1.25 / 256 of all tokens up to 256 heads, / 512 from
+# 512 on, at least 256, at most the default).  Few long heads (chunks of ~800 tokens, every head
+# split many times), many short ones (nothing split), one head far longer than the rest.
+DEVICE_CHUNK_CASES = [
+    ("few_long_heads", dict(S=1, Lyr=1, Hk=8, r=4, d=128, kv_dtype="bf16", L=20000, rho=1.3), None),
+    ("many_short_heads", dict(S=6, Lyr=5, Hk=8, r=4, d=128, kv_dtype="bf16", L=700, rho=1.5), None),
+    ("one_long_head_r8_fp8", dict(S=2, Lyr=2, Hk=8, r=8, d=128, kv_dtype="fp8", L=1200, rho=2.0, b=32), 30000),
+]
+
+
+@pytest.mark.parametrize("name,kw,long_head", DEVICE_CHUNK_CASES, ids=[c[0] for c in DEVICE_CHUNK_CASES])
+def test_decode_with_the_chunk_length_picked_on_the_device(name, kw, long_head):
+    say("decode, chunk length picked on the device", name)
+    shape, ctx, seed = W.small_mixed(71, **kw)
+    if long_head:
+        import dataclasses
+        ctx[5] = long_head
+        shape = dataclasses.replace(shape, num_blocks=shape.num_blocks + long_head // shape.block_size + 8,
+                                    max_blocks_per_head=long_head // shape.block_size + 8)
+    cache = W.make_cache(shape, ctx, seed, placement="fragmented", init_metric="prefill")
+    st = oracle_state(cache)
+    q = W.make_query(shape, seed)
+    want = O.paged_decode(st, q.double().numpy())
+    sess = session(cache)
+    out = sess.paged_decode(q.to(sess.device))
+    torch.cuda.synchronize()
+    np.testing.assert_allclose(out.cpu().numpy().astype(np.float64), want, rtol=0, atol=TOL)
+    live = st.free_map == 0
+    np.testing.assert_allclose(sess.cache.metric.cpu().numpy().astype(np.float64)[live], st.metric[live], rtol=0, atol=TOL)
+    # one layer of it alone (fewer heads, another length)
+    out2 = sess.paged_decode(q.to(sess.device), accumulate_metric=False, layer_begin=shape.num_layers - 1,
+                             layer_end=shape.num_layers)
+    torch.cuda.synchronize()
+    lsel = shape.num_layers - 1
+    np.testing.assert_allclose(out2.cpu().numpy().astype(np.float64)[:, lsel], want[:, lsel], rtol=0, atol=TOL)
+
+
 DOMINANT_CASES = [
     ("bf16_r8", dict(r=8, d=128, kv_dtype="bf16", L=600), 128),
     ("fp8_r8", dict(r=8, d=128, kv_dtype="fp8", L=600), 128),
