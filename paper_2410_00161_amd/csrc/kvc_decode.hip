@@ -19,6 +19,7 @@
 // The r dot products of a token are finished with a halving butterfly over the
 // LPT lanes, which leaves each lane with distinct (token, head) logits instead
 // of every lane with all of them.
+#include <algorithm>
 #include <cmath>
 
 #include "kvc_common.h"
@@ -1080,7 +1081,8 @@ int kvc_paged_decode(const kvc_config* cfg, const kvc_state* st, const void* q, 
   // items <= (slots in the pool) / T + heads, and <= heads * chunks a full row can hold.  A chunk
   // length picked on the device is T or at least 1.25 / 512 of all tokens, which makes at most
   // 512 / 1.25 full chunks (512 allowed for).
-  const size_t bound_pool = (size_t)D.N * D.b / T + (size_t)A.gsel + (A.adapt_T ? 512 : 0);
+  const size_t most_tokens = std::min((size_t)D.N * D.b, (size_t)A.gsel * D.maxb * D.b);   // pool, or the rows of the heads called for
+  const size_t bound_pool = most_tokens / T + (size_t)A.gsel + (A.adapt_T ? 512 : 0);
   const size_t Tmin = A.adapt_T ? 256 : (size_t)T;
   const size_t bound_row = (size_t)A.gsel * (((size_t)D.maxb * D.b + Tmin - 1) / Tmin);
   const size_t grid = bound_pool < bound_row ? bound_pool : bound_row;
