@@ -26,9 +26,11 @@
  *     KVC_ASYNC in `flags` skips that wait: the call returns KVC_OK at once,
  *     later launches that depend on a failed step become no-ops, and the code
  *     is read later with kvc_poll_status().
- *   - Host side, the library keeps a little process-wide state (the tuning and
- *     profiling switches below, what it has told the runtime about its kernels):
- *     call it from one host thread at a time.
+ *   - Host side, the library keeps no state of a cache: what a call needs is in
+ *     its arguments, so calls on different workspaces may come from different
+ *     host threads.  Process-wide are only the tuning knob kvc_set_decode_chunk
+ *     (read once per call) and what the library has told the runtime about its
+ *     kernels (set once, under atomics).
  *   - Head instance g = (s * num_layers + l) * num_kv_heads + h; G = S*Lyr*Hk.
  *     Query head hq of a layer belongs to KV head hq / group_size.
  *   - A head instance holds the blocks block_table[g][0 .. held), held = the
@@ -50,7 +52,7 @@ typedef enum {
   KVC_ERR_ARG = 1,        /* null / misaligned pointer, bad enum, bad range     */
   KVC_ERR_OOM = 2,        /* fewer free blocks than requested                    */
   KVC_ERR_TABLE_FULL = 3, /* a head would exceed max_blocks_per_head             */
-  KVC_ERR_BUDGET = 4,     /* reserved                                            */
+  /* 4 is not used */
   KVC_ERR_NUMERIC = 5,    /* NaN, infinite or negative block key                 */
   KVC_ERR_HIP = 6,        /* a HIP runtime call failed                           */
   KVC_ERR_UNSUPPORTED = 7 /* shape outside what the kernels cover                */
@@ -72,7 +74,7 @@ typedef struct kvc_config {
   int32_t num_kv_heads;        /* Hk (paper H)                                  */
   int32_t group_size;          /* r = query heads per KV head                   */
   int32_t head_dim;            /* d                                             */
-  int32_t block_size;          /* b                                             */
+  int32_t block_size;          /* b: a power of two, 1 .. 1024 (else KVC_ERR_UNSUPPORTED) */
   int32_t num_blocks;          /* N                                             */
   int32_t max_blocks_per_head; /* Lmax / b                                      */
   int32_t kv_dtype;            /* KVC_F32 | KVC_BF16 (q has the same type) | KVC_FP8_E4M3 (q is bf16) */
@@ -312,35 +314,6 @@ int kvc_get_decode_chunk(const kvc_config* cfg, int* tokens);
  * one wavefront per item, when it holds at most this many tokens (host out-param; for a call
  * over all layers; 0 on the fallback path).  Host only.                          */
 int kvc_get_decode_short(const kvc_config* cfg, int* tokens);
-
-/* Kernel timing for benchmarks.  kvc_profile_begin(n) makes the next n calls of
- * kvc_paged_decode record HIP event pairs on their stream around each of its
- * three launches: the chunk kernel over the long items (it streams nearly all
- * of K and V), the same kernel over the short items, and the combine kernel;
- * n = 0 switches recording off and releases the events.  Host only state,
- * process-wide, at most 4096 calls.  kvc_profile_collect waits for the recorded
- * events and writes up to `cap` durations in milliseconds to the host arrays
- * chunk_ms, short_ms and combine_ms (each may be NULL), returning the number of
- * recorded calls in *count (host).                                             */
-/* Bandwidth probe for benchmarks: reads `bytes` (a multiple of 16) of device
- * memory at `src` once with 16-byte non-temporal loads, grid-stride, and writes one 32-bit
- * checksum per workgroup to `sink` (device, at least `workgroups` words).
- * Gives the streaming-read rate this GPU reaches, to set beside the kernels'.   */
-int kvc_stream_read_probe(const void* src, size_t bytes, uint32_t* sink, int workgroups,
-                          void* stream);
-
-/* The same probe with a trickle of writes mixed in: every lane stores 16 bytes to `dst`
- * (device, dst_bytes, a multiple of 16; stores past its end are dropped) after every `every`
- * rounds of four 16-byte loads, i.e. 16 bytes written per 64 * every bytes read.  Shows what
- * small writes cost a saturated read stream on this GPU.                          */
-int kvc_stream_rw_probe(const void* src, size_t bytes, void* dst, size_t dst_bytes, int every,
-                        uint32_t* sink, int workgroups, void* stream);
-
-int kvc_profile_begin(int n);
-/* Pauses (0) or resumes (non-zero) the recording without releasing anything, so that a
- * benchmark can time every k-th call only.  Host only.                            */
-int kvc_profile_enable(int on);
-int kvc_profile_collect(float* chunk_ms, float* short_ms, float* combine_ms, int cap, int* count);
 
 #ifdef __cplusplus
 }

@@ -16,7 +16,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libkvc.so")
 
 KVC_OK, KVC_ERR_ARG, KVC_ERR_OOM, KVC_ERR_TABLE_FULL = 0, 1, 2, 3
-KVC_ERR_BUDGET, KVC_ERR_NUMERIC, KVC_ERR_HIP, KVC_ERR_UNSUPPORTED = 4, 5, 6, 7
+KVC_ERR_NUMERIC, KVC_ERR_HIP, KVC_ERR_UNSUPPORTED = 5, 6, 7
 KVC_F32, KVC_BF16, KVC_FP8_E4M3 = 0, 1, 2
 KVC_L2, KVC_L1 = 0, 1
 KVC_KEY_SUM, KVC_KEY_MAX = 0, 1
@@ -27,7 +27,7 @@ EXPORTS = [
     "kvc_poll_status", "kvc_check_state", "kvc_block_alloc", "kvc_block_free", "kvc_append", "kvc_paged_decode",
     "kvc_metric_reduce", "kvc_evict_select", "kvc_compact", "kvc_set_decode_chunk",
     "kvc_get_decode_chunk", "kvc_get_decode_short", "kvc_evict_rank_select", "kvc_compact_rank", "kvc_window_metric", "kvc_query_block_metric", "kvc_count_blocks", "kvc_prefill_alloc", "kvc_preempt", "kvc_compression_batch",
-    "kvc_profile_begin", "kvc_profile_enable", "kvc_profile_collect", "kvc_stream_read_probe", "kvc_stream_rw_probe",
+    "kvc_profile_begin", "kvc_profile_enable", "kvc_profile_collect", "kvc_stream_read_probe",
 ]
 
 
@@ -90,7 +90,6 @@ def lib() -> C.CDLL:
         L.kvc_profile_begin.argtypes = [I]
         L.kvc_profile_enable.argtypes = [I]
         L.kvc_stream_read_probe.argtypes = [P, C.c_size_t, P, I, P]
-        L.kvc_stream_rw_probe.argtypes = [P, C.c_size_t, P, C.c_size_t, I, P, I, P]
         L.kvc_profile_collect.argtypes = [P, P, P, I, C.POINTER(C.c_int)]
         for n in EXPORTS:
             if n not in ("kvc_workspace_bytes", "kvc_status_string"):
@@ -263,12 +262,6 @@ def kvc_get_decode_short(cfg) -> int:
     out = C.c_int(0)
     _check(lib().kvc_get_decode_short(C.byref(cfg), C.byref(out)), "kvc_get_decode_short")
     return out.value
-
-
-def kvc_stream_rw_probe(src, nbytes, dst, dst_bytes, every, sink, workgroups, stream=None):
-    _check(lib().kvc_stream_rw_probe(_ptr(src), int(nbytes), _ptr(dst), int(dst_bytes), int(every),
-                                     _ptr(sink, torch.int32), int(workgroups), _stream(stream)),
-           "kvc_stream_rw_probe")
 
 
 def kvc_evict_rank_select(cfg, st, seg_offsets, budget, nseg, protect_tail_blocks, evict_rows, selected, ws,

@@ -17,6 +17,9 @@ int validate(const kvc_config* c, const kvc_state* st) {
   if (G * c->max_blocks_per_head > (1ll << 40)) return KVC_ERR_UNSUPPORTED;
   if ((int64_t)c->num_blocks * c->block_size > (1ll << 40)) return KVC_ERR_UNSUPPORTED;
   if (c->group_size > 16 || c->head_dim > 512) return KVC_ERR_UNSUPPORTED;
+  // slots are indexed as (block id << log2 b) + (j & (b - 1)) by the compaction, rank-schedule and
+  // window kernels: a block size that is not a power of two would send rows to wrong slots
+  if ((c->block_size & (c->block_size - 1)) != 0 || c->block_size > 1024) return KVC_ERR_UNSUPPORTED;
   const int esz = kv_esz(c->kv_dtype);
   if ((c->head_dim * esz) % 16 != 0) return KVC_ERR_UNSUPPORTED;  // rows are read 16 bytes at a time
   if (st) {
@@ -46,29 +49,6 @@ __global__ void __launch_bounds__(256) stream_read_kernel(const uint4* __restric
   if ((threadIdx.x & 63) == 0) atomicXor(&sink[blockIdx.x], acc);
 }
 
-// Same read stream, plus one 16-byte store per lane every `every` rounds of four loads: a
-// trickle of writes (16 bytes per 256 * every bytes read per lane) into a saturated read stream.
-__global__ void __launch_bounds__(256) stream_rw_kernel(const uint4* __restrict__ src, size_t n16,
-                                                        uint4* __restrict__ dst, size_t dst16, int every,
-                                                        uint32_t* __restrict__ sink) {
-  uint32_t acc = 0;
-  const size_t stride = (size_t)gridDim.x * 256;
-  size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
-  size_t wpos = i;
-  int round = 0;
-  for (; i + 3 * stride < n16; i += 4 * stride) {
-    const uint4 a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
-    acc ^= a.x ^ a.y ^ a.z ^ a.w ^ b.x ^ b.y ^ b.z ^ b.w ^ c.x ^ c.y ^ c.z ^ c.w ^ d.x ^ d.y ^ d.z ^ d.w;
-    if (++round == every) {
-      round = 0;
-      if (wpos < dst16) dst[wpos] = make_uint4(acc, a.x, b.y, c.z);
-      wpos += stride;
-    }
-  }
-  for (int m = 32; m >= 1; m >>= 1) acc ^= __shfl_xor(acc, m);
-  if ((threadIdx.x & 63) == 0) atomicXor(&sink[blockIdx.x], acc);
-}
-
 }  // namespace kvc
 
 using namespace kvc;
@@ -89,7 +69,6 @@ const char* kvc_status_string(int status) {
     case KVC_ERR_ARG: return "invalid argument";
     case KVC_ERR_OOM: return "not enough free blocks";
     case KVC_ERR_TABLE_FULL: return "block table row full";
-    case KVC_ERR_BUDGET: return "eviction budget error";
     case KVC_ERR_NUMERIC: return "NaN, infinite or negative block key";
     case KVC_ERR_HIP: return "HIP runtime error";
     case KVC_ERR_UNSUPPORTED: return "shape not supported";
@@ -113,17 +92,6 @@ int kvc_stream_read_probe(const void* src, size_t bytes, uint32_t* sink, int wor
   if (!src || !sink || workgroups <= 0 || (bytes & 15) || ((uintptr_t)src & 15)) return KVC_ERR_ARG;
   hipLaunchKernelGGL(stream_read_kernel, dim3(workgroups), dim3(256), 0, (hipStream_t)stream,
                      (const uint4*)src, bytes / 16, sink);
-  KVC_LAUNCH_CHECK();
-  return KVC_OK;
-}
-
-int kvc_stream_rw_probe(const void* src, size_t bytes, void* dst, size_t dst_bytes, int every,
-                        uint32_t* sink, int workgroups, void* stream) {
-  if (!src || !dst || !sink || workgroups <= 0 || every <= 0 || (bytes & 15) || (dst_bytes & 15) ||
-      (((uintptr_t)src | (uintptr_t)dst) & 15))
-    return KVC_ERR_ARG;
-  hipLaunchKernelGGL(stream_rw_kernel, dim3(workgroups), dim3(256), 0, (hipStream_t)stream, (const uint4*)src,
-                     bytes / 16, (uint4*)dst, dst_bytes / 16, every, sink);
   KVC_LAUNCH_CHECK();
   return KVC_OK;
 }

@@ -3,6 +3,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <atomic>
 #include <stdint.h>
 #include <stddef.h>
 
@@ -301,6 +302,44 @@ static __global__ void resolve_kernel(int32_t* header, int check_oom) {
   else if (check_oom == 1 && header[HW_TOTAL_REQ] > header[HW_TOTAL_FREE]) st = KVC_ERR_OOM;
   if (st != KVC_OK && header[HW_STATUS] == KVC_OK) header[HW_STATUS] = st;
   header[HW_SCRATCH0] = 0;
+}
+
+// Per-segment state of a selection (block mode and rank-block mode share it): eight words.
+enum SegWord { SEG_PREFIX = 0, SEG_REMAIN = 1, SEG_CAND = 2, SEG_TAKE = 3, SEG_FIRSTG = 4 };
+
+// First launch of either selection: the segment of every sequence (segments are runs of
+// consecutive sequences; seg_offsets NULL = one per sequence), cleared histograms and segment
+// state with the segment's first head instance, cleared per-head counts and per-segment results,
+// and the check of the offsets (first 0, last S, non-decreasing).
+static __global__ void __launch_bounds__(256) segments_init_kernel(Dims D, const int32_t* __restrict__ seg_offsets,
+                                                                   int nseg, int32_t* __restrict__ seq_seg,
+                                                                   int32_t* __restrict__ seg_hist,
+                                                                   int32_t* __restrict__ seg_state,
+                                                                   int32_t* __restrict__ per_head,
+                                                                   int32_t* __restrict__ selected,
+                                                                   int32_t* __restrict__ header) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < D.S) {
+    int sg = i;
+    if (seg_offsets) {  // last segment whose first sequence is <= i
+      int lo = 0, hi = nseg;
+      while (hi - lo > 1) { const int mid = (lo + hi) >> 1; if (seg_offsets[mid] <= i) lo = mid; else hi = mid; }
+      sg = lo;
+    }
+    seq_seg[i] = sg;
+  }
+  if (i < nseg * 256) seg_hist[i] = 0;
+  if (i < nseg) {
+    selected[i] = 0;
+    for (int k = 0; k < 8; ++k) seg_state[i * 8 + k] = 0;
+    const int first_seq = seg_offsets ? seg_offsets[i] : i;
+    seg_state[i * 8 + SEG_FIRSTG] = first_seq * D.Lyr * D.Hk;
+    if (seg_offsets) {
+      const int a = seg_offsets[i], b2 = seg_offsets[i + 1];
+      if (a > b2 || (i == 0 && a != 0) || (i == nseg - 1 && b2 != D.S)) atomicOr(&header[HW_SCRATCH0], EB_ARG);
+    }
+  }
+  if (i < D.G) per_head[i] = 0;
 }
 
 // Reads the status word; a non-zero word is cleared so that the next call starts clean.

@@ -20,19 +20,31 @@
 // LPT lanes, which leaves each lane with distinct (token, head) logits instead
 // of every lane with all of them.
 #include <algorithm>
+#include <atomic>
 #include <cmath>
+#include <mutex>
 
 #include "kvc_common.h"
 #include "kvc_worklist.h"
 
 namespace kvc {
 
-static int g_chunk_tokens = 0;  // 0 = default; set by kvc_set_decode_chunk
+// Host-side state of the process: the chunk-length knob (read once per call), what the runtime
+// has been told about the chunk kernels' LDS, and the benchmark's event recording behind one lock.
+static std::atomic<int> g_chunk_tokens{0};  // 0 = default; set by kvc_set_decode_chunk
 
-// optional event pairs around the two decode kernels (kvc_profile_begin / _collect)
+// optional event pairs around the decode kernels (kvc_profile_begin / _collect)
 struct ProfilePair { hipEvent_t a0, a1, s0, s1, b0, b1; };  // long-item, short-item, combine launches
+static std::mutex g_prof_lock;
 static ProfilePair* g_prof = nullptr;
 static int g_prof_cap = 0, g_prof_used = 0, g_prof_on = 1;
+static std::atomic<bool> g_prof_any{false};   // recording asked for: only then a call takes the lock
+
+static ProfilePair* claim_profile_pair() {
+  if (!g_prof_any.load(std::memory_order_acquire)) return nullptr;
+  std::lock_guard<std::mutex> hold(g_prof_lock);
+  return (g_prof && g_prof_on && g_prof_used < g_prof_cap) ? &g_prof[g_prof_used++] : nullptr;
+}
 
 typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
@@ -850,14 +862,15 @@ template <int ESZ, int HD, int R>
 static int launch_tiled(const DecodeArgs& A, int grid, size_t lds, int grid_short, hipStream_t s) {
   auto kern = (A.D.b % 16 == 0) ? decode_chunk_kernel<ESZ, HD, R, true, 4> : decode_chunk_kernel<ESZ, HD, R, false, 4>;
   auto kern_short = (A.D.b % 16 == 0) ? decode_chunk_kernel<ESZ, HD, R, true, 1> : decode_chunk_kernel<ESZ, HD, R, false, 1>;
-  ProfilePair* pp = (g_prof && g_prof_on && g_prof_used < g_prof_cap) ? &g_prof[g_prof_used++] : nullptr;
+  ProfilePair* pp = claim_profile_pair();
   if (pp) KVC_HIP(hipEventRecord(pp->a0, s));
   if (lds > 64 * 1024) {  // above the default cap the kernel must be told once how much it may take
-    static size_t allowed[2] = {0, 0};
-    size_t& a = allowed[A.D.b % 16 == 0];
-    if (lds > a) {
+    static std::atomic<size_t> allowed[2];   // per instantiation: zero-initialised, only ever raised
+    std::atomic<size_t>& a = allowed[A.D.b % 16 == 0];
+    if (lds > a.load(std::memory_order_acquire)) {
       KVC_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-      a = lds;
+      size_t seen = a.load(std::memory_order_relaxed);
+      while (seen < lds && !a.compare_exchange_weak(seen, lds, std::memory_order_release)) {}
     }
   }
   hipLaunchKernelGGL(kern, dim3(grid), dim3(kDecodeThreads), lds, s, A);
@@ -904,10 +917,11 @@ static bool choose_chunk(const Dims& D, int gsel, int* T_out, size_t* lds_out, b
   if (!tiled) return false;
   // default: a chunk that lets two workgroups share a CU (at r = 8, d = 128, 16-bit rows: 3456
   // tokens x 16 bytes of exps + the rest = 81 764 of the 81 920 bytes a half CU has)
-  int T = g_chunk_tokens ? g_chunk_tokens : (D.r >= 8 ? 3456 : 6144);
+  const int knob = g_chunk_tokens.load(std::memory_order_relaxed);
+  int T = knob ? knob : (D.r >= 8 ? 3456 : 6144);
   const int T_default = T;
   bool shrunk = false, device_side = false;
-  if (!g_chunk_tokens) {
+  if (!knob) {
     // a call over few head instances (one layer at a time) has too few long chunks to fill the
     // chip: shorten them until full rows would give a few thousand work items
     const long long want_items = 6144;
@@ -948,6 +962,8 @@ extern "C" {
 
 int kvc_profile_begin(int n) {
   if (n < 0 || n > 4096) return KVC_ERR_ARG;
+  std::lock_guard<std::mutex> hold(g_prof_lock);
+  g_prof_any.store(n > 0, std::memory_order_release);
   if (g_prof) {
     for (int i = 0; i < g_prof_cap; ++i) {
       hipEventDestroy(g_prof[i].a0); hipEventDestroy(g_prof[i].a1);
@@ -971,12 +987,14 @@ int kvc_profile_begin(int n) {
 }
 
 int kvc_profile_enable(int on) {
+  std::lock_guard<std::mutex> hold(g_prof_lock);
   g_prof_on = on != 0;
   return KVC_OK;
 }
 
 int kvc_profile_collect(float* chunk_ms, float* short_ms, float* combine_ms, int cap, int* count) {
   if (!count || cap < 0) return KVC_ERR_ARG;
+  std::lock_guard<std::mutex> hold(g_prof_lock);
   *count = g_prof_used;
   for (int i = 0; i < g_prof_used && i < cap; ++i) {
     KVC_HIP(hipEventSynchronize(g_prof[i].b1));
@@ -1016,7 +1034,7 @@ int kvc_get_decode_short(const kvc_config* cfg, int* tokens) {
 
 int kvc_set_decode_chunk(int tokens) {
   if (tokens != 0 && (tokens < kMinChunk || tokens > kMaxChunk || tokens % 64 != 0)) return KVC_ERR_ARG;
-  g_chunk_tokens = tokens;
+  g_chunk_tokens.store(tokens, std::memory_order_relaxed);
   return KVC_OK;
 }
 
@@ -1069,6 +1087,15 @@ int kvc_paged_decode(const kvc_config* cfg, const kvc_state* st, const void* q, 
     KVC_LAUNCH_CHECK();
     return KVC_OK;
   }
+  // items <= (slots in the pool) / T + heads, and <= heads * chunks a full row can hold.  A chunk
+  // length picked on the device is T or at least 1.25 / 512 of all tokens, which makes at most
+  // 512 / 1.25 full chunks (512 allowed for).
+  const size_t most_tokens = std::min((size_t)D.N * D.b, (size_t)A.gsel * D.maxb * D.b);   // pool, or the rows of the heads called for
+  const size_t bound_pool = most_tokens / T + (size_t)A.gsel + (A.adapt_T ? 512 : 0);
+  const size_t Tmin = A.adapt_T ? 256 : (size_t)T;
+  const size_t bound_row = (size_t)A.gsel * (((size_t)D.maxb * D.b + Tmin - 1) / Tmin);
+  const size_t grid = bound_pool < bound_row ? bound_pool : bound_row;
+  if (grid > 0x7fffffffull) return KVC_ERR_UNSUPPORTED;   // before anything is launched: the work list stays clean
   if (A.gsel <= kSmallWorklistHeads) {
     hipLaunchKernelGGL(decode_worklist_small_kernel, dim3(1), dim3(1024), 0, s, A);
     KVC_LAUNCH_CHECK();
@@ -1078,15 +1105,6 @@ int kvc_paged_decode(const kvc_config* cfg, const kvc_state* st, const void* q, 
     hipLaunchKernelGGL(decode_items_kernel, dim3((A.gsel + 255) / 256), dim3(256), 0, s, A);
     KVC_LAUNCH_CHECK();
   }
-  // items <= (slots in the pool) / T + heads, and <= heads * chunks a full row can hold.  A chunk
-  // length picked on the device is T or at least 1.25 / 512 of all tokens, which makes at most
-  // 512 / 1.25 full chunks (512 allowed for).
-  const size_t most_tokens = std::min((size_t)D.N * D.b, (size_t)A.gsel * D.maxb * D.b);   // pool, or the rows of the heads called for
-  const size_t bound_pool = most_tokens / T + (size_t)A.gsel + (A.adapt_T ? 512 : 0);
-  const size_t Tmin = A.adapt_T ? 256 : (size_t)T;
-  const size_t bound_row = (size_t)A.gsel * (((size_t)D.maxb * D.b + Tmin - 1) / Tmin);
-  const size_t grid = bound_pool < bound_row ? bound_pool : bound_row;
-  if (grid > 0x7fffffffull) return KVC_ERR_UNSUPPORTED;
   const int gs = A.gsel;   // a head ends in at most one item shorter than a chunk
   if (esz == 1) return D.d == 64 ? launch_tiled_r<1, 64>(A, (int)grid, lds, gs, s) : launch_tiled_r<1, 128>(A, (int)grid, lds, gs, s);
   if (esz == 2) return D.d == 64 ? launch_tiled_r<2, 64>(A, (int)grid, lds, gs, s) : launch_tiled_r<2, 128>(A, (int)grid, lds, gs, s);

@@ -11,7 +11,7 @@
 
 namespace kvc {
 
-enum { SS_PREFIX = 0, SS_REMAIN = 1, SS_CAND = 2, SS_TAKE = 3, SS_FIRSTG = 4 };
+enum { SS_PREFIX = SEG_PREFIX, SS_REMAIN = SEG_REMAIN, SS_CAND = SEG_CAND, SS_TAKE = SEG_TAKE, SS_FIRSTG = SEG_FIRSTG };
 
 // ---------------------------------------------------------------------------
 // block keys
@@ -57,38 +57,6 @@ __global__ void __launch_bounds__(256) block_key_kernel(Dims D, int key_mode, co
 // ---------------------------------------------------------------------------
 // selection
 // ---------------------------------------------------------------------------
-
-__global__ void __launch_bounds__(256) select_init_kernel(Dims D, const int32_t* __restrict__ seg_offsets,
-                                                          int nseg, int32_t* __restrict__ seq_seg,
-                                                          int32_t* __restrict__ seg_hist,
-                                                          int32_t* __restrict__ seg_state,
-                                                          int32_t* __restrict__ evict_count,
-                                                          int32_t* __restrict__ selected,
-                                                          int32_t* __restrict__ header) {
-  const int i = blockIdx.x * 256 + threadIdx.x;
-  if (i < D.S) {
-    int sg = i;
-    if (seg_offsets) {  // last segment whose first sequence is <= i
-      int lo = 0, hi = nseg;
-      while (hi - lo > 1) { int mid = (lo + hi) >> 1; if (seg_offsets[mid] <= i) lo = mid; else hi = mid; }
-      sg = lo;
-    }
-    seq_seg[i] = sg;
-  }
-  if (i < nseg * 256) seg_hist[i] = 0;
-  if (i < nseg) {
-    selected[i] = 0;
-    for (int k = 0; k < 8; ++k) seg_state[i * 8 + k] = 0;
-    const int first_seq = seg_offsets ? seg_offsets[i] : i;
-    seg_state[i * 8 + SS_FIRSTG] = first_seq * D.Lyr * D.Hk;
-    if (seg_offsets) {
-      const int a = seg_offsets[i], b2 = seg_offsets[i + 1];
-      bool bad = a > b2 || (i == 0 && a != 0) || (i == nseg - 1 && b2 != D.S);
-      if (bad) atomicOr(&header[HW_SCRATCH0], EB_ARG);
-    }
-  }
-  if (i < D.G) evict_count[i] = 0;
-}
 
 __global__ void __launch_bounds__(256) zero_bytes_kernel(uint8_t* p, size_t n) {
   size_t i = ((size_t)blockIdx.x * 256 + threadIdx.x) * 16;
@@ -417,7 +385,7 @@ int kvc_evict_select(const kvc_config* cfg, const kvc_state* st, const float* bl
   int32_t* seq_seg = W.held;  // [S] fits in the [G] array
   const int gw = (D.G + 3) / 4;
   int n_init = D.G > nseg * 256 ? D.G : nseg * 256;
-  hipLaunchKernelGGL(select_init_kernel, dim3((n_init + 255) / 256), dim3(256), 0, s, D, seg_offsets, nseg,
+  hipLaunchKernelGGL(segments_init_kernel, dim3((n_init + 255) / 256), dim3(256), 0, s, D, seg_offsets, nseg,
                      seq_seg, W.seg_hist, W.seg_state, evict_count, selected, W.header);
   KVC_LAUNCH_CHECK();
   const size_t nflag = (size_t)D.G * D.maxb;

@@ -19,42 +19,11 @@
 
 namespace kvc {
 
-enum { RS_PREFIX = 0, RS_REMAIN = 1, RS_CAND = 2, RS_TAKE = 3, RS_FIRSTG = 4 };
+enum { RS_PREFIX = SEG_PREFIX, RS_REMAIN = SEG_REMAIN, RS_CAND = SEG_CAND, RS_TAKE = SEG_TAKE, RS_FIRSTG = SEG_FIRSTG };
 
 __device__ __forceinline__ uint32_t metric_bits(float f) {
   const uint32_t k = __float_as_uint(f);
   return k == 0x80000000u ? 0u : k;  // -0 orders as +0
-}
-
-__global__ void __launch_bounds__(256) rank_init_kernel(Dims D, const int32_t* __restrict__ seg_offsets,
-                                                        int nseg, int32_t* __restrict__ seq_seg,
-                                                        int32_t* __restrict__ seg_hist,
-                                                        int32_t* __restrict__ seg_state,
-                                                        int32_t* __restrict__ evict_rows,
-                                                        int32_t* __restrict__ selected,
-                                                        int32_t* __restrict__ header) {
-  const int i = blockIdx.x * 256 + threadIdx.x;
-  if (i < D.S) {
-    int sg = i;
-    if (seg_offsets) {
-      int lo = 0, hi = nseg;
-      while (hi - lo > 1) { const int mid = (lo + hi) >> 1; if (seg_offsets[mid] <= i) lo = mid; else hi = mid; }
-      sg = lo;
-    }
-    seq_seg[i] = sg;
-  }
-  if (i < nseg * 256) seg_hist[i] = 0;
-  if (i < nseg) {
-    selected[i] = 0;
-    for (int k = 0; k < 8; ++k) seg_state[i * 8 + k] = 0;
-    const int first_seq = seg_offsets ? seg_offsets[i] : i;
-    seg_state[i * 8 + RS_FIRSTG] = first_seq * D.Lyr * D.Hk;
-    if (seg_offsets) {
-      const int a = seg_offsets[i], b2 = seg_offsets[i + 1];
-      if (a > b2 || (i == 0 && a != 0) || (i == nseg - 1 && b2 != D.S)) atomicOr(&header[HW_SCRATCH0], EB_ARG);
-    }
-  }
-  if (i < D.G) evict_rows[i] = 0;
 }
 
 // A head's metrics as ordered bit patterns, four strided elements per thread at a time: the four
@@ -410,7 +379,7 @@ int kvc_evict_rank_select(const kvc_config* cfg, const kvc_state* st, const int3
   hipStream_t s = (hipStream_t)stream;
   int32_t* seq_seg = W.held;
   const int n_init = D.G > nseg * 256 ? D.G : nseg * 256;
-  hipLaunchKernelGGL(rank_init_kernel, dim3((n_init + 255) / 256), dim3(256), 0, s, D, seg_offsets, nseg, seq_seg,
+  hipLaunchKernelGGL(segments_init_kernel, dim3((n_init + 255) / 256), dim3(256), 0, s, D, seg_offsets, nseg, seq_seg,
                      W.seg_hist, W.seg_state, evict_rows, selected, W.header);
   KVC_LAUNCH_CHECK();
   for (int pass = 0; pass < 4; ++pass) {
@@ -463,10 +432,10 @@ int kvc_compact_rank(const kvc_config* cfg, const kvc_state* st, const int32_t* 
     // LDS (up to 36864 tokens; one such workgroup per CU is all there is to run anyway)
     const size_t head_tokens = (size_t)D.maxb * D.b;
     const int lds_tokens = (int)(head_tokens < 36864 ? head_tokens : 36864);
-    static bool told = false;
-    if (!told) {
+    static std::atomic<bool> told{false};   // setting it twice is harmless: several host threads may race here
+    if (!told.load(std::memory_order_acquire)) {
       KVC_HIP(hipFuncSetAttribute((const void*)rank_compact_kernel<1024>, hipFuncAttributeMaxDynamicSharedMemorySize, 36864 * 4));
-      told = true;
+      told.store(true, std::memory_order_release);
     }
     hipLaunchKernelGGL(rank_compact_kernel<1024>, dim3(D.G), dim3(1024), (size_t)lds_tokens * 4, s, D, (char*)st->k_cache,
                        (char*)st->v_cache, st->metric, st->pos, st->block_table, st->ctx_len, st->free_map, evict_rows,

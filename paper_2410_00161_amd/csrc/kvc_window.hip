@@ -443,12 +443,13 @@ static int launch_window(const WindowArgs& W, int grid, hipStream_t s) {
   const size_t lds = q_bytes + (size_t)kWinWaves * NT * window_pairs_per_tile(M, NT) * 8 + tab;
   const size_t lds2 = q_bytes + rows * 4 + tab;
   static_assert((size_t)kWinWaves * rows * 2 * 4 <= q_bytes, "pairs fit where Q was");
-  static size_t allowed = 0;   // above the default cap a kernel must be told how much it may take
-  if (lds > 64 * 1024 && lds > allowed) {   // (lds >= lds2; the block-id array grows as blocks shrink)
+  static std::atomic<size_t> allowed{0};   // above the default cap a kernel must be told how much it may take
+  if (lds > 64 * 1024 && lds > allowed.load(std::memory_order_acquire)) {   // (lds >= lds2; the block-id array grows as blocks shrink)
     KVC_HIP(hipFuncSetAttribute((const void*)window_stats_kernel<M, NT>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     KVC_HIP(hipFuncSetAttribute((const void*)window_sum_kernel<M, NT, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     KVC_HIP(hipFuncSetAttribute((const void*)window_sum_kernel<M, NT, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    allowed = lds;
+    size_t seen = allowed.load(std::memory_order_relaxed);
+    while (seen < lds && !allowed.compare_exchange_weak(seen, lds, std::memory_order_release)) {}
   }
   hipLaunchKernelGGL((window_stats_kernel<M, NT>), dim3(grid), dim3(kWinThreads), lds, s, W);
   KVC_LAUNCH_CHECK();

@@ -8,8 +8,9 @@ from . import binding as B
 
 
 class KvcSession:
-    def __init__(self, cache, metric_mode=B.KVC_L2, device="cuda:0"):
-        """cache: workloads.Cache (any device); tensors are moved to `device`."""
+    def __init__(self, cache, metric_mode=B.KVC_L2, device="cuda:0", with_pos=True):
+        """cache: workloads.Cache (any device); tensors are moved to `device`.  with_pos=False
+        hands the library a state whose `pos` is NULL (logical indices not tracked)."""
         self.device = torch.device(device)
         sh = cache.shape
         self.shape = sh
@@ -20,8 +21,8 @@ class KvcSession:
                                  sh.kv_dtype, metric_mode)
         for name in ("k_cache", "v_cache", "metric", "pos", "block_table", "ctx_len", "free_map"):
             setattr(c, name, getattr(c, name).contiguous())
-        self.st = B.make_state(c.k_cache, c.v_cache, c.metric, c.pos, c.block_table, c.ctx_len,
-                               c.free_map)
+        self.st = B.make_state(c.k_cache, c.v_cache, c.metric, c.pos if with_pos else None, c.block_table,
+                               c.ctx_len, c.free_map)
         torch.cuda.set_device(self.device)
         self.ws = B.new_workspace(self.cfg, self.device)
         G, maxb = sh.G, sh.max_blocks_per_head

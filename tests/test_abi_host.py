@@ -14,7 +14,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def declared_functions():
-    src = open(os.path.join(ROOT, "include", "kvc.h")).read()
+    src = "".join(open(os.path.join(ROOT, "include", h)).read() for h in sorted(os.listdir(os.path.join(ROOT, "include"))))
     src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
     return sorted(set(re.findall(r"\b(kvc_[a-z_]+)\s*\(", src)))
 
@@ -48,11 +48,20 @@ def test_validate_and_workspace_size():
         assert B.kvc_workspace_bytes(c) == 0
     assert B.kvc_validate(good_cfg(group_size=32)) == B.KVC_ERR_UNSUPPORTED
     assert B.kvc_validate(good_cfg(head_dim=100, kv_dtype="bf16")) == B.KVC_ERR_UNSUPPORTED
+    # block sizes are powers of two: the compaction, rank-schedule and window kernels index a slot
+    # as (block id << log2 b) + (j & (b - 1)), so anything else is refused at the boundary
+    for b in (3, 24, 48, 2048):
+        c = good_cfg(block_size=b)
+        assert B.kvc_validate(c) == B.KVC_ERR_UNSUPPORTED, b
+        assert B.kvc_workspace_bytes(c) == 0
+    for b in (1, 2, 4, 8, 16, 32, 64, 128):
+        assert B.kvc_validate(good_cfg(block_size=b)) == B.KVC_OK, b
 
 
 def test_status_strings_and_chunk_knob():
-    seen = {B.status_string(c) for c in range(8)}
-    assert len(seen) == 8 and "ok" in seen
+    seen = {B.status_string(c) for c in (0, 1, 2, 3, 5, 6, 7)}
+    assert len(seen) == 7 and "ok" in seen and "unknown status" not in seen
+    assert B.status_string(4) == "unknown status"   # no such code
     assert B.status_string(99) == "unknown status"
     L = B.lib()
     assert L.kvc_set_decode_chunk(100) == B.KVC_ERR_ARG

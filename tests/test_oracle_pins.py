@@ -440,21 +440,121 @@ def test_select_errors_and_clamp():
 
 # --- compaction ---------------------------------------------------------------
 
+def one_head_state(C, b, rng, spare=3):
+    """One head instance of C KVs over a shuffled pool; the K row, V row, metric and pos of
+    logical slot j all carry j, so that after a compaction every slot says where its KV came
+    from.  Slots past C (the rest of the last block) carry -7."""
+    nb = -(-C // b)
+    N = nb + spare
+    ids = rng.permutation(N)[:nb]
+    kc = np.full((N, b, 2), -7.0); vc = np.full((N, b, 2), -7.0)
+    M = np.full((N, b), -7.0); pos = np.full((N, b), -7)
+    for j in range(C):
+        n, o = ids[j // b], j % b
+        kc[n, o] = (j, 1000 + j); vc[n, o] = (2000 + j, 3000 + j); M[n, o] = j; pos[n, o] = j
+    table = -np.ones((1, nb + 1), dtype=np.int64); table[0, :nb] = ids
+    free = np.ones(N, dtype=np.uint8); free[ids] = 0
+    return O.State(1, 1, 1, 1, 2, b, N, nb + 1, kc, vc, M, pos, table, [C], free), ids
+
+
+def logical_sources(st):
+    """The original logical index of the KV that sits in each logical slot now; checks that
+    key, value, metric and pos of a slot all moved together."""
+    n, o = O.slots_of(st, 0)
+    src = st.pos[n, o]
+    np.testing.assert_array_equal(st.k_cache[n, o][:, 0], src)
+    np.testing.assert_array_equal(st.k_cache[n, o][:, 1], 1000 + src)
+    np.testing.assert_array_equal(st.v_cache[n, o][:, 0], 2000 + src)
+    np.testing.assert_array_equal(st.v_cache[n, o][:, 1], 3000 + src)
+    np.testing.assert_array_equal(st.metric[n, o], src)
+    return [int(x) for x in src]
+
+
+def two_pointer_by_hand(w):
+    """Algorithm 1 restated inside the test, independently of the oracle: j walks down from the
+    last KV through the eviction range (the last n_ev slots); every kept KV met there goes to
+    the evicted slot that i, walking up from slot 0, finds next.  Returns the logical order
+    after the moves (content of slots 0 .. T-1)."""
+    C = len(w); n_ev = int(np.sum(w)); T = C - n_ev
+    content = list(range(C))
+    i = 0
+    for j in range(C - 1, T - 1, -1):
+        if w[j]:
+            continue
+        while not w[i]:
+            i += 1
+        assert i < T
+        content[i] = j
+        i += 1
+    return content[:T]
+
+
+def test_movecache_pairing_order_by_hand():
+    """Algorithm 1 on a case worked by hand.  b = 2, C = 6, the head's first block (slots 0, 1)
+    is evicted: the eviction range is slots 4, 5; j starts at 5, so slot 5 moves first and lands
+    in the first hole i finds, slot 0; then slot 4 goes to slot 1.  Logical order afterwards:
+    5, 4, 2, 3.  (The reversed pairing, movers ascending, would give 4, 5, 2, 3.)"""
+    rng = np.random.default_rng(0)
+    for via in ("flags", "slots"):
+        st, ids = one_head_state(6, 2, rng)
+        if via == "flags":
+            flag = np.zeros((1, st.max_blocks), dtype=np.uint8); flag[0, 0] = 1
+            freed = O.compact(st, flag, [1])
+        else:
+            freed = O.compact_slots(st, [np.array([1, 1, 0, 0, 0, 0], dtype=bool)])
+        assert freed == 1 and int(st.lens()[0]) == 4
+        assert logical_sources(st) == [5, 4, 2, 3]
+        # the freed block is the LAST one of the row (the eviction range), not the flagged one
+        assert st.table()[0].tolist() == [ids[0], ids[1], -1, -1]
+        assert st.free_map[ids[2]] == 1 and st.free_map[ids[0]] == 0
+    # a mask that is not block-aligned: slots 1 and 2 evicted of 7 (b = 4).  Range = slots 5, 6;
+    # 6 -> hole 1, 5 -> hole 2: order 0, 6, 5, 3, 4; T = 5 still needs both blocks.
+    st, ids = one_head_state(7, 4, rng)
+    assert O.compact_slots(st, [np.array([0, 1, 1, 0, 0, 0, 0], dtype=bool)]) == 0
+    assert logical_sources(st) == [0, 6, 5, 3, 4]
+    assert st.table()[0, :2].tolist() == [ids[0], ids[1]]
+    # kept KVs inside the range that are themselves evicted are skipped: evict 0 and 5 of 6:
+    # range = slots 4, 5; 5 is evicted, 4 -> hole 0: order 4, 1, 2, 3
+    st, ids = one_head_state(6, 2, rng)
+    O.compact_slots(st, [np.array([1, 0, 0, 0, 0, 1], dtype=bool)])
+    assert logical_sources(st) == [4, 1, 2, 3]
+
+
 @pytest.mark.parametrize("seed", range(6))
-def test_compact_pairs_match_the_two_pointer_loop(seed):
-    """Closed form of MoveCache == the sequential two-pointer loop, for masks
-    that are block-aligned and masks that are not."""
+def test_compact_moves_match_the_two_pointer_loop(seed):
+    """The oracle's compaction (the closed form: k-th kept KV from the top of the range into
+    the k-th evicted slot from the bottom), run on real states through O.compact_slots and
+    O.compact, leaves in every slot what Algorithm 1's two-pointer walk leaves there - checked
+    slot by slot against the walk restated in this test and against
+    O.movecache_sequential's (src, dst) pairs, for masks that are block-aligned and masks that
+    are not."""
     rng = np.random.default_rng(seed)
-    for _ in range(40):
+    for trial in range(40):
+        b = int(rng.choice([1, 2, 4, 8]))
         C = int(rng.integers(1, 60))
-        w = rng.random(C) < rng.random()
-        n_ev = int(w.sum())
-        T = C - n_ev
-        holes = [i for i in range(T) if w[i]]
-        movers = [j for j in range(C - 1, T - 1, -1) if not w[j]]
-        assert len(holes) == len(movers)
-        seq = O.movecache_sequential(w, C, n_ev)
-        assert seq == list(zip(movers, holes))
+        nb = -(-C // b)
+        if trial % 2 == 0:      # any slot mask
+            w = rng.random(C) < rng.random()
+            st, ids = one_head_state(C, b, rng)
+            O.compact_slots(st, [w])
+        else:                   # whole blocks, as the block selection flags them
+            fl = rng.random(nb) < rng.random()
+            w = fl[np.arange(C) // b]
+            st, ids = one_head_state(C, b, rng)
+            flag = np.zeros((1, st.max_blocks), dtype=np.uint8); flag[0, :nb] = fl
+            O.compact(st, flag, [int(fl.sum())])
+        n_ev = int(w.sum()); T = C - n_ev
+        assert int(st.lens()[0]) == T
+        got = logical_sources(st)
+        assert got == two_pointer_by_hand(w)
+        want = list(range(C))
+        for src, dst in O.movecache_sequential(w, C, n_ev):
+            want[dst] = src
+        assert got == want[:T]
+        # the blocks freed are the row's last ones
+        nb2 = -(-T // b)
+        assert st.table()[0, :nb2].tolist() == list(ids[:nb2]) and (st.table()[0, nb2:] == -1).all()
+        assert sorted(np.flatnonzero(st.free_map == 0)) == sorted(ids[:nb2])
 
 
 @pytest.mark.parametrize("protect", [0, 1])
@@ -539,6 +639,56 @@ def test_scheduling_helpers_by_hand():
     check_allocator_invariants(st)
     with pytest.raises(O.OracleError):
         O.prefill_alloc(st, [1000, 0])                         # row too short / pool too small
+
+
+def test_count_blocks_over_a_layer_range_by_hand():
+    """One sequence of three layers, two heads each, b = 4.  Lengths 4, 3 | 8, 0 | 5, 12 with
+    1, 1 | 2, 0 | 2, 3 blocks held: the heads whose blocks are all full (a head with no block
+    counts as full) are layer 0 head 0, layer 1 both heads, layer 2 head 1.  'needed' counts
+    those of the chosen layers only; 'held' is over all layers whatever the range."""
+    S, Lyr, Hk, b, N, maxb = 1, 3, 2, 4, 12, 3
+    table = -np.ones((6, maxb), dtype=np.int64)
+    table[0, :1] = [0]; table[1, :1] = [1]; table[2, :2] = [2, 3]
+    table[4, :2] = [4, 5]; table[5, :3] = [6, 7, 8]
+    lens = np.array([4, 3, 8, 0, 5, 12])
+    free = np.ones(N, dtype=np.uint8); free[:9] = 0
+    st = O.State(S, Lyr, Hk, 1, 2, b, N, maxb, np.zeros((N, b, 2)), np.zeros((N, b, 2)), np.zeros((N, b)),
+                 np.zeros((N, b)), table, lens, free)
+    for (l0, l1), want in {(0, 3): 4, (0, 1): 1, (1, 2): 2, (2, 3): 1, (1, 3): 3, (0, 2): 3}.items():
+        needed, held = O.count_blocks(st, l0, l1)
+        assert list(needed) == [want], (l0, l1)
+        assert list(held) == [9]
+
+
+def test_append_with_caller_positions_by_hand():
+    """Two sequences, one layer, one head each, b = 2.  Sequence 0 holds 2 KVs (its block is
+    full), sequence 1 holds 3 (blocks 4 and 1, second half-empty).  Appending with
+    new_pos = [40, 7]: sequence 0 takes the lowest free block (0) and writes slot (0, 0);
+    sequence 1 writes slot (1, 1); the new slots carry the caller's positions, not the heads'
+    old lengths, and nothing else of pos changes.  With new_pos = None the old lengths go in."""
+    S, Lyr, Hk, b, N, maxb, d = 2, 1, 1, 2, 6, 3, 2
+    def fresh():
+        table = -np.ones((2, maxb), dtype=np.int64)
+        table[0, :1] = [2]; table[1, :2] = [4, 1]
+        free = np.ones(N, dtype=np.uint8); free[[2, 4, 1]] = 0
+        pos = np.arange(N * b).reshape(N, b) + 100
+        return O.State(S, Lyr, Hk, 1, d, b, N, maxb, np.zeros((N, b, d)), np.zeros((N, b, d)),
+                       np.ones((N, b)), pos, table, [2, 3], free)
+    k = np.array([[1.0, 2.0], [3.0, 4.0]]).reshape(S, Lyr, Hk, d)
+    v = -k
+    st = fresh()
+    pos0 = st.pos.copy()
+    O.append(st, k, v, new_pos=[40, 7])
+    assert st.table()[0].tolist() == [2, 0, -1] and st.table()[1].tolist() == [4, 1, -1]
+    assert list(st.lens()) == [3, 4] and st.free_map.tolist() == [0, 0, 0, 1, 0, 1]
+    assert st.pos[0, 0] == 40 and st.pos[1, 1] == 7
+    changed = st.pos != pos0
+    assert int(changed.sum()) == 2 and changed[0, 0] and changed[1, 1]
+    np.testing.assert_array_equal(st.k_cache[0, 0], [1.0, 2.0]); np.testing.assert_array_equal(st.v_cache[1, 1], [-3.0, -4.0])
+    assert st.metric[0, 0] == 0.0 and st.metric[1, 1] == 0.0 and st.metric[1, 0] == 1.0
+    st = fresh()
+    O.append(st, k, v)
+    assert st.pos[0, 0] == 2 and st.pos[1, 1] == 3
 
 
 def test_compression_batch_by_hand_and_against_a_prefix_search():
