@@ -202,6 +202,18 @@ int kvc_paged_decode(const kvc_config* cfg, const kvc_state* st, const void* q, 
                      int layer_begin, int layer_end, int accumulate_metric,
                      void* ws, void* stream);
 
+/* kvc_paged_decode for callers that cannot allocate device memory or bring a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, kernels and results as kvc_paged_decode, without `ws`: the temporaries live in a
+ * fixed array of KVC_STATIC_SCRATCH_BYTES inside the library (every GPU the library runs on
+ * holds one until the process ends).  KVC_ERR_UNSUPPORTED when kvc_workspace_bytes(cfg) exceeds
+ * that size - such caches go through kvc_paged_decode with a caller's workspace.  Allocates
+ * nothing and calls no allocating routine.  All calls on one GPU share the array: two calls
+ * that overlap there (different streams, different threads) race; order them.  Asynchronous. */
+#define KVC_STATIC_SCRATCH_BYTES (32u << 20)
+int kvc_paged_decode_static(const kvc_config* cfg, const kvc_state* st, const void* q, float* out,
+                            int layer_begin, int layer_end, int accumulate_metric, void* stream);
+
 /* Block-level reduction of the metric ("Evicting from a Paged KV Cache": the
  * requirement orders blocks by the SUM of their KVs' metrics; the matrix the
  * same section builds takes the last column of a row, its MAX).  block_key

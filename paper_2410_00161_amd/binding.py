@@ -24,7 +24,7 @@ KVC_ASYNC = 1
 
 EXPORTS = [
     "kvc_workspace_bytes", "kvc_validate", "kvc_status_string", "kvc_workspace_reset",
-    "kvc_poll_status", "kvc_check_state", "kvc_block_alloc", "kvc_block_free", "kvc_append", "kvc_paged_decode",
+    "kvc_poll_status", "kvc_check_state", "kvc_block_alloc", "kvc_block_free", "kvc_append", "kvc_paged_decode", "kvc_paged_decode_static",
     "kvc_metric_reduce", "kvc_evict_select", "kvc_compact", "kvc_set_decode_chunk",
     "kvc_get_decode_chunk", "kvc_get_decode_short", "kvc_evict_rank_select", "kvc_compact_rank", "kvc_window_metric", "kvc_query_block_metric", "kvc_count_blocks", "kvc_prefill_alloc", "kvc_preempt", "kvc_compression_batch",
     "kvc_profile_begin", "kvc_profile_enable", "kvc_profile_collect", "kvc_stream_read_probe",
@@ -72,6 +72,7 @@ def lib() -> C.CDLL:
         L.kvc_block_free.argtypes = [cfgp, stp, P, C.POINTER(C.c_int64), P, P, I]
         L.kvc_append.argtypes = [cfgp, stp, P, P, P, I, I, P, P, I]
         L.kvc_paged_decode.argtypes = [cfgp, stp, P, P, I, I, I, P, P]
+        L.kvc_paged_decode_static.argtypes = [cfgp, stp, P, P, I, I, I, P]
         L.kvc_metric_reduce.argtypes = [cfgp, stp, P, I, P, P]
         L.kvc_evict_select.argtypes = [cfgp, stp, P, P, P, I, I, P, P, P, P, P, I]
         L.kvc_compact.argtypes = [cfgp, stp, P, P, P, P, P, I]
@@ -200,6 +201,15 @@ def kvc_paged_decode(cfg, st, q, out, layer_begin, layer_end, accumulate_metric,
     _check(lib().kvc_paged_decode(C.byref(cfg), C.byref(st), _ptr(q), _ptr(out, torch.float32),
                                   layer_begin, layer_end, int(accumulate_metric), _ptr(ws),
                                   _stream(stream)), "kvc_paged_decode")
+
+
+KVC_STATIC_SCRATCH_BYTES = 32 << 20
+
+
+def kvc_paged_decode_static(cfg, st, q, out, layer_begin, layer_end, accumulate_metric, stream=None):
+    _check(lib().kvc_paged_decode_static(C.byref(cfg), C.byref(st), _ptr(q), _ptr(out, torch.float32),
+                                         layer_begin, layer_end, int(accumulate_metric), _stream(stream)),
+           "kvc_paged_decode_static")
 
 
 def kvc_metric_reduce(cfg, st, block_key, ws, stream=None, key_mode=KVC_KEY_SUM):

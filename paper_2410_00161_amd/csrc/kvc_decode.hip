@@ -1038,14 +1038,24 @@ int kvc_set_decode_chunk(int tokens) {
   return KVC_OK;
 }
 
-int kvc_paged_decode(const kvc_config* cfg, const kvc_state* st, const void* q, float* out,
-                     int layer_begin, int layer_end, int accumulate_metric, void* ws, void* stream) {
-  int rc = validate(cfg, st);
+}  // extern "C"
+
+// What both decode entry points check on the host before anything is launched.
+static int decode_args_check(const kvc_config* cfg, const kvc_state* st, const void* q, const float* out,
+                             int layer_begin, int layer_end) {
+  const int rc = validate(cfg, st);
   if (rc != KVC_OK) return rc;
-  if (!q || !out || !ws || ((uintptr_t)ws & 255)) return KVC_ERR_ARG;
-  if (((uintptr_t)q & 15) || ((uintptr_t)out & 15)) return KVC_ERR_ARG;
+  if (!q || !out || ((uintptr_t)q & 15) || ((uintptr_t)out & 15)) return KVC_ERR_ARG;
+  if (layer_begin < 0 || layer_end > cfg->num_layers || layer_begin >= layer_end) return KVC_ERR_ARG;
+  return KVC_OK;
+}
+
+static int paged_decode_impl(const kvc_config* cfg, const kvc_state* st, const void* q, float* out,
+                             int layer_begin, int layer_end, int accumulate_metric, void* ws, void* stream) {
+  int rc = decode_args_check(cfg, st, q, out, layer_begin, layer_end);
+  if (rc != KVC_OK) return rc;
+  if (!ws || ((uintptr_t)ws & 255)) return KVC_ERR_ARG;
   Dims D = dims_of(cfg);
-  if (layer_begin < 0 || layer_end > D.Lyr || layer_begin >= layer_end) return KVC_ERR_ARG;
   Workspace W = carve(D, ws);
   hipStream_t s = (hipStream_t)stream;
 
@@ -1109,6 +1119,55 @@ int kvc_paged_decode(const kvc_config* cfg, const kvc_state* st, const void* q, 
   if (esz == 1) return D.d == 64 ? launch_tiled_r<1, 64>(A, (int)grid, lds, gs, s) : launch_tiled_r<1, 128>(A, (int)grid, lds, gs, s);
   if (esz == 2) return D.d == 64 ? launch_tiled_r<2, 64>(A, (int)grid, lds, gs, s) : launch_tiled_r<2, 128>(A, (int)grid, lds, gs, s);
   return D.d == 64 ? launch_tiled_r<4, 64>(A, (int)grid, lds, gs, s) : launch_tiled_r<4, 128>(A, (int)grid, lds, gs, s);
+}
+
+// ---- the decode for callers that cannot allocate --------------------------------------------
+// The temporaries of kvc_paged_decode (work items, per-chunk partial results, the 16-bit exps of
+// split heads) in a fixed array of this library's own instead of a caller's workspace.  Every
+// GPU holds its own copy of the array at its own address; host code never uses the array's name
+// as an address, only what hipGetSymbolAddress returned for the device that is current.
+static __device__ __align__(256) unsigned char scratch[KVC_STATIC_SCRATCH_BYTES];
+
+static constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_lock;
+static void* g_scratch_ptr[kMaxDevices] = {};   // per device, filled on the first call there
+
+static int scratch_of_current_device(void** out) {
+  int dev = -1;
+  KVC_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return KVC_ERR_UNSUPPORTED;
+  std::lock_guard<std::mutex> hold(g_scratch_lock);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    KVC_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p || ((uintptr_t)p & 255)) return KVC_ERR_HIP;
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return KVC_OK;
+}
+
+extern "C" {
+
+int kvc_paged_decode(const kvc_config* cfg, const kvc_state* st, const void* q, float* out,
+                     int layer_begin, int layer_end, int accumulate_metric, void* ws, void* stream) {
+  return paged_decode_impl(cfg, st, q, out, layer_begin, layer_end, accumulate_metric, ws, stream);
+}
+
+int kvc_paged_decode_static(const kvc_config* cfg, const kvc_state* st, const void* q, float* out,
+                            int layer_begin, int layer_end, int accumulate_metric, void* stream) {
+  int rc = decode_args_check(cfg, st, q, out, layer_begin, layer_end);
+  if (rc != KVC_OK) return rc;
+  if (carve(dims_of(cfg), nullptr).bytes > (size_t)KVC_STATIC_SCRATCH_BYTES) return KVC_ERR_UNSUPPORTED;
+  void* ws = nullptr;
+  rc = scratch_of_current_device(&ws);
+  if (rc != KVC_OK) return rc;
+  // The array keeps what the last call left, possibly a call with another config: the header words
+  // (item counts, work-list cursors) start from zero again.  A fill kernel, not a memset, so that
+  // the call may be recorded into a HIP graph.
+  hipLaunchKernelGGL(zero_words_kernel, dim3((HW_WORDS + 63) / 64), dim3(64), 0, (hipStream_t)stream, (int32_t*)ws, HW_WORDS);
+  KVC_LAUNCH_CHECK();
+  return paged_decode_impl(cfg, st, q, out, layer_begin, layer_end, accumulate_metric, ws, stream);
 }
 
 }  // extern "C"
