@@ -4,12 +4,19 @@
 A step = one pass of the path over the batch: append the new token's k, v for
 every (sequence, layer, KV head), then one paged decode over all layers with
 metric accumulation; every --evict-every steps a compression round (block keys
--> selection -> compaction) returns as many blocks as were appended since the
-last round, so the cache stays at its compression rate.
+-> selection -> compaction).  The round returns as many blocks as were appended
+since the last one, so the cache stays at its compression rate, or, with
+--evict-frac, that fraction of every sequence's blocks.
 
-Workload at N = 1: the Llama-3.1-8B-shaped decode (32 layers, 32 q / 8 KV
-heads, d = 128, bf16, b = 16, 64 sequences of 8192 prompt tokens, per-head
-retention log-uniform with mean 8x), synthetic data, inputs resident in HBM.
+Workload at N = 1 (the headline): the Llama-3.1-8B-shaped decode (32 layers,
+32 q / 8 KV heads, d = 128, bf16, b = 16, 64 sequences of 8192 prompt tokens,
+per-head retention log-uniform with mean 8x), synthetic data, inputs resident
+in HBM.  The default run then measures, each as a record under "other_configs":
+the same workload on a fragmented pool, the 256 x 32768 / 64x configuration with
+10 % rounds, and the Llama-3.1-70B shape at 16 x 131072.  Every configuration
+ends with one decode step that is checked against the CPU oracle on a sample of
+head instances, plus allocator and metric invariants over the whole cache on the
+device ("parity_sample").
 
 Prints ONE JSON line.  value = algorithmic decode bytes moved per second over
 the whole timed region (append and compression rounds included in the time).
@@ -25,6 +32,8 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+TOL = 2e-3
 
 
 def algorithmic_bytes_per_kv(shape):
@@ -43,161 +52,290 @@ def read_traffic_note(name):
     return None
 
 
-def cpu_baseline(sess, q, shape, n_heads, seed, budget_s=12.0):
-    """Times the CPU oracle, as it stands, on a sample of head instances."""
+# ---------------------------------------------------------------------------
+# CPU oracle baseline: the sample is split over worker processes, one per host core
+# ---------------------------------------------------------------------------
+
+def _cpu_worker(job):
+    """Runs in a worker process: whole decode steps (with metric accumulation and block keys) of
+    the CPU oracle over this worker's share of the sampled head instances until the time budget is
+    used.  Numpy only; BLAS kept to one thread per worker."""
     import numpy as np
-    import torch
     from threadpoolctl import threadpool_limits
     from oracle import kvc_oracle as O
-    from paper_2410_00161_amd import workloads as W
-    sys.path.insert(0, os.path.join(ROOT, "tests"))
-    from helpers import oracle_state
-    g = torch.Generator().manual_seed(seed)
-    heads = torch.randperm(shape.G, generator=g)[:n_heads].tolist()
-    small, q_small = W.gather_heads(sess.cache, heads, q)
-    st = oracle_state(small)
+    dims, arrays, q, budget_s = job
+    st = O.State(*dims, *arrays)
     kvs = int(st.lens().sum())
     reps, dt = 0, 0.0
     with threadpool_limits(limits=1):
-        while dt < budget_s:                      # whole decode steps until the time budget is used
+        while dt < budget_s:
             t0 = time.perf_counter()
-            O.paged_decode(st, q_small.double().numpy())
-            key, _ = O.block_keys(st)
+            O.paged_decode(st, q)
+            O.block_keys(st)
             dt += time.perf_counter() - t0
             reps += 1
-    gbs = reps * kvs * algorithmic_bytes_per_kv(shape) / dt / 1e9
-    return {"value": gbs, "unit": "GB/s", "cores": 1, "kind": "oracle",
-            "sample": f"{n_heads} of {shape.G} head instances ({kvs} KVs) x {reps} decode steps with "
-                      f"metric accumulation + block keys, {dt:.1f} s, numpy fp64 oracle, BLAS limited to 1 thread"}
+    return reps, kvs, dt
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=64)
-    ap.add_argument("--warmup", type=int, default=8)
-    ap.add_argument("--evict-every", type=int, default=16)
-    ap.add_argument("--num-seqs", type=int, default=64)
-    ap.add_argument("--prompt", type=int, default=8192)
-    ap.add_argument("--rho", type=float, default=8.0, help="mean compression rate")
-    ap.add_argument("--placement", default="fresh", choices=["fresh", "fragmented"])
-    ap.add_argument("--chunk", type=int, default=0, help="decode chunk tokens (0 = library default)")
-    ap.add_argument("--cpu-heads", type=int, default=1024, help="head instances timed on the CPU oracle (0 = skip)")
-    ap.add_argument("--workload", default="llama8b", choices=["llama8b", "llama70b"])
-    ap.add_argument("--block-size", type=int, default=16, choices=[16, 32, 64],
-                    help="variant (llama8b workload): tokens per cache block")
-    ap.add_argument("--kv-dtype", default="bf16", choices=["bf16", "fp8"],
-                    help="variant: K and V stored as OCP e4m3 bytes (queries stay bf16)")
-    ap.add_argument("--evict-mode", default="block", choices=["block", "rank"],
-                    help="block: physical blocks by summed metric; rank: the paper's rank-block schedule")
-    ap.add_argument("--uniform", action="store_true", help="diagnostic: every head holds prompt/rho KVs")
-    ap.add_argument("--no-metric", action="store_true", help="diagnostic: decode without metric accumulation")
-    ap.add_argument("--per-layer-steps", type=int, default=4,
-                    help="extra untimed-region steps that call the decode once per layer (0 = skip)")
-    ap.add_argument("--all-queries-block", type=int, default=1024, choices=[32, 64, 256, 1024],
-                    help="queries per call when the prefill-end probe gathers the metric over all prompt queries")
-    ap.add_argument("--window-probe", type=int, default=1,
-                    help="also time the observation-window metric and a rank-block eviction to 8x on a "
-                         "Mistral-7B-shaped 16384-token prompt (0 = skip)")
-    ap.add_argument("--calibrate-copy", action="store_true",
-                    help="also run one plain 1 GiB device copy (a kernel of known traffic, for scaling rocprofv3 counters)")
-    args = ap.parse_args()
-    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
-              "(every step is independent per head instance and would shard without communication).",
-              file=sys.stderr)
-        sys.exit(2)
+def cpu_baseline(sess, q, shape, n_heads, seed, budget_s=12.0):
+    """Times the CPU oracle, as it stands, on a sample of head instances spread over all host
+    cores (head instances are independent, so each worker process takes a share of the sample)."""
+    import multiprocessing as mp
+    from concurrent.futures import ProcessPoolExecutor
+    import numpy as np
+    import torch
+    from paper_2410_00161_amd import workloads as W
+    try:
+        cores = len(os.sched_getaffinity(0))
+    except AttributeError:
+        cores = os.cpu_count() or 1
+    cores = max(1, min(cores, 16, n_heads))     # a one-GPU box has a share of 16 cores
+    g = torch.Generator().manual_seed(seed)
+    heads = torch.randperm(shape.G, generator=g)[:n_heads].tolist()
+    jobs = []
+    for w in range(cores):
+        mine = heads[w::cores]
+        small, q_small = W.gather_heads(sess.cache, mine, q)
+        sh = small.shape
+        f = lambda t: t.to(torch.float32).numpy()
+        i = lambda t: t.to(torch.int64).numpy()
+        dims = (sh.num_seqs, sh.num_layers, sh.num_kv_heads, sh.group_size, sh.head_dim, sh.block_size,
+                sh.num_blocks, sh.max_blocks_per_head)
+        arrays = (f(small.k_cache), f(small.v_cache), f(small.metric), i(small.pos), i(small.block_table),
+                  i(small.ctx_len), i(small.free_map))
+        jobs.append((dims, arrays, q_small.to(torch.float32).numpy(), budget_s))
+    t0 = time.perf_counter()
+    with ProcessPoolExecutor(max_workers=cores, mp_context=mp.get_context("spawn")) as ex:
+        res = list(ex.map(_cpu_worker, jobs))
+    wall = time.perf_counter() - t0
+    bpk = algorithmic_bytes_per_kv(shape)
+    gbs = sum(reps * kvs * bpk / dt for reps, kvs, dt in res) / 1e9    # the workers run side by side
+    kvs = sum(k for _, k, _ in res)
+    reps = [r for r, _, _ in res]
+    return {"value": gbs, "unit": "GB/s", "cores": cores, "kind": "oracle",
+            "sample": f"{n_heads} of {shape.G} head instances ({kvs} KVs) split over {cores} worker processes, "
+                      f"each repeating whole decode steps with metric accumulation + block keys for {budget_s:g} s "
+                      f"({min(reps)}-{max(reps)} steps per worker, {wall:.1f} s wall), numpy fp64 oracle, one BLAS thread per worker"}
 
+
+# ---------------------------------------------------------------------------
+# in-run check: a sample of head instances against the oracle, invariants over the whole cache
+# ---------------------------------------------------------------------------
+
+def sample_heads(ctx_len, chunk_T, n, seed):
+    """The longest head, the shortest, one just over a chunk when there is one, the rest at random."""
+    import torch
+    c = ctx_len.reshape(-1).cpu()
+    g = torch.Generator().manual_seed(seed + 31)
+    picks = [int(c.argmax()), int(c.argmin())]
+    over = torch.nonzero(c > chunk_T).reshape(-1) if chunk_T > 0 else torch.empty(0, dtype=torch.long)
+    if over.numel():
+        picks.append(int(over[int(c[over].argmin())]))
+    for h in torch.randperm(c.numel(), generator=g).tolist():
+        if len(picks) >= n:
+            break
+        if h not in picks:
+            picks.append(h)
+    return picks[:n]
+
+
+def parity_sample(sess, shape, q, seed, n_heads, rounds_mode):
+    """One more decode step on the state the timed region left, checked on a sample of head
+    instances against the CPU oracle (outputs and metrics, 2e-3), with the invariants that hold
+    at any size checked over the whole cache on the device: metric increments per cache between
+    sum r/C_g and r per live head and none negative, the tables/free map/lengths consistent
+    (kvc_check_state) and blocks held + blocks free = N.  Then one compression round whose
+    selection is checked against the oracle on one sequence, given the device's keys."""
+    import numpy as np
+    import torch
+    from oracle import kvc_oracle as O
+    from paper_2410_00161_amd import binding as B, workloads as W
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+    from helpers import oracle_state
+    G, r, d, b = shape.G, shape.group_size, shape.head_dim, shape.block_size
+    dev = sess.device
+    chunk_T = B.kvc_get_decode_chunk(sess.cfg)
+    heads = sample_heads(sess.cache.ctx_len, chunk_T, n_heads, seed)
+    small, q_small = W.gather_heads(sess.cache, heads, q)
+    st = oracle_state(small)
+    m_sum_before = float(sess.cache.metric.double().sum())
+    m_min_before = sess.cache.metric.clone()
+    out = sess.paged_decode(q)
+    torch.cuda.synchronize()
+    want = O.paged_decode(st, q_small.double().numpy())
+    got = out.reshape(G, r, d)[torch.tensor(heads, device=dev)].cpu().numpy()
+    err_out = float(np.abs(got - want.reshape(len(heads), r, d)).max())
+    after, _ = W.gather_heads(sess.cache, heads)
+    err_m = 0.0
+    for i in range(len(heads)):
+        n, o = O.slots_of(st, i)
+        if len(n):
+            err_m = max(err_m, float(np.abs(after.metric.numpy()[n, o] - st.metric[n, o]).max()))
+    ok = err_out <= TOL and err_m <= TOL and bool(torch.isfinite(out).all())
+    # whole-cache properties
+    ctx = sess.cache.ctx_len.reshape(-1).double()
+    live = ctx > 0
+    inc = float(sess.cache.metric.double().sum()) - m_sum_before
+    lo = float((r / ctx[live]).sum()) if shape_mode_l2(sess) else float(r * live.sum())
+    hi = float(r * live.sum())
+    ok_inc = (lo - 1e-3 * G <= inc <= hi + 1e-3 * G) and bool((sess.cache.metric >= m_min_before).all())
+    del m_min_before
+    try:
+        sess.check_state()
+        ok_state = True
+    except B.KvcError:
+        ok_state = False
+    held = int(((sess.cache.ctx_len.reshape(-1).long() + b - 1) // b).sum())
+    ok_state = ok_state and held + int(sess.cache.free_map.sum()) == shape.num_blocks
+    # one round: selection of one sequence against the oracle on the device's keys (block mode),
+    # or the rank schedule of one sequence (rank mode); then the compaction must keep the state consistent
+    per_seq = shape.num_layers * shape.num_kv_heads
+    nb = (sess.cache.ctx_len.reshape(shape.num_seqs, -1).long() + b - 1) // b
+    budget = (nb.sum(1) // 10).to(torch.int32)
+    s = shape.num_seqs // 2
+    sl = slice(s * per_seq, (s + 1) * per_seq)
+    ok_sel = True
+    if rounds_mode == "block":
+        key = sess.metric_reduce()
+        flag, count, sel = sess.evict_select(budget)
+        torch.cuda.synchronize()
+        mini = O.State(1, shape.num_layers, shape.num_kv_heads, 1, 1, b, 1, shape.max_blocks_per_head,
+                       np.zeros((1, b, 1)), np.zeros((1, b, 1)), np.zeros((1, b)), np.zeros((1, b)),
+                       -np.ones((per_seq, shape.max_blocks_per_head)), sess.cache.ctx_len.reshape(-1)[sl].cpu().numpy(),
+                       np.zeros(1, dtype=np.uint8))
+        fw, cw, sw = O.evict_select(mini, key[sl].cpu().numpy(), [int(budget[s])])
+        ok_sel = bool(np.array_equal(flag[sl].cpu().numpy(), fw)) and int(sel[s]) == int(sw[0])
+        freed = int(sess.compact().item())
+        ok_sel = ok_sel and freed == int(sel.sum())
+    else:
+        rows, sel = sess.evict_rank_select(budget)
+        freed = int(sess.compact_rank().item())
+        ok_sel = freed == int(sel.sum()) == int(rows.sum())
+    try:
+        sess.check_state()
+    except B.KvcError:
+        ok_sel = False
+    held2 = int(((sess.cache.ctx_len.reshape(-1).long() + b - 1) // b).sum())
+    ok_sel = ok_sel and held2 == held - freed and held2 + int(sess.cache.free_map.sum()) == shape.num_blocks
+    verdict = "ok" if (ok and ok_inc and ok_state and ok_sel) else "FAILED"
+    return {"parity_sample": verdict, "sampled_heads": len(heads), "sampled_kvs": int(st.lens().sum()),
+            "max_abs_err_out": err_out, "max_abs_err_metric": err_m, "tolerance": TOL,
+            "metric_increment_within_bounds": bool(ok_inc), "allocator_invariants": bool(ok_state),
+            "round_checked": bool(ok_sel), "blocks_freed_in_checked_round": freed}
+
+
+def shape_mode_l2(sess):
+    from paper_2410_00161_amd import binding as B
+    return sess.cfg.metric_mode == B.KVC_L2
+
+
+# ---------------------------------------------------------------------------
+# one decode configuration
+# ---------------------------------------------------------------------------
+
+def make_workload(spec):
+    from paper_2410_00161_amd import workloads as W
+    extra = spec["steps"] + spec["warmup"] + 2 * max(spec["evict_every"], 1) + 24
+    if spec["workload"] == "llama8b":
+        shape, ctx, seed = W.llama8b_decode(num_seqs=spec["num_seqs"], prompt=spec["prompt"], rho=spec["rho"],
+                                            extra_tokens=extra, block_size=spec["block_size"])
+        name = (f"Llama-3.1-8B-shaped decode: 32 layers, 32q/8kv heads, d=128, {spec['kv_dtype']} KV, b={spec['block_size']}, "
+                f"{spec['num_seqs']} seqs x {spec['prompt']} prompt tokens, per-head retention log-uniform mean {spec['rho']:g}x")
+    else:
+        shape, ctx, seed = W.llama70b_decode(num_seqs=spec["num_seqs"], prompt=spec["prompt"], rho=spec["rho"],
+                                             extra_tokens=extra)
+        name = (f"Llama-3.1-70B-shaped decode: 80 layers, 64q/8kv heads, d=128, {spec['kv_dtype']} KV, b=16, "
+                f"{spec['num_seqs']} seqs x {spec['prompt']} prompt tokens, per-head retention log-uniform mean {spec['rho']:g}x")
+    if spec["kv_dtype"] != "bf16":
+        import dataclasses
+        shape = dataclasses.replace(shape, kv_dtype=spec["kv_dtype"])
+    if spec.get("uniform"):
+        ctx = W.uniform_lengths(shape.G, int(spec["prompt"] / spec["rho"]))
+        name += " [diagnostic: uniform lengths]"
+    return shape, ctx, seed, name
+
+
+def run_decode_config(spec, dev, keep_session=False):
+    """Builds the cache, runs warmup + timed steps, returns (record, session or None).  The record
+    carries the whole-path rate, the dominant kernel's roofline from HIP events on the launch
+    stream, the split of a compression round, and the in-run check."""
     import numpy as np
     import torch
     from paper_2410_00161_amd import binding as B, workloads as W
     from paper_2410_00161_amd.session import KvcSession
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible", file=sys.stderr)
-        sys.exit(2)
-    B.lib()
-    dev = torch.device("cuda:0")
-    torch.cuda.set_device(dev)
-
-    total_steps = args.steps + args.warmup
-    extra = total_steps + 2 * args.evict_every + 16
-    if args.workload == "llama8b":
-        shape, ctx, seed = W.llama8b_decode(num_seqs=args.num_seqs, prompt=args.prompt, rho=args.rho,
-                                            extra_tokens=extra, block_size=args.block_size)
-        name = (f"Llama-3.1-8B-shaped decode: 32 layers, 32q/8kv heads, d=128, {args.kv_dtype} KV, b={args.block_size}, "
-                f"{args.num_seqs} seqs x {args.prompt} prompt tokens, per-head retention log-uniform mean {args.rho:g}x")
-    else:
-        shape, ctx, seed = W.llama70b_decode(num_seqs=args.num_seqs, prompt=args.prompt, rho=args.rho,
-                                             extra_tokens=extra)
-        name = (f"Llama-3.1-70B-shaped decode: 80 layers, 64q/8kv heads, d=128, {args.kv_dtype} KV, b=16, "
-                f"{args.num_seqs} seqs x {args.prompt} prompt tokens, per-head retention log-uniform mean {args.rho:g}x")
-    if args.kv_dtype != "bf16":
-        import dataclasses
-        shape = dataclasses.replace(shape, kv_dtype=args.kv_dtype)
-    if args.uniform:
-        ctx = W.uniform_lengths(shape.G, int(args.prompt / args.rho))
-        name += " [diagnostic: uniform lengths]"
+    steps, warmup, evict_every = spec["steps"], spec["warmup"], spec["evict_every"]
+    total_steps = steps + warmup
+    shape, ctx, seed, name = make_workload(spec)
     t_setup = time.perf_counter()
-    cache = W.make_cache(shape, ctx, seed, device=dev, placement=args.placement, init_metric="prefill")
+    cache = W.make_cache(shape, ctx, seed, device=dev, placement=spec["placement"], init_metric="prefill")
     sess = KvcSession(cache, device=dev)
     del cache
-    B.kvc_set_decode_chunk(args.chunk)
+    B.kvc_set_decode_chunk(spec.get("chunk", 0))
     bytes_kv = algorithmic_bytes_per_kv(shape)
     G = shape.G
     per_seq = shape.num_layers * shape.num_kv_heads
-    print(f"[bench] {name}", file=sys.stderr)
+    print(f"[bench] {name} ({spec['placement']} pool)", file=sys.stderr)
     print(f"[bench] G={G} head instances, {int(ctx.sum())} KVs, {shape.num_blocks} blocks in the pool, "
-          f"realised compression {args.prompt * G / float(ctx.sum()):.2f}x, "
+          f"realised compression {spec['prompt'] * G / float(ctx.sum()):.2f}x, "
           f"setup {time.perf_counter() - t_setup:.1f}s", file=sys.stderr, flush=True)
 
     # pre-generated inputs for a few steps, reused round-robin (they stay in HBM)
-    n_in = 4
+    n_in = 4 if shape.G * shape.group_size * shape.head_dim < (1 << 28) else 2
     qs = [W.make_query(shape, seed, i, dev) for i in range(n_in)]
     kvs_new = [W.make_new_kv(shape, seed, i, dev) for i in range(n_in)]
     snaps = {}   # step -> context lengths the decode of that step saw
-    snap_every = args.evict_every if args.evict_every > 0 else 16
-    prof_every = 4
-    budget = torch.full((shape.num_seqs,), per_seq * args.evict_every // shape.block_size,
+    snap_every = evict_every if evict_every > 0 else 16
+    prof_every = spec.get("prof_every", 4)
+    frac = spec.get("evict_frac", 0.0)
+    budget = torch.full((shape.num_seqs,), max(1, per_seq * max(evict_every, 1) // shape.block_size),
                         dtype=torch.int32, device=dev)
+    held = torch.zeros(shape.num_seqs, dtype=torch.int32, device=dev)
     ev = lambda: torch.cuda.Event(enable_timing=True)
-    evict_events = []
+    evict_events, evict_blocks = [], []
+    no_metric = bool(spec.get("no_metric"))
+    mode = spec["evict_mode"]
 
     def step(i, timed):
         k, v = kvs_new[i % n_in]
         sess.append(k, v, flags=B.KVC_ASYNC)
         if timed:
-            B.kvc_profile_enable((i - args.warmup) % prof_every == 0)
-        sess.paged_decode(qs[i % n_in], accumulate_metric=not args.no_metric)
-        if i % snap_every == 0 or i == args.warmup:
+            B.kvc_profile_enable((i - warmup) % prof_every == 0)
+        sess.paged_decode(qs[i % n_in], accumulate_metric=not no_metric)
+        if i % snap_every == 0 or i == warmup:
             snaps[i] = sess.cache.ctx_len.reshape(-1).clone()
-        if args.evict_every > 0 and (i + 1) % args.evict_every == 0:
+        if evict_every > 0 and (i + 1) % evict_every == 0:
             e = [ev() for _ in range(4)]
+            bud = budget
+            if frac > 0:      # that fraction of the blocks every sequence holds now (counted on the device)
+                B.kvc_count_blocks(sess.cfg, sess.st, 0, shape.num_layers, None, held, sess.ws)
+                bud = (held.double() * frac).to(torch.int32)
             e[0].record()
-            if args.evict_mode == "block":
+            if mode == "block":
                 sess.metric_reduce()
                 e[1].record()
-                sess.evict_select(budget, flags=B.KVC_ASYNC)
+                sess.evict_select(bud, flags=B.KVC_ASYNC)
                 e[2].record()
                 sess.compact(flags=B.KVC_ASYNC)
             else:
                 e[1].record()
-                sess.evict_rank_select(budget, flags=B.KVC_ASYNC)
+                sess.evict_rank_select(bud, flags=B.KVC_ASYNC)
                 e[2].record()
                 sess.compact_rank(flags=B.KVC_ASYNC)
             e[3].record()
             if timed:
                 evict_events.append(e)
+                evict_blocks.append(sess.blocks_freed.clone())
 
-    for i in range(args.warmup):
+    for i in range(warmup):
         step(i, False)
     torch.cuda.synchronize()
     assert B.kvc_poll_status(sess.cfg, sess.ws) == B.KVC_OK
-    B.kvc_profile_begin((args.steps + prof_every - 1) // prof_every)
+    B.kvc_profile_begin((steps + prof_every - 1) // prof_every)
     t0, t1 = ev(), ev()
     torch.cuda.synchronize()
     wall0 = time.perf_counter()
     t0.record()
-    for i in range(args.warmup, total_steps):
+    for i in range(warmup, total_steps):
         step(i, True)
     t1.record()
     torch.cuda.synchronize()
@@ -219,46 +357,127 @@ def main():
     short_T = B.kvc_get_decode_short(sess.cfg)
     kv_per_step, long_kv, long_single, short_single = [], [], [], []
     keys = sorted(snaps)
-    for i in range(args.warmup, total_steps):
+    for i in range(warmup, total_steps):
         s0 = max(k for k in keys if k <= i)
         c = snaps[s0].to(torch.int64) + (i - s0)
-        rem = c % chunk_T
-        in_short = rem * ((rem > 0) & (rem <= short_T))
+        if chunk_T > 0:
+            rem = c % chunk_T
+            in_short = rem * ((rem > 0) & (rem <= short_T))
+            long_single.append(float((c * ((c <= chunk_T) & (c > short_T))).sum()))
+            short_single.append(float((c * (c <= min(short_T, chunk_T))).sum()))
+        else:               # fallback kernel: one launch, every head whole
+            in_short = torch.zeros_like(c)
+            long_single.append(float(c.sum()))
+            short_single.append(0.0)
         kv_per_step.append(float(c.sum()))
         long_kv.append(float((c - in_short).sum()))
-        long_single.append(float((c * ((c <= chunk_T) & (c > short_T))).sum()))
-        short_single.append(float((c * (c <= min(short_T, chunk_T))).sum()))
     kv_per_step, long_kv = np.array(kv_per_step), np.array(long_kv)
     long_single, short_single = np.array(long_single), np.array(short_single)
     total_bytes = float(kv_per_step.sum()) * bytes_kv
     value = total_bytes / (ms_total * 1e-3) / 1e9
-    ms_step = ms_total / args.steps
+    ms_step = ms_total / steps
 
     # dominant kernel: decode_chunk_kernel over the long items (four wavefronts per item): streams
     # their K and V once, metric RMW for heads of one chunk
     per_kv = 2 * shape.head_dim * shape.kv_bytes + 4.0 / shape.block_size
     chunk_alg = long_kv * per_kv + 8.0 * long_single
     short_alg = (kv_per_step - long_kv) * per_kv + 8.0 * short_single
-    chunk_ms = np.array(chunk_ms, dtype=np.float64)
-    short_ms = np.array(short_ms, dtype=np.float64)
-    combine_ms = np.array(combine_ms, dtype=np.float64)
-    chunk_alg_s = chunk_alg[::prof_every][:len(chunk_ms)]          # the steps that were timed
-    short_alg_s = short_alg[::prof_every][:len(chunk_ms)]
-    ach = float(chunk_alg_s.mean() / (chunk_ms.mean() * 1e-3) / 1e9)
-    traffic = read_traffic_note("decode_chunk_kernel_llama8b_pmc.txt") if args.workload == "llama8b" else None
-    roofline = {"bound": "hbm", "kernel": "decode_chunk_kernel<%d,128,%d,b16,4> (long items)" % (shape.kv_bytes, shape.group_size),
-                "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
-                "traffic": traffic, "avg_kernel_ms": float(chunk_ms.mean()),
-                "algorithmic_bytes_per_launch": float(chunk_alg_s.mean()),
-                "timed_launches": int(len(chunk_ms)),
-                "short_items_kernel_ms": float(short_ms.mean()),
-                "short_items_GBps": float(short_alg_s.mean() / (short_ms.mean() * 1e-3) / 1e9),
-                "short_items_max_tokens": short_T,
-                "decode_call_GBps": float((kv_per_step[::prof_every][:len(chunk_ms)] * bytes_kv).mean() /
-                                          ((chunk_ms + short_ms + combine_ms).mean() * 1e-3) / 1e9),
-                "combine_kernel_ms": float(combine_ms.mean())}
+    roofline = None
+    if len(chunk_ms):
+        chunk_ms = np.array(chunk_ms, dtype=np.float64)
+        short_ms = np.array(short_ms, dtype=np.float64)
+        combine_ms = np.array(combine_ms, dtype=np.float64)
+        chunk_alg_s = chunk_alg[::prof_every][:len(chunk_ms)]          # the steps that were timed
+        short_alg_s = short_alg[::prof_every][:len(chunk_ms)]
+        ach = float(chunk_alg_s.mean() / (chunk_ms.mean() * 1e-3) / 1e9)
+        roofline = {"bound": "hbm",
+                    "kernel": "decode_chunk_kernel<%d,%d,%d,%s,4> (long items)" % (shape.kv_bytes, shape.head_dim, shape.group_size,
+                                                                               "b16" if shape.block_size % 16 == 0 else "b<16"),
+                    "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
+                    "traffic": None, "avg_kernel_ms": float(chunk_ms.mean()),
+                    "algorithmic_bytes_per_launch": float(chunk_alg_s.mean()),
+                    "timed_launches": int(len(chunk_ms)),
+                    "short_items_kernel_ms": float(short_ms.mean()),
+                    "short_items_GBps": float(short_alg_s.mean() / (short_ms.mean() * 1e-3) / 1e9) if short_ms.mean() > 0 else None,
+                    "short_items_max_tokens": short_T,
+                    "decode_call_GBps": float((kv_per_step[::prof_every][:len(chunk_ms)] * bytes_kv).mean() /
+                                              ((chunk_ms + short_ms + combine_ms).mean() * 1e-3) / 1e9),
+                    "combine_kernel_ms": float(combine_ms.mean())}
 
-    # measured streaming-read ceiling of this GPU: the K cache read once with plain 16-byte loads
+    evict = None
+    if evict_events:
+        r = np.array([[e[j].elapsed_time(e[j + 1]) for j in range(3)] for e in evict_events])
+        evict = {"mode": mode, "rounds": len(evict_events), "reduce_ms": float(r[:, 0].mean()),
+                 "select_ms": float(r[:, 1].mean()), "compact_ms": float(r[:, 2].mean()),
+                 "total_ms": float(r.sum(1).mean()),
+                 "blocks_per_round": float(np.mean([int(x.item()) for x in evict_blocks])),
+                 "budget": f"{frac:g} of every sequence's blocks" if frac > 0 else "the blocks appended since the last round"}
+
+    check = None
+    if spec.get("check_heads", 0) > 0:
+        check = parity_sample(sess, shape, qs[0], seed, spec["check_heads"], mode)
+        if check["parity_sample"] != "ok":
+            print(f"bench.py: in-run check FAILED for {name}: {check}", file=sys.stderr)
+
+    rec = {"workload": name, "placement": spec["placement"], "evict_every": evict_every, "evict_mode": mode,
+           "steps": steps, "warmup": warmup, "ms_per_step": ms_step, "value": value, "unit": "GB/s",
+           "frac_of_hbm_peak": value / HBM_PEAK_GBS,
+           "kv_only_GBps": float(kv_per_step.sum()) * 2 * shape.head_dim * shape.kv_bytes / (ms_total * 1e-3) / 1e9,
+           "decode_steps_per_s": 1e3 / ms_step, "chunk_tokens": chunk_T, "head_instances": G,
+           "mean_kvs_per_step": float(kv_per_step.mean()), "wall_s": wall,
+           "eviction": evict, "roofline": roofline}
+    if check:
+        rec.update(check)
+    extras = {"shape": shape, "seed": seed, "qs": qs, "n_in": n_in, "no_metric": no_metric}
+    if keep_session:
+        return rec, sess, extras
+    del sess, qs, kvs_new
+    torch.cuda.empty_cache()
+    return rec, None, None
+
+
+def per_layer_probe(sess, extras, steps):
+    """The same decode issued the way a model runs it: one call per layer (no append), then the
+    same calls captured once into a HIP graph and replayed."""
+    import torch
+    shape, qs, n_in, no_metric = extras["shape"], extras["qs"], extras["n_in"], extras["no_metric"]
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    for l in range(shape.num_layers):      # untimed first pass
+        sess.paged_decode(qs[0], accumulate_metric=not no_metric, layer_begin=l, layer_end=l + 1)
+    a, b_ = ev(), ev()
+    torch.cuda.synchronize()
+    a.record()
+    for i in range(steps):
+        for l in range(shape.num_layers):
+            sess.paged_decode(qs[i % n_in], accumulate_metric=not no_metric, layer_begin=l, layer_end=l + 1)
+    b_.record()
+    torch.cuda.synchronize()
+    per_layer_ms = a.elapsed_time(b_) / steps
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.graph(graph, stream=side):
+        for l in range(shape.num_layers):
+            sess.paged_decode(qs[0], accumulate_metric=not no_metric, layer_begin=l, layer_end=l + 1)
+    torch.cuda.synchronize()
+    graph.replay()
+    torch.cuda.synchronize()
+    a, b_ = ev(), ev()
+    a.record()
+    for i in range(steps):
+        graph.replay()
+    b_.record()
+    torch.cuda.synchronize()
+    per_layer_graph_ms = a.elapsed_time(b_) / steps
+    del graph
+    return per_layer_ms, per_layer_graph_ms
+
+
+def stream_read_probe(sess, dev):
+    """Measured streaming-read ceiling of this GPU: the K cache read once with 16-byte loads."""
+    import torch
+    from paper_2410_00161_amd import binding as B
+    ev = lambda: torch.cuda.Event(enable_timing=True)
     nbytes = sess.cache.k_cache.numel() * sess.cache.k_cache.element_size()
     nbytes -= nbytes % 16
     sink = torch.zeros(65536, dtype=torch.int32, device=dev)
@@ -271,8 +490,171 @@ def main():
             b_.record()
             torch.cuda.synchronize()
             best = max(best, nbytes / (a.elapsed_time(b_) * 1e-3) / 1e9)
+    return best
+
+
+def prefill_end_probe(dev, all_queries_block):
+    """Prefill-end compression, Mistral-7B shape: one 16384-token prompt, the metric from the last
+    32 prompt queries on the matrix cores, the metric over all prompt queries, a rank-block
+    eviction to 8x and 256 decode steps on what is left."""
+    import torch
+    from paper_2410_00161_amd import binding as B, workloads as W
+    from paper_2410_00161_amd.session import KvcSession
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    Lp, wq = 16384, 32
+    shp = W.Shape(1, 32, 8, 4, 128, 16, 256 * (Lp // 16) + 512, Lp // 16 + 2, "bf16")
+    c4 = W.make_cache(shp, W.uniform_lengths(shp.G, Lp), 1004, device=dev)
+    s4 = KvcSession(c4, device=dev)
+    del c4
+    g4 = torch.Generator(device=dev).manual_seed(1004)
+    qw = torch.randn((1, 32, 32, wq, 128), generator=g4, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    # the metric over ALL prompt queries (every query attends to the keys at least 10 positions
+    # before it), gathered one block of queries at a time; the same random block of queries stands
+    # in for every block of the prompt
+    wb, excl = all_queries_block, 10
+    qb = torch.randn((1, 32, 32, wb, 128), generator=g4, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    s4.cache.metric.zero_()
+    a, b_ = ev(), ev()
+    a.record()
+    for start in range(0, Lp, wb):
+        s4.query_block_metric(qb, wb, start, excl)
+    b_.record()
+    torch.cuda.synchronize()
+    all_queries_ms = a.elapsed_time(b_)
+    del qb
+    best = 1e9
+    for _ in range(4):
+        a, b_ = ev(), ev()
+        a.record()
+        s4.window_metric(qw, wq, 7)
+        b_.record()
+        torch.cuda.synchronize()
+        best = min(best, a.elapsed_time(b_))
+    kvs4 = shp.G * Lp
+    bud4 = torch.tensor([shp.G * (Lp // 16) * 7 // 8], dtype=torch.int32, device=dev)
+    s4.evict_rank_select(bud4, flags=B.KVC_ASYNC)   # untimed first call (selection changes no cache state)
+    torch.cuda.synchronize()
+    a, b_, c_ = ev(), ev(), ev()
+    a.record()
+    s4.evict_rank_select(bud4, flags=B.KVC_ASYNC)
+    b_.record()
+    s4.compact_rank(flags=B.KVC_ASYNC)
+    c_.record()
+    torch.cuda.synchronize()
+    assert B.kvc_poll_status(s4.cfg, s4.ws) == B.KVC_OK
+    kvs_after = int(s4.cache.ctx_len.sum().item())
+    select_ms, compact_ms = a.elapsed_time(b_), b_.elapsed_time(c_)
+    # then 256 decode steps on what is left (append + decode + metric)
+    q4 = [W.make_query(shp, 1004, i, dev) for i in range(2)]
+    kv4 = [W.make_new_kv(shp, 1004, i, dev) for i in range(2)]
+    nd = 256
+    a, b_ = ev(), ev()
+    a.record()
+    for i in range(nd):
+        s4.append(*kv4[i % 2], flags=B.KVC_ASYNC)
+        s4.paged_decode(q4[i % 2])
+    b_.record()
+    torch.cuda.synchronize()
+    assert B.kvc_poll_status(s4.cfg, s4.ws) == B.KVC_OK
+    decode_ms = a.elapsed_time(b_) / nd
+    # Algorithmic figures: K read ONCE (256 B per key) and one Q K^T (2 * rows * d flop per key).
+    # The kernels as built pass over K twice (row statistics, then the sums); the "executed"
+    # figures count both passes and are what the hardware did, not what the method needs.
+    win_bytes, win_flop = 256.0 * kvs4, 2.0 * (wq * 4) * 128 * kvs4
+    all_flop = 2.0 * (4 * 128) * shp.G * (Lp * (Lp + min(wb, 64)) / 2)
+    rec = {"workload": "Mistral-7B-shaped: 32 layers, 32q/8kv heads, d=128, bf16, one 16384-token prompt",
+           "window_queries": wq, "pool": 7, "window_metric_ms": best,
+           "window_metric_K_GBps": win_bytes / (best * 1e-3) / 1e9,
+           "window_metric_frac_of_hbm_peak": win_bytes / (best * 1e-3) / 1e9 / HBM_PEAK_GBS,
+           "window_metric_TFLOPs": win_flop / (best * 1e-3) / 1e12,
+           "window_metric_executed_two_pass": {"K_GBps": 2 * win_bytes / (best * 1e-3) / 1e9,
+                                               "TFLOPs": 2 * win_flop / (best * 1e-3) / 1e12},
+           "rank_select_to_8x_ms": select_ms, "rank_compact_ms": compact_ms,
+           "kvs_after": kvs_after, "kvs_before": kvs4,
+           "all_queries_metric_ms": all_queries_ms, "all_queries_block": wb, "all_queries_exclude": excl,
+           "all_queries_TFLOPs": all_flop / (all_queries_ms * 1e-3) / 1e12,
+           "all_queries_frac_of_bf16_mfma_peak": all_flop / (all_queries_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+           "all_queries_executed_two_pass_TFLOPs": 2 * all_flop / (all_queries_ms * 1e-3) / 1e12,
+           "decode_steps_after": nd, "decode_ms_per_step_after": decode_ms,
+           "decode_GBps_after": (kvs_after + shp.G * nd / 2) * algorithmic_bytes_per_kv(shp) / (decode_ms * 1e-3) / 1e9}
+    del s4, qw, q4, kv4
+    torch.cuda.empty_cache()
+    return rec
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=64)
+    ap.add_argument("--warmup", type=int, default=8)
+    ap.add_argument("--evict-every", type=int, default=16)
+    ap.add_argument("--evict-frac", type=float, default=0.0,
+                    help="blocks a round evicts, as a fraction of every sequence's blocks (0 = as many as were appended since the last round)")
+    ap.add_argument("--num-seqs", type=int, default=64)
+    ap.add_argument("--prompt", type=int, default=8192)
+    ap.add_argument("--rho", type=float, default=8.0, help="mean compression rate")
+    ap.add_argument("--placement", default="fresh", choices=["fresh", "fragmented"])
+    ap.add_argument("--chunk", type=int, default=0, help="decode chunk tokens (0 = library default)")
+    ap.add_argument("--cpu-heads", type=int, default=1024, help="head instances timed on the CPU oracle (0 = skip)")
+    ap.add_argument("--check-heads", type=int, default=32,
+                    help="head instances of the in-run check against the CPU oracle (0 = skip the check)")
+    ap.add_argument("--workload", default="llama8b", choices=["llama8b", "llama70b"])
+    ap.add_argument("--block-size", type=int, default=16, choices=[1, 2, 4, 8, 16, 32, 64],
+                    help="variant (llama8b workload): tokens per cache block")
+    ap.add_argument("--kv-dtype", default="bf16", choices=["bf16", "fp8"],
+                    help="variant: K and V stored as OCP e4m3 bytes (queries stay bf16)")
+    ap.add_argument("--evict-mode", default="block", choices=["block", "rank"],
+                    help="block: physical blocks by summed metric; rank: the paper's rank-block schedule")
+    ap.add_argument("--uniform", action="store_true", help="diagnostic: every head holds prompt/rho KVs")
+    ap.add_argument("--no-metric", action="store_true", help="diagnostic: decode without metric accumulation")
+    ap.add_argument("--per-layer-steps", type=int, default=4,
+                    help="extra untimed-region steps that call the decode once per layer (0 = skip)")
+    ap.add_argument("--all-queries-block", type=int, default=1024, choices=[32, 64, 256, 1024],
+                    help="queries per call when the prefill-end probe gathers the metric over all prompt queries")
+    ap.add_argument("--window-probe", type=int, default=1,
+                    help="also time the observation-window metric and a rank-block eviction to 8x on a "
+                         "Mistral-7B-shaped 16384-token prompt (0 = skip)")
+    ap.add_argument("--other-configs", type=int, default=-1,
+                    help="also measure the fragmented pool, the 256 x 32768 / 64x configuration and the 70B shape "
+                         "(default: yes when the main workload is the default one)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy (a kernel of known traffic, for scaling rocprofv3 counters)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
+              "(every step is independent per head instance and would shard without communication).",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2410_00161_amd import binding as B
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    B.lib()
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    main_spec = dict(workload=args.workload, num_seqs=args.num_seqs, prompt=args.prompt, rho=args.rho,
+                     block_size=args.block_size, kv_dtype=args.kv_dtype, placement=args.placement,
+                     steps=args.steps, warmup=args.warmup, evict_every=args.evict_every, evict_frac=args.evict_frac,
+                     evict_mode=args.evict_mode, chunk=args.chunk, uniform=args.uniform, no_metric=args.no_metric,
+                     check_heads=0)   # the headline's check runs after its other probes (it changes the cache)
+    is_default = (args.workload == "llama8b" and args.num_seqs == 64 and args.prompt == 8192 and args.rho == 8.0 and
+                  args.block_size == 16 and args.kv_dtype == "bf16" and args.placement == "fresh" and not args.uniform and
+                  not args.no_metric and args.chunk == 0 and args.evict_frac == 0.0)
+    others_on = is_default if args.other_configs < 0 else bool(args.other_configs)
+
+    rec, sess, extras = run_decode_config(main_spec, dev, keep_session=True)
+    shape, seed = extras["shape"], extras["seed"]
+    roofline = rec["roofline"]
+    if args.workload == "llama8b" and is_default:
+        roofline["traffic"] = read_traffic_note("decode_chunk_kernel_llama8b_pmc.txt")
+        roofline["traffic_source"] = ("profiles/decode_chunk_kernel_llama8b_pmc.txt: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE "
+                                      "of this kernel on this workload, a stored measurement, not a quantity of this run")
+    best = stream_read_probe(sess, dev)
     roofline["measured_stream_read_GBps"] = best
-    roofline["frac_of_measured_stream_read"] = ach / best
+    roofline["frac_of_measured_stream_read"] = roofline["achieved"] / best
 
     if args.calibrate_copy:
         src = torch.empty(1 << 28, dtype=torch.float32, device=dev).fill_(1.0)
@@ -282,136 +664,62 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    # the same decode issued the way a model runs it: one call per layer (no append, no metric
-    # writes skipped), a few steps, reported beside the all-layers launch
     per_layer_ms = per_layer_graph_ms = None
     if args.per_layer_steps > 0:
-        a, b_ = ev(), ev()
-        torch.cuda.synchronize()
-        a.record()
-        for i in range(args.per_layer_steps):
-            for l in range(shape.num_layers):
-                sess.paged_decode(qs[i % n_in], accumulate_metric=not args.no_metric, layer_begin=l, layer_end=l + 1)
-        b_.record()
-        torch.cuda.synchronize()
-        per_layer_ms = a.elapsed_time(b_) / args.per_layer_steps
-        # the same 32 calls captured once into a HIP graph and replayed
-        graph = torch.cuda.CUDAGraph()
-        side = torch.cuda.Stream()
-        side.wait_stream(torch.cuda.current_stream())
-        with torch.cuda.graph(graph, stream=side):
-            for l in range(shape.num_layers):
-                sess.paged_decode(qs[0], accumulate_metric=not args.no_metric, layer_begin=l, layer_end=l + 1)
-        torch.cuda.synchronize()
-        a, b_ = ev(), ev()
-        a.record()
-        for i in range(args.per_layer_steps):
-            graph.replay()
-        b_.record()
-        torch.cuda.synchronize()
-        per_layer_graph_ms = a.elapsed_time(b_) / args.per_layer_steps
-        del graph
-
-    # prefill-end compression, Mistral-7B shape: one 16384-token prompt, metric from the last 32
-    # prompt queries on the matrix cores, then rank-block eviction to 8x
-    prefill_end = None
-    if args.window_probe:
-        Lp, wq = 16384, 32
-        shp = W.Shape(1, 32, 8, 4, 128, 16, 256 * (Lp // 16) + 512, Lp // 16 + 2, "bf16")
-        c4 = W.make_cache(shp, W.uniform_lengths(shp.G, Lp), 1004, device=dev)
-        s4 = KvcSession(c4, device=dev)
-        del c4
-        g4 = torch.Generator(device=dev).manual_seed(1004)
-        qw = torch.randn((1, 32, 32, wq, 128), generator=g4, device=dev, dtype=torch.float32).to(torch.bfloat16)
-        # the metric over ALL prompt queries (every query attends to the keys at least 10
-        # positions before it), gathered one block of 1024 queries at a time; the same random
-        # block of queries stands in for every block of the prompt
-        wb, excl = args.all_queries_block, 10
-        qb = torch.randn((1, 32, 32, wb, 128), generator=g4, device=dev, dtype=torch.float32).to(torch.bfloat16)
-        s4.cache.metric.zero_()
-        a, b_ = ev(), ev()
-        a.record()
-        for start in range(0, Lp, wb):
-            s4.query_block_metric(qb, wb, start, excl)
-        b_.record()
-        torch.cuda.synchronize()
-        all_queries_ms = a.elapsed_time(b_)
-        del qb
-        best = 1e9
-        for _ in range(4):
-            a, b_ = ev(), ev()
-            a.record()
-            s4.window_metric(qw, wq, 7)
-            b_.record()
-            torch.cuda.synchronize()
-            best = min(best, a.elapsed_time(b_))
-        kvs4 = shp.G * Lp
-        bud4 = torch.tensor([shp.G * (Lp // 16) * 7 // 8], dtype=torch.int32, device=dev)
-        s4.evict_rank_select(bud4, flags=B.KVC_ASYNC)   # untimed first call (selection changes no cache state)
-        torch.cuda.synchronize()
-        a, b_, c_ = ev(), ev(), ev()
-        a.record()
-        s4.evict_rank_select(bud4, flags=B.KVC_ASYNC)
-        b_.record()
-        s4.compact_rank(flags=B.KVC_ASYNC)
-        c_.record()
-        torch.cuda.synchronize()
-        assert B.kvc_poll_status(s4.cfg, s4.ws) == B.KVC_OK
-        kvs_after = int(s4.cache.ctx_len.sum().item())
-        select_ms, compact_ms = a.elapsed_time(b_), b_.elapsed_time(c_)
-        # then 256 decode steps on what is left (append + decode + metric)
-        q4 = [W.make_query(shp, 1004, i, dev) for i in range(2)]
-        kv4 = [W.make_new_kv(shp, 1004, i, dev) for i in range(2)]
-        nd = 256
-        a, b_ = ev(), ev()
-        a.record()
-        for i in range(nd):
-            s4.append(*kv4[i % 2], flags=B.KVC_ASYNC)
-            s4.paged_decode(q4[i % 2])
-        b_.record()
-        torch.cuda.synchronize()
-        assert B.kvc_poll_status(s4.cfg, s4.ws) == B.KVC_OK
-        decode_ms = a.elapsed_time(b_) / nd
-        prefill_end = {"workload": "Mistral-7B-shaped: 32 layers, 32q/8kv heads, d=128, bf16, one 16384-token prompt",
-                       "window_queries": wq, "pool": 7, "window_metric_ms": best,
-                       "window_metric_K_GBps": 2 * 256 * kvs4 / (best * 1e-3) / 1e9,
-                       "window_metric_TFLOPs": 2 * 2 * (wq * 4) * 128 * kvs4 / (best * 1e-3) / 1e12,
-                       "rank_select_to_8x_ms": select_ms, "rank_compact_ms": compact_ms,
-                       "kvs_after": kvs_after, "kvs_before": kvs4,
-                       "all_queries_metric_ms": all_queries_ms, "all_queries_block": wb, "all_queries_exclude": excl,
-                       "all_queries_TFLOPs": 2 * 2 * (4 * 128) * shp.G * (Lp * (Lp + min(wb, 64)) / 2) / (all_queries_ms * 1e-3) / 1e12,
-                       "decode_steps_after": nd, "decode_ms_per_step_after": decode_ms,
-                       "decode_GBps_after": (kvs_after + shp.G * nd / 2) * algorithmic_bytes_per_kv(shp) / (decode_ms * 1e-3) / 1e9}
-        del s4, qw, q4, kv4
-
-    evict = None
-    if evict_events:
-        r = np.array([[e[j].elapsed_time(e[j + 1]) for j in range(3)] for e in evict_events])
-        evict = {"mode": args.evict_mode, "rounds": len(evict_events), "reduce_ms": float(r[:, 0].mean()),
-                 "select_ms": float(r[:, 1].mean()), "compact_ms": float(r[:, 2].mean()),
-                 "total_ms": float(r.sum(1).mean()), "blocks_per_round": int(budget.sum().item())}
+        per_layer_ms, per_layer_graph_ms = per_layer_probe(sess, extras, args.per_layer_steps)
 
     cpu = None
     if args.cpu_heads > 0:
-        cpu = cpu_baseline(sess, qs[0], shape, args.cpu_heads, seed)
+        cpu = cpu_baseline(sess, extras["qs"][0], shape, args.cpu_heads, seed)
+
+    check = None
+    if args.check_heads > 0:
+        check = parity_sample(sess, shape, extras["qs"][0], seed, args.check_heads, args.evict_mode)
+        if check["parity_sample"] != "ok":
+            print(f"bench.py: in-run check FAILED: {check}", file=sys.stderr)
+    del sess, extras
+    torch.cuda.empty_cache()
+
+    prefill_end = prefill_end_probe(dev, args.all_queries_block) if args.window_probe else None
+
+    other = []
+    if others_on:
+        base = dict(block_size=16, kv_dtype="bf16", evict_mode="block", check_heads=args.check_heads, prof_every=4)
+        for spec in (
+            dict(base, workload="llama8b", num_seqs=64, prompt=8192, rho=8.0, placement="fragmented",
+                 steps=32, warmup=8, evict_every=16, evict_frac=0.0),
+            dict(base, workload="llama8b", num_seqs=256, prompt=32768, rho=64.0, placement="fresh",
+                 steps=32, warmup=8, evict_every=16, evict_frac=0.10),
+            dict(base, workload="llama70b", num_seqs=16, prompt=131072, rho=8.0, placement="fresh",
+                 steps=32, warmup=4, evict_every=32, evict_frac=0.10, check_heads=min(args.check_heads, 16)),
+        ):
+            try:
+                r, _, _ = run_decode_config(spec, dev)
+            except torch.OutOfMemoryError as e:   # another tenant on the card: say so rather than fail the line
+                r = {"workload": spec["workload"], "skipped": f"out of device memory: {str(e)[:120]}"}
+                torch.cuda.empty_cache()
+            other.append(r)
 
     out = {
         "metric": "decode-attn HBM GB/s (% of peak) at 8x compression; eviction+compaction ms",
-        "value": value, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "value": rec["value"], "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": rec["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if args.kv_dtype == "bf16" else "fp8 K/V (e4m3), bf16 q, f32 accumulation", "data": "synthetic",
-        "config": {"workload": name, "placement": args.placement, "evict_every": args.evict_every,
+        "config": {"workload": rec["workload"], "placement": args.placement, "evict_every": args.evict_every,
                    "evict_mode": args.evict_mode,
-                   "chunk_tokens": chunk_T, "head_instances": G,
-                   "mean_kvs_per_step": float(kv_per_step.mean())},
-        "frac_of_hbm_peak": value / HBM_PEAK_GBS,
-        "kv_only_GBps": float(kv_per_step.sum()) * 2 * shape.head_dim * shape.kv_bytes / (ms_total * 1e-3) / 1e9,
-        "decode_steps_per_s": 1e3 / ms_step,
+                   "chunk_tokens": rec["chunk_tokens"], "head_instances": rec["head_instances"],
+                   "mean_kvs_per_step": rec["mean_kvs_per_step"]},
+        "frac_of_hbm_peak": rec["frac_of_hbm_peak"],
+        "kv_only_GBps": rec["kv_only_GBps"],
+        "decode_steps_per_s": rec["decode_steps_per_s"],
         "decode_only_ms_per_step_one_call_per_layer": per_layer_ms,
         "decode_only_ms_per_step_one_call_per_layer_hip_graph": per_layer_graph_ms,
-        "wall_s": wall,
-        "eviction": evict,
+        "wall_s": rec["wall_s"],
+        "eviction": rec["eviction"],
+        "parity_sample": check["parity_sample"] if check else None,
+        "parity_sample_detail": check,
         "prefill_end": prefill_end,
+        "other_configs": other,
         "roofline": roofline,
         "cpu_baseline": cpu,
         "gpu": torch.cuda.get_device_name(0), "host_cpus": os.cpu_count(),
