@@ -292,7 +292,7 @@ def paged_decode(st: State, q, accumulate_metric=True, metric_mode="L2",
 
 
 def window_metric(st: State, q_win, w, pool=7, metric_mode="L2", accumulate=False,
-                  layer_begin=0, layer_end=None):
+                  layer_begin=0, layer_end=None, row_lse=None):
     """Prefill-end metric from an observation window (Preliminaries, "KV Cache
     Compression": sum over the last w prompt queries; Method, "Query Group
     Compression": also over the query heads of the group; "Metric Calculation":
@@ -304,10 +304,19 @@ def window_metric(st: State, q_win, w, pool=7, metric_mode="L2", accumulate=Fals
     Keys before the window get the maximum of raw over the pool//2 neighbours
     on either side, the neighbourhood cut at the ends of that prefix; keys
     inside the window keep raw.  The result replaces the metric of the head's
-    slots (or is added when accumulate)."""
+    slots (or is added when accumulate).
+
+    row_lse [S, Lyr, Hq, w] (optional): the natural logarithm of every window
+    query's softmax denominator, ln sum_j exp(q.k_j / sqrt d) over the keys it
+    attends to, as the attention kernel of a prefill leaves it.  A = softmax
+    means A_ij = exp(s_ij - lse_i) (Preliminaries, "Multi-head Attention"), so
+    when it is given the probabilities are taken as exactly that, without
+    forming the denominator again."""
     layer_end = st.Lyr if layer_end is None else layer_end
     Hq = st.Hk * st.r
     q_win = np.asarray(q_win, dtype=np.float64).reshape(st.S, st.Lyr, Hq, w, st.d)
+    if row_lse is not None:
+        row_lse = np.asarray(row_lse, dtype=np.float64).reshape(st.S, st.Lyr, Hq, w)
     half = pool // 2
     for s in range(st.S):
         for l in range(layer_begin, layer_end):
@@ -325,8 +334,11 @@ def window_metric(st: State, q_win, w, pool=7, metric_mode="L2", accumulate=Fals
                         if last < 0:
                             continue
                         sc = (K[:last + 1] @ q_win[s, l, hq, i]) / np.sqrt(float(st.d))
-                        e = np.exp(sc - sc.max())
-                        p = e / e.sum()
+                        if row_lse is None:
+                            e = np.exp(sc - sc.max())
+                            p = e / e.sum()
+                        else:
+                            p = np.exp(sc - row_lse[s, l, hq, i])
                         raw[:last + 1] += p * p if metric_mode == "L2" else p
                 P = max(0, C - w)
                 pooled = raw.copy()
@@ -339,15 +351,18 @@ def window_metric(st: State, q_win, w, pool=7, metric_mode="L2", accumulate=Fals
 
 
 def query_block_metric(st: State, q_blk, w, first_pos, exclude=0, metric_mode="L2",
-                       layer_begin=0, layer_end=None):
+                       layer_begin=0, layer_end=None, row_lse=None):
     """One block of the all-queries metric ("Metric Calculation", KVC-full):
     query i of the block sits at position first_pos + i, attends causally to
     keys 0 .. min(position, C - 1), and adds p^2 to the metric of key j only
     when position - j >= exclude (the first `exclude` queries after a key are
-    left out).  Always accumulates."""
+    left out).  Always accumulates.  row_lse [S, Lyr, Hq, w] (optional) as in
+    window_metric: p = exp(score - lse) with the caller's log-sum-exp."""
     layer_end = st.Lyr if layer_end is None else layer_end
     Hq = st.Hk * st.r
     q_blk = np.asarray(q_blk, dtype=np.float64).reshape(st.S, st.Lyr, Hq, w, st.d)
+    if row_lse is not None:
+        row_lse = np.asarray(row_lse, dtype=np.float64).reshape(st.S, st.Lyr, Hq, w)
     for s in range(st.S):
         for l in range(layer_begin, layer_end):
             for h in range(st.Hk):
@@ -363,8 +378,11 @@ def query_block_metric(st: State, q_blk, w, first_pos, exclude=0, metric_mode="L
                         pos = first_pos + i
                         last = min(pos, C - 1)
                         sc = (K[:last + 1] @ q_blk[s, l, hq, i]) / np.sqrt(float(st.d))
-                        e = np.exp(sc - sc.max())
-                        p = e / e.sum()
+                        if row_lse is None:
+                            e = np.exp(sc - sc.max())
+                            p = e / e.sum()
+                        else:
+                            p = np.exp(sc - row_lse[s, l, hq, i])
                         cnt = min(last, pos - exclude) + 1
                         if cnt > 0:
                             inc[:cnt] += (p * p if metric_mode == "L2" else p)[:cnt]

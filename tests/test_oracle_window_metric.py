@@ -127,3 +127,55 @@ def test_query_block_past_the_end_of_a_head():
     np.testing.assert_allclose(_metric_of(st), want, rtol=1e-12, atol=1e-15)
     assert want[C - 1 - (v - (start + w - 1 - (C - 1))) + 1:].sum() == 0     # keys too close to every query
     assert want[C - 3] > 0      # key 18 is 5 behind the last query (position 23): it does get its share
+
+
+def test_metrics_from_a_given_log_sum_exp():
+    """With the log-sum-exp of every query row handed over (what a prefill's attention kernel
+    leaves behind), both prefill-end metrics take A_ij = exp(s_ij - lse_i).  Pinned three ways:
+    a library logsumexp over the keys each query sees gives back the self-normalised result;
+    identical keys give the closed form 1 / (keys seen); and a log-sum-exp that is too large by
+    ln 2 halves every probability (the value is used as given, nothing is renormalised)."""
+    rng = np.random.default_rng(12)
+    r, d, b, C, w, pool = 2, 16, 4, 41, 6, 7
+    K = rng.standard_normal((C, d)); Q = rng.standard_normal((r, w, d))
+    scores = torch.from_numpy(np.einsum("hwd,cd->hwc", Q, K)) / math.sqrt(d)
+    pos = torch.arange(C).view(1, 1, C)
+    qpos = (C - w + torch.arange(w)).view(1, w, 1)
+    lse = torch.logsumexp(scores.masked_fill(pos > qpos, float("-inf")), dim=-1).numpy()     # [r, w]
+    for mode in ("L2", "L1"):
+        a = _one_head_state(K, np.zeros((C, d)), r, b)
+        c = _one_head_state(K, np.zeros((C, d)), r, b)
+        O.window_metric(a, Q.reshape(1, 1, r, w, d), w, pool, metric_mode=mode)
+        O.window_metric(c, Q.reshape(1, 1, r, w, d), w, pool, metric_mode=mode, row_lse=lse.reshape(1, 1, r, w))
+        np.testing.assert_allclose(_metric_of(c), _metric_of(a), rtol=1e-12, atol=1e-15)
+        h = _one_head_state(K, np.zeros((C, d)), r, b)
+        O.window_metric(h, Q.reshape(1, 1, r, w, d), w, pool, metric_mode=mode,
+                        row_lse=(lse + math.log(2.0)).reshape(1, 1, r, w))
+        np.testing.assert_allclose(_metric_of(h), _metric_of(a) * (0.25 if mode == "L2" else 0.5), rtol=1e-12)
+    # identical keys: every score of a row is the same number c, lse = c + ln(keys seen), p = 1 / keys seen
+    k0 = rng.standard_normal(d)
+    Ku = np.tile(k0, (C, 1))
+    qv = rng.standard_normal(d)
+    c0 = float(k0 @ qv) / math.sqrt(d)
+    seen = np.array([C - w + i + 1 for i in range(w)], dtype=np.float64)
+    st = _one_head_state(Ku, np.zeros((C, d)), r, b)
+    O.window_metric(st, np.tile(qv, (1, 1, r, w, 1)), w, 1, row_lse=np.tile(c0 + np.log(seen), (1, 1, r, 1)))
+    want = np.zeros(C)
+    for i in range(w):
+        want[:int(seen[i])] += r / seen[i] ** 2
+    np.testing.assert_allclose(_metric_of(st), want, rtol=1e-12)
+    # the block form of the all-queries metric, blocks of 8 queries with an excluded window of 3
+    L, v, blk = 29, 3, 8
+    K = rng.standard_normal((L, d)); Q = rng.standard_normal((r, L, d))
+    sc = torch.from_numpy(np.einsum("hid,jd->hij", Q, K)) / math.sqrt(d)
+    i_ = torch.arange(L).view(1, L, 1); j_ = torch.arange(L).view(1, 1, L)
+    lse_all = torch.logsumexp(sc.masked_fill(j_ > i_, float("-inf")), dim=-1).numpy()      # [r, L]
+    a = _one_head_state(K, np.zeros((L, d)), r, b)
+    c = _one_head_state(K, np.zeros((L, d)), r, b)
+    for start in range(0, L, blk):
+        wq = min(blk, L - start)
+        O.query_block_metric(a, Q[:, start:start + wq].reshape(1, 1, r, wq, d), wq, start, v)
+        O.query_block_metric(c, Q[:, start:start + wq].reshape(1, 1, r, wq, d), wq, start, v,
+                             row_lse=lse_all[:, start:start + wq].reshape(1, 1, r, wq))
+    np.testing.assert_allclose(_metric_of(c), _metric_of(a), rtol=1e-12, atol=1e-15)
+    assert _metric_of(a).sum() > 0
