@@ -521,6 +521,18 @@ def prefill_end_probe(dev, all_queries_block):
     b_.record()
     torch.cuda.synchronize()
     all_queries_ms = a.elapsed_time(b_)
+    # the same with every query's log-sum-exp handed over, as a prefill's attention kernel leaves it
+    # (one pass over the keys instead of two); for timing any plausible value serves: ln(keys seen) + 1/2
+    pos = torch.arange(wb, device=dev, dtype=torch.float32)
+    s4.cache.metric.zero_()
+    a, b_ = ev(), ev()
+    a.record()
+    for start in range(0, Lp, wb):
+        lse_b = (torch.log(pos + float(start + 1)) + 0.5).expand(1, 32, 32, wb).contiguous()
+        s4.query_block_metric(qb, wb, start, excl, row_lse=lse_b)
+    b_.record()
+    torch.cuda.synchronize()
+    all_queries_lse_ms = a.elapsed_time(b_)
     del qb
     best = 1e9
     for _ in range(4):
@@ -530,6 +542,15 @@ def prefill_end_probe(dev, all_queries_block):
         b_.record()
         torch.cuda.synchronize()
         best = min(best, a.elapsed_time(b_))
+    lse_w = (torch.log(torch.arange(wq, device=dev, dtype=torch.float32) + float(Lp - wq + 1)) + 0.5).expand(1, 32, 32, wq).contiguous()
+    best_lse = 1e9
+    for _ in range(4):
+        a, b_ = ev(), ev()
+        a.record()
+        s4.window_metric(qw, wq, 7, row_lse=lse_w)
+        b_.record()
+        torch.cuda.synchronize()
+        best_lse = min(best_lse, a.elapsed_time(b_))
     kvs4 = shp.G * Lp
     bud4 = torch.tensor([shp.G * (Lp // 16) * 7 // 8], dtype=torch.int32, device=dev)
     s4.evict_rank_select(bud4, flags=B.KVC_ASYNC)   # untimed first call (selection changes no cache state)
@@ -569,12 +590,18 @@ def prefill_end_probe(dev, all_queries_block):
            "window_metric_TFLOPs": win_flop / (best * 1e-3) / 1e12,
            "window_metric_executed_two_pass": {"K_GBps": 2 * win_bytes / (best * 1e-3) / 1e9,
                                                "TFLOPs": 2 * win_flop / (best * 1e-3) / 1e12},
+           "window_metric_given_lse_ms": best_lse,
+           "window_metric_given_lse_K_GBps": win_bytes / (best_lse * 1e-3) / 1e9,
+           "window_metric_given_lse_frac_of_hbm_peak": win_bytes / (best_lse * 1e-3) / 1e9 / HBM_PEAK_GBS,
            "rank_select_to_8x_ms": select_ms, "rank_compact_ms": compact_ms,
            "kvs_after": kvs_after, "kvs_before": kvs4,
            "all_queries_metric_ms": all_queries_ms, "all_queries_block": wb, "all_queries_exclude": excl,
            "all_queries_TFLOPs": all_flop / (all_queries_ms * 1e-3) / 1e12,
            "all_queries_frac_of_bf16_mfma_peak": all_flop / (all_queries_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
            "all_queries_executed_two_pass_TFLOPs": 2 * all_flop / (all_queries_ms * 1e-3) / 1e12,
+           "all_queries_given_lse_ms": all_queries_lse_ms,
+           "all_queries_given_lse_TFLOPs": all_flop / (all_queries_lse_ms * 1e-3) / 1e12,
+           "all_queries_given_lse_frac_of_bf16_mfma_peak": all_flop / (all_queries_lse_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
            "decode_steps_after": nd, "decode_ms_per_step_after": decode_ms,
            "decode_GBps_after": (kvs_after + shp.G * nd / 2) * algorithmic_bytes_per_kv(shp) / (decode_ms * 1e-3) / 1e9}
     del s4, qw, q4, kv4

@@ -285,17 +285,21 @@ int kvc_compact_rank(const kvc_config* cfg, const kvc_state* st, const int32_t* 
  * attention summed over the last w prompt queries, max-pooled over the sequence; "Query Group
  * Compression": and over the query heads of the group; "Metric Calculation", KVC-w: squared
  * before summation, p itself with KVC_L1) over layers [layer_begin, layer_end).
- * q_win [S, Lyr, Hq, w, d] kv_dtype: window query i of a head with C = ctx_len KVs sits at
+ * q_win [S, Lyr, Hq, w, d] bf16: window query i of a head with C = ctx_len KVs sits at
  * position C - w + i and attends to keys 0 .. C - w + i; queries that would sit before
  * position 0 are ignored.  raw[j] = sum over the r heads and w queries of p^2.  Keys before
  * the window get max(raw[j - pool/2 .. j + pool/2]) with the range cut at the ends of that
  * prefix (pool odd; 1 = no pooling); keys inside the window keep raw.  The result replaces
  * metric[slot] of every KV of those layers, or is added to it when accumulate != 0.
- * Runs on the matrix cores; covers kv_dtype = KVC_BF16, head_dim = 128, block_size in
- * {16, 32, 64}, w <= 64 and w * group_size <= 256, else KVC_ERR_UNSUPPORTED (such callers can
- * gather the same sums with one kvc_paged_decode per window query).  Asynchronous. */
-int kvc_window_metric(const kvc_config* cfg, const kvc_state* st, const void* q_win, int w, int pool,
-                      int accumulate, int layer_begin, int layer_end, void* ws, void* stream);
+ * row_lse [S, Lyr, Hq, w] f32 (device) or NULL: ln of every window query's softmax
+ * denominator over the keys it attends to (what a prefill's attention kernel leaves per query
+ * row).  With it p = exp(q.k / sqrt d - row_lse) is formed in ONE pass over the keys; without
+ * it the kernels first pass over the keys once more to find the denominators themselves.
+ * Runs on the matrix cores; covers kv_dtype = KVC_BF16 and KVC_FP8_E4M3, head_dim 64 and 128,
+ * every block size, w <= 64 and w * group_size <= 256, else KVC_ERR_UNSUPPORTED (such callers
+ * can gather the same sums with one kvc_paged_decode per window query).  Asynchronous. */
+int kvc_window_metric(const kvc_config* cfg, const kvc_state* st, const void* q_win, const float* row_lse,
+                      int w, int pool, int accumulate, int layer_begin, int layer_end, void* ws, void* stream);
 
 /* Building block of the all-queries metric ("Metric Calculation", KVC-full: squared attention
  * aggregated over all observed queries, one block of queries at a time, leaving out the first v
@@ -303,11 +307,12 @@ int kvc_window_metric(const kvc_config* cfg, const kvc_state* st, const void* q_
  * (the same for every head; a prefill), attends to keys 0 .. min(position, ctx_len - 1), and
  * adds p^2 (p with KVC_L1) to metric[slot of key j] only when j <= position - exclude.
  * Always accumulates; no pooling.  Calling it for consecutive blocks of a prompt's queries
- * builds M_full[j] = sum over i >= j + v and the group's heads of A_ij^2.  Shapes and errors as
- * kvc_window_metric, except that w may be any length (the paper aggregates 1024 queries at a
- * time): a longer block is worked off 64 queries, or 256 query rows, at a time.  Asynchronous. */
-int kvc_query_block_metric(const kvc_config* cfg, const kvc_state* st, const void* q_blk, int w,
-                           int first_pos, int exclude, int layer_begin, int layer_end, void* ws,
+ * builds M_full[j] = sum over i >= j + v and the group's heads of A_ij^2.  row_lse
+ * [S, Lyr, Hq, w] or NULL, shapes and errors as kvc_window_metric, except that w may be any
+ * length (the paper aggregates 1024 queries at a time): a longer block is worked off 64
+ * queries, or 256 query rows, at a time.  Asynchronous.                            */
+int kvc_query_block_metric(const kvc_config* cfg, const kvc_state* st, const void* q_blk, const float* row_lse,
+                           int w, int first_pos, int exclude, int layer_begin, int layer_end, void* ws,
                            void* stream);
 
 /* Tuning knob of kvc_paged_decode: tokens handled by one workgroup before a

@@ -84,8 +84,8 @@ def lib() -> C.CDLL:
         L.kvc_preempt.argtypes = [cfgp, stp, P, C.POINTER(C.c_int64), P, P, I]
         L.kvc_check_state.argtypes = [cfgp, stp, P, P, I]
         L.kvc_compression_batch.argtypes = [cfgp, stp, P, P, C.c_int64, P, P, P, P]
-        L.kvc_window_metric.argtypes = [cfgp, stp, P, I, I, I, I, I, P, P]
-        L.kvc_query_block_metric.argtypes = [cfgp, stp, P, I, I, I, I, I, P, P]
+        L.kvc_window_metric.argtypes = [cfgp, stp, P, P, I, I, I, I, I, P, P]
+        L.kvc_query_block_metric.argtypes = [cfgp, stp, P, P, I, I, I, I, I, P, P]
         L.kvc_get_decode_chunk.argtypes = [cfgp, C.POINTER(C.c_int)]
         L.kvc_get_decode_short.argtypes = [cfgp, C.POINTER(C.c_int)]
         L.kvc_profile_begin.argtypes = [I]
@@ -289,14 +289,16 @@ def kvc_compact_rank(cfg, st, evict_rows, blocks_freed, ws, stream=None, flags=0
                                   _ptr(ws), _stream(stream), flags), "kvc_compact_rank")
 
 
-def kvc_window_metric(cfg, st, q_win, w, pool, accumulate, layer_begin, layer_end, ws, stream=None):
-    _check(lib().kvc_window_metric(C.byref(cfg), C.byref(st), _ptr(q_win), int(w), int(pool), int(accumulate),
-                                   layer_begin, layer_end, _ptr(ws), _stream(stream)), "kvc_window_metric")
+def kvc_window_metric(cfg, st, q_win, row_lse, w, pool, accumulate, layer_begin, layer_end, ws, stream=None):
+    _check(lib().kvc_window_metric(C.byref(cfg), C.byref(st), _ptr(q_win),
+                                   _ptr(row_lse, torch.float32) if row_lse is not None else None, int(w), int(pool),
+                                   int(accumulate), layer_begin, layer_end, _ptr(ws), _stream(stream)), "kvc_window_metric")
 
 
-def kvc_query_block_metric(cfg, st, q_blk, w, first_pos, exclude, layer_begin, layer_end, ws, stream=None):
-    _check(lib().kvc_query_block_metric(C.byref(cfg), C.byref(st), _ptr(q_blk), int(w), int(first_pos),
-                                        int(exclude), layer_begin, layer_end, _ptr(ws), _stream(stream)),
+def kvc_query_block_metric(cfg, st, q_blk, row_lse, w, first_pos, exclude, layer_begin, layer_end, ws, stream=None):
+    _check(lib().kvc_query_block_metric(C.byref(cfg), C.byref(st), _ptr(q_blk),
+                                        _ptr(row_lse, torch.float32) if row_lse is not None else None, int(w),
+                                        int(first_pos), int(exclude), layer_begin, layer_end, _ptr(ws), _stream(stream)),
            "kvc_query_block_metric")
 
 

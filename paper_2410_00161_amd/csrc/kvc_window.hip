@@ -21,6 +21,7 @@
 // keys (online, then merged over lanes, wavefronts and chunks); (2) normalised
 // probabilities, squared, summed over the query rows per key.  V is never
 // read.  A last light pass max-pools over the logical sequence.
+#include <cmath>
 #include <type_traits>
 
 #include "kvc_common.h"
@@ -46,6 +47,8 @@ struct WindowArgs {
   int exclude;         // a query at position x adds to key j only when j <= x - exclude
   float* part;         // [partial slot][rows_pad][2]
   float* raw;          // [N * b] un-pooled sums, by physical slot
+  const float* lse;    // [S, Lyr, Hq, q_count] natural-log softmax denominators from the caller, or NULL
+  int reverse;         // pass 2 walks the work list backwards (what pass 1 read last is read first)
 };
 
 // Last key, in a head of C KVs, that any query of the call sees (lag = 0; query i sits at
@@ -78,11 +81,31 @@ template <> struct Mma<32> {
   }
   static __device__ __forceinline__ int token(int i, int lane) { return (i & 3) + 8 * (i >> 2) + 4 * (lane >> 5); }
 };
-// lanes that share a query row; 16-byte k-slices of a lane's part of a 256-byte row; products
-// per 64-token tile
+// lanes that share a query row; k-slices (8 elements: 16 bytes of a query row, 16 or 8 bytes of a
+// key row) of a lane's part of a row of HD elements; products per 64-token tile
 template <int M> constexpr int kLanesPerRow = 64 / M;
-template <int M> constexpr int kSlices = 16 / kLanesPerRow<M>;
+template <int M, int HD> constexpr int kSlices = (HD / 8) / kLanesPerRow<M>;
 template <int M> constexpr int kProducts = 64 / M;
+
+// The piece of a key row a lane loads per k-slice, and its eight elements as packed bf16 (8-bit
+// rows are widened exactly: 3 mantissa bits fit in 7).
+template <int ESZ> struct KPiece;
+template <> struct KPiece<2> {
+  typedef uint4 Raw;
+  static __device__ __forceinline__ Raw zero() { return make_uint4(0, 0, 0, 0); }
+  static __device__ __forceinline__ uint4 widen(const uint4& a) { return a; }
+};
+template <> struct KPiece<1> {
+  typedef uint2 Raw;
+  typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+  static __device__ __forceinline__ Raw zero() { return make_uint2(0, 0); }
+  static __device__ __forceinline__ uint4 widen(const uint2& a) {
+    return make_uint4(__builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(a.x, 1.0f, false)),
+                      __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(a.x, 1.0f, true)),
+                      __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(a.y, 1.0f, false)),
+                      __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(a.y, 1.0f, true)));
+  }
+};
 
 // Q of one head instance into LDS, in B-operand order: entry ((ct * KS + s) * 64 + lane) holds,
 // for query row ct * M + lane % M, the 8 dimensions at byte 16 KS (lane / M) + 16 s of the row.
@@ -91,13 +114,15 @@ template <int M> constexpr int kProducts = 64 / M;
 // thread's loads before its stores; the LDS writes then meet a 4-way bank conflict, well under
 // a microsecond per workgroup.  (One lane per LDS entry in entry order, every 16-byte read on
 // a line of its own, measured the same.)
-template <int M, int NT>
+template <int HD, int M, int NT>
 __device__ __forceinline__ void stage_queries(const WindowArgs& W, int g, uint4* s_q) {
-  constexpr int KS = kSlices<M>, ROWS = NT * M;
-  constexpr int PER = ROWS * 16 / kWinThreads;   // pieces per thread
-  static_assert(PER * kWinThreads == ROWS * 16 && PER <= 16, "whole rounds of the workgroup");
+  constexpr int KS = kSlices<M, HD>, ROWS = NT * M;
+  constexpr int QP = HD / 8;                      // 16-byte pieces of a query row
+  constexpr int QROWB = HD * 2;
+  constexpr int PER = ROWS * QP / kWinThreads;    // pieces per thread
+  static_assert(PER * kWinThreads == ROWS * QP && PER >= 1 && PER <= 16, "whole rounds of the workgroup");
   const int r = W.A.D.r, w = W.q_count;
-  const char* qbase = W.A.q + ((size_t)g * r * w + W.q_first) * 256;  // [r][q_count][128] bf16, from query q_first
+  const char* qbase = W.A.q + ((size_t)g * r * w + W.q_first) * QROWB;  // [r][q_count][HD] bf16, from query q_first
   // all of a thread's loads first, then its stores: one trip to memory, not PER of them
   uint4 v[PER];
 #pragma unroll
@@ -107,7 +132,7 @@ __device__ __forceinline__ void stage_queries(const WindowArgs& W, int g, uint4*
     const int c = 4 * ((e >> 2) / ROWS) + (e & 3);   // 16-byte piece of the row
     const int i = rho / r, hh = rho % r;
     // (rows past w * r read row 0 and are zeroed: a select between values, no branch around a load)
-    const uint4 t = *(const uint4*)(qbase + (rho < W.rows ? (size_t)hh * w + i : 0) * 256 + 16 * c);
+    const uint4 t = *(const uint4*)(qbase + (rho < W.rows ? (size_t)hh * w + i : 0) * QROWB + 16 * c);
     v[it] = rho < W.rows ? t : make_uint4(0, 0, 0, 0);
   }
 #pragma unroll
@@ -120,21 +145,24 @@ __device__ __forceinline__ void stage_queries(const WindowArgs& W, int g, uint4*
 }
 
 // Loads the 64-token tile starting at chunk token `tt` as A operands of M tokens each: lane
-// (token lane % M, part lane / M of its row) holds that part's k-slices.  16-token blocks past
-// the end of the chunk are not touched and read as zero.
-template <int M>
+// (token lane % M, part lane / M of its row) holds that part's k-slices.  Every lane looks its own
+// token's block up (blocks may be shorter than the 16 tokens that share a row of lanes); tokens
+// past the end of the chunk are not touched and read as zero.
+template <int ESZ, int HD, int M>
 __device__ __forceinline__ void load_tile(const WindowArgs& W, const int* s_tab, int tt, int n_tok, int lane,
-                                          uint4 (&k)[kProducts<M>][kSlices<M>]) {
-  constexpr int KS = kSlices<M>;
+                                          typename KPiece<ESZ>::Raw (&k)[kProducts<M>][kSlices<M, HD>]) {
+  constexpr int KS = kSlices<M, HD>;
+  constexpr int PB = 8 * ESZ;                     // bytes of one k-slice of a key row
+  typedef typename KPiece<ESZ>::Raw Raw;
   const int lb = W.A.log2b, b = W.A.D.b;
 #pragma unroll
   for (int pr = 0; pr < kProducts<M>; ++pr) {
-    const int t = tt + pr * M + (lane & (M - 16));   // first token of this lane's 16-token block
+    const int t = tt + pr * M + (lane & (M - 1));
     const bool live = t < n_tok;
-    const size_t slot = live ? ((size_t)s_tab[t >> lb] << lb) + (t & (b - 1)) + (lane & 15) : 0;
-    const char* p = W.A.kc + slot * 256 + 16 * KS * (lane / M);
+    const size_t slot = live ? ((size_t)s_tab[t >> lb] << lb) + (t & (b - 1)) : 0;
+    const char* p = W.A.kc + slot * (size_t)(HD * ESZ) + PB * KS * (lane / M);
 #pragma unroll
-    for (int sl = 0; sl < KS; ++sl) k[pr][sl] = live ? *(const uint4*)(p + 16 * sl) : make_uint4(0, 0, 0, 0);
+    for (int sl = 0; sl < KS; ++sl) k[pr][sl] = live ? *(const Raw*)(p + PB * sl) : KPiece<ESZ>::zero();
   }
 }
 
@@ -145,10 +173,11 @@ __device__ __forceinline__ void load_tile(const WindowArgs& W, const int* s_tab,
 __host__ __device__ constexpr int window_pairs_per_tile(int m, int nt) { return nt * m >= 256 ? m : 64; }
 
 // Pass 1: per chunk and query row, max and sum of exp2 over the visible keys.
-template <int M, int NT>
+template <int ESZ, int HD, int M, int NT>
 __global__ void __launch_bounds__(kWinThreads) window_stats_kernel(WindowArgs W) {
   typedef Mma<M> MM;
-  constexpr int KS = kSlices<M>, NP = kProducts<M>, ROWS = NT * M;
+  typedef typename KPiece<ESZ>::Raw Raw;
+  constexpr int KS = kSlices<M, HD>, NP = kProducts<M>, ROWS = NT * M;
   constexpr int PPT = window_pairs_per_tile(M, NT);
   constexpr bool kRowMerged = PPT == M;
   const DecodeArgs& A = W.A;
@@ -177,13 +206,18 @@ __global__ void __launch_bounds__(kWinThreads) window_stats_kernel(WindowArgs W)
     const int32_t* row = A.table + (size_t)g * A.D.maxb + (t0 >> lb);
     for (int i = tid; i < nblk; i += kWinThreads) s_tab[i] = row[i];
   }
-  stage_queries<M, NT>(W, g, s_q);
+  stage_queries<HD, M, NT>(W, g, s_q);
   __syncthreads();
   // running (max, sum) per column tile: kept in LDS so that the loop over column tiles stays a
   // loop (registers: one K tile and one Q tile at a time)
   float2* my_st = s_st + (size_t)wv * NT * PPT + (lane & (PPT - 1));
   for (int ct = 0; ct < NT; ++ct) my_st[ct * PPT] = make_float2(-INFINITY, 0.0f);
-  auto tile = [&](uint4 (&k)[NP][KS], int tt) {
+  auto tile = [&](Raw (&kraw)[NP][KS], int tt) {
+    uint4 k[NP][KS];
+#pragma unroll
+    for (int pr = 0; pr < NP; ++pr)
+#pragma unroll
+      for (int sl = 0; sl < KS; ++sl) k[pr][sl] = KPiece<ESZ>::widen(kraw[pr][sl]);
     // most tiles lie wholly in front of the window: they run the loop without the causal mask
     auto column_tiles = [&](auto masked_c) {
       constexpr bool kMasked = decltype(masked_c)::value;
@@ -244,8 +278,8 @@ __global__ void __launch_bounds__(kWinThreads) window_stats_kernel(WindowArgs W)
     else column_tiles(std::false_type{});
   };
   for (int tt = wv * 64; tt < min(n_tok, n_seen); tt += 64 * kWinWaves) {
-    uint4 k[NP][KS];
-    load_tile<M>(W, s_tab, tt, n_tok, lane, k);
+    Raw k[NP][KS];
+    load_tile<ESZ, HD, M>(W, s_tab, tt, n_tok, lane, k);
     tile(k, tt);
   }
   __syncthreads();   // every wavefront is done with Q: its bytes now take the per-wavefront pairs
@@ -306,16 +340,19 @@ __global__ void __launch_bounds__(256) window_rows_kernel(WindowArgs W, int rows
 }
 
 // Pass 2: raw[j] = sum over query rows of p^2 (or p), p normalised with the head's max and sum.
-template <int M, int NT, bool L2>
+template <int ESZ, int HD, int M, int NT, bool L2>
 __global__ void __launch_bounds__(kWinThreads) window_sum_kernel(WindowArgs W) {
   typedef Mma<M> MM;
-  constexpr int KS = kSlices<M>, NP = kProducts<M>, ROWS = NT * M;
+  typedef typename KPiece<ESZ>::Raw Raw;
+  constexpr int KS = kSlices<M, HD>, NP = kProducts<M>, ROWS = NT * M;
   const DecodeArgs& A = W.A;
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   const int total_items = A.header[HW_TOTAL_ITEMS];
   if (blockIdx.x == 0 && tid < HW_DEC_END - HW_DEC_BINS) A.header[HW_DEC_BINS + tid] = 0;  // work-list block back to zero
   if ((int)blockIdx.x >= total_items || total_items > A.cap) return;
-  const DecodeItem it = A.items[blockIdx.x];
+  // Backwards through the list when this pass follows pass 1: the keys that pass read last are the
+  // ones still held by the memory-side cache, and this pass reads them first.
+  const DecodeItem it = A.items[W.reverse ? total_items - 1 - (int)blockIdx.x : (int)blockIdx.x];
   const int g = it.g, t0 = it.t0, n_tok = it.n_tok, nch = it.nch;
   if ((unsigned)g >= (unsigned)A.D.G || n_tok <= 0 || n_tok > A.T || t0 < 0 || nch <= 0 || it.pbase < 0 ||
       it.pbase + nch > A.cap)
@@ -335,10 +372,22 @@ __global__ void __launch_bounds__(kWinThreads) window_sum_kernel(WindowArgs W) {
   }
   const int first_free = W.first_pos >= 0 ? W.first_pos : C - W.w;
   const int free_lim = min(first_free - W.exclude, C - 1);   // keys up to here count for every query
-  stage_queries<M, NT>(W, g, s_q);
-  for (int rho = tid; rho < ROWS; rho += kWinThreads) s_ml[rho] = W.part[((size_t)it.pbase * ROWS + rho) * 2];
+  stage_queries<HD, M, NT>(W, g, s_q);
+  for (int rho = tid; rho < ROWS; rho += kWinThreads) {
+    if (W.lse) {   // the caller's ln(sum of exp) per query row, to log2 units; padded rows add nothing
+      const int i = rho / A.D.r, hh = rho % A.D.r;
+      s_ml[rho] = rho < W.rows ? W.lse[((size_t)g * A.D.r + hh) * W.q_count + W.q_first + i] * 1.4426950408889634f : INFINITY;
+    } else {
+      s_ml[rho] = W.part[((size_t)it.pbase * ROWS + rho) * 2];
+    }
+  }
   __syncthreads();
-  auto tile = [&](uint4 (&k)[NP][KS], int tt) {
+  auto tile = [&](Raw (&kraw)[NP][KS], int tt) {
+    uint4 k[NP][KS];
+#pragma unroll
+    for (int pr = 0; pr < NP; ++pr)
+#pragma unroll
+      for (int sl = 0; sl < KS; ++sl) k[pr][sl] = KPiece<ESZ>::widen(kraw[pr][sl]);
     float tok[M];   // [product][element]
 #pragma unroll
     for (int e = 0; e < M; ++e) tok[e] = 0.0f;
@@ -387,8 +436,8 @@ __global__ void __launch_bounds__(kWinThreads) window_sum_kernel(WindowArgs W) {
     }
   };
   for (int tt = wv * 64; tt < min(n_tok, n_fed); tt += 64 * kWinWaves) {
-    uint4 k[NP][KS];
-    load_tile<M>(W, s_tab, tt, n_tok, lane, k);
+    Raw k[NP][KS];
+    load_tile<ESZ, HD, M>(W, s_tab, tt, n_tok, lane, k);
     tile(k, tt);
   }
 }
@@ -433,32 +482,45 @@ __global__ void __launch_bounds__(256) window_pool_kernel(WindowArgs W) {
   }
 }
 
-template <int M, int NT>
+template <int ESZ, int HD, int M, int NT>
 static int launch_window(const WindowArgs& W, int grid, hipStream_t s) {
   // pass 1: Q (later the per-wavefront pairs), running pairs per column tile, block ids;
-  // pass 2: Q, one float per query row, block ids.  Three and four workgroups per CU at 128 rows,
-  // two and two at 256.
-  constexpr size_t q_bytes = (size_t)NT * M * 256, rows = (size_t)NT * M;
+  // pass 2: Q, one float per query row, block ids.  Three and four workgroups per CU at 128 rows
+  // of d = 128, two and two at 256.
+  constexpr size_t q_bytes = (size_t)NT * M * HD * 2, rows = (size_t)NT * M;
   const size_t tab = ((size_t)kWinChunk / W.A.D.b + 1) * 4;
+  static_assert((size_t)kWinWaves * rows * 2 * 4 <= q_bytes, "the per-wavefront pairs of pass 1 fit where Q was");
   const size_t lds = q_bytes + (size_t)kWinWaves * NT * window_pairs_per_tile(M, NT) * 8 + tab;
   const size_t lds2 = q_bytes + rows * 4 + tab;
-  static_assert((size_t)kWinWaves * rows * 2 * 4 <= q_bytes, "pairs fit where Q was");
   static std::atomic<size_t> allowed{0};   // above the default cap a kernel must be told how much it may take
-  if (lds > 64 * 1024 && lds > allowed.load(std::memory_order_acquire)) {   // (lds >= lds2; the block-id array grows as blocks shrink)
-    KVC_HIP(hipFuncSetAttribute((const void*)window_stats_kernel<M, NT>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    KVC_HIP(hipFuncSetAttribute((const void*)window_sum_kernel<M, NT, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    KVC_HIP(hipFuncSetAttribute((const void*)window_sum_kernel<M, NT, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+  const size_t most = lds > lds2 ? lds : lds2;
+  if (most > 64 * 1024 && most > allowed.load(std::memory_order_acquire)) {   // (the block-id array grows as blocks shrink)
+    KVC_HIP(hipFuncSetAttribute((const void*)window_stats_kernel<ESZ, HD, M, NT>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)most));
+    KVC_HIP(hipFuncSetAttribute((const void*)window_sum_kernel<ESZ, HD, M, NT, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)most));
+    KVC_HIP(hipFuncSetAttribute((const void*)window_sum_kernel<ESZ, HD, M, NT, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)most));
     size_t seen = allowed.load(std::memory_order_relaxed);
-    while (seen < lds && !allowed.compare_exchange_weak(seen, lds, std::memory_order_release)) {}
+    while (seen < most && !allowed.compare_exchange_weak(seen, most, std::memory_order_release)) {}
   }
-  hipLaunchKernelGGL((window_stats_kernel<M, NT>), dim3(grid), dim3(kWinThreads), lds, s, W);
-  KVC_LAUNCH_CHECK();
-  hipLaunchKernelGGL(window_rows_kernel, dim3(grid), dim3(256), 0, s, W, (int)rows);
-  KVC_LAUNCH_CHECK();
-  if (W.A.D.mode == KVC_L2) hipLaunchKernelGGL((window_sum_kernel<M, NT, true>), dim3(grid), dim3(kWinThreads), lds2, s, W);
-  else hipLaunchKernelGGL((window_sum_kernel<M, NT, false>), dim3(grid), dim3(kWinThreads), lds2, s, W);
+  if (!W.lse) {   // with the caller's log-sum-exp there is nothing for pass 1 to find
+    hipLaunchKernelGGL((window_stats_kernel<ESZ, HD, M, NT>), dim3(grid), dim3(kWinThreads), lds, s, W);
+    KVC_LAUNCH_CHECK();
+    hipLaunchKernelGGL(window_rows_kernel, dim3(grid), dim3(256), 0, s, W, (int)rows);
+    KVC_LAUNCH_CHECK();
+  }
+  if (W.A.D.mode == KVC_L2) hipLaunchKernelGGL((window_sum_kernel<ESZ, HD, M, NT, true>), dim3(grid), dim3(kWinThreads), lds2, s, W);
+  else hipLaunchKernelGGL((window_sum_kernel<ESZ, HD, M, NT, false>), dim3(grid), dim3(kWinThreads), lds2, s, W);
   KVC_LAUNCH_CHECK();
   return KVC_OK;
+}
+
+template <int ESZ, int HD>
+static int launch_window_rows(const WindowArgs& W, int padded_rows, int grid, hipStream_t s) {
+  switch (padded_rows) {
+    case 32: return launch_window<ESZ, HD, 16, 2>(W, grid, s);
+    case 64: return launch_window<ESZ, HD, 16, 4>(W, grid, s);
+    case 128: return launch_window<ESZ, HD, 16, 8>(W, grid, s);
+    default: return launch_window<ESZ, HD, 32, 8>(W, grid, s);
+  }
 }
 
 }  // namespace kvc
@@ -468,16 +530,18 @@ using namespace kvc;
 extern "C" {
 
 static int window_common(const kvc_config* cfg, const kvc_state* st, const void* q_win, int w, int pool,
-                         int accumulate, int first_pos, int exclude, int layer_begin, int layer_end, void* ws,
-                         void* stream) {
+                         int accumulate, int first_pos, int exclude, const float* row_lse, int layer_begin,
+                         int layer_end, void* ws, void* stream) {
   int rc = validate(cfg, st);
   if (rc != KVC_OK) return rc;
-  if (!q_win || !ws || ((uintptr_t)ws & 255) || ((uintptr_t)q_win & 15)) return KVC_ERR_ARG;
+  if (!q_win || !ws || ((uintptr_t)ws & 255) || ((uintptr_t)q_win & 15) || ((uintptr_t)row_lse & 3)) return KVC_ERR_ARG;
   Dims D = dims_of(cfg);
   if (layer_begin < 0 || layer_end > D.Lyr || layer_begin >= layer_end) return KVC_ERR_ARG;
   if (w <= 0 || pool <= 0 || (pool & 1) == 0 || exclude < 0) return KVC_ERR_ARG;
-  // the matrix-core kernels cover bf16, d = 128, blocks of a multiple of 16 tokens, up to 256 query rows
-  if (D.dtype != KVC_BF16 || D.d != 128 || D.b % 16 != 0 || 64 % D.b != 0) return KVC_ERR_UNSUPPORTED;
+  // the matrix-core kernels cover 16-bit and 8-bit rows (bf16 queries), d = 64 or 128, any block
+  // size that divides a chunk, up to 256 query rows
+  if ((D.dtype != KVC_BF16 && D.dtype != KVC_FP8_E4M3) || (D.d != 128 && D.d != 64) || kWinChunk % D.b != 0)
+    return KVC_ERR_UNSUPPORTED;
   // One pass of the kernels takes at most 64 queries and 256 query rows (a chunk's pairs, 8 bytes
   // per padded query row, live in the decode's slot of r * d floats).  A block of queries at a
   // given position may be longer: it is worked off in such passes over one work list.
@@ -504,10 +568,12 @@ static int window_common(const kvc_config* cfg, const kvc_state* st, const void*
   A.cap = (int)(max_items_of(D) < 0x7fffffffull ? max_items_of(D) : 0x7fffffffull);
   A.items = (DecodeItem*)Wk.items; A.slot_item = Wk.slot_item; A.part_ml = Wk.part_ml; A.part_acc = Wk.part_acc; A.stash = Wk.stash;
   A.header = Wk.header;
-  A.scale_log2 = (float)(1.4426950408889634 / 11.313708498984761);  // log2(e) / sqrt(128)
+  A.scale_log2 = (float)(1.4426950408889634 / sqrt((double)D.d));
   W.pool = pool; W.add = accumulate != 0; W.exclude = exclude;
   W.q_count = w;
   W.part = Wk.part_acc; W.raw = Wk.stash;
+  W.lse = row_lse;
+  W.reverse = row_lse == nullptr;
   // a head that holds no KV has no output here: the item kernel's zero rows must not be written
   if (A.gsel <= kSmallWorklistHeads) {
     hipLaunchKernelGGL(decode_worklist_small_kernel, dim3(1), dim3(1024), 0, s, A);
@@ -529,12 +595,9 @@ static int window_common(const kvc_config* cfg, const kvc_state* st, const void*
     W.w = w - q0 < w_pass ? w - q0 : w_pass;
     W.rows = W.w * D.r;
     W.first_pos = first_pos < 0 ? first_pos : first_pos + q0;
-    switch (padded(W.rows)) {
-      case 32: rc = launch_window<16, 2>(W, (int)grid, s); break;
-      case 64: rc = launch_window<16, 4>(W, (int)grid, s); break;
-      case 128: rc = launch_window<16, 8>(W, (int)grid, s); break;
-      default: rc = launch_window<32, 8>(W, (int)grid, s); break;
-    }
+    const int pr = padded(W.rows);
+    if (D.dtype == KVC_BF16) rc = D.d == 128 ? launch_window_rows<2, 128>(W, pr, (int)grid, s) : launch_window_rows<2, 64>(W, pr, (int)grid, s);
+    else rc = D.d == 128 ? launch_window_rows<1, 128>(W, pr, (int)grid, s) : launch_window_rows<1, 64>(W, pr, (int)grid, s);
     if (rc != KVC_OK) return rc;
     hipLaunchKernelGGL(window_pool_kernel, dim3(A.gsel, pool_tiles), dim3(256), 0, s, W);
     KVC_LAUNCH_CHECK();
@@ -542,15 +605,15 @@ static int window_common(const kvc_config* cfg, const kvc_state* st, const void*
   return KVC_OK;
 }
 
-int kvc_window_metric(const kvc_config* cfg, const kvc_state* st, const void* q_win, int w, int pool,
-                      int accumulate, int layer_begin, int layer_end, void* ws, void* stream) {
-  return window_common(cfg, st, q_win, w, pool, accumulate, -1, 0, layer_begin, layer_end, ws, stream);
+int kvc_window_metric(const kvc_config* cfg, const kvc_state* st, const void* q_win, const float* row_lse, int w,
+                      int pool, int accumulate, int layer_begin, int layer_end, void* ws, void* stream) {
+  return window_common(cfg, st, q_win, w, pool, accumulate, -1, 0, row_lse, layer_begin, layer_end, ws, stream);
 }
 
-int kvc_query_block_metric(const kvc_config* cfg, const kvc_state* st, const void* q_blk, int w, int first_pos,
-                           int exclude, int layer_begin, int layer_end, void* ws, void* stream) {
+int kvc_query_block_metric(const kvc_config* cfg, const kvc_state* st, const void* q_blk, const float* row_lse, int w,
+                           int first_pos, int exclude, int layer_begin, int layer_end, void* ws, void* stream) {
   if (first_pos < 0) return KVC_ERR_ARG;
-  return window_common(cfg, st, q_blk, w, 1, 1, first_pos, exclude, layer_begin, layer_end, ws, stream);
+  return window_common(cfg, st, q_blk, w, 1, 1, first_pos, exclude, row_lse, layer_begin, layer_end, ws, stream);
 }
 
 }  // extern "C"

@@ -102,12 +102,13 @@ class KvcSession:
                                 kv_limit, in_batch, kvs, self.ws)
         return in_batch, kvs
 
-    def window_metric(self, q_win, w, pool=7, accumulate=False, layer_begin=0, layer_end=None):
+    def window_metric(self, q_win, w, pool=7, accumulate=False, layer_begin=0, layer_end=None, row_lse=None):
         layer_end = self.shape.num_layers if layer_end is None else layer_end
-        B.kvc_window_metric(self.cfg, self.st, q_win, w, pool, accumulate, layer_begin, layer_end, self.ws)
+        B.kvc_window_metric(self.cfg, self.st, q_win, row_lse, w, pool, accumulate, layer_begin, layer_end, self.ws)
         return self.cache.metric
 
-    def query_block_metric(self, q_blk, w, first_pos, exclude=0, layer_begin=0, layer_end=None):
+    def query_block_metric(self, q_blk, w, first_pos, exclude=0, layer_begin=0, layer_end=None, row_lse=None):
         layer_end = self.shape.num_layers if layer_end is None else layer_end
-        B.kvc_query_block_metric(self.cfg, self.st, q_blk, w, first_pos, exclude, layer_begin, layer_end, self.ws)
+        B.kvc_query_block_metric(self.cfg, self.st, q_blk, row_lse, w, first_pos, exclude, layer_begin, layer_end,
+                                 self.ws)
         return self.cache.metric

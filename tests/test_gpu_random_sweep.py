@@ -65,17 +65,19 @@ def test_window_metric_on_random_shapes(seed0):
     for case in range(30):
         r = int(rng.choice([1, 2, 4, 8]))
         w = int(rng.integers(1, min(32, 256 // r) + 1))
-        b = int(rng.choice([16, 32, 64]))
+        b = int(rng.choice([16, 32, 64, 4, 8, 1]))
+        d = int(rng.choice([128, 128, 64]))
+        dt = str(rng.choice(["bf16", "bf16", "fp8"]))
         pool = int(rng.choice([1, 3, 5, 7, 9, 131]))
         S, Lyr, Hk = int(rng.integers(1, 4)), int(rng.integers(1, 3)), int(rng.integers(1, 3))
         L = int(rng.integers(64, 4200))
         rho = float(rng.uniform(1.0, 3.0))
         mode = int(rng.choice([B.KVC_L2, B.KVC_L1]))
         acc = bool(rng.random() < 0.3)
-        say("random window", dict(seed0=seed0, case=case, r=r, w=w, b=b, pool=pool, S=S, Lyr=Lyr, Hk=Hk, L=L,
+        say("random window", dict(seed0=seed0, case=case, r=r, w=w, b=b, d=d, dt=dt, pool=pool, S=S, Lyr=Lyr, Hk=Hk, L=L,
                                   rho=round(rho, 2), mode=mode, acc=acc))
-        shape, ctx, seed = W.small_mixed(5000 + seed0 * 1000 + case, S=S, Lyr=Lyr, Hk=Hk, r=r, d=128, b=b, L=L,
-                                         rho=rho, kv_dtype="bf16")
+        shape, ctx, seed = W.small_mixed(5000 + seed0 * 1000 + case, S=S, Lyr=Lyr, Hk=Hk, r=r, d=d, b=b, L=L,
+                                         rho=rho, kv_dtype=dt)
         if rng.random() < 0.3:
             ctx[int(rng.integers(0, len(ctx)))] = 0
         if rng.random() < 0.3:
@@ -84,7 +86,7 @@ def test_window_metric_on_random_shapes(seed0):
                              init_metric="prefill")
         st = oracle_state(cache)
         g = torch.Generator().manual_seed(seed + 3)
-        qw = torch.randn((S, Lyr, Hk * r, w, 128), generator=g).to(torch.bfloat16)
+        qw = torch.randn((S, Lyr, Hk * r, w, d), generator=g).to(torch.bfloat16)
         O.window_metric(st, qw.double().numpy(), w, pool, "L2" if mode == B.KVC_L2 else "L1", accumulate=acc)
         sess = session(cache, mode)
         sess.window_metric(qw.to(sess.device), w, pool, accumulate=acc)
@@ -109,16 +111,18 @@ def test_query_block_metric_on_random_shapes(seed0):
         w = int(rng.integers(1, min(64, 256 // r) + 1))
         if case % 4 == 3:
             w = int(rng.integers(65, 300))       # a long block: several passes of the kernels
-        b = int(rng.choice([16, 32, 64]))
+        b = int(rng.choice([16, 32, 64, 8, 2]))
+        d = int(rng.choice([128, 128, 64]))
+        dt = str(rng.choice(["bf16", "bf16", "fp8"]))
         S, Lyr, Hk = int(rng.integers(1, 3)), int(rng.integers(1, 3)), int(rng.integers(1, 4))
         L = int(rng.choice([int(rng.integers(64, 3000)), 2048, 8192]))
         rho = float(rng.choice([1.0, rng.uniform(1.0, 3.0)]))
         mode = int(rng.choice([B.KVC_L2, B.KVC_L1]))
         excl = int(rng.choice([0, 1, 10, w + 5]))
-        say("random query blocks", dict(seed0=seed0, case=case, r=r, w=w, b=b, S=S, Lyr=Lyr, Hk=Hk, L=L,
+        say("random query blocks", dict(seed0=seed0, case=case, r=r, w=w, b=b, d=d, dt=dt, S=S, Lyr=Lyr, Hk=Hk, L=L,
                                         rho=round(rho, 2), mode=mode, excl=excl))
-        shape, ctx, seed = W.small_mixed(7000 + seed0 * 1000 + case, S=S, Lyr=Lyr, Hk=Hk, r=r, d=128, b=b, L=L,
-                                         rho=rho, kv_dtype="bf16")
+        shape, ctx, seed = W.small_mixed(7000 + seed0 * 1000 + case, S=S, Lyr=Lyr, Hk=Hk, r=r, d=d, b=b, L=L,
+                                         rho=rho, kv_dtype=dt)
         if rng.random() < 0.3:
             ctx[int(rng.integers(0, len(ctx)))] = 0
         cache = W.make_cache(shape, ctx, seed, placement=str(rng.choice(["fresh", "fragmented"])),
@@ -128,7 +132,7 @@ def test_query_block_metric_on_random_shapes(seed0):
         g = torch.Generator().manual_seed(seed + 5)
         starts = [0, int(rng.integers(0, L)), max(0, L - w), int(rng.integers(0, L))]
         for start in starts[: 2 if L > 4096 else 4]:
-            qb = torch.randn((S, Lyr, Hk * r, w, 128), generator=g).to(torch.bfloat16)
+            qb = torch.randn((S, Lyr, Hk * r, w, d), generator=g).to(torch.bfloat16)
             O.query_block_metric(st, qb.double().numpy(), w, start, excl, "L2" if mode == B.KVC_L2 else "L1")
             sess.query_block_metric(qb.to(sess.device), w, start, excl)
         torch.cuda.synchronize()

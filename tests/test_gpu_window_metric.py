@@ -21,6 +21,18 @@ CASES = [
     # a pool wider than the halo the pooling kernel stages; heads longer than one pooling tile
     ("w8_r4_wide_pool", dict(r=4, L=2600, rho=1.5), 8, 201, B.KVC_L2),
     ("w4_r2_pool_129", dict(r=2, L=4500, rho=1.2), 4, 129, B.KVC_L2),
+    # the shapes the decode covers as well: 8-bit rows, d = 64, blocks shorter than a row of lanes
+    ("fp8_w32_r4", dict(r=4, L=1500, rho=1.5, kv_dtype="fp8"), 32, 7, B.KVC_L2),
+    ("fp8_w32_r8_b32", dict(r=8, L=1300, rho=2.0, kv_dtype="fp8", b=32), 32, 7, B.KVC_L2),
+    ("fp8_d64_w16_r2_L1", dict(r=2, L=1300, rho=2.0, kv_dtype="fp8", d=64), 16, 3, B.KVC_L1),
+    ("d64_w32_r4", dict(r=4, L=1500, rho=1.5, d=64), 32, 7, B.KVC_L2),
+    ("d64_w8_r1", dict(r=1, L=2600, rho=1.5, d=64), 8, 7, B.KVC_L2),
+    ("d64_w32_r8_b64", dict(r=8, L=1300, rho=2.0, d=64, b=64), 32, 5, B.KVC_L2),
+    ("b4_w32_r4", dict(r=4, L=1500, rho=1.5, b=4), 32, 7, B.KVC_L2),
+    ("b8_w8_r8", dict(r=8, L=1300, rho=2.0, b=8), 8, 7, B.KVC_L2),
+    ("b1_w16_r2", dict(r=2, L=1200, rho=2.0, b=1), 16, 7, B.KVC_L2),
+    ("b2_fp8_d64_w8_r4", dict(r=4, L=1200, rho=2.0, b=2, kv_dtype="fp8", d=64), 8, 3, B.KVC_L2),
+    ("b128_w8_r4", dict(r=4, L=2600, rho=1.5, b=128), 8, 7, B.KVC_L2),
 ]
 
 
@@ -28,13 +40,46 @@ def window_queries(shape, w, seed, device):
     g = torch.Generator(device=device).manual_seed(seed)
     q = torch.randn((shape.num_seqs, shape.num_layers, shape.num_q_heads, w, shape.head_dim),
                     generator=g, device=device, dtype=torch.float32)
-    return q.to(shape.torch_dtype)
+    return q.to(shape.q_torch_dtype)
+
+
+def poison_unowned_keys(cache, real):
+    if cache.k_cache.dtype == torch.float8_e4m3fn:
+        cache.k_cache.view(torch.uint8)[~real] = 0x7F      # the 8-bit NaN
+    else:
+        cache.k_cache[~real] = float("nan")
+
+
+def row_lse(st, q, w, first_pos=None):
+    """ln of every query row's softmax denominator over the keys it attends to, with a library
+    logsumexp on the host (what a prefill's attention kernel would hand over).  q [S, Lyr, Hq, w, d];
+    query i sits at C - w + i (first_pos None) or at first_pos + i, seeing keys up to
+    min(position, C - 1).  Rows that see no key get 0 (never used)."""
+    S, Lyr, Hk, r, d = st.S, st.Lyr, st.Hk, st.r, st.d
+    q = np.asarray(q, dtype=np.float64).reshape(S, Lyr, Hk * r, w, d)
+    out = np.zeros((S, Lyr, Hk * r, w), dtype=np.float32)
+    for g in range(st.G):
+        s, l, h = g // (Lyr * Hk), (g // Hk) % Lyr, g % Hk
+        C = int(st.lens()[g])
+        if C == 0:
+            continue
+        n, o = O.slots_of(st, g)
+        K = torch.from_numpy(st.k_cache[n, o])
+        for hq in range(r * h, r * (h + 1)):
+            sc = (K @ torch.from_numpy(q[s, l, hq]).T) / np.sqrt(float(d))         # [C, w]
+            for i in range(w):
+                last = (C - w + i) if first_pos is None else min(first_pos + i, C - 1)
+                if last >= 0:
+                    out[s, l, hq, i] = float(torch.logsumexp(sc[:last + 1, i], dim=0))
+    return out
 
 
 @pytest.mark.parametrize("name,kw,w,pool,mode", CASES, ids=[c[0] for c in CASES])
 def test_window_metric_matches_oracle(name, kw, w, pool, mode):
     say("window metric", name)
-    shape, ctx, seed = W.small_mixed(101, S=2, Lyr=2, Hk=2, d=128, kv_dtype="bf16", **kw)
+    base = dict(d=128, kv_dtype="bf16")
+    base.update(kw)
+    shape, ctx, seed = W.small_mixed(101, S=2, Lyr=2, Hk=2, **base)
     ctx[1] = 0            # no KV at all
     ctx[2] = 3            # shorter than the window
     ctx[3] = w            # exactly the window
@@ -45,7 +90,7 @@ def test_window_metric_matches_oracle(name, kw, w, pool, mode):
     for g in range(st0.G):
         n, o = O.slots_of(st0, g)
         real[torch.from_numpy(n), torch.from_numpy(o)] = True
-    cache.k_cache[~real] = float("nan")          # slots that hold no KV must never leak in
+    poison_unowned_keys(cache, real)             # slots that hold no KV must never leak in
     st = oracle_state(cache)
     qw = window_queries(shape, w, seed, "cpu")
     O.window_metric(st, qw.double().numpy(), w, pool, "L2" if mode == B.KVC_L2 else "L1")
@@ -60,6 +105,25 @@ def test_window_metric_matches_oracle(name, kw, w, pool, mode):
     # relative check too: the sums span orders of magnitude
     big = rm & (st.metric > 1e-3)
     np.testing.assert_allclose(m[big], st.metric[big], rtol=2e-2, atol=0)
+    # the same metric in one pass, from the log-sum-exp of every query row: first the true one (the
+    # result above again), then one that is off by a different amount per row (used as given)
+    st1 = oracle_state(cache)
+    lse = row_lse(st1, qw.double().numpy(), w)
+    rng = np.random.default_rng(5)
+    for shift in (0.0, 0.4):
+        lse_s = (lse + shift * rng.random(lse.shape)).astype(np.float32)
+        st2 = oracle_state(cache)
+        O.window_metric(st2, qw.double().numpy(), w, pool, "L2" if mode == B.KVC_L2 else "L1", row_lse=lse_s)
+        sess2 = session(cache, mode)
+        sess2.window_metric(qw.to(sess2.device), w, pool, row_lse=torch.from_numpy(lse_s).to(sess2.device))
+        torch.cuda.synchronize()
+        m2 = sess2.cache.metric.cpu().numpy().astype(np.float64)
+        np.testing.assert_allclose(m2[rm], st2.metric[rm], rtol=0, atol=TOL)
+        np.testing.assert_array_equal(m2[~rm], cache.metric.numpy().astype(np.float64)[~rm])
+        big2 = rm & (st2.metric > 1e-3)
+        np.testing.assert_allclose(m2[big2], st2.metric[big2], rtol=2e-2, atol=0)
+        if shift == 0.0:
+            np.testing.assert_allclose(st2.metric[rm], st.metric[rm], rtol=0, atol=1e-5)
 
 
 def test_window_metric_layer_range_accumulate_and_unsupported():
@@ -130,3 +194,17 @@ def test_query_block_metric_builds_kvc_full():
     np.testing.assert_allclose(m[used], st.metric[used], rtol=0, atol=TOL)
     big = used[:, None] & (st.metric > 1e-3)
     np.testing.assert_allclose(m[big], st.metric[big], rtol=2e-2, atol=0)
+    # the same blocks with the queries' log-sum-exp handed over (one pass over the keys)
+    st2 = oracle_state(cache)
+    sess2 = session(cache)
+    for start in (0, 5 * blk, L - (L % blk or blk)):
+        w = min(blk, L - start)
+        qb = Q[:, :, :, start:start + w].contiguous()
+        lse = row_lse(st2, qb.double().numpy(), w, first_pos=start)
+        O.query_block_metric(st2, qb.double().numpy(), w, start, v, row_lse=lse)
+        sess2.query_block_metric(qb.to(sess2.device), w, start, v, row_lse=torch.from_numpy(lse).to(sess2.device))
+    torch.cuda.synchronize()
+    m2 = sess2.cache.metric.cpu().numpy().astype(np.float64)
+    np.testing.assert_allclose(m2[used], st2.metric[used], rtol=0, atol=TOL)
+    big = used[:, None] & (st2.metric > 1e-3)
+    np.testing.assert_allclose(m2[big], st2.metric[big], rtol=2e-2, atol=0)
