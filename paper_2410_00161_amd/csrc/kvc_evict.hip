@@ -271,9 +271,9 @@ __global__ void __launch_bounds__(256) compact_scan_kernel(Dims D, const uint8_t
   if (__any(bad) && lane == 0) atomicOr(&header[HW_SCRATCH0], EB_ARG);
 }
 
-// One workgroup per head instance.  A 16-lane group moves one KV: its key row,
-// value row, metric and logical index.  Sources lie in [T, C), destinations in
-// [0, T), so moves of one head never overlap; heads own disjoint blocks.
+// One workgroup per head instance.  A 16-lane group moves one KV: its key row, value row, metric
+// and logical index.  Sources lie in [T, C), destinations in [0, T), so moves of one head never
+// overlap; heads own disjoint blocks.
 // STAGED: the head's prefix counts of flags and its block ids are copied into LDS first (one
 // round of loads), so that a mover's walk - its block's flag, the flags before it, a binary
 // search for its hole - no longer is a chain of a dozen dependent global loads.
@@ -346,6 +346,147 @@ __global__ void __launch_bounds__(256) compact_move_kernel(Dims D, char* __restr
     row[u] = -1;
   }
   if (threadIdx.x == 0) ctx[g] = T;   // nb - nb2 = e blocks went back
+}
+
+// Tables sized for long prompts: workgroup (g, y) moves the kept KVs of logical slots
+// T + y * kSlice .. + kSlice - 1 of head g, and the tables are left to compact_free_kernel.
+// (One workgroup per head with the head's whole table in LDS: a 131072-token head that loses a
+// tenth of its blocks is 12 MB of moves behind one workgroup, two such workgroups fit a CU, and
+// a round of a million blocks took 7.4 ms.)  The movers of a slice are consecutive in rank, so
+// their holes are consecutive flagged blocks: the workgroup finds the first of them with a
+// 256-way search over the prefix counts, walks on from there gathering block ids, and keeps only
+// its own stretch of the table in LDS (a few KB).
+constexpr int kSlice = 2048;
+__global__ void __launch_bounds__(256) compact_move_sliced_kernel(Dims D, char* __restrict__ kc, char* __restrict__ vc,
+                                                                  float* __restrict__ metric, int32_t* __restrict__ pos,
+                                                                  const int32_t* __restrict__ table,
+                                                                  const int32_t* __restrict__ ctx,
+                                                                  const int32_t* __restrict__ evict_count,
+                                                                  const int32_t* __restrict__ flag_scan,
+                                                                  const int32_t* __restrict__ header) {
+  if (header[HW_STATUS] != KVC_OK) return;
+  const int g = blockIdx.x;
+  const int e = evict_count[g];
+  if (e <= 0) return;
+  const int b = D.b;
+  if ((long long)blockIdx.y * kSlice >= (long long)e * b) return;   // the range of movers is at most e * b slots long
+  int lb = 0;
+  while ((1 << lb) < b) ++lb;   // block sizes are powers of two
+  const int C = ctx[g];
+  const int nb = (C + b - 1) >> lb;
+  const int32_t* row = table + (size_t)g * D.maxb;
+  const int32_t* pi = flag_scan + (size_t)g * D.maxb;  // inclusive prefix of flags
+  const int last_flag = pi[nb - 1] - (nb > 1 ? pi[nb - 2] : 0);
+  const int n_ev = e * b - (last_flag ? nb * b - C : 0);
+  const int T = C - n_ev;
+  const int j_lo = T + (int)blockIdx.y * kSlice;
+  if (j_lo >= C) return;
+  const int j_hi = min(C, j_lo + kSlice);
+  const int tid = threadIdx.x;
+  constexpr int kMaxBlk = kSlice + 2;                 // blocks of a slice at b = 1, and one before
+  __shared__ int s_pi[kMaxBlk], s_id[kMaxBlk], s_hole[kMaxBlk];
+  __shared__ int s_first;
+  // this slice's stretch of the table: blocks ub0 .. ub1 and the prefix count before ub0
+  const int ub0 = j_lo >> lb, ub1 = (j_hi - 1) >> lb;
+  for (int i = tid; i <= ub1 - ub0 + 1; i += 256) {
+    const int u = ub0 - 1 + i;                        // s_pi[i] = pi[ub0 - 1 + i], 0 before the row
+    s_pi[i] = u >= 0 ? pi[u] : 0;
+    if (i > 0) s_id[i] = row[u];
+  }
+  __syncthreads();
+  // kept slots above j (= rank of mover j when j itself is kept), for any slot j of the slice
+  auto kept_above = [&](int j) {
+    const int uj = j >> lb;
+    const int before = s_pi[uj - ub0], here = s_pi[uj - ub0 + 1];
+    const int ev_upto = (before << lb) + (here != before ? (j & (b - 1)) + 1 : 0);   // evicted slots in [0, j]
+    return (C - 1 - j) - (n_ev - ev_upto);
+  };
+  const int r_lo = kept_above(j_hi - 1) >> lb, r_hi = kept_above(j_lo) >> lb;   // flagged blocks (by rank) that hold the holes
+  // first block u with pi[u] >= r_lo + 1: a 256-way search, twice
+  {
+    const int want = r_lo + 1;
+    int lo = 0, hi = nb - 1;      // the answer lies in [lo, hi]: pi[nb - 1] = e > r_hi >= r_lo
+    while (hi - lo >= 256) {
+      const int step = (hi - lo + 256) / 256;
+      if (tid == 0) s_first = 256;
+      __syncthreads();
+      const int u = min(hi, lo + tid * step);
+      if (pi[u] >= want) atomicMin(&s_first, tid);
+      __syncthreads();
+      const int t = s_first;      // < 256: the probe at hi always succeeds
+      const int nhi = min(hi, lo + t * step), nlo = t == 0 ? lo : min(hi, lo + (t - 1) * step) + 1;
+      __syncthreads();
+      lo = nlo; hi = nhi;
+    }
+    if (tid == 0) s_first = hi;
+    __syncthreads();
+    if (lo + tid <= hi && pi[lo + tid] >= want) atomicMin(&s_first, lo + tid);
+    __syncthreads();
+  }
+  // walk on from there: the flagged blocks of ranks r_lo .. r_hi, their ids into s_hole
+  for (int base = s_first; base < nb; base += 256) {
+    const int u = base + tid;
+    int here = 0, before = 0;
+    if (u < nb) { here = pi[u]; before = u ? pi[u - 1] : 0; }
+    if (u < nb && here != before && here - 1 >= r_lo && here - 1 <= r_hi) s_hole[here - 1 - r_lo] = row[u];
+    const int last = pi[min(nb - 1, base + 255)];
+    if (last > r_hi) break;       // the same for every thread
+  }
+  __syncthreads();
+  const size_t row_bytes = (size_t)D.d * kv_esz(D.dtype);
+  const int pieces = (int)(row_bytes / 16);
+  const int grp = tid >> 4, gl = tid & 15;
+  auto route = [&](int j, size_t& src, size_t& dst) {
+    if (j >= j_hi) return false;
+    const int uj = j >> lb;
+    if (s_pi[uj - ub0 + 1] != s_pi[uj - ub0]) return false;   // its block is flagged: evicted, nothing to keep
+    const int k = kept_above(j);                               // rank among the movers, from the top
+    src = ((size_t)s_id[uj - ub0 + 1] << lb) + (j & (b - 1));
+    dst = ((size_t)s_hole[(k >> lb) - r_lo] << lb) + (k & (b - 1));   // k-th hole: offset k % b of the (k / b)-th flagged block
+    return true;
+  };
+  for (int j = j_lo + grp; j < j_hi; j += 16) {
+    size_t src = 0, dst = 0;
+    if (!route(j, src, dst)) continue;
+    for (int c = gl; c < pieces; c += 16) {
+      ((uint4*)(kc + dst * row_bytes))[c] = ((const uint4*)(kc + src * row_bytes))[c];
+      ((uint4*)(vc + dst * row_bytes))[c] = ((const uint4*)(vc + src * row_bytes))[c];
+    }
+    if (gl == 0) {
+      metric[dst] = metric[src];
+      if (pos) pos[dst] = pos[src];
+    }
+  }
+}
+
+// The free step after a sliced move: one wavefront per head instance gives the tail blocks back
+// and shortens the head.
+__global__ void __launch_bounds__(256) compact_free_kernel(Dims D, int32_t* __restrict__ table,
+                                                           int32_t* __restrict__ ctx,
+                                                           uint8_t* __restrict__ free_map,
+                                                           const int32_t* __restrict__ evict_count,
+                                                           const int32_t* __restrict__ flag_scan,
+                                                           const int32_t* __restrict__ header) {
+  if (header[HW_STATUS] != KVC_OK) return;
+  const int g = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (g >= D.G) return;
+  const int lane = threadIdx.x & 63;
+  const int e = evict_count[g];
+  if (e <= 0) return;
+  const int b = D.b;
+  const int C = ctx[g];
+  const int nb = (C + b - 1) / b;
+  const int32_t* pi = flag_scan + (size_t)g * D.maxb;
+  const int last_flag = pi[nb - 1] - (nb > 1 ? pi[nb - 2] : 0);
+  const int n_ev = e * b - (last_flag ? nb * b - C : 0);
+  const int T = C - n_ev;
+  int32_t* row = table + (size_t)g * D.maxb;
+  const int nb2 = (T + b - 1) / b;
+  for (int u = nb2 + lane; u < nb; u += 64) {
+    free_map[row[u]] = 1;
+    row[u] = -1;
+  }
+  if (lane == 0) ctx[g] = T;
 }
 
 }  // namespace kvc
@@ -432,14 +573,28 @@ int kvc_compact(const kvc_config* cfg, const kvc_state* st, const uint8_t* evict
   hipLaunchKernelGGL(resolve_kernel, dim3(1), dim3(64), 0, s, W.header, 0);
   KVC_LAUNCH_CHECK();
   const size_t stage_bytes = (size_t)D.maxb * 8;   // prefix counts and block ids of one head
-  if (stage_bytes <= 64 * 1024)
-    hipLaunchKernelGGL(compact_move_kernel<true>, dim3(D.G), dim3(256), stage_bytes, s, D, (char*)st->k_cache,
-                       (char*)st->v_cache, st->metric, st->pos, st->block_table, st->ctx_len, st->free_map,
-                       evict_count, W.flag_scan, W.header);
-  else
-    hipLaunchKernelGGL(compact_move_kernel<false>, dim3(D.G), dim3(256), 0, s, D, (char*)st->k_cache,
-                       (char*)st->v_cache, st->metric, st->pos, st->block_table, st->ctx_len, st->free_map,
-                       evict_count, W.flag_scan, W.header);
+  char* kcp = (char*)st->k_cache;
+  char* vcp = (char*)st->v_cache;
+  // Tables sized for long prompts (more than 65536 tokens a head, where a head's table no longer
+  // fits the LDS several times over): a head's movers are spread over workgroups of kSlice logical
+  // slots each, and the tables change in a launch of their own.  (Below that the empty workgroups
+  // of the slice grid cost more than the slices gain: 65536 heads with tables for 32768 tokens,
+  // 0.70 ms per head-sized workgroup against 1.36 ms sliced.)
+  const size_t row_tokens = (size_t)D.maxb * D.b;
+  const size_t slices = (row_tokens + kSlice - 1) / kSlice;
+  if (row_tokens > 65536 && slices <= 65535) {
+    hipLaunchKernelGGL(compact_move_sliced_kernel, dim3(D.G, (unsigned)slices), dim3(256), 0, s, D, kcp, vcp, st->metric,
+                       st->pos, st->block_table, st->ctx_len, evict_count, W.flag_scan, W.header);
+    KVC_LAUNCH_CHECK();
+    hipLaunchKernelGGL(compact_free_kernel, dim3((D.G + 3) / 4), dim3(256), 0, s, D, st->block_table, st->ctx_len,
+                       st->free_map, evict_count, W.flag_scan, W.header);
+  } else if (stage_bytes <= 64 * 1024) {
+    hipLaunchKernelGGL(compact_move_kernel<true>, dim3(D.G), dim3(256), stage_bytes, s, D, kcp, vcp, st->metric,
+                       st->pos, st->block_table, st->ctx_len, st->free_map, evict_count, W.flag_scan, W.header);
+  } else {
+    hipLaunchKernelGGL(compact_move_kernel<false>, dim3(D.G), dim3(256), 0, s, D, kcp, vcp, st->metric, st->pos,
+                       st->block_table, st->ctx_len, st->free_map, evict_count, W.flag_scan, W.header);
+  }
   KVC_LAUNCH_CHECK();
   if (blocks_freed) {
     hipLaunchKernelGGL(publish_freed_kernel, dim3(1), dim3(1024), 0, s, W.header, evict_count, D.G, blocks_freed);

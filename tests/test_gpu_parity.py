@@ -473,6 +473,39 @@ def test_select_and_compact_bit_exact(name, kw):
     np.testing.assert_allclose(out.cpu().numpy(), want, rtol=0, atol=TOL)
 
 
+@pytest.mark.parametrize("kv_dtype,b", [("bf16", 16), ("fp8", 64), ("f32", 4)])
+def test_compaction_of_long_heads_in_slices(kv_dtype, b):
+    """Tables sized for more than 65536 tokens a head: the compaction spreads a head's movers over
+    several workgroups and frees the tail blocks in a launch of its own.  Heads of up to 20000 KVs
+    (movers in several slices), one that loses nearly everything, one that loses nothing, one empty."""
+    import dataclasses
+    say("sliced compaction", kv_dtype, b)
+    shape, ctx, seed = W.small_mixed(77, S=2, Lyr=1, Hk=3, r=1, d=64, L=20000, rho=1.3, b=b, kv_dtype=kv_dtype)
+    shape = dataclasses.replace(shape, max_blocks_per_head=70000 // b)
+    assert shape.max_blocks_per_head * b > 65536
+    ctx[4] = 0
+    cache = W.make_cache(shape, ctx, seed, placement="fragmented", init_metric="prefill")
+    g = torch.Generator().manual_seed(9)
+    cache.metric = torch.rand(cache.metric.shape, generator=g)
+    t = cache.block_table.reshape(shape.G, -1)
+    cache.metric[t[1][t[1] >= 0].long()] += 10.0      # head 1 keeps everything
+    cache.metric[t[2][t[2] >= 0].long()] *= 1e-3      # head 2 is the cheapest by far
+    st = oracle_state(cache)
+    sess = session(cache)
+    key = sess.metric_reduce()
+    want_key, _ = O.block_keys(st, cache.metric.numpy())
+    nb = -(-st.lens() // st.b)
+    budget = torch.tensor([int(0.45 * x) for x in nb.reshape(st.S, -1).sum(1)], dtype=torch.int32)
+    flag_w, count_w, sel_w = O.evict_select(st, want_key, budget.numpy())
+    flag, count, sel = sess.evict_select(budget)
+    np.testing.assert_array_equal(flag.cpu().numpy(), flag_w)
+    assert count_w[1] == 0 and count_w[2] == nb[2] - 1
+    freed_w = O.compact(st, flag_w, count_w)
+    assert int(sess.compact().item()) == freed_w
+    assert_state_equal(sess, st)
+    check_allocator_invariants(st)
+
+
 def test_select_numeric_error_and_compact_argument_error():
     say("select/compact errors")
     shape, ctx, seed = W.small_mixed(73, S=2, Lyr=2, Hk=2, r=2, d=64, L=300)
