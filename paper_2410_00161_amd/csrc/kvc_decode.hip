@@ -769,8 +769,8 @@ __global__ void __launch_bounds__(256) decode_combine_kernel(DecodeArgs A) {
   }
 }
 
-// Fallback for shapes the tiled kernel does not cover (any b, any d that is a
-// multiple of 16 bytes, any r <= 16): one workgroup per head instance, logits
+// Fallback for shapes the tiled kernel does not cover (blocks of more than 64 tokens, any d that
+// is a multiple of 16 bytes, any r <= 16): one workgroup per head instance, logits
 // kept in the workspace.  Correct, not fast.
 __global__ void __launch_bounds__(256) decode_generic_kernel(DecodeArgs A) {
   const int gi = blockIdx.x;
@@ -912,8 +912,10 @@ static bool choose_chunk(const Dims& D, int gsel, int* T_out, size_t* lds_out, b
   const int esz = kv_esz(D.dtype);
   const int lpt = D.d * esz / 16;
   const int tpi = (lpt >= 1 && lpt <= 64) ? 64 / lpt : 0;
+  // (blocks shorter than the tokens one wavefront load covers are fine: off the 16-token-block
+  // fast path every token of a load looks its own block up)
   bool tiled = (D.r == 1 || D.r == 2 || D.r == 4 || D.r == 8) && (D.d == 64 || D.d == 128) &&
-               tpi >= 1 && D.b % tpi == 0 && 64 % D.b == 0;
+               tpi >= 1 && 64 % D.b == 0;
   if (!tiled) return false;
   // default: a chunk that lets two workgroups share a CU (at r = 8, d = 128, 16-bit rows: 3456
   // tokens x 16 bytes of exps + the rest = 81 764 of the 81 920 bytes a half CU has)
@@ -934,6 +936,12 @@ static bool choose_chunk(const Dims& D, int gsel, int* T_out, size_t* lds_out, b
     if (shrunk && gsel <= kSmallWorklistHeads) { T = T_default; device_side = true; }
   }
   const bool mf = decode_pv_mfma(esz, D.r, D.d, D.b);   // a per-wavefront operand tile in LDS
+  // the default is sized so that two workgroups share a CU's LDS with blocks of 16 tokens; blocks
+  // of one or two tokens put a block id per token or two next to the exps: a shorter chunk keeps
+  // the second workgroup on the CU
+  if (!g_chunk_tokens.load(std::memory_order_relaxed) && D.b < 4 &&
+      decode_lds_bytes(T, D.r, D.d, 16, kDecodeWaves, mf) <= kLdsLimit / 2)
+    while (T > 1024 && decode_lds_bytes(T, D.r, D.d, D.b, kDecodeWaves, mf) > kLdsLimit / 2) T -= 64;
   while (T > kMinChunk && decode_lds_bytes(T, D.r, D.d, D.b, kDecodeWaves, mf) > kLdsLimit) T -= 64;
   const size_t lds = decode_lds_bytes(T, D.r, D.d, D.b, kDecodeWaves, mf);
   if (lds > kLdsLimit || T % 64 != 0) return false;

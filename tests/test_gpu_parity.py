@@ -66,7 +66,12 @@ DECODE_CASES = [
     ("f32_d128_r4_split", dict(r=4, d=128, kv_dtype="f32", L=400), 64, B.KVC_L2),
     ("bf16_b32", dict(r=4, d=128, kv_dtype="bf16", L=400, b=32), 128, B.KVC_L2),
     ("bf16_b4", dict(r=4, d=128, kv_dtype="bf16", L=200, b=4), 64, B.KVC_L2),
-    ("generic_b2", dict(r=4, d=128, kv_dtype="bf16", L=120, b=2), 0, B.KVC_L2),
+    ("bf16_b2", dict(r=4, d=128, kv_dtype="bf16", L=120, b=2), 0, B.KVC_L2),
+    ("bf16_b1_split", dict(r=4, d=128, kv_dtype="bf16", L=700, b=1), 128, B.KVC_L2),
+    ("bf16_b2_r8_split", dict(r=8, d=128, kv_dtype="bf16", L=500, b=2), 64, B.KVC_L1),
+    ("f32_b1_d64", dict(r=2, d=64, kv_dtype="f32", L=300, b=1), 0, B.KVC_L2),
+    ("fp8_b1_r8", dict(r=8, d=128, kv_dtype="fp8", L=400, b=1), 64, B.KVC_L2),
+    ("generic_b128", dict(r=4, d=128, kv_dtype="bf16", L=600, b=128), 0, B.KVC_L2),
     ("generic_r3", dict(r=3, d=64, kv_dtype="f32", L=200), 0, B.KVC_L1),
     ("generic_d32", dict(r=2, d=32, kv_dtype="bf16", L=200), 0, B.KVC_L2),
     ("fp8_d128_r4", dict(r=4, d=128, kv_dtype="fp8", L=700), 0, B.KVC_L2),
@@ -75,7 +80,8 @@ DECODE_CASES = [
     ("fp8_d128_r1_L1", dict(r=1, d=128, kv_dtype="fp8", L=300), 0, B.KVC_L1),
     ("fp8_d64_r2", dict(r=2, d=64, kv_dtype="fp8", L=400), 64, B.KVC_L2),
     ("fp8_b8", dict(r=4, d=128, kv_dtype="fp8", L=200, b=8), 64, B.KVC_L2),
-    ("fp8_generic_b2", dict(r=4, d=128, kv_dtype="fp8", L=120, b=2), 0, B.KVC_L2),
+    ("fp8_b2", dict(r=4, d=128, kv_dtype="fp8", L=120, b=2), 0, B.KVC_L2),
+    ("fp8_generic_b128", dict(r=4, d=128, kv_dtype="fp8", L=600, b=128), 0, B.KVC_L2),
 ]
 
 
@@ -128,7 +134,7 @@ def _shape_matrix():
     """Every query-group size x row type x head dimension, each with a block size and a chunk
     setting taken in rotation (0 = the library's own choice for a call over few heads)."""
     cases, i = [], 0
-    blocks = (16, 64, 8, 32, 4)
+    blocks = (16, 64, 8, 32, 4, 2, 1)
     chunks = (0, 64, 0, 192, 0, 1088)
     for r in (1, 2, 4, 8):
         for dt in ("bf16", "f32", "fp8"):
