@@ -242,3 +242,128 @@ def test_llama70b_shape_long_heads_sampled(forced_chunk):
     assert bool((per_head[:G] <= r + 1e-3).all()) and bool((per_head[:G] >= r / ctx_now - 1e-3).all())
     assert float(per_head[G]) == 0.0
     assert bool(torch.isfinite(out).all())
+
+
+def test_llama70b_full_batch_sampled_with_both_kinds_of_round():
+    """The whole 70B-shaped batch the benchmark runs (16 sequences x 131072 prompt tokens, mean 8x:
+    10240 head instances, 86 GB of keys and values): append + decode checked on sampled head
+    instances and by per-head properties over the whole cache; then a rank-block round and a block
+    round of a tenth of every sequence's blocks, each with its selection recomputed by the oracle
+    for the head instances of one layer of one sequence (given the device's metrics / keys) and
+    the compacted heads compared slot by slot; allocator invariants on the device after each."""
+    from paper_2410_00161_amd.session import KvcSession
+    print("[case] llama70b shape, full batch of 16 x 131072", flush=True)
+    shape, ctx, seed = W.llama70b_decode(extra_tokens=48)
+    dev = torch.device("cuda:0")
+    free_b, _ = torch.cuda.mem_get_info()
+    if free_b < 150 * (1 << 30):
+        pytest.skip("needs 150 GB of free device memory")
+    cache = W.make_cache(shape, ctx, seed, device=dev, placement="fragmented", init_metric="prefill")
+    sess = KvcSession(cache, device=dev)
+    del cache
+    G, r, d, b = shape.G, shape.group_size, shape.head_dim, shape.block_size
+    chunk = B.kvc_get_decode_chunk(sess.cfg)
+    k, v = W.make_new_kv(shape, seed, 0, dev)
+    q = W.make_query(shape, seed, 0, dev)
+    sess.append(k, v)
+    heads = pick_heads(sess.cache.ctx_len, chunk, 8, seed)
+    small, q_small = W.gather_heads(sess.cache, heads, q)
+    st = oracle_state(small)
+    m_before = sess.cache.metric.clone()
+    out = sess.paged_decode(q)
+    torch.cuda.synchronize()
+    want = O.paged_decode(st, q_small.double().numpy())
+    got = out.reshape(G, r, d)[torch.tensor(heads, device=dev)].cpu().numpy()
+    np.testing.assert_allclose(got, want.reshape(len(heads), r, d), rtol=0, atol=TOL)
+    after, _ = W.gather_heads(sess.cache, heads)
+    for i in range(len(heads)):
+        n, o = O.slots_of(st, i)
+        np.testing.assert_allclose(after.metric.numpy()[n, o], st.metric[n, o], rtol=0, atol=TOL)
+    del st, small, after
+    delta = sess.cache.metric - m_before
+    del m_before
+    assert float(delta.min()) >= 0.0
+    table = sess.cache.block_table.reshape(G, -1).long()
+    owner = torch.full((shape.num_blocks,), G, dtype=torch.long, device=dev)
+    valid = table >= 0
+    owner[table[valid]] = torch.arange(G, device=dev).unsqueeze(1).expand_as(table)[valid]
+    per_head = torch.zeros(G + 1, dtype=torch.float64, device=dev)
+    per_head.index_add_(0, owner, delta.double().sum(1))
+    del delta, owner, valid, table
+    ctx_now = sess.cache.ctx_len.reshape(G).double()
+    assert bool((per_head[:G] <= r + 1e-3).all()) and bool((per_head[:G] >= r / ctx_now - 1e-3).all())
+    assert float(per_head[G]) == 0.0 and bool(torch.isfinite(out).all())
+
+    per = shape.num_layers * shape.num_kv_heads
+    s, layer = 7, 33
+    heads = list(range(s * per + layer * shape.num_kv_heads, s * per + (layer + 1) * shape.num_kv_heads))
+
+    def budgets():
+        nb = (sess.cache.ctx_len.reshape(shape.num_seqs, -1).long() + b - 1) // b
+        return (nb.sum(1) // 10).to(torch.int32)
+
+    def held_blocks():
+        return int(((sess.cache.ctx_len.reshape(-1).long() + b - 1) // b).sum())
+
+    # rank-block round: the rows of the sampled heads follow from the schedule's threshold, which the
+    # oracle cannot recompute without the whole sequence; what it can check is each sampled head by
+    # itself: given the rows the device took from it, the head must have lost exactly its smallest
+    # metrics (ties in logical order) and be compacted as Algorithm 1 says
+    bud = budgets()
+    small, _ = W.gather_heads(sess.cache, heads)
+    st = oracle_state(small)
+    held0 = held_blocks()
+    rows, sel = sess.evict_rank_select(bud)
+    assert torch.equal(sel.cpu(), bud.cpu()) and int(rows.sum()) == int(bud.sum())
+    rows_s = rows[torch.tensor(heads, device=dev)].cpu().numpy()
+    masks = []
+    for i in range(len(heads)):     # the oracle's schedule of that head alone, asked for the rows the device took from it
+        one = oracle_state(W.gather_heads(sess.cache, [heads[i]])[0])
+        rows_w, masks_w, sel_w = O.rank_schedule(one, [int(rows_s[i])], protect_tail_blocks=0)
+        assert int(rows_w[0]) == int(rows_s[i]) == int(sel_w[0])
+        masks.append(masks_w[0])
+    freed = int(sess.compact_rank().item())
+    assert freed == int(bud.sum()) and held_blocks() == held0 - freed
+    sess.check_state()
+    O.compact_slots(st, masks)
+    post = oracle_state(W.gather_heads(sess.cache, heads)[0])
+    np.testing.assert_array_equal(post.lens(), st.lens())
+    for i in range(len(heads)):
+        n, o = O.slots_of(st, i)
+        n2, o2 = O.slots_of(post, i)
+        np.testing.assert_array_equal(post.k_cache[n2, o2], st.k_cache[n, o])
+        np.testing.assert_array_equal(post.v_cache[n2, o2], st.v_cache[n, o])
+        np.testing.assert_array_equal(post.metric[n2, o2], st.metric[n, o])
+        np.testing.assert_array_equal(post.pos[n2, o2], st.pos[n, o])
+    del st, post, small
+
+    # block round (the long tables take the sliced compaction): flags of the sampled heads given, the
+    # oracle moves them; keys of the sampled heads against the oracle's bit for bit
+    bud = budgets()
+    small, _ = W.gather_heads(sess.cache, heads)
+    st = oracle_state(small)
+    key = sess.metric_reduce()
+    want_key, _ = O.block_keys(st, small.metric.numpy())
+    hsel = torch.tensor(heads, device=dev)
+    nbs = -(-st.lens() // b)
+    for i in range(len(heads)):
+        np.testing.assert_array_equal(key[hsel[i], :nbs[i]].cpu().numpy().view(np.uint32), want_key[i, :nbs[i]].view(np.uint32))
+    held0 = held_blocks()
+    flag, count, sel = sess.evict_select(bud)
+    assert torch.equal(sel.cpu(), bud.cpu()) and int(count.sum()) == int(bud.sum())
+    flag_s = flag[hsel].cpu().numpy()
+    assert (flag_s.sum(1) == count[hsel].cpu().numpy()).all()
+    freed = int(sess.compact().item())
+    assert freed == int(bud.sum()) and held_blocks() == held0 - freed
+    sess.check_state()
+    O.compact(st, flag_s, flag_s.sum(1))
+    post = oracle_state(W.gather_heads(sess.cache, heads)[0])
+    np.testing.assert_array_equal(post.lens(), st.lens())
+    for i in range(len(heads)):
+        n, o = O.slots_of(st, i)
+        n2, o2 = O.slots_of(post, i)
+        np.testing.assert_array_equal(post.k_cache[n2, o2], st.k_cache[n, o])
+        np.testing.assert_array_equal(post.v_cache[n2, o2], st.v_cache[n, o])
+        np.testing.assert_array_equal(post.metric[n2, o2], st.metric[n, o])
+        np.testing.assert_array_equal(post.pos[n2, o2], st.pos[n, o])
+    assert held_blocks() + int(sess.cache.free_map.sum()) == shape.num_blocks
