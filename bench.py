@@ -437,40 +437,62 @@ def run_decode_config(spec, dev, keep_session=False):
 
 
 def per_layer_probe(sess, extras, steps):
-    """The same decode issued the way a model runs it: one call per layer (no append), then the
-    same calls captured once into a HIP graph and replayed."""
+    """The same decode issued the way a model runs it: one call per layer (no append).  Three ways:
+    kvc_paged_decode per layer (each call builds its own work list); the work lists of all layers
+    kept from one kvc_decode_plan launch per step and kvc_paged_decode_planned per layer; and
+    either sequence captured once into a HIP graph and replayed."""
     import torch
+    from paper_2410_00161_amd import binding as B
     shape, qs, n_in, no_metric = extras["shape"], extras["qs"], extras["n_in"], extras["no_metric"]
     ev = lambda: torch.cuda.Event(enable_timing=True)
-    for l in range(shape.num_layers):      # untimed first pass
-        sess.paged_decode(qs[0], accumulate_metric=not no_metric, layer_begin=l, layer_end=l + 1)
-    a, b_ = ev(), ev()
-    torch.cuda.synchronize()
-    a.record()
-    for i in range(steps):
+
+    def plain(q):
         for l in range(shape.num_layers):
-            sess.paged_decode(qs[i % n_in], accumulate_metric=not no_metric, layer_begin=l, layer_end=l + 1)
-    b_.record()
-    torch.cuda.synchronize()
-    per_layer_ms = a.elapsed_time(b_) / steps
-    graph = torch.cuda.CUDAGraph()
-    side = torch.cuda.Stream()
-    side.wait_stream(torch.cuda.current_stream())
-    with torch.cuda.graph(graph, stream=side):
+            sess.paged_decode(q, accumulate_metric=not no_metric, layer_begin=l, layer_end=l + 1)
+
+    def planned(q):
+        sess.decode_plan()
         for l in range(shape.num_layers):
-            sess.paged_decode(qs[0], accumulate_metric=not no_metric, layer_begin=l, layer_end=l + 1)
-    torch.cuda.synchronize()
-    graph.replay()
-    torch.cuda.synchronize()
-    a, b_ = ev(), ev()
-    a.record()
-    for i in range(steps):
+            sess.paged_decode_planned(q, l, accumulate_metric=not no_metric)
+
+    def timed(fn):
+        fn(qs[0])                          # untimed first pass
+        a, b_ = ev(), ev()
+        torch.cuda.synchronize()
+        a.record()
+        for i in range(steps):
+            fn(qs[i % n_in])
+        b_.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b_) / steps
+
+    def timed_graph(fn):
+        graph = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.graph(graph, stream=side):
+            fn(qs[0])
+        torch.cuda.synchronize()
         graph.replay()
-    b_.record()
-    torch.cuda.synchronize()
-    per_layer_graph_ms = a.elapsed_time(b_) / steps
-    del graph
-    return per_layer_ms, per_layer_graph_ms
+        torch.cuda.synchronize()
+        a, b_ = ev(), ev()
+        a.record()
+        for i in range(steps):
+            graph.replay()
+        b_.record()
+        torch.cuda.synchronize()
+        ms = a.elapsed_time(b_) / steps
+        del graph
+        return ms
+
+    res = {"plain": timed(plain), "plain_graph": timed_graph(plain), "planned": None, "planned_graph": None}
+    try:
+        res["planned"] = timed(planned)
+        res["planned_graph"] = timed_graph(planned)
+    except B.KvcError:      # shapes the kept lists do not cover
+        pass
+    assert B.kvc_poll_status(sess.cfg, sess.ws) == B.KVC_OK
+    return res
 
 
 def stream_read_probe(sess, dev):
@@ -694,9 +716,9 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    per_layer_ms = per_layer_graph_ms = None
+    per_layer = {"plain": None, "plain_graph": None, "planned": None, "planned_graph": None}
     if args.per_layer_steps > 0:
-        per_layer_ms, per_layer_graph_ms = per_layer_probe(sess, extras, args.per_layer_steps)
+        per_layer = per_layer_probe(sess, extras, args.per_layer_steps)
 
     cpu = None
     if args.cpu_heads > 0:
@@ -742,8 +764,10 @@ def main():
         "frac_of_hbm_peak": rec["frac_of_hbm_peak"],
         "kv_only_GBps": rec["kv_only_GBps"],
         "decode_steps_per_s": rec["decode_steps_per_s"],
-        "decode_only_ms_per_step_one_call_per_layer": per_layer_ms,
-        "decode_only_ms_per_step_one_call_per_layer_hip_graph": per_layer_graph_ms,
+        "decode_only_ms_per_step_one_call_per_layer": per_layer["plain"],
+        "decode_only_ms_per_step_one_call_per_layer_hip_graph": per_layer["plain_graph"],
+        "decode_only_ms_per_step_one_call_per_layer_kept_lists": per_layer["planned"],
+        "decode_only_ms_per_step_one_call_per_layer_kept_lists_hip_graph": per_layer["planned_graph"],
         "wall_s": rec["wall_s"],
         "eviction": rec["eviction"],
         "parity_sample": check["parity_sample"] if check else None,

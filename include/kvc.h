@@ -202,6 +202,22 @@ int kvc_paged_decode(const kvc_config* cfg, const kvc_state* st, const void* q, 
                      int layer_begin, int layer_end, int accumulate_metric,
                      void* ws, void* stream);
 
+/* A model decodes one layer at a time (the query of a layer follows from the layer before), and
+ * a call over one layer's few heads spends a fair part of its time on its work list.  This call
+ * builds the work lists of ALL layers in one launch and keeps them in the workspace;
+ * kvc_paged_decode_planned then decodes one layer from its kept list (same kernels, same
+ * results as kvc_paged_decode over that layer).  ctx_plus = 0: the lists are for the heads as
+ * they are now; 1: for every head one token longer than now, i.e. planned before the step's
+ * kvc_append calls (layer by layer, each before its layer's decode).  The lists stay valid
+ * until a context length changes in any other way (compaction, free, preemption, a second
+ * append): a layer decoded from a stale list does nothing for the heads that changed and leaves
+ * KVC_ERR_ARG in the status word (kvc_poll_status; the cache state is not touched).
+ * Covers what kvc_paged_decode runs on its tiled kernels with at most 1024 head instances per
+ * layer and the library's own chunk length, else KVC_ERR_UNSUPPORTED.  Asynchronous.     */
+int kvc_decode_plan(const kvc_config* cfg, const kvc_state* st, int ctx_plus, void* ws, void* stream);
+int kvc_paged_decode_planned(const kvc_config* cfg, const kvc_state* st, const void* q, float* out, int layer,
+                             int accumulate_metric, void* ws, void* stream);
+
 /* kvc_paged_decode for callers that cannot allocate device memory or bring a workspace: code
  * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
  * arguments, kernels and results as kvc_paged_decode, without `ws`: the temporaries live in a

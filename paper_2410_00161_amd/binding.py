@@ -24,7 +24,7 @@ KVC_ASYNC = 1
 
 EXPORTS = [
     "kvc_workspace_bytes", "kvc_validate", "kvc_status_string", "kvc_workspace_reset",
-    "kvc_poll_status", "kvc_check_state", "kvc_block_alloc", "kvc_block_free", "kvc_append", "kvc_paged_decode", "kvc_paged_decode_static",
+    "kvc_poll_status", "kvc_check_state", "kvc_block_alloc", "kvc_block_free", "kvc_append", "kvc_paged_decode", "kvc_paged_decode_static", "kvc_decode_plan", "kvc_paged_decode_planned",
     "kvc_metric_reduce", "kvc_evict_select", "kvc_compact", "kvc_set_decode_chunk",
     "kvc_get_decode_chunk", "kvc_get_decode_short", "kvc_evict_rank_select", "kvc_compact_rank", "kvc_window_metric", "kvc_query_block_metric", "kvc_count_blocks", "kvc_prefill_alloc", "kvc_preempt", "kvc_compression_batch",
     "kvc_profile_begin", "kvc_profile_enable", "kvc_profile_collect", "kvc_stream_read_probe",
@@ -73,6 +73,8 @@ def lib() -> C.CDLL:
         L.kvc_append.argtypes = [cfgp, stp, P, P, P, I, I, P, P, I]
         L.kvc_paged_decode.argtypes = [cfgp, stp, P, P, I, I, I, P, P]
         L.kvc_paged_decode_static.argtypes = [cfgp, stp, P, P, I, I, I, P]
+        L.kvc_decode_plan.argtypes = [cfgp, stp, I, P, P]
+        L.kvc_paged_decode_planned.argtypes = [cfgp, stp, P, P, I, I, P, P]
         L.kvc_metric_reduce.argtypes = [cfgp, stp, P, I, P, P]
         L.kvc_evict_select.argtypes = [cfgp, stp, P, P, P, I, I, P, P, P, P, P, I]
         L.kvc_compact.argtypes = [cfgp, stp, P, P, P, P, P, I]
@@ -201,6 +203,15 @@ def kvc_paged_decode(cfg, st, q, out, layer_begin, layer_end, accumulate_metric,
     _check(lib().kvc_paged_decode(C.byref(cfg), C.byref(st), _ptr(q), _ptr(out, torch.float32),
                                   layer_begin, layer_end, int(accumulate_metric), _ptr(ws),
                                   _stream(stream)), "kvc_paged_decode")
+
+
+def kvc_decode_plan(cfg, st, ctx_plus, ws, stream=None):
+    _check(lib().kvc_decode_plan(C.byref(cfg), C.byref(st), int(ctx_plus), _ptr(ws), _stream(stream)), "kvc_decode_plan")
+
+
+def kvc_paged_decode_planned(cfg, st, q, out, layer, accumulate_metric, ws, stream=None):
+    _check(lib().kvc_paged_decode_planned(C.byref(cfg), C.byref(st), _ptr(q), _ptr(out, torch.float32), int(layer),
+                                          int(accumulate_metric), _ptr(ws), _stream(stream)), "kvc_paged_decode_planned")
 
 
 KVC_STATIC_SCRATCH_BYTES = 32 << 20

@@ -82,8 +82,8 @@ int kvc_workspace_reset(const kvc_config* cfg, void* ws, void* stream) {
   if (!ws || ((uintptr_t)ws & 255)) return KVC_ERR_ARG;
   Workspace W = carve(dims_of(cfg), ws);
   // a fill kernel rather than a memset node: safe to record into a HIP graph
-  hipLaunchKernelGGL(zero_words_kernel, dim3((HW_WORDS + 63) / 64), dim3(64), 0, (hipStream_t)stream, W.header,
-                     HW_WORDS);
+  const int words = HW_WORDS * (1 + dims_of(cfg).Lyr);   // the header, then the layers' plan headers, back to back
+  hipLaunchKernelGGL(zero_words_kernel, dim3((words + 255) / 256), dim3(256), 0, (hipStream_t)stream, W.header, words);
   KVC_LAUNCH_CHECK();
   return KVC_OK;
 }

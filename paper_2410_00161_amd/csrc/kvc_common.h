@@ -59,6 +59,7 @@ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 // Carves the caller's workspace.  All offsets are multiples of 256 bytes.
 struct Workspace {
   int32_t* header;     // [HW_WORDS]
+  int32_t* plan_hdr;   // [Lyr][HW_WORDS]     header block of every layer's kept work list (kvc_decode_plan)
   int32_t* tile_sums;  // [ntile_max + 1]
   int32_t* off_a;      // [G + 1]  scan over head instances (requests / chunks / ties)
   int32_t* off_b;      // [G + 1]
@@ -88,6 +89,7 @@ inline Workspace carve(const Dims& D, void* base) {
   size_t nmax = (size_t)(D.N > D.G ? D.N : D.G) + 1;
   size_t ntile = nmax / kScanTile + 2;
   w.header = (int32_t*)take(HW_WORDS * 4);
+  w.plan_hdr = (int32_t*)take((size_t)D.Lyr * HW_WORDS * 4);
   w.tile_sums = (int32_t*)take(ntile * 4);
   w.off_a = (int32_t*)take(((size_t)D.G + 1) * 4);
   w.off_b = (int32_t*)take(((size_t)D.G + 1) * 4);

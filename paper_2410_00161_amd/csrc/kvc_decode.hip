@@ -258,6 +258,13 @@ __global__ void __launch_bounds__(NW * 64) decode_chunk_kernel(DecodeArgs A) {
   const int total_items = A.header[HW_TOTAL_ITEMS];
   const int short_items = A.header[HW_SHORT_ITEMS];
   if (NW == 4 && blockIdx.x == 0 && tid < HW_DEC_END - HW_DEC_BINS) A.header[HW_DEC_BINS + tid] = 0;  // work-list block back to zero
+  if (NW == 4 && A.plan && (int)blockIdx.x < A.gsel) {
+    // a list kept from kvc_decode_plan was made without the output at hand: the zero rows of a
+    // head that holds no KV are written here, by the workgroup with the head's index
+    const int ge = sel_to_g(A.D, A.l0, A.nl, blockIdx.x);
+    if (A.ctx[ge] == 0)
+      for (int i = tid; i < R * HD; i += NT) A.out[(size_t)ge * R * HD + i] = 0.0f;
+  }
   if (total_items > A.cap || short_items < 0 || short_items > total_items) return;
   const int n_long = total_items - short_items;
   if ((int)blockIdx.x >= (NW == 4 ? n_long : short_items)) return;
@@ -269,6 +276,14 @@ __global__ void __launch_bounds__(NW * 64) decode_chunk_kernel(DecodeArgs A) {
   if ((unsigned)g >= (unsigned)A.D.G || n_tok <= 0 || n_tok > T || t0 < 0 || nch <= 0 || Tc < 64 || Tc > A.T ||
       (nch > 1 && (it.pbase < 0 || it.pbase + nch > A.cap)))
     return;  // not a record this call wrote
+  if (A.plan) {
+    // the head must still be as long as the plan took it to be (the record carries that length).
+    // A stale plan is an argument error, found here and left in the status word.
+    if (A.ctx[g] != it.pad[0]) {
+      if (tid == 0 && A.status[HW_STATUS] == KVC_OK) A.status[HW_STATUS] = KVC_ERR_ARG;
+      return;
+    }
+  }
   const int b = A.D.b, lb = A.log2b;
 
   extern __shared__ __align__(16) char smem_raw[];
@@ -702,6 +717,7 @@ __global__ void __launch_bounds__(256) decode_combine_kernel(DecodeArgs A) {
   const int g = it.g, t0 = it.t0, n_tok = it.n_tok;
   const int Tc = A.header[HW_CHUNK_T];       // tokens the work list was cut at
   if (Tc < 64 || Tc > A.T) return;
+  if (A.plan && A.ctx[g] != it.pad[0]) return;   // a kept list that no longer fits the head: its chunks did nothing either
   const int c = t0 / Tc;
   if (c >= nch) return;
   const int first = it.pbase;                // partial-result slots first .. first + nch - 1
@@ -1058,12 +1074,17 @@ static int decode_args_check(const kvc_config* cfg, const kvc_state* st, const v
   return KVC_OK;
 }
 
+// plan_mode 0: an ordinary call (work list, chunks, combine).  1: only the work lists, one per
+// layer, kept in the workspace (q and out are not looked at).  2: layer `layer_begin` from its kept list.
+enum { PLAN_NONE = 0, PLAN_BUILD = 1, PLAN_USE = 2 };
 static int paged_decode_impl(const kvc_config* cfg, const kvc_state* st, const void* q, float* out,
-                             int layer_begin, int layer_end, int accumulate_metric, void* ws, void* stream) {
-  int rc = decode_args_check(cfg, st, q, out, layer_begin, layer_end);
+                             int layer_begin, int layer_end, int accumulate_metric, void* ws, void* stream,
+                             int plan_mode = PLAN_NONE, int ctx_plus = 0) {
+  int rc = plan_mode == PLAN_BUILD ? validate(cfg, st) : decode_args_check(cfg, st, q, out, layer_begin, layer_end);
   if (rc != KVC_OK) return rc;
   if (!ws || ((uintptr_t)ws & 255)) return KVC_ERR_ARG;
   Dims D = dims_of(cfg);
+  if (plan_mode == PLAN_BUILD) { layer_begin = 0; layer_end = 1; }   // lists are per layer: sized as a one-layer call
   Workspace W = carve(D, ws);
   hipStream_t s = (hipStream_t)stream;
 
@@ -1079,6 +1100,8 @@ static int paged_decode_impl(const kvc_config* cfg, const kvc_state* st, const v
   A.cap = (int)(max_items_of(D) < 0x7fffffffull ? max_items_of(D) : 0x7fffffffull);
   A.items = (DecodeItem*)W.items; A.slot_item = W.slot_item; A.part_ml = W.part_ml; A.part_acc = W.part_acc; A.stash = W.stash;
   A.header = W.header;
+  A.status = W.header;
+  A.plan = 0; A.plan_stride = 0; A.ctx_plus = 0;
   A.scale_log2 = (float)(1.4426950408889634 / sqrt((double)D.d));
 
   int T = 0;
@@ -1099,6 +1122,9 @@ static int paged_decode_impl(const kvc_config* cfg, const kvc_state* st, const v
   A.log2b = 0;
   while ((1 << A.log2b) < D.b) ++A.log2b;
 
+  // kept lists exist for what a model's layer-by-layer calls look like: the tiled kernels, few heads
+  // per layer, the chunk length picked on the device
+  if (plan_mode != PLAN_NONE && !(tiled && small_call && on_device && A.gsel <= kSmallWorklistHeads)) return KVC_ERR_UNSUPPORTED;
   if (!tiled) {
     const size_t gl = ((size_t)D.r * D.d + 4 * 16 + 2 * 16) * 4;
     hipLaunchKernelGGL(decode_generic_kernel, dim3(A.gsel), dim3(256), gl, s, A);
@@ -1114,7 +1140,24 @@ static int paged_decode_impl(const kvc_config* cfg, const kvc_state* st, const v
   const size_t bound_row = (size_t)A.gsel * (((size_t)D.maxb * D.b + Tmin - 1) / Tmin);
   const size_t grid = bound_pool < bound_row ? bound_pool : bound_row;
   if (grid > 0x7fffffffull) return KVC_ERR_UNSUPPORTED;   // before anything is launched: the work list stays clean
-  if (A.gsel <= kSmallWorklistHeads) {
+  if (plan_mode != PLAN_NONE) {
+    // every layer's list has `grid` records of its own (the most its call could need)
+    if (grid * (size_t)D.Lyr > (size_t)A.cap) return KVC_ERR_UNSUPPORTED;
+    A.plan = 1;
+    A.plan_stride = (int)grid;
+    A.ctx_plus = ctx_plus;
+    A.header = W.plan_hdr;
+    if (plan_mode == PLAN_BUILD) {
+      A.out = nullptr;    // (the zero rows of heads without a KV are written when the layer is decoded)
+      hipLaunchKernelGGL(decode_worklist_small_kernel, dim3(D.Lyr), dim3(1024), 0, s, A);
+      KVC_LAUNCH_CHECK();
+      return KVC_OK;
+    }
+    A.header += (size_t)layer_begin * HW_WORDS;
+    A.items += (size_t)layer_begin * grid;
+    A.slot_item += (size_t)layer_begin * grid;
+    A.cap = (int)grid;
+  } else if (A.gsel <= kSmallWorklistHeads) {
     hipLaunchKernelGGL(decode_worklist_small_kernel, dim3(1), dim3(1024), 0, s, A);
     KVC_LAUNCH_CHECK();
   } else {
@@ -1160,6 +1203,16 @@ extern "C" {
 int kvc_paged_decode(const kvc_config* cfg, const kvc_state* st, const void* q, float* out,
                      int layer_begin, int layer_end, int accumulate_metric, void* ws, void* stream) {
   return paged_decode_impl(cfg, st, q, out, layer_begin, layer_end, accumulate_metric, ws, stream);
+}
+
+int kvc_decode_plan(const kvc_config* cfg, const kvc_state* st, int ctx_plus, void* ws, void* stream) {
+  if (ctx_plus < 0 || ctx_plus > 1) return KVC_ERR_ARG;
+  return paged_decode_impl(cfg, st, nullptr, nullptr, 0, 1, 0, ws, stream, PLAN_BUILD, ctx_plus);
+}
+
+int kvc_paged_decode_planned(const kvc_config* cfg, const kvc_state* st, const void* q, float* out, int layer,
+                             int accumulate_metric, void* ws, void* stream) {
+  return paged_decode_impl(cfg, st, q, out, layer, layer + 1, accumulate_metric, ws, stream, PLAN_USE, 0);
 }
 
 int kvc_paged_decode_static(const kvc_config* cfg, const kvc_state* st, const void* q, float* out,

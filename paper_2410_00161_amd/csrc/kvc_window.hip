@@ -568,6 +568,8 @@ static int window_common(const kvc_config* cfg, const kvc_state* st, const void*
   A.cap = (int)(max_items_of(D) < 0x7fffffffull ? max_items_of(D) : 0x7fffffffull);
   A.items = (DecodeItem*)Wk.items; A.slot_item = Wk.slot_item; A.part_ml = Wk.part_ml; A.part_acc = Wk.part_acc; A.stash = Wk.stash;
   A.header = Wk.header;
+  A.status = Wk.header;
+  A.plan = 0; A.plan_stride = 0; A.ctx_plus = 0;
   A.scale_log2 = (float)(1.4426950408889634 / sqrt((double)D.d));
   W.pool = pool; W.add = accumulate != 0; W.exclude = exclude;
   W.q_count = w;

@@ -13,7 +13,7 @@ struct DecodeItem {   // 32 bytes
   int n_tok;    // tokens in the chunk
   int nch;      // chunks of the head
   int pbase;    // first partial-result slot of the head (heads of more than one chunk)
-  int pad[3];
+  int pad[3];   // [0]: the head's length the list was made for (lists kept by kvc_decode_plan)
 };
 
 struct DecodeArgs {
@@ -39,6 +39,11 @@ struct DecodeArgs {
   float* part_acc;
   float* stash;
   int32_t* header;
+  // Work lists kept from one launch for every layer (kvc_decode_plan): layer l has its own header
+  // block at header + l * HW_WORDS and its own stretch of plan_stride records of items / slot_item.
+  int plan, plan_stride;  // plan: the work-list kernel runs one workgroup per layer; a decode reads one layer's list
+  int ctx_plus;           // the plan is made for heads ctx_plus tokens longer than they are now
+  int32_t* status;        // the workspace's own header (status word), whatever `header` points at
   float scale_log2;       // log2(e) / sqrt(d)
 };
 
@@ -165,14 +170,20 @@ static __global__ void __launch_bounds__(1024) decode_worklist_small_kernel(Deco
   __shared__ unsigned long long tokens;
   __shared__ int live;
   const int tid = threadIdx.x;
+  // a plan: workgroup l lists layer A.l0 + l into that layer's header block and stretch of records
+  const int layer = A.plan ? (int)blockIdx.x : 0;
+  int32_t* header = A.header + (size_t)layer * (A.plan ? HW_WORDS : 0);
+  DecodeItem* items = A.items + (size_t)layer * A.plan_stride;
+  int32_t* slot_item = A.slot_item + (size_t)layer * A.plan_stride;
+  const int cap = A.plan ? A.plan_stride : A.cap;
   if (tid == 0) { ptot = 0; tokens = 0; live = 0; }
   if (tid < 16) bins[tid] = 0;
   if (tid < 17) cur[tid] = 0;
   __syncthreads();
   int g = 0, C = 0, nfull = 0, rem = 0, nch = 0, cls = 0;
   if (tid < A.gsel) {
-    g = sel_to_g(A.D, A.l0, A.nl, tid);
-    C = A.ctx[g];
+    g = sel_to_g(A.D, A.l0 + layer, A.nl, tid);
+    C = A.ctx[g] + A.ctx_plus;
   }
   // Chunk length of a call over few heads.  Such a call is over when its slowest item is.  One
   // workgroup alone on its CU streams ~25 GB/s, two that share one ~12 each, the chip ~6 TB/s:
@@ -193,7 +204,7 @@ static __global__ void __launch_bounds__(1024) decode_worklist_small_kernel(Deco
     const int t64 = (int)((want < (unsigned long long)A.T ? want : (unsigned long long)A.T) + 63) & ~63;
     T = min(A.T, max(256, t64));
   }
-  if (tid == 0) A.header[HW_CHUNK_T] = T;
+  if (tid == 0) header[HW_CHUNK_T] = T;
   if (tid < A.gsel) {
     nfull = C / T;
     rem = C - nfull * T;
@@ -205,15 +216,15 @@ static __global__ void __launch_bounds__(1024) decode_worklist_small_kernel(Deco
   }
   __syncthreads();
   if (tid == 0) {
-    A.header[HW_TOTAL_PARTIALS] = ptot;
+    header[HW_TOTAL_PARTIALS] = ptot;
     int run = 0, shorts = 0;
     for (int k = 0; k < 16; ++k) {
       base[k] = run;
       run += bins[k];
       if (k >= A.short_class) shorts += bins[k];
     }
-    A.header[HW_TOTAL_ITEMS] = run;
-    A.header[HW_SHORT_ITEMS] = shorts;
+    header[HW_TOTAL_ITEMS] = run;
+    header[HW_SHORT_ITEMS] = shorts;
   }
   __syncthreads();
   if (tid >= A.gsel) return;
@@ -226,23 +237,23 @@ static __global__ void __launch_bounds__(1024) decode_worklist_small_kernel(Deco
   }
   const bool slotted = nch > 1 || A.all_partials;
   const int pbase = slotted ? atomicAdd(&cur[16], nch) : 0;
-  if (pbase < 0 || pbase + nch > A.cap) return;
+  if (pbase < 0 || pbase + nch > cap) return;
   if (nfull) {
     const int at = base[0] + atomicAdd(&cur[0], nfull);
-    if (at < 0 || at + nfull > A.cap) return;
+    if (at < 0 || at + nfull > cap) return;
     for (int c = 0; c < nfull; ++c) {
-      DecodeItem it = {g, c * T, T, nch, pbase, {0, 0, 0}};
+      DecodeItem it = {g, c * T, T, nch, pbase, {C, 0, 0}};
       const int place = at + (A.rotate_chunks ? (c + g) % nfull : c);
-      A.items[place] = it;
-      if (slotted) A.slot_item[pbase + c] = place;
+      items[place] = it;
+      if (slotted) slot_item[pbase + c] = place;
     }
   }
   if (rem) {
     const int at = base[cls] + atomicAdd(&cur[cls], 1);
-    if (at < 0 || at >= A.cap) return;
-    DecodeItem it = {g, nfull * T, rem, nch, pbase, {0, 0, 0}};
-    A.items[at] = it;
-    if (slotted) A.slot_item[pbase + nfull] = at;
+    if (at < 0 || at >= cap) return;
+    DecodeItem it = {g, nfull * T, rem, nch, pbase, {C, 0, 0}};
+    items[at] = it;
+    if (slotted) slot_item[pbase + nfull] = at;
   }
 }
 

@@ -57,6 +57,14 @@ class KvcSession:
         B.kvc_paged_decode(self.cfg, self.st, q, out, layer_begin, layer_end, accumulate_metric, self.ws)
         return out
 
+    def decode_plan(self, ctx_plus=0):
+        B.kvc_decode_plan(self.cfg, self.st, ctx_plus, self.ws)
+
+    def paged_decode_planned(self, q, layer, accumulate_metric=True, out=None):
+        out = self.out if out is None else out
+        B.kvc_paged_decode_planned(self.cfg, self.st, q, out, layer, accumulate_metric, self.ws)
+        return out
+
     def metric_reduce(self, key_mode=B.KVC_KEY_SUM):
         B.kvc_metric_reduce(self.cfg, self.st, self.block_key, self.ws, key_mode=key_mode)
         return self.block_key

@@ -702,3 +702,96 @@ def test_compression_batch_matches_oracle(skw):
     with pytest.raises(B.KvcError):
         B.kvc_compression_batch(sess.cfg, sess.st, torch.zeros(shape.num_seqs, dtype=torch.int64, device=sess.device),
                                 None, -1, in_batch, kvs, sess.ws)
+
+
+# ---------------------------------------------------------------------------
+# work lists of all layers kept from one launch (kvc_decode_plan / kvc_paged_decode_planned)
+# ---------------------------------------------------------------------------
+
+PLAN_CASES = [
+    ("many_short_heads", dict(S=6, Lyr=5, Hk=8, r=4, d=128, kv_dtype="bf16", L=700, rho=1.5)),
+    ("few_long_heads_r8_fp8", dict(S=1, Lyr=3, Hk=8, r=8, d=128, kv_dtype="fp8", L=9000, rho=1.3, b=32)),
+    ("b4_d64", dict(S=3, Lyr=2, Hk=4, r=2, d=64, kv_dtype="bf16", L=2000, rho=2.0, b=4)),
+]
+
+
+@pytest.mark.parametrize("name,kw", PLAN_CASES, ids=[c[0] for c in PLAN_CASES])
+def test_decode_layer_by_layer_from_kept_work_lists(name, kw):
+    say("planned decode", name)
+    shape, ctx, seed = W.small_mixed(83, extra_blocks=3, **kw)
+    ctx[2] = 0
+    cache = W.make_cache(shape, ctx, seed, placement="fragmented", init_metric="prefill")
+    st = oracle_state(cache)
+    sess = session(cache)
+    q = W.make_query(shape, seed)
+    want = O.paged_decode(st, q.double().numpy())
+    sess.out.fill_(5.0)
+    sess.decode_plan()
+    for l in reversed(range(shape.num_layers)):          # any order of layers
+        sess.paged_decode_planned(q.to(sess.device), l)
+    torch.cuda.synchronize()
+    assert B.kvc_poll_status(sess.cfg, sess.ws) == B.KVC_OK
+    np.testing.assert_allclose(sess.out.cpu().numpy().astype(np.float64), want, rtol=0, atol=TOL)
+    live = st.free_map == 0
+    np.testing.assert_allclose(sess.cache.metric.cpu().numpy().astype(np.float64)[live], st.metric[live], rtol=0, atol=TOL)
+    # the same numbers as the ordinary call over that layer, bit for bit (same kernels, same cuts)
+    ref = session(cache)
+    for l in range(shape.num_layers):
+        ref.paged_decode(q.to(ref.device), layer_begin=l, layer_end=l + 1)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(sess.out.cpu().numpy(), ref.out.cpu().numpy())
+    np.testing.assert_array_equal(sess.cache.metric.cpu().numpy(), ref.cache.metric.cpu().numpy())
+    # a step as a model runs it: the lists are made for heads one token longer, then every layer
+    # appends its token and decodes from its list
+    k, v = W.make_new_kv(shape, seed, 1)
+    q2 = W.make_query(shape, seed, 1)
+    for l in range(shape.num_layers):     # (the allocation order follows the order of the appends)
+        O.append(st, k.double().numpy(), v.double().numpy(), layer_begin=l, layer_end=l + 1)
+    want2 = O.paged_decode(st, q2.double().numpy())
+    sess.decode_plan(ctx_plus=1)
+    for l in range(shape.num_layers):
+        sess.append(k.to(sess.device), v.to(sess.device), None, l, l + 1)
+        sess.paged_decode_planned(q2.to(sess.device), l)
+    torch.cuda.synchronize()
+    assert B.kvc_poll_status(sess.cfg, sess.ws) == B.KVC_OK
+    np.testing.assert_allclose(sess.out.cpu().numpy().astype(np.float64), want2, rtol=0, atol=TOL)
+    assert_state_equal(sess, st)
+    # a stale list: the heads have grown since it was made.  Nothing of the cache changes, and the
+    # status word says so
+    m0 = sess.cache.metric.clone()
+    sess.append(k.to(sess.device), v.to(sess.device))
+    m1 = sess.cache.metric.clone()
+    sess.paged_decode_planned(q2.to(sess.device), 0)
+    torch.cuda.synchronize()
+    assert torch.equal(sess.cache.metric, m1)
+    assert B.kvc_poll_status(sess.cfg, sess.ws) == B.KVC_ERR_ARG
+    B.kvc_workspace_reset(sess.cfg, sess.ws)
+    del m0
+
+
+def test_kept_work_lists_refuse_what_they_do_not_cover():
+    say("planned decode, unsupported shapes")
+    # more than 1024 head instances per layer
+    shape, ctx, seed = W.small_mixed(85, S=140, Lyr=1, Hk=8, r=1, d=64, L=64, rho=1.0)
+    sess = session(W.make_cache(shape, ctx, seed))
+    with pytest.raises(B.KvcError) as e:
+        sess.decode_plan()
+    assert e.value.code == B.KVC_ERR_UNSUPPORTED
+    # a shape of the fallback kernel; a forced chunk length
+    shape, ctx, seed = W.small_mixed(86, S=2, Lyr=2, Hk=2, r=3, d=64, kv_dtype="f32", L=100)
+    sess = session(W.make_cache(shape, ctx, seed))
+    with pytest.raises(B.KvcError) as e:
+        sess.decode_plan()
+    assert e.value.code == B.KVC_ERR_UNSUPPORTED
+    shape, ctx, seed = W.small_mixed(87, S=2, Lyr=2, Hk=2, r=4, d=128, L=300)
+    sess = session(W.make_cache(shape, ctx, seed))
+    B.kvc_set_decode_chunk(128)
+    try:
+        with pytest.raises(B.KvcError) as e:
+            sess.decode_plan()
+        assert e.value.code == B.KVC_ERR_UNSUPPORTED
+    finally:
+        B.kvc_set_decode_chunk(0)
+    with pytest.raises(B.KvcError) as e:
+        B.kvc_decode_plan(sess.cfg, sess.st, 2, sess.ws)
+    assert e.value.code == B.KVC_ERR_ARG
