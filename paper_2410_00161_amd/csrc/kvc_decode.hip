@@ -1132,10 +1132,11 @@ static int paged_decode_impl(const kvc_config* cfg, const kvc_state* st, const v
     return KVC_OK;
   }
   // items <= (slots in the pool) / T + heads, and <= heads * chunks a full row can hold.  A chunk
-  // length picked on the device is T or at least 1.25 / 512 of all tokens, which makes at most
-  // 512 / 1.25 full chunks (512 allowed for).
+  // length picked on the device is T (then the first bound holds), or at least 1.25 / 512 of all
+  // tokens, or the 256-token floor with under 256 * 512 / 1.25 tokens in all: at most 512 / 1.25
+  // full chunks either way, and one shorter item per head.
   const size_t most_tokens = std::min((size_t)D.N * D.b, (size_t)A.gsel * D.maxb * D.b);   // pool, or the rows of the heads called for
-  const size_t bound_pool = most_tokens / T + (size_t)A.gsel + (A.adapt_T ? 512 : 0);
+  const size_t bound_pool = (A.adapt_T ? std::max(most_tokens / T, (size_t)410) : most_tokens / T) + (size_t)A.gsel;
   const size_t Tmin = A.adapt_T ? 256 : (size_t)T;
   const size_t bound_row = (size_t)A.gsel * (((size_t)D.maxb * D.b + Tmin - 1) / Tmin);
   const size_t grid = bound_pool < bound_row ? bound_pool : bound_row;
