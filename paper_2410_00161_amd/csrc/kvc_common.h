@@ -85,7 +85,8 @@ inline Workspace carve(const Dims& D, void* base) {
   Workspace w;
   char* p = (char*)base;
   size_t o = 0;
-  auto take = [&](size_t bytes) { char* q = p + o; o += align_up(bytes, 256); return q; };
+  // (sized with a null base by kvc_workspace_bytes: then only the offsets are formed)
+  auto take = [&](size_t bytes) { char* q = p ? p + o : nullptr; o += align_up(bytes, 256); return q; };
   size_t nmax = (size_t)(D.N > D.G ? D.N : D.G) + 1;
   size_t ntile = nmax / kScanTile + 2;
   w.header = (int32_t*)take(HW_WORDS * 4);

@@ -272,3 +272,51 @@ def test_append_and_decode_replay_from_a_hip_graph():
         assert np.isfinite(scratch)
     assert B.kvc_poll_status(sess.cfg, sess.ws) == B.KVC_OK
     assert_state_equal(sess, st)
+
+
+def test_snapshot_of_the_six_buffers_resumes_bit_for_bit():
+    """The whole state of a cache is its plain buffers (keys, values, metrics, logical indices,
+    tables, lengths, free map); the workspace holds nothing between calls.  A copy of them taken in
+    the middle of a run, put into a new session with a new workspace, continues exactly as the
+    original does: same outputs, same metrics, same tables after decode steps and both kinds of round."""
+    from paper_2410_00161_amd.session import KvcSession
+    print("[case] snapshot / resume", flush=True)
+    shape, ctx, seed = W.small_mixed(311, S=3, Lyr=2, Hk=2, r=4, d=128, L=900, rho=2.0, extra_blocks=4)
+    a = KvcSession(W.make_cache(shape, ctx, seed, placement="fragmented", init_metric="prefill"))
+
+    def steps(sess, first, n, outs):
+        for i in range(first, first + n):
+            k, v = W.make_new_kv(shape, seed, i, sess.device)
+            sess.append(k, v)
+            outs.append(sess.paged_decode(W.make_query(shape, seed, i, sess.device)).clone())
+
+    def round_(sess, rank):
+        nb = (sess.cache.ctx_len.reshape(shape.num_seqs, -1).long() + shape.block_size - 1) // shape.block_size
+        bud = (nb.sum(1) // 5).to(torch.int32)
+        if rank:
+            sess.evict_rank_select(bud)
+            return int(sess.compact_rank().item())
+        sess.metric_reduce()
+        sess.evict_select(bud)
+        return int(sess.compact().item())
+
+    warm = []
+    steps(a, 0, 5, warm)
+    assert round_(a, False) > 0
+    snap = a.cache.clone().to("cpu")                     # the snapshot: six buffers (and pos), nothing else
+    b = KvcSession(snap)                                 # new tensors, new workspace
+    out_a, out_b = [], []
+    for sess, outs in ((a, out_a), (b, out_b)):
+        steps(sess, 5, 7, outs)
+        outs.append(torch.tensor(round_(sess, True)))
+        steps(sess, 12, 3, outs)
+        outs.append(torch.tensor(round_(sess, False)))
+    torch.cuda.synchronize()
+    for x, y in zip(out_a, out_b):
+        assert torch.equal(x.cpu(), y.cpu())
+    for name in ("k_cache", "v_cache", "metric", "pos", "block_table", "ctx_len", "free_map"):
+        ta, tb = getattr(a.cache, name), getattr(b.cache, name)
+        if ta.dtype == torch.float8_e4m3fn:
+            ta, tb = ta.view(torch.uint8), tb.view(torch.uint8)
+        assert torch.equal(ta.cpu(), tb.cpu()), name
+    a.check_state()
