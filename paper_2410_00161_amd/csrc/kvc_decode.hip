@@ -756,18 +756,32 @@ __global__ void __launch_bounds__(256) decode_combine_kernel(DecodeArgs A) {
     float wv[R];
 #pragma unroll
     for (int hh = 0; hh < R; ++hh) wv[hh] = s_w[hh];
-    for (int tok = tid; tok < n_tok; tok += 256) {
-      const int j = t0 + tok;
-      const size_t slot = ((size_t)row[j >> lb] << lb) + (j & (b - 1));
-      float e[R];
-      stash_load<R>(A.stash, slot, e);
-      float inc = 0.0f;
+    // four tokens per thread at a time, their block ids asked for together and then their exps:
+    // a token by itself is a chain of two dependent loads in front of one add, and a chunk of
+    // 3456 tokens a dozen such chains per thread one after the other
+    for (int tok0 = tid; tok0 < n_tok; tok0 += 4 * 256) {
+      int id[4];
 #pragma unroll
-      for (int hh = 0; hh < R; ++hh) {
-        const float p = e[hh] * wv[hh];
-        inc += A.D.mode == KVC_L2 ? p * p : p;
+      for (int u = 0; u < 4; ++u) id[u] = row[(t0 + min(tok0 + u * 256, n_tok - 1)) >> lb];
+      size_t slot[4];
+      float e[4][R];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int j = t0 + min(tok0 + u * 256, n_tok - 1);
+        slot[u] = ((size_t)id[u] << lb) + (j & (b - 1));
+        stash_load<R>(A.stash, slot[u], e[u]);
       }
-      unsafeAtomicAdd(&A.metric[slot], inc);
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        if (tok0 + u * 256 >= n_tok) break;
+        float inc = 0.0f;
+#pragma unroll
+        for (int hh = 0; hh < R; ++hh) {
+          const float p = e[u][hh] * wv[hh];
+          inc += A.D.mode == KVC_L2 ? p * p : p;
+        }
+        unsafeAtomicAdd(&A.metric[slot[u]], inc);
+      }
     }
   }
   if (c == 0) {

@@ -432,7 +432,8 @@ __global__ void __launch_bounds__(kWinThreads) window_sum_kernel(WindowArgs W) {
     const int t = tt + (e / MM::NV) * M + MM::token(e % MM::NV, lane);
     if (t < n_tok && t0 + t < C) {
       const size_t slot = ((size_t)s_tab[t >> lb] << lb) + (t & (b - 1));
-      W.raw[slot] = tok[0];
+      if (W.pool > 1) W.raw[slot] = tok[0];          // pooled over the sequence by window_pool_kernel
+      else if (t < n_fed) A.metric[slot] = W.add ? A.metric[slot] + tok[0] : tok[0];   // no pooling: straight into the metric (one writer per slot)
     }
   };
   for (int tt = wv * 64; tt < min(n_tok, n_fed); tt += 64 * kWinWaves) {
@@ -601,8 +602,10 @@ static int window_common(const kvc_config* cfg, const kvc_state* st, const void*
     if (D.dtype == KVC_BF16) rc = D.d == 128 ? launch_window_rows<2, 128>(W, pr, (int)grid, s) : launch_window_rows<2, 64>(W, pr, (int)grid, s);
     else rc = D.d == 128 ? launch_window_rows<1, 128>(W, pr, (int)grid, s) : launch_window_rows<1, 64>(W, pr, (int)grid, s);
     if (rc != KVC_OK) return rc;
-    hipLaunchKernelGGL(window_pool_kernel, dim3(A.gsel, pool_tiles), dim3(256), 0, s, W);
-    KVC_LAUNCH_CHECK();
+    if (pool > 1) {   // without pooling the sums went into the metric as they were formed
+      hipLaunchKernelGGL(window_pool_kernel, dim3(A.gsel, pool_tiles), dim3(256), 0, s, W);
+      KVC_LAUNCH_CHECK();
+    }
   }
   return KVC_OK;
 }
