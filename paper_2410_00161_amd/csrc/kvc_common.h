@@ -201,7 +201,13 @@ static __global__ void __launch_bounds__(1024) publish_freed_kernel(const int32_
                                                                     int64_t* __restrict__ out) {
   __shared__ long long part[1024 / 64];
   long long s = 0;
-  for (int g = threadIdx.x; g < G; g += 1024) s += max(counts[g], 0);
+  for (int g0 = threadIdx.x; g0 < G; g0 += 8 * 1024) {   // eight counts asked for at a time: one workgroup reads them all
+    int v[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) v[k] = g0 + k * 1024 < G ? counts[g0 + k * 1024] : 0;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) s += max(v[k], 0);
+  }
 #pragma unroll
   for (int o = 32; o >= 1; o >>= 1) s += __shfl_xor(s, o);
   if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = s;
@@ -308,7 +314,7 @@ static __global__ void resolve_kernel(int32_t* header, int check_oom) {
 }
 
 // Per-segment state of a selection (block mode and rank-block mode share it): eight words.
-enum SegWord { SEG_PREFIX = 0, SEG_REMAIN = 1, SEG_CAND = 2, SEG_TAKE = 3, SEG_FIRSTG = 4 };
+enum SegWord { SEG_PREFIX = 0, SEG_REMAIN = 1, SEG_CAND = 2, SEG_TAKE = 3, SEG_FIRSTG = 4, SEG_ALLTIES = 5 };
 
 // First launch of either selection: the segment of every sequence (segments are runs of
 // consecutive sequences; seg_offsets NULL = one per sequence), cleared histograms and segment

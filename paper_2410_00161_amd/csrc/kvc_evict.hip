@@ -8,10 +8,11 @@
 // are then granted in ascending (s, l, h, u).  All counting is integer, so the
 // result is the one a stable sort by (key, s, l, h, u) would give.
 #include "kvc_common.h"
+#include <atomic>
 
 namespace kvc {
 
-enum { SS_PREFIX = SEG_PREFIX, SS_REMAIN = SEG_REMAIN, SS_CAND = SEG_CAND, SS_TAKE = SEG_TAKE, SS_FIRSTG = SEG_FIRSTG };
+enum { SS_PREFIX = SEG_PREFIX, SS_REMAIN = SEG_REMAIN, SS_CAND = SEG_CAND, SS_TAKE = SEG_TAKE, SS_FIRSTG = SEG_FIRSTG, SS_ALLTIES = SEG_ALLTIES };
 
 // ---------------------------------------------------------------------------
 // block keys
@@ -196,15 +197,17 @@ __global__ void __launch_bounds__(256) select_mark_kernel(Dims D, int protect, c
   const int g = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (g >= D.G) return;
   const int lane = threadIdx.x & 63;
-  const int sg = seq_seg[g / (D.Lyr * D.Hk)];
+  const int sg = seq_seg ? seq_seg[g / (D.Lyr * D.Hk)] : g / (D.Lyr * D.Hk);   // no map: one segment per sequence
   const int32_t* stt = seg_state + sg * 8;
   const int take = stt[SS_TAKE];
   if (g == stt[SS_FIRSTG] && lane == 0) selected[sg] = take;
   if (take <= 0) return;
   const uint32_t thr = (uint32_t)stt[SS_PREFIX];
-  // ties granted to this head: those whose rank inside the segment is below SS_REMAIN
-  int ties_before = tie_off[g] - tie_off[stt[SS_FIRSTG]];
-  const int want = stt[SS_REMAIN];
+  // ties granted to this head: those whose rank inside the segment is below SS_REMAIN (a segment
+  // that takes every key at its threshold has no ranks to look up)
+  const bool all_ties = stt[SS_ALLTIES] != 0;
+  int ties_before = all_ties ? 0 : tie_off[g] - tie_off[stt[SS_FIRSTG]];
+  const int want = all_ties ? 0x7fffffff : stt[SS_REMAIN];
   const int ncand = max(0, (ctx[g] + D.b - 1) / D.b - protect);
   const float* krow = key + (size_t)g * D.maxb;
   uint8_t* frow = flag + (size_t)g * D.maxb;
@@ -222,6 +225,211 @@ __global__ void __launch_bounds__(256) select_mark_kernel(Dims D, int protect, c
     ties_before += __popcll(tm);
   }
   if (lane == 0) evict_count[g] = cnt;
+}
+
+// The whole selection of one segment in one workgroup, for segments that are single sequences
+// (the case of every decode-time round): instead of four histogram launches over all heads with a
+// pick launch after each, a tie count, a scan and the marking, the segment's workgroup walks its
+// own candidates -- head instances (s, *, *), blocks 0 .. nb - protect - 1 of each, numbered
+// j = 0, 1, ... in (g, u) order -- four times, the last three over a copy of the keys in LDS when
+// they fit (lds_keys words; else over the keys again), and leaves threshold, ties wanted and, only
+// when some but not all keys at the threshold are taken, every head's count of such keys in front
+// of it.  It also clears its share of the outputs; the marking launch fills them once the status
+// is settled.  heads_lds: per-head first candidate numbers, kept in LDS (Lyr Hk + 1 words).
+constexpr int kSegThreads = 1024;
+constexpr int kSegWaves = kSegThreads / 64;
+constexpr int kSegMaxHeads = 4096;     // head instances of a sequence whose first candidate numbers fit the LDS
+constexpr int kSegLdsKeys = 28672;     // keys of a segment kept in LDS between the passes (112 KB)
+
+__global__ void __launch_bounds__(kSegThreads) select_segment_kernel(Dims D, int protect, int lds_keys,
+                                                                      const float* __restrict__ key,
+                                                                      const int32_t* __restrict__ ctx,
+                                                                      const int32_t* __restrict__ budget,
+                                                                      uint8_t* __restrict__ flag,
+                                                                      int32_t* __restrict__ evict_count,
+                                                                      int32_t* __restrict__ selected,
+                                                                      int32_t* __restrict__ seg_state,
+                                                                      int32_t* __restrict__ tie_before,
+                                                                      int32_t* __restrict__ header) {
+  extern __shared__ __align__(16) uint32_t seg_smem[];
+  const int nh = D.Lyr * D.Hk;
+  int* s_base = (int*)seg_smem;                        // [nh + 1]
+  int* s_whist = s_base + ((nh + 1 + 3) & ~3);         // [waves][256]
+  uint32_t* s_key = (uint32_t*)(s_whist + kSegWaves * 256);   // [lds_keys]
+  __shared__ int smem[kSegThreads / 64 + 1];
+  __shared__ int hist[256];
+  __shared__ int carry_s, chosen_s, prefix_s, remain_s, clast_s, bad_s;
+  const int sg = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wid = tid >> 6;
+  const int g0 = sg * nh;
+
+  // this workgroup's share of the outputs starts from zero
+  {
+    const size_t nflag = (size_t)D.G * D.maxb;
+    const size_t per = ((nflag + gridDim.x - 1) / gridDim.x + 15) & ~(size_t)15;
+    const size_t lo = (size_t)sg * per, hi = lo + per < nflag ? lo + per : nflag;
+    if (lo < hi) {
+      size_t i = lo + (size_t)tid * 16;
+      const bool wide = ((uintptr_t)flag & 15) == 0;
+      for (; i < hi; i += (size_t)kSegThreads * 16) {
+        if (wide && i + 16 <= hi) *(uint4*)(flag + i) = make_uint4(0, 0, 0, 0);
+        else for (size_t k = i; k < hi && k < i + 16; ++k) flag[k] = 0;
+      }
+    }
+    for (int i = g0 + tid; i < g0 + nh; i += kSegThreads) evict_count[i] = 0;
+    if (tid == 0) selected[sg] = 0;
+  }
+
+  // candidates per head and their first numbers
+  if (tid == 0) { carry_s = 0; bad_s = 0; }
+  __syncthreads();
+  for (int h0 = 0; h0 < nh; h0 += kSegThreads) {
+    const int h = h0 + tid;
+    const int n = h < nh ? max(0, (ctx[g0 + h] + D.b - 1) / D.b - protect) : 0;
+    int tot;
+    const int ex = block_exclusive_scan<kSegThreads>(n, smem, &tot);
+    const int carry = carry_s;
+    if (h < nh) s_base[h] = carry + ex;
+    __syncthreads();
+    if (tid == 0) carry_s = carry + tot;
+    __syncthreads();
+  }
+  const int K = carry_s;
+  if (tid == 0) s_base[nh] = K;
+  int bud = budget[sg];
+  if (bud < 0) { if (tid == 0) atomicOr(&header[HW_SCRATCH0], EB_ARG); bud = 0; }
+  const int take = min(bud, K);
+  if (tid == 0) { prefix_s = 0; remain_s = take; clast_s = 0; }
+  __syncthreads();
+  const bool kept = K <= lds_keys;
+  // key number j -> (head, block): the last head whose first number is <= j.  The searches of the
+  // UQ keys a thread asks for at a time run side by side, a fixed number of halvings each, so that
+  // their LDS reads overlap.
+  constexpr int UQ = 8;
+  int halvings = 0;
+  while ((1 << halvings) < nh) ++halvings;
+  auto keys_from_memory = [&](int jfirst, uint32_t (&out)[UQ]) {
+    int lo[UQ], hi[UQ];
+#pragma unroll
+    for (int q = 0; q < UQ; ++q) { lo[q] = 0; hi[q] = nh; }
+    for (int step = 0; step < halvings; ++step) {
+#pragma unroll
+      for (int q = 0; q < UQ; ++q) {
+        const int mid = (lo[q] + hi[q]) >> 1;      // == lo once hi - lo <= 1: then nothing moves
+        const bool le = s_base[mid] <= jfirst + q * kSegThreads;
+        lo[q] = le ? mid : lo[q];
+        hi[q] = le ? hi[q] : mid;
+      }
+    }
+#pragma unroll
+    for (int q = 0; q < UQ; ++q) {
+      const int j = jfirst + q * kSegThreads;
+      out[q] = j < K ? key_bits(key[(size_t)(g0 + lo[q]) * D.maxb + (j - s_base[lo[q]])]) : 0u;
+    }
+  };
+
+  for (int pass = 0; pass < 4; ++pass) {
+    if (pass > 0 && take == 0) break;   // (the first pass also checks the keys, so it always runs)
+    for (int i = tid; i < kSegWaves * 256; i += kSegThreads) s_whist[i] = 0;
+    __syncthreads();
+    const int shift = 24 - 8 * pass;
+    const uint32_t prefix = (uint32_t)prefix_s;
+    int* my = s_whist + wid * 256;
+    bool bad = false;
+    for (int j0 = 0; j0 < K; j0 += UQ * kSegThreads) {
+      uint32_t kq[UQ];   // eight keys asked for before the first is used
+      if (pass == 0 || !kept) {
+        keys_from_memory(j0 + tid, kq);
+      } else {
+#pragma unroll
+        for (int q = 0; q < UQ; ++q) {
+          const int j = j0 + q * kSegThreads + tid;
+          kq[q] = j < K ? s_key[j] : 0u;
+        }
+      }
+#pragma unroll
+      for (int q = 0; q < UQ; ++q) {
+        const int j = j0 + q * kSegThreads + tid;
+        const bool in = j < K;
+        const uint32_t k = kq[q];
+        if (pass == 0) {
+          bad |= in && k >= 0x7f800000u;
+          if (in && kept) s_key[j] = k;
+        }
+        const bool counts = in && (pass == 0 || (k >> (shift + 8)) == prefix);
+        const int digit = (int)((k >> shift) & 255u);
+        // nearly all keys of a segment share their exponent byte: a wavefront whose lanes agree adds once
+        const unsigned long long m = __ballot(counts);
+        if (m) {
+          const int first = __builtin_amdgcn_readlane(digit, __builtin_ctzll(m));
+          if (__ballot(counts && digit != first) == 0ull) {
+            if (lane == 0) my[first] += __popcll(m);
+          } else if (counts) {
+            atomicAdd(&my[digit], 1);
+          }
+        }
+      }
+    }
+    if (pass == 0 && __any(bad) && lane == 0) bad_s = 1;
+    __syncthreads();
+    if (tid < 256) {
+      int c = 0;
+#pragma unroll
+      for (int w2 = 0; w2 < kSegWaves; ++w2) c += s_whist[w2 * 256 + tid];
+      hist[tid] = c;
+    }
+    __syncthreads();
+    const int c = tid < 256 ? hist[tid] : 0;
+    const int ex = block_exclusive_scan<kSegThreads>(c, smem, nullptr);
+    const int remain = remain_s;
+    if (tid == 0) chosen_s = -1;
+    __syncthreads();
+    if (take > 0 && tid < 256 && ex < remain && remain <= ex + c) chosen_s = tid;   // exactly one thread
+    __syncthreads();
+    if (take > 0 && tid == chosen_s) {
+      prefix_s = (int)((prefix << 8) | (uint32_t)tid);
+      remain_s = remain - ex;    // still wanted among keys equal on all digits so far
+      clast_s = c;               // keys equal on all digits so far
+    }
+    __syncthreads();
+  }
+  if (tid == 0 && bad_s) atomicOr(&header[HW_SCRATCH0], EB_NUMERIC);
+  const uint32_t thr = (uint32_t)prefix_s;
+  const int want = remain_s;
+  const bool all_ties = take == 0 || want == clast_s;
+  if (tid == 0) {
+    int32_t* stt = seg_state + sg * 8;
+    stt[SS_PREFIX] = (int32_t)thr;
+    stt[SS_REMAIN] = want;
+    stt[SS_CAND] = K;
+    stt[SS_TAKE] = take;
+    stt[SS_FIRSTG] = g0;
+    stt[SS_ALLTIES] = all_ties ? 1 : 0;
+    stt[6] = stt[7] = 0;
+  }
+  if (all_ties) return;
+  // some of the keys at the threshold stay: the first `want` in (g, u) order go.  Every head
+  // with candidates learns how many such keys lie in front of its first one.
+  if (tid == 0) carry_s = 0;
+  __syncthreads();
+  for (int j0 = 0; j0 < K; j0 += kSegThreads) {
+    const int j = j0 + tid;
+    uint32_t k = 0xffffffffu;
+    int h = 0;
+    if (j < K) {
+      int lo = 0, hi = nh;
+      while (hi - lo > 1) { const int mid = (lo + hi) >> 1; if (s_base[mid] <= j) lo = mid; else hi = mid; }
+      h = lo;
+      k = kept ? s_key[j] : key_bits(key[(size_t)(g0 + lo) * D.maxb + (j - s_base[lo])]);
+    }
+    const int is_tie = (j < K) && k == thr;
+    int tot;
+    const int rank = block_exclusive_scan<kSegThreads>(is_tie, smem, &tot) + carry_s;
+    if (j < K && j == s_base[h]) tie_before[g0 + h] = rank;
+    if (j0 == 0 && tid == 0 && s_base[1] == 0) tie_before[g0] = 0;   // (the marking launch subtracts the first head's count)
+    __syncthreads();
+    if (tid == 0) carry_s += tot;
+    __syncthreads();
+  }
 }
 
 // ---------------------------------------------------------------------------
@@ -525,6 +733,31 @@ int kvc_evict_select(const kvc_config* cfg, const kvc_state* st, const float* bl
   hipStream_t s = (hipStream_t)stream;
   int32_t* seq_seg = W.held;  // [S] fits in the [G] array
   const int gw = (D.G + 3) / 4;
+  // One segment per sequence, and a pool that gives the average sequence no more blocks than a
+  // workgroup keeps on chip: every segment's selection in its own workgroup, three launches in
+  // all.  (A sequence with more candidates than that is still served, its keys re-read in every
+  // pass; with sequences of 650 000 blocks each that took 3.2 ms against 0.5 for the launches
+  // over all heads below, which is why the pool size decides.)
+  const int heads_per_seq = D.Lyr * D.Hk;
+  if (!seg_offsets && heads_per_seq <= kSegMaxHeads && (size_t)D.N <= (size_t)kSegLdsKeys * D.S) {
+    const size_t lds = ((size_t)((heads_per_seq + 1 + 3) & ~3) + kSegWaves * 256 + kSegLdsKeys) * 4;
+    static std::atomic<bool> told{false};   // the runtime is told once that this kernel may take that much LDS
+    if (!told.load(std::memory_order_acquire)) {
+      KVC_HIP(hipFuncSetAttribute((const void*)select_segment_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                  (int)(((size_t)kSegMaxHeads + 4 + kSegWaves * 256 + kSegLdsKeys) * 4)));
+      told.store(true, std::memory_order_release);
+    }
+    hipLaunchKernelGGL(select_segment_kernel, dim3(D.S), dim3(kSegThreads), lds, s, D, protect_tail_blocks, kSegLdsKeys,
+                       block_key, st->ctx_len, budget, evict_flag, evict_count, selected, W.seg_state, W.off_a, W.header);
+    KVC_LAUNCH_CHECK();
+    hipLaunchKernelGGL(resolve_kernel, dim3(1), dim3(64), 0, s, W.header, 0);
+    KVC_LAUNCH_CHECK();
+    hipLaunchKernelGGL(select_mark_kernel, dim3(gw), dim3(256), 0, s, D, protect_tail_blocks, block_key,
+                       st->ctx_len, (const int32_t*)nullptr, W.seg_state, W.off_a, evict_flag, evict_count, selected,
+                       W.header);
+    KVC_LAUNCH_CHECK();
+    return (flags & KVC_ASYNC) ? KVC_OK : finish_sync(W, s);
+  }
   int n_init = D.G > nseg * 256 ? D.G : nseg * 256;
   hipLaunchKernelGGL(segments_init_kernel, dim3((n_init + 255) / 256), dim3(256), 0, s, D, seg_offsets, nseg,
                      seq_seg, W.seg_hist, W.seg_state, evict_count, selected, W.header);

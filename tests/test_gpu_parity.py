@@ -2,6 +2,8 @@
 the same seeded inputs.  Floating point within 2e-3 max-abs (outputs and
 metrics, fp32 accumulation on the GPU, fp64 in the oracle); tables, free maps,
 context lengths, block keys, selections and compacted caches bit-exact."""
+import dataclasses
+
 import numpy as np
 import pytest
 import torch
@@ -477,6 +479,62 @@ def test_select_and_compact_bit_exact(name, kw):
     out = sess.paged_decode(q.to(sess.device))
     torch.cuda.synchronize()
     np.testing.assert_allclose(out.cpu().numpy(), want, rtol=0, atol=TOL)
+
+
+SEGMENT_CASES = [
+    # one workgroup per sequence walks that sequence's candidate blocks: more of them than the
+    # copy it keeps on chip holds (blocks of one token), and keys that tie at the threshold
+    ("more_keys_than_the_on_chip_copy", dict(b=1, L=6800, protect=1, ties=True, empty=False)),
+    ("more_keys_protect0_distinct", dict(b=1, L=6800, protect=0, ties=False, empty=False)),
+    # sequences whose first head instances have no candidate at all, with ties to rank behind them
+    ("first_heads_without_candidates", dict(b=16, L=900, protect=1, ties=True, empty=True)),
+    ("first_heads_without_candidates_protect2", dict(b=4, L=300, protect=2, ties=True, empty=True)),
+]
+
+
+@pytest.mark.parametrize("name,kw", SEGMENT_CASES, ids=[c[0] for c in SEGMENT_CASES])
+def test_select_one_sequence_per_segment_edges(name, kw):
+    say("select by sequence", name)
+    shape, ctx, seed = W.small_mixed(83, S=2, Lyr=3, Hk=2, r=2, d=64, b=kw["b"], L=kw["L"], rho=1.2)
+    ctx = ctx.clone()
+    if kw["b"] == 1:
+        # the library picks this path by the pool's blocks per sequence: one long sequence next to
+        # a short one keeps that average low while the long one overflows the on-chip copy
+        ctx.reshape(2, -1)[1] //= 16
+        total = int(ctx.sum())
+        shape = dataclasses.replace(shape, num_blocks=int(1.3 * total) + 64)
+        assert shape.num_blocks <= 28672 * shape.num_seqs
+    if kw["empty"]:
+        flat = ctx.reshape(2, -1)
+        flat[0, 0] = 0                                  # no KV at all
+        flat[0, 1] = kw["b"] * kw["protect"]            # only protected blocks
+        flat[1, 0] = 1
+        flat[1, 2] = 0
+    cache = W.make_cache(shape, ctx, seed, placement="fragmented", init_metric="prefill")
+    if kw["ties"]:
+        g = torch.Generator().manual_seed(11)
+        cache.metric = torch.randint(0, 2, cache.metric.shape, generator=g).float()
+    st = oracle_state(cache)
+    sess = session(cache)
+    key = sess.metric_reduce()
+    want_key, _ = O.block_keys(st, cache.metric.numpy())
+    nb = -(-st.lens() // st.b)
+    cand = np.maximum(nb - kw["protect"], 0).reshape(st.S, -1).sum(1)
+    if kw["b"] == 1:
+        assert cand[0] > 28672, "the case is about a sequence with more candidates than are kept on chip"
+    for frac in (0.37, 0.9):
+        budget = torch.tensor([int(frac * c) for c in cand], dtype=torch.int32)
+        flag_w, count_w, sel_w = O.evict_select(st, want_key, budget.numpy(), None, kw["protect"])
+        flag, count, sel = sess.evict_select(budget, None, kw["protect"])
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(sel.cpu().numpy(), sel_w)
+        np.testing.assert_array_equal(count.cpu().numpy(), count_w)
+        np.testing.assert_array_equal(flag.cpu().numpy(), flag_w)
+    freed_w = O.compact(st, flag_w, count_w)
+    freed = sess.compact()
+    torch.cuda.synchronize()
+    assert int(freed.item()) == freed_w == int(sel_w.sum())
+    assert_state_equal(sess, st)
 
 
 @pytest.mark.parametrize("kv_dtype,b", [("bf16", 16), ("fp8", 64), ("f32", 4)])
