@@ -178,16 +178,16 @@ constexpr int kDecodeThreads = 256;
 constexpr int kDecodeWaves = kDecodeThreads / 64;
 
 // A shape takes Q K^T to the matrix cores where the plain ALUs are the bound: 16-bit or 8-bit
-// rows (the latter widened to bf16 on their way into the operand tile), eight query heads per KV
-// head, d = 128, blocks of a multiple of 16 tokens.
+// rows (the latter widened to bf16 on their way into the operand tile) with eight query heads per
+// KV head, 8-bit rows with four (half the bytes per logit: with the dot products on the plain ALUs
+// that launch ran 8 % longer), d = 128, blocks of a multiple of 16 tokens.
 __host__ __device__ constexpr bool decode_uses_mfma(int esz, int R, int HD, int b) {
-  return esz <= 2 && R == 8 && HD == 128 && b % 16 == 0;
+  return esz <= 2 && (R == 8 || (R == 4 && esz == 1)) && HD == 128 && b % 16 == 0;
 }
 
-// P V alone goes to the matrix cores for 8-bit rows under four query heads: there the plain ALUs
-// are the bound, and the FMAs of P V are the largest part of their work.
+// P V goes to the matrix cores wherever Q K^T does.
 __host__ __device__ constexpr bool decode_pv_mfma(int esz, int R, int HD, int b) {
-  return decode_uses_mfma(esz, R, HD, b) || (esz == 1 && R == 4 && HD == 128 && b % 16 == 0);
+  return decode_uses_mfma(esz, R, HD, b);
 }
 
 // Register buffers of K and V groups a wavefront rotates through (one less is in flight behind
