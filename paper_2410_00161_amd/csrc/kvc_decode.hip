@@ -324,7 +324,7 @@ __global__ void __launch_bounds__(NW * 64) decode_chunk_kernel(DecodeArgs A) {
 
   // One 16-token group = U wavefront loads of 64 pieces each (1 KiB; 512 bytes for 8-bit
   // rows).  With b a multiple of 16 a group lies in one block, so one table lookup serves it
-  // and the slots past the end of the head (still inside the block) are read and masked later.
+  // and the slots past the end of the head (still inside the block) are masked later, read or not.
   // Otherwise every load looks its block up and tokens past the end re-read the last token.
   const int last = n_tok - 1;
   auto load_group = [&](const char* __restrict__ basep, int grp, Piece (&buf)[U]) {
@@ -333,7 +333,13 @@ __global__ void __launch_bounds__(NW * 64) decode_chunk_kernel(DecodeArgs A) {
       const size_t slot = ((size_t)s_tab[tk >> lb] << lb) + (tk & (b - 1));
       const char* p = basep + slot * ROWB + (size_t)lane * PB;
 #pragma unroll
-      for (int u = 0; u < U; ++u) buf[u] = Row<ESZ>::load(p + (size_t)u * (64 * PB));
+      for (int u = 0; u < U; ++u) {
+        // A short item's last block is half empty on average, 7 % of what the item reads: the
+        // one-wavefront launch leaves the slots past the head's end unread.  (In the long items'
+        // loop the test costs more than the few rows it saves.)
+        if (NW == 1 && tk + u * TPI + sub >= n_tok) buf[u] = Row<ESZ>::zero();
+        else buf[u] = Row<ESZ>::load(p + (size_t)u * (64 * PB));
+      }
     } else {
 #pragma unroll
       for (int u = 0; u < U; ++u) {
