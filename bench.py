@@ -515,6 +515,33 @@ def stream_read_probe(sess, dev):
     return best
 
 
+def stream_read_add_probe(sess, dev):
+    """A read stream shaped like the decode's (a workgroup reads 3 MiB at a stretch), alone and with the
+    decode's share of writes (one float added per 512 bytes read, the metric of 16-bit rows of
+    d = 128): what this GPU's memory system gives to that pattern and to that mix.  GB/s of bytes read."""
+    import torch
+    from paper_2410_00161_amd import binding as B
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    item = 3 << 20
+    nbytes = sess.cache.k_cache.numel() * sess.cache.k_cache.element_size()
+    n_items = nbytes // item
+    if n_items < 1024:
+        return None, None
+    dst = torch.zeros(n_items * 6144, dtype=torch.float32, device=dev)
+    sink = torch.zeros(65536, dtype=torch.int32, device=dev)
+    best = {0: 0.0, 6144: 0.0}
+    for adds in best:
+        for wgs in (512, 1024):
+            for _ in range(3):
+                a, b_ = ev(), ev()
+                a.record()
+                B.kvc_stream_read_add_probe(sess.cache.k_cache, nbytes, adds, dst, sink, wgs)
+                b_.record()
+                torch.cuda.synchronize()
+                best[adds] = max(best[adds], n_items * item / (a.elapsed_time(b_) * 1e-3) / 1e9)
+    return best[0], best[6144]
+
+
 def prefill_end_probe(dev, all_queries_block):
     """Prefill-end compression, Mistral-7B shape: one 16384-token prompt, the metric from the last
     32 prompt queries on the matrix cores, the metric over all prompt queries, a rank-block
@@ -707,6 +734,14 @@ def main():
                     "unit": "GB/s", "frac": rec["value"] / HBM_PEAK_GBS, "traffic": None}
     roofline["measured_stream_read_GBps"] = best
     roofline["frac_of_measured_stream_read"] = roofline["achieved"] / best
+    plain, mixed = stream_read_add_probe(sess, dev)
+    if mixed:
+        # a read stream in stretches of 3 MiB per workgroup, alone and adding one float per 512 bytes
+        # read as the metric does: the rates this chip gives to the decode's pattern and to its mix
+        roofline["measured_stream_read_GBps"] = max(best, plain)
+        roofline["frac_of_measured_stream_read"] = roofline["achieved"] / max(best, plain)
+        roofline["measured_stream_read_with_metric_adds_GBps"] = mixed
+        roofline["frac_of_measured_stream_read_with_metric_adds"] = roofline["achieved"] / mixed
 
     if args.calibrate_copy:
         src = torch.empty(1 << 28, dtype=torch.float32, device=dev).fill_(1.0)

@@ -28,6 +28,7 @@ EXPORTS = [
     "kvc_metric_reduce", "kvc_evict_select", "kvc_compact", "kvc_set_decode_chunk",
     "kvc_get_decode_chunk", "kvc_get_decode_short", "kvc_evict_rank_select", "kvc_compact_rank", "kvc_window_metric", "kvc_query_block_metric", "kvc_count_blocks", "kvc_prefill_alloc", "kvc_preempt", "kvc_compression_batch",
     "kvc_profile_begin", "kvc_profile_enable", "kvc_profile_collect", "kvc_stream_read_probe",
+    "kvc_stream_read_add_probe",
 ]
 
 
@@ -93,6 +94,7 @@ def lib() -> C.CDLL:
         L.kvc_profile_begin.argtypes = [I]
         L.kvc_profile_enable.argtypes = [I]
         L.kvc_stream_read_probe.argtypes = [P, C.c_size_t, P, I, P]
+        L.kvc_stream_read_add_probe.argtypes = [P, C.c_size_t, I, P, C.c_size_t, P, I, P]
         L.kvc_profile_collect.argtypes = [P, P, P, I, C.POINTER(C.c_int)]
         for n in EXPORTS:
             if n not in ("kvc_workspace_bytes", "kvc_status_string"):
@@ -262,6 +264,12 @@ def kvc_profile_collect(cap: int = 4096):
     _check(lib().kvc_profile_collect(a, sh, b, cap, C.byref(n)), "kvc_profile_collect")
     k = min(n.value, cap)
     return list(a[:k]), list(sh[:k]), list(b[:k])
+
+
+def kvc_stream_read_add_probe(src, nbytes, adds_per_item, dst, sink, workgroups, stream=None):
+    _check(lib().kvc_stream_read_add_probe(_ptr(src), int(nbytes), int(adds_per_item), _ptr(dst, torch.float32), int(dst.numel()),
+                                           _ptr(sink, torch.int32), int(workgroups), _stream(stream)),
+           "kvc_stream_read_add_probe")
 
 
 def kvc_stream_read_probe(src, nbytes, sink, workgroups, stream=None):

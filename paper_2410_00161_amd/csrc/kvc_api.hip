@@ -49,6 +49,30 @@ __global__ void __launch_bounds__(256) stream_read_kernel(const uint4* __restric
   if ((threadIdx.x & 63) == 0) atomicXor(&sink[blockIdx.x], acc);
 }
 
+// The same read stream with the decode's share of writes: a workgroup reads items of 3 MiB (what
+// a 6144-token chunk of 16-bit rows, d = 128, holds in K and V) and after each item adds one float
+// per 512 bytes read (or fewer: `adds` per item) to `dst`, with the hardware add the decode uses for
+// the metric.
+constexpr size_t kProbeItem16 = ((size_t)3 << 20) / 16;   // 16-byte pieces per item
+constexpr int kProbeAdds = 6144;                          // floats added per item
+
+__global__ void __launch_bounds__(256) stream_read_add_kernel(const uint4* __restrict__ src, int n_items, int adds,
+                                                              float* __restrict__ dst, uint32_t* __restrict__ sink) {
+  uint32_t acc = 0;
+  for (int item = blockIdx.x; item < n_items; item += gridDim.x) {
+    const uint4* p = src + (size_t)item * kProbeItem16;
+    for (size_t i = threadIdx.x; i + 3 * 256 < kProbeItem16; i += 4 * 256) {
+      const uint4 a = load_stream16(p + i), b = load_stream16(p + i + 256);
+      const uint4 c = load_stream16(p + i + 512), d = load_stream16(p + i + 768);
+      acc ^= a.x ^ a.y ^ a.z ^ a.w ^ b.x ^ b.y ^ b.z ^ b.w ^ c.x ^ c.y ^ c.z ^ c.w ^ d.x ^ d.y ^ d.z ^ d.w;
+    }
+    float* m = dst + (size_t)item * kProbeAdds;
+    for (int k = threadIdx.x; k < adds; k += 256) unsafeAtomicAdd(&m[k], 1.0f);
+  }
+  for (int m = 32; m >= 1; m >>= 1) acc ^= __shfl_xor(acc, m);
+  if ((threadIdx.x & 63) == 0) atomicXor(&sink[blockIdx.x], acc);
+}
+
 }  // namespace kvc
 
 using namespace kvc;
@@ -92,6 +116,18 @@ int kvc_stream_read_probe(const void* src, size_t bytes, uint32_t* sink, int wor
   if (!src || !sink || workgroups <= 0 || (bytes & 15) || ((uintptr_t)src & 15)) return KVC_ERR_ARG;
   hipLaunchKernelGGL(stream_read_kernel, dim3(workgroups), dim3(256), 0, (hipStream_t)stream,
                      (const uint4*)src, bytes / 16, sink);
+  KVC_LAUNCH_CHECK();
+  return KVC_OK;
+}
+
+int kvc_stream_read_add_probe(const void* src, size_t bytes, int adds_per_item, float* dst, size_t dst_floats,
+                              uint32_t* sink, int workgroups, void* stream) {
+  if (!src || !dst || !sink || workgroups <= 0 || ((uintptr_t)src & 15) || ((uintptr_t)dst & 3)) return KVC_ERR_ARG;
+  if (adds_per_item < 0 || adds_per_item > kProbeAdds) return KVC_ERR_ARG;
+  const size_t n_items = bytes / (kProbeItem16 * 16);
+  if (n_items == 0 || n_items > 0x7fffffffull || dst_floats < n_items * kProbeAdds) return KVC_ERR_ARG;
+  hipLaunchKernelGGL(stream_read_add_kernel, dim3(workgroups), dim3(256), 0, (hipStream_t)stream,
+                     (const uint4*)src, (int)n_items, adds_per_item, dst, sink);
   KVC_LAUNCH_CHECK();
   return KVC_OK;
 }
