@@ -428,7 +428,8 @@ def run_decode_config(spec, dev, keep_session=False):
            "eviction": evict, "roofline": roofline}
     if check:
         rec.update(check)
-    extras = {"shape": shape, "seed": seed, "qs": qs, "n_in": n_in, "no_metric": no_metric}
+    extras = {"shape": shape, "seed": seed, "qs": qs, "n_in": n_in, "no_metric": no_metric,
+              "kvs_new": kvs_new, "budget": budget, "evict_every": evict_every}
     if keep_session:
         return rec, sess, extras
     del sess, qs, kvs_new
@@ -493,6 +494,53 @@ def per_layer_probe(sess, extras, steps):
         pass
     assert B.kvc_poll_status(sess.cfg, sess.ws) == B.KVC_OK
     return res
+
+
+def eviction_graph_probe(sess, extras, rounds=3):
+    """A physical-block compression round (block keys, selection, compaction, all asynchronous)
+    captured once into a HIP graph and replayed after every evict_every decode steps: what a
+    serving loop that keeps the round as a graph pays for it.  ms per round, mean over `rounds`."""
+    import torch
+    from paper_2410_00161_amd import binding as B
+    qs, kvs_new, n_in = extras["qs"], extras["kvs_new"], extras["n_in"]
+    budget, every = extras["budget"], max(1, extras["evict_every"])
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+
+    def round_():
+        sess.metric_reduce()
+        sess.evict_select(budget, flags=B.KVC_ASYNC)
+        sess.compact(flags=B.KVC_ASYNC)
+
+    def steps(first):
+        for i in range(first, first + every):
+            k, v = kvs_new[i % n_in]
+            sess.append(k, v, flags=B.KVC_ASYNC)
+            sess.paged_decode(qs[i % n_in])
+
+    steps(0)
+    round_()                                  # eager once
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    steps(every)
+    torch.cuda.synchronize()
+    with torch.cuda.graph(graph, stream=side):
+        round_()
+    torch.cuda.synchronize()
+    total = 0.0
+    for r in range(rounds):
+        steps((r + 2) * every)
+        a, b_ = ev(), ev()
+        torch.cuda.synchronize()
+        a.record()
+        graph.replay()
+        b_.record()
+        torch.cuda.synchronize()
+        total += a.elapsed_time(b_)
+    del graph
+    assert B.kvc_poll_status(sess.cfg, sess.ws) == B.KVC_OK
+    return total / rounds
 
 
 def stream_read_probe(sess, dev):
@@ -759,6 +807,11 @@ def main():
     if args.cpu_heads > 0:
         cpu = cpu_baseline(sess, extras["qs"][0], shape, args.cpu_heads, seed)
 
+    round_graph_ms = None
+    if (args.evict_mode == "block" and args.evict_every > 0 and args.evict_frac == 0 and not args.no_metric
+            and args.per_layer_steps > 0):   # (a probe like the per-layer one: left out together with it)
+        round_graph_ms = eviction_graph_probe(sess, extras)
+
     check = None
     if args.check_heads > 0:
         check = parity_sample(sess, shape, extras["qs"][0], seed, args.check_heads, args.evict_mode)
@@ -804,7 +857,7 @@ def main():
         "decode_only_ms_per_step_one_call_per_layer_kept_lists": per_layer["planned"],
         "decode_only_ms_per_step_one_call_per_layer_kept_lists_hip_graph": per_layer["planned_graph"],
         "wall_s": rec["wall_s"],
-        "eviction": rec["eviction"],
+        "eviction": dict(rec["eviction"] or {}, round_from_hip_graph_ms=round_graph_ms) if rec["eviction"] else rec["eviction"],
         "parity_sample": check["parity_sample"] if check else None,
         "parity_sample_detail": check,
         "prefill_end": prefill_end,

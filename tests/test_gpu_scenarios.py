@@ -274,6 +274,70 @@ def test_append_and_decode_replay_from_a_hip_graph():
     assert_state_equal(sess, st)
 
 
+def test_compression_round_replays_from_a_hip_graph():
+    """A compression round (block keys, selection, compaction) issued with KVC_ASYNC holds no host
+    synchronisation either: captured once, replayed after further decode steps, every replay checked
+    against the oracle's round on the same metrics."""
+    say("graph capture of a compression round")
+    shape, ctx, seed = W.small_mixed(131, S=3, Lyr=2, Hk=2, r=4, d=128, L=1500, rho=2.0, extra_blocks=6)
+    cache = W.make_cache(shape, ctx, seed, placement="fragmented", init_metric="prefill")
+    st = oracle_state(cache)
+    sess = session(cache)
+    budget = torch.tensor([5, 0, 9], dtype=torch.int32)
+    budget_dev = budget.to(sess.device)
+
+    def decode_steps(first, n):
+        for i in range(first, first + n):
+            k, v = W.make_new_kv(shape, seed, i)
+            q = W.make_query(shape, seed, i)
+            O.append(st, k.double().numpy(), v.double().numpy())
+            want = O.paged_decode(st, q.double().numpy())
+            sess.append(k.to(sess.device), v.to(sess.device))
+            out = sess.paged_decode(q.to(sess.device))
+            torch.cuda.synchronize()
+            np.testing.assert_allclose(out.cpu().numpy(), want, rtol=0, atol=TOL)
+
+    def oracle_round():
+        torch.cuda.synchronize()
+        st.metric = sess.cache.metric.cpu().numpy().astype(np.float64)   # identical metric inputs
+        want_key, _ = O.block_keys(st)
+        flag_w, count_w, sel_w = O.evict_select(st, want_key, budget.numpy())
+        return flag_w, count_w, sel_w, O.compact(st, flag_w, count_w)
+
+    def device_round():
+        sess.metric_reduce()
+        _, _, sel = sess.evict_select(budget_dev, flags=B.KVC_ASYNC)
+        return sel, sess.compact(flags=B.KVC_ASYNC)
+
+    decode_steps(0, 2)
+    flag_w, count_w, sel_w, freed_w = oracle_round()
+    sel, freed = device_round()          # eager once: whatever a first call sets up happens outside the capture
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(sel.cpu().numpy(), sel_w)
+    assert int(freed.item()) == freed_w
+    assert_state_equal(sess, st)
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.graph(graph, stream=side):
+        sel, freed = device_round()
+    torch.cuda.synchronize()
+    for rep in range(3):
+        decode_steps(2 + 3 * rep, 3)
+        flag_w, count_w, sel_w, freed_w = oracle_round()
+        graph.replay()
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(sess.evict_flag.cpu().numpy(), flag_w)
+        np.testing.assert_array_equal(sess.evict_count.cpu().numpy(), count_w)
+        np.testing.assert_array_equal(sel.cpu().numpy(), sel_w)
+        assert int(freed.item()) == freed_w == int(sel_w.sum())
+        assert_state_equal(sess, st)
+        scratch = torch.randn(1 << 16, device=sess.device).sum().item()   # eager work in between
+        assert np.isfinite(scratch)
+    assert B.kvc_poll_status(sess.cfg, sess.ws) == B.KVC_OK
+    check_allocator_invariants(st)
+
+
 def test_snapshot_of_the_six_buffers_resumes_bit_for_bit():
     """The whole state of a cache is its plain buffers (keys, values, metrics, logical indices,
     tables, lengths, free map); the workspace holds nothing between calls.  A copy of them taken in
