@@ -192,14 +192,32 @@ __device__ __forceinline__ int block_exclusive_scan(int v, int* smem, int* total
   return base + inc - v;
 }
 
+// Error bits a kernel leaves in the header's scratch word for the launch that settles the status.
+enum ErrBit { EB_ARG = 1, EB_TABLE = 2, EB_NUMERIC = 4 };
+
 // Blocks a compaction freed = the sum of the per-head counts it was given (each head gives back
 // exactly the blocks it loses), or 0 when the call failed.  One workgroup adds the counts up:
 // a counter bumped by every head would see thousands of adds to one word, which the chip runs
 // one after the other (that counter alone took 0.13 ms per round at 16 384 heads).
-static __global__ void __launch_bounds__(1024) publish_freed_kernel(const int32_t* __restrict__ header,
+// With `resolve` set the launch also does what resolve_kernel(header, 0) does, first: a compaction
+// that reports its count settles its status and publishes in one launch, ahead of the moves.
+static __global__ void __launch_bounds__(1024) publish_freed_kernel(int32_t* __restrict__ header,
                                                                     const int32_t* __restrict__ counts, int G,
-                                                                    int64_t* __restrict__ out) {
+                                                                    int64_t* __restrict__ out, int resolve) {
   __shared__ long long part[1024 / 64];
+  __shared__ int status_s;
+  if (threadIdx.x == 0) {
+    if (resolve) {
+      const int bits = header[HW_SCRATCH0];
+      int st = KVC_OK;
+      if (bits & EB_ARG) st = KVC_ERR_ARG;
+      else if (bits & EB_TABLE) st = KVC_ERR_TABLE_FULL;
+      else if (bits & EB_NUMERIC) st = KVC_ERR_NUMERIC;
+      if (st != KVC_OK && header[HW_STATUS] == KVC_OK) header[HW_STATUS] = st;
+      header[HW_SCRATCH0] = 0;
+    }
+    status_s = header[HW_STATUS];
+  }
   long long s = 0;
   // One workgroup reads all the counts: 32 of them per thread asked for at a time (eight 16-byte
   // loads) when the array is 16-byte aligned, else eight.
@@ -230,7 +248,7 @@ static __global__ void __launch_bounds__(1024) publish_freed_kernel(const int32_
   if (threadIdx.x == 0) {
     long long t = 0;
     for (int w = 0; w < 1024 / 64; ++w) t += part[w];
-    out[0] = header[HW_STATUS] == KVC_OK ? t : 0;
+    out[0] = status_s == KVC_OK ? t : 0;
   }
 }
 
@@ -307,7 +325,6 @@ inline int device_exclusive_scan(F f, int n, int32_t* tile_sums, int32_t* out, i
 }
 
 // ---- status word plumbing shared by the entry points ------------------------
-enum ErrBit { EB_ARG = 1, EB_TABLE = 2, EB_NUMERIC = 4 };
 
 static __global__ void zero_words_kernel(int32_t* p, int n) {
   int i = blockIdx.x * blockDim.x + threadIdx.x;

@@ -803,7 +803,10 @@ int kvc_compact(const kvc_config* cfg, const kvc_state* st, const uint8_t* evict
   hipLaunchKernelGGL(compact_scan_kernel, dim3((D.G + 3) / 4), dim3(256), 0, s, D, evict_flag, evict_count,
                      st->ctx_len, W.flag_scan, W.header);
   KVC_LAUNCH_CHECK();
-  hipLaunchKernelGGL(resolve_kernel, dim3(1), dim3(64), 0, s, W.header, 0);
+  // the status is settled before anything moves; a caller that wants the count gets it from the
+  // same launch (the counts are this call's input, the moves do not change them)
+  if (blocks_freed) hipLaunchKernelGGL(publish_freed_kernel, dim3(1), dim3(1024), 0, s, W.header, evict_count, D.G, blocks_freed, 1);
+  else hipLaunchKernelGGL(resolve_kernel, dim3(1), dim3(64), 0, s, W.header, 0);
   KVC_LAUNCH_CHECK();
   const size_t stage_bytes = (size_t)D.maxb * 8;   // prefix counts and block ids of one head
   char* kcp = (char*)st->k_cache;
@@ -829,10 +832,6 @@ int kvc_compact(const kvc_config* cfg, const kvc_state* st, const uint8_t* evict
                        st->block_table, st->ctx_len, st->free_map, evict_count, W.flag_scan, W.header);
   }
   KVC_LAUNCH_CHECK();
-  if (blocks_freed) {
-    hipLaunchKernelGGL(publish_freed_kernel, dim3(1), dim3(1024), 0, s, W.header, evict_count, D.G, blocks_freed);
-    KVC_LAUNCH_CHECK();
-  }
   return (flags & KVC_ASYNC) ? KVC_OK : finish_sync(W, s);
 }
 

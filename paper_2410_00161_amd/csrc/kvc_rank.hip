@@ -425,7 +425,10 @@ int kvc_compact_rank(const kvc_config* cfg, const kvc_state* st, const int32_t* 
   hipLaunchKernelGGL(rank_check_kernel, dim3((D.G + 255) / 256), dim3(256), 0, s, D, st->ctx_len, evict_rows,
                      W.header);
   KVC_LAUNCH_CHECK();
-  hipLaunchKernelGGL(resolve_kernel, dim3(1), dim3(64), 0, s, W.header, 0);
+  // the status is settled before anything moves; a caller that wants the count gets it from the
+  // same launch (the counts are this call's input, the moves do not change them)
+  if (blocks_freed) hipLaunchKernelGGL(publish_freed_kernel, dim3(1), dim3(1024), 0, s, W.header, evict_rows, D.G, blocks_freed, 1);
+  else hipLaunchKernelGGL(resolve_kernel, dim3(1), dim3(64), 0, s, W.header, 0);
   KVC_LAUNCH_CHECK();
   if (D.G <= 1024) {
     // few, possibly long heads: a workgroup of 1024 threads per head, the head's metrics kept in
@@ -448,10 +451,6 @@ int kvc_compact_rank(const kvc_config* cfg, const kvc_state* st, const int32_t* 
                        (int32_t*)W.stash, W.header, 0);
   }
   KVC_LAUNCH_CHECK();
-  if (blocks_freed) {
-    hipLaunchKernelGGL(publish_freed_kernel, dim3(1), dim3(1024), 0, s, W.header, evict_rows, D.G, blocks_freed);
-    KVC_LAUNCH_CHECK();
-  }
   return (flags & KVC_ASYNC) ? KVC_OK : finish_sync(W, s);
 }
 
