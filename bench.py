@@ -564,30 +564,31 @@ def stream_read_probe(sess, dev):
 
 
 def stream_read_add_probe(sess, dev):
-    """A read stream shaped like the decode's (a workgroup reads 3 MiB at a stretch), alone and with the
-    decode's share of writes (one float added per 512 bytes read, the metric of 16-bit rows of
-    d = 128): what this GPU's memory system gives to that pattern and to that mix.  GB/s of bytes read."""
+    """A read stream shaped like the decode's (a workgroup reads an item at a stretch), alone and with
+    the decode's share of writes (one float added per 512 bytes read, the metric of 16-bit rows of
+    d = 128): what this GPU's memory system gives to that pattern and to that mix, the best over a
+    few item lengths and grid sizes.  GB/s of bytes read."""
     import torch
     from paper_2410_00161_amd import binding as B
     ev = lambda: torch.cuda.Event(enable_timing=True)
-    item = 3 << 20
     nbytes = sess.cache.k_cache.numel() * sess.cache.k_cache.element_size()
-    n_items = nbytes // item
-    if n_items < 1024:
+    if nbytes < (1 << 31):
         return None, None
-    dst = torch.zeros(n_items * 6144, dtype=torch.float32, device=dev)
+    dst = torch.zeros(nbytes // 512, dtype=torch.float32, device=dev)
     sink = torch.zeros(65536, dtype=torch.int32, device=dev)
-    best = {0: 0.0, 6144: 0.0}
+    best = {0: 0.0, 1: 0.0}
     for adds in best:
-        for wgs in (512, 1024):
-            for _ in range(3):
-                a, b_ = ev(), ev()
-                a.record()
-                B.kvc_stream_read_add_probe(sess.cache.k_cache, nbytes, adds, dst, sink, wgs)
-                b_.record()
-                torch.cuda.synchronize()
-                best[adds] = max(best[adds], n_items * item / (a.elapsed_time(b_) * 1e-3) / 1e9)
-    return best[0], best[6144]
+        for item in (1 << 20, 3 << 19, 3 << 20):      # 1, 1.5 (a 6144-token chunk's K rows, or its V rows) and 3 MiB
+            n_items = nbytes // item
+            for wgs in (512, 1024):
+                for _ in range(2):
+                    a, b_ = ev(), ev()
+                    a.record()
+                    B.kvc_stream_read_add_probe(sess.cache.k_cache, nbytes, item, adds, dst, sink, wgs)
+                    b_.record()
+                    torch.cuda.synchronize()
+                    best[adds] = max(best[adds], n_items * item / (a.elapsed_time(b_) * 1e-3) / 1e9)
+    return best[0], best[1]
 
 
 def prefill_end_probe(dev, all_queries_block):

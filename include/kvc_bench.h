@@ -38,16 +38,15 @@ int kvc_profile_collect(float* chunk_ms, float* short_ms, float* combine_ms, int
 int kvc_stream_read_probe(const void* src, size_t bytes, uint32_t* sink, int workgroups,
                           void* stream);
 
-/* A read stream shaped like the decode's, with its share of writes: `bytes` of device memory at
- * `src` (16-byte aligned) are read in items of 3 MiB, one workgroup per item at a time, and after
- * each item the first adds_per_item (0 .. 6144) of the item's 6144 floats in `dst` (device; at
- * least (bytes / 3 MiB) * 6144 floats, else KVC_ERR_ARG) get 1.0 added with the hardware float
- * add.  6144 is one float per 512 bytes read, what the metric of 16-bit rows of d = 128 asks for;
- * 0 gives the plain read rate of this access pattern.  What is left of `bytes` after the last
- * whole item is not read.  One 32-bit checksum per workgroup goes to `sink` (device, at least
- * `workgroups` words).                                                                  */
-int kvc_stream_read_add_probe(const void* src, size_t bytes, int adds_per_item, float* dst, size_t dst_floats,
-                              uint32_t* sink, int workgroups, void* stream);
+/* A read stream shaped like the decode's, with its share of writes if asked for: `bytes` of device
+ * memory at `src` (16-byte aligned) are read in items of item_bytes (a multiple of 512, at least
+ * 4096), one workgroup per item at a time, and with adds != 0 every item is followed by one
+ * hardware float add per 512 bytes read, into dst[item * (item_bytes / 512) ...] (device; at least
+ * (bytes / item_bytes) * (item_bytes / 512) floats, else KVC_ERR_ARG): what the metric of 16-bit
+ * rows of d = 128 asks for.  What is left of `bytes` after the last whole item is not read.  One
+ * 32-bit checksum per workgroup goes to `sink` (device, at least `workgroups` words).    */
+int kvc_stream_read_add_probe(const void* src, size_t bytes, size_t item_bytes, int adds, float* dst,
+                              size_t dst_floats, uint32_t* sink, int workgroups, void* stream);
 
 #ifdef __cplusplus
 }

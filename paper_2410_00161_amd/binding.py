@@ -94,7 +94,7 @@ def lib() -> C.CDLL:
         L.kvc_profile_begin.argtypes = [I]
         L.kvc_profile_enable.argtypes = [I]
         L.kvc_stream_read_probe.argtypes = [P, C.c_size_t, P, I, P]
-        L.kvc_stream_read_add_probe.argtypes = [P, C.c_size_t, I, P, C.c_size_t, P, I, P]
+        L.kvc_stream_read_add_probe.argtypes = [P, C.c_size_t, C.c_size_t, I, P, C.c_size_t, P, I, P]
         L.kvc_profile_collect.argtypes = [P, P, P, I, C.POINTER(C.c_int)]
         for n in EXPORTS:
             if n not in ("kvc_workspace_bytes", "kvc_status_string"):
@@ -266,8 +266,8 @@ def kvc_profile_collect(cap: int = 4096):
     return list(a[:k]), list(sh[:k]), list(b[:k])
 
 
-def kvc_stream_read_add_probe(src, nbytes, adds_per_item, dst, sink, workgroups, stream=None):
-    _check(lib().kvc_stream_read_add_probe(_ptr(src), int(nbytes), int(adds_per_item), _ptr(dst, torch.float32), int(dst.numel()),
+def kvc_stream_read_add_probe(src, nbytes, item_bytes, adds, dst, sink, workgroups, stream=None):
+    _check(lib().kvc_stream_read_add_probe(_ptr(src), int(nbytes), int(item_bytes), int(bool(adds)), _ptr(dst, torch.float32), int(dst.numel()),
                                            _ptr(sink, torch.int32), int(workgroups), _stream(stream)),
            "kvc_stream_read_add_probe")
 

@@ -49,25 +49,29 @@ __global__ void __launch_bounds__(256) stream_read_kernel(const uint4* __restric
   if ((threadIdx.x & 63) == 0) atomicXor(&sink[blockIdx.x], acc);
 }
 
-// The same read stream with the decode's share of writes: a workgroup reads items of 3 MiB (what
-// a 6144-token chunk of 16-bit rows, d = 128, holds in K and V) and after each item adds one float
-// per 512 bytes read (or fewer: `adds` per item) to `dst`, with the hardware add the decode uses for
-// the metric.
-constexpr size_t kProbeItem16 = ((size_t)3 << 20) / 16;   // 16-byte pieces per item
-constexpr int kProbeAdds = 6144;                          // floats added per item
-
-__global__ void __launch_bounds__(256) stream_read_add_kernel(const uint4* __restrict__ src, int n_items, int adds,
-                                                              float* __restrict__ dst, uint32_t* __restrict__ sink) {
+// A read stream shaped like the decode's, with the decode's share of writes if asked for: a
+// workgroup reads items of `item16` 16-byte pieces at a stretch (what a chunk's workgroup does with
+// a chunk's K and V rows) and after each item adds one float per 512 bytes read to `dst`, with the
+// hardware add the decode uses for the metric (`adds`; 512 bytes are the K and V rows of one KV of
+// 16-bit elements, d = 128).
+__global__ void __launch_bounds__(256) stream_read_add_kernel(const uint4* __restrict__ src, size_t item16, int n_items,
+                                                              int adds, float* __restrict__ dst,
+                                                              uint32_t* __restrict__ sink) {
   uint32_t acc = 0;
+  const int per_item = (int)(item16 / 32);   // floats added per item
   for (int item = blockIdx.x; item < n_items; item += gridDim.x) {
-    const uint4* p = src + (size_t)item * kProbeItem16;
-    for (size_t i = threadIdx.x; i + 3 * 256 < kProbeItem16; i += 4 * 256) {
+    const uint4* p = src + (size_t)item * item16;
+    size_t i = threadIdx.x;
+    for (; i + 3 * 256 < item16; i += 4 * 256) {
       const uint4 a = load_stream16(p + i), b = load_stream16(p + i + 256);
       const uint4 c = load_stream16(p + i + 512), d = load_stream16(p + i + 768);
       acc ^= a.x ^ a.y ^ a.z ^ a.w ^ b.x ^ b.y ^ b.z ^ b.w ^ c.x ^ c.y ^ c.z ^ c.w ^ d.x ^ d.y ^ d.z ^ d.w;
     }
-    float* m = dst + (size_t)item * kProbeAdds;
-    for (int k = threadIdx.x; k < adds; k += 256) unsafeAtomicAdd(&m[k], 1.0f);
+    for (; i < item16; i += 256) { const uint4 a = load_stream16(p + i); acc ^= a.x ^ a.y ^ a.z ^ a.w; }
+    if (adds) {
+      float* m = dst + (size_t)item * per_item;
+      for (int k = threadIdx.x; k < per_item; k += 256) unsafeAtomicAdd(&m[k], 1.0f);
+    }
   }
   for (int m = 32; m >= 1; m >>= 1) acc ^= __shfl_xor(acc, m);
   if ((threadIdx.x & 63) == 0) atomicXor(&sink[blockIdx.x], acc);
@@ -120,14 +124,14 @@ int kvc_stream_read_probe(const void* src, size_t bytes, uint32_t* sink, int wor
   return KVC_OK;
 }
 
-int kvc_stream_read_add_probe(const void* src, size_t bytes, int adds_per_item, float* dst, size_t dst_floats,
-                              uint32_t* sink, int workgroups, void* stream) {
+int kvc_stream_read_add_probe(const void* src, size_t bytes, size_t item_bytes, int adds, float* dst,
+                              size_t dst_floats, uint32_t* sink, int workgroups, void* stream) {
   if (!src || !dst || !sink || workgroups <= 0 || ((uintptr_t)src & 15) || ((uintptr_t)dst & 3)) return KVC_ERR_ARG;
-  if (adds_per_item < 0 || adds_per_item > kProbeAdds) return KVC_ERR_ARG;
-  const size_t n_items = bytes / (kProbeItem16 * 16);
-  if (n_items == 0 || n_items > 0x7fffffffull || dst_floats < n_items * kProbeAdds) return KVC_ERR_ARG;
+  if (item_bytes < 4096 || (item_bytes & 511)) return KVC_ERR_ARG;
+  const size_t n_items = bytes / item_bytes;
+  if (n_items == 0 || n_items > 0x7fffffffull || dst_floats < n_items * (item_bytes / 512)) return KVC_ERR_ARG;
   hipLaunchKernelGGL(stream_read_add_kernel, dim3(workgroups), dim3(256), 0, (hipStream_t)stream,
-                     (const uint4*)src, (int)n_items, adds_per_item, dst, sink);
+                     (const uint4*)src, item_bytes / 16, (int)n_items, adds ? 1 : 0, dst, sink);
   KVC_LAUNCH_CHECK();
   return KVC_OK;
 }
