@@ -114,6 +114,8 @@ int main(void) {
   EXPECT(kvc_profile_enable(1) == KVC_OK && kvc_profile_collect(NULL, NULL, NULL, 0, &cnt) == KVC_OK && cnt == 0);
   EXPECT(kvc_profile_collect(NULL, NULL, NULL, 0, NULL) == KVC_ERR_ARG);
   EXPECT(kvc_stream_read_probe(p, 24, (uint32_t*)p, 4, NULL) == KVC_ERR_ARG);
+  EXPECT(kvc_stream_read_add_probe(p, (size_t)64 << 20, 1000, 1, (float*)p, 1 << 20, (uint32_t*)p, 4, NULL) == KVC_ERR_ARG);
+  EXPECT(kvc_stream_read_add_probe(p, (size_t)64 << 20, (size_t)1 << 20, 1, (float*)p, 100, (uint32_t*)p, 4, NULL) == KVC_ERR_ARG);
   if (failures) { fprintf(stderr, "%d host checks failed\n", failures); return 1; }
   printf("host checks passed\n");
   return 0;

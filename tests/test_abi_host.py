@@ -112,6 +112,16 @@ def test_entry_points_reject_bad_arguments_on_the_host():
     assert L.kvc_metric_reduce(C.byref(cfg), C.byref(st), one, 7, one, None) == B.KVC_ERR_ARG
     st_bad = B.kvc_state(4097, 8192, 4096, None, 4096, 4096, 4096)
     assert B.kvc_validate(cfg, st_bad) == B.KVC_ERR_ARG
+    # the measurement hooks check their arguments the same way
+    mib = 1 << 20
+    probe = L.kvc_stream_read_add_probe
+    assert probe(None, 64 * mib, mib, 1, one, 1 << 20, one, 512, None) == B.KVC_ERR_ARG            # no source
+    assert probe(C.c_void_p(4104), 64 * mib, mib, 1, one, 1 << 20, one, 512, None) == B.KVC_ERR_ARG  # source not 16-byte aligned
+    assert probe(one, 64 * mib, 1000, 1, one, 1 << 20, one, 512, None) == B.KVC_ERR_ARG            # item not a multiple of 512
+    assert probe(one, 64 * mib, mib, 1, one, 64 * 2048 - 1, one, 512, None) == B.KVC_ERR_ARG       # too few floats to add to
+    assert probe(one, mib // 2, mib, 1, one, 1 << 20, one, 512, None) == B.KVC_ERR_ARG             # not one whole item
+    assert probe(one, 64 * mib, mib, 1, one, 1 << 20, one, 0, None) == B.KVC_ERR_ARG               # no workgroups
+    assert L.kvc_stream_read_probe(one, 100, one, 512, None) == B.KVC_ERR_ARG                      # bytes not a multiple of 16
 
 
 def test_binding_refuses_wrong_dtypes_and_strides():
