@@ -21,6 +21,10 @@ namespace kvc {
 
 enum { RS_PREFIX = SEG_PREFIX, RS_REMAIN = SEG_REMAIN, RS_CAND = SEG_CAND, RS_TAKE = SEG_TAKE, RS_FIRSTG = SEG_FIRSTG };
 
+// Heads of at most this many KVs (by the table's row length) get a wavefront each in the histogram
+// passes of the rank schedule; longer ones a workgroup.
+constexpr size_t kRankWaveTokens = 16384;
+
 __device__ __forceinline__ uint32_t metric_bits(float f) {
   const uint32_t k = __float_as_uint(f);
   return k == 0x80000000u ? 0u : k;  // -0 orders as +0
@@ -119,6 +123,125 @@ __global__ void __launch_bounds__(NTH) rank_hist_kernel(Dims D, int pass, int pr
     __syncthreads();   // hist and below_s are reused by the next head
   }
   flush();
+}
+
+// The same step with one wavefront per head instance (four per workgroup, each taking
+// heads_per_wave consecutive heads), for caches of many heads of a few thousand KVs at most:
+// nothing in it waits at a barrier, the 256 counters of a head are four per lane, and a CU holds
+// four times as many heads in flight as with a workgroup per head (16 384 heads of ~1000 KVs:
+// a pass took 50 us that way).
+__global__ void __launch_bounds__(256) rank_hist_wave_kernel(Dims D, int pass, int protect, int heads_per_wave,
+                                                             const float* __restrict__ metric,
+                                                             const int32_t* __restrict__ table,
+                                                             const int32_t* __restrict__ ctx,
+                                                             const int32_t* __restrict__ seq_seg,
+                                                             int32_t* __restrict__ seg_hist,
+                                                             int32_t* __restrict__ seg_state,
+                                                             int32_t* __restrict__ header) {
+  __shared__ __align__(16) int hist_all[4][256];
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  int* hist = hist_all[wv];   // this wavefront's own: its LDS accesses happen in program order
+  const int g_first = (blockIdx.x * 4 + wv) * heads_per_wave;
+  const int g_end = min(D.G, g_first + heads_per_wave);
+  const int shift = 24 - 8 * pass;
+  int lb = 0;
+  while ((1 << lb) < D.b) ++lb;   // block sizes are powers of two
+  const int bmask = D.b - 1;
+  int cur_sg = -1, cand_acc = 0;
+  int rows_acc[4] = {0, 0, 0, 0};   // digits 4 lane .. 4 lane + 3
+  bool bad = false;
+  auto flush = [&]() {
+    if (cur_sg < 0) return;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      if (rows_acc[k]) atomicAdd(&seg_hist[cur_sg * 256 + 4 * lane + k], rows_acc[k]);
+      rows_acc[k] = 0;
+    }
+    if (pass == 0 && lane == 0 && cand_acc) atomicAdd(&seg_state[cur_sg * 8 + RS_CAND], cand_acc);
+    cand_acc = 0;
+  };
+  for (int g = g_first; g < g_end; ++g) {
+    const int sg = seq_seg[g / (D.Lyr * D.Hk)];
+    if (sg != cur_sg) { flush(); cur_sg = sg; }
+    const int C = ctx[g];
+    const int nb = (C + D.b - 1) / D.b;
+    const int ncand = max(0, nb - protect);
+    cand_acc += ncand;
+    if (ncand == 0) continue;
+    if (pass > 0 && seg_state[sg * 8 + RS_TAKE] <= 0) continue;
+    *(int4*)(hist + 4 * lane) = make_int4(0, 0, 0, 0);
+    const uint32_t prefix = (uint32_t)seg_state[sg * 8 + RS_PREFIX];
+    const int32_t* row = table + (size_t)g * D.maxb;
+    int below = 0;
+    auto count = [&](uint32_t k) {
+      if (pass == 0) bad |= k >= 0x7f800000u;
+      const uint32_t top = pass == 0 ? 0u : (k >> (shift + 8));
+      if (top < prefix) ++below;
+      else if (top == prefix) atomicAdd(&hist[(k >> shift) & 255], 1);
+    };
+    if (D.b >= 4) {
+      // four consecutive slots (one block: b is a power of two >= 4) per lane and load: a head of
+      // 1000 KVs is four block ids and four 16-byte loads per lane, all asked for together
+      const int nq = (C + 3) >> 2;
+      for (int q0 = lane; q0 < nq; q0 += 4 * 64) {
+        int id[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) id[i] = row[(4 * min(q0 + i * 64, nq - 1)) >> lb];
+        float4 m[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int j = 4 * min(q0 + i * 64, nq - 1);
+          m[i] = *(const float4*)&metric[((size_t)id[i] << lb) + (j & bmask)];
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int j = 4 * (q0 + i * 64);
+          if (j < C) count(metric_bits(m[i].x));
+          if (j + 1 < C) count(metric_bits(m[i].y));
+          if (j + 2 < C) count(metric_bits(m[i].z));
+          if (j + 3 < C) count(metric_bits(m[i].w));
+        }
+      }
+    } else {
+      for (int j0 = lane; j0 < C; j0 += 4 * 64) {   // four block ids, then four metrics, asked for together
+        int id[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) id[i] = row[min(j0 + i * 64, C - 1) >> lb];
+        float m[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int j = min(j0 + i * 64, C - 1);
+          m[i] = metric[((size_t)id[i] << lb) + (j & bmask)];
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          if (j0 + i * 64 < C) count(metric_bits(m[i]));
+      }
+    }
+    const int z = nb * D.b - C;  // the empty slots count as zeros, ahead of every real metric
+    if (lane == 0 && z) {
+      if (prefix == 0) atomicAdd(&hist[0], z); else below += z;
+    }
+    below = wave_sum_i(below);
+    // running counts over the digits in order: four per lane, then over the lanes
+    const int4 c = *(const int4*)(hist + 4 * lane);
+    const int mine = c.x + c.y + c.z + c.w;
+    int inc = mine;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const int t = __shfl_up(inc, o);
+      if (lane >= o) inc += t;
+    }
+    int ex = below + inc - mine;
+    const int cc[4] = {c.x, c.y, c.z, c.w};
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      rows_acc[k] += min(ncand, (ex + cc[k]) >> lb) - min(ncand, ex >> lb);
+      ex += cc[k];
+    }
+  }
+  flush();
+  if (__any(bad) && lane == 0) atomicOr(&header[HW_SCRATCH0], EB_NUMERIC);
 }
 
 // One workgroup per segment: the digit that holds the E-th smallest row key (same rule as the
@@ -386,7 +509,11 @@ int kvc_evict_rank_select(const kvc_config* cfg, const kvc_state* st, const int3
     // first pass (the exponent byte): nearly every head lands on the same digit of its segment's
     // histogram, and four heads per workgroup (a quarter of the adds) measured fastest
     const int hpw = pass == 0 ? 4 : 1;
-    if (D.G <= 1024)
+    if ((size_t)D.maxb * D.b <= kRankWaveTokens)
+      hipLaunchKernelGGL(rank_hist_wave_kernel, dim3((D.G + 4 * hpw - 1) / (4 * hpw)), dim3(256), 0, s, D, pass,
+                         protect_tail_blocks, hpw, st->metric,
+                         st->block_table, st->ctx_len, seq_seg, W.seg_hist, W.seg_state, W.header);
+    else if (D.G <= 1024)
       hipLaunchKernelGGL(rank_hist_kernel<1024>, dim3(D.G), dim3(1024), 0, s, D, pass, protect_tail_blocks, 1,
                          st->metric, st->block_table, st->ctx_len, seq_seg, W.seg_hist, W.seg_state, W.header);
     else
@@ -446,6 +573,11 @@ int kvc_compact_rank(const kvc_config* cfg, const kvc_state* st, const int32_t* 
   } else {
     // many heads: what hides the load latencies is workgroups per CU, and LDS for the metrics would
     // cost more of those than the second reads through the table do (measured: 0.19 -> 0.24 ms)
+    // many heads: what hides the load latencies is workgroups per CU, and LDS for the metrics would
+    // cost more of those than the second reads through the table do (measured: 0.19 -> 0.24 ms).
+    // (A wavefront per head of up to 2048 KVs, its metrics in registers and ranks by ballots, took
+    // 0.08 ms for the four fifths of the heads it covers, and the workgroups left with the long
+    // heads still 0.16: no gain.)
     hipLaunchKernelGGL(rank_compact_kernel<256>, dim3(D.G), dim3(256), 0, s, D, (char*)st->k_cache,
                        (char*)st->v_cache, st->metric, st->pos, st->block_table, st->ctx_len, st->free_map, evict_rows,
                        (int32_t*)W.stash, W.header, 0);

@@ -24,6 +24,10 @@ CASES = [
     # and possibly long heads, a workgroup has 1024 threads)
     ("many_heads", dict(S=24, Lyr=7, Hk=8, L=150, b=16), dict(pooled=False, protect=1, ties=False, frac=0.4)),
     ("many_heads_ties_b4", dict(S=24, Lyr=7, Hk=8, L=60, b=4), dict(pooled=True, protect=0, ties=True, frac=0.5)),
+    # tables sized for more than 16 384 KVs a head: the histogram passes give a head a workgroup
+    # (of 1024 threads with few heads, of 256 with many) instead of a wavefront
+    ("long_tables_few_heads", dict(L=17000, rho=8.0, b=16), dict(pooled=False, protect=1, ties=False, frac=0.4)),
+    ("long_tables_many_heads", dict(S=24, Lyr=7, Hk=8, L=17000, rho=64.0, b=16), dict(pooled=True, protect=1, ties=True, frac=0.5)),
 ]
 
 
