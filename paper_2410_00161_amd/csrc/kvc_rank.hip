@@ -322,6 +322,84 @@ __global__ void __launch_bounds__(256) rank_tie_kernel(Dims D, int protect, cons
   }
 }
 
+// The same with one wavefront per head instance (heads of a few thousand KVs at most), four
+// consecutive slots per lane and load when a block holds at least four.
+__global__ void __launch_bounds__(256) rank_tie_wave_kernel(Dims D, int protect, const float* __restrict__ metric,
+                                                            const int32_t* __restrict__ table,
+                                                            const int32_t* __restrict__ ctx,
+                                                            const int32_t* __restrict__ seq_seg,
+                                                            const int32_t* __restrict__ seg_state,
+                                                            int32_t* __restrict__ rows_lt,
+                                                            int32_t* __restrict__ rows_tie) {
+  const int lane = threadIdx.x & 63;
+  const int g = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (g >= D.G) return;
+  const int sg = seq_seg[g / (D.Lyr * D.Hk)];
+  const int C = ctx[g];
+  const int nb = (C + D.b - 1) / D.b;
+  const int ncand = max(0, nb - protect);
+  if (ncand == 0 || seg_state[sg * 8 + RS_TAKE] <= 0) {
+    if (lane == 0) { rows_lt[g] = 0; rows_tie[g] = 0; }
+    return;
+  }
+  const uint32_t thr = (uint32_t)seg_state[sg * 8 + RS_PREFIX];
+  const int32_t* row = table + (size_t)g * D.maxb;
+  int lt = 0, le = 0;
+  int lb = 0;
+  while ((1 << lb) < D.b) ++lb;   // block sizes are powers of two
+  const int bmask = D.b - 1;
+  auto count = [&](uint32_t k) { lt += k < thr; le += k <= thr; };
+  if (D.b >= 4) {
+    const int nq = (C + 3) >> 2;
+    for (int q0 = lane; q0 < nq; q0 += 4 * 64) {
+      int id[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) id[i] = row[(4 * min(q0 + i * 64, nq - 1)) >> lb];
+      float4 m[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int j = 4 * min(q0 + i * 64, nq - 1);
+        m[i] = *(const float4*)&metric[((size_t)id[i] << lb) + (j & bmask)];
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int j = 4 * (q0 + i * 64);
+        if (j < C) count(metric_bits(m[i].x));
+        if (j + 1 < C) count(metric_bits(m[i].y));
+        if (j + 2 < C) count(metric_bits(m[i].z));
+        if (j + 3 < C) count(metric_bits(m[i].w));
+      }
+    }
+  } else {
+    for (int j0 = lane; j0 < C; j0 += 4 * 64) {
+      int id[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) id[i] = row[min(j0 + i * 64, C - 1) >> lb];
+      float m[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int j = min(j0 + i * 64, C - 1);
+        m[i] = metric[((size_t)id[i] << lb) + (j & bmask)];
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        if (j0 + i * 64 < C) count(metric_bits(m[i]));
+    }
+  }
+  if (lane == 0) {
+    const int z = nb * D.b - C;
+    le += z;
+    if (thr > 0) lt += z;
+  }
+  lt = wave_sum_i(lt);
+  le = wave_sum_i(le);
+  if (lane == 0) {
+    const int a = min(ncand, lt / D.b), c = min(ncand, le / D.b);
+    rows_lt[g] = a;
+    rows_tie[g] = c - a;
+  }
+}
+
 struct RowTieFn {
   const int32_t* cnt;
   __device__ int operator()(int i) const { return cnt[i]; }
@@ -529,8 +607,12 @@ int kvc_evict_rank_select(const kvc_config* cfg, const kvc_state* st, const int3
       KVC_LAUNCH_CHECK();
     }
   }
-  hipLaunchKernelGGL(rank_tie_kernel, dim3(D.G), dim3(256), 0, s, D, protect_tail_blocks, st->metric,
-                     st->block_table, st->ctx_len, seq_seg, W.seg_state, evict_rows, W.off_b);
+  if ((size_t)D.maxb * D.b <= kRankWaveTokens)
+    hipLaunchKernelGGL(rank_tie_wave_kernel, dim3((D.G + 3) / 4), dim3(256), 0, s, D, protect_tail_blocks, st->metric,
+                       st->block_table, st->ctx_len, seq_seg, W.seg_state, evict_rows, W.off_b);
+  else
+    hipLaunchKernelGGL(rank_tie_kernel, dim3(D.G), dim3(256), 0, s, D, protect_tail_blocks, st->metric,
+                       st->block_table, st->ctx_len, seq_seg, W.seg_state, evict_rows, W.off_b);
   KVC_LAUNCH_CHECK();
   rc = device_exclusive_scan(RowTieFn{W.off_b}, D.G, W.tile_sums, W.off_a, nullptr, s);
   if (rc != KVC_OK) return rc;
