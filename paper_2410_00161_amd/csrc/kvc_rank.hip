@@ -37,6 +37,31 @@ __device__ __forceinline__ uint32_t metric_bits(float f) {
 template <int NTH, class Visit>
 __device__ __forceinline__ void for_each_metric(const float* __restrict__ metric, const int32_t* __restrict__ row,
                                                 int C, int lb, int bmask, Visit visit) {
+  if (bmask >= 3) {
+    // blocks of at least four slots: four consecutive slots (one block) per load, so a round of
+    // loads covers 16 slots per thread
+    const int nq = (C + 3) >> 2;
+    for (int q0 = threadIdx.x; q0 < nq; q0 += 4 * NTH) {
+      int id[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) id[i] = row[(4 * min(q0 + i * NTH, nq - 1)) >> lb];
+      float4 m[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int j = 4 * min(q0 + i * NTH, nq - 1);
+        m[i] = *(const float4*)&metric[((size_t)id[i] << lb) + (j & bmask)];
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int j = 4 * (q0 + i * NTH);
+        if (j < C) visit(j, metric_bits(m[i].x));
+        if (j + 1 < C) visit(j + 1, metric_bits(m[i].y));
+        if (j + 2 < C) visit(j + 2, metric_bits(m[i].z));
+        if (j + 3 < C) visit(j + 3, metric_bits(m[i].w));
+      }
+    }
+    return;
+  }
   for (int j0 = threadIdx.x; j0 < C; j0 += 4 * NTH) {
     int id[4];
 #pragma unroll
@@ -458,8 +483,7 @@ __global__ void __launch_bounds__(NTH) rank_compact_kernel(Dims D, char* __restr
   const int e = evict_rows[g];
   if (e <= 0) return;
   __shared__ int hist[256];
-  __shared__ int smem[NTH / 64 + 1];
-  __shared__ int chosen_s, prefix_s, remain_s, carry_tie, carry_ev, nholes_s;
+  __shared__ int prefix_s, remain_s;
   // the head's metrics as ordered bit patterns, kept from the first radix pass on when the head
   // fits the lds_tokens words this launch has: the three passes and the ordered pass after it
   // then read LDS instead of gathering through the table again
@@ -476,8 +500,10 @@ __global__ void __launch_bounds__(NTH) rank_compact_kernel(Dims D, char* __restr
   const bool kept = C <= lds_tokens;
 
   // ---- threshold metric: the n_ev-th smallest by (metric, logical index) ----
+  // Three barriers per pass: the 256 counters are walked by the first wavefront alone, four per
+  // lane (a scan over the whole workgroup would wait at six more).
+  const int lane = tid & 63, wv = tid >> 6;
   if (tid == 0) { prefix_s = 0; remain_s = n_ev; }
-  __syncthreads();
   for (int pass = 0; pass < 4; ++pass) {
     if (tid < 256) hist[tid] = 0;
     __syncthreads();
@@ -495,16 +521,25 @@ __global__ void __launch_bounds__(NTH) rank_compact_kernel(Dims D, char* __restr
       }
     }
     __syncthreads();
-    const int c = tid < 256 ? hist[tid] : 0;
-    const int ex = block_exclusive_scan<NTH>(c, smem, nullptr);
-    const int remain = remain_s;
-    if (tid == 0) chosen_s = -1;
-    __syncthreads();
-    if (tid < 256 && ex < remain && remain <= ex + c) chosen_s = tid;
-    __syncthreads();
-    if (tid == chosen_s) {
-      prefix_s = (int)((prefix << 8) | (uint32_t)tid);
-      remain_s = remain - ex;
+    if (wv == 0) {
+      const int c4[4] = {hist[4 * lane], hist[4 * lane + 1], hist[4 * lane + 2], hist[4 * lane + 3]};
+      const int mine = c4[0] + c4[1] + c4[2] + c4[3];
+      int inc = mine;
+#pragma unroll
+      for (int o = 1; o < 64; o <<= 1) {
+        const int t = __shfl_up(inc, o);
+        if (lane >= o) inc += t;
+      }
+      int ex = inc - mine;
+      const int remain = remain_s;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        if (ex < remain && remain <= ex + c4[q]) {   // exactly one lane and digit
+          prefix_s = (int)((prefix << 8) | (uint32_t)(4 * lane + q));
+          remain_s = remain - ex;
+        }
+        ex += c4[q];
+      }
     }
     __syncthreads();
   }
@@ -512,31 +547,59 @@ __global__ void __launch_bounds__(NTH) rank_compact_kernel(Dims D, char* __restr
   const int ties_take = remain_s;
 
   // ---- ordered pass: who is evicted, hole and mover ranks ----
-  if (tid == 0) { carry_tie = 0; carry_ev = 0; nholes_s = 0; }
-  __syncthreads();
-  for (int base = 0; base < C; base += NTH) {
+  // Ranks inside a wavefront come from ballots; the wavefronts exchange their counts through LDS,
+  // two barriers per round of NTH slots (counts double-buffered by the round's parity), and every
+  // thread keeps the running totals itself.
+  __shared__ int cnt_s[2][3][NTH / 64];
+  const unsigned long long lower = (1ull << lane) - 1ull;
+  int carry_tie = 0, carry_ev = 0, n_moves = 0;
+  auto ordered_round = [&](int base, int par, uint32_t k) {
     const int j = base + tid;
-    uint32_t k = 0xffffffffu;
-    if (j < C) k = kept ? s_bits[j] : metric_bits(metric[phys(j)]);
-    const int is_tie = (j < C) && k == thr;
-    int tot_tie;
-    const int tie_rank = block_exclusive_scan<NTH>(is_tie, smem, &tot_tie) + carry_tie;
-    const int ev = (j < C) && (k < thr || (is_tie && tie_rank < ties_take));
-    int tot_ev;
-    const int ev_before = block_exclusive_scan<NTH>(ev, smem, &tot_ev) + carry_ev;
+    const bool is_tie = (j < C) && k == thr;
+    const unsigned long long tm = __ballot(is_tie);
+    if (lane == 0) cnt_s[par][0][wv] = __popcll(tm);
+    __syncthreads();
+    int tie_rank = carry_tie + __popcll(tm & lower), tot_tie = 0;
+#pragma unroll
+    for (int w2 = 0; w2 < NTH / 64; ++w2) {
+      const int c = cnt_s[par][0][w2];
+      if (w2 < wv) tie_rank += c;
+      tot_tie += c;
+    }
+    const bool ev = (j < C) && (k < thr || (is_tie && tie_rank < ties_take));
+    const unsigned long long em = __ballot(ev);
+    const unsigned long long hm = __ballot(ev && j < T);
+    if (lane == 0) { cnt_s[par][1][wv] = __popcll(em); cnt_s[par][2][wv] = __popcll(hm); }
+    __syncthreads();
+    int ev_before = carry_ev + __popcll(em & lower), tot_ev = 0;
+#pragma unroll
+    for (int w2 = 0; w2 < NTH / 64; ++w2) {
+      const int c = cnt_s[par][1][w2];
+      if (w2 < wv) ev_before += c;
+      tot_ev += c;
+      n_moves += cnt_s[par][2][w2];
+    }
     if (j < C) {
       if (ev) {
-        if (j < T) { scratch[phys(ev_before)] = j; atomicAdd(&nholes_s, 1); }
+        if (j < T) scratch[phys(ev_before)] = j;
       } else if (j >= T) {
         const int kk = (C - 1 - j) - (n_ev - ev_before);  // kept slots above j
         scratch[phys(C - 1 - kk)] = j;
       }
     }
-    __syncthreads();
-    if (tid == 0) { carry_tie += tot_tie; carry_ev += tot_ev; }
-    __syncthreads();
+    carry_tie += tot_tie;
+    carry_ev += tot_ev;
+  };
+  {
+    for (int base = 0, par = 0; base < C; base += NTH, par ^= 1) {
+      const int j = base + tid;
+      uint32_t k = 0xffffffffu;
+      if (j < C) k = kept ? s_bits[j] : metric_bits(metric[phys(j)]);
+      ordered_round(base, par, k);
+    }
   }
-  const int n_moves = nholes_s;
+  __syncthreads();   // the lists are complete (and in memory) before anyone reads them back
+
   const size_t row_bytes = (size_t)D.d * kv_esz(D.dtype);
   const int pieces = (int)(row_bytes / 16);
   const int grp = tid >> 4, gl = tid & 15;
@@ -655,14 +718,17 @@ int kvc_compact_rank(const kvc_config* cfg, const kvc_state* st, const int32_t* 
   } else {
     // many heads: what hides the load latencies is workgroups per CU, and LDS for the metrics would
     // cost more of those than the second reads through the table do (measured: 0.19 -> 0.24 ms)
-    // many heads: what hides the load latencies is workgroups per CU, and LDS for the metrics would
-    // cost more of those than the second reads through the table do (measured: 0.19 -> 0.24 ms).
+    // many heads: what hides the load latencies is workgroups per CU.  16 KB of LDS for the metrics
+    // of heads of up to 4096 KVs leaves a CU its eight workgroups (0.18 -> 0.16 ms per round of
+    // 16 384 heads); 32 KB for up to 8192 costs three of them (0.19 ms).
     // (A wavefront per head of up to 2048 KVs, its metrics in registers and ranks by ballots, took
     // 0.08 ms for the four fifths of the heads it covers, and the workgroups left with the long
     // heads still 0.16: no gain.)
-    hipLaunchKernelGGL(rank_compact_kernel<256>, dim3(D.G), dim3(256), 0, s, D, (char*)st->k_cache,
+    const size_t head_tokens = (size_t)D.maxb * D.b;
+    const int lds_tokens = (int)(head_tokens < 4096 ? head_tokens : 4096);
+    hipLaunchKernelGGL(rank_compact_kernel<256>, dim3(D.G), dim3(256), (size_t)lds_tokens * 4, s, D, (char*)st->k_cache,
                        (char*)st->v_cache, st->metric, st->pos, st->block_table, st->ctx_len, st->free_map, evict_rows,
-                       (int32_t*)W.stash, W.header, 0);
+                       (int32_t*)W.stash, W.header, lds_tokens);
   }
   KVC_LAUNCH_CHECK();
   return (flags & KVC_ASYNC) ? KVC_OK : finish_sync(W, s);
