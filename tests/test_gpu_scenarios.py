@@ -384,3 +384,29 @@ def test_snapshot_of_the_six_buffers_resumes_bit_for_bit():
             ta, tb = ta.view(torch.uint8), tb.view(torch.uint8)
         assert torch.equal(ta.cpu(), tb.cpu()), name
     a.check_state()
+
+
+def test_read_probes_read_and_add_what_they_say():
+    """The bench's bandwidth probes: the checksum of the bytes read is the XOR of all of them (so every
+    byte was read once), and the adds land once per 512 bytes read, nowhere else."""
+    say("read probes")
+    dev = torch.device("cuda:0")
+    g = torch.Generator(device=dev).manual_seed(3)
+    nbytes, item = 9 << 20, 1 << 20
+    src = torch.randint(0, 2 ** 31 - 1, (nbytes // 4,), generator=g, device=dev, dtype=torch.int32)
+    want = 0
+    for w in src.cpu().numpy().view(np.uint32).reshape(-1, 1 << 16):
+        want ^= int(np.bitwise_xor.reduce(w))
+    for wgs in (7, 512):
+        sink = torch.zeros(wgs, dtype=torch.int32, device=dev)
+        B.kvc_stream_read_probe(src, nbytes, sink, wgs)
+        got = int(np.bitwise_xor.reduce(sink.cpu().numpy().view(np.uint32)))
+        assert got == want
+        for adds in (0, 1):
+            dst = torch.zeros(nbytes // 512 + 100, dtype=torch.float32, device=dev)
+            sink.zero_()
+            B.kvc_stream_read_add_probe(src, nbytes, item, adds, dst, sink, wgs)
+            torch.cuda.synchronize()
+            assert int(np.bitwise_xor.reduce(sink.cpu().numpy().view(np.uint32))) == want
+            d = dst.cpu().numpy()
+            assert (d[: nbytes // 512] == float(adds)).all() and (d[nbytes // 512:] == 0).all()
