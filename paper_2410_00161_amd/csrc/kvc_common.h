@@ -383,6 +383,26 @@ static __global__ void __launch_bounds__(256) segments_init_kernel(Dims D, const
   if (i < D.G) per_head[i] = 0;
 }
 
+// How much dynamic LDS a kernel may take above the default 64 KB is an attribute of the kernel on
+// a device: remembered per device (the first 64 of a process), raised when a call needs more.
+// Host threads may race here; telling the runtime twice is harmless.
+struct LdsLimit {
+  std::atomic<size_t> allowed[64] = {};
+  template <class... Kernels>
+  int need(size_t bytes, Kernels... kernels) {
+    if (bytes <= 64 * 1024) return KVC_OK;
+    int dev = -1;
+    KVC_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= 64) return KVC_ERR_UNSUPPORTED;
+    if (bytes <= allowed[dev].load(std::memory_order_acquire)) return KVC_OK;
+    const void* ks[] = {(const void*)kernels...};
+    for (const void* k : ks) KVC_HIP(hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes));
+    size_t seen = allowed[dev].load(std::memory_order_relaxed);
+    while (seen < bytes && !allowed[dev].compare_exchange_weak(seen, bytes, std::memory_order_release)) {}
+    return KVC_OK;
+  }
+};
+
 // Reads the status word; a non-zero word is cleared so that the next call starts clean.
 inline int finish_sync(const Workspace& W, hipStream_t s) {
   int32_t w = 0;

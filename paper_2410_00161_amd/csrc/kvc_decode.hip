@@ -900,14 +900,10 @@ static int launch_tiled(const DecodeArgs& A, int grid, size_t lds, int grid_shor
   auto kern_short = (A.D.b % 16 == 0) ? decode_chunk_kernel<ESZ, HD, R, true, 1> : decode_chunk_kernel<ESZ, HD, R, false, 1>;
   ProfilePair* pp = claim_profile_pair();
   if (pp) KVC_HIP(hipEventRecord(pp->a0, s));
-  if (lds > 64 * 1024) {  // above the default cap the kernel must be told once how much it may take
-    static std::atomic<size_t> allowed[2];   // per instantiation: zero-initialised, only ever raised
-    std::atomic<size_t>& a = allowed[A.D.b % 16 == 0];
-    if (lds > a.load(std::memory_order_acquire)) {
-      KVC_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-      size_t seen = a.load(std::memory_order_relaxed);
-      while (seen < lds && !a.compare_exchange_weak(seen, lds, std::memory_order_release)) {}
-    }
+  {  // above the default cap the kernel must be told how much it may take (per instantiation and device)
+    static LdsLimit limit[2];
+    const int rc = limit[A.D.b % 16 == 0].need(lds, kern);
+    if (rc != KVC_OK) return rc;
   }
   hipLaunchKernelGGL(kern, dim3(grid), dim3(kDecodeThreads), lds, s, A);
   KVC_LAUNCH_CHECK();

@@ -741,12 +741,9 @@ int kvc_evict_select(const kvc_config* cfg, const kvc_state* st, const float* bl
   const int heads_per_seq = D.Lyr * D.Hk;
   if (!seg_offsets && heads_per_seq <= kSegMaxHeads && (size_t)D.N <= (size_t)kSegLdsKeys * D.S) {
     const size_t lds = ((size_t)((heads_per_seq + 1 + 3) & ~3) + kSegWaves * 256 + kSegLdsKeys) * 4;
-    static std::atomic<bool> told{false};   // the runtime is told once that this kernel may take that much LDS
-    if (!told.load(std::memory_order_acquire)) {
-      KVC_HIP(hipFuncSetAttribute((const void*)select_segment_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                  (int)(((size_t)kSegMaxHeads + 4 + kSegWaves * 256 + kSegLdsKeys) * 4)));
-      told.store(true, std::memory_order_release);
-    }
+    static LdsLimit limit;
+    rc = limit.need(((size_t)kSegMaxHeads + 4 + kSegWaves * 256 + kSegLdsKeys) * 4, select_segment_kernel);
+    if (rc != KVC_OK) return rc;
     hipLaunchKernelGGL(select_segment_kernel, dim3(D.S), dim3(kSegThreads), lds, s, D, protect_tail_blocks, kSegLdsKeys,
                        block_key, st->ctx_len, budget, evict_flag, evict_count, selected, W.seg_state, W.off_a, W.header);
     KVC_LAUNCH_CHECK();

@@ -707,11 +707,9 @@ int kvc_compact_rank(const kvc_config* cfg, const kvc_state* st, const int32_t* 
     // LDS (up to 36864 tokens; one such workgroup per CU is all there is to run anyway)
     const size_t head_tokens = (size_t)D.maxb * D.b;
     const int lds_tokens = (int)(head_tokens < 36864 ? head_tokens : 36864);
-    static std::atomic<bool> told{false};   // setting it twice is harmless: several host threads may race here
-    if (!told.load(std::memory_order_acquire)) {
-      KVC_HIP(hipFuncSetAttribute((const void*)rank_compact_kernel<1024>, hipFuncAttributeMaxDynamicSharedMemorySize, 36864 * 4));
-      told.store(true, std::memory_order_release);
-    }
+    static LdsLimit limit;
+    const int rc2 = limit.need((size_t)36864 * 4, rank_compact_kernel<1024>);
+    if (rc2 != KVC_OK) return rc2;
     hipLaunchKernelGGL(rank_compact_kernel<1024>, dim3(D.G), dim3(1024), (size_t)lds_tokens * 4, s, D, (char*)st->k_cache,
                        (char*)st->v_cache, st->metric, st->pos, st->block_table, st->ctx_len, st->free_map, evict_rows,
                        (int32_t*)W.stash, W.header, lds_tokens);

@@ -493,14 +493,11 @@ static int launch_window(const WindowArgs& W, int grid, hipStream_t s) {
   static_assert((size_t)kWinWaves * rows * 2 * 4 <= q_bytes, "the per-wavefront pairs of pass 1 fit where Q was");
   const size_t lds = q_bytes + (size_t)kWinWaves * NT * window_pairs_per_tile(M, NT) * 8 + tab;
   const size_t lds2 = q_bytes + rows * 4 + tab;
-  static std::atomic<size_t> allowed{0};   // above the default cap a kernel must be told how much it may take
-  const size_t most = lds > lds2 ? lds : lds2;
-  if (most > 64 * 1024 && most > allowed.load(std::memory_order_acquire)) {   // (the block-id array grows as blocks shrink)
-    KVC_HIP(hipFuncSetAttribute((const void*)window_stats_kernel<ESZ, HD, M, NT>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)most));
-    KVC_HIP(hipFuncSetAttribute((const void*)window_sum_kernel<ESZ, HD, M, NT, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)most));
-    KVC_HIP(hipFuncSetAttribute((const void*)window_sum_kernel<ESZ, HD, M, NT, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)most));
-    size_t seen = allowed.load(std::memory_order_relaxed);
-    while (seen < most && !allowed.compare_exchange_weak(seen, most, std::memory_order_release)) {}
+  {  // above the default cap a kernel must be told how much it may take (the block-id array grows as blocks shrink)
+    static LdsLimit limit;
+    const int rc = limit.need(lds > lds2 ? lds : lds2, window_stats_kernel<ESZ, HD, M, NT>,
+                              window_sum_kernel<ESZ, HD, M, NT, true>, window_sum_kernel<ESZ, HD, M, NT, false>);
+    if (rc != KVC_OK) return rc;
   }
   if (!W.lse) {   // with the caller's log-sum-exp there is nothing for pass 1 to find
     hipLaunchKernelGGL((window_stats_kernel<ESZ, HD, M, NT>), dim3(grid), dim3(kWinThreads), lds, s, W);
